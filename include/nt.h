@@ -1,0 +1,204 @@
+/*
+ * nt.h -- C ABI of the MI355X (gfx950) arrange-and-apply tiled-contraction library.
+ *
+ * The library implements the tiled computation that the paper's code generator emits
+ * for its canonical arrangement: a matrix multiply whose output tiles are programs
+ * (tile-to-program mapping, Section 3.2.1) and whose operand tiles are located through
+ * per-program index sets (source-to-target mapping, Section 3.2.2), plus batched matmul
+ * and 2D convolution lowered to the same product (Section 4.3).
+ *
+ * Conventions for every entry point
+ *   - Plain C types only.  "device" pointers are HIP device addresses (for example
+ *     torch.Tensor.data_ptr()); "host" pointers are ordinary process memory.
+ *   - Strides are in ELEMENTS, not bytes, and may describe any non-overlapping view.
+ *   - The caller owns every buffer.  Nothing user-visible is allocated or kept between calls.
+ *   - Kernel-launching calls enqueue on `hip_stream` (a hipStream_t, NULL = default
+ *     stream) and return without waiting.  nt_arrange_* calls are synchronous host code.
+ *   - Errors are returned as nt_status; nothing throws or aborts across the ABI.
+ *     nt_last_error() gives a thread-local message for the last failing call.
+ */
+#ifndef NT_H
+#define NT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NT_MAX_DIMS 6
+#define NT_MAX_LEVELS 8
+
+typedef enum {
+    NT_OK = 0,
+    NT_ERR_INVALID_ARG = 1,      /* null pointer, ndim out of range, negative size, bad enum */
+    NT_ERR_SHAPE_MISMATCH = 2,   /* improper arrangement (Section 3.2.1), K mismatch, expand/squeeze of non-singleton */
+    NT_ERR_UNSUPPORTED = 3,      /* dtype / tile combination that is not built */
+    NT_ERR_BUFFER_TOO_SMALL = 4, /* `capacity` smaller than the tile; required size is still reported */
+    NT_ERR_DEVICE = 5            /* HIP runtime error (launch failure, no device) */
+} nt_status;
+
+typedef enum { NT_F16 = 0, NT_BF16 = 1, NT_F32 = 2 } nt_dtype;
+
+/* A source tensor: sizes and element strides, as a framework front end reports them
+ * (Section 3.2.1, last paragraph). */
+typedef struct {
+    int32_t ndim;
+    int64_t size[NT_MAX_DIMS];
+    int64_t stride[NT_MAX_DIMS];
+} nt_tensor_desc;
+
+/* One meta-operation (Table 1).  An arrangement is an array of these, applied in order
+ * to the level the cursor points at (initially the outermost).
+ *   TILE     a = tile shape (-1 = whole dimension), b = strides between tiles (-1 or 0 =
+ *            default = tile shape; Section 3.1.3), c = low padding, d = high padding
+ *            (c, d: 0 in the paper; needed for padded convolution).  n = rank.
+ *   EXPAND   a = new shape (-1 keeps a dimension); only singleton dimensions grow.
+ *   SQUEEZE  a[0] = dimension to drop; it must have size 1.
+ *   PERMUTE  a = order (new dimension i is old dimension a[i]).
+ *   FLATTEN  a[0] = start_dim, a[1] = end_dim, EXCLUSIVE (the shapes printed in Section
+ *            4.3 require it), first merged dimension slowest.
+ *   RAVEL    concatenates all levels from the cursor inwards into one level.
+ *   DESCEND  move the cursor one level inwards (the paper's `.dtype`).
+ *   ASCEND   move it back out (assigning the edited `.dtype` back).
+ */
+typedef enum {
+    NT_OP_TILE = 0, NT_OP_EXPAND = 1, NT_OP_SQUEEZE = 2, NT_OP_PERMUTE = 3,
+    NT_OP_FLATTEN = 4, NT_OP_RAVEL = 5, NT_OP_DESCEND = 6, NT_OP_ASCEND = 7
+} nt_op_kind;
+
+typedef struct {
+    int32_t kind;               /* nt_op_kind */
+    int32_t n;                  /* number of valid entries in a/b/c/d */
+    int64_t a[NT_MAX_DIMS];
+    int64_t b[NT_MAX_DIMS];
+    int64_t c[NT_MAX_DIMS];
+    int64_t d[NT_MAX_DIMS];
+} nt_meta_op;
+
+/* Meta-parameters of the matmul arrangement (BLOCK_SIZE_M/N/K of Section 4.2).
+ * 0 in all three = library default for the problem.  Built tiles: see nt_tile_supported. */
+typedef struct { int32_t bm, bn, bk; } nt_tile_cfg;
+
+/* Operand selector for the *_arrange_tile calls. */
+typedef enum { NT_OPERAND_A = 0, NT_OPERAND_B = 1, NT_OPERAND_C = 2 } nt_operand;
+
+/* ---------------------------------------------------------------- arrangement (host, integer)
+ *
+ * nt_arrange_levels: run `ops` on `src` and report the resulting hierarchy
+ * (Section 3.1.2): n_levels_out, and for level l its rank level_ndim_out[l] and shape
+ * level_shape_out[l*NT_MAX_DIMS + d].  Arrays must hold NT_MAX_LEVELS (x NT_MAX_DIMS).
+ */
+nt_status nt_arrange_levels(const nt_tensor_desc *src, const nt_meta_op *ops, int32_t n_ops,
+                            int32_t *n_levels_out, int32_t *level_ndim_out, int64_t *level_shape_out);
+
+/*
+ * nt_arrange_tile: the source-to-target map of one tile (Section 3.2.2).  `program_id`
+ * selects the outermost index (row-major, last dimension fastest -- the paper fixes only
+ * the number of programs, Section 3.2.1); `mid_idx[n_mid]` indexes every dimension of the
+ * levels strictly between outermost and innermost (e.g. {k} for a matmul operand).  Writes,
+ * in row-major order over the innermost level, the element offset into the source
+ * (-1 where masked) and the mask (1 valid, 0 masked; masked loads read as zero, masked
+ * stores are dropped).  offsets_out / mask_out are host arrays of `capacity` entries;
+ * if the tile is larger, nothing is written to them, NT_ERR_BUFFER_TOO_SMALL is returned
+ * and the shapes are still reported.  tile_shape_out / grid_shape_out hold NT_MAX_DIMS
+ * entries.  Any of the *_out pointers except the shape outputs may be NULL to query shapes.
+ */
+nt_status nt_arrange_tile(const nt_tensor_desc *src, const nt_meta_op *ops, int32_t n_ops,
+                          int64_t program_id, const int64_t *mid_idx, int32_t n_mid,
+                          int64_t *offsets_out, uint8_t *mask_out, size_t capacity,
+                          int64_t *tile_shape_out, int32_t *tile_ndim_out,
+                          int64_t *grid_shape_out, int32_t *grid_ndim_out);
+
+/*
+ * The matmul arrangement of Section 4.2 applied to A [M,K], B [K,N], C [M,N]
+ * (nt_arrange_gemm), to [batch,M,K] x [batch,K,N] -> [batch,M,N] (nt_arrange_bmm; the
+ * paper does not print this arrangement: the matmul one with a leading batch dimension
+ * tiled by 1 is used) and to the implicit-GEMM view of a convolution (nt_arrange_conv2d,
+ * Section 4.3: input NCHW, filter KCRS, output NKPQ).  Each checks that the three
+ * outermost shapes agree (else NT_ERR_SHAPE_MISMATCH, Section 3.2.1) and reports the grid
+ * (grid_out[3] = {batch or 1, Mt, Nt}) and the number of k tiles.  With operand/program_id/k
+ * and non-NULL offsets_out they also evaluate that operand's tile exactly like
+ * nt_arrange_tile (tile_shape_out[2]).  These are the arrangements the kernels execute.
+ */
+nt_status nt_arrange_gemm(const nt_tensor_desc *dA, const nt_tensor_desc *dB, const nt_tensor_desc *dC,
+                          nt_tile_cfg cfg, int64_t *grid_out, int64_t *kt_out,
+                          int32_t operand, int64_t program_id, int64_t k,
+                          int64_t *offsets_out, uint8_t *mask_out, size_t capacity, int64_t *tile_shape_out);
+nt_status nt_arrange_bmm(const nt_tensor_desc *dA, const nt_tensor_desc *dB, const nt_tensor_desc *dC,
+                         nt_tile_cfg cfg, int64_t *grid_out, int64_t *kt_out,
+                         int32_t operand, int64_t program_id, int64_t k,
+                         int64_t *offsets_out, uint8_t *mask_out, size_t capacity, int64_t *tile_shape_out);
+nt_status nt_arrange_conv2d(const nt_tensor_desc *dx, const nt_tensor_desc *dw, const nt_tensor_desc *dy,
+                            int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                            nt_tile_cfg cfg, int64_t *grid_out, int64_t *kt_out,
+                            int32_t operand, int64_t program_id, int64_t k,
+                            int64_t *offsets_out, uint8_t *mask_out, size_t capacity, int64_t *tile_shape_out);
+
+/*
+ * nt_program_order: the permutation the kernels apply between the hardware workgroup
+ * index and the logical program id (cache-locality swizzle; any bijection yields the same
+ * result because programs are independent, Section 3.2.1).  Writes pid_out[w] for
+ * w in [0, batch*mt*nt).  Host arrays.
+ */
+nt_status nt_program_order(int64_t batch, int64_t mt, int64_t nt, int64_t *pid_out);
+
+/* 1 if kernels for this (bm, bn, bk) are built, else 0.  (0,0,0) is always supported. */
+int32_t nt_tile_supported(nt_tile_cfg cfg);
+
+/* ------------------------------------------------------------------------- kernels (device)
+ *
+ * nt_gemm: C[M,N] = A[M,K] . B[K,N]  -- the matmul application of Section 4.2 run over the
+ * arrangement above: fp32 accumulator, one dot per k tile, store converted to out_dtype
+ * (round to nearest even).  A, B, C are device pointers; descriptors are host structs
+ * with ndim 2.  in_dtype is NT_F16 or NT_BF16; out_dtype NT_F16, NT_BF16 or NT_F32.
+ * Any strides are accepted; unit-stride operands with 16-byte aligned rows take the
+ * fastest path.  M or N of 0: nothing is launched.  K of 0: C is zero-filled.
+ * C must not alias A or B.
+ */
+nt_status nt_gemm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
+                  void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
+                  nt_tile_cfg cfg, void *hip_stream);
+
+/* nt_bmm: the same per batch index; descriptors have ndim 3: [batch,M,K], [batch,K,N], [batch,M,N]
+ * (listed among the paper's kernels in Section 5.1). */
+nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
+                 void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
+                 nt_tile_cfg cfg, void *hip_stream);
+
+/*
+ * nt_conv2d_implicit: y[N,K,P,Q] = cross-correlation of x[N,C,H,W] with w[K,C,R,S]
+ * (Section 4.3), computed as the matmul (N*P*Q, C*R*S) x (C*R*S, K) without materialising
+ * the unfolded input: the input tile is gathered through the arrangement's index map,
+ * out-of-image positions (padding) read as zero.  dy must have P = (H + 2*pad_h - R) /
+ * stride_h + 1 (integer division), likewise Q; otherwise NT_ERR_SHAPE_MISMATCH.
+ * Descriptors have ndim 4 with arbitrary strides.
+ */
+nt_status nt_conv2d_implicit(const void *x, const nt_tensor_desc *dx, const void *w, const nt_tensor_desc *dw,
+                             void *y, const nt_tensor_desc *dy,
+                             int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                             nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *hip_stream);
+
+/*
+ * nt_trace_tile: device twin of the *_arrange_tile calls.  Launches a small kernel that
+ * runs the SAME device address generator the compute kernels use, for one operand tile of
+ * program `program_id` at k tile `k`, and writes offsets (int64, -1 where masked) and masks
+ * (uint8) to the DEVICE arrays offsets_out / mask_out of `capacity` entries (row-major over
+ * the tile).  kind: 0 = gemm, 1 = bmm, 2 = conv2d (conv arguments ignored otherwise).
+ */
+nt_status nt_trace_tile(int32_t kind, const nt_tensor_desc *d0, const nt_tensor_desc *d1, const nt_tensor_desc *d2,
+                        int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                        nt_tile_cfg cfg, int32_t operand, int64_t program_id, int64_t k,
+                        int64_t *offsets_out, uint8_t *mask_out, size_t capacity, void *hip_stream);
+
+/* Thread-local, statically stored description of the last error on this thread ("" if none). */
+const char *nt_last_error(void);
+
+/* Library version string (static storage). */
+const char *nt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NT_H */

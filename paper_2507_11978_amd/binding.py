@@ -1,0 +1,291 @@
+"""ctypes binding of include/nt.h -- argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libnt.so")
+MAX_DIMS, MAX_LEVELS = 6, 8
+
+OP_TILE, OP_EXPAND, OP_SQUEEZE, OP_PERMUTE, OP_FLATTEN, OP_RAVEL, OP_DESCEND, OP_ASCEND = range(8)
+_DTYPES = {"f16": 0, "bf16": 1, "f32": 2}
+_STATUS = {1: "NT_ERR_INVALID_ARG", 2: "NT_ERR_SHAPE_MISMATCH", 3: "NT_ERR_UNSUPPORTED",
+           4: "NT_ERR_BUFFER_TOO_SMALL", 5: "NT_ERR_DEVICE"}
+
+
+class NtError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+        self.name = _STATUS.get(status, str(status))
+
+
+class TensorDesc(C.Structure):
+    _fields_ = [("ndim", C.c_int32), ("size", C.c_int64 * MAX_DIMS), ("stride", C.c_int64 * MAX_DIMS)]
+
+
+class MetaOp(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("n", C.c_int32), ("a", C.c_int64 * MAX_DIMS), ("b", C.c_int64 * MAX_DIMS),
+                ("c", C.c_int64 * MAX_DIMS), ("d", C.c_int64 * MAX_DIMS)]
+
+
+class TileCfg(C.Structure):
+    _fields_ = [("bm", C.c_int32), ("bn", C.c_int32), ("bk", C.c_int32)]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load libnt.so (built beforehand by paper_2507_11978_amd/build.py); never falls back."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: run `python -m paper_2507_11978_amd.build` "
+                           "(or __graft_entry__.build()) first; there is no fallback path")
+    L = C.CDLL(_LIB_PATH)
+    P, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    D, O = C.POINTER(TensorDesc), C.POINTER(MetaOp)
+    L.nt_arrange_levels.argtypes = [D, O, i32, P, P, P]
+    L.nt_arrange_tile.argtypes = [D, O, i32, i64, P, i32, P, P, C.c_size_t, P, P, P, P]
+    arr_tail = [TileCfg, P, P, i32, i64, i64, P, P, C.c_size_t, P]
+    L.nt_arrange_gemm.argtypes = [D, D, D] + arr_tail
+    L.nt_arrange_bmm.argtypes = [D, D, D] + arr_tail
+    L.nt_arrange_conv2d.argtypes = [D, D, D, i32, i32, i32, i32] + arr_tail
+    L.nt_program_order.argtypes = [i64, i64, i64, P]
+    L.nt_tile_supported.argtypes = [TileCfg]
+    L.nt_tile_supported.restype = i32
+    L.nt_gemm.argtypes = [P, D, P, D, P, D, i32, i32, TileCfg, P]
+    L.nt_bmm.argtypes = [P, D, P, D, P, D, i32, i32, TileCfg, P]
+    L.nt_conv2d_implicit.argtypes = [P, D, P, D, P, D, i32, i32, i32, i32, i32, i32, TileCfg, P]
+    L.nt_trace_tile.argtypes = [i32, D, D, D, i32, i32, i32, i32, TileCfg, i32, i64, i64, P, P, C.c_size_t, P]
+    for name in ("nt_arrange_levels", "nt_arrange_tile", "nt_arrange_gemm", "nt_arrange_bmm", "nt_arrange_conv2d",
+                 "nt_program_order", "nt_gemm", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile"):
+        getattr(L, name).restype = i32
+    L.nt_last_error.restype = C.c_char_p
+    L.nt_version.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def _check(st: int):
+    if st != 0:
+        raise NtError(st, load().nt_last_error().decode())
+
+
+def version() -> str:
+    return load().nt_version().decode()
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def make_desc(shape: Sequence[int], strides: Sequence[int] | None = None) -> TensorDesc:
+    shape = [int(s) for s in shape]
+    if strides is None:
+        strides, acc = [], 1
+        for s in reversed(shape):
+            strides.append(acc)
+            acc *= max(s, 1)
+        strides.reverse()
+    d = TensorDesc()
+    d.ndim = len(shape)
+    for i, (s, t) in enumerate(zip(shape, strides)):
+        d.size[i], d.stride[i] = int(s), int(t)
+    return d
+
+
+def _desc_of(t) -> TensorDesc:
+    """Descriptor of a torch tensor (sizes and element strides) or a (shape, strides) pair."""
+    if isinstance(t, TensorDesc):
+        return t
+    if hasattr(t, "data_ptr"):
+        return make_desc(tuple(t.shape), tuple(t.stride()))
+    return make_desc(*t)
+
+
+def make_ops(ops) -> tuple:
+    """ops: tuples ("tile", shape[, strides[, pad]]), ("expand", shape), ("squeeze", dim),
+    ("permute", order), ("flatten", start, end), ("ravel",), ("descend",), ("ascend",);
+    pad is a sequence of (low, high) pairs."""
+    arr = (MetaOp * max(len(ops), 1))()
+    for o, op in zip(arr, ops):
+        kind = op[0]
+        vals = {"a": [], "b": [], "c": [], "d": []}
+        if kind == "tile":
+            o.kind, vals["a"] = OP_TILE, list(op[1])
+            if len(op) > 2 and op[2] is not None:
+                vals["b"] = list(op[2])
+            if len(op) > 3 and op[3] is not None:
+                vals["c"], vals["d"] = [p[0] for p in op[3]], [p[1] for p in op[3]]
+        elif kind == "expand":
+            o.kind, vals["a"] = OP_EXPAND, list(op[1])
+        elif kind == "squeeze":
+            o.kind, vals["a"] = OP_SQUEEZE, [op[1]]
+        elif kind == "permute":
+            o.kind, vals["a"] = OP_PERMUTE, list(op[1])
+        elif kind == "flatten":
+            o.kind, vals["a"] = OP_FLATTEN, [op[1], op[2]]
+        elif kind == "ravel":
+            o.kind = OP_RAVEL
+        elif kind == "descend":
+            o.kind = OP_DESCEND
+        elif kind == "ascend":
+            o.kind = OP_ASCEND
+        else:
+            raise ValueError(kind)
+        o.n = len(vals["a"])
+        for f, v in vals.items():
+            for i, x in enumerate(v):
+                getattr(o, f)[i] = int(x)
+    return arr, len(ops)
+
+
+def _cfg(tile) -> TileCfg:
+    if tile is None:
+        return TileCfg(0, 0, 0)
+    if isinstance(tile, TileCfg):
+        return tile
+    return TileCfg(*[int(x) for x in tile])
+
+
+# ------------------------------------------------------------------------ arrangement
+def arrange_levels(shape, strides, ops):
+    d = make_desc(shape, strides)
+    arr, n = make_ops(ops)
+    nl = C.c_int32()
+    nd = (C.c_int32 * MAX_LEVELS)()
+    sh = (C.c_int64 * (MAX_LEVELS * MAX_DIMS))()
+    _check(load().nt_arrange_levels(C.byref(d), arr, n, C.byref(nl), nd, sh))
+    return [tuple(sh[l * MAX_DIMS + i] for i in range(nd[l])) for l in range(nl.value)]
+
+
+def arrange_tile(shape, strides, ops, program_id, mid=(), capacity=None):
+    """Returns (offsets int64[], mask uint8[], tile_shape, grid_shape)."""
+    d = make_desc(shape, strides)
+    arr, n = make_ops(ops)
+    tshape, gshape = (C.c_int64 * MAX_DIMS)(), (C.c_int64 * MAX_DIMS)()
+    tnd, gnd = C.c_int32(), C.c_int32()
+    midv = (C.c_int64 * max(len(mid), 1))(*[int(m) for m in mid])
+    L = load()
+    _check(L.nt_arrange_tile(C.byref(d), arr, n, int(program_id), midv, len(mid), None, None, 0,
+                             tshape, C.byref(tnd), gshape, C.byref(gnd)))
+    ts = tuple(tshape[i] for i in range(tnd.value))
+    gs = tuple(gshape[i] for i in range(gnd.value))
+    count = int(np.prod(ts)) if ts else 1
+    cap = count if capacity is None else capacity
+    off = np.empty(max(cap, 1), dtype=np.int64)
+    mask = np.empty(max(cap, 1), dtype=np.uint8)
+    _check(L.nt_arrange_tile(C.byref(d), arr, n, int(program_id), midv, len(mid), off.ctypes.data, mask.ctypes.data,
+                             cap, tshape, C.byref(tnd), gshape, C.byref(gnd)))
+    return off[:count], mask[:count], ts, gs
+
+
+def _arrange_problem(fn, descs, extra, tile, operand, program_id, k):
+    grid = (C.c_int64 * 3)()
+    kt = C.c_int64()
+    tshape = (C.c_int64 * 2)()
+    cfg = _cfg(tile)
+    ds = [C.byref(_desc_of(d)) for d in descs]
+    if operand is None:
+        _check(fn(*ds, *extra, cfg, grid, C.byref(kt), 0, 0, 0, None, None, 0, None))
+        return tuple(grid), kt.value
+    _check(fn(*ds, *extra, cfg, grid, C.byref(kt), int(operand), int(program_id), int(k), None, None, 0, tshape))
+    count = tshape[0] * tshape[1]
+    off = np.empty(max(count, 1), dtype=np.int64)
+    mask = np.empty(max(count, 1), dtype=np.uint8)
+    _check(fn(*ds, *extra, cfg, grid, C.byref(kt), int(operand), int(program_id), int(k),
+              off.ctypes.data, mask.ctypes.data, count, tshape))
+    return off[:count], mask[:count], (tshape[0], tshape[1]), tuple(grid), kt.value
+
+
+def arrange_gemm(dA, dB, dC, tile=None, operand=None, program_id=0, k=0):
+    return _arrange_problem(load().nt_arrange_gemm, (dA, dB, dC), (), tile, operand, program_id, k)
+
+
+def arrange_bmm(dA, dB, dC, tile=None, operand=None, program_id=0, k=0):
+    return _arrange_problem(load().nt_arrange_bmm, (dA, dB, dC), (), tile, operand, program_id, k)
+
+
+def arrange_conv2d(dx, dw, dy, stride=(1, 1), pad=(0, 0), tile=None, operand=None, program_id=0, k=0):
+    extra = (int(stride[0]), int(stride[1]), int(pad[0]), int(pad[1]))
+    return _arrange_problem(load().nt_arrange_conv2d, (dx, dw, dy), extra, tile, operand, program_id, k)
+
+
+def program_order(batch: int, mt: int, nt: int) -> np.ndarray:
+    out = np.empty(max(batch * mt * nt, 1), dtype=np.int64)
+    _check(load().nt_program_order(batch, mt, nt, out.ctypes.data))
+    return out[:batch * mt * nt]
+
+
+def tile_supported(tile) -> bool:
+    return bool(load().nt_tile_supported(_cfg(tile)))
+
+
+# ---------------------------------------------------------------------------- kernels
+def _torch_dtype_name(t) -> str:
+    import torch
+    return {torch.float16: "f16", torch.bfloat16: "bf16", torch.float32: "f32"}[t.dtype]
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _require_cuda(*ts):
+    for t in ts:
+        if not t.is_cuda:
+            raise ValueError("tensors must live on the GPU (no CPU path exists)")
+
+
+def gemm(A, B, Cout, tile=None, stream=None):
+    """Cout[M,N] = A[M,K] @ B[K,N] on the GPU; tensors may be any strided views."""
+    _require_cuda(A, B, Cout)
+    _check(load().nt_gemm(A.data_ptr(), C.byref(_desc_of(A)), B.data_ptr(), C.byref(_desc_of(B)),
+                          Cout.data_ptr(), C.byref(_desc_of(Cout)), _DTYPES[_torch_dtype_name(A)],
+                          _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
+    return Cout
+
+
+def bmm(A, B, Cout, tile=None, stream=None):
+    _require_cuda(A, B, Cout)
+    _check(load().nt_bmm(A.data_ptr(), C.byref(_desc_of(A)), B.data_ptr(), C.byref(_desc_of(B)),
+                         Cout.data_ptr(), C.byref(_desc_of(Cout)), _DTYPES[_torch_dtype_name(A)],
+                         _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
+    return Cout
+
+
+def conv2d_implicit(x, w, y, stride=(1, 1), pad=(0, 0), tile=None, stream=None):
+    _require_cuda(x, w, y)
+    _check(load().nt_conv2d_implicit(x.data_ptr(), C.byref(_desc_of(x)), w.data_ptr(), C.byref(_desc_of(w)),
+                                     y.data_ptr(), C.byref(_desc_of(y)), int(stride[0]), int(stride[1]),
+                                     int(pad[0]), int(pad[1]), _DTYPES[_torch_dtype_name(x)],
+                                     _DTYPES[_torch_dtype_name(y)], _cfg(tile), _stream_ptr(stream)))
+    return y
+
+
+def trace_tile(kind, d0, d1, d2, tile, operand, program_id, k, stride=(1, 1), pad=(0, 0), stream=None):
+    """Device twin of arrange_*: returns (offsets, mask) numpy arrays computed on the GPU."""
+    import torch
+    kinds = {"gemm": 0, "bmm": 1, "conv2d": 2}
+    cfg = _cfg(tile)
+    if cfg.bm == 0:
+        raise ValueError("trace_tile needs an explicit tile")
+    cap = max(cfg.bm * cfg.bk, cfg.bk * cfg.bn, cfg.bm * cfg.bn)
+    off = torch.full((cap,), -7, dtype=torch.int64, device="cuda")
+    mask = torch.full((cap,), 9, dtype=torch.uint8, device="cuda")
+    _check(load().nt_trace_tile(kinds[kind], C.byref(_desc_of(d0)), C.byref(_desc_of(d1)), C.byref(_desc_of(d2)),
+                                int(stride[0]), int(stride[1]), int(pad[0]), int(pad[1]), cfg, int(operand),
+                                int(program_id), int(k), off.data_ptr(), mask.data_ptr(), cap, _stream_ptr(stream)))
+    torch.cuda.synchronize()
+    n = [cfg.bm * cfg.bk, cfg.bk * cfg.bn, cfg.bm * cfg.bn][operand]
+    return off[:n].cpu().numpy(), mask[:n].cpu().numpy()

@@ -1,0 +1,61 @@
+// Launch interface between the C ABI layer and the HIP kernels (host side).
+#pragma once
+#include <cstdint>
+#include <string>
+
+#include "../../include/nt.h"
+#include "opmap.h"
+
+namespace nt {
+
+nt_status fail(nt_status st, const std::string &msg);   // records the thread-local error text
+
+struct GemmLaunch {
+    const void *A;
+    const void *B;
+    void *C;
+    OperandMap ma, mb, mc;            // lowered operand maps (rows x cols views)
+    int64_t batch;                    // number of batch entries (1 for gemm / conv)
+    int64_t sa_batch, sb_batch, sc_batch;
+    int64_t M, N, K;
+    int64_t mt, nt, kt;               // grid of programs and k tiles (from the arrangement)
+    nt_tile_cfg tile;
+    int in_dtype, out_dtype;
+    void *stream;
+};
+
+// Which code path a launch would take (reported for tests and the benchmark).
+enum KernelPath { PATH_GENERIC = 0, PATH_FAST = 1 };
+
+bool tile_is_built(nt_tile_cfg cfg);
+nt_status launch_gemm(const GemmLaunch &g, int *path_out);
+nt_status launch_fill_zero(void *C, const OperandMap &mc, int64_t batch, int64_t sc_batch, int out_dtype, void *stream);
+nt_status launch_trace(const OperandMap &m, int64_t batch_off, int64_t row0, int64_t col0, int32_t rows, int32_t cols,
+                       int64_t *offsets_out, uint8_t *mask_out, void *stream);
+
+// workgroup index -> logical program id (shared by host query and device code)
+NT_HD int64_t program_of_workgroup(int64_t w, int64_t mt, int64_t nt)
+{
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one contiguous share of
+    // the tile sequence so that tiles resident on one L2 share operand rows / columns, and
+    // walk that sequence in bands of up to 8 tile rows.
+    const int64_t G = mt * nt;
+    const int64_t nx = 8;
+    int64_t seq;
+    {
+        const int64_t q = G / nx, r = G % nx;      // first r XCDs get q+1 tiles
+        const int64_t x = w % nx, l = w / nx;
+        seq = x < r ? x * (q + 1) + l : r * (q + 1) + (x - r) * q + l;
+    }
+    const int64_t band = 8;
+    const int64_t per_band = band * nt;
+    const int64_t b = seq / per_band;
+    const int64_t first = b * band;
+    const int64_t rows = mt - first < band ? mt - first : band;
+    const int64_t in = seq - b * per_band;
+    const int64_t i = first + in % rows;
+    const int64_t j = in / rows;
+    return i * nt + j;
+}
+
+}  // namespace nt

@@ -1,0 +1,263 @@
+// C ABI entry points (declared in include/nt.h): argument checking, the library's own
+// arrangements, lowering to device operand maps and kernel launches.
+#include <cstring>
+#include <string>
+
+#include "arrange.h"
+#include "kernels.h"
+
+namespace nt {
+const std::string &last_error();
+}
+
+using nt::Arrangement;
+using nt::fail;
+using nt::MatmulArrangement;
+using nt::OperandMap;
+
+namespace {
+
+#define NT_TRY(x) do { nt_status st__ = (x); if (st__ != NT_OK) return st__; } while (0)
+
+bool dtype_in_ok(int d) { return d == NT_F16 || d == NT_BF16; }
+bool dtype_out_ok(int d) { return d == NT_F16 || d == NT_BF16 || d == NT_F32; }
+
+// Default meta-parameters: the largest built tile that still yields enough programs to
+// occupy the 256 compute units.
+nt_tile_cfg pick_tile(int64_t batch, int64_t M, int64_t N, nt_tile_cfg cfg)
+{
+    if (cfg.bm || cfg.bn || cfg.bk) return cfg;
+    if (M <= 64 || N <= 64) return nt_tile_cfg{64, 64, 32};
+    const nt_tile_cfg cands[] = {{256, 256, 64}, {256, 128, 64}, {128, 128, 64}};
+    for (const nt_tile_cfg &c : cands) {
+        const int64_t tiles = batch * ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+        if (tiles >= 200) return c;
+    }
+    return nt_tile_cfg{128, 128, 64};
+}
+
+enum Kind { KIND_GEMM = 0, KIND_BMM = 1, KIND_CONV = 2 };
+
+struct Problem {
+    Arrangement va, vb, vc;          // single-level matrix views of the three operands
+    MatmulArrangement mm;            // the matmul arrangement applied to them
+    nt_tile_cfg tile;
+    int64_t batch = 1, M = 0, N = 0, K = 0;
+};
+
+nt_status build_problem(int kind, const nt_tensor_desc *d0, const nt_tensor_desc *d1, const nt_tensor_desc *d2,
+                        int32_t sh, int32_t sw, int32_t ph, int32_t pw, nt_tile_cfg cfg, Problem *p)
+{
+    if (!d0 || !d1 || !d2) return fail(NT_ERR_INVALID_ARG, "null tensor descriptor");
+    if (cfg.bm < 0 || cfg.bn < 0 || cfg.bk < 0) return fail(NT_ERR_INVALID_ARG, "negative tile size");
+    if ((cfg.bm || cfg.bn || cfg.bk) && !(cfg.bm && cfg.bn && cfg.bk))
+        return fail(NT_ERR_INVALID_ARG, "tile sizes must be all zero (default) or all positive");
+    if (kind == KIND_CONV) {
+        NT_TRY(nt::conv2d_views(d0, d1, d2, sh, sw, ph, pw, &p->va, &p->vb, &p->vc));
+    } else {
+        const int want = kind == KIND_BMM ? 3 : 2;
+        if (d0->ndim != want || d1->ndim != want || d2->ndim != want)
+            return fail(NT_ERR_SHAPE_MISMATCH, kind == KIND_BMM ? "bmm tensors must be 3-D" : "gemm tensors must be 2-D");
+        NT_TRY(p->va.init(d0));
+        NT_TRY(p->vb.init(d1));
+        NT_TRY(p->vc.init(d2));
+    }
+    const std::vector<int64_t> sa = p->va.level_shape(0), sb = p->vb.level_shape(0), sc = p->vc.level_shape(0);
+    const size_t o = sa.size() == 3 ? 1 : 0;
+    if (o == 1) {
+        if (sa[0] != sb[0] || sa[0] != sc[0]) return fail(NT_ERR_SHAPE_MISMATCH, "batch sizes differ");
+        p->batch = sa[0];
+    }
+    p->M = sa[o];
+    p->K = sa[o + 1];
+    p->N = sb[o + 1];
+    if (sb[o] != p->K) return fail(NT_ERR_SHAPE_MISMATCH, "inner dimensions of A and B differ");
+    if (sc[o] != p->M || sc[o + 1] != p->N) return fail(NT_ERR_SHAPE_MISMATCH, "output shape differs from [M, N]");
+    p->tile = pick_tile(p->batch, p->M, p->N, cfg);
+    NT_TRY(nt::arrange_matmul(p->va, p->vb, p->vc, p->tile, &p->mm));
+    return NT_OK;
+}
+
+nt_status arrange_query(int kind, const nt_tensor_desc *d0, const nt_tensor_desc *d1, const nt_tensor_desc *d2,
+                        int32_t sh, int32_t sw, int32_t ph, int32_t pw, nt_tile_cfg cfg,
+                        int64_t *grid_out, int64_t *kt_out, int32_t operand, int64_t program_id, int64_t k,
+                        int64_t *offsets_out, uint8_t *mask_out, size_t capacity, int64_t *tile_shape_out)
+{
+    Problem p;
+    NT_TRY(build_problem(kind, d0, d1, d2, sh, sw, ph, pw, cfg, &p));
+    if (grid_out) { grid_out[0] = p.mm.batch; grid_out[1] = p.mm.mt; grid_out[2] = p.mm.nt; }
+    if (kt_out) *kt_out = p.mm.kt;
+    if (!offsets_out && !mask_out && !tile_shape_out) return NT_OK;
+    if (operand < NT_OPERAND_A || operand > NT_OPERAND_C) return fail(NT_ERR_INVALID_ARG, "operand must be 0 (A), 1 (B) or 2 (C)");
+    const Arrangement &arr = operand == NT_OPERAND_A ? p.mm.a : operand == NT_OPERAND_B ? p.mm.b : p.mm.c;
+    int64_t shape[NT_MAX_DIMS] = {0}, gshape[NT_MAX_DIMS];
+    int32_t nd = 0, gnd = 0;
+    const int64_t mid[1] = {k};
+    const int n_mid = operand == NT_OPERAND_C ? 0 : 1;
+    nt_status st = arr.tile_index_set(program_id, mid, n_mid, offsets_out, mask_out, capacity, shape, &nd, gshape, &gnd);
+    if (tile_shape_out) { tile_shape_out[0] = shape[0]; tile_shape_out[1] = shape[1]; }
+    return st;
+}
+
+nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
+              void *C, const nt_tensor_desc *dC, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
+              nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *stream)
+{
+    if (!dtype_in_ok(in_dtype)) return fail(NT_ERR_UNSUPPORTED, "input dtype must be NT_F16 or NT_BF16");
+    if (!dtype_out_ok(out_dtype)) return fail(NT_ERR_UNSUPPORTED, "output dtype must be NT_F16, NT_BF16 or NT_F32");
+    if ((cfg.bm || cfg.bn || cfg.bk) && cfg.bm > 0 && cfg.bn > 0 && cfg.bk > 0 && !nt::tile_is_built(cfg))
+        return fail(NT_ERR_UNSUPPORTED, "no kernel built for this tile shape (see nt_tile_supported)");
+    Problem p;
+    NT_TRY(build_problem(kind, dA, dB, dC, sh, sw, ph, pw, cfg, &p));
+    if (p.batch == 0 || p.M == 0 || p.N == 0) return NT_OK;
+    if (!C || (p.K > 0 && (!A || !B))) return fail(NT_ERR_INVALID_ARG, "null device pointer");
+    nt::GemmLaunch g{};
+    int64_t nb;
+    NT_TRY(p.va.lower_matrix_view(&g.ma, &nb, &g.sa_batch));
+    NT_TRY(p.vb.lower_matrix_view(&g.mb, &nb, &g.sb_batch));
+    NT_TRY(p.vc.lower_matrix_view(&g.mc, &nb, &g.sc_batch));
+    if (p.K == 0) return nt::launch_fill_zero(C, g.mc, p.batch, g.sc_batch, out_dtype, stream);
+    g.A = A; g.B = B; g.C = C;
+    g.batch = p.batch;
+    g.M = p.M; g.N = p.N; g.K = p.K;
+    g.mt = p.mm.mt; g.nt = p.mm.nt; g.kt = p.mm.kt;
+    g.tile = p.tile;
+    g.in_dtype = in_dtype;
+    g.out_dtype = out_dtype;
+    g.stream = stream;
+    return nt::launch_gemm(g, nullptr);
+}
+
+}  // namespace
+
+extern "C" {
+
+nt_status nt_arrange_levels(const nt_tensor_desc *src, const nt_meta_op *ops, int32_t n_ops,
+                            int32_t *n_levels_out, int32_t *level_ndim_out, int64_t *level_shape_out)
+{
+    if (!n_levels_out || !level_ndim_out || !level_shape_out) return fail(NT_ERR_INVALID_ARG, "null output pointer");
+    Arrangement a;
+    NT_TRY(a.init(src));
+    NT_TRY(a.apply_all(ops, n_ops));
+    *n_levels_out = a.n_levels();
+    for (int l = 0; l < a.n_levels(); ++l) {
+        const std::vector<int64_t> s = a.level_shape(l);
+        level_ndim_out[l] = (int32_t)s.size();
+        for (size_t d = 0; d < s.size(); ++d) level_shape_out[l * NT_MAX_DIMS + d] = s[d];
+    }
+    return NT_OK;
+}
+
+nt_status nt_arrange_tile(const nt_tensor_desc *src, const nt_meta_op *ops, int32_t n_ops,
+                          int64_t program_id, const int64_t *mid_idx, int32_t n_mid,
+                          int64_t *offsets_out, uint8_t *mask_out, size_t capacity,
+                          int64_t *tile_shape_out, int32_t *tile_ndim_out,
+                          int64_t *grid_shape_out, int32_t *grid_ndim_out)
+{
+    Arrangement a;
+    NT_TRY(a.init(src));
+    NT_TRY(a.apply_all(ops, n_ops));
+    return a.tile_index_set(program_id, mid_idx, n_mid, offsets_out, mask_out, capacity,
+                            tile_shape_out, tile_ndim_out, grid_shape_out, grid_ndim_out);
+}
+
+nt_status nt_arrange_gemm(const nt_tensor_desc *dA, const nt_tensor_desc *dB, const nt_tensor_desc *dC,
+                          nt_tile_cfg cfg, int64_t *grid_out, int64_t *kt_out,
+                          int32_t operand, int64_t program_id, int64_t k,
+                          int64_t *offsets_out, uint8_t *mask_out, size_t capacity, int64_t *tile_shape_out)
+{
+    return arrange_query(KIND_GEMM, dA, dB, dC, 1, 1, 0, 0, cfg, grid_out, kt_out, operand, program_id, k,
+                         offsets_out, mask_out, capacity, tile_shape_out);
+}
+
+nt_status nt_arrange_bmm(const nt_tensor_desc *dA, const nt_tensor_desc *dB, const nt_tensor_desc *dC,
+                         nt_tile_cfg cfg, int64_t *grid_out, int64_t *kt_out,
+                         int32_t operand, int64_t program_id, int64_t k,
+                         int64_t *offsets_out, uint8_t *mask_out, size_t capacity, int64_t *tile_shape_out)
+{
+    return arrange_query(KIND_BMM, dA, dB, dC, 1, 1, 0, 0, cfg, grid_out, kt_out, operand, program_id, k,
+                         offsets_out, mask_out, capacity, tile_shape_out);
+}
+
+nt_status nt_arrange_conv2d(const nt_tensor_desc *dx, const nt_tensor_desc *dw, const nt_tensor_desc *dy,
+                            int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                            nt_tile_cfg cfg, int64_t *grid_out, int64_t *kt_out,
+                            int32_t operand, int64_t program_id, int64_t k,
+                            int64_t *offsets_out, uint8_t *mask_out, size_t capacity, int64_t *tile_shape_out)
+{
+    return arrange_query(KIND_CONV, dx, dw, dy, stride_h, stride_w, pad_h, pad_w, cfg, grid_out, kt_out,
+                         operand, program_id, k, offsets_out, mask_out, capacity, tile_shape_out);
+}
+
+nt_status nt_program_order(int64_t batch, int64_t mt, int64_t nt_, int64_t *pid_out)
+{
+    if (!pid_out) return fail(NT_ERR_INVALID_ARG, "null output pointer");
+    if (batch < 0 || mt < 0 || nt_ < 0) return fail(NT_ERR_INVALID_ARG, "negative grid size");
+    const int64_t per = mt * nt_;
+    for (int64_t w = 0; w < batch * per; ++w) {
+        const int64_t b = w / per;
+        pid_out[w] = b * per + nt::program_of_workgroup(w - b * per, mt, nt_);
+    }
+    return NT_OK;
+}
+
+int32_t nt_tile_supported(nt_tile_cfg cfg)
+{
+    if (cfg.bm == 0 && cfg.bn == 0 && cfg.bk == 0) return 1;
+    return nt::tile_is_built(cfg) ? 1 : 0;
+}
+
+nt_status nt_gemm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
+                  void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
+                  nt_tile_cfg cfg, void *hip_stream)
+{
+    return run(KIND_GEMM, A, dA, B, dB, C, dC, 1, 1, 0, 0, in_dtype, out_dtype, cfg, hip_stream);
+}
+
+nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
+                 void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
+                 nt_tile_cfg cfg, void *hip_stream)
+{
+    return run(KIND_BMM, A, dA, B, dB, C, dC, 1, 1, 0, 0, in_dtype, out_dtype, cfg, hip_stream);
+}
+
+nt_status nt_conv2d_implicit(const void *x, const nt_tensor_desc *dx, const void *w, const nt_tensor_desc *dw,
+                             void *y, const nt_tensor_desc *dy,
+                             int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                             nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *hip_stream)
+{
+    return run(KIND_CONV, x, dx, w, dw, y, dy, stride_h, stride_w, pad_h, pad_w, in_dtype, out_dtype, cfg, hip_stream);
+}
+
+nt_status nt_trace_tile(int32_t kind, const nt_tensor_desc *d0, const nt_tensor_desc *d1, const nt_tensor_desc *d2,
+                        int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                        nt_tile_cfg cfg, int32_t operand, int64_t program_id, int64_t k,
+                        int64_t *offsets_out, uint8_t *mask_out, size_t capacity, void *hip_stream)
+{
+    if (kind < KIND_GEMM || kind > KIND_CONV) return fail(NT_ERR_INVALID_ARG, "kind must be 0 (gemm), 1 (bmm) or 2 (conv2d)");
+    if (operand < NT_OPERAND_A || operand > NT_OPERAND_C) return fail(NT_ERR_INVALID_ARG, "operand must be 0, 1 or 2");
+    if (!offsets_out || !mask_out) return fail(NT_ERR_INVALID_ARG, "null output pointer");
+    Problem p;
+    NT_TRY(build_problem(kind, d0, d1, d2, stride_h, stride_w, pad_h, pad_w, cfg, &p));
+    const int64_t per = p.mm.mt * p.mm.nt;
+    if (program_id < 0 || program_id >= p.mm.batch * per) return fail(NT_ERR_INVALID_ARG, "program_id outside the grid");
+    if (operand != NT_OPERAND_C && (k < 0 || k >= p.mm.kt)) return fail(NT_ERR_INVALID_ARG, "k outside the k tiles");
+    const int64_t b = program_id / per, i = (program_id % per) / p.mm.nt, j = program_id % p.mm.nt;
+    OperandMap m;
+    int64_t nb, bstride;
+    const Arrangement &view = operand == NT_OPERAND_A ? p.va : operand == NT_OPERAND_B ? p.vb : p.vc;
+    NT_TRY(view.lower_matrix_view(&m, &nb, &bstride));
+    int64_t row0, col0;
+    int32_t rows, cols;
+    if (operand == NT_OPERAND_A) { row0 = i * p.tile.bm; col0 = k * p.tile.bk; rows = p.tile.bm; cols = p.tile.bk; }
+    else if (operand == NT_OPERAND_B) { row0 = k * p.tile.bk; col0 = j * p.tile.bn; rows = p.tile.bk; cols = p.tile.bn; }
+    else { row0 = i * p.tile.bm; col0 = j * p.tile.bn; rows = p.tile.bm; cols = p.tile.bn; }
+    if ((size_t)rows * (size_t)cols > capacity) return fail(NT_ERR_BUFFER_TOO_SMALL, "trace buffers smaller than the tile");
+    return nt::launch_trace(m, b * bstride, row0, col0, rows, cols, offsets_out, mask_out, hip_stream);
+}
+
+const char *nt_last_error(void) { return nt::last_error().c_str(); }
+
+const char *nt_version(void) { return "nt-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

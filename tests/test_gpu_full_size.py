@@ -1,0 +1,88 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times:
+sampled outputs against the oracle's one-by-one dot products (corners, tile borders and
+random positions), plus cheap whole-output properties."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_11978_amd as nt
+import synthetic_inputs as si
+from oracle import numeric as onum
+from gpu_util import ABS_GATE, REL_GATE, REL_GATE_F32, TORCH_DT, to_f64, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_positions(M, N, tile, n_random, seed):
+    rng = np.random.default_rng(seed)
+    bm, bn = tile
+    ms = [0, M - 1, 0, M - 1, bm - 1, min(bm, M - 1), (M // bm) * bm - 1, min((M // bm) * bm, M - 1)]
+    ns = [0, N - 1, N - 1, 0, bn - 1, min(bn, N - 1), (N // bn) * bn - 1, min((N // bn) * bn, N - 1)]
+    ms += rng.integers(0, M, n_random).tolist()
+    ns += rng.integers(0, N, n_random).tolist()
+    return np.array(ms, dtype=np.int64), np.array(ns, dtype=np.int64)
+
+
+def check_samples(got, ref, out):
+    d = got - ref
+    assert np.abs(d).max() <= ABS_GATE, f"max abs err {np.abs(d).max():.3e}"
+    rel = np.linalg.norm(d) / np.linalg.norm(ref)
+    assert rel <= (REL_GATE_F32 if out == "f32" else REL_GATE), f"rel err {rel:.3e}"
+
+
+@pytest.mark.parametrize("name", ["c2_f16_4096", "c3_bf16_ragged", "p_f16_8192"])
+def test_full_size_gemm(name):
+    cfg = si.CONFIGS[name]
+    M, N, K, dt, out = cfg["M"], cfg["N"], cfg["K"], cfg["dtype"], cfg["out"]
+    A, B = si.gemm_inputs(M, N, K, dt, cfg["seed"], cfg["dist"])
+    C = torch.full((M, N), float("nan"), dtype=TORCH_DT[out], device="cuda")
+    nt.gemm(to_gpu(A, dt), to_gpu(B, dt), C)           # library default tile, as in the benchmark
+    torch.cuda.synchronize()
+    assert torch.isfinite(C).all()
+    ms, ns = sample_positions(M, N, (256, 256), 300, seed=1)
+    ref = onum.gemm_samples(A, B, dt, ms, ns)
+    got = to_f64(C[torch.from_numpy(ms).cuda(), torch.from_numpy(ns).cuda()])
+    check_samples(got, ref, out)
+    if name == "c3_bf16_ragged":
+        # also the bf16-output variant, gated on the relative error only (|C| reaches ~70, where
+        # the bf16 spacing alone exceeds the absolute gate)
+        Cb = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        nt.gemm(to_gpu(A, dt), to_gpu(B, dt), Cb)
+        torch.cuda.synchronize()
+        gotb = to_f64(Cb[torch.from_numpy(ms).cuda(), torch.from_numpy(ns).cuda()])
+        assert np.linalg.norm(gotb - ref) / np.linalg.norm(ref) <= REL_GATE
+        assert np.array_equal(to_f64(C.to(torch.bfloat16)), to_f64(Cb))
+
+
+def test_full_size_bmm():
+    cfg = si.CONFIGS["c4_f16_bmm"]
+    Bn, M, N, K, dt = cfg["batch"], cfg["M"], cfg["N"], cfg["K"], cfg["dtype"]
+    A, B = si.gemm_inputs(M, N, K, dt, cfg["seed"], cfg["dist"], batch=Bn)
+    C = torch.full((Bn, M, N), float("nan"), dtype=torch.float16, device="cuda")
+    nt.bmm(to_gpu(A, dt), to_gpu(B, dt), C)
+    torch.cuda.synchronize()
+    assert torch.isfinite(C).all()
+    for b in [0, 13, Bn - 1]:
+        ms, ns = sample_positions(M, N, (256, 256), 100, seed=b)
+        ref = onum.gemm_samples(A[b], B[b], dt, ms, ns)
+        got = to_f64(C[b][torch.from_numpy(ms).cuda(), torch.from_numpy(ns).cuda()])
+        check_samples(got, ref, "f16")
+
+
+def test_full_size_conv():
+    cfg = si.CONFIGS["c5_f16_conv"]
+    N, Cc, H, W, K, R, S = (cfg[k] for k in ("N", "C", "H", "W", "K", "R", "S"))
+    dt = cfg["dtype"]
+    X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, dt, cfg["seed"])
+    Y = torch.full((N, K, H, W), float("nan"), dtype=torch.float16, device="cuda")
+    nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), (1, 1))
+    torch.cuda.synchronize()
+    assert torch.isfinite(Y).all()
+    rng = np.random.default_rng(3)
+    idx = np.stack([rng.integers(0, N, 300), rng.integers(0, K, 300), rng.integers(0, H, 300), rng.integers(0, W, 300)], 1)
+    corners = [[0, 0, 0, 0], [N - 1, K - 1, H - 1, W - 1], [0, K - 1, 0, W - 1], [N - 1, 0, H - 1, 0], [5, 7, 0, 31], [5, 7, 55, 31]]
+    idx = np.concatenate([np.array(corners), idx])
+    ref = onum.conv2d_samples(X, Wt, dt, idx, (1, 1), (1, 1))
+    ti = torch.from_numpy(idx).cuda()
+    got = to_f64(Y[ti[:, 0], ti[:, 1], ti[:, 2], ti[:, 3]])
+    check_samples(got, ref, "f16")

@@ -1,0 +1,234 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element
+on sizes the oracle finishes in seconds, covering several tiles, ragged tails, every operand
+orientation, both input formats, all output formats and the degenerate cases."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_11978_amd as nt
+import synthetic_inputs as si
+from oracle import arrangement as arr
+from oracle import numeric as onum
+from gpu_util import TORCH_DT, assert_gates, to_f64, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gemm(A, B, dt, out, tile, M, N):
+    C = torch.full((M, N), float("nan"), dtype=TORCH_DT[out], device="cuda")
+    nt.gemm(to_gpu(A, dt), to_gpu(B, dt), C, tile=tile)
+    torch.cuda.synchronize()
+    return to_f64(C)
+
+
+def test_c1_256_cubed_tile_64x64x32():
+    cfg = si.CONFIGS["c1_f16_256"]
+    A, B = si.gemm_inputs(256, 256, 256, "f16", cfg["seed"], cfg["dist"])
+    ref = onum.gemm(A, B, "f16")
+    got = run_gemm(A, B, "f16", "f16", (64, 64, 32), 256, 256)
+    assert_gates(got, ref, "f16", "c1")
+    got32 = run_gemm(A, B, "f16", "f32", (64, 64, 32), 256, 256)
+    assert_gates(got32, ref, "f32", "c1 f32 out")
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("tile", [(64, 64, 32), (128, 128, 64), (256, 128, 64), (128, 256, 64), (256, 256, 64), None])
+@pytest.mark.parametrize("M,N,K", [(300, 260, 200), (512, 512, 256), (257, 129, 65), (1, 1, 1), (129, 520, 72)])
+def test_gemm_shapes_and_tiles(dt, tile, M, N, K):
+    A, B = si.gemm_inputs(M, N, K, dt, seed=M + N + K, dist="uniform")
+    ref = onum.gemm(A, B, dt)
+    got = run_gemm(A, B, dt, "f32", tile, M, N)
+    assert_gates(got, ref, "f32", f"{dt} {M}x{N}x{K} tile {tile}")
+
+
+@pytest.mark.parametrize("out", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+def test_output_formats_round_to_nearest_even(dt, out):
+    M, N, K = 200, 264, 136
+    A, B = si.gemm_inputs(M, N, K, dt, seed=5, dist="normal")
+    ref = onum.gemm(A, B, dt)
+    got = run_gemm(A, B, dt, out, (128, 128, 64), M, N)
+    assert_gates(got, ref, out, f"{dt}->{out}")
+    if out != "f32":
+        # the stored value must be the fp32 accumulator rounded once: compare with the fp32 run
+        acc = torch.from_numpy(run_gemm(A, B, dt, "f32", (128, 128, 64), M, N)).to(torch.float32)
+        assert np.array_equal(to_f64(acc.to(TORCH_DT[out])), got)
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("tile", [(64, 64, 32), (128, 128, 64), (256, 256, 64)])
+def test_integer_inputs_are_exact(dt, tile):
+    # small integers: every product and partial sum is exact in fp32, so the result is bit exact
+    M, N, K = 260, 300, 190
+    A, B = si.gemm_inputs(M, N, K, dt, seed=2, dist="int")
+    ref = onum.gemm(A, B, dt)
+    got = run_gemm(A, B, dt, "f32", tile, M, N)
+    assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("tb", [False, True])
+@pytest.mark.parametrize("tc", [False, True])
+@pytest.mark.parametrize("M,N,K,tile", [(384, 256, 192, (128, 128, 64)), (301, 263, 131, (128, 128, 64)),
+                                        (301, 263, 131, (64, 64, 32)), (512, 512, 128, (256, 256, 64))])
+def test_operand_orientations(ta, tb, tc, M, N, K, tile):
+    """A, B, C given as transposed views (unit stride along the other axis)."""
+    dt = "f16"
+    A, B = si.gemm_inputs(M, N, K, dt, seed=9, dist="uniform")
+    ref = onum.gemm(A, B, dt)
+    At = to_gpu(A.T.copy(), dt).t() if ta else to_gpu(A, dt)
+    Bt = to_gpu(B.T.copy(), dt).t() if tb else to_gpu(B, dt)
+    Cs = torch.full((N, M) if tc else (M, N), float("nan"), dtype=torch.float32, device="cuda")
+    Cv = Cs.t() if tc else Cs
+    assert At.shape == (M, K) and Bt.shape == (K, N) and Cv.shape == (M, N)
+    nt.gemm(At, Bt, Cv, tile=tile)
+    torch.cuda.synchronize()
+    assert_gates(to_f64(Cv), ref, "f32", f"ta={ta} tb={tb} tc={tc}")
+
+
+def test_general_strides_and_padded_pitch():
+    dt, M, N, K = "bf16", 150, 170, 90
+    A, B = si.gemm_inputs(M, N, K, dt, seed=4, dist="uniform")
+    ref = onum.gemm(A, B, dt)
+    # A embedded with row pitch K+3 and column step 2; B with pitch N+5; C with pitch N+7
+    Abuf = torch.zeros((M, 2 * K + 3), dtype=TORCH_DT[dt], device="cuda")
+    Abuf[:, 0:2 * K:2] = to_gpu(A, dt)
+    Bbuf = torch.zeros((K, N + 5), dtype=TORCH_DT[dt], device="cuda")
+    Bbuf[:, :N] = to_gpu(B, dt)
+    Cbuf = torch.full((M, N + 7), -5.0, dtype=torch.float32, device="cuda")
+    for tile in [(64, 64, 32), (128, 128, 64)]:
+        Cbuf.fill_(-5.0)
+        nt.gemm(Abuf[:, 0:2 * K:2], Bbuf[:, :N], Cbuf[:, :N], tile=tile)
+        torch.cuda.synchronize()
+        assert_gates(to_f64(Cbuf[:, :N]), ref, "f32", f"strided {tile}")
+        assert (Cbuf[:, N:] == -5.0).all(), "store outside the C view"
+
+
+def test_unaligned_base_pointers():
+    # operands that start 2 bytes off a 16-byte boundary and have odd pitches (like the ragged bf16 case)
+    dt, M, N, K = "bf16", 271, 333, 199
+    A, B = si.gemm_inputs(M, N, K, dt, seed=6, dist="uniform")
+    ref = onum.gemm(A, B, dt)
+    Ab = torch.zeros(M * K + 1, dtype=TORCH_DT[dt], device="cuda")
+    Bb = torch.zeros(K * N + 3, dtype=TORCH_DT[dt], device="cuda")
+    Ab[1:] = to_gpu(A, dt).reshape(-1)
+    Bb[3:] = to_gpu(B, dt).reshape(-1)
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    nt.gemm(Ab[1:].view(M, K), Bb[3:].view(K, N), C, tile=(128, 128, 64))
+    torch.cuda.synchronize()
+    assert_gates(to_f64(C), ref, "f32", "unaligned")
+
+
+@pytest.mark.parametrize("tile", [(64, 64, 32), (128, 128, 64), None])
+def test_bmm_small(tile):
+    dt, Bn, M, N, K = "f16", 3, 200, 136, 72
+    A, B = si.gemm_inputs(M, N, K, dt, seed=8, dist="normal", batch=Bn)
+    ref = onum.bmm(A, B, dt)
+    C = torch.full((Bn, M, N), float("nan"), dtype=torch.float16, device="cuda")
+    nt.bmm(to_gpu(A, dt), to_gpu(B, dt), C, tile=tile)
+    torch.cuda.synchronize()
+    assert_gates(to_f64(C), ref, "f16", f"bmm {tile}")
+
+
+def test_bmm_strided_batch_views():
+    dt, Bn, M, N, K = "f16", 4, 128, 128, 64
+    A, B = si.gemm_inputs(M, N, K, dt, seed=12, dist="normal", batch=Bn)
+    ref = onum.bmm(A, B, dt)
+    # batch-minor storage: [M, batch, K] viewed as [batch, M, K]
+    Ag = to_gpu(A.transpose(1, 0, 2).copy(), dt).permute(1, 0, 2)
+    C = torch.full((Bn, M, N), float("nan"), dtype=torch.float32, device="cuda")
+    nt.bmm(Ag, to_gpu(B, dt), C, tile=(128, 128, 64))
+    torch.cuda.synchronize()
+    assert_gates(to_f64(C), ref, "f32", "bmm strided")
+
+
+@pytest.mark.parametrize("shape,stride,pad,tile", [
+    ((2, 8, 12, 14, 24, 3, 3), (1, 1), (1, 1), (64, 64, 32)),
+    ((3, 16, 9, 10, 70, 3, 2), (2, 2), (1, 0), (64, 64, 32)),
+    ((2, 32, 16, 16, 130, 3, 3), (1, 1), (1, 1), (128, 128, 64)),
+    ((1, 5, 7, 7, 3, 1, 1), (1, 1), (0, 0), None),
+    ((2, 6, 10, 8, 9, 3, 3), (2, 1), (2, 1), None),
+    ((4, 64, 14, 14, 64, 3, 3), (1, 1), (1, 1), None),
+])
+def test_conv2d_small(shape, stride, pad, tile):
+    N, Cc, H, W, K, R, S = shape
+    dt = "f16"
+    X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, dt, seed=13)
+    ref = onum.conv2d(X, Wt, dt, stride, pad)
+    Y = torch.full(ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+    nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, stride, pad, tile=tile)
+    torch.cuda.synchronize()
+    assert_gates(to_f64(Y), ref, "f32", f"conv {shape} {stride} {pad}")
+
+
+def test_conv2d_channels_last_views():
+    # NHWC storage presented as NCHW views: the index map is stride generic
+    N, Cc, H, W, K, R, S = 2, 8, 9, 9, 16, 3, 3
+    X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, "bf16", seed=14)
+    ref = onum.conv2d(X, Wt, "bf16", (1, 1), (1, 1))
+    Xg = to_gpu(X.transpose(0, 2, 3, 1).copy(), "bf16").permute(0, 3, 1, 2)
+    Y = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda").permute(0, 3, 1, 2)
+    nt.conv2d_implicit(Xg, to_gpu(Wt, "bf16"), Y, (1, 1), (1, 1))
+    torch.cuda.synchronize()
+    assert_gates(to_f64(Y), ref, "f32", "conv nhwc")
+
+
+def test_degenerate_shapes():
+    dt = "f16"
+    z = torch.zeros((0,), dtype=torch.float16, device="cuda")
+    # K = 0: C is zero-filled
+    C = torch.full((5, 7), float("nan"), dtype=torch.float32, device="cuda")
+    nt.gemm(z.view(5, 0), z.view(0, 7), C)
+    torch.cuda.synchronize()
+    assert (C == 0).all()
+    # M = 0 / N = 0: nothing happens, no error
+    nt.gemm(z.view(0, 4), torch.zeros((4, 7), dtype=torch.float16, device="cuda"), torch.zeros((0, 7), dtype=torch.float16, device="cuda"))
+    nt.bmm(z.view(0, 4, 4), z.view(0, 4, 4), z.view(0, 4, 4))
+    torch.cuda.synchronize()
+    with pytest.raises(nt.NtError) as e:
+        nt.gemm(torch.zeros((4, 5), dtype=torch.float16, device="cuda"), torch.zeros((6, 7), dtype=torch.float16, device="cuda"),
+                torch.zeros((4, 7), dtype=torch.float16, device="cuda"))
+    assert e.value.name == "NT_ERR_SHAPE_MISMATCH"
+
+
+# ---------------------------------------------------------------- device index maps
+def test_device_address_generator_matches_oracle():
+    """The address generator used inside the kernels, dumped by a trace kernel, against
+    the oracle's enumerator (bit exact)."""
+    # matmul, ragged
+    M, N, K, tile = 150, 170, 90, (64, 64, 32)
+    a, b, c = arr.mm_arrangement(arr.Tensor((M, K)), arr.Tensor((K, N)), arr.Tensor((M, N)), *tile)
+    d = (((M, K), None), ((K, N), None), ((M, N), None))
+    for pid in [0, 2, 8]:
+        for k in [0, 2]:
+            for operand, t in ((0, a), (1, b)):
+                off, mask = nt.trace_tile("gemm", *d, tile, operand, pid, k)
+                o_off, o_mask, _ = arr.tile_index_set(t, pid, (k,))
+                assert np.array_equal(off, o_off) and np.array_equal(mask, o_mask)
+        off, mask = nt.trace_tile("gemm", *d, tile, 2, pid, 0)
+        o_off, o_mask, _ = arr.tile_index_set(c, pid)
+        assert np.array_equal(off, o_off) and np.array_equal(mask, o_mask)
+    # convolution with stride and padding
+    Nn, Cc, H, W, Kf, R, S, stride, pad = 2, 5, 9, 10, 70, 3, 3, (2, 1), (1, 1)
+    P, Q = (H + 2 - R) // 2 + 1, (W + 2 - S) + 1
+    a, b, c = arr.conv2d_arrangement(arr.Tensor((Nn, Cc, H, W)), arr.Tensor((Kf, Cc, R, S)), arr.Tensor((Nn, Kf, P, Q)),
+                                     *tile, stride, pad)
+    d = (((Nn, Cc, H, W), None), ((Kf, Cc, R, S), None), ((Nn, Kf, P, Q), None))
+    G = a.levels[0][0] * a.levels[0][1]
+    for pid in range(G):
+        for k in range(a.levels[1][0]):
+            for operand, t in ((0, a), (1, b)):
+                off, mask = nt.trace_tile("conv2d", *d, tile, operand, pid, k, stride, pad)
+                o_off, o_mask, _ = arr.tile_index_set(t, pid, (k,))
+                assert np.array_equal(off, o_off) and np.array_equal(mask, o_mask)
+        off, mask = nt.trace_tile("conv2d", *d, tile, 2, pid, 0, stride, pad)
+        o_off, o_mask, _ = arr.tile_index_set(c, pid)
+        assert np.array_equal(off, o_off) and np.array_equal(mask, o_mask)
+    # batched
+    Bn = 3
+    a, b, c = arr.bmm_arrangement(arr.Tensor((Bn, M, K)), arr.Tensor((Bn, K, N)), arr.Tensor((Bn, M, N)), *tile)
+    d = (((Bn, M, K), None), ((Bn, K, N), None), ((Bn, M, N), None))
+    for pid in [0, 10, 26]:
+        off, mask = nt.trace_tile("bmm", *d, tile, 0, pid, 1)
+        o_off, o_mask, _ = arr.tile_index_set(a, pid, (1,))
+        assert np.array_equal(off, o_off) and np.array_equal(mask, o_mask)
