@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: one
+nt_gemm / nt_bmm / nt_conv2d_implicit call (arrangement build, lowering, kernel).  The
+default workload is the one the headline metric is quoted on: the square 8192^3 fp16 GEMM
+with fp32 accumulation and fp16 output.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: throughput (TFLOP/s, true 2*M*N*K flops), the roofline of the
+dominant kernel from HIP-event timings of each launch, and the CPU oracle timed on a
+bounded sample of the same workload (reported baseline only).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+METRIC = "GEMM TFLOP/s and % of MI355X fp16 MFMA peak, 1 GPU, 8192^3 fp16"
+MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense fp16/bf16 matrix peak (published)
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="p_f16_8192",
+                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c1_f16_256")
+    ap.add_argument("--tile", default=None, help="bm,bn,bk (default: library choice)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    return ap.parse_args()
+
+
+def flops_and_bytes(cfg):
+    """True flops per step and algorithmic HBM bytes (inputs read once, output written once)."""
+    osz = 4 if cfg["out"] == "f32" else 2
+    if cfg["kind"] == "conv":
+        N, C, H, W, K, R, S = (cfg[k] for k in ("N", "C", "H", "W", "K", "R", "S"))
+        P = (H + 2 * cfg["pad"] - R) // cfg["stride"] + 1
+        Q = (W + 2 * cfg["pad"] - S) // cfg["stride"] + 1
+        return 2.0 * N * P * Q * K * C * R * S, 2 * (N * C * H * W + K * C * R * S) + osz * N * K * P * Q
+    b = cfg.get("batch", 1)
+    M, N, K = cfg["M"], cfg["N"], cfg["K"]
+    return 2.0 * b * M * N * K, b * (2 * (M * K + K * N) + osz * M * N)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build targets one GPU; run with --gpus 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2507_11978_amd as nt
+    import synthetic_inputs as si
+    from gpu_util import TORCH_DT, to_f64, to_gpu
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    nt.load()
+    cfg = si.CONFIGS[args.workload]
+    tile = tuple(int(x) for x in args.tile.split(",")) if args.tile else cfg.get("tile")
+    dt, out = cfg["dtype"], cfg["out"]
+
+    # ---- inputs, resident in HBM before timing starts
+    if cfg["kind"] == "conv":
+        Xb, Wb = si.conv_inputs(cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"], cfg["R"], cfg["S"], dt, cfg["seed"])
+        x, w = to_gpu(Xb, dt), to_gpu(Wb, dt)
+        P = (cfg["H"] + 2 * cfg["pad"] - cfg["R"]) // cfg["stride"] + 1
+        Q = (cfg["W"] + 2 * cfg["pad"] - cfg["S"]) // cfg["stride"] + 1
+        y = torch.empty((cfg["N"], cfg["K"], P, Q), dtype=TORCH_DT[out], device="cuda")
+        st, pd = (cfg["stride"],) * 2, (cfg["pad"],) * 2
+        step = lambda: nt.conv2d_implicit(x, w, y, st, pd, tile=tile)
+        grid, kt = nt.arrange_conv2d(x, w, y, st, pd, tile=tile)
+    else:
+        Ab, Bb = si.gemm_inputs(cfg["M"], cfg["N"], cfg["K"], dt, cfg["seed"], cfg["dist"], batch=cfg.get("batch"))
+        a, b = to_gpu(Ab, dt), to_gpu(Bb, dt)
+        shape = (cfg["M"], cfg["N"]) if cfg["kind"] == "gemm" else (cfg["batch"], cfg["M"], cfg["N"])
+        y = torch.empty(shape, dtype=TORCH_DT[out], device="cuda")
+        fn = nt.gemm if cfg["kind"] == "gemm" else nt.bmm
+        step = lambda: fn(a, b, y, tile=tile)
+        grid, kt = (nt.arrange_gemm if cfg["kind"] == "gemm" else nt.arrange_bmm)(a, b, y, tile=tile)
+    flops, alg_bytes = flops_and_bytes(cfg)
+
+    # ---- warm-up, then exactly K timed steps bracketed by synchronisation
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record()          # events on the stream the kernel is launched on (torch's current)
+        step()
+        ends[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, ends)])
+    ms_per_step = wall * 1e3 / args.steps
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    kern_avg = float(kern_ms.mean())
+    achieved = flops / (kern_avg * 1e-3) / 1e12
+
+    result = {
+        "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
+        "pct_of_mfma_peak": round(100.0 * value / MFMA_PEAK_TFLOPS, 2),
+        "config": {"workload": args.workload, "shape": {k: cfg[k] for k in cfg if k in ("M", "N", "K", "batch", "C", "H", "W", "R", "S", "stride", "pad")},
+                   "in_dtype": dt, "out_dtype": out, "accumulate": "f32",
+                   "grid": list(grid), "k_tiles": int(kt), "tile": list(tile) if tile else "library default"},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "kernel_ms_avg": round(kern_avg, 4), "kernel_ms_min": round(float(kern_ms.min()), 4),
+                     "kernel_ms_median": round(float(np.median(kern_ms)), 4),
+                     "algorithmic_bytes": int(alg_bytes),
+                     "hbm_gbs_algorithmic": round(alg_bytes / (kern_avg * 1e-3) / 1e9, 1), "hbm_peak_gbs": HBM_PEAK_GBS},
+    }
+
+    # ---- correctness of the timed output, against the oracle on sampled elements
+    if not args.no_check:
+        from oracle import numeric as onum
+        rng = np.random.default_rng(7)
+        if cfg["kind"] == "conv":
+            idx = np.stack([rng.integers(0, s, 64) for s in y.shape], 1)
+            ref = onum.conv2d_samples(Xb, Wb, dt, idx, st, pd)
+            ti = torch.from_numpy(idx).cuda()
+            got = to_f64(y[ti[:, 0], ti[:, 1], ti[:, 2], ti[:, 3]])
+        else:
+            M, N = cfg["M"], cfg["N"]
+            ms, ns = rng.integers(0, M, 64), rng.integers(0, N, 64)
+            bsel = 0 if cfg["kind"] == "gemm" else cfg["batch"] - 1
+            A2, B2 = (Ab, Bb) if cfg["kind"] == "gemm" else (Ab[bsel], Bb[bsel])
+            ref = onum.gemm_samples(A2, B2, dt, ms, ns)
+            yy = y if cfg["kind"] == "gemm" else y[bsel]
+            got = to_f64(yy[torch.from_numpy(ms).cuda(), torch.from_numpy(ns).cuda()])
+        result["parity"] = {"samples": int(ref.size), "max_abs_err": float(np.abs(got - ref).max()),
+                            "rel_frobenius_err": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported baseline only)
+    if not args.no_cpu_baseline and cfg["kind"] != "conv":
+        from oracle import numeric as onum
+        cores = min(os.cpu_count() or 1, 16)
+        M, N, K = cfg["M"], cfg["N"], cfg["K"]
+        ms_, ns_ = min(M, 1024), min(N, 1024)
+        A2, B2 = (Ab, Bb) if cfg["kind"] == "gemm" else (Ab[0], Bb[0])
+        t1 = time.perf_counter()
+        onum.gemm(A2[:ms_, :], B2[:, :ns_], dt, nthreads=cores)
+        dt_cpu = time.perf_counter() - t1
+        result["cpu_baseline"] = {"value": round(2.0 * ms_ * ns_ * K / dt_cpu / 1e12, 6), "unit": "TFLOP/s", "cores": cores,
+                                  "kind": "oracle", "seconds": round(dt_cpu, 2),
+                                  "sample": f"rows 0..{ms_ - 1} x cols 0..{ns_ - 1} of the product, full K={K} (fp64 triple loop)"}
+    elif not args.no_cpu_baseline:
+        from oracle import numeric as onum
+        cores = min(os.cpu_count() or 1, 16)
+        t1 = time.perf_counter()
+        onum.conv2d(Xb[:1], Wb[:64], dt, st, pd, nthreads=cores)
+        dt_cpu = time.perf_counter() - t1
+        fl = 2.0 * P * Q * 64 * cfg["C"] * cfg["R"] * cfg["S"]
+        result["cpu_baseline"] = {"value": round(fl / dt_cpu / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                                  "seconds": round(dt_cpu, 2), "sample": "image 0, filters 0..63 (direct fp64 convolution)"}
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
