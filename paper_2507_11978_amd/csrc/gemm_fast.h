@@ -1,0 +1,338 @@
+// Fast kernel for plain operands that have unit stride along one of their axes.
+//
+// One workgroup (4 wavefronts, 2 x 2) computes one BM x BN output tile (one program of the
+// tile-to-program mapping, Section 3.2.1).  Per k tile (BK = 64) every thread fetches its
+// share of the A and B blocks with 16-byte global loads into staging registers, writes
+// them to LDS in the swizzled k-contiguous layout (B, or a column-major A, is transposed
+// in registers on the way) and the wavefronts read 8-element k runs as MFMA operands.
+//
+// This is the path for ragged sizes and operands that are not 16-byte aligned: loads are
+// predicated per 16-byte chunk (edge chunks fall back to element loads, masked elements read
+// as zero) and stores are masked.  Aligned full tiles take the direct kernel instead.
+#pragma once
+#include <type_traits>
+
+#include "gemm_device.h"
+
+namespace nt {
+
+// Operand orientations:
+//   A: KCONTIG = A[m, k] contiguous along k (row-major [M,K]); MNCONTIG = contiguous along m
+//   B: MNCONTIG = B[k, n] contiguous along n (row-major [K,N]); KCONTIG = contiguous along k
+constexpr int KCONTIG = 0, MNCONTIG = 1;
+constexpr int kBK = 64;
+
+struct FastArgs {
+    const uint16_t *A;
+    const uint16_t *B;
+    void *C;
+    int64_t lda, ldb;              // stride (elements) of the axis that is not contiguous
+    int64_t scm, scn;              // C strides (elements)
+    int64_t sa_batch, sb_batch, sc_batch;
+    int64_t M, N, K;
+    int64_t mt, nt, kt;
+    int out_dtype;
+};
+
+__device__ __forceinline__ u32x4 gload16(const char *base, uint32_t off)
+{
+    // 16 bytes from a possibly only 2-byte aligned address (unaligned vector loads are
+    // legal for global memory on this target); uniform base + 32-bit lane offset
+    u32x4 v;
+    __builtin_memcpy(&v, base + off, 16);
+    return v;
+}
+
+__device__ __forceinline__ u32x2 gload8(const char *base, uint32_t off)
+{
+    u32x2 v;
+    __builtin_memcpy(&v, base + off, 8);
+    return v;
+}
+
+__device__ __forceinline__ uint32_t gload2(const char *base, uint32_t off)
+{
+    return *reinterpret_cast<const uint16_t *>(base + off);
+}
+
+__device__ __forceinline__ void lds_write16(char *smem, uint32_t addr, u32x4 v)
+{
+    *reinterpret_cast<u32x4 *>(smem + addr) = v;
+}
+
+__device__ __forceinline__ u32x4 lds_read16(const char *smem, uint32_t addr)
+{
+    return *reinterpret_cast<const u32x4 *>(smem + addr);
+}
+
+// ---- staging of a (ROWS x 64) operand block whose LDS rows are contiguous in memory along k
+template <int ROWS, bool EDGE>
+struct StageK {
+    static constexpr int CH = ROWS * 8 / kThreads;        // 16-byte chunks per thread
+    u32x4 r[CH];
+    uint32_t voff[CH];                                    // byte offsets from the tile origin
+    uint32_t wbase;                                       // swizzled LDS byte offset of chunk 0
+    int row0, ch;
+
+    __device__ __forceinline__ void init(int tid, int64_t ld)
+    {
+        row0 = tid >> 3;
+        ch = tid & 7;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) voff[i] = ((uint32_t)(i * 32 + row0) * (uint32_t)ld + (uint32_t)(ch * 8)) * 2u;
+        const int s0 = (row0 & 7) ^ (tid >> 6);
+        wbase = (uint32_t)(row0 * 128 + ((ch ^ s0) << 4));
+    }
+    // rows_left / k_left: valid rows and k elements counted from the tile origin (EDGE only)
+    __device__ __forceinline__ void load(const char *base, int64_t rows_left, int64_t k_left)
+    {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            if constexpr (!EDGE) {
+                r[i] = gload16(base, voff[i]);
+            } else {
+                const int64_t left = k_left - ch * 8;
+                const bool row_ok = i * 32 + row0 < rows_left;
+                if (row_ok && left >= 8) {
+                    r[i] = gload16(base, voff[i]);
+                } else {
+                    uint32_t e[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) e[q] = (row_ok && q < left) ? gload2(base, voff[i] + 2 * q) : 0u;
+                    r[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+                }
+            }
+        }
+    }
+    __device__ __forceinline__ void store(char *smem, uint32_t buf_off) const
+    {
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+            lds_write16(smem, buf_off + (wbase ^ ((i & 1) << 6)) + i * 4096, r[i]);
+    }
+};
+
+// ---- staging of a (ROWS x 64) block whose memory is contiguous along the LDS row index
+// (m for a column-major A, n for a row-major B).  Each thread owns one 8(k) x NW(rows)
+// block: NW contiguous elements from each of 8 consecutive k lines, transposed in
+// registers into NW chunks of 8 consecutive k.
+template <int ROWS, bool EDGE>
+struct StageMN {
+    static constexpr int NW = ROWS / 32;                  // 8 for 256 rows, 4 for 128 rows
+    static_assert(NW == 8 || NW == 4, "transposing loader supports 128 or 256 rows");
+    uint32_t r[8][NW / 2];                                // [k line][packed pairs of rows]
+    uint32_t voff[8];
+    uint32_t wbase;
+    int kb, rb;
+
+    __device__ __forceinline__ void init(int tid, int64_t ld)
+    {
+        kb = tid >> 5;
+        rb = tid & 31;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) voff[j] = ((uint32_t)(kb * 8 + j) * (uint32_t)ld + (uint32_t)(rb * NW)) * 2u;
+        const int s = NW == 8 ? (rb & 7) : ((((rb & 1) << 2) ^ (rb >> 1)) & 7);
+        wbase = (uint32_t)(rb * NW * 128 + ((kb ^ s) << 4));
+    }
+    __device__ __forceinline__ void load(const char *base, int64_t rows_left, int64_t k_left)
+    {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            bool full = true;
+            if constexpr (EDGE) full = kb * 8 + j < k_left && rb * NW + NW <= rows_left;
+            if (full) {
+                if constexpr (NW == 8) {
+                    const u32x4 v = gload16(base, voff[j]);
+                    r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
+                } else {
+                    const u32x2 v = gload8(base, voff[j]);
+                    r[j][0] = v[0]; r[j][1] = v[1];
+                }
+            } else {
+                const bool k_ok = kb * 8 + j < k_left;
+#pragma unroll
+                for (int h = 0; h < NW / 2; ++h) {
+                    const uint32_t lo = (k_ok && rb * NW + 2 * h < rows_left) ? gload2(base, voff[j] + 4 * h) : 0u;
+                    const uint32_t hi = (k_ok && rb * NW + 2 * h + 1 < rows_left) ? gload2(base, voff[j] + 4 * h + 2) : 0u;
+                    r[j][h] = lo | (hi << 16);
+                }
+            }
+        }
+    }
+    __device__ __forceinline__ void store(char *smem, uint32_t buf_off) const
+    {
+#pragma unroll
+        for (int n = 0; n < NW; ++n) {
+            u32x4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t lo = r[2 * q][n >> 1], hi = r[2 * q + 1][n >> 1];
+                v[q] = (n & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+            }
+            lds_write16(smem, buf_off + (wbase ^ (n << 4)) + n * 128, v);
+        }
+    }
+};
+
+template <int ROWS, int LAY, bool EDGE> struct StageSel { using type = StageK<ROWS, EDGE>; };
+template <int ROWS, bool EDGE> struct StageSel<ROWS, MNCONTIG, EDGE> { using type = StageMN<ROWS, EDGE>; };
+
+template <int BM, int BN, typename OutT>
+__device__ __forceinline__ void store_tile_fast(OutT *__restrict__ C, int64_t scm, int64_t scn,
+                                                const float16v (&acc)[BM / 64][BN / 64],
+                                                int64_t row_base, int64_t col_base, int64_t M, int64_t N,
+                                                bool check, int out_dtype)
+{
+    constexpr int TM = BM / 64, TN = BN / 64;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const int64_t col = col_base + tn * 32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t row = row_base + tm * 32 + 8 * (v / 4) + (v % 4);
+                if (!check || (row < M && col < N)) {
+                    const float x = acc[tm][tn][v];
+                    if constexpr (sizeof(OutT) == 4) {
+                        C[row * scm + col * scn] = x;
+                    } else {
+                        C[row * scm + col * scn] = out_dtype == NT_F16 ? f32_to_f16_rne(x) : f32_to_bf16_rne(x);
+                    }
+                }
+            }
+        }
+}
+
+template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE>
+__global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
+{
+    constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr uint32_t A_BYTES = BM * kBK * 2, B_BYTES = BN * kBK * 2;
+    constexpr uint32_t B_BASE = 2 * A_BYTES;                 // LDS map: [A0][A1][B0][B1]
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    int64_t bi, ti, tj;
+    locate_program(g.mt, g.nt, &bi, &ti, &tj);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_m = wave >> 1, wave_n = wave & 1;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int64_t row0 = ti * BM, col0 = tj * BN;
+
+    // uniform tile origins (bytes) and per-k-tile steps
+    const char *gA = reinterpret_cast<const char *>(g.A + bi * g.sa_batch + (ALAY == KCONTIG ? row0 * g.lda : row0));
+    const char *gB = reinterpret_cast<const char *>(g.B + bi * g.sb_batch + (BLAY == KCONTIG ? col0 * g.ldb : col0));
+    const int64_t a_step = (ALAY == KCONTIG ? (int64_t)kBK : (int64_t)kBK * g.lda) * 2;
+    const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kBK : (int64_t)kBK * g.ldb) * 2;
+    const int64_t m_left = g.M - row0, n_left = g.N - col0;
+
+    typename StageSel<BM, ALAY, EDGE>::type sa;
+    typename StageSel<BN, BLAY, EDGE>::type sb;
+    sa.init(tid, g.lda);
+    sb.init(tid, g.ldb);
+
+    // per-lane LDS read bases: row (wave origin + l32) of each operand, chunk hi, swizzled
+    const int ra = wave_m * (BM / 2) + l32, rb = wave_n * (BN / 2) + l32;
+    const uint32_t a_rd = (uint32_t)(ra * 128 + ((hi ^ ((ra ^ (ra >> 3)) & 7)) << 4));
+    const uint32_t b_rd = (uint32_t)(rb * 128 + ((hi ^ ((rb ^ (rb >> 3)) & 7)) << 4)) + B_BASE;
+
+    float16v acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    // per-k-step fragment fetch from the copy at byte offset `copy_a` / `copy_b`
+    auto step = [&](int ks, uint32_t copy_a, uint32_t copy_b) {
+        u32x4 fa[TM], fb[TN];
+#pragma unroll
+        for (int t = 0; t < TM; ++t)
+            fa[t] = lds_read16(smem, (a_rd ^ (uint32_t)(((2 * ks) ^ ((t & 1) << 2)) << 4)) + t * 4096 + copy_a);
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+            fb[t] = lds_read16(smem, (b_rd ^ (uint32_t)(((2 * ks) ^ ((t & 1) << 2)) << 4)) + t * 4096 + copy_b);
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma32<BF16>(fa[tm], fb[tn], acc[tm][tn]);
+    };
+
+    // ---- prologue: tile 0 -> LDS copy 0
+    sa.load(gA, m_left, g.K);
+    sb.load(gB, n_left, g.K);
+    sa.store(smem, 0);
+    sb.store(smem, B_BASE);
+    __syncthreads();
+
+    // One k tile per trip: the next tile (clamped to the last one; the surplus copy is never
+    // read) is fetched into the staging registers before the current LDS copy is multiplied,
+    // and written to the idle copy afterwards.
+    const int64_t last = g.kt - 1;
+    uint32_t cur = 0;
+    for (int64_t k = 0; k < g.kt; ++k) {
+        const uint32_t nxt = cur ^ 1u;
+        const int64_t kn = k < last ? k + 1 : last;
+        sa.load(gA + kn * a_step, m_left, g.K - kn * kBK);
+        sb.load(gB + kn * b_step, n_left, g.K - kn * kBK);
+#pragma unroll
+        for (int ks = 0; ks < kBK / 16; ++ks) step(ks, cur * A_BYTES, cur * B_BYTES);
+        sa.store(smem, nxt * A_BYTES);
+        sb.store(smem, B_BASE + nxt * B_BYTES);
+        __syncthreads();
+        cur = nxt;
+    }
+
+    // ---- epilogue: convert and store (masked on ragged tiles)
+    const int64_t row_base = row0 + wave_m * (BM / 2) + 4 * hi;
+    const int64_t col_base = col0 + wave_n * (BN / 2) + l32;
+    const int64_t cb = bi * g.sc_batch;
+    const bool check = EDGE && (m_left < BM || n_left < BN);
+    if (g.out_dtype == NT_F32)
+        store_tile_fast<BM, BN, float>(reinterpret_cast<float *>(g.C) + cb, g.scm, g.scn, acc, row_base, col_base, g.M, g.N, check, g.out_dtype);
+    else
+        store_tile_fast<BM, BN, uint16_t>(reinterpret_cast<uint16_t *>(g.C) + cb, g.scm, g.scn, acc, row_base, col_base, g.M, g.N, check, g.out_dtype);
+}
+
+// ------------------------------------------------------------------ host launch helpers
+template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE>
+static nt_status launch_fast_inst(const FastArgs &a, int64_t nwg, hipStream_t s)
+{
+    constexpr size_t smem = (size_t)2 * (BM + BN) * kBK * sizeof(uint16_t);
+    auto kern = gemm_fast_kernel<BM, BN, BF16, ALAY, BLAY, EDGE>;
+    static bool configured = false;              // raise the dynamic LDS limit once per instantiation
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
+    return check_launch("gemm_fast_kernel");
+}
+
+template <int BM, int BN, bool BF16, bool EDGE>
+static nt_status launch_fast_lay(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s)
+{
+    if (alay == KCONTIG && blay == MNCONTIG) return launch_fast_inst<BM, BN, BF16, KCONTIG, MNCONTIG, EDGE>(a, nwg, s);
+    if (alay == KCONTIG && blay == KCONTIG) return launch_fast_inst<BM, BN, BF16, KCONTIG, KCONTIG, EDGE>(a, nwg, s);
+    if (alay == MNCONTIG && blay == MNCONTIG) return launch_fast_inst<BM, BN, BF16, MNCONTIG, MNCONTIG, EDGE>(a, nwg, s);
+    return launch_fast_inst<BM, BN, BF16, MNCONTIG, KCONTIG, EDGE>(a, nwg, s);
+}
+
+template <int BM, int BN>
+static nt_status launch_fast_t(const FastArgs &a, bool bf16, bool edge, int alay, int blay, int64_t nwg, hipStream_t s)
+{
+    if (bf16) return edge ? launch_fast_lay<BM, BN, true, true>(a, alay, blay, nwg, s)
+                          : launch_fast_lay<BM, BN, true, false>(a, alay, blay, nwg, s);
+    return edge ? launch_fast_lay<BM, BN, false, true>(a, alay, blay, nwg, s)
+                : launch_fast_lay<BM, BN, false, false>(a, alay, blay, nwg, s);
+}
+
+// one translation unit per tile shape defines these (parallel compilation)
+nt_status launch_fast_128x128(const FastArgs &a, bool bf16, bool edge, int alay, int blay, int64_t nwg, hipStream_t s);
+nt_status launch_fast_256x128(const FastArgs &a, bool bf16, bool edge, int alay, int blay, int64_t nwg, hipStream_t s);
+nt_status launch_fast_128x256(const FastArgs &a, bool bf16, bool edge, int alay, int blay, int64_t nwg, hipStream_t s);
+nt_status launch_fast_256x256(const FastArgs &a, bool bf16, bool edge, int alay, int blay, int64_t nwg, hipStream_t s);
+
+}  // namespace nt

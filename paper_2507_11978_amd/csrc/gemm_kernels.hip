@@ -1,5 +1,5 @@
 // Dispatch between the kernels, plus the small auxiliary kernels (zero fill, address trace).
-#include "gemm_device.h"
+#include "gemm_direct.h"
 
 namespace nt {
 
@@ -57,7 +57,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         if (g.mb.coff[0] == 1) { blay = MNCONTIG; a.ldb = g.mb.roff[0]; }
         else if (g.mb.roff[0] == 1) { blay = KCONTIG; a.ldb = g.mb.coff[0]; }
         else fast = false;
-        if (a.lda < 0 || a.ldb < 0) fast = false;
+        if (a.lda < 0 || a.ldb < 0 || a.lda >= (1 << 22) || a.ldb >= (1 << 22)) fast = false;   // 32-bit lane offsets
     }
     if (path_out) *path_out = fast ? PATH_FAST : PATH_GENERIC;
     if (fast) {
@@ -76,6 +76,17 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         const bool bf16 = g.in_dtype == NT_BF16;
         const int64_t nwg = g.batch * g.mt * g.nt;
         hipStream_t s = (hipStream_t)g.stream;
+        // full tiles of 16-byte aligned operands stream straight into LDS
+        auto al16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+        const bool direct = !edge && al16(a.A) && al16(a.B) && a.lda % 8 == 0 && a.ldb % 8 == 0 &&
+                            a.sa_batch % 8 == 0 && a.sb_batch % 8 == 0;
+        if (path_out) *path_out = direct ? PATH_DIRECT : PATH_FAST;
+        if (direct) {
+            if (t.bm == 128 && t.bn == 128) return launch_direct_128x128(a, bf16, alay, blay, nwg, s);
+            if (t.bm == 256 && t.bn == 128) return launch_direct_256x128(a, bf16, alay, blay, nwg, s);
+            if (t.bm == 128 && t.bn == 256) return launch_direct_128x256(a, bf16, alay, blay, nwg, s);
+            if (t.bm == 256 && t.bn == 256) return launch_direct_256x256(a, bf16, alay, blay, nwg, s);
+        }
         if (t.bm == 128 && t.bn == 128) return launch_fast_128x128(a, bf16, edge, alay, blay, nwg, s);
         if (t.bm == 256 && t.bn == 128) return launch_fast_256x128(a, bf16, edge, alay, blay, nwg, s);
         if (t.bm == 128 && t.bn == 256) return launch_fast_128x256(a, bf16, edge, alay, blay, nwg, s);
