@@ -1,21 +1,22 @@
 // Direct kernel: full tiles of 16-byte aligned, unit-stride operands.
 //
 // One workgroup (4 wavefronts, 2 x 2) computes one BM x BN output tile (one program of
-// the tile-to-program mapping, Section 3.2.1).  The (BM x 64) block of A and the
-// (64 x BN) block of B of each k tile (source-to-target mapping, Section 3.2.2) travel
-// from global memory straight into LDS (global_load_lds, 16 bytes per lane, no staging
-// registers); two LDS copies of each block alternate so the next k tile streams in while
-// the current one is multiplied.
+// the tile-to-program mapping, Section 3.2.1).  The blocks of A and B that the program
+// multiplies (source-to-target mapping, Section 3.2.2) travel from global memory straight
+// into LDS (global_load_lds, 16 bytes per lane, no staging registers) in slices of 32 k
+// (each 64-wide k tile of the arrangement is consumed as two such slices).  LDS holds a
+// ring of four slices per operand, so a slice is requested three slice-times (about 3000
+// cycles) before it is multiplied: long enough to cover an L2 miss.
 //
 // LDS layouts, chosen by how the operand lies in memory:
-//   k-major  (operand contiguous along k)    [row = m or n][64 k], 128 bytes per row; a
+//   k-major  (operand contiguous along k)    [row = m or n][32 k], 64 bytes per row; a
 //            lane's MFMA operand (8 consecutive k) is one ds_read_b128.
 //   mn-major (operand contiguous along m/n)  [k][E = BM or BN]; the MFMA operand is
 //            gathered with two transposing reads (ds_read_b64_tr_b16), each of which turns
 //            a 4(k) x 16(m/n) patch into 4 consecutive k per lane.
 // A direct-to-LDS load always writes lane l's 16 bytes to (instruction base + 16 l), so the
 // bank swizzle is applied on the global side: lane l fetches the chunk that belongs in
-// its slot.  k-major: chunk ^= (row ^ row/8) & 7; mn-major: chunk ^= (k & 3) * 4.
+// its slot.  k-major: chunk ^= (row / 4) & 3; mn-major: chunk ^= (k & 3) * 4.
 #pragma once
 #include <type_traits>
 
@@ -25,13 +26,18 @@ namespace nt {
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 
-// vmcnt(0) only: expcnt and lgkmcnt fields at "no wait"
-#define NT_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0F70)
+constexpr int kSliceK = 32;      // k extent of one LDS slice
+constexpr int kRing = 4;         // slices per operand resident in LDS
+
+// s_waitcnt that waits until at most n vector-memory operations are outstanding and leaves
+// the other counters alone (vmcnt is split over bits [3:0] and [15:14] of the immediate)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+#define NT_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(vmcnt_imm(n))
 
 // 16 bytes per lane from global memory straight into LDS: lane l's data lands at
 // lds_addr + 16 l.  gbase and lds_addr are wavefront-uniform, voff is the lane's byte offset.
 // Issued through inline assembly so that the compiler does not serialise later LDS reads of
-// the *other* LDS copy behind it; completion is awaited explicitly with NT_WAIT_VMCNT0.
+// other slices behind it; completion is awaited explicitly with NT_WAIT_VMCNT.
 __device__ __forceinline__ void dma16(const char *gbase, uint32_t voff, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
@@ -43,41 +49,46 @@ __device__ __forceinline__ void dma16(const char *gbase, uint32_t voff, uint32_t
 template <int E, int LAY>
 struct DirectTile;
 
-// ---- k-major block: E rows (m or n) x 64 k
+// ---- k-major slice: E rows (m or n) x 32 k
 template <int E>
 struct DirectTile<E, KCONTIG> {
-    static constexpr uint32_t BYTES = E * kBK * 2;
-    static constexpr int PER = BYTES / 1024 / 4;           // load instructions per wavefront
+    static constexpr uint32_t BYTES = E * kSliceK * 2;
+    static constexpr int PER = BYTES / 1024 / 4;           // load instructions per wavefront and slice
+    static constexpr int RPF = 1;                          // LDS reads per operand fragment
     uint32_t voff[PER];                                    // global byte offset of this lane's chunk
     uint32_t rd;                                           // LDS read base of this lane
 
-    __device__ __forceinline__ void init(int wave, int lane, int64_t ld, int wave_origin)
+    // region: LDS byte offset of this operand's ring (folded into the read base)
+    __device__ __forceinline__ void init(int wave, int lane, int64_t ld, int wave_origin, uint32_t region)
     {
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
-            const int row = (wave * PER + j) * 8 + (lane >> 3);
-            const int c = (lane & 7) ^ ((row ^ (row >> 3)) & 7);
+            const int row = (wave * PER + j) * 16 + (lane >> 2);
+            const int c = (lane & 3) ^ ((row >> 2) & 3);
             voff[j] = ((uint32_t)row * (uint32_t)ld + (uint32_t)(c * 8)) * 2u;
         }
         const int r = wave_origin + (lane & 31);
-        rd = (uint32_t)(r * 128 + (((lane >> 5) ^ ((r ^ (r >> 3)) & 7)) << 4));
+        rd = (uint32_t)(r * 64 + (((lane >> 5) ^ ((r >> 2) & 3)) << 4)) + region;
     }
-    __device__ __forceinline__ void issue(const char *g, uint32_t lds_base, int wave) const
+    __device__ __forceinline__ void issue_one(int j, const char *g, uint32_t lds_slice, int wave) const
     {
-#pragma unroll
-        for (int j = 0; j < PER; ++j) dma16(g, voff[j], lds_base + (uint32_t)((wave * PER + j) * 1024));
+        dma16(g, voff[j], lds_slice + (uint32_t)((wave * PER + j) * 1024));
     }
-    __device__ __forceinline__ u32x4 frag(const char *smem, int t, int ks, uint32_t lds_base) const
+    // fragment t (32 rows) of k step ks (0 or 1) of the slice at byte offset slice_off: one 16-byte read
+    __device__ __forceinline__ void read(u32x2 (&f)[2], const char *smem, int t, int ks, int part, uint32_t slice_off) const
     {
-        return lds_read16(smem, (rd ^ (uint32_t)(((2 * ks) ^ ((t & 1) << 2)) << 4)) + t * 4096 + lds_base);
+        const u32x4 v = lds_read16(smem, (rd ^ (uint32_t)(ks << 5)) + slice_off + t * 2048);
+        f[0] = u32x2{v[0], v[1]};
+        f[1] = u32x2{v[2], v[3]};
     }
 };
 
-// ---- mn-major block: 64 k rows x E (m or n)
+// ---- mn-major slice: 32 k rows x E (m or n)
 template <int E>
 struct DirectTile<E, MNCONTIG> {
-    static constexpr uint32_t BYTES = E * kBK * 2;
+    static constexpr uint32_t BYTES = E * kSliceK * 2;
     static constexpr int PER = BYTES / 1024 / 4;
+    static constexpr int RPF = 2;
     static constexpr int RB = 2 * E;                       // bytes per k row
     static constexpr int CPR = E / 8;                      // 16-byte chunks per k row
     static constexpr int RPI = 1024 / RB;                  // k rows per load instruction
@@ -85,7 +96,7 @@ struct DirectTile<E, MNCONTIG> {
     uint32_t voff[PER];
     uint32_t rd[T];
 
-    __device__ __forceinline__ void init(int wave, int lane, int64_t ld, int wave_origin)
+    __device__ __forceinline__ void init(int wave, int lane, int64_t ld, int wave_origin, uint32_t region)
     {
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
@@ -102,21 +113,18 @@ struct DirectTile<E, MNCONTIG> {
         const int sw = (i >> 2) << 2;                      // (k & 3) * 4 for every row this lane touches
 #pragma unroll
         for (int t = 0; t < T; ++t)
-            rd[t] = (uint32_t)(kl * RB + ((((mn >> 3) + 4 * t) ^ sw) << 4) + ((mn >> 2) & 1) * 8);
+            rd[t] = (uint32_t)(kl * RB + ((((mn >> 3) + 4 * t) ^ sw) << 4) + ((mn >> 2) & 1) * 8) + region;
     }
-    __device__ __forceinline__ void issue(const char *g, uint32_t lds_base, int wave) const
+    __device__ __forceinline__ void issue_one(int j, const char *g, uint32_t lds_slice, int wave) const
     {
-#pragma unroll
-        for (int j = 0; j < PER; ++j) dma16(g, voff[j], lds_base + (uint32_t)((wave * PER + j) * 1024));
+        dma16(g, voff[j], lds_slice + (uint32_t)((wave * PER + j) * 1024));
     }
-    __device__ __forceinline__ u32x4 frag(const char *smem, int t, int ks, uint32_t lds_base) const
+    // half `part` (k 0..3 or 4..7 of the lane's run) of fragment t: one transposing 8-byte read
+    __device__ __forceinline__ void read(u32x2 (&f)[2], const char *smem, int t, int ks, int part, uint32_t slice_off) const
     {
         typedef short4v __attribute__((address_space(3))) * lds_s4;
-        const uint32_t a = rd[t] + (uint32_t)(ks * 16 * RB) + lds_base;
-        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + a));
-        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + a + 4 * RB));
-        const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-        return u32x4{l2[0], l2[1], h2[0], h2[1]};
+        const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (rd[t] + slice_off + (uint32_t)((ks * 16 + part * 4) * RB))));
+        f[part] = __builtin_bit_cast(u32x2, v);
     }
 };
 
@@ -126,7 +134,7 @@ __global__ __launch_bounds__(kThreads) void gemm_direct_kernel(const FastArgs g)
     constexpr int TM = BM / 64, TN = BN / 64;
     using TileA = DirectTile<BM, ALAY>;
     using TileB = DirectTile<BN, BLAY>;
-    constexpr uint32_t A_BYTES = TileA::BYTES, B_BYTES = TileB::BYTES, B_BASE = 2 * A_BYTES;
+    constexpr uint32_t A_BYTES = TileA::BYTES, B_BYTES = TileB::BYTES, B_BASE = kRing * A_BYTES;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     int64_t bi, ti, tj;
@@ -139,13 +147,14 @@ __global__ __launch_bounds__(kThreads) void gemm_direct_kernel(const FastArgs g)
 
     const char *gA = reinterpret_cast<const char *>(g.A + bi * g.sa_batch + (ALAY == KCONTIG ? row0 * g.lda : row0));
     const char *gB = reinterpret_cast<const char *>(g.B + bi * g.sb_batch + (BLAY == KCONTIG ? col0 * g.ldb : col0));
-    const int64_t a_step = (ALAY == KCONTIG ? (int64_t)kBK : (int64_t)kBK * g.lda) * 2;
-    const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kBK : (int64_t)kBK * g.ldb) * 2;
+    const int64_t a_step = (ALAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.lda) * 2;
+    const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.ldb) * 2;
+    const int64_t n_slices = g.kt * (kBK / kSliceK);
 
     TileA ta;
     TileB tb;
-    ta.init(wave, lane, g.lda, wave_m * (BM / 2));
-    tb.init(wave, lane, g.ldb, wave_n * (BN / 2));
+    ta.init(wave, lane, g.lda, wave_m * (BM / 2), 0);
+    tb.init(wave, lane, g.ldb, wave_n * (BN / 2), B_BASE);
 
     float16v acc[TM][TN];
 #pragma unroll
@@ -158,60 +167,89 @@ __global__ __launch_bounds__(kThreads) void gemm_direct_kernel(const FastArgs g)
     // LDS byte address of the dynamic segment (it starts the workgroup's allocation)
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
 
-    u32x4 fa[2][TM], fb[2][TN];
-    auto fetch = [&](int slot, int ks, uint32_t copy) {
-#pragma unroll
-        for (int t = 0; t < TM; ++t) fa[slot][t] = ta.frag(smem, t, ks, copy * A_BYTES);
-#pragma unroll
-        for (int t = 0; t < TN; ++t) fb[slot][t] = tb.frag(smem, t, ks, B_BASE + copy * B_BYTES);
+    // operand fragments, double buffered: [slot][32-row block][low / high 4 k of the lane's run]
+    u32x2 fa[2][TM][2], fb[2][TN][2];
+    constexpr int NRB = TN * TileB::RPF, NR = TM * TileA::RPF + NRB;   // LDS reads per k step
+    // LDS read r of a k step, in the order the next step's MFMAs need the data:
+    // A block 0, every B block, then the remaining A blocks
+    auto lds_read = [&](int r, int slot, int ks, uint32_t ring) {
+        if (r < TileA::RPF) {
+            ta.read(fa[slot][0], smem, 0, ks, r, ring * A_BYTES);
+        } else if (r < TileA::RPF + NRB) {
+            const int q = r - TileA::RPF;
+            tb.read(fb[slot][q / TileB::RPF], smem, q / TileB::RPF, ks, q % TileB::RPF, ring * B_BYTES);
+        } else {
+            const int q = r - NRB;
+            ta.read(fa[slot][q / TileA::RPF], smem, q / TileA::RPF, ks, q % TileA::RPF, ring * A_BYTES);
+        }
     };
-    auto mma = [&](int slot) {
+    // The global->LDS loads of one slice, numbered 0 .. ND-1 (A's first): load d of the slice
+    // at (pa, pb) into ring position `ring`.
+    constexpr int NM = TM * TN, ND = TileA::PER + TileB::PER;
+    auto dma = [&](int d, const char *pa, const char *pb, uint32_t ring) {
+        if (d < TileA::PER) ta.issue_one(d, pa, lds0 + ring * A_BYTES, wave);
+        else tb.issue_one(d - TileA::PER, pb, lds0 + B_BASE + ring * B_BYTES, wave);
+    };
+    // One k step: the TM x TN MFMAs on fragment slot `slot`.  Between them, one at a time so
+    // that neither the LDS queue nor the memory queue ever holds the in-order wavefront back
+    // while the matrix pipe runs dry: the LDS reads of the next step's fragments (k step
+    // `ks_next` of ring position `rring`, into the other slot) and, if nd > 0, the nd
+    // global->LDS loads of the slice at (pa, pb) into ring position `dring`.
+    auto step = [&](int slot, int ks_next, uint32_t rring, int nd, const char *pa, const char *pb, uint32_t dring) {
+        constexpr int RQ = (NR + NM - 1) / NM;              // LDS reads after each MFMA
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
+        for (int idx = 0; idx < NM; ++idx) {
+            const int tm = idx / TN, tn = idx % TN;
+            const u32x4 xa{fa[slot][tm][0][0], fa[slot][tm][0][1], fa[slot][tm][1][0], fa[slot][tm][1][1]};
+            const u32x4 xb{fb[slot][tn][0][0], fb[slot][tn][0][1], fb[slot][tn][1][0], fb[slot][tn][1][1]};
+            acc[tm][tn] = mfma32<BF16>(xa, xb, acc[tm][tn]);
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma32<BF16>(fa[slot][tm], fb[slot][tn], acc[tm][tn]);
+            for (int q = 0; q < RQ; ++q)
+                if (idx * RQ + q < NR) lds_read(idx * RQ + q, slot ^ 1, ks_next, rring);
+            if (nd > 0) {
+                const int per = (nd + NM - 1) / NM;         // loads after each MFMA (when there are more loads than MFMAs)
+                const int gap = nd >= NM ? 1 : NM / nd;     // otherwise one load after every `gap` MFMAs
+                if (idx % gap == gap - 1)
+#pragma unroll
+                    for (int q = 0; q < per; ++q)
+                        if ((idx / gap) * per + q < nd) dma((idx / gap) * per + q, pa, pb, dring);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
-    // k tile 0 -> copy 0, then its first fragments
-    ta.issue(gA, lds0, wave);
-    tb.issue(gB, lds0 + B_BASE, wave);
-    NT_WAIT_VMCNT0();
+    const int64_t last = n_slices - 1;
+    auto slice_a = [&](int64_t s) { return gA + (s < last ? s : last) * a_step; };   // clamped: surplus slices are never read
+    auto slice_b = [&](int64_t s) { return gB + (s < last ? s : last) * b_step; };
+
+    // prologue: slices 0 .. 3 requested into the ring; wait for slice 0; its first fragments
+#pragma unroll
+    for (int s = 0; s < kRing; ++s)
+#pragma unroll
+        for (int d = 0; d < ND; ++d) dma(d, slice_a(s), slice_b(s), s);
+    NT_WAIT_VMCNT((kRing - 1) * ND);
     __syncthreads();
-    fetch(0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < NR; ++r) lds_read(r, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
 
-    // One k tile per trip, one basic block.  The next tile (clamped to the last one, whose
-    // surplus copy is never read) streams into the idle LDS copy while the current copy is
-    // multiplied; operand fragments are double buffered, each k step fetching the next
-    // step's fragments before issuing its own MFMAs.  The barrier sits before the last k
-    // step so that the first fragments of the next tile are fetched under its MFMAs.
-    const int64_t last = g.kt - 1;
-    uint32_t cur = 0;
-    for (int64_t k = 0; k < g.kt; ++k) {
-        const uint32_t nxt = cur ^ 1u;
-        const int64_t kn = k < last ? k + 1 : last;
-        ta.issue(gA + kn * a_step, lds0 + nxt * A_BYTES, wave);
-        tb.issue(gB + kn * b_step, lds0 + B_BASE + nxt * B_BYTES, wave);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(1, 1, cur);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(0);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(0, 2, cur);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(1);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(1, 3, cur);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(0);
-        __builtin_amdgcn_sched_barrier(0);
-        NT_WAIT_VMCNT0();                                  // this wave's share of the next tile has landed
-        __syncthreads();                                   // ... and everyone's; all reads of `cur` are done
-        fetch(0, 0, nxt);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(1);
-        __builtin_amdgcn_sched_barrier(0);
-        cur = nxt;
+    // One slice per trip, one basic block.  Slice s sits at ring position s % 4.
+    //   step A  multiplies k step 0 of slice s while reading its k step 1 fragments;
+    //   then waits until this wavefront's part of slice s+1 has landed (the loads of the two
+    //   younger slices may still be in flight) and meets the other wavefronts: slice s+1 is
+    //   complete, and nobody reads ring position s % 4 any more;
+    //   step B  multiplies k step 1 while reading the first fragments of slice s+1 and
+    //   requesting slice s+4 into the position just released.
+    uint32_t ring = 0;
+    for (int64_t sl = 0; sl < n_slices; ++sl) {
+        const uint32_t nxt = (ring + 1) & (kRing - 1);
+        step(0, 1, ring, 0, nullptr, nullptr, 0);
+        NT_WAIT_VMCNT(2 * ND);
+        __syncthreads();
+        step(1, 0, nxt, ND, slice_a(sl + kRing), slice_b(sl + kRing), ring);
+        ring = nxt;
     }
+    NT_WAIT_VMCNT(0);                                      // drain the surplus prefetches before the LDS is released
 
     const int64_t row_base = row0 + wave_m * (BM / 2) + 4 * hi;
     const int64_t col_base = col0 + wave_n * (BN / 2) + l32;
@@ -225,7 +263,7 @@ __global__ __launch_bounds__(kThreads) void gemm_direct_kernel(const FastArgs g)
 template <int BM, int BN, bool BF16, int ALAY, int BLAY>
 static nt_status launch_direct_inst(const FastArgs &a, int64_t nwg, hipStream_t s)
 {
-    constexpr size_t smem = (size_t)2 * (BM + BN) * kBK * sizeof(uint16_t);
+    constexpr size_t smem = (size_t)kRing * (BM + BN) * kSliceK * sizeof(uint16_t);
     auto kern = gemm_direct_kernel<BM, BN, BF16, ALAY, BLAY>;
     static bool configured = false;
     if (!configured) {
