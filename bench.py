@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"p_f16_8192": 1772000000}   # profiles/gemm_direct_8192_f16_counters.md
 
 
 def parse_args():
@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--tile", default=None, help="bm,bn,bk (default: library choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain device copy of known size instead (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -72,6 +74,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+    if args.calibrate_copy:
+        n = 1 << 30                                     # 1 GiB read + 1 GiB written per copy
+        src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "device copy", "bytes_read_per_copy": n, "bytes_written_per_copy": n, "copies": args.steps}))
+        return
     nt.load()
     cfg = si.CONFIGS[args.workload]
     tile = tuple(int(x) for x in args.tile.split(",")) if args.tile else cfg.get("tile")
@@ -157,7 +169,7 @@ def main():
         from oracle import numeric as onum
         cores = min(os.cpu_count() or 1, 16)
         M, N, K = cfg["M"], cfg["N"], cfg["K"]
-        ms_, ns_ = min(M, 1024), min(N, 1024)
+        ms_, ns_ = min(M, 4096), min(N, 4096)
         A2, B2 = (Ab, Bb) if cfg["kind"] == "gemm" else (Ab[0], Bb[0])
         t1 = time.perf_counter()
         onum.gemm(A2[:ms_, :], B2[:, :ns_], dt, nthreads=cores)
