@@ -1,4 +1,5 @@
 // Dispatch between the kernels, plus the small auxiliary kernels (zero fill, address trace).
+#include "gemm_conv.h"
 #include "gemm_direct.h"
 
 namespace nt {
@@ -39,6 +40,58 @@ bool tile_is_built(nt_tile_cfg cfg)
     return false;
 }
 
+// Recognise, from the lowered operand maps alone, the dense unit-stride convolution that
+// gemm_conv_kernel handles: A rows are (n, p, q) digits and columns (c, r, s) digits over a
+// contiguous NCHW input with the same step along h and along w for the output position and
+// the filter tap (conv stride 1), at most one element of left / right padding; B is a plain
+// k-contiguous matrix; C rows are (n, pq) digits with unit step along pq.
+static bool match_conv(const GemmLaunch &g, ConvArgs *a)
+{
+    const OperandMap &x = g.ma, &w = g.mb, &y = g.mc;
+    if (g.batch != 1 || g.tile.bm != 256 || g.tile.bk != 64 || (g.tile.bn != 128 && g.tile.bn != 256)) return false;
+    if (x.nrd != 3 || x.ncd != 3 || x.nchk > 2) return false;
+    const int64_t P = x.rrad[1], Q = x.rrad[2], R = x.crad[1], S = x.crad[2];
+    if (P <= 0 || Q <= 0 || R <= 0 || S <= 0 || R > 31 || Q % 8 != 0) return false;
+    if (x.roff[2] != 1 || x.coff[2] != 1 || x.roff[1] != x.coff[1]) return false;     // unit stride along w, conv stride 1
+    int64_t H = P + R - 1, W = Q + S - 1, ph = 0, pw = 0;
+    for (int q = 0; q < x.nchk; ++q) {
+        const bool is_h = x.rchk[q][0] == 0 && x.rchk[q][1] == 1 && x.rchk[q][2] == 0 && x.cchk[q][0] == 0 && x.cchk[q][1] == 1 && x.cchk[q][2] == 0;
+        const bool is_w = x.rchk[q][0] == 0 && x.rchk[q][1] == 0 && x.rchk[q][2] == 1 && x.cchk[q][0] == 0 && x.cchk[q][1] == 0 && x.cchk[q][2] == 1;
+        if (is_h) { ph = -x.chk0[q]; H = x.chk_size[q]; }
+        else if (is_w) { pw = -x.chk0[q]; W = x.chk_size[q]; }
+        else return false;
+    }
+    if (ph < 0 || pw < 0 || pw > 1 || W < 8) return false;
+    if (P != H + 2 * ph - R + 1 || Q != W + 2 * pw - S + 1) return false;
+    const int64_t CRS = x.cols, C = CRS / (R * S), NPQ = x.rows, Nimg = NPQ / (P * Q);
+    if (C * R * S != CRS || Nimg * P * Q != NPQ) return false;
+    if (x.coff[1] != W || x.coff[0] != H * W || x.roff[0] != C * H * W) return false;   // contiguous NCHW
+    if (x.base != -(ph * W + pw)) return false;
+    const int64_t numel = Nimg * C * H * W;
+    if (numel >= (1LL << 31) || NPQ >= (1LL << 31) || CRS >= (1 << 16) - 64) return false;
+    // filter: B[kk, f] with unit step along kk
+    if (!(w.nrd == 1 && w.ncd == 1 && w.nchk == 0 && w.roff[0] == 1 && w.coff[0] > 0 && w.coff[0] < (1 << 22))) return false;
+    // output: (n, pq) rows with unit step along pq, one digit along f
+    if (!(y.nrd == 2 && y.ncd == 1 && y.nchk == 0 && y.rrad[1] == P * Q && y.roff[1] == 1)) return false;
+    a->X = (const uint16_t *)g.A;
+    a->Wt = (const uint16_t *)g.B + w.base;
+    const int64_t esz = g.out_dtype == NT_F32 ? 4 : 2;
+    a->Y = (char *)g.C + y.base * esz;
+    a->ldb = w.coff[0];
+    a->syn = y.roff[0];
+    a->syf = y.coff[0];
+    a->x_numel = numel;
+    a->M = (int32_t)NPQ; a->N = (int32_t)g.N; a->K = (int32_t)CRS;
+    a->PQ = (int32_t)(P * Q); a->Q = (int32_t)Q; a->H = (int32_t)H; a->W = (int32_t)W;
+    a->HW = (int32_t)(H * W); a->CHW = (int32_t)(C * H * W);
+    a->RS = (int32_t)(R * S); a->S = (int32_t)S; a->R = (int32_t)R; a->ph = (int32_t)ph; a->pw = (int32_t)pw;
+    a->inv_rs = R * S > 1 ? (uint32_t)((1ULL << 32) / (uint64_t)(R * S)) + 1u : 0u;
+    a->inv_s = S > 1 ? (uint32_t)((1ULL << 32) / (uint64_t)S) + 1u : 0u;
+    a->mt = g.mt; a->nt = g.nt; a->kt = g.kt;
+    a->out_dtype = g.out_dtype;
+    return true;
+}
+
 // A map is "plain" when it is a strided matrix without bounds checks beyond rows / cols.
 static bool plain(const OperandMap &m) { return m.nrd == 1 && m.ncd == 1 && m.nchk == 0; }
 
@@ -60,6 +113,14 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         if (a.lda < 0 || a.ldb < 0 || a.lda >= (1 << 22) || a.ldb >= (1 << 22)) fast = false;   // 32-bit lane offsets
     }
     if (path_out) *path_out = fast ? PATH_FAST : PATH_GENERIC;
+    if (!fast) {
+        ConvArgs c{};
+        if (match_conv(g, &c)) {
+            if (path_out) *path_out = PATH_CONV;
+            const bool edge_b = (g.N % t.bn) || (g.K % t.bk);
+            return launch_conv(c, t.bn, g.in_dtype == NT_BF16, edge_b, g.mt * g.nt, (hipStream_t)g.stream);
+        }
+    }
     if (fast) {
         a.A = (const uint16_t *)g.A + g.ma.base;
         a.B = (const uint16_t *)g.B + g.mb.base;

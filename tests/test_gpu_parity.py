@@ -161,6 +161,39 @@ def test_conv2d_small(shape, stride, pad, tile):
     assert_gates(to_f64(Y), ref, "f32", f"conv {shape} {stride} {pad}")
 
 
+@pytest.mark.parametrize("dt,out", [("f16", "f32"), ("bf16", "bf16"), ("f16", "f16")])
+@pytest.mark.parametrize("shape,pad,tile", [
+    ((2, 32, 16, 16, 130, 3, 3), (1, 1), (256, 128, 64)),     # ragged filters and k tail
+    ((3, 16, 8, 24, 256, 3, 3), (1, 1), (256, 256, 64)),      # M = 576: last tile rows masked
+    ((2, 8, 10, 10, 64, 3, 3), (0, 0), (256, 128, 64)),       # no padding, M < one tile
+    ((1, 8, 8, 18, 128, 3, 3), (1, 0), (256, 128, 64)),       # padding along h only
+    ((2, 64, 8, 8, 128, 1, 1), (0, 0), (256, 128, 64)),       # 1x1 filter
+    ((2, 4, 9, 8, 256, 5, 3), (2, 1), (256, 256, 64)),        # 5x3 filter
+    ((5, 64, 24, 16, 256, 3, 3), (1, 1), None),               # library default tile
+])
+def test_conv2d_dense_unit_stride(shape, pad, tile, dt, out):
+    """Shapes the dedicated implicit-GEMM kernel takes: contiguous NCHW, stride 1, Q % 8 == 0."""
+    N, Cc, H, W, K, R, S = shape
+    X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, dt, seed=21)
+    ref = onum.conv2d(X, Wt, dt, (1, 1), pad)
+    assert ref.shape[3] % 8 == 0
+    Y = torch.full(ref.shape, float("nan"), dtype=TORCH_DT[out], device="cuda")
+    nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), pad, tile=tile)
+    torch.cuda.synchronize()
+    assert_gates(to_f64(Y), ref, out, f"conv dense {shape} {pad} {tile}")
+
+
+def test_conv2d_dense_integer_exact_and_padding_edges():
+    # small integers: exact; a wrong halo element or a missed padding row changes the result
+    N, Cc, H, W, K, R, S = 2, 8, 16, 16, 128, 3, 3
+    X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, "f16", seed=22, dist="int")
+    ref = onum.conv2d(X, Wt, "f16", (1, 1), (1, 1))
+    Y = torch.full(ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+    nt.conv2d_implicit(to_gpu(X, "f16"), to_gpu(Wt, "f16"), Y, (1, 1), (1, 1), tile=(256, 128, 64))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_f64(Y), ref)
+
+
 def test_conv2d_channels_last_views():
     # NHWC storage presented as NCHW views: the index map is stride generic
     N, Cc, H, W, K, R, S = 2, 8, 9, 9, 16, 3, 3
