@@ -83,23 +83,33 @@ struct StageK {
         const int s0 = (row0 & 7) ^ (tid >> 6);
         wbase = (uint32_t)(row0 * 128 + ((ch ^ s0) << 4));
     }
-    // rows_left / k_left: valid rows and k elements counted from the tile origin (EDGE only)
+    // rows_left / k_left: valid rows and k elements counted from the tile origin (EDGE only).
+    // Whole chunks are fetched with one predicated 16-byte load; only the k tile that holds the
+    // ragged end of K (a wavefront-uniform condition) revisits its one partial chunk per row
+    // element by element.  Masked elements read as zero.
     __device__ __forceinline__ void load(const char *base, int64_t rows_left, int64_t k_left)
     {
+        const int left = (int)(k_left < kBK ? k_left : kBK) - ch * 8;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             if constexpr (!EDGE) {
                 r[i] = gload16(base, voff[i]);
             } else {
-                const int64_t left = k_left - ch * 8;
-                const bool row_ok = i * 32 + row0 < rows_left;
-                if (row_ok && left >= 8) {
-                    r[i] = gload16(base, voff[i]);
-                } else {
-                    uint32_t e[8];
+                u32x4 v{0, 0, 0, 0};
+                if (i * 32 + row0 < rows_left && left >= 8) v = gload16(base, voff[i]);
+                r[i] = v;
+            }
+        }
+        if constexpr (EDGE) {
+            if (k_left < kBK) {
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) e[q] = (row_ok && q < left) ? gload2(base, voff[i] + 2 * q) : 0u;
-                    r[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+                for (int i = 0; i < CH; ++i) {
+                    if (i * 32 + row0 < rows_left && left > 0 && left < 8) {
+                        uint32_t e[8];
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) e[q] = q < left ? gload2(base, voff[i] + 2 * q) : 0u;
+                        r[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+                    }
                 }
             }
         }
@@ -134,27 +144,39 @@ struct StageMN {
         const int s = NW == 8 ? (rb & 7) : ((((rb & 1) << 2) ^ (rb >> 1)) & 7);
         wbase = (uint32_t)(rb * NW * 128 + ((kb ^ s) << 4));
     }
+    // Whole 8 x NW blocks are fetched with predicated vector loads; only tiles on the ragged
+    // m/n edge (a wavefront-uniform condition) revisit their one straddling block per k line
+    // element by element.  Masked elements read as zero.
     __device__ __forceinline__ void load(const char *base, int64_t rows_left, int64_t k_left)
     {
+        const int rl = (int)(rows_left < ROWS ? rows_left : ROWS) - rb * NW;     // valid rows of this block
+        const int kl = (int)(k_left < kBK ? k_left : kBK) - kb * 8;              // valid k lines of this block
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             bool full = true;
-            if constexpr (EDGE) full = kb * 8 + j < k_left && rb * NW + NW <= rows_left;
-            if (full) {
-                if constexpr (NW == 8) {
-                    const u32x4 v = gload16(base, voff[j]);
-                    r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
-                } else {
-                    const u32x2 v = gload8(base, voff[j]);
-                    r[j][0] = v[0]; r[j][1] = v[1];
-                }
+            if constexpr (EDGE) full = j < kl && rl >= NW;
+            if constexpr (NW == 8) {
+                u32x4 v{0, 0, 0, 0};
+                if (full) v = gload16(base, voff[j]);
+                r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
             } else {
-                const bool k_ok = kb * 8 + j < k_left;
+                u32x2 v{0, 0};
+                if (full) v = gload8(base, voff[j]);
+                r[j][0] = v[0]; r[j][1] = v[1];
+            }
+        }
+        if constexpr (EDGE) {
+            if (rows_left < ROWS) {
 #pragma unroll
-                for (int h = 0; h < NW / 2; ++h) {
-                    const uint32_t lo = (k_ok && rb * NW + 2 * h < rows_left) ? gload2(base, voff[j] + 4 * h) : 0u;
-                    const uint32_t hi = (k_ok && rb * NW + 2 * h + 1 < rows_left) ? gload2(base, voff[j] + 4 * h + 2) : 0u;
-                    r[j][h] = lo | (hi << 16);
+                for (int j = 0; j < 8; ++j) {
+                    if (j < kl && rl > 0 && rl < NW) {
+#pragma unroll
+                        for (int h = 0; h < NW / 2; ++h) {
+                            const uint32_t lo = 2 * h < rl ? gload2(base, voff[j] + 4 * h) : 0u;
+                            const uint32_t hi = 2 * h + 1 < rl ? gload2(base, voff[j] + 4 * h + 2) : 0u;
+                            r[j][h] = lo | (hi << 16);
+                        }
+                    }
                 }
             }
         }
