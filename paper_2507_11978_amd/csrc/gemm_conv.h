@@ -171,6 +171,7 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
     // k tile 0 -> LDS copy 0
     sa.load(g, g.K);
     sb.load(gB, n_left, g.K);
+    sb.settle();
     sa.store(smem, 0);
     sb.store(smem, B_BASE);
     __syncthreads();
@@ -186,6 +187,7 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
         sb.load(gB + kb_off * (kBK * 2), n_left, (int64_t)g.K - kb_off * kBK);
 #pragma unroll
         for (int ks = 0; ks < kBK / 16; ++ks) step(ks, cur * A_BYTES, cur * B_BYTES);
+        sb.settle();
         sa.store(smem, nxt * A_BYTES);
         sb.store(smem, B_BASE + nxt * B_BYTES);
         __syncthreads();

@@ -65,6 +65,25 @@ __device__ __forceinline__ u32x4 lds_read16(const char *smem, uint32_t addr)
     return *reinterpret_cast<const u32x4 *>(smem + addr);
 }
 
+// The 8 (4) 16-bit elements of v moved down by sh (0..7 / 0..3) element positions, zero filled
+// from the top: what a vector load that started sh elements early has to undergo.
+__device__ __forceinline__ u32x4 shift_down(u32x4 v, int sh)
+{
+    const uint32_t hb = (uint32_t)(sh & 1) * 16u;
+    uint32_t w0 = __builtin_amdgcn_alignbit(v[1], v[0], hb), w1 = __builtin_amdgcn_alignbit(v[2], v[1], hb);
+    uint32_t w2 = __builtin_amdgcn_alignbit(v[3], v[2], hb), w3 = v[3] >> hb;
+    if (sh & 2) { w0 = w1; w1 = w2; w2 = w3; w3 = 0; }
+    if (sh & 4) { w0 = w2; w1 = w3; w2 = 0; w3 = 0; }
+    return u32x4{w0, w1, w2, w3};
+}
+__device__ __forceinline__ u32x2 shift_down(u32x2 v, int sh)
+{
+    const uint32_t hb = (uint32_t)(sh & 1) * 16u;
+    uint32_t w0 = __builtin_amdgcn_alignbit(v[1], v[0], hb), w1 = v[1] >> hb;
+    if (sh & 2) { w0 = w1; w1 = 0; }
+    return u32x2{w0, w1};
+}
+
 // ---- staging of a (ROWS x 64) operand block whose LDS rows are contiguous in memory along k
 template <int ROWS, bool EDGE>
 struct StageK {
@@ -73,9 +92,11 @@ struct StageK {
     uint32_t voff[CH];                                    // byte offsets from the tile origin
     uint32_t wbase;                                       // swizzled LDS byte offset of chunk 0
     int row0, ch;
+    int shift;                                            // >= 0: pending shift of the last masked load
 
     __device__ __forceinline__ void init(int tid, int64_t ld)
     {
+        shift = -1;
         row0 = tid >> 3;
         ch = tid & 7;
 #pragma unroll
@@ -83,35 +104,39 @@ struct StageK {
         const int s0 = (row0 & 7) ^ (tid >> 6);
         wbase = (uint32_t)(row0 * 128 + ((ch ^ s0) << 4));
     }
-    // rows_left / k_left: valid rows and k elements counted from the tile origin (EDGE only).
-    // Whole chunks are fetched with one predicated 16-byte load; only the k tile that holds the
-    // ragged end of K (a wavefront-uniform condition) revisits its one partial chunk per row
-    // element by element.  Masked elements read as zero.
+    // rows_left / k_left: valid rows and k elements counted from the tile origin.  Chunks are
+    // fetched with one predicated 16-byte load each.  The one chunk per row that straddles the
+    // ragged end of K (left of its 8 elements valid) is fetched sh = 8 - left elements early,
+    // so that the load ends on the last valid element, and moved down by sh elements with zero
+    // fill in settle(); K must be at least 8 for that address to stay inside the operand.
+    // Masked elements read as zero.
+    // MASKED = false: the caller knows the whole block is inside the operand.
+    template <bool MASKED = EDGE>
     __device__ __forceinline__ void load(const char *base, int64_t rows_left, int64_t k_left)
     {
-        const int left = (int)(k_left < kBK ? k_left : kBK) - ch * 8;
+        if constexpr (!MASKED) {
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            if constexpr (!EDGE) {
-                r[i] = gload16(base, voff[i]);
-            } else {
+            for (int i = 0; i < CH; ++i) r[i] = gload16(base, voff[i]);
+            shift = -1;
+        } else {
+            const int left = (int)(k_left < kBK ? k_left : kBK) - ch * 8;
+            const int sh = (left > 0 && left < 8) ? 8 - left : 0;
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
                 u32x4 v{0, 0, 0, 0};
-                if (i * 32 + row0 < rows_left && left >= 8) v = gload16(base, voff[i]);
+                if (i * 32 + row0 < rows_left && left > 0) __builtin_memcpy(&v, base + ((int64_t)voff[i] - 2 * sh), 16);
                 r[i] = v;
             }
+            shift = k_left < kBK ? sh : -1;
         }
-        if constexpr (EDGE) {
-            if (k_left < kBK) {
+    }
+    // second half of a masked load, run when the data is needed (after the multiplications
+    // that hide the load latency)
+    __device__ __forceinline__ void settle()
+    {
+        if (shift >= 0) {                                  // wavefront-uniform
 #pragma unroll
-                for (int i = 0; i < CH; ++i) {
-                    if (i * 32 + row0 < rows_left && left > 0 && left < 8) {
-                        uint32_t e[8];
-#pragma unroll
-                        for (int q = 0; q < 8; ++q) e[q] = q < left ? gload2(base, voff[i] + 2 * q) : 0u;
-                        r[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-                    }
-                }
-            }
+            for (int i = 0; i < CH; ++i) r[i] = shift_down(r[i], shift);
         }
     }
     __device__ __forceinline__ void store(char *smem, uint32_t buf_off) const
@@ -134,9 +159,11 @@ struct StageMN {
     uint32_t voff[8];
     uint32_t wbase;
     int kb, rb;
+    int shift;                                            // >= 0: pending shift of the last masked load (see settle)
 
     __device__ __forceinline__ void init(int tid, int64_t ld)
     {
+        shift = -1;
         kb = tid >> 5;
         rb = tid & 31;
 #pragma unroll
@@ -144,39 +171,57 @@ struct StageMN {
         const int s = NW == 8 ? (rb & 7) : ((((rb & 1) << 2) ^ (rb >> 1)) & 7);
         wbase = (uint32_t)(rb * NW * 128 + ((kb ^ s) << 4));
     }
-    // Whole 8 x NW blocks are fetched with predicated vector loads; only tiles on the ragged
-    // m/n edge (a wavefront-uniform condition) revisit their one straddling block per k line
-    // element by element.  Masked elements read as zero.
+    // Blocks are fetched with one predicated vector load per k line.  The one block per k line
+    // that straddles the ragged m/n end (rl of its NW elements valid) is fetched sh = NW - rl
+    // elements early, so that the load ends on the last valid element, and shifted down by sh
+    // elements with zero fill; the operand must be at least NW long along its contiguous axis
+    // for that address to stay inside it.  Masked elements read as zero.
+    // MASKED = false: the caller knows the whole block is inside the operand.
+    template <bool MASKED = EDGE>
     __device__ __forceinline__ void load(const char *base, int64_t rows_left, int64_t k_left)
     {
         const int rl = (int)(rows_left < ROWS ? rows_left : ROWS) - rb * NW;     // valid rows of this block
         const int kl = (int)(k_left < kBK ? k_left : kBK) - kb * 8;              // valid k lines of this block
+        const int sh = (rl > 0 && rl < NW) ? NW - rl : 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            bool full = true;
-            if constexpr (EDGE) full = j < kl && rl >= NW;
-            if constexpr (NW == 8) {
-                u32x4 v{0, 0, 0, 0};
-                if (full) v = gload16(base, voff[j]);
-                r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
+            if constexpr (!MASKED) {
+                if constexpr (NW == 8) {
+                    const u32x4 v = gload16(base, voff[j]);
+                    r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
+                } else {
+                    const u32x2 v = gload8(base, voff[j]);
+                    r[j][0] = v[0]; r[j][1] = v[1];
+                }
             } else {
-                u32x2 v{0, 0};
-                if (full) v = gload8(base, voff[j]);
-                r[j][0] = v[0]; r[j][1] = v[1];
+                const bool any = j < kl && rl > 0;
+                const char *p = base + ((int64_t)voff[j] - 2 * sh);
+                if constexpr (NW == 8) {
+                    u32x4 v{0, 0, 0, 0};
+                    if (any) __builtin_memcpy(&v, p, 16);
+                    r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
+                } else {
+                    u32x2 v{0, 0};
+                    if (any) __builtin_memcpy(&v, p, 8);
+                    r[j][0] = v[0]; r[j][1] = v[1];
+                }
             }
         }
-        if constexpr (EDGE) {
-            if (rows_left < ROWS) {
+        shift = MASKED && rows_left < ROWS ? sh : -1;
+    }
+    // second half of a masked load, run when the data is needed (after the multiplications
+    // that hide the load latency): moves early-fetched straddling blocks into place
+    __device__ __forceinline__ void settle()
+    {
+        if (shift >= 0) {                                  // wavefront-uniform
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    if (j < kl && rl > 0 && rl < NW) {
-#pragma unroll
-                        for (int h = 0; h < NW / 2; ++h) {
-                            const uint32_t lo = 2 * h < rl ? gload2(base, voff[j] + 4 * h) : 0u;
-                            const uint32_t hi = 2 * h + 1 < rl ? gload2(base, voff[j] + 4 * h + 2) : 0u;
-                            r[j][h] = lo | (hi << 16);
-                        }
-                    }
+            for (int j = 0; j < 8; ++j) {
+                if constexpr (NW == 8) {
+                    const u32x4 v = shift_down(u32x4{r[j][0], r[j][1], r[j][2], r[j][3]}, shift);
+                    r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
+                } else {
+                    const u32x2 v = shift_down(u32x2{r[j][0], r[j][1]}, shift);
+                    r[j][0] = v[0]; r[j][1] = v[1];
                 }
             }
         }
@@ -284,6 +329,8 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
     // ---- prologue: tile 0 -> LDS copy 0
     sa.load(gA, m_left, g.K);
     sb.load(gB, n_left, g.K);
+    sa.settle();
+    sb.settle();
     sa.store(smem, 0);
     sb.store(smem, B_BASE);
     __syncthreads();
@@ -293,17 +340,29 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
     // and written to the idle copy afterwards.
     const int64_t last = g.kt - 1;
     uint32_t cur = 0;
-    for (int64_t k = 0; k < g.kt; ++k) {
+    auto trip = [&](auto masked, int64_t k) {
         const uint32_t nxt = cur ^ 1u;
         const int64_t kn = k < last ? k + 1 : last;
-        sa.load(gA + kn * a_step, m_left, g.K - kn * kBK);
-        sb.load(gB + kn * b_step, n_left, g.K - kn * kBK);
+        sa.template load<decltype(masked)::value>(gA + kn * a_step, m_left, g.K - kn * kBK);
+        sb.template load<decltype(masked)::value>(gB + kn * b_step, n_left, g.K - kn * kBK);
 #pragma unroll
         for (int ks = 0; ks < kBK / 16; ++ks) step(ks, cur * A_BYTES, cur * B_BYTES);
+        sa.settle();
+        sb.settle();
         sa.store(smem, nxt * A_BYTES);
         sb.store(smem, B_BASE + nxt * B_BYTES);
         __syncthreads();
         cur = nxt;
+    };
+    int64_t k = 0;
+    if constexpr (EDGE) {
+        // Programs whose tile lies inside C fetch every k tile but the last with plain loads
+        // (trip k fetches tile k + 1); the rest, and programs on the ragged edge, mask.
+        if (m_left >= BM && n_left >= BN)
+            for (; k < g.kt - 2; ++k) trip(std::false_type{}, k);
+        for (; k < g.kt; ++k) trip(std::true_type{}, k);
+    } else {
+        for (; k < g.kt; ++k) trip(std::false_type{}, k);
     }
 
     // ---- epilogue: convert and store (masked on ragged tiles)

@@ -68,7 +68,7 @@ static bool match_conv(const GemmLaunch &g, ConvArgs *a)
     if (x.coff[1] != W || x.coff[0] != H * W || x.roff[0] != C * H * W) return false;   // contiguous NCHW
     if (x.base != -(ph * W + pw)) return false;
     const int64_t numel = Nimg * C * H * W;
-    if (numel >= (1LL << 31) || NPQ >= (1LL << 31) || CRS >= (1 << 16) - 64) return false;
+    if (numel >= (1LL << 31) || NPQ >= (1LL << 31) || CRS >= (1 << 16) - 64 || CRS < 8) return false;   // (the filter loader needs K >= 8)
     // filter: B[kk, f] with unit step along kk
     if (!(w.nrd == 1 && w.ncd == 1 && w.nchk == 0 && w.roff[0] == 1 && w.coff[0] > 0 && w.coff[0] < (1 << 22))) return false;
     // output: (n, pq) rows with unit step along pq, one digit along f
@@ -111,6 +111,9 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         else if (g.mb.roff[0] == 1) { blay = KCONTIG; a.ldb = g.mb.coff[0]; }
         else fast = false;
         if (a.lda < 0 || a.ldb < 0 || a.lda >= (1 << 22) || a.ldb >= (1 << 22)) fast = false;   // 32-bit lane offsets
+        // the staged loader fetches a block that straddles the ragged end of the contiguous
+        // axis up to 7 elements early: that axis must be at least one block (8 elements) long
+        if ((alay == MNCONTIG ? g.M : g.K) < 8 || (blay == MNCONTIG ? g.N : g.K) < 8) fast = false;
     }
     if (path_out) *path_out = fast ? PATH_FAST : PATH_GENERIC;
     if (!fast) {
