@@ -86,6 +86,49 @@ def test_operand_orientations(ta, tb, tc, M, N, K, tile):
     assert_gates(to_f64(Cv), ref, "f32", f"ta={ta} tb={tb} tc={tc}")
 
 
+
+@pytest.mark.parametrize("tile", [(128, 128, 64), (256, 256, 64)])
+@pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, False), (True, True)])
+@pytest.mark.parametrize("r", [1, 2, 3, 4, 5, 6, 7, 8, 9, 15])
+def test_ragged_remainders_of_every_length(r, ta, tb, tile):
+    """Every possible length of the partial vector at the ragged end of M, N and K, for both
+    memory orientations of A and B; small integers make the comparison bit exact, and NaNs
+    planted right behind the operands must never reach the result."""
+    dt = "bf16"
+    M, N, K = tile[0] + r, tile[1] + 16 - r, 64 + r
+    A, B = si.gemm_inputs(M, N, K, dt, seed=100 + r, dist="int")
+    ref = onum.gemm(A, B, dt)
+
+    def planted(X, transposed):
+        X = X.T.copy() if transposed else X
+        buf = torch.full((X.size + 64,), float("nan"), dtype=TORCH_DT[dt], device="cuda")
+        buf[:X.size] = to_gpu(X, dt).reshape(-1)
+        v = buf[:X.size].view(X.shape)
+        return v.t() if transposed else v
+
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    nt.gemm(planted(A, ta), planted(B, tb), C, tile=tile)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_f64(C), ref)
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 7, 100), (7, 300, 100), (300, 300, 7), (300, 8, 8), (8, 8, 8), (300, 300, 9)])
+def test_axes_shorter_than_one_vector(M, N, K):
+    """Operands shorter than one 16-byte vector along an axis (the vector loaders' lower limit)."""
+    dt = "f16"
+    A, B = si.gemm_inputs(M, N, K, dt, seed=M + 3 * N + 5 * K, dist="int")
+    ref = onum.gemm(A, B, dt)
+    for tile in [(128, 128, 64), (256, 256, 64)]:
+        for ta in (False, True):
+            for tb in (False, True):
+                At = to_gpu(A.T.copy(), dt).t() if ta else to_gpu(A, dt)
+                Bt = to_gpu(B.T.copy(), dt).t() if tb else to_gpu(B, dt)
+                C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+                nt.gemm(At, Bt, C, tile=tile)
+                torch.cuda.synchronize()
+                assert np.array_equal(to_f64(C), ref), (tile, ta, tb)
+
+
 def test_general_strides_and_padded_pitch():
     dt, M, N, K = "bf16", 150, 170, 90
     A, B = si.gemm_inputs(M, N, K, dt, seed=4, dist="uniform")
