@@ -78,15 +78,18 @@ __device__ __forceinline__ int lds_chunk_pos(int row, int chunk)
     return row * BK + ((chunk ^ s) << 3);
 }
 
-// hardware workgroup index -> (batch, tile row, tile col)
+// hardware workgroup index -> (batch, tile row, tile col).  The divisions run on the vector
+// unit; the results (below 2^31, checked at launch) are moved to scalar registers so that
+// everything derived from them is wavefront-uniform for the compiler as well.
 __device__ __forceinline__ void locate_program(int64_t mt, int64_t nt, int64_t *b, int64_t *i, int64_t *j)
 {
     const int64_t per = mt * nt;
     const int64_t w = blockIdx.x;
-    *b = w / per;
-    const int64_t pid = program_of_workgroup(w - *b * per, mt, nt);
-    *i = pid / nt;
-    *j = pid % nt;
+    const int64_t bb = w / per;
+    const int64_t pid = program_of_workgroup(w - bb * per, mt, nt);
+    *b = __builtin_amdgcn_readfirstlane((int)bb);
+    *i = __builtin_amdgcn_readfirstlane((int)(pid / nt));
+    *j = __builtin_amdgcn_readfirstlane((int)(pid % nt));
 }
 
 // The LDS -> MFMA core for one staged k tile: acc[tm][tn] += A_tile . B_tile.

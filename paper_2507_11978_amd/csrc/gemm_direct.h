@@ -5,8 +5,8 @@
 // multiplies (source-to-target mapping, Section 3.2.2) travel from global memory straight
 // into LDS (global_load_lds, 16 bytes per lane, no staging registers) in slices of 32 k
 // (each 64-wide k tile of the arrangement is consumed as two such slices).  LDS holds a
-// ring of four slices per operand, so a slice is requested three slice-times (about 3000
-// cycles) before it is multiplied: long enough to cover an L2 miss.
+// ring of three or four slices per operand (see ring_of), so a slice is requested two or three
+// slice-times (2000 - 3000 cycles) before it is multiplied: long enough to cover an L2 miss.
 //
 // LDS layouts, chosen by how the operand lies in memory:
 //   k-major  (operand contiguous along k)    [row = m or n][32 k], 64 bytes per row; a
@@ -27,7 +27,14 @@ namespace nt {
 typedef short short4v __attribute__((ext_vector_type(4)));
 
 constexpr int kSliceK = 32;      // k extent of one LDS slice
-constexpr int kRing = 4;         // slices per operand resident in LDS
+// Slices per operand resident in LDS, and workgroups the kernel is built to co-reside on a
+// compute unit.  The 256 x 256 tile needs every accumulator register of its wavefronts (one
+// workgroup per unit, ring of four = 128 KB).  Smaller tiles leave room for two workgroups
+// per unit (at most 72 KB and 256 registers each), whose epilogues, launches and prologues
+// then overlap the other's multiplications; their ring is three slices (256 x 128: 72 KB) or
+// four (128 x 128: 64 KB).
+constexpr int ring_of(int bm, int bn) { return bm + bn == 384 ? 3 : 4; }
+constexpr int residency_of(int bm, int bn) { return bm + bn == 512 ? 1 : 2; }
 
 // s_waitcnt that waits until at most n vector-memory operations are outstanding and leaves
 // the other counters alone (vmcnt is split over bits [3:0] and [15:14] of the immediate)
@@ -129,9 +136,10 @@ struct DirectTile<E, MNCONTIG> {
 };
 
 template <int BM, int BN, bool BF16, int ALAY, int BLAY>
-__global__ __launch_bounds__(kThreads) void gemm_direct_kernel(const FastArgs g)
+__global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_kernel(const FastArgs g)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr int kRing = ring_of(BM, BN);
     using TileA = DirectTile<BM, ALAY>;
     using TileB = DirectTile<BN, BLAY>;
     constexpr uint32_t A_BYTES = TileA::BYTES, B_BYTES = TileB::BYTES, B_BASE = kRing * A_BYTES;
@@ -202,7 +210,7 @@ __global__ __launch_bounds__(kThreads) void gemm_direct_kernel(const FastArgs g)
             const int tm = idx / TN, tn = idx % TN;
             const u32x4 xa{fa[slot][tm][0][0], fa[slot][tm][0][1], fa[slot][tm][1][0], fa[slot][tm][1][1]};
             const u32x4 xb{fb[slot][tn][0][0], fb[slot][tn][0][1], fb[slot][tn][1][0], fb[slot][tn][1][1]};
-            acc[tm][tn] = mfma32<BF16>(xa, xb, acc[tm][tn]);
+            acc[tm][tn] = mfma32<BF16>(xb, xa, acc[tm][tn]);   // transposed block (see store_tile)
 #pragma unroll
             for (int q = 0; q < RQ; ++q)
                 if (idx * RQ + q < NR) lds_read(idx * RQ + q, slot ^ 1, ks_next, rring);
@@ -233,37 +241,31 @@ __global__ __launch_bounds__(kThreads) void gemm_direct_kernel(const FastArgs g)
     for (int r = 0; r < NR; ++r) lds_read(r, 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
 
-    // One slice per trip, one basic block.  Slice s sits at ring position s % 4.
+    // One slice per trip, one basic block.  Slice s sits at ring position s % kRing.
     //   step A  multiplies k step 0 of slice s while reading its k step 1 fragments;
-    //   then waits until this wavefront's part of slice s+1 has landed (the loads of the two
+    //   then waits until this wavefront's part of slice s+1 has landed (the loads of the
     //   younger slices may still be in flight) and meets the other wavefronts: slice s+1 is
-    //   complete, and nobody reads ring position s % 4 any more;
+    //   complete, and nobody reads the ring position of slice s any more;
     //   step B  multiplies k step 1 while reading the first fragments of slice s+1 and
-    //   requesting slice s+4 into the position just released.
+    //   requesting slice s+kRing into the position just released.
     uint32_t ring = 0;
     for (int64_t sl = 0; sl < n_slices; ++sl) {
-        const uint32_t nxt = (ring + 1) & (kRing - 1);
+        const uint32_t nxt = ring + 1 == kRing ? 0 : ring + 1;
         step(0, 1, ring, 0, nullptr, nullptr, 0);
-        NT_WAIT_VMCNT(2 * ND);
+        NT_WAIT_VMCNT((kRing - 2) * ND);
         __syncthreads();
         step(1, 0, nxt, ND, slice_a(sl + kRing), slice_b(sl + kRing), ring);
         ring = nxt;
     }
     NT_WAIT_VMCNT(0);                                      // drain the surplus prefetches before the LDS is released
 
-    const int64_t row_base = row0 + wave_m * (BM / 2) + 4 * hi;
-    const int64_t col_base = col0 + wave_n * (BN / 2) + l32;
-    const int64_t cb = bi * g.sc_batch;
-    if (g.out_dtype == NT_F32)
-        store_tile_fast<BM, BN, float>(reinterpret_cast<float *>(g.C) + cb, g.scm, g.scn, acc, row_base, col_base, g.M, g.N, false, g.out_dtype);
-    else
-        store_tile_fast<BM, BN, uint16_t>(reinterpret_cast<uint16_t *>(g.C) + cb, g.scm, g.scn, acc, row_base, col_base, g.M, g.N, false, g.out_dtype);
+    store_tile<BM, BN, false>(g, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane, false);
 }
 
 template <int BM, int BN, bool BF16, int ALAY, int BLAY>
 static nt_status launch_direct_inst(const FastArgs &a, int64_t nwg, hipStream_t s)
 {
-    constexpr size_t smem = (size_t)kRing * (BM + BN) * kSliceK * sizeof(uint16_t);
+    constexpr size_t smem = (size_t)ring_of(BM, BN) * (BM + BN) * kSliceK * sizeof(uint16_t);
     auto kern = gemm_direct_kernel<BM, BN, BF16, ALAY, BLAY>;
     static bool configured = false;
     if (!configured) {

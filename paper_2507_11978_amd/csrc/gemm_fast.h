@@ -244,31 +244,133 @@ struct StageMN {
 template <int ROWS, int LAY, bool EDGE> struct StageSel { using type = StageK<ROWS, EDGE>; };
 template <int ROWS, bool EDGE> struct StageSel<ROWS, MNCONTIG, EDGE> { using type = StageMN<ROWS, EDGE>; };
 
-template <int BM, int BN, typename OutT>
-__device__ __forceinline__ void store_tile_fast(OutT *__restrict__ C, int64_t scm, int64_t scn,
-                                                const float16v (&acc)[BM / 64][BN / 64],
-                                                int64_t row_base, int64_t col_base, int64_t M, int64_t N,
-                                                bool check, int out_dtype)
+// ---- epilogue (output = accumulator, Section 4.2).
+// The kernels in this file issue every MFMA with the B fragment as its first operand, so the
+// 32 x 32 accumulator block comes out transposed: a lane holds one row m = lane % 32 and 16 of
+// its columns, register v <-> n = 8 (v / 4) + 4 (lane / 32) + v % 4.
+
+// The 16 consecutive columns 16 (lane / 32) .. + 15 of the lane's row: the two half-wavefronts
+// trade register groups (v_permlane32_swap: the upper half's first operand <-> the lower half's
+// second), after which columns ascend through registers 0-3, 8-11, 4-7, 12-15.  All lanes
+// must be active.
+__device__ __forceinline__ void gather_row16(const float16v &acc, uint32_t (&o)[16])
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        // (elements are copied out first: a bit cast applied to a vector element directly reads element 0)
+        const float g0 = acc[q], g1 = acc[4 + q], g2 = acc[8 + q], g3 = acc[12 + q];
+        const auto lo = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, g0), __builtin_bit_cast(uint32_t, g2), false, false);
+        const auto up = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, g1), __builtin_bit_cast(uint32_t, g3), false, false);
+        o[q] = lo[0];
+        o[4 + q] = lo[1];
+        o[8 + q] = up[0];
+        o[12 + q] = up[1];
+    }
+}
+
+template <int OUT>
+__device__ __forceinline__ uint32_t pack_pair(uint32_t lo, uint32_t hi)
+{
+    const float a = __builtin_bit_cast(float, lo), b = __builtin_bit_cast(float, hi);
+    if constexpr (OUT == NT_F16) {
+        typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, half2v{(_Float16)a, (_Float16)b});          // round to nearest even
+    } else {
+        return (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
+    }
+}
+
+// C with unit stride along n: every lane stores its 16 consecutive columns of each block with
+// 16-byte stores.  row_w / col_w: first row / column of the wavefront's part of the tile.
+// CHECK masks rows >= M and columns >= N (a partly valid run of 16 is stored element-wise).
+template <int BM, int BN, int OUT, bool CHECK>
+__device__ __forceinline__ void store_tile_rows(char *C, int64_t scm, const float16v (&acc)[BM / 64][BN / 64],
+                                                int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr int ES = OUT == NT_F32 ? 4 : 2;
+    const int l32 = lane & 31, hi = lane >> 5;
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
+    for (int tm = 0; tm < TM; ++tm) {
+        const int64_t row = row_w + tm * 32 + l32;
+        const int64_t col = col_w + 16 * hi;
+        char *prow = C + (row * scm + col) * ES;
+        const bool row_ok = !CHECK || row < M;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
-            const int64_t col = col_base + tn * 32;
+            uint32_t o[16];
+            gather_row16(acc[tm][tn], o);
+            char *p = prow + tn * 32 * ES;
+            const int64_t nv = CHECK ? N - (col + tn * 32) : 16;      // valid columns from the lane's first
+            if (row_ok && nv >= 16) {
+                if constexpr (OUT == NT_F32) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t row = row_base + tm * 32 + 8 * (v / 4) + (v % 4);
-                if (!check || (row < M && col < N)) {
-                    const float x = acc[tm][tn][v];
-                    if constexpr (sizeof(OutT) == 4) {
-                        C[row * scm + col * scn] = x;
-                    } else {
-                        C[row * scm + col * scn] = out_dtype == NT_F16 ? f32_to_f16_rne(x) : f32_to_bf16_rne(x);
+                    for (int i = 0; i < 4; ++i) {
+                        const u32x4 v{o[4 * i], o[4 * i + 1], o[4 * i + 2], o[4 * i + 3]};
+                        __builtin_memcpy(p + 16 * i, &v, 16);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const u32x4 v{pack_pair<OUT>(o[8 * i], o[8 * i + 1]), pack_pair<OUT>(o[8 * i + 2], o[8 * i + 3]),
+                                      pack_pair<OUT>(o[8 * i + 4], o[8 * i + 5]), pack_pair<OUT>(o[8 * i + 6], o[8 * i + 7])};
+                        __builtin_memcpy(p + 16 * i, &v, 16);
                     }
                 }
+            } else if (CHECK && row_ok && nv > 0) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (i < nv) {
+                        if constexpr (OUT == NT_F32) *reinterpret_cast<uint32_t *>(p + 4 * i) = o[i];
+                        else *reinterpret_cast<uint16_t *>(p + 2 * i) = (uint16_t)pack_pair<OUT>(o[i], 0u);
+                    }
             }
         }
+    }
+}
+
+// C with any strides: one store per element, always masked.
+template <int BM, int BN>
+__device__ __forceinline__ void store_tile_strided(void *C, int64_t scm, int64_t scn, const float16v (&acc)[BM / 64][BN / 64],
+                                                   int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N, int out_dtype)
+{
+    constexpr int TM = BM / 64, TN = BN / 64;
+    const int l32 = lane & 31, hi = lane >> 5;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int64_t row = row_w + tm * 32 + l32;
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t col = col_w + tn * 32 + 8 * (v / 4) + 4 * hi + (v % 4);
+                if (row < M && col < N) store_out(C, row * scm + col * scn, acc[tm][tn][v], out_dtype);
+            }
+    }
+}
+
+// Epilogue of the transposed-accumulator kernels: picks the store routine for C's layout and format.
+template <int BM, int BN, bool EDGE>
+__device__ __forceinline__ void store_tile(const FastArgs &g, int64_t bi, const float16v (&acc)[BM / 64][BN / 64],
+                                           int64_t row_w, int64_t col_w, int lane, bool ragged)
+{
+    const int64_t esz = g.out_dtype == NT_F32 ? 4 : 2;
+    char *C = reinterpret_cast<char *>(g.C) + bi * g.sc_batch * esz;
+    if (g.scn != 1) {
+        store_tile_strided<BM, BN>(C, g.scm, g.scn, acc, row_w, col_w, lane, g.M, g.N, g.out_dtype);
+        return;
+    }
+    if constexpr (EDGE) {
+        if (ragged) {
+            if (g.out_dtype == NT_F32) store_tile_rows<BM, BN, NT_F32, true>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
+            else if (g.out_dtype == NT_F16) store_tile_rows<BM, BN, NT_F16, true>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
+            else store_tile_rows<BM, BN, NT_BF16, true>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
+            return;
+        }
+    }
+    if (g.out_dtype == NT_F32) store_tile_rows<BM, BN, NT_F32, false>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
+    else if (g.out_dtype == NT_F16) store_tile_rows<BM, BN, NT_F16, false>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
+    else store_tile_rows<BM, BN, NT_BF16, false>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
 }
 
 template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE>
@@ -323,7 +425,7 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma32<BF16>(fa[tm], fb[tn], acc[tm][tn]);
+            for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma32<BF16>(fb[tn], fa[tm], acc[tm][tn]);   // transposed block
     };
 
     // ---- prologue: tile 0 -> LDS copy 0
@@ -366,14 +468,7 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
     }
 
     // ---- epilogue: convert and store (masked on ragged tiles)
-    const int64_t row_base = row0 + wave_m * (BM / 2) + 4 * hi;
-    const int64_t col_base = col0 + wave_n * (BN / 2) + l32;
-    const int64_t cb = bi * g.sc_batch;
-    const bool check = EDGE && (m_left < BM || n_left < BN);
-    if (g.out_dtype == NT_F32)
-        store_tile_fast<BM, BN, float>(reinterpret_cast<float *>(g.C) + cb, g.scm, g.scn, acc, row_base, col_base, g.M, g.N, check, g.out_dtype);
-    else
-        store_tile_fast<BM, BN, uint16_t>(reinterpret_cast<uint16_t *>(g.C) + cb, g.scm, g.scn, acc, row_base, col_base, g.M, g.N, check, g.out_dtype);
+    store_tile<BM, BN, EDGE>(g, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane, m_left < BM || n_left < BN);
 }
 
 // ------------------------------------------------------------------ host launch helpers

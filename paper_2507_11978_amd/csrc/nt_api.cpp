@@ -22,21 +22,42 @@ namespace {
 bool dtype_in_ok(int d) { return d == NT_F16 || d == NT_BF16; }
 bool dtype_out_ok(int d) { return d == NT_F16 || d == NT_BF16 || d == NT_F32; }
 
-// Default meta-parameters: the largest built tile that still yields enough programs to
-// occupy the 256 compute units.
-nt_tile_cfg pick_tile(int64_t batch, int64_t M, int64_t N, nt_tile_cfg cfg)
+enum Kind { KIND_GEMM = 0, KIND_BMM = 1, KIND_CONV = 2 };
+
+// Default meta-parameters (the tile sizes are the arrangement's meta-parameters, Section 3.1.2).
+// GEMM / BMM: the built tile with the lowest estimated time.  A compute unit works through
+// p = ceil(programs / 256) programs; a program costs kt steps of `step` microseconds (time of
+// one 64-wide k tile with the whole unit's matrix rate) plus a fixed `fixed` microseconds of
+// launch, prologue and epilogue, which `resident` co-resident workgroups overlap with each
+// other's multiplications.  The constants are fits to measurements on 8192 x 8192 x K and
+// batched 2048 x 2048 x K problems.
+nt_tile_cfg pick_tile(int kind, int64_t batch, int64_t M, int64_t N, int64_t K, nt_tile_cfg cfg)
 {
     if (cfg.bm || cfg.bn || cfg.bk) return cfg;
     if (M <= 64 || N <= 64) return nt_tile_cfg{64, 64, 32};
-    const nt_tile_cfg cands[] = {{256, 256, 64}, {256, 128, 64}, {128, 128, 64}};
-    for (const nt_tile_cfg &c : cands) {
-        const int64_t tiles = batch * ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
-        if (tiles >= 200) return c;
+    if (kind == KIND_CONV) {
+        // the convolution kernel is built for 256 output positions per program
+        const int64_t mt = (M + 255) / 256;
+        return mt * ((N + 255) / 256) >= 200 || N > 128 ? nt_tile_cfg{256, 256, 64} : nt_tile_cfg{256, 128, 64};
     }
-    return nt_tile_cfg{128, 128, 64};
+    struct Cand { int bm, bn; double fixed, step; int resident; };
+    const Cand cands[] = {{256, 256, 14.0, 1.755, 1}, {128, 256, 8.0, 0.95, 2}, {256, 128, 8.0, 1.08, 2}, {128, 128, 7.0, 0.62, 2}};
+    const double kt = (double)((K + 63) / 64);
+    nt_tile_cfg best{128, 128, 64};
+    double best_cost = 0;
+    for (const Cand &c : cands) {
+        const int64_t programs = batch * ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+        const int64_t p = (programs + 255) / 256;
+        // ragged problems run on the staged kernels, whose larger LDS footprint leaves one
+        // workgroup per unit for every tile but the smallest
+        const bool full = M % c.bm == 0 && N % c.bn == 0 && K % 64 == 0;
+        const int resident = full || (c.bm == 128 && c.bn == 128) ? c.resident : 1;
+        const double cost = (double)((p + resident - 1) / resident) * c.fixed + (double)p * kt * c.step;
+        if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = nt_tile_cfg{c.bm, c.bn, 64}; }
+    }
+    return best;
 }
 
-enum Kind { KIND_GEMM = 0, KIND_BMM = 1, KIND_CONV = 2 };
 
 struct Problem {
     Arrangement va, vb, vc;          // single-level matrix views of the three operands
@@ -73,7 +94,7 @@ nt_status build_problem(int kind, const nt_tensor_desc *d0, const nt_tensor_desc
     p->N = sb[o + 1];
     if (sb[o] != p->K) return fail(NT_ERR_SHAPE_MISMATCH, "inner dimensions of A and B differ");
     if (sc[o] != p->M || sc[o + 1] != p->N) return fail(NT_ERR_SHAPE_MISMATCH, "output shape differs from [M, N]");
-    p->tile = pick_tile(p->batch, p->M, p->N, cfg);
+    p->tile = pick_tile(kind, p->batch, p->M, p->N, p->K, cfg);
     NT_TRY(nt::arrange_matmul(p->va, p->vb, p->vc, p->tile, &p->mm));
     return NT_OK;
 }
