@@ -5,6 +5,7 @@ possibly strided views) plus the format name, and returns fp64 results computed 
 plain definitions in nt_oracle.c:
   gemm / bmm        -- Section 4.2: C = sum_k A[:,k] B[k,:]
   conv2d            -- Section 4.3: direct cross-correlation the implicit GEMM must equal
+  addmm             -- Section 5.1 task list: beta * input + alpha * (A . B)
 """
 from __future__ import annotations
 
@@ -85,6 +86,20 @@ def gemm_samples(A, B, dtype: str, ms, ns) -> np.ndarray:
     lib().nto_gemm_samples(A.ctypes.data, sa[0], sa[1], B.ctypes.data, sb[0], sb[1], K, _DT[dtype],
                            ms.ctypes.data, ns.ctypes.data, ms.size, out.ctypes.data)
     return out
+
+
+def addmm(inp, A, B, dtype: str, alpha: float = 1.0, beta: float = 1.0, inp_dtype: str | None = None,
+          nthreads: int = 1) -> np.ndarray:
+    """beta * input + alpha * (A . B) in fp64 (the addmm task of Section 5.1; the definition is the
+    one the paper's PyTorch baseline evaluates).  `inp` broadcasts against [M, N]; it is either an
+    fp64 / fp32 array of exact values or 16-bit patterns in format `inp_dtype`.  beta = 0 drops
+    the input altogether (its values, NaN included, do not reach the result)."""
+    prod = gemm(A, B, dtype, nthreads)
+    if beta == 0:
+        return float(alpha) * prod
+    inp = np.asarray(inp)
+    vals = decode(inp, inp_dtype) if inp.dtype == np.uint16 else inp.astype(np.float64)
+    return float(beta) * np.broadcast_to(vals, prod.shape) + float(alpha) * prod
 
 
 def conv_out_size(H: int, R: int, stride: int, pad: int) -> int:

@@ -104,6 +104,33 @@ def test_bmm_is_per_batch_gemm():
         assert np.allclose(C[b], onum.decode(A[b], "f16") @ onum.decode(B[b], "f16"), rtol=1e-13, atol=1e-14)
 
 
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+def test_addmm_hand_worked_and_special_cases(dt):
+    for name in ("addmm2", "addmm2_bias"):
+        kv = _hand(name)
+        A, B, I, C = _mat(kv["A"]), _mat(kv["B"]), _mat(kv["I"]), _mat(kv["C"])
+        got = onum.addmm(I, _bits(A, dt), _bits(B, dt), dt, alpha=float(kv["alpha"]), beta=float(kv["beta"]))
+        assert np.array_equal(got, C)
+        # the same input handed over as 16-bit patterns
+        got = onum.addmm(_bits(I, dt), _bits(A, dt), _bits(B, dt), dt, alpha=float(kv["alpha"]), beta=float(kv["beta"]), inp_dtype=dt)
+        assert np.array_equal(got, C)
+    A, B = si.gemm_inputs(9, 11, 6, dt, seed=3, dist="int")
+    I = np.random.default_rng(5).integers(-8, 8, (9, 11)).astype(np.float64)
+    prod = onum.gemm(A, B, dt)
+    assert np.array_equal(onum.addmm(I, A, B, dt, alpha=1, beta=0), prod)                  # reduces to the product
+    assert np.array_equal(onum.addmm(I, A, np.zeros_like(B), dt, alpha=7, beta=1), I)       # A . 0 = 0
+    assert np.array_equal(onum.addmm(I, A, B, dt, alpha=-2, beta=0.5), 0.5 * I - 2 * prod)  # linearity (exact: small integers)
+    nan = np.full((9, 11), np.nan)
+    assert np.array_equal(onum.addmm(nan, A, B, dt, alpha=1, beta=0), prod)                 # beta = 0 drops the input
+    # brute force, element by element
+    Ad, Bd = onum.decode(A, dt), onum.decode(B, dt)
+    ref = np.array([[3 * I[m, n] + 2 * sum(Ad[m, k] * Bd[k, n] for k in range(6)) for n in range(11)] for m in range(9)])
+    assert np.array_equal(onum.addmm(I, A, B, dt, alpha=2, beta=3), ref)
+    # column bias broadcasts along n, row bias along m
+    col = np.arange(9, dtype=np.float64).reshape(9, 1)
+    assert np.array_equal(onum.addmm(col, A, B, dt), prod + col)
+
+
 def test_conv_hand_worked():
     kv = _hand("conv_3x3_2x2")
     X, W, Y = _mat(kv["X"]), _mat(kv["W"]), _mat(kv["Y"])
