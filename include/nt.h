@@ -161,6 +161,19 @@ nt_status nt_gemm(const void *A, const nt_tensor_desc *dA, const void *B, const 
                   void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
                   nt_tile_cfg cfg, void *hip_stream);
 
+/* nt_addmm: C[M,N] = beta * input[M,N] + alpha * (A[M,K] . B[K,N])  -- the addmm kernel of the paper's
+ * task list (Section 5.1): the matmul arrangement and application of Section 4.2 with `input` arranged
+ * like the output (tile(BM, BN)) and combined with the accumulator in fp32 before the one conversion to
+ * out_dtype.  `input` is a device pointer to elements of out_dtype, described by a host struct with
+ * ndim 2 and the sizes of C; a stride of 0 broadcasts (a bias row is {0, 1}).  beta == 0 leaves `input`
+ * unread (it may then be NULL).  K of 0: C = beta * input.  Everything else as nt_gemm.  C may alias
+ * `input` only if both have identical descriptors (each element is read before it is written).
+ */
+nt_status nt_addmm(const void *input, const nt_tensor_desc *dI, const void *A, const nt_tensor_desc *dA,
+                   const void *B, const nt_tensor_desc *dB, void *C, const nt_tensor_desc *dC,
+                   float alpha, float beta, nt_dtype in_dtype, nt_dtype out_dtype,
+                   nt_tile_cfg cfg, void *hip_stream);
+
 /* nt_bmm: the same per batch index; descriptors have ndim 3: [batch,M,K], [batch,K,N], [batch,M,N]
  * (listed among the paper's kernels in Section 5.1). */
 nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,

@@ -66,10 +66,11 @@ def load():
     L.nt_tile_supported.restype = i32
     L.nt_gemm.argtypes = [P, D, P, D, P, D, i32, i32, TileCfg, P]
     L.nt_bmm.argtypes = [P, D, P, D, P, D, i32, i32, TileCfg, P]
+    L.nt_addmm.argtypes = [P, D, P, D, P, D, P, D, C.c_float, C.c_float, i32, i32, TileCfg, P]
     L.nt_conv2d_implicit.argtypes = [P, D, P, D, P, D, i32, i32, i32, i32, i32, i32, TileCfg, P]
     L.nt_trace_tile.argtypes = [i32, D, D, D, i32, i32, i32, i32, TileCfg, i32, i64, i64, P, P, C.c_size_t, P]
     for name in ("nt_arrange_levels", "nt_arrange_tile", "nt_arrange_gemm", "nt_arrange_bmm", "nt_arrange_conv2d",
-                 "nt_program_order", "nt_gemm", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile"):
+                 "nt_program_order", "nt_gemm", "nt_addmm", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile"):
         getattr(L, name).restype = i32
     L.nt_last_error.restype = C.c_char_p
     L.nt_version.restype = C.c_char_p
@@ -253,6 +254,23 @@ def gemm(A, B, Cout, tile=None, stream=None):
     _check(load().nt_gemm(A.data_ptr(), C.byref(_desc_of(A)), B.data_ptr(), C.byref(_desc_of(B)),
                           Cout.data_ptr(), C.byref(_desc_of(Cout)), _DTYPES[_torch_dtype_name(A)],
                           _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
+    return Cout
+
+
+def addmm(inp, A, B, Cout, alpha=1.0, beta=1.0, tile=None, stream=None):
+    """Cout[M,N] = beta * inp + alpha * (A[M,K] @ B[K,N]); inp has Cout's dtype and is handed over as
+    an [M, N] view (stride 0 along broadcast axes)."""
+    _require_cuda(inp, A, B, Cout)
+    if inp.dtype != Cout.dtype:
+        raise ValueError("input must have the output's dtype")
+    try:
+        view = inp.expand(Cout.shape)
+    except RuntimeError:
+        view = inp                                    # not broadcastable: the library reports the mismatch
+    _check(load().nt_addmm(view.data_ptr(), C.byref(_desc_of(view)), A.data_ptr(), C.byref(_desc_of(A)),
+                           B.data_ptr(), C.byref(_desc_of(B)), Cout.data_ptr(), C.byref(_desc_of(Cout)),
+                           float(alpha), float(beta), _DTYPES[_torch_dtype_name(A)],
+                           _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
     return Cout
 
 

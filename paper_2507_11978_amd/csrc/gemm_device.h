@@ -68,6 +68,18 @@ __device__ __forceinline__ void store_out(void *C, int64_t off, float v, int out
         reinterpret_cast<uint16_t *>(C)[off] = f32_to_bf16_rne(v);
 }
 
+// element `off` of a tensor of type `dtype`, as fp32
+__device__ __forceinline__ float load_as_f32(const void *D, int64_t off, int dtype)
+{
+    if (dtype == NT_F32) return reinterpret_cast<const float *>(D)[off];
+    const uint16_t h = reinterpret_cast<const uint16_t *>(D)[off];
+    if (dtype == NT_F16) return (float)__builtin_bit_cast(_Float16, h);
+    return __builtin_bit_cast(float, (uint32_t)h << 16);
+}
+
+// the addmm combination, in fp32: alpha * accumulator + beta * addend
+__device__ __forceinline__ float combine(float acc, float d, float alpha, float beta) { return __builtin_fmaf(alpha, acc, beta * d); }
+
 // Swizzled LDS position (in 16-bit elements) of 16-byte chunk `chunk` of row `row`.
 template <int BK>
 __device__ __forceinline__ int lds_chunk_pos(int row, int chunk)
@@ -120,11 +132,13 @@ __device__ __forceinline__ void mma_tile(const uint16_t *__restrict__ as, const 
     }
 }
 
-// Store the accumulators through C's operand map (masked: out-of-range elements dropped).
+// Store alpha * accumulators (+ beta * D, read through D's operand map, if D is given) through
+// C's operand map (masked: out-of-range elements dropped).
 template <int BM, int BN>
 __device__ __forceinline__ void store_tile_generic(void *C, const OperandMap &mc, int64_t c_batch_off,
                                                    float16v (&acc)[BM / 64][BN / 64], int64_t row0, int64_t col0,
-                                                   int wave_m, int wave_n, int lane, int out_dtype)
+                                                   int wave_m, int wave_n, int lane, int out_dtype,
+                                                   const void *D, const OperandMap &md, int64_t d_batch_off, float alpha, float beta)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
     const int l32 = lane & 31, hi = lane >> 5;
@@ -139,7 +153,17 @@ __device__ __forceinline__ void store_tile_generic(void *C, const OperandMap &mc
                 const int64_t row = row0 + wave_m * (BM / 2) + tm * 32 + 8 * (v / 4) + 4 * hi + (v % 4);
                 const AxisPart rp = row_part(mc, row);
                 int64_t off;
-                if (element_at(mc, row, col, rp, cp, &off)) store_out(C, c_batch_off + off, acc[tm][tn][v], out_dtype);
+                if (element_at(mc, row, col, rp, cp, &off)) {
+                    float x = acc[tm][tn][v];
+                    if (D) {
+                        int64_t doff;
+                        const bool in = element_at(md, row, col, row_part(md, row), col_part(md, col), &doff);
+                        x = combine(x, in ? load_as_f32(D, d_batch_off + doff, out_dtype) : 0.f, alpha, beta);
+                    } else {
+                        x *= alpha;
+                    }
+                    store_out(C, c_batch_off + off, x, out_dtype);
+                }
             }
         }
     }
@@ -150,7 +174,8 @@ template <int BM, int BN, int BK, bool BF16>
 __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, void *__restrict__ C,
     const OperandMap ma, const OperandMap mb, const OperandMap mc,
-    int64_t sa_batch, int64_t sb_batch, int64_t sc_batch, int64_t mt, int64_t nt, int64_t kt, int out_dtype)
+    int64_t sa_batch, int64_t sb_batch, int64_t sc_batch, int64_t mt, int64_t nt, int64_t kt, int out_dtype,
+    const void *__restrict__ D, const OperandMap md, int64_t sd_batch, float alpha, float beta)
 {
     __shared__ __attribute__((aligned(16))) uint16_t as[BM * BK];
     __shared__ __attribute__((aligned(16))) uint16_t bs[BN * BK];
@@ -200,7 +225,7 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(
         mma_tile<BM, BN, BK, BF16>(as, bs, acc, wave_m, wave_n, lane);
         __syncthreads();
     }
-    store_tile_generic<BM, BN>(C, mc, bi * sc_batch, acc, row0, col0, wave_m, wave_n, lane, out_dtype);
+    store_tile_generic<BM, BN>(C, mc, bi * sc_batch, acc, row0, col0, wave_m, wave_n, lane, out_dtype, D, md, bi * sd_batch, alpha, beta);
 }
 
 // ---- host-side helper shared by the translation units that instantiate the kernels

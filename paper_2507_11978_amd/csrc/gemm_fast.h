@@ -32,6 +32,10 @@ struct FastArgs {
     int64_t M, N, K;
     int64_t mt, nt, kt;
     int out_dtype;
+    // epilogue C = alpha * acc + beta * D (D: out_dtype elements, read only if beta != 0 and D != nullptr)
+    const void *D;
+    int64_t sdm, sdn, sd_batch;
+    float alpha, beta;
 };
 
 __device__ __forceinline__ u32x4 gload16(const char *base, uint32_t off)
@@ -280,12 +284,50 @@ __device__ __forceinline__ uint32_t pack_pair(uint32_t lo, uint32_t hi)
     }
 }
 
+// 16 consecutive elements of type OUT at p, as fp32
+template <int OUT>
+__device__ __forceinline__ void load_row16(const char *p, float (&d)[16])
+{
+    if constexpr (OUT == NT_F32) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            u32x4 v;
+            __builtin_memcpy(&v, p + 16 * i, 16);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t w = v[q];               // (copied out: a bit cast of a vector element reads element 0)
+                d[4 * i + q] = __builtin_bit_cast(float, w);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            u32x4 v;
+            __builtin_memcpy(&v, p + 16 * i, 16);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t w = v[q];
+                if constexpr (OUT == NT_F16) {
+                    d[8 * i + 2 * q] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
+                    d[8 * i + 2 * q + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
+                } else {
+                    d[8 * i + 2 * q] = __builtin_bit_cast(float, w << 16);
+                    d[8 * i + 2 * q + 1] = __builtin_bit_cast(float, w & 0xffff0000u);
+                }
+            }
+        }
+    }
+}
+
 // C with unit stride along n: every lane stores its 16 consecutive columns of each block with
 // 16-byte stores.  row_w / col_w: first row / column of the wavefront's part of the tile.
 // CHECK masks rows >= M and columns >= N (a partly valid run of 16 is stored element-wise).
+// affine: the stored value is alpha * accumulator + beta * D (D: elements of the output type with
+// unit stride along n and row stride sdm, read under the same masks; nullptr = no addend).
 template <int BM, int BN, int OUT, bool CHECK>
 __device__ __forceinline__ void store_tile_rows(char *C, int64_t scm, const float16v (&acc)[BM / 64][BN / 64],
-                                                int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N)
+                                                int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N,
+                                                bool affine, const char *D, int64_t sdm, float alpha, float beta)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
     constexpr int ES = OUT == NT_F32 ? 4 : 2;
@@ -295,6 +337,7 @@ __device__ __forceinline__ void store_tile_rows(char *C, int64_t scm, const floa
         const int64_t row = row_w + tm * 32 + l32;
         const int64_t col = col_w + 16 * hi;
         char *prow = C + (row * scm + col) * ES;
+        const char *drow = D + (row * sdm + col) * ES;
         const bool row_ok = !CHECK || row < M;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
@@ -302,6 +345,23 @@ __device__ __forceinline__ void store_tile_rows(char *C, int64_t scm, const floa
             gather_row16(acc[tm][tn], o);
             char *p = prow + tn * 32 * ES;
             const int64_t nv = CHECK ? N - (col + tn * 32) : 16;      // valid columns from the lane's first
+            if (affine) {                                             // wavefront-uniform
+                float d[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) d[i] = 0.f;
+                if (D) {
+                    const char *dp = drow + tn * 32 * ES;
+                    if (row_ok && nv >= 16) {
+                        load_row16<OUT>(dp, d);
+                    } else if (CHECK && row_ok && nv > 0) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            if (i < nv) d[i] = load_as_f32(dp, i, OUT);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[i] = __builtin_bit_cast(uint32_t, combine(__builtin_bit_cast(float, o[i]), d[i], alpha, beta));
+            }
             if (row_ok && nv >= 16) {
                 if constexpr (OUT == NT_F32) {
 #pragma unroll
@@ -329,10 +389,11 @@ __device__ __forceinline__ void store_tile_rows(char *C, int64_t scm, const floa
     }
 }
 
-// C with any strides: one store per element, always masked.
+// C (and D) with any strides: one store per element, always masked.
 template <int BM, int BN>
 __device__ __forceinline__ void store_tile_strided(void *C, int64_t scm, int64_t scn, const float16v (&acc)[BM / 64][BN / 64],
-                                                   int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N, int out_dtype)
+                                                   int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N, int out_dtype,
+                                                   const void *D, int64_t sdm, int64_t sdn, float alpha, float beta)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
     const int l32 = lane & 31, hi = lane >> 5;
@@ -344,7 +405,10 @@ __device__ __forceinline__ void store_tile_strided(void *C, int64_t scm, int64_t
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t col = col_w + tn * 32 + 8 * (v / 4) + 4 * hi + (v % 4);
-                if (row < M && col < N) store_out(C, row * scm + col * scn, acc[tm][tn][v], out_dtype);
+                if (row < M && col < N) {
+                    const float d = D ? load_as_f32(D, row * sdm + col * sdn, out_dtype) : 0.f;
+                    store_out(C, row * scm + col * scn, combine(acc[tm][tn][v], d, alpha, beta), out_dtype);
+                }
             }
     }
 }
@@ -356,21 +420,25 @@ __device__ __forceinline__ void store_tile(const FastArgs &g, int64_t bi, const 
 {
     const int64_t esz = g.out_dtype == NT_F32 ? 4 : 2;
     char *C = reinterpret_cast<char *>(g.C) + bi * g.sc_batch * esz;
-    if (g.scn != 1) {
-        store_tile_strided<BM, BN>(C, g.scm, g.scn, acc, row_w, col_w, lane, g.M, g.N, g.out_dtype);
+    const char *D = g.D ? reinterpret_cast<const char *>(g.D) + bi * g.sd_batch * esz : nullptr;
+    if (g.scn != 1 || (D && g.sdn != 1)) {
+        store_tile_strided<BM, BN>(C, g.scm, g.scn, acc, row_w, col_w, lane, g.M, g.N, g.out_dtype, D, g.sdm, g.sdn, g.alpha, g.beta);
         return;
     }
+    const bool affine = D != nullptr || g.alpha != 1.f;
+#define NT_ROWS(OUT, CHECK) store_tile_rows<BM, BN, OUT, CHECK>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta)
     if constexpr (EDGE) {
         if (ragged) {
-            if (g.out_dtype == NT_F32) store_tile_rows<BM, BN, NT_F32, true>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
-            else if (g.out_dtype == NT_F16) store_tile_rows<BM, BN, NT_F16, true>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
-            else store_tile_rows<BM, BN, NT_BF16, true>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
+            if (g.out_dtype == NT_F32) NT_ROWS(NT_F32, true);
+            else if (g.out_dtype == NT_F16) NT_ROWS(NT_F16, true);
+            else NT_ROWS(NT_BF16, true);
             return;
         }
     }
-    if (g.out_dtype == NT_F32) store_tile_rows<BM, BN, NT_F32, false>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
-    else if (g.out_dtype == NT_F16) store_tile_rows<BM, BN, NT_F16, false>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
-    else store_tile_rows<BM, BN, NT_BF16, false>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N);
+    if (g.out_dtype == NT_F32) NT_ROWS(NT_F32, false);
+    else if (g.out_dtype == NT_F16) NT_ROWS(NT_F16, false);
+    else NT_ROWS(NT_BF16, false);
+#undef NT_ROWS
 }
 
 template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE>

@@ -100,7 +100,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
     if (g.batch * g.mt * g.nt > 0x7fffffffLL) return fail(NT_ERR_UNSUPPORTED, "grid too large");
     const nt_tile_cfg t = g.tile;
     // fast path: plain operands, each with unit stride along one of its axes
-    bool fast = plain(g.ma) && plain(g.mb) && plain(g.mc) && t.bk == 64 && t.bm >= 128 && t.bn >= 128;
+    bool fast = plain(g.ma) && plain(g.mb) && plain(g.mc) && (!g.has_d || plain(g.md)) && t.bk == 64 && t.bm >= 128 && t.bn >= 128 && g.kt > 0;
     int alay = KCONTIG, blay = MNCONTIG;
     FastArgs a{};
     if (fast) {
@@ -118,7 +118,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
     if (path_out) *path_out = fast ? PATH_FAST : PATH_GENERIC;
     if (!fast) {
         ConvArgs c{};
-        if (match_conv(g, &c)) {
+        if (!g.has_d && g.alpha == 1.f && match_conv(g, &c)) {
             if (path_out) *path_out = PATH_CONV;
             const bool edge_b = (g.N % t.bn) || (g.K % t.bk);
             return launch_conv(c, t.bn, g.in_dtype == NT_BF16, edge_b, g.mt * g.nt, (hipStream_t)g.stream);
@@ -136,6 +136,14 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         a.M = g.M; a.N = g.N; a.K = g.K;
         a.mt = g.mt; a.nt = g.nt; a.kt = g.kt;
         a.out_dtype = g.out_dtype;
+        a.alpha = g.alpha;
+        a.beta = g.has_d ? g.beta : 0.f;
+        if (g.has_d) {
+            a.D = (const char *)g.D + g.md.base * esz;
+            a.sdm = g.md.roff[0];
+            a.sdn = g.md.coff[0];
+            a.sd_batch = g.sd_batch;
+        }
         const bool edge = (g.M % t.bm) || (g.N % t.bn) || (g.K % t.bk);
         const bool bf16 = g.in_dtype == NT_BF16;
         const int64_t nwg = g.batch * g.mt * g.nt;

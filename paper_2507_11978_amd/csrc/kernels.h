@@ -22,6 +22,12 @@ struct GemmLaunch {
     nt_tile_cfg tile;
     int in_dtype, out_dtype;
     void *stream;
+    // epilogue: C = alpha * (A . B) + beta * D; D (elements of out_dtype, map md) is read only if has_d
+    const void *D;
+    OperandMap md;
+    int64_t sd_batch;
+    float alpha, beta;
+    bool has_d;
 };
 
 // Which code path a launch would take (reported for tests and the benchmark).

@@ -120,9 +120,11 @@ nt_status arrange_query(int kind, const nt_tensor_desc *d0, const nt_tensor_desc
     return st;
 }
 
+// D / dD / alpha / beta: the addmm epilogue C = beta * D + alpha * (A . B); dD == nullptr: plain product
 nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
               void *C, const nt_tensor_desc *dC, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
-              nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *stream)
+              nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *stream,
+              const void *D = nullptr, const nt_tensor_desc *dD = nullptr, float alpha = 1.f, float beta = 0.f)
 {
     if (!dtype_in_ok(in_dtype)) return fail(NT_ERR_UNSUPPORTED, "input dtype must be NT_F16 or NT_BF16");
     if (!dtype_out_ok(out_dtype)) return fail(NT_ERR_UNSUPPORTED, "output dtype must be NT_F16, NT_BF16 or NT_F32");
@@ -137,7 +139,23 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
     NT_TRY(p.va.lower_matrix_view(&g.ma, &nb, &g.sa_batch));
     NT_TRY(p.vb.lower_matrix_view(&g.mb, &nb, &g.sb_batch));
     NT_TRY(p.vc.lower_matrix_view(&g.mc, &nb, &g.sc_batch));
-    if (p.K == 0) return nt::launch_fill_zero(C, g.mc, p.batch, g.sc_batch, out_dtype, stream);
+    g.alpha = alpha;
+    g.beta = beta;
+    g.has_d = dD != nullptr && beta != 0.f;
+    if (g.has_d) {
+        if (!D) return fail(NT_ERR_INVALID_ARG, "null input pointer with beta != 0");
+        nt::Arrangement vd;
+        NT_TRY(vd.init(dD));
+        const std::vector<int64_t> sd = vd.level_shape(0);
+        if (sd.size() != 2 || sd[0] != p.M || sd[1] != p.N) return fail(NT_ERR_SHAPE_MISMATCH, "input shape differs from [M, N]");
+        NT_TRY(vd.lower_matrix_view(&g.md, &nb, &g.sd_batch));
+        g.D = D;
+    }
+    if (p.K == 0) {
+        if (!g.has_d) return nt::launch_fill_zero(C, g.mc, p.batch, g.sc_batch, out_dtype, stream);
+        // C = beta * input: the operand-map kernel with no k tiles (its grid is that of the 64 x 64 tile)
+        if (p.tile.bm != 64) return run(kind, A, dA, B, dB, C, dC, sh, sw, ph, pw, in_dtype, out_dtype, nt_tile_cfg{64, 64, 32}, stream, D, dD, alpha, beta);
+    }
     g.A = A; g.B = B; g.C = C;
     g.batch = p.batch;
     g.M = p.M; g.N = p.N; g.K = p.K;
@@ -233,6 +251,15 @@ nt_status nt_gemm(const void *A, const nt_tensor_desc *dA, const void *B, const 
                   nt_tile_cfg cfg, void *hip_stream)
 {
     return run(KIND_GEMM, A, dA, B, dB, C, dC, 1, 1, 0, 0, in_dtype, out_dtype, cfg, hip_stream);
+}
+
+nt_status nt_addmm(const void *input, const nt_tensor_desc *dI, const void *A, const nt_tensor_desc *dA,
+                   const void *B, const nt_tensor_desc *dB, void *C, const nt_tensor_desc *dC,
+                   float alpha, float beta, nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *hip_stream)
+{
+    if (!dI) return fail(NT_ERR_INVALID_ARG, "null tensor descriptor");
+    if (!(alpha == alpha) || !(beta == beta)) return fail(NT_ERR_INVALID_ARG, "alpha / beta is NaN");
+    return run(KIND_GEMM, A, dA, B, dB, C, dC, 1, 1, 0, 0, in_dtype, out_dtype, cfg, hip_stream, input, dI, alpha, beta);
 }
 
 nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,

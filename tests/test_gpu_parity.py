@@ -129,6 +129,78 @@ def test_axes_shorter_than_one_vector(M, N, K):
                 assert np.array_equal(to_f64(C), ref), (tile, ta, tb)
 
 
+
+@pytest.mark.parametrize("out", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("M,N,K,tile", [(256, 256, 128, (128, 128, 64)), (512, 512, 256, (256, 256, 64)), (300, 264, 200, (128, 128, 64)),
+                                        (301, 263, 131, (256, 256, 64)), (150, 170, 90, (64, 64, 32)), (512, 768, 128, None)])
+def test_addmm_full_input(M, N, K, tile, out):
+    """beta * input + alpha * (A . B) on the direct, staged and operand-map kernels."""
+    dt = "f16"
+    A, B = si.gemm_inputs(M, N, K, dt, seed=21, dist="normal")
+    rng = np.random.default_rng(23)
+    Ival = rng.standard_normal((M, N)).astype(np.float32)
+    Iten = torch.from_numpy(Ival).to(TORCH_DT[out]).cuda()
+    ref = onum.addmm(to_f64(Iten), A, B, dt, alpha=0.75, beta=-1.5)
+    C = torch.full((M, N), float("nan"), dtype=TORCH_DT[out], device="cuda")
+    nt.addmm(Iten, to_gpu(A, dt), to_gpu(B, dt), C, alpha=0.75, beta=-1.5, tile=tile)
+    torch.cuda.synchronize()
+    assert_gates(to_f64(C), ref, out, f"addmm {M}x{N}x{K} {tile} {out}")
+
+
+@pytest.mark.parametrize("tile", [(64, 64, 32), (128, 128, 64), (256, 256, 64)])
+def test_addmm_bias_broadcast_and_exact_integers(tile):
+    dt, M, N, K = "bf16", 260, 300, 72
+    A, B = si.gemm_inputs(M, N, K, dt, seed=31, dist="int")
+    prod = onum.gemm(A, B, dt)
+    rng = np.random.default_rng(32)
+    row = torch.from_numpy(rng.integers(-8, 8, (N,)).astype(np.float32)).cuda()
+    col = torch.from_numpy(rng.integers(-8, 8, (M, 1)).astype(np.float32)).cuda()
+    a, b = to_gpu(A, dt), to_gpu(B, dt)
+    for inp, alpha, beta in [(row, 1.0, 1.0), (col, 2.0, -3.0), (row, -1.0, 0.5)]:
+        C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        nt.addmm(inp, a, b, C, alpha=alpha, beta=beta, tile=tile)
+        torch.cuda.synchronize()
+        ref = onum.addmm(inp.cpu().numpy().astype(np.float64), A, B, dt, alpha=alpha, beta=beta)
+        assert np.array_equal(to_f64(C), ref), (tile, alpha, beta)
+    # beta = 0: the input is not read (NaNs in it must not reach C); alpha alone scales
+    nan = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    nt.addmm(nan, a, b, C, alpha=2.0, beta=0.0, tile=tile)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_f64(C), 2.0 * prod)
+    # in place: C doubles as the input
+    C = torch.from_numpy(rng.integers(-8, 8, (M, N)).astype(np.float32)).cuda()
+    ref = onum.addmm(to_f64(C), A, B, dt, alpha=1.0, beta=1.0)
+    nt.addmm(C, a, b, C, tile=tile)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_f64(C), ref)
+
+
+def test_addmm_strided_input_transposed_output_and_k_zero():
+    dt, M, N, K = "f16", 200, 136, 96
+    A, B = si.gemm_inputs(M, N, K, dt, seed=41, dist="int")
+    rng = np.random.default_rng(42)
+    It = torch.from_numpy(rng.integers(-8, 8, (N, M)).astype(np.float32)).cuda()      # input given transposed
+    ref = onum.addmm(to_f64(It.t()), A, B, dt, alpha=1.0, beta=2.0)
+    for tile in [(64, 64, 32), (128, 128, 64)]:
+        C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        nt.addmm(It.t(), to_gpu(A, dt), to_gpu(B, dt), C, alpha=1.0, beta=2.0, tile=tile)
+        Ct = torch.full((N, M), float("nan"), dtype=torch.float32, device="cuda")
+        nt.addmm(It.t(), to_gpu(A, dt), to_gpu(B, dt), Ct.t(), alpha=1.0, beta=2.0, tile=tile)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_f64(C), ref) and np.array_equal(to_f64(Ct.t()), ref)
+    # K = 0: C = beta * input
+    A0 = torch.empty((M, 0), dtype=torch.float16, device="cuda")
+    B0 = torch.empty((0, N), dtype=torch.float16, device="cuda")
+    for tile in [None, (128, 128, 64)]:
+        C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        nt.addmm(It.t(), A0, B0, C, alpha=3.0, beta=-2.0, tile=tile)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_f64(C), -2.0 * to_f64(It.t()))
+    with pytest.raises(nt.NtError):
+        nt.addmm(It, to_gpu(A, dt), to_gpu(B, dt), torch.empty((M, N), dtype=torch.float32, device="cuda"))   # [N, M] input
+
+
 def test_general_strides_and_padded_pitch():
     dt, M, N, K = "bf16", 150, 170, 90
     A, B = si.gemm_inputs(M, N, K, dt, seed=4, dist="uniform")
