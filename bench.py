@@ -37,7 +37,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="p_f16_8192",
-                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c1_f16_256")
+                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c1_f16_256, f1_f16_addmm")
     ap.add_argument("--tile", default=None, help="bm,bn,bk (default: library choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -56,7 +56,8 @@ def flops_and_bytes(cfg):
         return 2.0 * N * P * Q * K * C * R * S, 2 * (N * C * H * W + K * C * R * S) + osz * N * K * P * Q
     b = cfg.get("batch", 1)
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
-    return 2.0 * b * M * N * K, b * (2 * (M * K + K * N) + osz * M * N)
+    extra = osz * M * N if cfg["kind"] == "addmm" else 0            # the added input is read once
+    return 2.0 * b * M * N * K, b * (2 * (M * K + K * N) + osz * M * N) + extra
 
 
 def main():
@@ -102,11 +103,16 @@ def main():
     else:
         Ab, Bb = si.gemm_inputs(cfg["M"], cfg["N"], cfg["K"], dt, cfg["seed"], cfg["dist"], batch=cfg.get("batch"))
         a, b = to_gpu(Ab, dt), to_gpu(Bb, dt)
-        shape = (cfg["M"], cfg["N"]) if cfg["kind"] == "gemm" else (cfg["batch"], cfg["M"], cfg["N"])
+        shape = (cfg["batch"], cfg["M"], cfg["N"]) if cfg["kind"] == "bmm" else (cfg["M"], cfg["N"])
         y = torch.empty(shape, dtype=TORCH_DT[out], device="cuda")
-        fn = nt.gemm if cfg["kind"] == "gemm" else nt.bmm
-        step = lambda: fn(a, b, y, tile=tile)
-        grid, kt = (nt.arrange_gemm if cfg["kind"] == "gemm" else nt.arrange_bmm)(a, b, y, tile=tile)
+        if cfg["kind"] == "addmm":
+            Ib = si.normal_bits((cfg["M"], cfg["N"]), out, cfg["seed"] + 2, 1.0)
+            inp = to_gpu(Ib, out)
+            step = lambda: nt.addmm(inp, a, b, y, alpha=cfg["alpha"], beta=cfg["beta"], tile=tile)
+        else:
+            fn = nt.gemm if cfg["kind"] == "gemm" else nt.bmm
+            step = lambda: fn(a, b, y, tile=tile)
+        grid, kt = (nt.arrange_bmm if cfg["kind"] == "bmm" else nt.arrange_gemm)(a, b, y, tile=tile)
     flops, alg_bytes = flops_and_bytes(cfg)
 
     # ---- warm-up, then exactly K timed steps bracketed by synchronisation
@@ -156,10 +162,12 @@ def main():
         else:
             M, N = cfg["M"], cfg["N"]
             ms, ns = rng.integers(0, M, 64), rng.integers(0, N, 64)
-            bsel = 0 if cfg["kind"] == "gemm" else cfg["batch"] - 1
-            A2, B2 = (Ab, Bb) if cfg["kind"] == "gemm" else (Ab[bsel], Bb[bsel])
+            bsel = cfg["batch"] - 1 if cfg["kind"] == "bmm" else 0
+            A2, B2 = (Ab[bsel], Bb[bsel]) if cfg["kind"] == "bmm" else (Ab, Bb)
             ref = onum.gemm_samples(A2, B2, dt, ms, ns)
-            yy = y if cfg["kind"] == "gemm" else y[bsel]
+            if cfg["kind"] == "addmm":
+                ref = cfg["beta"] * onum.decode(Ib, out)[ms, ns] + cfg["alpha"] * ref
+            yy = y[bsel] if cfg["kind"] == "bmm" else y
             got = to_f64(yy[torch.from_numpy(ms).cuda(), torch.from_numpy(ns).cuda()])
         result["parity"] = {"samples": int(ref.size), "max_abs_err": float(np.abs(got - ref).max()),
                             "rel_frobenius_err": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
@@ -170,7 +178,7 @@ def main():
         cores = min(os.cpu_count() or 1, 16)
         M, N, K = cfg["M"], cfg["N"], cfg["K"]
         ms_, ns_ = min(M, 4096), min(N, 4096)
-        A2, B2 = (Ab, Bb) if cfg["kind"] == "gemm" else (Ab[0], Bb[0])
+        A2, B2 = (Ab[0], Bb[0]) if cfg["kind"] == "bmm" else (Ab, Bb)
         t1 = time.perf_counter()
         onum.gemm(A2[:ms_, :], B2[:, :ns_], dt, nthreads=cores)
         dt_cpu = time.perf_counter() - t1

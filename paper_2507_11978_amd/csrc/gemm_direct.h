@@ -277,22 +277,23 @@ static nt_status launch_direct_inst(const FastArgs &a, int64_t nwg, hipStream_t 
     return check_launch("gemm_direct_kernel");
 }
 
-template <int BM, int BN>
-static nt_status launch_direct_t(const FastArgs &a, bool bf16, int alay, int blay, int64_t nwg, hipStream_t s)
+template <int BM, int BN, bool BF16>
+static nt_status launch_direct_t(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s)
 {
-#define NT_DIRECT(BF, AL, BL) launch_direct_inst<BM, BN, BF, AL, BL>(a, nwg, s)
-    if (bf16) {
-        if (alay == KCONTIG) return blay == MNCONTIG ? NT_DIRECT(true, KCONTIG, MNCONTIG) : NT_DIRECT(true, KCONTIG, KCONTIG);
-        return blay == MNCONTIG ? NT_DIRECT(true, MNCONTIG, MNCONTIG) : NT_DIRECT(true, MNCONTIG, KCONTIG);
-    }
-    if (alay == KCONTIG) return blay == MNCONTIG ? NT_DIRECT(false, KCONTIG, MNCONTIG) : NT_DIRECT(false, KCONTIG, KCONTIG);
-    return blay == MNCONTIG ? NT_DIRECT(false, MNCONTIG, MNCONTIG) : NT_DIRECT(false, MNCONTIG, KCONTIG);
-#undef NT_DIRECT
+    if (alay == KCONTIG && blay == MNCONTIG) return launch_direct_inst<BM, BN, BF16, KCONTIG, MNCONTIG>(a, nwg, s);
+    if (alay == KCONTIG && blay == KCONTIG) return launch_direct_inst<BM, BN, BF16, KCONTIG, KCONTIG>(a, nwg, s);
+    if (alay == MNCONTIG && blay == MNCONTIG) return launch_direct_inst<BM, BN, BF16, MNCONTIG, MNCONTIG>(a, nwg, s);
+    return launch_direct_inst<BM, BN, BF16, MNCONTIG, KCONTIG>(a, nwg, s);
 }
 
-nt_status launch_direct_128x128(const FastArgs &a, bool bf16, int alay, int blay, int64_t nwg, hipStream_t s);
-nt_status launch_direct_256x128(const FastArgs &a, bool bf16, int alay, int blay, int64_t nwg, hipStream_t s);
-nt_status launch_direct_128x256(const FastArgs &a, bool bf16, int alay, int blay, int64_t nwg, hipStream_t s);
-nt_status launch_direct_256x256(const FastArgs &a, bool bf16, int alay, int blay, int64_t nwg, hipStream_t s);
+// one translation unit per tile shape and input format defines these (parallel compilation)
+#define NT_DIRECT_DECL(T) \
+    nt_status launch_direct_##T##_f16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s); \
+    nt_status launch_direct_##T##_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s);
+NT_DIRECT_DECL(128x128)
+NT_DIRECT_DECL(256x128)
+NT_DIRECT_DECL(128x256)
+NT_DIRECT_DECL(256x256)
+#undef NT_DIRECT_DECL
 
 }  // namespace nt

@@ -414,6 +414,7 @@ __device__ __forceinline__ void store_tile_strided(void *C, int64_t scm, int64_t
 }
 
 // Epilogue of the transposed-accumulator kernels: picks the store routine for C's layout and format.
+// EDGE = false (the direct kernel): full tiles, C and D with unit stride along n.
 template <int BM, int BN, bool EDGE>
 __device__ __forceinline__ void store_tile(const FastArgs &g, int64_t bi, const float16v (&acc)[BM / 64][BN / 64],
                                            int64_t row_w, int64_t col_w, int lane, bool ragged)
@@ -421,9 +422,11 @@ __device__ __forceinline__ void store_tile(const FastArgs &g, int64_t bi, const 
     const int64_t esz = g.out_dtype == NT_F32 ? 4 : 2;
     char *C = reinterpret_cast<char *>(g.C) + bi * g.sc_batch * esz;
     const char *D = g.D ? reinterpret_cast<const char *>(g.D) + bi * g.sd_batch * esz : nullptr;
-    if (g.scn != 1 || (D && g.sdn != 1)) {
-        store_tile_strided<BM, BN>(C, g.scm, g.scn, acc, row_w, col_w, lane, g.M, g.N, g.out_dtype, D, g.sdm, g.sdn, g.alpha, g.beta);
-        return;
+    if constexpr (EDGE) {       // (launches with such a C or D always take the EDGE flavour)
+        if (g.scn != 1 || (D && g.sdn != 1)) {
+            store_tile_strided<BM, BN>(C, g.scm, g.scn, acc, row_w, col_w, lane, g.M, g.N, g.out_dtype, D, g.sdm, g.sdn, g.alpha, g.beta);
+            return;
+        }
     }
     const bool affine = D != nullptr || g.alpha != 1.f;
 #define NT_ROWS(OUT, CHECK) store_tile_rows<BM, BN, OUT, CHECK>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta)
@@ -441,7 +444,7 @@ __device__ __forceinline__ void store_tile(const FastArgs &g, int64_t bi, const 
 #undef NT_ROWS
 }
 
-template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE>
+template <int BM, int BN, bool BF16, int ALAY, int BLAY>
 __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
@@ -463,8 +466,8 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
     const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kBK : (int64_t)kBK * g.ldb) * 2;
     const int64_t m_left = g.M - row0, n_left = g.N - col0;
 
-    typename StageSel<BM, ALAY, EDGE>::type sa;
-    typename StageSel<BN, BLAY, EDGE>::type sb;
+    typename StageSel<BM, ALAY, true>::type sa;
+    typename StageSel<BN, BLAY, true>::type sb;
     sa.init(tid, g.lda);
     sb.init(tid, g.ldb);
 
@@ -524,27 +527,23 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
         __syncthreads();
         cur = nxt;
     };
+    // Programs whose tile lies inside C fetch every k tile but the last with plain loads
+    // (trip k fetches tile k + 1); the rest, and programs on the ragged edge, mask.
     int64_t k = 0;
-    if constexpr (EDGE) {
-        // Programs whose tile lies inside C fetch every k tile but the last with plain loads
-        // (trip k fetches tile k + 1); the rest, and programs on the ragged edge, mask.
-        if (m_left >= BM && n_left >= BN)
-            for (; k < g.kt - 2; ++k) trip(std::false_type{}, k);
-        for (; k < g.kt; ++k) trip(std::true_type{}, k);
-    } else {
-        for (; k < g.kt; ++k) trip(std::false_type{}, k);
-    }
+    if (m_left >= BM && n_left >= BN)
+        for (; k < g.kt - 2; ++k) trip(std::false_type{}, k);
+    for (; k < g.kt; ++k) trip(std::true_type{}, k);
 
     // ---- epilogue: convert and store (masked on ragged tiles)
-    store_tile<BM, BN, EDGE>(g, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane, m_left < BM || n_left < BN);
+    store_tile<BM, BN, true>(g, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane, m_left < BM || n_left < BN);
 }
 
 // ------------------------------------------------------------------ host launch helpers
-template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE>
+template <int BM, int BN, bool BF16, int ALAY, int BLAY>
 static nt_status launch_fast_inst(const FastArgs &a, int64_t nwg, hipStream_t s)
 {
     constexpr size_t smem = (size_t)2 * (BM + BN) * kBK * sizeof(uint16_t);
-    auto kern = gemm_fast_kernel<BM, BN, BF16, ALAY, BLAY, EDGE>;
+    auto kern = gemm_fast_kernel<BM, BN, BF16, ALAY, BLAY>;
     static bool configured = false;              // raise the dynamic LDS limit once per instantiation
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -555,28 +554,23 @@ static nt_status launch_fast_inst(const FastArgs &a, int64_t nwg, hipStream_t s)
     return check_launch("gemm_fast_kernel");
 }
 
-template <int BM, int BN, bool BF16, bool EDGE>
-static nt_status launch_fast_lay(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s)
+template <int BM, int BN, bool BF16>
+static nt_status launch_fast_t(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s)
 {
-    if (alay == KCONTIG && blay == MNCONTIG) return launch_fast_inst<BM, BN, BF16, KCONTIG, MNCONTIG, EDGE>(a, nwg, s);
-    if (alay == KCONTIG && blay == KCONTIG) return launch_fast_inst<BM, BN, BF16, KCONTIG, KCONTIG, EDGE>(a, nwg, s);
-    if (alay == MNCONTIG && blay == MNCONTIG) return launch_fast_inst<BM, BN, BF16, MNCONTIG, MNCONTIG, EDGE>(a, nwg, s);
-    return launch_fast_inst<BM, BN, BF16, MNCONTIG, KCONTIG, EDGE>(a, nwg, s);
+    if (alay == KCONTIG && blay == MNCONTIG) return launch_fast_inst<BM, BN, BF16, KCONTIG, MNCONTIG>(a, nwg, s);
+    if (alay == KCONTIG && blay == KCONTIG) return launch_fast_inst<BM, BN, BF16, KCONTIG, KCONTIG>(a, nwg, s);
+    if (alay == MNCONTIG && blay == MNCONTIG) return launch_fast_inst<BM, BN, BF16, MNCONTIG, MNCONTIG>(a, nwg, s);
+    return launch_fast_inst<BM, BN, BF16, MNCONTIG, KCONTIG>(a, nwg, s);
 }
 
-template <int BM, int BN>
-static nt_status launch_fast_t(const FastArgs &a, bool bf16, bool edge, int alay, int blay, int64_t nwg, hipStream_t s)
-{
-    if (bf16) return edge ? launch_fast_lay<BM, BN, true, true>(a, alay, blay, nwg, s)
-                          : launch_fast_lay<BM, BN, true, false>(a, alay, blay, nwg, s);
-    return edge ? launch_fast_lay<BM, BN, false, true>(a, alay, blay, nwg, s)
-                : launch_fast_lay<BM, BN, false, false>(a, alay, blay, nwg, s);
-}
-
-// one translation unit per tile shape defines these (parallel compilation)
-nt_status launch_fast_128x128(const FastArgs &a, bool bf16, bool edge, int alay, int blay, int64_t nwg, hipStream_t s);
-nt_status launch_fast_256x128(const FastArgs &a, bool bf16, bool edge, int alay, int blay, int64_t nwg, hipStream_t s);
-nt_status launch_fast_128x256(const FastArgs &a, bool bf16, bool edge, int alay, int blay, int64_t nwg, hipStream_t s);
-nt_status launch_fast_256x256(const FastArgs &a, bool bf16, bool edge, int alay, int blay, int64_t nwg, hipStream_t s);
+// one translation unit per tile shape and input format defines these (parallel compilation)
+#define NT_FAST_DECL(T) \
+    nt_status launch_fast_##T##_f16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s); \
+    nt_status launch_fast_##T##_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s);
+NT_FAST_DECL(128x128)
+NT_FAST_DECL(256x128)
+NT_FAST_DECL(128x256)
+NT_FAST_DECL(256x256)
+#undef NT_FAST_DECL
 
 }  // namespace nt

@@ -1,0 +1,9 @@
+// Instantiations of the staged (register-staged, masked) kernel for the 256 x 128 x 64 tile, bf16 inputs.
+#include "gemm_fast.h"
+
+namespace nt {
+nt_status launch_fast_256x128_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s)
+{
+    return launch_fast_t<256, 128, true>(a, alay, blay, nwg, s);
+}
+}  // namespace nt

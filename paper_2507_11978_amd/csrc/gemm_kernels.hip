@@ -144,25 +144,23 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             a.sdn = g.md.coff[0];
             a.sd_batch = g.sd_batch;
         }
-        const bool edge = (g.M % t.bm) || (g.N % t.bn) || (g.K % t.bk);
         const bool bf16 = g.in_dtype == NT_BF16;
         const int64_t nwg = g.batch * g.mt * g.nt;
         hipStream_t s = (hipStream_t)g.stream;
-        // full tiles of 16-byte aligned operands stream straight into LDS
+        // full tiles of 16-byte aligned operands, stored to a C (and added to a D) with unit stride
+        // along n, stream straight into LDS; everything else takes the staged kernel
+        const bool ragged = (g.M % t.bm) || (g.N % t.bn) || (g.K % t.bk);
         auto al16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-        const bool direct = !edge && al16(a.A) && al16(a.B) && a.lda % 8 == 0 && a.ldb % 8 == 0 &&
-                            a.sa_batch % 8 == 0 && a.sb_batch % 8 == 0;
+        const bool direct = !ragged && a.scn == 1 && (!a.D || a.sdn == 1) && al16(a.A) && al16(a.B) &&
+                            a.lda % 8 == 0 && a.ldb % 8 == 0 && a.sa_batch % 8 == 0 && a.sb_batch % 8 == 0;
         if (path_out) *path_out = direct ? PATH_DIRECT : PATH_FAST;
-        if (direct) {
-            if (t.bm == 128 && t.bn == 128) return launch_direct_128x128(a, bf16, alay, blay, nwg, s);
-            if (t.bm == 256 && t.bn == 128) return launch_direct_256x128(a, bf16, alay, blay, nwg, s);
-            if (t.bm == 128 && t.bn == 256) return launch_direct_128x256(a, bf16, alay, blay, nwg, s);
-            if (t.bm == 256 && t.bn == 256) return launch_direct_256x256(a, bf16, alay, blay, nwg, s);
-        }
-        if (t.bm == 128 && t.bn == 128) return launch_fast_128x128(a, bf16, edge, alay, blay, nwg, s);
-        if (t.bm == 256 && t.bn == 128) return launch_fast_256x128(a, bf16, edge, alay, blay, nwg, s);
-        if (t.bm == 128 && t.bn == 256) return launch_fast_128x256(a, bf16, edge, alay, blay, nwg, s);
-        if (t.bm == 256 && t.bn == 256) return launch_fast_256x256(a, bf16, edge, alay, blay, nwg, s);
+        typedef nt_status (*Launcher)(const FastArgs &, int, int, int64_t, hipStream_t);
+        struct Entry { int bm, bn; Launcher direct[2], staged[2]; };      // [f16, bf16]
+#define NT_ENTRY(BM, BN, T) {BM, BN, {launch_direct_##T##_f16, launch_direct_##T##_bf16}, {launch_fast_##T##_f16, launch_fast_##T##_bf16}}
+        static const Entry table[] = {NT_ENTRY(128, 128, 128x128), NT_ENTRY(256, 128, 256x128), NT_ENTRY(128, 256, 128x256), NT_ENTRY(256, 256, 256x256)};
+#undef NT_ENTRY
+        for (const Entry &e : table)
+            if (e.bm == t.bm && e.bn == t.bn) return (direct ? e.direct : e.staged)[bf16 ? 1 : 0](a, alay, blay, nwg, s);
         return fail(NT_ERR_UNSUPPORTED, "no fast kernel for this tile");
     }
     return launch_generic(g);
