@@ -257,9 +257,10 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_ke
         step(1, 0, nxt, ND, slice_a(sl + kRing), slice_b(sl + kRing), ring);
         ring = nxt;
     }
-    NT_WAIT_VMCNT(0);                                      // drain the surplus prefetches before the LDS is released
+    NT_WAIT_VMCNT(0);                                      // drain the surplus prefetches ...
+    __syncthreads();                                       // ... of every wavefront: the epilogue reuses the LDS
 
-    store_tile<BM, BN, false>(g, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane, false);
+    store_tile<BM, BN, false>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane, false);
 }
 
 template <int BM, int BN, bool BF16, int ALAY, int BLAY>

@@ -319,13 +319,15 @@ __device__ __forceinline__ void load_row16(const char *p, float (&d)[16])
     }
 }
 
-// C with unit stride along n: every lane stores its 16 consecutive columns of each block with
-// 16-byte stores.  row_w / col_w: first row / column of the wavefront's part of the tile.
+// C with unit stride along n, 16-bit output: every lane stores its 16 consecutive columns of each
+// block with two 16-byte stores straight from registers.  (Lines of C are completed by several
+// instructions, but the epilogue is one burst of stores at the memory's write rate either way, and
+// this routine issues it sooner than the one through LDS below, which fp32 outputs need.)  row_w / col_w: first row / column of the wavefront's part of the tile.
 // CHECK masks rows >= M and columns >= N (a partly valid run of 16 is stored element-wise).
 // affine: the stored value is alpha * accumulator + beta * D (D: elements of the output type with
 // unit stride along n and row stride sdm, read under the same masks; nullptr = no addend).
 template <int BM, int BN, int OUT, bool CHECK>
-__device__ __forceinline__ void store_tile_rows(char *C, int64_t scm, const float16v (&acc)[BM / 64][BN / 64],
+__device__ __forceinline__ void store_tile_regs(char *C, int64_t scm, const float16v (&acc)[BM / 64][BN / 64],
                                                 int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N,
                                                 bool affine, const char *D, int64_t sdm, float alpha, float beta)
 {
@@ -389,6 +391,106 @@ __device__ __forceinline__ void store_tile_rows(char *C, int64_t scm, const floa
     }
 }
 
+// C with unit stride along n.  The wavefront's (BM/2) x (BN/2) part of the tile goes through LDS
+// (free by now; each wavefront uses a region of its own) so that global stores are whole lines:
+//   write phase  every lane gathers 16 consecutive columns of its row per 32 x 32 block, applies
+//                alpha / beta * D in fp32 if asked (D: elements of the output type with unit stride
+//                along n and row stride sdm), converts once, and writes 16-byte chunks to
+//                [row][RB bytes], chunk index XOR-swizzled with the row so that the 16-byte writes
+//                of 16 lanes (16 rows, same chunk) fall on different banks;
+//   read phase   RB / 16 consecutive lanes read one row, so a store instruction covers 64 / (RB/16)
+//                rows of RB contiguous bytes each.
+// An fp32 tile takes two passes (one per half of the columns) through the same region.
+// row_w / col_w: first row / column of the wavefront's part.  CHECK masks rows >= M and columns
+// >= N (a partly valid 16-byte chunk is stored element-wise).
+template <int BM, int BN, int OUT, bool CHECK>
+__device__ __forceinline__ void store_tile_rows(char *smem, int wave, char *C, int64_t scm, const float16v (&acc)[BM / 64][BN / 64],
+                                                int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N,
+                                                bool affine, const char *D, int64_t sdm, float alpha, float beta)
+{
+    constexpr int TM = BM / 64, TN = BN / 64, WM = BM / 2, WN = BN / 2;
+    constexpr int ES = OUT == NT_F32 ? 4 : 2;
+    constexpr int PASSES = OUT == NT_F32 ? 2 : 1;
+    constexpr int TNP = TN / PASSES;                      // 32-column blocks per pass
+    constexpr int RB = WN * 2;                            // bytes per region row (16-bit: WN elements; fp32: WN / 2)
+    constexpr int CPR = RB / 16;                          // 16-byte chunks per row: 16 or 8
+    constexpr int RSH = RB == 256 ? 0 : 1;                // log2(rows per 256 bytes of LDS)
+    constexpr int EPC = 16 / ES;                          // elements per chunk
+    constexpr int RPI = 64 / CPR;                         // rows per store instruction
+    const int l32 = lane & 31, hi = lane >> 5;
+    char *reg = smem + wave * (WM * RB);
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass) {
+        // ---- write phase
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int r = tm * 32 + l32;
+            const int64_t row = row_w + r;
+            const bool row_ok = !CHECK || row < M;
+#pragma unroll
+            for (int tnp = 0; tnp < TNP; ++tnp) {
+                const int tn = pass * TNP + tnp;
+                uint32_t o[16];
+                gather_row16(acc[tm][tn], o);
+                if (affine) {                                         // wavefront-uniform
+                    float d[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) d[i] = 0.f;
+                    if (D) {
+                        const int64_t col = col_w + tn * 32 + 16 * hi;
+                        const char *dp = D + (row * sdm + col) * ES;
+                        const int64_t nv = CHECK ? N - col : 16;      // valid columns from the lane's first
+                        if (row_ok && nv >= 16) {
+                            load_row16<OUT>(dp, d);
+                        } else if (CHECK && row_ok && nv > 0) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i)
+                                if (i < nv) d[i] = load_as_f32(dp, i, OUT);
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[i] = __builtin_bit_cast(uint32_t, combine(__builtin_bit_cast(float, o[i]), d[i], alpha, beta));
+                }
+                const int c0 = (tnp * 32 + 16 * hi) / EPC;
+                const int sw = (r >> RSH) & (CPR - 1);
+                char *prow = reg + r * RB;
+                if constexpr (OUT == NT_F32) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        lds_write16(prow, (uint32_t)(((c0 + q) ^ sw) << 4), u32x4{o[4 * q], o[4 * q + 1], o[4 * q + 2], o[4 * q + 3]});
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+                        lds_write16(prow, (uint32_t)(((c0 + q) ^ sw) << 4),
+                                    u32x4{pack_pair<OUT>(o[8 * q], o[8 * q + 1]), pack_pair<OUT>(o[8 * q + 2], o[8 * q + 3]),
+                                          pack_pair<OUT>(o[8 * q + 4], o[8 * q + 5]), pack_pair<OUT>(o[8 * q + 6], o[8 * q + 7])});
+                }
+            }
+        }
+        // ---- read phase (same wavefront: LDS operations complete in order)
+#pragma unroll
+        for (int it = 0; it < WM / RPI; ++it) {
+            const int r = it * RPI + lane / CPR, c = lane % CPR;
+            const u32x4 v = lds_read16(reg, (uint32_t)(r * RB + ((c ^ ((r >> RSH) & (CPR - 1))) << 4)));
+            const int64_t row = row_w + r;
+            const int64_t col = col_w + pass * (WN / PASSES) + c * EPC;
+            char *p = C + (row * scm + col) * ES;
+            if (!CHECK || (row < M && col + EPC <= N)) {
+                __builtin_memcpy(p, &v, 16);
+            } else if (row < M && col < N) {
+                const int nv = (int)(N - col);
+#pragma unroll
+                for (int e = 0; e < EPC; ++e)
+                    if (e < nv) {
+                        const uint32_t w = v[ES == 4 ? e : e / 2];
+                        if constexpr (OUT == NT_F32) *reinterpret_cast<uint32_t *>(p + 4 * e) = w;
+                        else *reinterpret_cast<uint16_t *>(p + 2 * e) = (uint16_t)((e & 1) ? w >> 16 : w & 0xffffu);
+                    }
+            }
+        }
+    }
+}
+
 // C (and D) with any strides: one store per element, always masked.
 template <int BM, int BN>
 __device__ __forceinline__ void store_tile_strided(void *C, int64_t scm, int64_t scn, const float16v (&acc)[BM / 64][BN / 64],
@@ -415,8 +517,9 @@ __device__ __forceinline__ void store_tile_strided(void *C, int64_t scm, int64_t
 
 // Epilogue of the transposed-accumulator kernels: picks the store routine for C's layout and format.
 // EDGE = false (the direct kernel): full tiles, C and D with unit stride along n.
+// smem: the workgroup's LDS, no longer in use by any wavefront (the caller has passed a barrier).
 template <int BM, int BN, bool EDGE>
-__device__ __forceinline__ void store_tile(const FastArgs &g, int64_t bi, const float16v (&acc)[BM / 64][BN / 64],
+__device__ __forceinline__ void store_tile(const FastArgs &g, char *smem, int wave, int64_t bi, const float16v (&acc)[BM / 64][BN / 64],
                                            int64_t row_w, int64_t col_w, int lane, bool ragged)
 {
     const int64_t esz = g.out_dtype == NT_F32 ? 4 : 2;
@@ -429,19 +532,21 @@ __device__ __forceinline__ void store_tile(const FastArgs &g, int64_t bi, const 
         }
     }
     const bool affine = D != nullptr || g.alpha != 1.f;
-#define NT_ROWS(OUT, CHECK) store_tile_rows<BM, BN, OUT, CHECK>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta)
+#define NT_ROWS(CHECK) store_tile_rows<BM, BN, NT_F32, CHECK>(smem, wave, C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta)
+#define NT_REGS(OUT, CHECK) store_tile_regs<BM, BN, OUT, CHECK>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta)
     if constexpr (EDGE) {
         if (ragged) {
-            if (g.out_dtype == NT_F32) NT_ROWS(NT_F32, true);
-            else if (g.out_dtype == NT_F16) NT_ROWS(NT_F16, true);
-            else NT_ROWS(NT_BF16, true);
+            if (g.out_dtype == NT_F32) NT_ROWS(true);
+            else if (g.out_dtype == NT_F16) NT_REGS(NT_F16, true);
+            else NT_REGS(NT_BF16, true);
             return;
         }
     }
-    if (g.out_dtype == NT_F32) NT_ROWS(NT_F32, false);
-    else if (g.out_dtype == NT_F16) NT_ROWS(NT_F16, false);
-    else NT_ROWS(NT_BF16, false);
+    if (g.out_dtype == NT_F32) NT_ROWS(false);
+    else if (g.out_dtype == NT_F16) NT_REGS(NT_F16, false);
+    else NT_REGS(NT_BF16, false);
 #undef NT_ROWS
+#undef NT_REGS
 }
 
 template <int BM, int BN, bool BF16, int ALAY, int BLAY>
@@ -535,7 +640,7 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
     for (; k < g.kt; ++k) trip(std::true_type{}, k);
 
     // ---- epilogue: convert and store (masked on ragged tiles)
-    store_tile<BM, BN, true>(g, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane, m_left < BM || n_left < BN);
+    store_tile<BM, BN, true>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane, m_left < BM || n_left < BN);
 }
 
 // ------------------------------------------------------------------ host launch helpers
