@@ -143,11 +143,15 @@ struct StageK {
             for (int i = 0; i < CH; ++i) r[i] = shift_down(r[i], shift);
         }
     }
+    static constexpr int PIECES = CH;                     // LDS writes per thread and block
+    __device__ __forceinline__ void store_piece(char *smem, uint32_t buf_off, int i) const
+    {
+        lds_write16(smem, buf_off + (wbase ^ ((i & 1) << 6)) + i * 4096, r[i]);
+    }
     __device__ __forceinline__ void store(char *smem, uint32_t buf_off) const
     {
 #pragma unroll
-        for (int i = 0; i < CH; ++i)
-            lds_write16(smem, buf_off + (wbase ^ ((i & 1) << 6)) + i * 4096, r[i]);
+        for (int i = 0; i < CH; ++i) store_piece(smem, buf_off, i);
     }
 };
 
@@ -230,18 +234,21 @@ struct StageMN {
             }
         }
     }
+    static constexpr int PIECES = NW;                     // LDS writes per thread and block
+    __device__ __forceinline__ void store_piece(char *smem, uint32_t buf_off, int n) const
+    {
+        u32x4 v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t lo = r[2 * q][n >> 1], hi = r[2 * q + 1][n >> 1];
+            v[q] = (n & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+        }
+        lds_write16(smem, buf_off + (wbase ^ (n << 4)) + n * 128, v);
+    }
     __device__ __forceinline__ void store(char *smem, uint32_t buf_off) const
     {
 #pragma unroll
-        for (int n = 0; n < NW; ++n) {
-            u32x4 v;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t lo = r[2 * q][n >> 1], hi = r[2 * q + 1][n >> 1];
-                v[q] = (n & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-            }
-            lds_write16(smem, buf_off + (wbase ^ (n << 4)) + n * 128, v);
-        }
+        for (int n = 0; n < NW; ++n) store_piece(smem, buf_off, n);
     }
 };
 
@@ -623,12 +630,36 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
         const int64_t kn = k < last ? k + 1 : last;
         sa.template load<decltype(masked)::value>(gA + kn * a_step, m_left, g.K - kn * kBK);
         sb.template load<decltype(masked)::value>(gB + kn * b_step, n_left, g.K - kn * kBK);
+        __builtin_amdgcn_sched_barrier(0);           // the loads stay ahead of the multiplications that hide their latency
 #pragma unroll
-        for (int ks = 0; ks < kBK / 16; ++ks) step(ks, cur * A_BYTES, cur * B_BYTES);
+        for (int ks = 0; ks < kBK / 16 - 1; ++ks) step(ks, cur * A_BYTES, cur * B_BYTES);
+        __builtin_amdgcn_sched_barrier(0);
         sa.settle();
         sb.settle();
-        sa.store(smem, nxt * A_BYTES);
-        sb.store(smem, B_BASE + nxt * B_BYTES);
+        // last k step: the fetched tile goes to the idle LDS copy piece by piece between the MFMAs
+        {
+            constexpr int ks = kBK / 16 - 1;
+            constexpr int PA = decltype(sa)::PIECES, PB = decltype(sb)::PIECES, NM = TM * TN;
+            constexpr int PER = (PA + PB + NM - 1) / NM;      // pieces after each MFMA
+            u32x4 fa[TM], fb[TN];
+#pragma unroll
+            for (int t = 0; t < TM; ++t)
+                fa[t] = lds_read16(smem, (a_rd ^ (uint32_t)(((2 * ks) ^ ((t & 1) << 2)) << 4)) + t * 4096 + cur * A_BYTES);
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+                fb[t] = lds_read16(smem, (b_rd ^ (uint32_t)(((2 * ks) ^ ((t & 1) << 2)) << 4)) + t * 4096 + cur * B_BYTES);
+#pragma unroll
+            for (int idx = 0; idx < NM; ++idx) {
+                acc[idx / TN][idx % TN] = mfma32<BF16>(fb[idx % TN], fa[idx / TN], acc[idx / TN][idx % TN]);
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    const int piece = idx * PER + q;
+                    if (piece < PA) sa.store_piece(smem, nxt * A_BYTES, piece);
+                    else if (piece < PA + PB) sb.store_piece(smem, B_BASE + nxt * B_BYTES, piece - PA);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
         __syncthreads();
         cur = nxt;
     };
