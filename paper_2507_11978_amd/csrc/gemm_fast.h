@@ -93,7 +93,10 @@ template <int ROWS, bool EDGE>
 struct StageK {
     static constexpr int CH = ROWS * 8 / kThreads;        // 16-byte chunks per thread
     u32x4 r[CH];
-    uint32_t voff[CH];                                    // byte offsets from the tile origin
+    uint32_t voff0;                                       // byte offset of the thread's first chunk from the tile origin
+    uint32_t vsel;                                        // the same with the row clamped to the tile's last valid one (set_edge)
+    int ip;
+    int64_t step;                                         // bytes between its chunks (32 rows; wavefront-uniform)
     uint32_t wbase;                                       // swizzled LDS byte offset of chunk 0
     int row0, ch;
     int shift;                                            // >= 0: pending shift of the last masked load
@@ -103,8 +106,8 @@ struct StageK {
         shift = -1;
         row0 = tid >> 3;
         ch = tid & 7;
-#pragma unroll
-        for (int i = 0; i < CH; ++i) voff[i] = ((uint32_t)(i * 32 + row0) * (uint32_t)ld + (uint32_t)(ch * 8)) * 2u;
+        voff0 = ((uint32_t)row0 * (uint32_t)ld + (uint32_t)(ch * 8)) * 2u;
+        step = 64 * ld;
         const int s0 = (row0 & 7) ^ (tid >> 6);
         wbase = (uint32_t)(row0 * 128 + ((ch ^ s0) << 4));
     }
@@ -115,20 +118,38 @@ struct StageK {
     // fill in settle(); K must be at least 8 for that address to stay inside the operand.
     // Masked elements read as zero.
     // MASKED = false: the caller knows the whole block is inside the operand.
+    // Preparation of the clamped loads below for a tile with rows_left valid rows.
+    __device__ __forceinline__ void set_edge(int64_t rows_left, int64_t ld)
+    {
+        const int last_row = (int)(rows_left < ROWS ? rows_left : ROWS) - 1;
+        ip = last_row >> 5;                                   // 32-row group that holds the last valid row
+        const int rp = last_row & 31;
+        vsel = row0 > rp ? ((uint32_t)rp * (uint32_t)ld + (uint32_t)(ch * 8)) * 2u : voff0;
+    }
+    // One of the PIECES loads of a block whose 64 k lie inside the operand.  CLAMP = false: so do
+    // all its rows.  CLAMP = true (after set_edge): rows past the ragged end fetch the last valid
+    // row instead -- their products only reach outputs that are never stored -- so the load
+    // needs no predicate and can sit between MFMAs.
+    template <bool CLAMP>
+    __device__ __forceinline__ void load_piece(const char *base, int i)
+    {
+        if constexpr (!CLAMP) r[i] = gload16(base + i * step, voff0);
+        else r[i] = gload16(base + (i < ip ? i : ip) * step, i < ip ? voff0 : vsel);
+        shift = -1;
+    }
     template <bool MASKED = EDGE>
     __device__ __forceinline__ void load(const char *base, int64_t rows_left, int64_t k_left)
     {
         if constexpr (!MASKED) {
 #pragma unroll
-            for (int i = 0; i < CH; ++i) r[i] = gload16(base, voff[i]);
-            shift = -1;
+            for (int i = 0; i < CH; ++i) load_piece<false>(base, i);
         } else {
             const int left = (int)(k_left < kBK ? k_left : kBK) - ch * 8;
             const int sh = (left > 0 && left < 8) ? 8 - left : 0;
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
                 u32x4 v{0, 0, 0, 0};
-                if (i * 32 + row0 < rows_left && left > 0) __builtin_memcpy(&v, base + ((int64_t)voff[i] - 2 * sh), 16);
+                if (i * 32 + row0 < rows_left && left > 0) __builtin_memcpy(&v, base + i * step + ((int64_t)voff0 - 2 * sh), 16);
                 r[i] = v;
             }
             shift = k_left < kBK ? sh : -1;
@@ -164,7 +185,9 @@ struct StageMN {
     static constexpr int NW = ROWS / 32;                  // 8 for 256 rows, 4 for 128 rows
     static_assert(NW == 8 || NW == 4, "transposing loader supports 128 or 256 rows");
     uint32_t r[8][NW / 2];                                // [k line][packed pairs of rows]
-    uint32_t voff[8];
+    uint32_t voff0;                                       // byte offset of the thread's first k line from the tile origin
+    uint32_t vsel;                                        // the same, or that of the tile's first block if this one starts outside (set_edge)
+    int64_t step;                                         // bytes between k lines (wavefront-uniform)
     uint32_t wbase;
     int kb, rb;
     int shift;                                            // >= 0: pending shift of the last masked load (see settle)
@@ -174,8 +197,8 @@ struct StageMN {
         shift = -1;
         kb = tid >> 5;
         rb = tid & 31;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) voff[j] = ((uint32_t)(kb * 8 + j) * (uint32_t)ld + (uint32_t)(rb * NW)) * 2u;
+        voff0 = ((uint32_t)(kb * 8) * (uint32_t)ld + (uint32_t)(rb * NW)) * 2u;
+        step = 2 * ld;
         const int s = NW == 8 ? (rb & 7) : ((((rb & 1) << 2) ^ (rb >> 1)) & 7);
         wbase = (uint32_t)(rb * NW * 128 + ((kb ^ s) << 4));
     }
@@ -185,9 +208,44 @@ struct StageMN {
     // elements with zero fill; the operand must be at least NW long along its contiguous axis
     // for that address to stay inside it.  Masked elements read as zero.
     // MASKED = false: the caller knows the whole block is inside the operand.
+    // plain load of k line j (and j + NW for the narrower block, so that there are PIECES loads)
+    // of a block that lies inside the operand
+    // Preparation of the clamped loads below for a tile with rows_left valid rows.
+    __device__ __forceinline__ void set_edge(int64_t rows_left, int64_t ld)
+    {
+        vsel = rb * NW < rows_left ? voff0 : voff0 - (uint32_t)(rb * NW * 2);
+    }
+    // Plain load of k line p (and p + NW for the narrower block, so that there are PIECES loads).
+    // CLAMP = false: the block lies inside the operand.  CLAMP = true (after set_edge): it may lie
+    // on the ragged m / n end of a k tile that is not the operand's last.  A block that starts
+    // inside is fetched where it is (what it reads past the end of its k line is the next k line:
+    // valid memory, and its products only reach outputs that are never stored); a block that
+    // starts outside fetches the tile's first block instead.  No predicate, so the load can sit
+    // between MFMAs.
+    template <bool CLAMP>
+    __device__ __forceinline__ void load_piece(const char *base, int p)
+    {
+        const uint32_t off = CLAMP ? vsel : voff0;
+#pragma unroll
+        for (int j = p; j < 8; j += NW) {
+            if constexpr (NW == 8) {
+                const u32x4 v = gload16(base + j * step, off);
+                r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
+            } else {
+                const u32x2 v = gload8(base + j * step, off);
+                r[j][0] = v[0]; r[j][1] = v[1];
+            }
+        }
+        shift = -1;
+    }
     template <bool MASKED = EDGE>
     __device__ __forceinline__ void load(const char *base, int64_t rows_left, int64_t k_left)
     {
+        if constexpr (!MASKED) {
+#pragma unroll
+            for (int p = 0; p < NW; ++p) load_piece<false>(base, p);
+            return;
+        }
         const int rl = (int)(rows_left < ROWS ? rows_left : ROWS) - rb * NW;     // valid rows of this block
         const int kl = (int)(k_left < kBK ? k_left : kBK) - kb * 8;              // valid k lines of this block
         const int sh = (rl > 0 && rl < NW) ? NW - rl : 0;
@@ -195,15 +253,15 @@ struct StageMN {
         for (int j = 0; j < 8; ++j) {
             if constexpr (!MASKED) {
                 if constexpr (NW == 8) {
-                    const u32x4 v = gload16(base, voff[j]);
+                    const u32x4 v = gload16(base + j * step, voff0);
                     r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
                 } else {
-                    const u32x2 v = gload8(base, voff[j]);
+                    const u32x2 v = gload8(base + j * step, voff0);
                     r[j][0] = v[0]; r[j][1] = v[1];
                 }
             } else {
                 const bool any = j < kl && rl > 0;
-                const char *p = base + ((int64_t)voff[j] - 2 * sh);
+                const char *p = base + j * step + ((int64_t)voff0 - 2 * sh);
                 if constexpr (NW == 8) {
                     u32x4 v{0, 0, 0, 0};
                     if (any) __builtin_memcpy(&v, p, 16);
@@ -578,10 +636,17 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
     const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kBK : (int64_t)kBK * g.ldb) * 2;
     const int64_t m_left = g.M - row0, n_left = g.N - col0;
 
-    typename StageSel<BM, ALAY, true>::type sa;
-    typename StageSel<BN, BLAY, true>::type sb;
-    sa.init(tid, g.lda);
-    sb.init(tid, g.ldb);
+    // two sets of staging registers: a tile is requested two trips before it is multiplied
+    typename StageSel<BM, ALAY, true>::type sa0, sa1;
+    typename StageSel<BN, BLAY, true>::type sb0, sb1;
+    sa0.init(tid, g.lda);
+    sb0.init(tid, g.ldb);
+    sa1.init(tid, g.lda);
+    sb1.init(tid, g.ldb);
+    sa0.set_edge(m_left, g.lda);
+    sb0.set_edge(n_left, g.ldb);
+    sa1.set_edge(m_left, g.lda);
+    sb1.set_edge(n_left, g.ldb);
 
     // per-lane LDS read bases: row (wave origin + l32) of each operand, chunk hi, swizzled
     const int ra = wave_m * (BM / 2) + l32, rb = wave_n * (BN / 2) + l32;
@@ -596,79 +661,129 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    // per-k-step fragment fetch from the copy at byte offset `copy_a` / `copy_b`
-    auto step = [&](int ks, uint32_t copy_a, uint32_t copy_b) {
-        u32x4 fa[TM], fb[TN];
-#pragma unroll
-        for (int t = 0; t < TM; ++t)
-            fa[t] = lds_read16(smem, (a_rd ^ (uint32_t)(((2 * ks) ^ ((t & 1) << 2)) << 4)) + t * 4096 + copy_a);
-#pragma unroll
-        for (int t = 0; t < TN; ++t)
-            fb[t] = lds_read16(smem, (b_rd ^ (uint32_t)(((2 * ks) ^ ((t & 1) << 2)) << 4)) + t * 4096 + copy_b);
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma32<BF16>(fb[tn], fa[tm], acc[tm][tn]);   // transposed block
+    // MFMA operand fragments, double buffered: [slot][32-row block]
+    u32x4 fa[2][TM], fb[2][TN];
+    constexpr int NM = TM * TN, NR = TM + TN;
+    // LDS read r of k step ks of LDS copy `copy`, in the order the MFMAs need the data:
+    // A block 0, every B block, then the remaining A blocks
+    auto frag_read = [&](int r, int slot, int ks, uint32_t copy) {
+        const int t = r == 0 ? 0 : (r <= TN ? r - 1 : r - TN);
+        const uint32_t kx = (uint32_t)(((2 * ks) ^ ((t & 1) << 2)) << 4);
+        if (r == 0 || r > TN) fa[slot][t] = lds_read16(smem, (a_rd ^ kx) + t * 4096 + copy * A_BYTES);
+        else fb[slot][t] = lds_read16(smem, (b_rd ^ kx) + t * 4096 + copy * B_BYTES);
     };
-
-    // ---- prologue: tile 0 -> LDS copy 0
-    sa.load(gA, m_left, g.K);
-    sb.load(gB, n_left, g.K);
-    sa.settle();
-    sb.settle();
-    sa.store(smem, 0);
-    sb.store(smem, B_BASE);
-    __syncthreads();
-
-    // One k tile per trip: the next tile (clamped to the last one; the surplus copy is never
-    // read) is fetched into the staging registers before the current LDS copy is multiplied,
-    // and written to the idle copy afterwards.
-    const int64_t last = g.kt - 1;
-    uint32_t cur = 0;
-    auto trip = [&](auto masked, int64_t k) {
-        const uint32_t nxt = cur ^ 1u;
-        const int64_t kn = k < last ? k + 1 : last;
-        sa.template load<decltype(masked)::value>(gA + kn * a_step, m_left, g.K - kn * kBK);
-        sb.template load<decltype(masked)::value>(gB + kn * b_step, n_left, g.K - kn * kBK);
-        __builtin_amdgcn_sched_barrier(0);           // the loads stay ahead of the multiplications that hide their latency
+    // One k step: the MFMAs on fragment slot `slot`.  Between them, one at a time: the LDS reads of
+    // the next k step's fragments (k step ks_next of copy rcopy, into the other slot) and, if
+    // `moving`, the pieces of the tile held in staging set (ha, hb) on their way to LDS copy wcopy.
+    // `fetch` (callable or nullptr): called with the MFMA's number after every MFMA, to issue its
+    // share of a block's global loads.
+    auto kstep = [&](int slot, int ks_next, uint32_t rcopy, auto moving, auto &ha, auto &hb, uint32_t wcopy, auto fetch) {
+        constexpr int PA = std::remove_reference_t<decltype(ha)>::PIECES, PB = std::remove_reference_t<decltype(hb)>::PIECES;
+        constexpr int PER = (PA + PB + NM - 1) / NM;          // pieces after each MFMA
+        constexpr int RQ = (NR + NM - 1) / NM;                // reads after each MFMA, if one per MFMA is not enough
+        constexpr int GAP = NM / NR > 0 ? NM / NR : 1;        // otherwise one read after every GAP MFMAs
 #pragma unroll
-        for (int ks = 0; ks < kBK / 16 - 1; ++ks) step(ks, cur * A_BYTES, cur * B_BYTES);
-        __builtin_amdgcn_sched_barrier(0);
-        sa.settle();
-        sb.settle();
-        // last k step: the fetched tile goes to the idle LDS copy piece by piece between the MFMAs
-        {
-            constexpr int ks = kBK / 16 - 1;
-            constexpr int PA = decltype(sa)::PIECES, PB = decltype(sb)::PIECES, NM = TM * TN;
-            constexpr int PER = (PA + PB + NM - 1) / NM;      // pieces after each MFMA
-            u32x4 fa[TM], fb[TN];
+        for (int idx = 0; idx < NM; ++idx) {
+            acc[idx / TN][idx % TN] = mfma32<BF16>(fb[slot][idx % TN], fa[slot][idx / TN], acc[idx / TN][idx % TN]);   // transposed block
+            if (idx % GAP == 0)
 #pragma unroll
-            for (int t = 0; t < TM; ++t)
-                fa[t] = lds_read16(smem, (a_rd ^ (uint32_t)(((2 * ks) ^ ((t & 1) << 2)) << 4)) + t * 4096 + cur * A_BYTES);
-#pragma unroll
-            for (int t = 0; t < TN; ++t)
-                fb[t] = lds_read16(smem, (b_rd ^ (uint32_t)(((2 * ks) ^ ((t & 1) << 2)) << 4)) + t * 4096 + cur * B_BYTES);
-#pragma unroll
-            for (int idx = 0; idx < NM; ++idx) {
-                acc[idx / TN][idx % TN] = mfma32<BF16>(fb[idx % TN], fa[idx / TN], acc[idx / TN][idx % TN]);
+                for (int q = 0; q < RQ; ++q)
+                    if ((idx / GAP) * RQ + q < NR) frag_read((idx / GAP) * RQ + q, slot ^ 1, ks_next, rcopy);
+            if constexpr (decltype(moving)::value) {
 #pragma unroll
                 for (int q = 0; q < PER; ++q) {
                     const int piece = idx * PER + q;
-                    if (piece < PA) sa.store_piece(smem, nxt * A_BYTES, piece);
-                    else if (piece < PA + PB) sb.store_piece(smem, B_BASE + nxt * B_BYTES, piece - PA);
+                    if (piece < PA) ha.store_piece(smem, wcopy * A_BYTES, piece);
+                    else if (piece < PA + PB) hb.store_piece(smem, B_BASE + wcopy * B_BYTES, piece - PA);
                 }
-                __builtin_amdgcn_sched_barrier(0);
             }
+            if constexpr (!std::is_same_v<decltype(fetch), std::nullptr_t>) fetch(idx);
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+
+    // ---- prologue: tile 0 -> LDS copy 0 (through set 0), tile 1 requested into set 1
+    const int64_t last = g.kt - 1;
+    sa0.load(gA, m_left, g.K);
+    sb0.load(gB, n_left, g.K);
+    if (last > 1) {                                  // tile 1 is not the last: its 64 k lie inside the operands
+#pragma unroll
+        for (int i = 0; i < decltype(sa1)::PIECES; ++i) sa1.template load_piece<true>(gA + a_step, i);
+#pragma unroll
+        for (int i = 0; i < decltype(sb1)::PIECES; ++i) sb1.template load_piece<true>(gB + b_step, i);
+    } else {
+        sa1.load(gA + last * a_step, m_left, g.K - last * kBK);
+        sb1.load(gB + last * b_step, n_left, g.K - last * kBK);
+    }
+    sa0.settle();
+    sb0.settle();
+    sa0.store(smem, 0);
+    sb0.store(smem, B_BASE);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < NR; ++r) frag_read(r, 0, 0, 0);
+
+    // One k tile (four k steps) per trip.  Trip k multiplies LDS copy k % 2 (tile k).  It requests
+    // tile k + 2 (clamped to the last one; surplus copies are never read) into the staging set
+    // that trip k - 1 emptied (fa_set / fb_set), before the multiplications: memory latency (about
+    // 2 us under load) exceeds one trip.  Tile k + 1, requested a trip earlier into the other set
+    // (ha / hb), moves to the idle LDS copy during k step 2; after the barrier that publishes it,
+    // k step 3 already reads its first fragments.
+    uint32_t cur = 0;
+    // mode 0: the requested tile lies inside both operands (plain loads); 1: its 64 k do, its rows
+    // may not (clamped loads); 2: anything (predicated loads that zero what lies outside, and a
+    // fix-up of the vectors that straddle a ragged end).
+    auto trip = [&](auto mode_tag, auto &fa_set, auto &fb_set, auto &ha, auto &hb, int64_t k) {
+        constexpr int mode = decltype(mode_tag)::value;
+        const uint32_t nxt = cur ^ 1u;
+        const int64_t kn = k + 2 < last ? k + 2 : last;
+        const char *pa = gA + kn * a_step, *pb = gB + kn * b_step;
+        if constexpr (mode == 2) {
+            fa_set.template load<true>(pa, m_left, g.K - kn * kBK);
+            fb_set.template load<true>(pb, n_left, g.K - kn * kBK);
+            __builtin_amdgcn_sched_barrier(0);       // the loads stay ahead of the multiplications that hide their latency
+            kstep(0, 1, cur, std::false_type{}, ha, hb, nxt, nullptr);
+            kstep(1, 2, cur, std::false_type{}, ha, hb, nxt, nullptr);
+        } else {
+            // requests without predicates go out one at a time between the MFMAs of k steps 0 and 1
+            constexpr int PA = std::remove_reference_t<decltype(fa_set)>::PIECES, PB = std::remove_reference_t<decltype(fb_set)>::PIECES;
+            kstep(0, 1, cur, std::false_type{}, ha, hb, nxt, [&](int idx) {
+#pragma unroll
+                for (int i = idx * PA / NM; i < (idx + 1) * PA / NM; ++i) fa_set.template load_piece<mode == 1>(pa, i);
+            });
+            kstep(1, 2, cur, std::false_type{}, ha, hb, nxt, [&](int idx) {
+#pragma unroll
+                for (int i = idx * PB / NM; i < (idx + 1) * PB / NM; ++i) fb_set.template load_piece<mode == 1>(pb, i);
+            });
+        }
+        if constexpr (mode == 2) {                   // (trips in modes 0 and 1 only ever hold tiles requested without predicates)
+            ha.settle();
+            hb.settle();
+        }
+        kstep(0, 3, cur, std::true_type{}, ha, hb, nxt, nullptr);
         __syncthreads();
+        kstep(1, 0, nxt, std::false_type{}, ha, hb, nxt, nullptr);
         cur = nxt;
     };
-    // Programs whose tile lies inside C fetch every k tile but the last with plain loads
-    // (trip k fetches tile k + 1); the rest, and programs on the ragged edge, mask.
+    // Programs whose tile lies inside C request every k tile but the last with plain loads (trip k
+    // requests tile k + 2); the rest, and programs on the ragged edge, mask.  (Clamped requests in
+    // the loop of the edge programs would spare them the predicates, but that loop then needs more
+    // registers than there are.)  Trips come in pairs so that the roles of the two staging sets
+    // are fixed at compile time.
     int64_t k = 0;
+    typedef std::integral_constant<int, 0> Plain;
+    typedef std::integral_constant<int, 2> Masked;
     if (m_left >= BM && n_left >= BN)
-        for (; k < g.kt - 2; ++k) trip(std::false_type{}, k);
-    for (; k < g.kt; ++k) trip(std::true_type{}, k);
+        for (; k + 1 <= g.kt - 4; k += 2) {
+            trip(Plain{}, sa0, sb0, sa1, sb1, k);
+            trip(Plain{}, sa1, sb1, sa0, sb0, k + 1);
+        }
+    for (; k + 1 < g.kt; k += 2) {
+        trip(Masked{}, sa0, sb0, sa1, sb1, k);
+        trip(Masked{}, sa1, sb1, sa0, sb0, k + 1);
+    }
+    if (k < g.kt) trip(Masked{}, sa0, sb0, sa1, sb1, k);
+    __syncthreads();                                 // every wavefront is done with the LDS copies: the epilogue reuses them
 
     // ---- epilogue: convert and store (masked on ragged tiles)
     store_tile<BM, BN, true>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane, m_left < BM || n_left < BN);
