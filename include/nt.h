@@ -174,6 +174,37 @@ nt_status nt_addmm(const void *input, const nt_tensor_desc *dI, const void *A, c
                    float alpha, float beta, nt_dtype in_dtype, nt_dtype out_dtype,
                    nt_tile_cfg cfg, void *hip_stream);
 
+/* ------------------------------------------------------------------ memory-bound kernels (device)
+ *
+ * The element-wise and row-wise kernels of the paper's task list (Section 5.1).  x, y, out are device
+ * pointers to 16-bit elements of `dtype` (NT_F16 or NT_BF16, the same for inputs and output);
+ * descriptors are host structs, strides in elements, any strides accepted (unit strides take the
+ * vector path).  Arithmetic is fp32 with one round-to-nearest-even conversion of the result.
+ * `out` may alias an input only with an identical descriptor.  Empty tensors: nothing is launched.
+ *
+ * nt_add: out[i] = x[i] + y[i] over 1-D tensors of equal size -- vector addition as arranged in
+ * Section 4.1: each vector tiled into blocks (`tile((BLOCK_SIZE,))`), application
+ * `output = input + other`.  block_size is that meta-parameter (0 = 1024, the paper's value; it
+ * must be positive otherwise); the result does not depend on it (nt_arrange_tile with one TILE
+ * operation gives the blocks' index sets).  Sizes that differ: NT_ERR_SHAPE_MISMATCH.
+ */
+nt_status nt_add(const void *x, const nt_tensor_desc *dx, const void *y, const nt_tensor_desc *dy,
+                 void *out, const nt_tensor_desc *dout, nt_dtype dtype, int64_t block_size, void *hip_stream);
+
+/* nt_silu: out[i] = x[i] / (1 + exp(-x[i])), arranged like nt_add. */
+nt_status nt_silu(const void *x, const nt_tensor_desc *dx, void *out, const nt_tensor_desc *dout,
+                  nt_dtype dtype, int64_t block_size, void *hip_stream);
+
+/* nt_softmax: softmax along the last axis of a 2-D tensor [rows, cols]; each row is one program
+ * (`tile((1, -1))`): out[r, c] = exp(x[r, c] - max_c x[r, :]) / sum_c exp(x[r, c] - max_c x[r, :]). */
+nt_status nt_softmax(const void *x, const nt_tensor_desc *dx, void *out, const nt_tensor_desc *dout,
+                     nt_dtype dtype, void *hip_stream);
+
+/* nt_rms_norm: out[r, c] = x[r, c] / sqrt(mean_c x[r, :]^2 + eps) along the last axis of a 2-D tensor,
+ * without a weight (the task takes one tensor), rows arranged as in nt_softmax.  eps >= 0. */
+nt_status nt_rms_norm(const void *x, const nt_tensor_desc *dx, void *out, const nt_tensor_desc *dout,
+                      float eps, nt_dtype dtype, void *hip_stream);
+
 /* nt_bmm: the same per batch index; descriptors have ndim 3: [batch,M,K], [batch,K,N], [batch,M,N]
  * (listed among the paper's kernels in Section 5.1). */
 nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,

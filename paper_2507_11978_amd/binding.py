@@ -68,9 +68,14 @@ def load():
     L.nt_bmm.argtypes = [P, D, P, D, P, D, i32, i32, TileCfg, P]
     L.nt_addmm.argtypes = [P, D, P, D, P, D, P, D, C.c_float, C.c_float, i32, i32, TileCfg, P]
     L.nt_conv2d_implicit.argtypes = [P, D, P, D, P, D, i32, i32, i32, i32, i32, i32, TileCfg, P]
+    L.nt_add.argtypes = [P, D, P, D, P, D, i32, i64, P]
+    L.nt_silu.argtypes = [P, D, P, D, i32, i64, P]
+    L.nt_softmax.argtypes = [P, D, P, D, i32, P]
+    L.nt_rms_norm.argtypes = [P, D, P, D, C.c_float, i32, P]
     L.nt_trace_tile.argtypes = [i32, D, D, D, i32, i32, i32, i32, TileCfg, i32, i64, i64, P, P, C.c_size_t, P]
     for name in ("nt_arrange_levels", "nt_arrange_tile", "nt_arrange_gemm", "nt_arrange_bmm", "nt_arrange_conv2d",
-                 "nt_program_order", "nt_gemm", "nt_addmm", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile"):
+                 "nt_program_order", "nt_gemm", "nt_addmm", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile",
+                 "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm"):
         getattr(L, name).restype = i32
     L.nt_last_error.restype = C.c_char_p
     L.nt_version.restype = C.c_char_p
@@ -272,6 +277,37 @@ def addmm(inp, A, B, Cout, alpha=1.0, beta=1.0, tile=None, stream=None):
                            float(alpha), float(beta), _DTYPES[_torch_dtype_name(A)],
                            _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
     return Cout
+
+
+def add(x, y, out, block_size=0, stream=None):
+    """out = x + y over 1-D tensors (16-bit floating point, any stride)."""
+    _require_cuda(x, y, out)
+    _check(load().nt_add(x.data_ptr(), C.byref(_desc_of(x)), y.data_ptr(), C.byref(_desc_of(y)), out.data_ptr(),
+                         C.byref(_desc_of(out)), _DTYPES[_torch_dtype_name(x)], int(block_size), _stream_ptr(stream)))
+    return out
+
+
+def silu(x, out, block_size=0, stream=None):
+    _require_cuda(x, out)
+    _check(load().nt_silu(x.data_ptr(), C.byref(_desc_of(x)), out.data_ptr(), C.byref(_desc_of(out)),
+                          _DTYPES[_torch_dtype_name(x)], int(block_size), _stream_ptr(stream)))
+    return out
+
+
+def softmax(x, out, stream=None):
+    """Row-wise softmax of a 2-D tensor."""
+    _require_cuda(x, out)
+    _check(load().nt_softmax(x.data_ptr(), C.byref(_desc_of(x)), out.data_ptr(), C.byref(_desc_of(out)),
+                             _DTYPES[_torch_dtype_name(x)], _stream_ptr(stream)))
+    return out
+
+
+def rms_norm(x, out, eps=1e-6, stream=None):
+    """Row-wise x / sqrt(mean(x^2) + eps) of a 2-D tensor (no weight)."""
+    _require_cuda(x, out)
+    _check(load().nt_rms_norm(x.data_ptr(), C.byref(_desc_of(x)), out.data_ptr(), C.byref(_desc_of(out)),
+                              float(eps), _DTYPES[_torch_dtype_name(x)], _stream_ptr(stream)))
+    return out
 
 
 def bmm(A, B, Cout, tile=None, stream=None):

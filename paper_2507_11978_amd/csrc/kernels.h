@@ -39,6 +39,12 @@ nt_status launch_fill_zero(void *C, const OperandMap &mc, int64_t batch, int64_t
 nt_status launch_trace(const OperandMap &m, int64_t batch_off, int64_t row0, int64_t col0, int32_t rows, int32_t cols,
                        int64_t *offsets_out, uint8_t *mask_out, void *stream);
 
+// memory-bound kernels: op 0 = add (x + y), 1 = silu (y unused); strides in elements
+nt_status launch_map(int op, const void *x, int64_t sx, const void *y, int64_t sy, void *out, int64_t so, int64_t n, int dtype, void *stream);
+// row-wise kernels: op 0 = softmax, 1 = rms_norm (eps used)
+nt_status launch_rows(int op, const void *x, int64_t sxr, int64_t sxc, void *out, int64_t sor, int64_t soc, int64_t rows, int64_t cols,
+                      float eps, int dtype, void *stream);
+
 // workgroup index -> logical program id (shared by host query and device code)
 NT_HD int64_t program_of_workgroup(int64_t w, int64_t mt, int64_t nt)
 {

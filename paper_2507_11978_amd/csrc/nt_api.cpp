@@ -262,6 +262,66 @@ nt_status nt_addmm(const void *input, const nt_tensor_desc *dI, const void *A, c
     return run(KIND_GEMM, A, dA, B, dB, C, dC, 1, 1, 0, 0, in_dtype, out_dtype, cfg, hip_stream, input, dI, alpha, beta);
 }
 
+static nt_status check_1d(const nt_tensor_desc *d, const void *p, int64_t *n, int64_t *stride)
+{
+    if (!d) return fail(NT_ERR_INVALID_ARG, "null tensor descriptor");
+    if (d->ndim != 1) return fail(NT_ERR_SHAPE_MISMATCH, "tensor must be 1-D");
+    if (d->size[0] < 0) return fail(NT_ERR_INVALID_ARG, "negative size");
+    if (d->size[0] > 0 && !p) return fail(NT_ERR_INVALID_ARG, "null device pointer");
+    *n = d->size[0];
+    *stride = d->stride[0];
+    return NT_OK;
+}
+
+static nt_status map_op(int op, const void *x, const nt_tensor_desc *dx, const void *y, const nt_tensor_desc *dy,
+                        void *out, const nt_tensor_desc *dout, nt_dtype dtype, int64_t block_size, void *stream)
+{
+    if (!dtype_in_ok(dtype)) return fail(NT_ERR_UNSUPPORTED, "dtype must be NT_F16 or NT_BF16");
+    if (block_size < 0) return fail(NT_ERR_INVALID_ARG, "block_size must be positive (0 = default)");
+    int64_t n, sx, ny = 0, sy = 0, no, so;
+    NT_TRY(check_1d(dx, x, &n, &sx));
+    if (op == 0) NT_TRY(check_1d(dy, y, &ny, &sy));
+    NT_TRY(check_1d(dout, out, &no, &so));
+    if (no != n || (op == 0 && ny != n)) return fail(NT_ERR_SHAPE_MISMATCH, "tensor sizes differ");
+    return nt::launch_map(op, x, sx, y, sy, out, so, n, dtype, stream);
+}
+
+static nt_status rows_op(int op, const void *x, const nt_tensor_desc *dx, void *out, const nt_tensor_desc *dout,
+                         float eps, nt_dtype dtype, void *stream)
+{
+    if (!dtype_in_ok(dtype)) return fail(NT_ERR_UNSUPPORTED, "dtype must be NT_F16 or NT_BF16");
+    if (!dx || !dout) return fail(NT_ERR_INVALID_ARG, "null tensor descriptor");
+    if (dx->ndim != 2 || dout->ndim != 2) return fail(NT_ERR_SHAPE_MISMATCH, "tensors must be 2-D");
+    if (dx->size[0] < 0 || dx->size[1] < 0) return fail(NT_ERR_INVALID_ARG, "negative size");
+    if (dx->size[0] != dout->size[0] || dx->size[1] != dout->size[1]) return fail(NT_ERR_SHAPE_MISMATCH, "input and output shapes differ");
+    if (!(eps >= 0.f)) return fail(NT_ERR_INVALID_ARG, "eps must be >= 0");
+    if (dx->size[0] > 0 && dx->size[1] > 0 && (!x || !out)) return fail(NT_ERR_INVALID_ARG, "null device pointer");
+    return nt::launch_rows(op, x, dx->stride[0], dx->stride[1], out, dout->stride[0], dout->stride[1], dx->size[0], dx->size[1], eps, dtype, stream);
+}
+
+nt_status nt_add(const void *x, const nt_tensor_desc *dx, const void *y, const nt_tensor_desc *dy,
+                 void *out, const nt_tensor_desc *dout, nt_dtype dtype, int64_t block_size, void *hip_stream)
+{
+    return map_op(0, x, dx, y, dy, out, dout, dtype, block_size, hip_stream);
+}
+
+nt_status nt_silu(const void *x, const nt_tensor_desc *dx, void *out, const nt_tensor_desc *dout,
+                  nt_dtype dtype, int64_t block_size, void *hip_stream)
+{
+    return map_op(1, x, dx, nullptr, nullptr, out, dout, dtype, block_size, hip_stream);
+}
+
+nt_status nt_softmax(const void *x, const nt_tensor_desc *dx, void *out, const nt_tensor_desc *dout, nt_dtype dtype, void *hip_stream)
+{
+    return rows_op(0, x, dx, out, dout, 0.f, dtype, hip_stream);
+}
+
+nt_status nt_rms_norm(const void *x, const nt_tensor_desc *dx, void *out, const nt_tensor_desc *dout,
+                      float eps, nt_dtype dtype, void *hip_stream)
+{
+    return rows_op(1, x, dx, out, dout, eps, dtype, hip_stream);
+}
+
 nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
                  void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
                  nt_tile_cfg cfg, void *hip_stream)
