@@ -37,7 +37,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="p_f16_8192",
-                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c1_f16_256, f1_f16_addmm")
+                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c1_f16_256, f1_f16_addmm, f3_f16_add, f3_f16_silu, f3_f16_softmax, f3_f16_rms_norm")
     ap.add_argument("--tile", default=None, help="bm,bn,bk (default: library choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -58,6 +58,92 @@ def flops_and_bytes(cfg):
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
     extra = osz * M * N if cfg["kind"] == "addmm" else 0            # the added input is read once
     return 2.0 * b * M * N * K, b * (2 * (M * K + K * N) + osz * M * N) + extra
+
+
+def bench_memory_bound(args, cfg):
+    """The memory-bound kernels (add, silu, softmax, rms_norm): value and roofline in GB/s of
+    algorithmic HBM traffic (every input read once, the output written once)."""
+    import numpy as np
+    import torch
+    import paper_2507_11978_amd as nt
+    import synthetic_inputs as si
+    from gpu_util import TORCH_DT, to_gpu
+    from oracle import elementwise as oe
+
+    dt, kind = cfg["dtype"], cfg["kind"]
+    if kind in ("add", "silu"):
+        n = cfg["n"]
+        xb = si.normal_bits((n,), dt, cfg["seed"], 2.0)
+        x = to_gpu(xb, dt)
+        out = torch.empty(n, dtype=TORCH_DT[dt], device="cuda")
+        if kind == "add":
+            yb = si.normal_bits((n,), dt, cfg["seed"] + 1, 2.0)
+            y = to_gpu(yb, dt)
+            step = lambda: nt.add(x, y, out)
+            ref_fn = lambda sl: oe.add(xb[sl], yb[sl], dt)
+            alg_bytes = 3 * 2 * n
+        else:
+            step = lambda: nt.silu(x, out)
+            ref_fn = lambda sl: oe.silu(xb[sl], dt)
+            alg_bytes = 2 * 2 * n
+        shape = {"n": n}
+        sample_sl, sample_desc = slice(0, 1 << 22), "elements 0..4194303"
+    else:
+        rows, cols = cfg["rows"], cfg["cols"]
+        xb = si.normal_bits((rows, cols), dt, cfg["seed"], 2.0)
+        x = to_gpu(xb, dt)
+        out = torch.empty((rows, cols), dtype=TORCH_DT[dt], device="cuda")
+        if kind == "softmax":
+            step = lambda: nt.softmax(x, out)
+            ref_fn = lambda sl: oe.softmax(xb[sl], dt)
+        else:
+            step = lambda: nt.rms_norm(x, out, eps=cfg["eps"])
+            ref_fn = lambda sl: oe.rms_norm(xb[sl], dt, cfg["eps"])
+        alg_bytes = 2 * 2 * rows * cols
+        shape = {"rows": rows, "cols": cols}
+        sample_sl, sample_desc = slice(0, 1024), "rows 0..1023"
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record()
+        step()
+        ends[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, ends)])
+    ms_per_step = wall * 1e3 / args.steps
+    kern_avg = float(kern_ms.mean())
+    achieved = alg_bytes / (kern_avg * 1e-3) / 1e9
+    result = {
+        "metric": f"{kind}: GB/s of algorithmic HBM traffic, 1 GPU", "value": round(alg_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
+        "config": {"workload": args.workload, "shape": shape, "in_dtype": dt, "out_dtype": dt, "arithmetic": "f32"},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "kernel_ms_avg": round(kern_avg, 4),
+                     "kernel_ms_min": round(float(kern_ms.min()), 4), "kernel_ms_median": round(float(np.median(kern_ms)), 4),
+                     "algorithmic_bytes": int(alg_bytes)},
+    }
+    if not args.no_check:
+        got = oe.decode(out[sample_sl].contiguous().view(torch.int16).cpu().numpy().view(np.uint16), dt)
+        ref = ref_fn(sample_sl)
+        result["parity"] = {"sample": sample_desc, "max_abs_err": float(np.abs(got - ref).max()),
+                            "max_err_in_output_ulps": float((np.abs(got - ref) / (np.abs(ref) * 2.0 ** (-10 if dt == "f16" else -7) + 2.0 ** -24)).max())}
+    if not args.no_cpu_baseline:
+        t1 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t1 < 10.0:
+            ref_fn(sample_sl)
+            reps += 1
+        dt_cpu = (time.perf_counter() - t1) / reps
+        frac = (sample_sl.stop - sample_sl.start) / (cfg["n"] if kind in ("add", "silu") else cfg["rows"])
+        result["cpu_baseline"] = {"value": round(alg_bytes * frac / dt_cpu / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "seconds": round(dt_cpu * reps, 2), "sample": f"{sample_desc}, repeated {reps} times (numpy fp64)"}
+    print(json.dumps(result), flush=True)
 
 
 def main():
@@ -87,6 +173,8 @@ def main():
         return
     nt.load()
     cfg = si.CONFIGS[args.workload]
+    if cfg["kind"] in ("add", "silu", "softmax", "rms_norm"):
+        return bench_memory_bound(args, cfg)
     tile = tuple(int(x) for x in args.tile.split(",")) if args.tile else cfg.get("tile")
     dt, out = cfg["dtype"], cfg["out"]
 

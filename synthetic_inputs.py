@@ -85,6 +85,10 @@ CONFIGS = {
     "c4_f16_bmm": dict(kind="bmm", batch=32, M=2048, N=2048, K=512, dtype="f16", out="f16", dist="normal", seed=0),
     "p_f16_8192": dict(kind="gemm", M=8192, N=8192, K=8192, dtype="f16", out="f16", dist="normal", seed=0),
     "f1_f16_addmm": dict(kind="addmm", M=4096, N=4096, K=4096, dtype="f16", out="f16", dist="normal", seed=0, alpha=1.0, beta=1.0),
+    "f3_f16_add": dict(kind="add", n=16777216, dtype="f16", out="f16", seed=0),
+    "f3_f16_silu": dict(kind="silu", n=16777216, dtype="f16", out="f16", seed=0),
+    "f3_f16_softmax": dict(kind="softmax", rows=4096, cols=4096, dtype="f16", out="f16", seed=0),
+    "f3_f16_rms_norm": dict(kind="rms_norm", rows=4096, cols=4096, dtype="f16", out="f16", seed=0, eps=1e-6),
     "c5_f16_conv": dict(kind="conv", N=32, C=256, H=56, W=56, K=256, R=3, S=3, stride=1, pad=1,
                         dtype="f16", out="f16", seed=0),
 }
