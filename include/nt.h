@@ -144,6 +144,11 @@ nt_status nt_arrange_conv2d(const nt_tensor_desc *dx, const nt_tensor_desc *dw, 
  */
 nt_status nt_program_order(int64_t batch, int64_t mt, int64_t nt, int64_t *pid_out);
 
+/* Which kernel the calling thread's last nt_gemm / nt_addmm / nt_bmm / nt_conv2d_implicit call launched:
+ * 0 operand-map (generic) kernel, 1 staged kernel, 2 direct-to-LDS kernel, 3 convolution kernel,
+ * -1 none (nothing launched yet, an error, or an empty problem).  For tests and diagnostics. */
+int32_t nt_last_kernel_path(void);
+
 /* 1 if kernels for this (bm, bn, bk) are built, else 0.  (0,0,0) is always supported. */
 int32_t nt_tile_supported(nt_tile_cfg cfg);
 

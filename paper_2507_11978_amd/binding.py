@@ -77,6 +77,7 @@ def load():
                  "nt_program_order", "nt_gemm", "nt_addmm", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile",
                  "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm"):
         getattr(L, name).restype = i32
+    L.nt_last_kernel_path.restype = i32
     L.nt_last_error.restype = C.c_char_p
     L.nt_version.restype = C.c_char_p
     _lib = L
@@ -260,6 +261,14 @@ def gemm(A, B, Cout, tile=None, stream=None):
                           Cout.data_ptr(), C.byref(_desc_of(Cout)), _DTYPES[_torch_dtype_name(A)],
                           _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
     return Cout
+
+
+PATH_GENERIC, PATH_STAGED, PATH_DIRECT, PATH_CONV = 0, 1, 2, 3
+
+
+def last_kernel_path() -> int:
+    """Kernel launched by this thread's last gemm / addmm / bmm / conv2d_implicit call (-1: none)."""
+    return int(load().nt_last_kernel_path())
 
 
 def addmm(inp, A, B, Cout, alpha=1.0, beta=1.0, tile=None, stream=None):

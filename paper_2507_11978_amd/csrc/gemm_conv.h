@@ -31,7 +31,8 @@ struct ConvArgs {
 };
 
 // floor(t / d) for 0 <= t < 2^16 with inv = floor(2^32 / d) + 1 (d >= 2), inv = 0 standing for d = 1
-__device__ __forceinline__ uint32_t udiv_small(uint32_t t, uint32_t inv) { return inv ? __umulhi(t, inv) : t; }
+// (no branch: the loaders that call this sit between MFMAs)
+__device__ __forceinline__ uint32_t udiv_small(uint32_t t, uint32_t inv) { return __umulhi(t, inv) + (t & (inv ? 0u : 0xffffffffu)); }
 
 // staging of the (256 x 64) block of the unfolded input
 struct StageConv {
@@ -41,6 +42,9 @@ struct StageConv {
     int32_t base;                  // element offset of x[n, 0, p - ph, q0 - pw]
     int32_t q0;
     uint32_t hmask;                // bit r: input row p + r - ph lies inside the image (and m < M)
+    uint32_t todo[2];              // what settle() has to do to each fetched line
+    uint32_t first_mask, last_mask;   // bit s: with filter column s this run's first / last element lies in the padding
+    int32_t l_rr, l_ss, l_off;     // filter row, column and input offset of the next line to fetch
     int32_t c, rs;                 // channel and r*S+s of this thread's first k line in the current k tile
 
     // first_tile: the k tile this set fetches first
@@ -48,6 +52,7 @@ struct StageConv {
     {
         kb = tid >> 5;
         rb = tid & 31;
+        todo[0] = todo[1] = 0;
         wbase = (uint32_t)(rb * 8 * 128 + ((kb ^ (rb & 7)) << 4));
         const int64_t m = row0 + rb * 8;
         const bool m_ok = m < g.M;
@@ -57,6 +62,13 @@ struct StageConv {
         const uint32_t p = pq / (uint32_t)g.Q;
         q0 = (int32_t)(pq - p * (uint32_t)g.Q);
         base = (int32_t)(nn * (uint32_t)g.CHW) + ((int32_t)p - g.ph) * g.W + q0 - g.pw;
+        first_mask = last_mask = 0;
+        for (int sx = 0; sx < g.S; ++sx) {
+            const int w0 = q0 + sx - g.pw;
+            if (w0 < 0) first_mask |= 1u << sx;
+            if (w0 + 7 >= g.W) last_mask |= 1u << sx;
+        }
+        l_rr = l_ss = l_off = 0;
         hmask = 0;
         for (int rr = 0; rr < g.R; ++rr) {
             const int h = (int)p + rr - g.ph;
@@ -68,33 +80,65 @@ struct StageConv {
     }
 
     // Line j (one (c, r, s) combination, 8 consecutive output positions) of the block of the k
-    // tile the state points at; k_left: valid k from the tile origin.
+    // tile the state points at; k_left: valid k from the tile origin.  The load itself is
+    // unconditional, from the run's position clamped into the tensor, and nothing here looks at
+    // the data, so that it can stay in flight; what has to happen to it -- zeroing a line that lies
+    // in the top / bottom padding or past K, clearing the one element in the left / right padding,
+    // moving a run that was clamped by one element back into place -- is noted in `todo` (8 bits per
+    // line) and done by settle().
+    enum { ZERO = 1, CLEAR_FIRST = 2, CLEAR_LAST = 4, MOVE_UP = 8, MOVE_DOWN = 16 };
+    // Lines are fetched in order j = 0 .. 7; (l_rr, l_ss, l_off) walk through the (r, s) taps and
+    // channels like an odometer, so only line 0 of a tile costs a division.
     __device__ __forceinline__ void load_line(const ConvArgs &g, int j, int64_t k_left)
     {
-        const uint16_t *X = g.X;
-        const uint32_t t = (uint32_t)(rs + j);
-        const uint32_t dq = udiv_small(t, g.inv_rs);          // t / RS
-        const int32_t cj = c + (int32_t)dq;
-        const uint32_t rsj = t - dq * (uint32_t)g.RS;
-        const uint32_t rr = udiv_small(rsj, g.inv_s);          // rsj / S
-        const int32_t ss = (int32_t)(rsj - rr * (uint32_t)g.S);
-        const bool ok = kb * 8 + j < k_left && ((hmask >> rr) & 1u);
-        const int64_t off = (int64_t)base + (int64_t)cj * g.HW + (int32_t)rr * g.W + ss;
-        const int32_t w0 = q0 + ss - g.pw;
-        u32x4 v{0, 0, 0, 0};
-        if (ok) {
-            if (off >= 0 && off + 8 <= g.x_numel) {
-                __builtin_memcpy(&v, X + off, 16);
-            } else {                                           // first / last run of the whole tensor
-                uint32_t e[8];
-#pragma unroll
-                for (int q = 0; q < 8; ++q) e[q] = (off + q >= 0 && off + q < g.x_numel) ? (uint32_t)X[off + q] : 0u;
-                v = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-            }
-            if (w0 < 0) v[0] &= 0xffff0000u;                   // q0 + s - pad = -1: left padding
-            if (w0 + 7 >= g.W) v[3] &= 0x0000ffffu;            // ... = W: right padding
+        if (j == 0) {
+            l_rr = (int32_t)udiv_small((uint32_t)rs, g.inv_s);
+            l_ss = rs - l_rr * g.S;
+            l_off = base + c * g.HW + l_rr * g.W + l_ss;       // (all below 2^31: checked at launch)
         }
+        const bool ok = kb * 8 + j < k_left && ((hmask >> l_rr) & 1u);
+        const int32_t hi_lim = (int32_t)g.x_numel - 8;
+        int32_t offc = l_off < 0 ? 0 : l_off;
+        offc = offc > hi_lim ? hi_lim : offc;
+        if (!ok) offc = 0;
+        uint32_t code = ok ? 0u : (uint32_t)ZERO;
+        code |= ((first_mask >> l_ss) & 1u) * CLEAR_FIRST;     // q0 + s - pad = -1: left padding
+        code |= ((last_mask >> l_ss) & 1u) * CLEAR_LAST;       // ... = W: right padding
+        if (ok && l_off < 0) code |= MOVE_UP;                  // fetched one element late (very first run of the tensor)
+        if (ok && l_off > hi_lim) code |= MOVE_DOWN;           // fetched one element early (very last run)
+        if ((j & 3) == 0) todo[j >> 2] = code;
+        else todo[j >> 2] |= code << (8 * (j & 3));
+        u32x4 v;
+        __builtin_memcpy(&v, g.X + offc, 16);
         r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
+        // next tap: s + 1, carrying into r and then into the channel
+        const bool row_done = l_ss + 1 == g.S;
+        l_ss = row_done ? 0 : l_ss + 1;
+        l_off += row_done ? g.W - g.S + 1 : 1;
+        l_rr += row_done ? 1 : 0;
+        const bool chan_done = l_rr == g.R;
+        l_rr = chan_done ? 0 : l_rr;
+        l_off += chan_done ? g.HW - g.R * g.W : 0;
+    }
+    __device__ __forceinline__ void settle()
+    {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t code = (todo[j >> 2] >> (8 * (j & 3))) & 0xffu;
+            uint32_t v0 = r[j][0], v1 = r[j][1], v2 = r[j][2], v3 = r[j][3];
+            if (code & MOVE_UP) {                              // element i <- element i - 1 (element 0 is cleared below)
+                v3 = __builtin_amdgcn_alignbit(v3, v2, 16); v2 = __builtin_amdgcn_alignbit(v2, v1, 16);
+                v1 = __builtin_amdgcn_alignbit(v1, v0, 16); v0 = v0 << 16;
+            }
+            if (code & MOVE_DOWN) {                            // element i <- element i + 1 (element 7 is cleared below)
+                v0 = __builtin_amdgcn_alignbit(v1, v0, 16); v1 = __builtin_amdgcn_alignbit(v2, v1, 16);
+                v2 = __builtin_amdgcn_alignbit(v3, v2, 16); v3 = v3 >> 16;
+            }
+            if (code & CLEAR_FIRST) v0 &= 0xffff0000u;
+            if (code & CLEAR_LAST) v3 &= 0x0000ffffu;
+            if (code & ZERO) { v0 = 0; v1 = 0; v2 = 0; v3 = 0; }
+            r[j][0] = v0; r[j][1] = v1; r[j][2] = v2; r[j][3] = v3;
+        }
     }
     // moves the state on by `tiles` k tiles (kk += 64 * tiles; tiles <= 2)
     __device__ __forceinline__ void advance(const ConvArgs &g, int tiles)
@@ -211,6 +255,7 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
     for (int j = 0; j < 8; ++j) sa1.load_line(g, j, (int64_t)g.K - kBK);
     sa1.advance(g, 2);
     sb1.template load<true>(gB + kBK * 2, n_left, (int64_t)g.K - kBK);
+    sa0.settle();
     sb0.settle();
     sa0.store(smem, 0);
     sb0.store(smem, B_BASE);
@@ -239,13 +284,15 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
             hb.settle();
         } else {
             constexpr int PB = std::remove_reference_t<decltype(fb_set)>::PIECES;
-            const bool inside = k_left >= kBK;                  // (K is a multiple of 64 here)
+            // (K is a multiple of 64 here: the tile exists or it does not; a request past the end is
+            // redirected to the first tile -- no branch -- and lands in a copy that is never read)
+            const char *pbc = k_left >= kBK ? pb : gB;
             kstep(1, 2, cur, std::false_type{}, ha, hb, nxt, [&](int idx) {
-                if (inside)
 #pragma unroll
-                    for (int i = idx * PB / NM; i < (idx + 1) * PB / NM; ++i) fb_set.template load_piece<false>(pb, i);
+                for (int i = idx * PB / NM; i < (idx + 1) * PB / NM; ++i) fb_set.template load_piece<false>(pbc, i);
             });
         }
+        ha.settle();
         kstep(0, 3, cur, std::true_type{}, ha, hb, nxt, nullptr);
         __syncthreads();
         kstep(1, 0, nxt, std::false_type{}, ha, hb, nxt, nullptr);
@@ -258,35 +305,53 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
     }
     if (k < g.kt) trip(sa0, sb0, sa1, sb1, k);
 
-    // epilogue: lane holds, per 32 x 32 block, 4 groups of 4 consecutive m for one filter f.
-    // 4 consecutive m (aligned to 4) lie in one image because P*Q is a multiple of 8.
-    const bool f16 = g.out_dtype == NT_F16;
+    // epilogue: a lane holds one filter f = lane % 32 of each 32 x 32 block; after the half-wavefronts
+    // have traded register groups (gather_row16) it owns 16 consecutive output positions m of it,
+    // stored as two runs of 8 (a run of 8 aligned to 8 lies in one image because P*Q is a multiple of 8)
+    // with 16-byte stores along the contiguous (p, q) axis of the output.
+    auto store_runs = [&](auto out_tag) {
+        constexpr int OUT = decltype(out_tag)::value;
+        constexpr int ES = OUT == NT_F32 ? 4 : 2;
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
+        for (int tm = 0; tm < TM; ++tm) {
+            int64_t o_run[2];
+            bool m_ok[2];
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-            const int64_t m = row0 + wave_m * (BM / 2) + tm * 32 + 8 * gq + 4 * hi;
-            if (m >= g.M) continue;
-            const uint32_t n = (uint32_t)m / (uint32_t)g.PQ;
-            const uint32_t pq = (uint32_t)m - n * (uint32_t)g.PQ;
+            for (int h2 = 0; h2 < 2; ++h2) {
+                const int64_t m = row0 + wave_m * (BM / 2) + tm * 32 + 16 * hi + 8 * h2;
+                m_ok[h2] = m < g.M;
+                const uint32_t mm = m_ok[h2] ? (uint32_t)m : 0u;
+                const uint32_t n = mm / (uint32_t)g.PQ;
+                o_run[h2] = (int64_t)n * g.syn + (int64_t)(mm - n * (uint32_t)g.PQ);
+            }
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
+                uint32_t o[16];
+                gather_row16(acc[tm][tn], o);                      // (all lanes take part)
                 const int64_t f = col0 + wave_n * (BN / 2) + tn * 32 + l32;
-                if (f >= g.N) continue;
-                const int64_t o = (int64_t)n * g.syn + f * g.syf + pq;
-                if (g.out_dtype == NT_F32) {
-                    float *y = reinterpret_cast<float *>(g.Y) + o;
+                if (f < g.N) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) y[i] = acc[tm][tn][4 * gq + i];
-                } else {
-                    uint16_t h[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) h[i] = f16 ? f32_to_f16_rne(acc[tm][tn][4 * gq + i]) : f32_to_bf16_rne(acc[tm][tn][4 * gq + i]);
-                    const u32x2 v{h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16)};
-                    __builtin_memcpy(reinterpret_cast<uint16_t *>(g.Y) + o, &v, 8);
+                    for (int h2 = 0; h2 < 2; ++h2) {
+                        if (!m_ok[h2]) continue;
+                        char *y = reinterpret_cast<char *>(g.Y) + (o_run[h2] + f * g.syf) * ES;
+                        if constexpr (OUT == NT_F32) {
+                            const u32x4 v0{o[8 * h2], o[8 * h2 + 1], o[8 * h2 + 2], o[8 * h2 + 3]};
+                            const u32x4 v1{o[8 * h2 + 4], o[8 * h2 + 5], o[8 * h2 + 6], o[8 * h2 + 7]};
+                            __builtin_memcpy(y, &v0, 16);
+                            __builtin_memcpy(y + 16, &v1, 16);
+                        } else {
+                            const u32x4 v{pack_pair<OUT>(o[8 * h2], o[8 * h2 + 1]), pack_pair<OUT>(o[8 * h2 + 2], o[8 * h2 + 3]),
+                                          pack_pair<OUT>(o[8 * h2 + 4], o[8 * h2 + 5]), pack_pair<OUT>(o[8 * h2 + 6], o[8 * h2 + 7])};
+                            __builtin_memcpy(y, &v, 16);
+                        }
+                    }
                 }
             }
         }
+    };
+    if (g.out_dtype == NT_F32) store_runs(std::integral_constant<int, NT_F32>{});
+    else if (g.out_dtype == NT_F16) store_runs(std::integral_constant<int, NT_F16>{});
+    else store_runs(std::integral_constant<int, NT_BF16>{});
 }
 
 template <int BN, bool BF16, bool EDGE_B>

@@ -40,53 +40,33 @@ bool tile_is_built(nt_tile_cfg cfg)
     return false;
 }
 
-// Recognise, from the lowered operand maps alone, the dense unit-stride convolution that
-// gemm_conv_kernel handles: A rows are (n, p, q) digits and columns (c, r, s) digits over a
-// contiguous NCHW input with the same step along h and along w for the output position and
-// the filter tap (conv stride 1), at most one element of left / right padding; B is a plain
-// k-contiguous matrix; C rows are (n, pq) digits with unit step along pq.
+// The dense convolution that gemm_conv_kernel handles: contiguous NCHW input, conv stride 1, at
+// most one element of left / right padding, output rows that are multiples of 8 long, a filter
+// whose (c, r, s) are contiguous, an output with contiguous (p, q).  Everything else runs on the
+// operand-map kernel.
 static bool match_conv(const GemmLaunch &g, ConvArgs *a)
 {
-    const OperandMap &x = g.ma, &w = g.mb, &y = g.mc;
-    if (g.batch != 1 || g.tile.bm != 256 || g.tile.bk != 64 || (g.tile.bn != 128 && g.tile.bn != 256)) return false;
-    if (x.nrd != 3 || x.ncd != 3 || x.nchk > 2) return false;
-    const int64_t P = x.rrad[1], Q = x.rrad[2], R = x.crad[1], S = x.crad[2];
-    if (P <= 0 || Q <= 0 || R <= 0 || S <= 0 || R > 31 || Q % 8 != 0) return false;
-    if (x.roff[2] != 1 || x.coff[2] != 1 || x.roff[1] != x.coff[1]) return false;     // unit stride along w, conv stride 1
-    int64_t H = P + R - 1, W = Q + S - 1, ph = 0, pw = 0;
-    for (int q = 0; q < x.nchk; ++q) {
-        const bool is_h = x.rchk[q][0] == 0 && x.rchk[q][1] == 1 && x.rchk[q][2] == 0 && x.cchk[q][0] == 0 && x.cchk[q][1] == 1 && x.cchk[q][2] == 0;
-        const bool is_w = x.rchk[q][0] == 0 && x.rchk[q][1] == 0 && x.rchk[q][2] == 1 && x.cchk[q][0] == 0 && x.cchk[q][1] == 0 && x.cchk[q][2] == 1;
-        if (is_h) { ph = -x.chk0[q]; H = x.chk_size[q]; }
-        else if (is_w) { pw = -x.chk0[q]; W = x.chk_size[q]; }
-        else return false;
-    }
-    if (ph < 0 || pw < 0 || pw > 1 || W < 8) return false;
-    if (P != H + 2 * ph - R + 1 || Q != W + 2 * pw - S + 1) return false;
-    const int64_t CRS = x.cols, C = CRS / (R * S), NPQ = x.rows, Nimg = NPQ / (P * Q);
-    if (C * R * S != CRS || Nimg * P * Q != NPQ) return false;
-    if (x.coff[1] != W || x.coff[0] != H * W || x.roff[0] != C * H * W) return false;   // contiguous NCHW
-    if (x.base != -(ph * W + pw)) return false;
-    const int64_t numel = Nimg * C * H * W;
-    if (numel >= (1LL << 31) || NPQ >= (1LL << 31) || CRS >= (1 << 16) - 64 || CRS < 8) return false;   // (the filter loader needs K >= 8)
-    // filter: B[kk, f] with unit step along kk
-    if (!(w.nrd == 1 && w.ncd == 1 && w.nchk == 0 && w.roff[0] == 1 && w.coff[0] > 0 && w.coff[0] < (1 << 22))) return false;
-    // output: (n, pq) rows with unit step along pq, one digit along f
-    if (!(y.nrd == 2 && y.ncd == 1 && y.nchk == 0 && y.rrad[1] == P * Q && y.roff[1] == 1)) return false;
+    const ConvHint &h = g.conv;
+    if (!h.valid || g.batch != 1 || g.tile.bm != 256 || g.tile.bk != 64 || (g.tile.bn != 128 && g.tile.bn != 256)) return false;
+    if (h.sh != 1 || h.sw != 1 || h.ph < 0 || h.pw < 0 || h.pw > 1 || h.R > 31 || h.S > 31 || h.Q % 8 != 0 || h.W < 8 || h.P <= 0) return false;
+    if (h.xs[3] != 1 || h.xs[2] != h.W || h.xs[1] != h.H * h.W || h.xs[0] != h.C * h.H * h.W) return false;
+    if (h.ws[3] != 1 || h.ws[2] != h.S || h.ws[1] != h.R * h.S || h.ws[0] <= 0 || h.ws[0] >= (1 << 22)) return false;
+    if (h.ys[3] != 1 || h.ys[2] != h.Q) return false;
+    const int64_t CRS = h.C * h.R * h.S, NPQ = h.N * h.P * h.Q, numel = h.N * h.C * h.H * h.W;
+    if (numel >= (1LL << 31) || NPQ >= (1LL << 31) || CRS >= (1 << 16) - 128 || CRS < 8) return false;   // (the filter loader needs K >= 8)
     a->X = (const uint16_t *)g.A;
-    a->Wt = (const uint16_t *)g.B + w.base;
-    const int64_t esz = g.out_dtype == NT_F32 ? 4 : 2;
-    a->Y = (char *)g.C + y.base * esz;
-    a->ldb = w.coff[0];
-    a->syn = y.roff[0];
-    a->syf = y.coff[0];
+    a->Wt = (const uint16_t *)g.B;
+    a->Y = g.C;
+    a->ldb = h.ws[0];
+    a->syn = h.ys[0];
+    a->syf = h.ys[1];
     a->x_numel = numel;
     a->M = (int32_t)NPQ; a->N = (int32_t)g.N; a->K = (int32_t)CRS;
-    a->PQ = (int32_t)(P * Q); a->Q = (int32_t)Q; a->H = (int32_t)H; a->W = (int32_t)W;
-    a->HW = (int32_t)(H * W); a->CHW = (int32_t)(C * H * W);
-    a->RS = (int32_t)(R * S); a->S = (int32_t)S; a->R = (int32_t)R; a->ph = (int32_t)ph; a->pw = (int32_t)pw;
-    a->inv_rs = R * S > 1 ? (uint32_t)((1ULL << 32) / (uint64_t)(R * S)) + 1u : 0u;
-    a->inv_s = S > 1 ? (uint32_t)((1ULL << 32) / (uint64_t)S) + 1u : 0u;
+    a->PQ = (int32_t)(h.P * h.Q); a->Q = (int32_t)h.Q; a->H = (int32_t)h.H; a->W = (int32_t)h.W;
+    a->HW = (int32_t)(h.H * h.W); a->CHW = (int32_t)(h.C * h.H * h.W);
+    a->RS = (int32_t)(h.R * h.S); a->S = (int32_t)h.S; a->R = (int32_t)h.R; a->ph = (int32_t)h.ph; a->pw = (int32_t)h.pw;
+    a->inv_rs = h.R * h.S > 1 ? (uint32_t)((1ULL << 32) / (uint64_t)(h.R * h.S)) + 1u : 0u;
+    a->inv_s = h.S > 1 ? (uint32_t)((1ULL << 32) / (uint64_t)h.S) + 1u : 0u;
     a->mt = g.mt; a->nt = g.nt; a->kt = g.kt;
     a->out_dtype = g.out_dtype;
     return true;

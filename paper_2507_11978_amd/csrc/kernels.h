@@ -10,6 +10,14 @@ namespace nt {
 
 nt_status fail(nt_status st, const std::string &msg);   // records the thread-local error text
 
+// What nt_conv2d_implicit was called with (strides in elements), so that the dense case can be
+// given to the convolution kernel; the lowered operand maps describe the same operands.
+struct ConvHint {
+    bool valid;
+    int64_t N, C, H, W, K, R, S, P, Q, sh, sw, ph, pw;
+    int64_t xs[4], ws[4], ys[4];
+};
+
 struct GemmLaunch {
     const void *A;
     const void *B;
@@ -28,6 +36,7 @@ struct GemmLaunch {
     int64_t sd_batch;
     float alpha, beta;
     bool has_d;
+    ConvHint conv;
 };
 
 // Which code path a launch would take (reported for tests and the benchmark).

@@ -121,11 +121,14 @@ nt_status arrange_query(int kind, const nt_tensor_desc *d0, const nt_tensor_desc
 }
 
 // D / dD / alpha / beta: the addmm epilogue C = beta * D + alpha * (A . B); dD == nullptr: plain product
+thread_local int t_last_path = -1;
+
 nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
               void *C, const nt_tensor_desc *dC, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
               nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *stream,
               const void *D = nullptr, const nt_tensor_desc *dD = nullptr, float alpha = 1.f, float beta = 0.f)
 {
+    t_last_path = -1;
     if (!dtype_in_ok(in_dtype)) return fail(NT_ERR_UNSUPPORTED, "input dtype must be NT_F16 or NT_BF16");
     if (!dtype_out_ok(out_dtype)) return fail(NT_ERR_UNSUPPORTED, "output dtype must be NT_F16, NT_BF16 or NT_F32");
     if ((cfg.bm || cfg.bn || cfg.bk) && cfg.bm > 0 && cfg.bn > 0 && cfg.bk > 0 && !nt::tile_is_built(cfg))
@@ -156,6 +159,15 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
         // C = beta * input: the operand-map kernel with no k tiles (its grid is that of the 64 x 64 tile)
         if (p.tile.bm != 64) return run(kind, A, dA, B, dB, C, dC, sh, sw, ph, pw, in_dtype, out_dtype, nt_tile_cfg{64, 64, 32}, stream, D, dD, alpha, beta);
     }
+    if (kind == KIND_CONV) {
+        nt::ConvHint &h = g.conv;
+        h.valid = true;
+        h.N = dA->size[0]; h.C = dA->size[1]; h.H = dA->size[2]; h.W = dA->size[3];
+        h.K = dB->size[0]; h.R = dB->size[2]; h.S = dB->size[3];
+        h.P = dC->size[2]; h.Q = dC->size[3];
+        h.sh = sh; h.sw = sw; h.ph = ph; h.pw = pw;
+        for (int d = 0; d < 4; ++d) { h.xs[d] = dA->stride[d]; h.ws[d] = dB->stride[d]; h.ys[d] = dC->stride[d]; }
+    }
     g.A = A; g.B = B; g.C = C;
     g.batch = p.batch;
     g.M = p.M; g.N = p.N; g.K = p.K;
@@ -164,7 +176,7 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
     g.in_dtype = in_dtype;
     g.out_dtype = out_dtype;
     g.stream = stream;
-    return nt::launch_gemm(g, nullptr);
+    return nt::launch_gemm(g, &t_last_path);
 }
 
 }  // namespace
@@ -245,6 +257,8 @@ int32_t nt_tile_supported(nt_tile_cfg cfg)
     if (cfg.bm == 0 && cfg.bn == 0 && cfg.bk == 0) return 1;
     return nt::tile_is_built(cfg) ? 1 : 0;
 }
+
+int32_t nt_last_kernel_path(void) { return t_last_path; }
 
 nt_status nt_gemm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
                   void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,

@@ -295,7 +295,41 @@ def test_conv2d_dense_unit_stride(shape, pad, tile, dt, out):
     Y = torch.full(ref.shape, float("nan"), dtype=TORCH_DT[out], device="cuda")
     nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), pad, tile=tile)
     torch.cuda.synchronize()
+    assert nt.last_kernel_path() == nt.PATH_CONV
     assert_gates(to_f64(Y), ref, out, f"conv dense {shape} {pad} {tile}")
+
+
+def test_kernel_paths_are_the_intended_ones():
+    """Aligned full tiles stream directly into LDS, ragged or unaligned problems take the staged
+    kernel, other strides and tiny tiles the operand-map kernel, strided convolutions too."""
+    def path_of(M, N, K, tile=None, view=None):
+        A, B = si.gemm_inputs(M, N, K, "f16", seed=1, dist="int")
+        a, b = to_gpu(A, "f16"), to_gpu(B, "f16")
+        if view == "strided_a":
+            buf = torch.zeros((M, 2 * K), dtype=torch.float16, device="cuda")
+            buf[:, ::2] = a
+            a = buf[:, ::2]
+        Cc = torch.empty((M, N), dtype=torch.float16, device="cuda")
+        nt.gemm(a, b, Cc, tile=tile)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_f64(Cc), onum.gemm(A, B, "f16"))
+        return nt.last_kernel_path()
+    assert path_of(512, 512, 256) == nt.PATH_DIRECT
+    assert path_of(512, 512, 256, tile=(256, 256, 64)) == nt.PATH_DIRECT
+    assert path_of(500, 512, 256) == nt.PATH_STAGED          # ragged M
+    assert path_of(512, 520, 264) == nt.PATH_STAGED          # ragged N and K
+    assert path_of(512, 516, 256, tile=(128, 128, 64)) == nt.PATH_STAGED   # pitch of B not a multiple of 8
+    assert path_of(512, 512, 256, view="strided_a") == nt.PATH_GENERIC
+    assert path_of(256, 256, 64, tile=(64, 64, 32)) == nt.PATH_GENERIC
+    X, Wt = si.conv_inputs(2, 8, 16, 16, 128, 3, 3, "f16", seed=3)
+    for stride, pad, want in [((1, 1), (1, 1), nt.PATH_CONV), ((2, 2), (1, 1), nt.PATH_GENERIC), ((1, 1), (2, 2), nt.PATH_GENERIC)]:
+        ref = onum.conv2d(X, Wt, "f16", stride, pad)
+        Y = torch.empty(ref.shape, dtype=torch.float16, device="cuda")
+        nt.conv2d_implicit(to_gpu(X, "f16"), to_gpu(Wt, "f16"), Y, stride, pad)
+        torch.cuda.synchronize()
+        if ref.shape[3] % 8 == 0 or want == nt.PATH_GENERIC:
+            assert nt.last_kernel_path() == want, (stride, pad)
+        assert_gates(to_f64(Y), ref, "f16", f"conv {stride} {pad}")
 
 
 def test_conv2d_dense_integer_exact_and_padding_edges():
