@@ -210,6 +210,22 @@ nt_status nt_softmax(const void *x, const nt_tensor_desc *dx, void *out, const n
 nt_status nt_rms_norm(const void *x, const nt_tensor_desc *dx, void *out, const nt_tensor_desc *dout,
                       float eps, nt_dtype dtype, void *hip_stream);
 
+/* nt_matmul_views: the matmul arrangement and application of Section 4.2 over operands that are
+ * themselves arranged tensors -- the way Section 4.3 builds a convolution: each operand is a tensor
+ * plus a meta-operation program (Table 1; same encoding as nt_arrange_tile) that must end in a single
+ * level of rank 2 ([rows, cols]) or, for all three, rank 3 ([batch, rows, cols]).  C_view = A_view . B_view,
+ * where elements of A_view / B_view that fall outside their tensor (padding, ragged tiles) read as zero
+ * and elements of C_view outside C are dropped.  C_view must not address an element of C twice.  The
+ * operands may use any composition of tile (with strides and padding), expand, squeeze, permute,
+ * flatten, ravel and level navigation; the lowered views drive the operand-map kernel, and views that
+ * reduce to plain strided matrices take the kernels of nt_gemm / nt_bmm.  Errors as nt_arrange_tile and
+ * nt_gemm.  (n_ops = 0: the tensor itself is the view.)
+ */
+nt_status nt_matmul_views(const void *A, const nt_tensor_desc *dA, const nt_meta_op *opsA, int32_t nA,
+                          const void *B, const nt_tensor_desc *dB, const nt_meta_op *opsB, int32_t nB,
+                          void *C, const nt_tensor_desc *dC, const nt_meta_op *opsC, int32_t nC,
+                          nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *hip_stream);
+
 /* nt_bmm: the same per batch index; descriptors have ndim 3: [batch,M,K], [batch,K,N], [batch,M,N]
  * (listed among the paper's kernels in Section 5.1). */
 nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,

@@ -374,6 +374,41 @@ def tile_index_set(a: Arranged, pid: int, mid=()):
     return off, valid.astype(np.uint8), inner
 
 
+def view_index_set(a: Arranged):
+    """A single-level arranged tensor (a view) written out: the offset of every element of the
+    view (-1 where it falls outside the source) and the mask, both shaped like the view."""
+    if len(a.levels) != 1:
+        raise ShapeMismatch("a view has a single level")
+    shape = a.levels[0]
+    grids = np.indices(shape, dtype=np.int64).reshape(len(shape), -1)
+    coords, valid = a.fn([[grids[d] for d in range(len(shape))]])
+    n = int(np.prod(shape)) if shape else 1
+    off = np.zeros(n, dtype=np.int64)
+    for x, s in zip(coords, a.src_strides):
+        off = off + np.asarray(x, dtype=np.int64) * np.int64(s)
+    valid = np.broadcast_to(np.asarray(valid, dtype=bool), (n,))
+    return np.where(valid, off, np.int64(-1)).reshape(shape), valid.reshape(shape)
+
+
+def matmul_views(a_view: Arranged, b_view: Arranged, c_view: Arranged, a_flat, b_flat, c_flat):
+    """C_view = A_view . B_view (Sections 4.2 / 4.3: the matrix product over operands that are
+    themselves arranged tensors) on flat fp64 source arrays: elements of A_view / B_view outside
+    their tensor read as zero, elements of C_view outside C are dropped.  Views are [rows, cols]
+    or [batch, rows, cols].  Returns the updated copy of c_flat."""
+    oa, ma = view_index_set(a_view)
+    ob, mb = view_index_set(b_view)
+    oc, mc = view_index_set(c_view)
+    A = np.where(ma, np.asarray(a_flat, dtype=np.float64)[np.where(ma, oa, 0)], 0.0)
+    B = np.where(mb, np.asarray(b_flat, dtype=np.float64)[np.where(mb, ob, 0)], 0.0)
+    if A.ndim != B.ndim or A.ndim != oc.ndim or A.shape[-1] != B.shape[-2] or oc.shape[-2:] != (A.shape[-2], B.shape[-1]) \
+            or A.shape[:-2] != B.shape[:-2] or A.shape[:-2] != oc.shape[:-2]:
+        raise ShapeMismatch("view shapes do not form a matrix product")
+    prod = np.matmul(A, B)
+    out = np.array(c_flat, dtype=np.float64, copy=True)
+    out[oc[mc]] = prod[mc]
+    return out
+
+
 # --------------------------------------------------- application on arranged tiles
 def apply_mm(a_arr, b_arr, c_arr, a_flat, b_flat, c_flat):
     """The matrix-multiplication application (Section 4.2) executed serially, one

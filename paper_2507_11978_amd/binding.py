@@ -68,6 +68,7 @@ def load():
     L.nt_bmm.argtypes = [P, D, P, D, P, D, i32, i32, TileCfg, P]
     L.nt_addmm.argtypes = [P, D, P, D, P, D, P, D, C.c_float, C.c_float, i32, i32, TileCfg, P]
     L.nt_conv2d_implicit.argtypes = [P, D, P, D, P, D, i32, i32, i32, i32, i32, i32, TileCfg, P]
+    L.nt_matmul_views.argtypes = [P, D, O, i32, P, D, O, i32, P, D, O, i32, i32, i32, TileCfg, P]
     L.nt_add.argtypes = [P, D, P, D, P, D, i32, i64, P]
     L.nt_silu.argtypes = [P, D, P, D, i32, i64, P]
     L.nt_softmax.argtypes = [P, D, P, D, i32, P]
@@ -75,7 +76,7 @@ def load():
     L.nt_trace_tile.argtypes = [i32, D, D, D, i32, i32, i32, i32, TileCfg, i32, i64, i64, P, P, C.c_size_t, P]
     for name in ("nt_arrange_levels", "nt_arrange_tile", "nt_arrange_gemm", "nt_arrange_bmm", "nt_arrange_conv2d",
                  "nt_program_order", "nt_gemm", "nt_addmm", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile",
-                 "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm"):
+                 "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm", "nt_matmul_views"):
         getattr(L, name).restype = i32
     L.nt_last_kernel_path.restype = i32
     L.nt_last_error.restype = C.c_char_p
@@ -317,6 +318,19 @@ def rms_norm(x, out, eps=1e-6, stream=None):
     _check(load().nt_rms_norm(x.data_ptr(), C.byref(_desc_of(x)), out.data_ptr(), C.byref(_desc_of(out)),
                               float(eps), _DTYPES[_torch_dtype_name(x)], _stream_ptr(stream)))
     return out
+
+
+def matmul_views(A, ops_a, B, ops_b, Cout, ops_c, tile=None, stream=None):
+    """Cview = Aview @ Bview, each view being the tensor run through a meta-operation program
+    (see make_ops) that ends in one level of rank 2 or 3."""
+    _require_cuda(A, B, Cout)
+    oa, na = make_ops(ops_a)
+    ob, nb = make_ops(ops_b)
+    oc, nc = make_ops(ops_c)
+    _check(load().nt_matmul_views(A.data_ptr(), C.byref(_desc_of(A)), oa, na, B.data_ptr(), C.byref(_desc_of(B)), ob, nb,
+                                  Cout.data_ptr(), C.byref(_desc_of(Cout)), oc, nc, _DTYPES[_torch_dtype_name(A)],
+                                  _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
+    return Cout
 
 
 def bmm(A, B, Cout, tile=None, stream=None):

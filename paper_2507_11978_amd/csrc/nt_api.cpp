@@ -22,7 +22,10 @@ namespace {
 bool dtype_in_ok(int d) { return d == NT_F16 || d == NT_BF16; }
 bool dtype_out_ok(int d) { return d == NT_F16 || d == NT_BF16 || d == NT_F32; }
 
-enum Kind { KIND_GEMM = 0, KIND_BMM = 1, KIND_CONV = 2 };
+enum Kind { KIND_GEMM = 0, KIND_BMM = 1, KIND_CONV = 2, KIND_VIEWS = 3 };
+
+// meta-operation programs of the three operands of nt_matmul_views
+struct ViewPrograms { const nt_meta_op *ops[3]; int32_t n[3]; };
 
 // Default meta-parameters (the tile sizes are the arrangement's meta-parameters, Section 3.1.2).
 // GEMM / BMM: the built tile with the lowest estimated time.  A compute unit works through
@@ -67,7 +70,8 @@ struct Problem {
 };
 
 nt_status build_problem(int kind, const nt_tensor_desc *d0, const nt_tensor_desc *d1, const nt_tensor_desc *d2,
-                        int32_t sh, int32_t sw, int32_t ph, int32_t pw, nt_tile_cfg cfg, Problem *p)
+                        int32_t sh, int32_t sw, int32_t ph, int32_t pw, nt_tile_cfg cfg, Problem *p,
+                        const ViewPrograms *views = nullptr)
 {
     if (!d0 || !d1 || !d2) return fail(NT_ERR_INVALID_ARG, "null tensor descriptor");
     if (cfg.bm < 0 || cfg.bn < 0 || cfg.bk < 0) return fail(NT_ERR_INVALID_ARG, "negative tile size");
@@ -75,6 +79,19 @@ nt_status build_problem(int kind, const nt_tensor_desc *d0, const nt_tensor_desc
         return fail(NT_ERR_INVALID_ARG, "tile sizes must be all zero (default) or all positive");
     if (kind == KIND_CONV) {
         NT_TRY(nt::conv2d_views(d0, d1, d2, sh, sw, ph, pw, &p->va, &p->vb, &p->vc));
+    } else if (kind == KIND_VIEWS) {
+        if (!views) return fail(NT_ERR_INVALID_ARG, "null meta-operation programs");
+        Arrangement *v[3] = {&p->va, &p->vb, &p->vc};
+        const nt_tensor_desc *d[3] = {d0, d1, d2};
+        for (int t = 0; t < 3; ++t) {
+            if (views->n[t] < 0 || (views->n[t] > 0 && !views->ops[t])) return fail(NT_ERR_INVALID_ARG, "null meta-operation program");
+            NT_TRY(v[t]->init(d[t]));
+            NT_TRY(v[t]->apply_all(views->ops[t], views->n[t]));
+            if (v[t]->n_levels() != 1) return fail(NT_ERR_SHAPE_MISMATCH, "an operand's program must end in a single level (a matrix view)");
+        }
+        const size_t ra = p->va.level_shape(0).size(), rb = p->vb.level_shape(0).size(), rc = p->vc.level_shape(0).size();
+        if (ra != rb || ra != rc || (ra != 2 && ra != 3))
+            return fail(NT_ERR_SHAPE_MISMATCH, "the three views must all be [rows, cols] or all [batch, rows, cols]");
     } else {
         const int want = kind == KIND_BMM ? 3 : 2;
         if (d0->ndim != want || d1->ndim != want || d2->ndim != want)
@@ -126,7 +143,8 @@ thread_local int t_last_path = -1;
 nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
               void *C, const nt_tensor_desc *dC, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
               nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *stream,
-              const void *D = nullptr, const nt_tensor_desc *dD = nullptr, float alpha = 1.f, float beta = 0.f)
+              const void *D = nullptr, const nt_tensor_desc *dD = nullptr, float alpha = 1.f, float beta = 0.f,
+              const ViewPrograms *views = nullptr)
 {
     t_last_path = -1;
     if (!dtype_in_ok(in_dtype)) return fail(NT_ERR_UNSUPPORTED, "input dtype must be NT_F16 or NT_BF16");
@@ -134,7 +152,7 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
     if ((cfg.bm || cfg.bn || cfg.bk) && cfg.bm > 0 && cfg.bn > 0 && cfg.bk > 0 && !nt::tile_is_built(cfg))
         return fail(NT_ERR_UNSUPPORTED, "no kernel built for this tile shape (see nt_tile_supported)");
     Problem p;
-    NT_TRY(build_problem(kind, dA, dB, dC, sh, sw, ph, pw, cfg, &p));
+    NT_TRY(build_problem(kind, dA, dB, dC, sh, sw, ph, pw, cfg, &p, views));
     if (p.batch == 0 || p.M == 0 || p.N == 0) return NT_OK;
     if (!C || (p.K > 0 && (!A || !B))) return fail(NT_ERR_INVALID_ARG, "null device pointer");
     nt::GemmLaunch g{};
@@ -259,6 +277,15 @@ int32_t nt_tile_supported(nt_tile_cfg cfg)
 }
 
 int32_t nt_last_kernel_path(void) { return t_last_path; }
+
+nt_status nt_matmul_views(const void *A, const nt_tensor_desc *dA, const nt_meta_op *opsA, int32_t nA,
+                          const void *B, const nt_tensor_desc *dB, const nt_meta_op *opsB, int32_t nB,
+                          void *C, const nt_tensor_desc *dC, const nt_meta_op *opsC, int32_t nC,
+                          nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *hip_stream)
+{
+    const ViewPrograms views{{opsA, opsB, opsC}, {nA, nB, nC}};
+    return run(KIND_VIEWS, A, dA, B, dB, C, dC, 1, 1, 0, 0, in_dtype, out_dtype, cfg, hip_stream, nullptr, nullptr, 1.f, 0.f, &views);
+}
 
 nt_status nt_gemm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
                   void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,

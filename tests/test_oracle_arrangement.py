@@ -260,3 +260,36 @@ def test_planted_mistakes_are_caught():
         assert not np.allclose(wrong, ref, atol=1e-9)
     except (arr.ShapeMismatch, ValueError):
         pass
+
+
+def test_matmul_views_equals_direct_convolution_and_plain_products():
+    """The product over arranged operands: with the Section 4.3 programs it must equal the direct
+    convolution (7 loops, here numpy's own sliding windows), with empty programs a plain product,
+    with a permute a transposed one."""
+    rng = np.random.default_rng(3)
+    for (N, C, H, W, K, R, S), stride, pad in [((2, 3, 7, 6, 4, 3, 2), (1, 1), (0, 0)), ((1, 2, 8, 9, 3, 3, 3), (2, 1), (1, 2))]:
+        x = rng.integers(-3, 4, (N, C, H, W)).astype(np.float64)
+        w = rng.integers(-3, 4, (K, C, R, S)).astype(np.float64)
+        P = (H + 2 * pad[0] - R) // stride[0] + 1
+        Q = (W + 2 * pad[1] - S) // stride[1] + 1
+        px, pw, py = arr.conv2d_operand_programs(R, S, C, stride, pad, P, Q, H, W)
+        X, Wt, Y = arr.Tensor((N, C, H, W)), arr.Tensor((K, C, R, S)), arr.Tensor((N, K, P, Q))
+        got = arr.matmul_views(arr.run_program(X, px), arr.run_program(Wt, pw), arr.run_program(Y, py),
+                               x.ravel(), w.ravel(), np.full(N * K * P * Q, np.nan)).reshape(N, K, P, Q)
+        xp = np.pad(x, ((0, 0), (0, 0), (pad[0], pad[0]), (pad[1], pad[1])))
+        ref = np.zeros((N, K, P, Q))
+        for p in range(P):
+            for q in range(Q):
+                patch = xp[:, :, p * stride[0]:p * stride[0] + R, q * stride[1]:q * stride[1] + S]
+                ref[:, :, p, q] = np.einsum("ncrs,kcrs->nk", patch, w)
+        assert np.array_equal(got, ref)
+    a, b = rng.integers(-3, 4, (5, 4)).astype(np.float64), rng.integers(-3, 4, (4, 6)).astype(np.float64)
+    A, B, Cc = arr.Tensor((5, 4)), arr.Tensor((4, 6)), arr.Tensor((5, 6))
+    assert np.array_equal(arr.matmul_views(A, B, Cc, a.ravel(), b.ravel(), np.zeros(30)).reshape(5, 6), a @ b)
+    # B handed over as its transpose's storage and viewed back through a permute
+    Bt = arr.run_program(arr.Tensor((6, 4)), [("permute", (1, 0))])
+    assert np.array_equal(arr.matmul_views(A, Bt, Cc, a.ravel(), b.T.copy().ravel(), np.zeros(30)).reshape(5, 6), a @ b)
+    # every second row of A (a tile of height 1 every 2 rows, squeezed): a strided gather expressed as an arrangement
+    A2 = arr.run_program(arr.Tensor((5, 4)), [("tile", (1, -1), (2, -1)), ("squeeze", 1), ("descend",), ("squeeze", 0), ("ascend",), ("ravel",)])
+    C3 = arr.Tensor((3, 6))
+    assert np.array_equal(arr.matmul_views(A2, B, C3, a.ravel(), b.ravel(), np.zeros(18)).reshape(3, 6), a[::2] @ b)
