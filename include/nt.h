@@ -226,6 +226,19 @@ nt_status nt_matmul_views(const void *A, const nt_tensor_desc *dA, const nt_meta
                           void *C, const nt_tensor_desc *dC, const nt_meta_op *opsC, int32_t nC,
                           nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *hip_stream);
 
+/* nt_sdpa: scaled dot-product attention, O[b,h,i,:] = sum_j softmax_j(scale * <Q[b,h,i,:], K[b,h,j,:]>) V[b,h,j,:]
+ * (no mask, no dropout), computed with the FlashAttention-2 scheme the paper's sdpa kernels use (Section 5.1):
+ * Q and O tiled into blocks of query rows (one program per batch, head and block), K and V into blocks of keys
+ * that every program visits in turn with a running maximum and sum; scores and sums in fp32, the probabilities
+ * rounded to the 16-bit format before they multiply V.  All four tensors are device pointers to 16-bit elements
+ * of `dtype` (NT_F16 or NT_BF16) with descriptors [batch, heads, seq, 64]: any strides along the first three axes,
+ * unit stride along the last; other head sizes: NT_ERR_UNSUPPORTED.  K and V share their sequence length (>= 1),
+ * Q and O theirs.  scale = 0 stands for 1 / sqrt(64).  O must not alias an input.
+ */
+nt_status nt_sdpa(const void *q, const nt_tensor_desc *dq, const void *k, const nt_tensor_desc *dk,
+                  const void *v, const nt_tensor_desc *dv, void *o, const nt_tensor_desc *dout,
+                  float scale, nt_dtype dtype, void *hip_stream);
+
 /* nt_bmm: the same per batch index; descriptors have ndim 3: [batch,M,K], [batch,K,N], [batch,M,N]
  * (listed among the paper's kernels in Section 5.1). */
 nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,

@@ -69,6 +69,7 @@ def load():
     L.nt_addmm.argtypes = [P, D, P, D, P, D, P, D, C.c_float, C.c_float, i32, i32, TileCfg, P]
     L.nt_conv2d_implicit.argtypes = [P, D, P, D, P, D, i32, i32, i32, i32, i32, i32, TileCfg, P]
     L.nt_matmul_views.argtypes = [P, D, O, i32, P, D, O, i32, P, D, O, i32, i32, i32, TileCfg, P]
+    L.nt_sdpa.argtypes = [P, D, P, D, P, D, P, D, C.c_float, i32, P]
     L.nt_add.argtypes = [P, D, P, D, P, D, i32, i64, P]
     L.nt_silu.argtypes = [P, D, P, D, i32, i64, P]
     L.nt_softmax.argtypes = [P, D, P, D, i32, P]
@@ -76,7 +77,7 @@ def load():
     L.nt_trace_tile.argtypes = [i32, D, D, D, i32, i32, i32, i32, TileCfg, i32, i64, i64, P, P, C.c_size_t, P]
     for name in ("nt_arrange_levels", "nt_arrange_tile", "nt_arrange_gemm", "nt_arrange_bmm", "nt_arrange_conv2d",
                  "nt_program_order", "nt_gemm", "nt_addmm", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile",
-                 "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm", "nt_matmul_views"):
+                 "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm", "nt_matmul_views", "nt_sdpa"):
         getattr(L, name).restype = i32
     L.nt_last_kernel_path.restype = i32
     L.nt_last_error.restype = C.c_char_p
@@ -331,6 +332,14 @@ def matmul_views(A, ops_a, B, ops_b, Cout, ops_c, tile=None, stream=None):
                                   Cout.data_ptr(), C.byref(_desc_of(Cout)), oc, nc, _DTYPES[_torch_dtype_name(A)],
                                   _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
     return Cout
+
+
+def sdpa(q, k, v, out, scale=0.0, stream=None):
+    """out = softmax(scale * q @ k^T) @ v per (batch, head); tensors [batch, heads, seq, 64]; scale 0 = 1/sqrt(64)."""
+    _require_cuda(q, k, v, out)
+    _check(load().nt_sdpa(q.data_ptr(), C.byref(_desc_of(q)), k.data_ptr(), C.byref(_desc_of(k)), v.data_ptr(), C.byref(_desc_of(v)),
+                          out.data_ptr(), C.byref(_desc_of(out)), float(scale), _DTYPES[_torch_dtype_name(q)], _stream_ptr(stream)))
+    return out
 
 
 def bmm(A, B, Cout, tile=None, stream=None):

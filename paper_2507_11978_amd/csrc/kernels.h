@@ -54,6 +54,11 @@ nt_status launch_map(int op, const void *x, int64_t sx, const void *y, int64_t s
 nt_status launch_rows(int op, const void *x, int64_t sxr, int64_t sxc, void *out, int64_t sor, int64_t soc, int64_t rows, int64_t cols,
                       float eps, int dtype, void *stream);
 
+// scaled dot-product attention over [batch, heads, seq, 64] tensors (strides in elements, unit stride along the head dimension)
+nt_status launch_sdpa_desc(const void *q, const nt_tensor_desc *dq, const void *k, const nt_tensor_desc *dk,
+                           const void *v, const nt_tensor_desc *dv, void *o, const nt_tensor_desc *dout,
+                           float scale, int dtype, void *stream);
+
 // workgroup index -> logical program id (shared by host query and device code)
 NT_HD int64_t program_of_workgroup(int64_t w, int64_t mt, int64_t nt)
 {

@@ -363,6 +363,14 @@ nt_status nt_rms_norm(const void *x, const nt_tensor_desc *dx, void *out, const 
     return rows_op(1, x, dx, out, dout, eps, dtype, hip_stream);
 }
 
+nt_status nt_sdpa(const void *q, const nt_tensor_desc *dq, const void *k, const nt_tensor_desc *dk,
+                  const void *v, const nt_tensor_desc *dv, void *o, const nt_tensor_desc *dout,
+                  float scale, nt_dtype dtype, void *hip_stream)
+{
+    if (!dtype_in_ok(dtype)) return fail(NT_ERR_UNSUPPORTED, "dtype must be NT_F16 or NT_BF16");
+    return nt::launch_sdpa_desc(q, dq, k, dk, v, dv, o, dout, scale, dtype, hip_stream);
+}
+
 nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
                  void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
                  nt_tile_cfg cfg, void *hip_stream)
