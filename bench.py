@@ -37,7 +37,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="p_f16_8192",
-                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c1_f16_256, f1_f16_addmm, f3_f16_add, f3_f16_silu, f3_f16_softmax, f3_f16_rms_norm")
+                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c1_f16_256, f1_f16_addmm, f3_f16_add, f3_f16_silu, f3_f16_softmax, f3_f16_rms_norm, f4_f16_sdpa")
     ap.add_argument("--tile", default=None, help="bm,bn,bk (default: library choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -146,6 +146,65 @@ def bench_memory_bound(args, cfg):
     print(json.dumps(result), flush=True)
 
 
+def bench_sdpa(args, cfg):
+    """Attention forward at the paper's task shape: TFLOP/s over the 4 * B * H * S^2 * D flops of the two products."""
+    import numpy as np
+    import torch
+    import paper_2507_11978_amd as nt
+    import synthetic_inputs as si
+    from gpu_util import TORCH_DT, to_f64, to_gpu
+    from oracle import attention as oat
+
+    dt, B, H, S, D = cfg["dtype"], cfg["B"], cfg["H"], cfg["S"], cfg["D"]
+    qb, kb, vb = (si.normal_bits((B, H, S, D), dt, cfg["seed"] + i, 1.0) for i in range(3))
+    q, k, v = to_gpu(qb, dt), to_gpu(kb, dt), to_gpu(vb, dt)
+    out = torch.empty((B, H, S, D), dtype=TORCH_DT[dt], device="cuda")
+    step = lambda: nt.sdpa(q, k, v, out)
+    flops = 4.0 * B * H * S * S * D
+    alg_bytes = 4 * 2 * B * H * S * D
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record()
+        step()
+        ends[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, ends)])
+    ms_per_step = wall * 1e3 / args.steps
+    kern_avg = float(kern_ms.mean())
+    achieved = flops / (kern_avg * 1e-3) / 1e12
+    result = {
+        "metric": "sdpa forward TFLOP/s (4*B*H*S^2*D flops), 1 GPU", "value": round(flops / (ms_per_step * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
+        "config": {"workload": args.workload, "shape": {"B": B, "H": H, "S": S, "D": D}, "in_dtype": dt, "out_dtype": dt, "accumulate": "f32"},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "kernel_ms_avg": round(kern_avg, 4),
+                     "kernel_ms_min": round(float(kern_ms.min()), 4), "kernel_ms_median": round(float(np.median(kern_ms)), 4),
+                     "algorithmic_bytes": int(alg_bytes)},
+    }
+    if not args.no_check:
+        ref = oat.sdpa(qb[B - 1, H - 1, :256], kb[B - 1, H - 1], vb[B - 1, H - 1], dt)
+        got = to_f64(out[B - 1, H - 1, :256])
+        result["parity"] = {"sample": "last batch and head, query rows 0..255", "max_abs_err": float(np.abs(got - ref).max()),
+                            "rel_frobenius_err": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+    if not args.no_cpu_baseline:
+        t1 = time.perf_counter()
+        heads = 0
+        while time.perf_counter() - t1 < 10.0:
+            oat.sdpa(qb[0, heads % H], kb[0, heads % H], vb[0, heads % H], dt)
+            heads += 1
+        dt_cpu = time.perf_counter() - t1
+        result["cpu_baseline"] = {"value": round(4.0 * S * S * D * heads / dt_cpu / 1e12, 6), "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+                                  "seconds": round(dt_cpu, 2), "sample": f"{heads} heads of batch 0 (numpy fp64)"}
+    print(json.dumps(result), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -175,6 +234,8 @@ def main():
     cfg = si.CONFIGS[args.workload]
     if cfg["kind"] in ("add", "silu", "softmax", "rms_norm"):
         return bench_memory_bound(args, cfg)
+    if cfg["kind"] == "sdpa":
+        return bench_sdpa(args, cfg)
     tile = tuple(int(x) for x in args.tile.split(",")) if args.tile else cfg.get("tile")
     dt, out = cfg["dtype"], cfg["out"]
 

@@ -137,24 +137,35 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
                 st[jb] = mfma32<BF16>(kf, qf[ks], st[jb]);
             }
         }
-        // ---- scale, mask keys past Sk (last block only), running maximum
+        // ---- mask keys past Sk (last block only), running maximum.  The scale (> 0 or < 0) is folded
+        // into the exponent below: m tracks max(scale * S) in base-2 units.
         const int key_base = kb * kKeyBlock;
-        const bool ragged = key_base + kKeyBlock > g.Sk;               // wavefront-uniform
-        float mx = -INFINITY;
+        if (key_base + kKeyBlock > g.Sk) {                                // wavefront-uniform
+            const float out = g.scale_log2e >= 0.f ? -INFINITY : INFINITY;
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
+            for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float s = st[jb][v] * g.scale_log2e;
-                if (ragged && key_base + jb * 32 + 8 * (v / 4) + 4 * hi + (v % 4) >= g.Sk) s = -INFINITY;
-                st[jb][v] = s;
-                mx = fmaxf(mx, s);
-            }
+                for (int v = 0; v < 16; ++v)
+                    if (key_base + jb * 32 + 8 * (v / 4) + 4 * hi + (v % 4) >= g.Sk) st[jb][v] = out;
+        }
+        float mx = st[0][0];
+        if (g.scale_log2e >= 0.f) {                                      // wavefront-uniform
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, st[jb][v]);
+        } else {
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fminf(mx, st[jb][v]);
+        }
+        mx *= g.scale_log2e;                                             // max of the scaled scores
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m_run, mx);
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 0 at the first block (m_run = -inf)
         m_run = m_new;
-        // ---- P^T = exp2(S^T - m), its row sum (this lane's keys only; the halves are added at the end), packed to 16 bits
+        // ---- P^T = exp2(scale * S^T - m), its row sum (this lane's keys only; the halves are added at the end), packed to 16 bits
         float rs = 0.f;
         u32x4 pk[2][2];
 #pragma unroll
@@ -164,16 +175,18 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
                 float p[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    p[j] = __builtin_amdgcn_exp2f(st[jb][8 * s2 + j] - m_new);
+                    p[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[jb][8 * s2 + j], g.scale_log2e, -m_new));
                     rs += p[j];
                 }
                 pk[jb][s2] = u32x4{pack2<BF16>(p[0], p[1]), pack2<BF16>(p[2], p[3]), pack2<BF16>(p[4], p[5]), pack2<BF16>(p[6], p[7])};
             }
         l_run = l_run * alpha + rs;
+        if (__any(alpha != 1.0f)) {                                      // the maximum rarely moves after the first blocks
 #pragma unroll
-        for (int db = 0; db < 2; ++db)
+            for (int db = 0; db < 2; ++db)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) ot[db][v] *= alpha;
+                for (int v = 0; v < 16; ++v) ot[db][v] *= alpha;
+        }
         // ---- O^T += V^T P^T: k step (jb, s2) lists its 16 keys as jb*32 + 16 s2 + 8 part + 4 hi + 0..3
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)

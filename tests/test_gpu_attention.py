@@ -74,3 +74,9 @@ def test_sdpa_strided_views_and_errors():
         nt.sdpa(a, a[:, :, :0], a[:, :, :0], a)                           # no keys
     with pytest.raises(nt.NtError):
         nt.sdpa(a, a, a[:, :, :4], a)                                     # K and V lengths differ
+
+
+def test_sdpa_negative_scale():
+    dt = "f16"
+    q, k, v = (si.normal_bits((1, 2, 90, 64), dt, 40 + i, 1.0) for i in range(3))
+    assert_gates(run(q, k, v, dt, scale=-0.3), oat.sdpa(q, k, v, dt, scale=-0.3), dt, "sdpa negative scale")
