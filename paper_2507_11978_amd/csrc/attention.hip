@@ -21,6 +21,7 @@
 // several workgroups share a compute unit, which hides the exponentials of one behind the MFMAs
 // of another.
 #include "gemm_fast.h"
+#include <type_traits>
 
 namespace nt {
 
@@ -97,18 +98,21 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
 
     // ---- per-lane LDS read addresses
     // K fragment (A operand, row = key l32 of a 32-key half, chunk 2 ks + hi, swizzled like the write)
-    uint32_t k_rd[2];
+    // Key row 32 + l32 has the swizzle of row l32 with bit 2 flipped, so its chunk for k step ks sits where row
+    // l32's chunk for k step ks ^ 2 does: four addresses serve both halves, everything else is an immediate offset.
+    uint32_t k_rd[4];
 #pragma unroll
-    for (int jb = 0; jb < 2; ++jb) {
-        const int row = jb * 32 + l32;
-        k_rd[jb] = (uint32_t)(row * 128 + ((hi ^ ((row ^ (row >> 3)) & 7)) << 4));
-    }
+    for (int ks = 0; ks < 4; ++ks) k_rd[ks] = (uint32_t)(l32 * 128 + (((hi + 2 * ks) ^ ((l32 ^ (l32 >> 3)) & 7)) << 4));
     // V^T fragment through the transposing read: 16-lane group gq covers d = 16 (gq & 1) .. + 15 and
     // keys 4 (gq >> 1) .. + 3 of an 8-key part; lane i of the group points at key i / 4, columns 4 (i % 4) .. + 3
     const int gq = lane >> 4, li = lane & 15;
     const int v_key = 4 * (gq >> 1) + (li >> 2);                       // + jb * 32 + 16 * s2 + 8 * part
     const int v_c8 = 4 * (gq & 1) + (li & 3);                          // 8-byte chunk within the 32-d block; + 8 * db
-    const uint32_t v_swz = (uint32_t)(((v_key >> 1) & 1) << 3);        // (every key offset added later is a multiple of 8)
+    // the swizzle flips bit 3 of the 8-byte chunk index on keys with bit 1 set (key offsets added later are multiples of 8)
+    uint32_t v_rd[2];
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+        v_rd[db] = (uint32_t)(v_key * 128) + ((((uint32_t)(v_c8 + 8 * db)) ^ (uint32_t)(((v_key >> 1) & 1) << 3)) << 3);
 
     float16v ot[2];
 #pragma unroll
@@ -121,8 +125,9 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
     fetch(0);
     stash(0);
     __syncthreads();
-    for (int kb = 0; kb < nblk; ++kb) {
-        const uint32_t cur = (uint32_t)(kb & 1);
+    // one key block; the LDS buffer index is a compile-time constant so that every LDS address is base + immediate
+    auto block = [&](auto cur_c, const int kb) {
+        constexpr uint32_t cur = (uint32_t)decltype(cur_c)::value;
         if (kb + 1 < nblk) fetch((kb + 1) * kKeyBlock);                // in flight during this block's arithmetic
 
         // ---- S^T = K Q^T: st[jb][v] <-> key jb * 32 + 8 (v / 4) + 4 hi + v % 4, query l32
@@ -133,7 +138,7 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
             for (int v = 0; v < 16; ++v) st[jb][v] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                const u32x4 kf = lds_read16(smem, cur * BLK + (k_rd[jb] ^ (uint32_t)((2 * ks) << 4)));
+                const u32x4 kf = lds_read16(smem, k_rd[jb ? (ks ^ 2) : ks] + (cur * BLK + (uint32_t)(jb * 4096)));
                 st[jb] = mfma32<BF16>(kf, qf[ks], st[jb]);
             }
         }
@@ -197,8 +202,7 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
                     u32x2 part[2];
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt) {
-                        const int key = v_key + jb * 32 + 16 * s2 + 8 * pt;
-                        const uint32_t addr = (2 + cur) * BLK + (uint32_t)(key * 128) + ((((uint32_t)(v_c8 + 8 * db)) ^ v_swz) << 3);
+                        const uint32_t addr = v_rd[db] + ((2 + cur) * BLK + (uint32_t)((jb * 32 + 16 * s2 + 8 * pt) * 128));
                         typedef short4v_a __attribute__((address_space(3))) * lds_s4;
                         const short4v_a t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + addr));
                         part[pt] = __builtin_bit_cast(u32x2, t);
@@ -209,6 +213,10 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
         // ---- next block into the other LDS buffer
         if (kb + 1 < nblk) stash(cur ^ 1u);
         __syncthreads();
+    };
+    for (int kb = 0; kb < nblk; kb += 2) {
+        block(std::integral_constant<int, 0>{}, kb);
+        if (kb + 1 < nblk) block(std::integral_constant<int, 1>{}, kb + 1);
     }
 
     // ---- O = O^T / l, stored along d: after the half-wavefronts trade register groups a lane owns
