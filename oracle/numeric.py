@@ -102,6 +102,27 @@ def addmm(inp, A, B, dtype: str, alpha: float = 1.0, beta: float = 1.0, inp_dtyp
     return float(beta) * np.broadcast_to(vals, prod.shape) + float(alpha) * prod
 
 
+def activation(x, act) -> np.ndarray:
+    """The activations an epilogue may fuse, by their textbook definitions, in fp64:
+    relu max(x, 0); silu x / (1 + exp(-x)); gelu_tanh 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))."""
+    x = np.asarray(x, dtype=np.float64)
+    if act in (None, "none"):
+        return x
+    if act == "relu":
+        return np.maximum(x, 0.0)
+    if act == "silu":
+        return x / (1.0 + np.exp(-x))
+    if act == "gelu_tanh":
+        return 0.5 * x * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (x + 0.044715 * x ** 3)))
+    raise ValueError(act)
+
+
+def addmm_act(inp, A, B, dtype: str, act, alpha: float = 1.0, beta: float = 1.0, inp_dtype: str | None = None,
+              nthreads: int = 1) -> np.ndarray:
+    """act(beta * input + alpha * (A . B)): addmm followed by an element-wise activation."""
+    return activation(addmm(inp, A, B, dtype, alpha, beta, inp_dtype, nthreads), act)
+
+
 def conv_out_size(H: int, R: int, stride: int, pad: int) -> int:
     """P = floor((H + 2*pad - R) / stride) + 1: number of filter positions that fit."""
     return (H + 2 * pad - R) // stride + 1

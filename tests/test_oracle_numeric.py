@@ -131,6 +131,33 @@ def test_addmm_hand_worked_and_special_cases(dt):
     assert np.array_equal(onum.addmm(col, A, B, dt), prod + col)
 
 
+def test_activation_pins():
+    from scipy import special
+    # relu: hand-worked product (tests/golden/hand_worked.txt)
+    kv = _hand("addmm2_relu")
+    A, B, I, C = _mat(kv["A"]), _mat(kv["B"]), _mat(kv["I"]), _mat(kv["C"])
+    got = onum.addmm_act(I, _bits(A, "f16"), _bits(B, "f16"), "f16", "relu", alpha=float(kv["alpha"]), beta=float(kv["beta"]))
+    assert np.array_equal(got, C)
+    assert np.array_equal(onum.addmm_act(I, _bits(A, "f16"), _bits(B, "f16"), "f16", None, alpha=-1.0, beta=1.0), [[11, -52], [-93, 10]])
+    x = np.linspace(-8.0, 8.0, 3201)
+    for act in ("silu", "gelu_tanh"):
+        y = onum.activation(x, act)
+        assert onum.activation(0.0, act) == 0.0
+        assert np.allclose(y - onum.activation(-x, act), x, rtol=0, atol=1e-14)      # f(x) - f(-x) = x for x * sigmoid-like gates
+        assert np.allclose(onum.activation(40.0, act), 40.0) and abs(onum.activation(-40.0, act)) < 1e-15
+    # silu: closed form at ln 3 (sigmoid = 3/4) and a library second opinion (logistic function)
+    assert abs(onum.activation(np.log(3.0), "silu") - 0.75 * np.log(3.0)) < 1e-15
+    assert np.allclose(onum.activation(x, "silu"), x * special.expit(x), rtol=1e-14, atol=1e-15)
+    # gelu, tanh form: 0.5 (1 + tanh u) is the logistic function of 2u; and it approximates the
+    # erf-based definition x Phi(x) to within 5e-4 (a wrong cubic coefficient or a dropped term leaves that band)
+    u = np.sqrt(2.0 / np.pi) * (x + 0.044715 * x ** 3)
+    assert np.allclose(onum.activation(x, "gelu_tanh"), x * special.expit(2.0 * u), rtol=1e-13, atol=1e-15)
+    exact = 0.5 * x * (1.0 + special.erf(x / np.sqrt(2.0)))
+    assert np.abs(onum.activation(x, "gelu_tanh") - exact).max() < 5e-4
+    assert np.abs(0.5 * x * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * x)) - exact).max() > 5e-3   # the planted mistake is visible
+    assert np.array_equal(onum.activation(x, "relu"), np.where(x > 0, x, 0.0))
+
+
 def test_conv_hand_worked():
     kv = _hand("conv_3x3_2x2")
     X, W, Y = _mat(kv["X"]), _mat(kv["W"]), _mat(kv["Y"])
