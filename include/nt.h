@@ -144,7 +144,7 @@ nt_status nt_arrange_conv2d(const nt_tensor_desc *dx, const nt_tensor_desc *dw, 
  */
 nt_status nt_program_order(int64_t batch, int64_t mt, int64_t nt, int64_t *pid_out);
 
-/* Which kernel the calling thread's last nt_gemm / nt_addmm / nt_bmm / nt_conv2d_implicit call launched:
+/* Which kernel the calling thread's last nt_gemm / nt_addmm / nt_addmm_act / nt_bmm / nt_conv2d_implicit call launched:
  * 0 operand-map (generic) kernel, 1 staged kernel, 2 direct-to-LDS kernel, 3 convolution kernel,
  * -1 none (nothing launched yet, an error, or an empty problem).  For tests and diagnostics. */
 int32_t nt_last_kernel_path(void);
@@ -178,6 +178,22 @@ nt_status nt_addmm(const void *input, const nt_tensor_desc *dI, const void *A, c
                    const void *B, const nt_tensor_desc *dB, void *C, const nt_tensor_desc *dC,
                    float alpha, float beta, nt_dtype in_dtype, nt_dtype out_dtype,
                    nt_tile_cfg cfg, void *hip_stream);
+
+/* nt_addmm_act: C = act(beta * input + alpha * (A . B))  -- nt_addmm with an activation fused into the
+ * epilogue (bias + activation in one pass over the accumulators; the paper's generated kernels fuse
+ * their whole application into one kernel in the same way, Section 3.2).  The activation acts on the fp32
+ * combined value, before the one conversion to out_dtype:
+ *   NT_ACT_NONE       x
+ *   NT_ACT_RELU       max(x, 0)
+ *   NT_ACT_SILU       x / (1 + exp(-x))
+ *   NT_ACT_GELU_TANH  0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))
+ * `input` / dI may be NULL when beta == 0 (then C = act(alpha * A . B)).  Everything else as nt_addmm.
+ */
+typedef enum { NT_ACT_NONE = 0, NT_ACT_RELU = 1, NT_ACT_SILU = 2, NT_ACT_GELU_TANH = 3 } nt_activation;
+nt_status nt_addmm_act(const void *input, const nt_tensor_desc *dI, const void *A, const nt_tensor_desc *dA,
+                       const void *B, const nt_tensor_desc *dB, void *C, const nt_tensor_desc *dC,
+                       float alpha, float beta, nt_activation act, nt_dtype in_dtype, nt_dtype out_dtype,
+                       nt_tile_cfg cfg, void *hip_stream);
 
 /* ------------------------------------------------------------------ memory-bound kernels (device)
  *

@@ -67,6 +67,7 @@ def load():
     L.nt_gemm.argtypes = [P, D, P, D, P, D, i32, i32, TileCfg, P]
     L.nt_bmm.argtypes = [P, D, P, D, P, D, i32, i32, TileCfg, P]
     L.nt_addmm.argtypes = [P, D, P, D, P, D, P, D, C.c_float, C.c_float, i32, i32, TileCfg, P]
+    L.nt_addmm_act.argtypes = [P, D, P, D, P, D, P, D, C.c_float, C.c_float, i32, i32, i32, TileCfg, P]
     L.nt_conv2d_implicit.argtypes = [P, D, P, D, P, D, i32, i32, i32, i32, i32, i32, TileCfg, P]
     L.nt_matmul_views.argtypes = [P, D, O, i32, P, D, O, i32, P, D, O, i32, i32, i32, TileCfg, P]
     L.nt_sdpa.argtypes = [P, D, P, D, P, D, P, D, C.c_float, i32, P]
@@ -76,7 +77,7 @@ def load():
     L.nt_rms_norm.argtypes = [P, D, P, D, C.c_float, i32, P]
     L.nt_trace_tile.argtypes = [i32, D, D, D, i32, i32, i32, i32, TileCfg, i32, i64, i64, P, P, C.c_size_t, P]
     for name in ("nt_arrange_levels", "nt_arrange_tile", "nt_arrange_gemm", "nt_arrange_bmm", "nt_arrange_conv2d",
-                 "nt_program_order", "nt_gemm", "nt_addmm", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile",
+                 "nt_program_order", "nt_gemm", "nt_addmm", "nt_addmm_act", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile",
                  "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm", "nt_matmul_views", "nt_sdpa"):
         getattr(L, name).restype = i32
     L.nt_last_kernel_path.restype = i32
@@ -273,9 +274,31 @@ def last_kernel_path() -> int:
     return int(load().nt_last_kernel_path())
 
 
-def addmm(inp, A, B, Cout, alpha=1.0, beta=1.0, tile=None, stream=None):
-    """Cout[M,N] = beta * inp + alpha * (A[M,K] @ B[K,N]); inp has Cout's dtype and is handed over as
-    an [M, N] view (stride 0 along broadcast axes)."""
+ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu_tanh": 3}
+
+
+def addmm(inp, A, B, Cout, alpha=1.0, beta=1.0, tile=None, stream=None, act=None):
+    """Cout[M,N] = act(beta * inp + alpha * (A[M,K] @ B[K,N])); inp has Cout's dtype and is handed over as
+    an [M, N] view (stride 0 along broadcast axes).  act: None, "relu", "silu" or "gelu_tanh" (fused into the
+    epilogue); inp may be None when beta is 0."""
+    if act is not None or inp is None:
+        if act not in ACTIVATIONS:
+            raise ValueError(f"unknown activation {act!r}")
+        _require_cuda(A, B, Cout)
+        view = None
+        if inp is not None:
+            _require_cuda(inp)
+            if inp.dtype != Cout.dtype:
+                raise ValueError("input must have the output's dtype")
+            try:
+                view = inp.expand(Cout.shape)
+            except RuntimeError:
+                view = inp
+        _check(load().nt_addmm_act(view.data_ptr() if view is not None else None, C.byref(_desc_of(view)) if view is not None else None,
+                                   A.data_ptr(), C.byref(_desc_of(A)), B.data_ptr(), C.byref(_desc_of(B)),
+                                   Cout.data_ptr(), C.byref(_desc_of(Cout)), float(alpha), float(beta), ACTIVATIONS[act],
+                                   _DTYPES[_torch_dtype_name(A)], _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
+        return Cout
     _require_cuda(inp, A, B, Cout)
     if inp.dtype != Cout.dtype:
         raise ValueError("input must have the output's dtype")

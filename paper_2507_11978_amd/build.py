@@ -16,7 +16,11 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnt.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function", "-Wno-pass-failed"]
+         # the epilogues unroll 256 accumulator elements with address arithmetic, masks and format switches per
+         # element: above LLVM's default size limit for "#pragma unroll", and a loop left rolled would index
+         # the accumulator registers dynamically, i.e. move them to scratch memory
+         "-mllvm", "-pragma-unroll-threshold=100000",
+         "-Wall", "-Wno-unused-function"]
 
 
 def sources():

@@ -80,6 +80,40 @@ __device__ __forceinline__ float load_as_f32(const void *D, int64_t off, int dty
 // the addmm combination, in fp32: alpha * accumulator + beta * addend
 __device__ __forceinline__ float combine(float acc, float d, float alpha, float beta) { return __builtin_fmaf(alpha, acc, beta * d); }
 
+// Activation applied to the combined value before the single conversion to the output type (codes:
+// nt_activation).  One branch-free formula serves all of them, so that the fully unrolled epilogues
+// carry a single short instruction sequence per element:
+//   t = max(x, lo);  y = t * (g1 + g0 / (1 + 2^(-t (c1 + c3 t^2))))
+//   relu       lo = 0,     g1 = 1, g0 = 0                     -> max(x, 0) exactly
+//   silu       lo = -inf,  g1 = 0, g0 = 1, c1 = log2(e)       -> x sigmoid(x)
+//   gelu_tanh  lo = -inf,  g1 = 0, g0 = 1, c1 = 2 sqrt(2/pi) log2(e), c3 = 0.044715 c1
+//              (0.5 (1 + tanh u) is the logistic function of 2u)
+// The gate's argument is built from t clamped to +-1e15, where the gate has long saturated, so that
+// t^2 cannot overflow into 0 * inf.
+struct ActParams {
+    float lo, c1, c3, g0, g1;
+};
+
+__device__ __forceinline__ ActParams act_params(int act)
+{
+    ActParams p;
+    p.lo = act == 1 ? 0.f : -INFINITY;
+    p.g1 = act == 1 ? 1.f : 0.f;
+    p.g0 = act == 1 ? 0.f : 1.f;
+    p.c1 = act == 2 ? 1.4426950408889634f : (act == 3 ? 2.302208198f : 0.f);      // 2 * 0.7978845608 * 1.4426950409
+    p.c3 = act == 3 ? 0.102943240f : 0.f;                                         // 0.044715 * 2.302208198
+    return p;
+}
+
+__device__ __forceinline__ float activate(float x, const ActParams &p)
+{
+    const float t = fmaxf(x, p.lo);
+    const float tc = __builtin_amdgcn_fmed3f(t, -1e15f, 1e15f);
+    const float z = tc * __builtin_fmaf(p.c3, tc * tc, p.c1);
+    const float gate = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-z));
+    return t * __builtin_fmaf(p.g0, gate, p.g1);
+}
+
 // Swizzled LDS position (in 16-bit elements) of 16-byte chunk `chunk` of row `row`.
 template <int BK>
 __device__ __forceinline__ int lds_chunk_pos(int row, int chunk)
@@ -138,10 +172,11 @@ template <int BM, int BN>
 __device__ __forceinline__ void store_tile_generic(void *C, const OperandMap &mc, int64_t c_batch_off,
                                                    float16v (&acc)[BM / 64][BN / 64], int64_t row0, int64_t col0,
                                                    int wave_m, int wave_n, int lane, int out_dtype,
-                                                   const void *D, const OperandMap &md, int64_t d_batch_off, float alpha, float beta)
+                                                   const void *D, const OperandMap &md, int64_t d_batch_off, float alpha, float beta, int act)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
     const int l32 = lane & 31, hi = lane >> 5;
+    const ActParams ap = act_params(act);
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int64_t col = col0 + wave_n * (BN / 2) + tn * 32 + l32;
@@ -162,7 +197,7 @@ __device__ __forceinline__ void store_tile_generic(void *C, const OperandMap &mc
                     } else {
                         x *= alpha;
                     }
-                    store_out(C, c_batch_off + off, x, out_dtype);
+                    store_out(C, c_batch_off + off, act ? activate(x, ap) : x, out_dtype);
                 }
             }
         }
@@ -175,7 +210,7 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, void *__restrict__ C,
     const OperandMap ma, const OperandMap mb, const OperandMap mc,
     int64_t sa_batch, int64_t sb_batch, int64_t sc_batch, int64_t mt, int64_t nt, int64_t kt, int out_dtype,
-    const void *__restrict__ D, const OperandMap md, int64_t sd_batch, float alpha, float beta)
+    const void *__restrict__ D, const OperandMap md, int64_t sd_batch, float alpha, float beta, int act)
 {
     __shared__ __attribute__((aligned(16))) uint16_t as[BM * BK];
     __shared__ __attribute__((aligned(16))) uint16_t bs[BN * BK];
@@ -225,7 +260,7 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(
         mma_tile<BM, BN, BK, BF16>(as, bs, acc, wave_m, wave_n, lane);
         __syncthreads();
     }
-    store_tile_generic<BM, BN>(C, mc, bi * sc_batch, acc, row0, col0, wave_m, wave_n, lane, out_dtype, D, md, bi * sd_batch, alpha, beta);
+    store_tile_generic<BM, BN>(C, mc, bi * sc_batch, acc, row0, col0, wave_m, wave_n, lane, out_dtype, D, md, bi * sd_batch, alpha, beta, act);
 }
 
 // ---- host-side helper shared by the translation units that instantiate the kernels

@@ -150,7 +150,6 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_ke
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = wave >> 1, wave_n = wave & 1;
-    const int l32 = lane & 31, hi = lane >> 5;
     const int64_t row0 = ti * BM, col0 = tj * BN;
 
     const char *gA = reinterpret_cast<const char *>(g.A + bi * g.sa_batch + (ALAY == KCONTIG ? row0 * g.lda : row0));

@@ -36,6 +36,7 @@ struct FastArgs {
     const void *D;
     int64_t sdm, sdn, sd_batch;
     float alpha, beta;
+    int32_t act;                   // activation of the combined value (0 = none)
 };
 
 __device__ __forceinline__ u32x4 gload16(const char *base, uint32_t off)
@@ -394,11 +395,12 @@ __device__ __forceinline__ void load_row16(const char *p, float (&d)[16])
 template <int BM, int BN, int OUT, bool CHECK>
 __device__ __forceinline__ void store_tile_regs(char *C, int64_t scm, const float16v (&acc)[BM / 64][BN / 64],
                                                 int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N,
-                                                bool affine, const char *D, int64_t sdm, float alpha, float beta)
+                                                bool affine, const char *D, int64_t sdm, float alpha, float beta, int act)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
     constexpr int ES = OUT == NT_F32 ? 4 : 2;
     const int l32 = lane & 31, hi = lane >> 5;
+    const ActParams ap = act_params(act);
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
         const int64_t row = row_w + tm * 32 + l32;
@@ -428,6 +430,10 @@ __device__ __forceinline__ void store_tile_regs(char *C, int64_t scm, const floa
                 }
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[i] = __builtin_bit_cast(uint32_t, combine(__builtin_bit_cast(float, o[i]), d[i], alpha, beta));
+                if (act) {                                            // wavefront-uniform
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[i] = __builtin_bit_cast(uint32_t, activate(__builtin_bit_cast(float, o[i]), ap));
+                }
             }
             if (row_ok && nv >= 16) {
                 if constexpr (OUT == NT_F32) {
@@ -471,7 +477,7 @@ __device__ __forceinline__ void store_tile_regs(char *C, int64_t scm, const floa
 template <int BM, int BN, int OUT, bool CHECK>
 __device__ __forceinline__ void store_tile_rows(char *smem, int wave, char *C, int64_t scm, const float16v (&acc)[BM / 64][BN / 64],
                                                 int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N,
-                                                bool affine, const char *D, int64_t sdm, float alpha, float beta)
+                                                bool affine, const char *D, int64_t sdm, float alpha, float beta, int act)
 {
     constexpr int TM = BM / 64, TN = BN / 64, WM = BM / 2, WN = BN / 2;
     constexpr int ES = OUT == NT_F32 ? 4 : 2;
@@ -483,6 +489,7 @@ __device__ __forceinline__ void store_tile_rows(char *smem, int wave, char *C, i
     constexpr int EPC = 16 / ES;                          // elements per chunk
     constexpr int RPI = 64 / CPR;                         // rows per store instruction
     const int l32 = lane & 31, hi = lane >> 5;
+    const ActParams ap = act_params(act);
     char *reg = smem + wave * (WM * RB);
 #pragma unroll
     for (int pass = 0; pass < PASSES; ++pass) {
@@ -515,6 +522,10 @@ __device__ __forceinline__ void store_tile_rows(char *smem, int wave, char *C, i
                     }
 #pragma unroll
                     for (int i = 0; i < 16; ++i) o[i] = __builtin_bit_cast(uint32_t, combine(__builtin_bit_cast(float, o[i]), d[i], alpha, beta));
+                if (act) {                                            // wavefront-uniform
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[i] = __builtin_bit_cast(uint32_t, activate(__builtin_bit_cast(float, o[i]), ap));
+                }
                 }
                 const int c0 = (tnp * 32 + 16 * hi) / EPC;
                 const int sw = (r >> RSH) & (CPR - 1);
@@ -560,10 +571,11 @@ __device__ __forceinline__ void store_tile_rows(char *smem, int wave, char *C, i
 template <int BM, int BN>
 __device__ __forceinline__ void store_tile_strided(void *C, int64_t scm, int64_t scn, const float16v (&acc)[BM / 64][BN / 64],
                                                    int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N, int out_dtype,
-                                                   const void *D, int64_t sdm, int64_t sdn, float alpha, float beta)
+                                                   const void *D, int64_t sdm, int64_t sdn, float alpha, float beta, int act)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
     const int l32 = lane & 31, hi = lane >> 5;
+    const ActParams ap = act_params(act);
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
         const int64_t row = row_w + tm * 32 + l32;
@@ -574,7 +586,8 @@ __device__ __forceinline__ void store_tile_strided(void *C, int64_t scm, int64_t
                 const int64_t col = col_w + tn * 32 + 8 * (v / 4) + 4 * hi + (v % 4);
                 if (row < M && col < N) {
                     const float d = D ? load_as_f32(D, row * sdm + col * sdn, out_dtype) : 0.f;
-                    store_out(C, row * scm + col * scn, combine(acc[tm][tn][v], d, alpha, beta), out_dtype);
+                    const float x = combine(acc[tm][tn][v], d, alpha, beta);
+                    store_out(C, row * scm + col * scn, act ? activate(x, ap) : x, out_dtype);
                 }
             }
     }
@@ -592,13 +605,13 @@ __device__ __forceinline__ void store_tile(const FastArgs &g, char *smem, int wa
     const char *D = g.D ? reinterpret_cast<const char *>(g.D) + bi * g.sd_batch * esz : nullptr;
     if constexpr (EDGE) {       // (launches with such a C or D always take the EDGE flavour)
         if (g.scn != 1 || (D && g.sdn != 1)) {
-            store_tile_strided<BM, BN>(C, g.scm, g.scn, acc, row_w, col_w, lane, g.M, g.N, g.out_dtype, D, g.sdm, g.sdn, g.alpha, g.beta);
+            store_tile_strided<BM, BN>(C, g.scm, g.scn, acc, row_w, col_w, lane, g.M, g.N, g.out_dtype, D, g.sdm, g.sdn, g.alpha, g.beta, g.act);
             return;
         }
     }
-    const bool affine = D != nullptr || g.alpha != 1.f;
-#define NT_ROWS(CHECK) store_tile_rows<BM, BN, NT_F32, CHECK>(smem, wave, C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta)
-#define NT_REGS(OUT, CHECK) store_tile_regs<BM, BN, OUT, CHECK>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta)
+    const bool affine = D != nullptr || g.alpha != 1.f || g.act != 0;
+#define NT_ROWS(CHECK) store_tile_rows<BM, BN, NT_F32, CHECK>(smem, wave, C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta, g.act)
+#define NT_REGS(OUT, CHECK) store_tile_regs<BM, BN, OUT, CHECK>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta, g.act)
     if constexpr (EDGE) {
         if (ragged) {
             if (g.out_dtype == NT_F32) NT_ROWS(true);

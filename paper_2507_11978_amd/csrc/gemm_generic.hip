@@ -12,12 +12,12 @@ static nt_status launch_generic_t(const GemmLaunch &g)
         hipLaunchKernelGGL((gemm_generic_kernel<BM, BN, BK, true>), grid, dim3(kThreads), 0, s,
                            (const uint16_t *)g.A, (const uint16_t *)g.B, g.C, g.ma, g.mb, g.mc,
                            g.sa_batch, g.sb_batch, g.sc_batch, g.mt, g.nt, g.kt, g.out_dtype,
-                           g.has_d ? g.D : nullptr, g.md, g.sd_batch, g.alpha, g.beta);
+                           g.has_d ? g.D : nullptr, g.md, g.sd_batch, g.alpha, g.beta, g.act);
     else
         hipLaunchKernelGGL((gemm_generic_kernel<BM, BN, BK, false>), grid, dim3(kThreads), 0, s,
                            (const uint16_t *)g.A, (const uint16_t *)g.B, g.C, g.ma, g.mb, g.mc,
                            g.sa_batch, g.sb_batch, g.sc_batch, g.mt, g.nt, g.kt, g.out_dtype,
-                           g.has_d ? g.D : nullptr, g.md, g.sd_batch, g.alpha, g.beta);
+                           g.has_d ? g.D : nullptr, g.md, g.sd_batch, g.alpha, g.beta, g.act);
     return check_launch("gemm_generic_kernel");
 }
 

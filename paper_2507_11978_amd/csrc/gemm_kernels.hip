@@ -98,7 +98,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
     if (path_out) *path_out = fast ? PATH_FAST : PATH_GENERIC;
     if (!fast) {
         ConvArgs c{};
-        if (!g.has_d && g.alpha == 1.f && match_conv(g, &c)) {
+        if (!g.has_d && g.alpha == 1.f && g.act == 0 && match_conv(g, &c)) {
             if (path_out) *path_out = PATH_CONV;
             const bool edge_b = (g.N % t.bn) || (g.K % t.bk);
             return launch_conv(c, t.bn, g.in_dtype == NT_BF16, edge_b, g.mt * g.nt, (hipStream_t)g.stream);
@@ -118,6 +118,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         a.out_dtype = g.out_dtype;
         a.alpha = g.alpha;
         a.beta = g.has_d ? g.beta : 0.f;
+        a.act = g.act;
         if (g.has_d) {
             a.D = (const char *)g.D + g.md.base * esz;
             a.sdm = g.md.roff[0];

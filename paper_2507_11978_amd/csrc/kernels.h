@@ -35,6 +35,7 @@ struct GemmLaunch {
     OperandMap md;
     int64_t sd_batch;
     float alpha, beta;
+    int act;                                // activation of the combined value (nt_activation)
     bool has_d;
     ConvHint conv;
 };

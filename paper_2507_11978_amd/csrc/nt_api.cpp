@@ -144,7 +144,7 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
               void *C, const nt_tensor_desc *dC, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
               nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *stream,
               const void *D = nullptr, const nt_tensor_desc *dD = nullptr, float alpha = 1.f, float beta = 0.f,
-              const ViewPrograms *views = nullptr)
+              const ViewPrograms *views = nullptr, int act = 0)
 {
     t_last_path = -1;
     if (!dtype_in_ok(in_dtype)) return fail(NT_ERR_UNSUPPORTED, "input dtype must be NT_F16 or NT_BF16");
@@ -162,6 +162,7 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
     NT_TRY(p.vc.lower_matrix_view(&g.mc, &nb, &g.sc_batch));
     g.alpha = alpha;
     g.beta = beta;
+    g.act = act;
     g.has_d = dD != nullptr && beta != 0.f;
     if (g.has_d) {
         if (!D) return fail(NT_ERR_INVALID_ARG, "null input pointer with beta != 0");
@@ -175,7 +176,7 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
     if (p.K == 0) {
         if (!g.has_d) return nt::launch_fill_zero(C, g.mc, p.batch, g.sc_batch, out_dtype, stream);
         // C = beta * input: the operand-map kernel with no k tiles (its grid is that of the 64 x 64 tile)
-        if (p.tile.bm != 64) return run(kind, A, dA, B, dB, C, dC, sh, sw, ph, pw, in_dtype, out_dtype, nt_tile_cfg{64, 64, 32}, stream, D, dD, alpha, beta);
+        if (p.tile.bm != 64) return run(kind, A, dA, B, dB, C, dC, sh, sw, ph, pw, in_dtype, out_dtype, nt_tile_cfg{64, 64, 32}, stream, D, dD, alpha, beta, views, act);
     }
     if (kind == KIND_CONV) {
         nt::ConvHint &h = g.conv;
@@ -301,6 +302,18 @@ nt_status nt_addmm(const void *input, const nt_tensor_desc *dI, const void *A, c
     if (!dI) return fail(NT_ERR_INVALID_ARG, "null tensor descriptor");
     if (!(alpha == alpha) || !(beta == beta)) return fail(NT_ERR_INVALID_ARG, "alpha / beta is NaN");
     return run(KIND_GEMM, A, dA, B, dB, C, dC, 1, 1, 0, 0, in_dtype, out_dtype, cfg, hip_stream, input, dI, alpha, beta);
+}
+
+nt_status nt_addmm_act(const void *input, const nt_tensor_desc *dI, const void *A, const nt_tensor_desc *dA,
+                       const void *B, const nt_tensor_desc *dB, void *C, const nt_tensor_desc *dC,
+                       float alpha, float beta, nt_activation act, nt_dtype in_dtype, nt_dtype out_dtype,
+                       nt_tile_cfg cfg, void *hip_stream)
+{
+    if (!(alpha == alpha) || !(beta == beta)) return fail(NT_ERR_INVALID_ARG, "alpha / beta is NaN");
+    if (act != NT_ACT_NONE && act != NT_ACT_RELU && act != NT_ACT_SILU && act != NT_ACT_GELU_TANH)
+        return fail(NT_ERR_INVALID_ARG, "unknown activation");
+    if (!dI && beta != 0.f) return fail(NT_ERR_INVALID_ARG, "null input descriptor with beta != 0");
+    return run(KIND_GEMM, A, dA, B, dB, C, dC, 1, 1, 0, 0, in_dtype, out_dtype, cfg, hip_stream, input, dI, alpha, beta, nullptr, (int)act);
 }
 
 static nt_status check_1d(const nt_tensor_desc *d, const void *p, int64_t *n, int64_t *stride)

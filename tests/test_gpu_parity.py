@@ -201,6 +201,54 @@ def test_addmm_strided_input_transposed_output_and_k_zero():
         nt.addmm(It, to_gpu(A, dt), to_gpu(B, dt), torch.empty((M, N), dtype=torch.float32, device="cuda"))   # [N, M] input
 
 
+@pytest.mark.parametrize("act", ["relu", "silu", "gelu_tanh"])
+@pytest.mark.parametrize("M,N,K,tile,out,path", [(512, 512, 256, (256, 256, 64), "f16", "direct"), (256, 384, 128, (128, 128, 64), "f32", "direct"),
+                                                 (301, 263, 131, (256, 256, 64), "bf16", "staged"), (300, 264, 200, (128, 256, 64), "f32", "staged"),
+                                                 (150, 170, 90, (64, 64, 32), "f16", "generic")])
+def test_addmm_fused_activation(M, N, K, tile, out, path, act):
+    """act(beta * bias + alpha * (A . B)): the activation acts on the fp32 combined value in every epilogue."""
+    dt = "f16"
+    A, B = si.gemm_inputs(M, N, K, dt, seed=51, dist="normal")
+    A = si.round_to_bits(onum.decode(A, dt).astype(np.float32) * 12.0, dt)         # spread the results over the activations' bends
+    bias = torch.from_numpy(np.random.default_rng(52).standard_normal((N,)).astype(np.float32)).to(TORCH_DT[out]).cuda()
+    ref = onum.addmm_act(to_f64(bias), A, B, dt, act, alpha=0.5, beta=2.0)
+    C = torch.full((M, N), float("nan"), dtype=TORCH_DT[out], device="cuda")
+    nt.addmm(bias, to_gpu(A, dt), to_gpu(B, dt), C, alpha=0.5, beta=2.0, tile=tile, act=act)
+    torch.cuda.synchronize()
+    assert nt.last_kernel_path() == {"direct": nt.PATH_DIRECT, "staged": nt.PATH_STAGED, "generic": nt.PATH_GENERIC}[path]
+    if out == "f32":
+        # fp32 accumulation plus the activation's fast exponential / reciprocal (a few ulp of fp32)
+        assert np.abs(to_f64(C) - ref).max() <= 2e-5 * max(1.0, np.abs(ref).max())
+    else:
+        assert_gates(to_f64(C), ref, out, f"addmm_act {act} {M}x{N}x{K} {tile} {out}")
+    assert (to_f64(C) < 0).any() == (act != "relu")                                 # the case does reach the negative side
+
+
+def test_addmm_activation_without_input_strided_output_and_errors():
+    dt, M, N, K = "bf16", 136, 200, 64
+    A, B = si.gemm_inputs(M, N, K, dt, seed=61, dist="int")
+    prod = onum.gemm(A, B, dt)
+    a, b = to_gpu(A, dt), to_gpu(B, dt)
+    for tile in [(64, 64, 32), (128, 128, 64)]:
+        C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        nt.addmm(None, a, b, C, alpha=-1.0, beta=0.0, tile=tile, act="relu")         # exact: small integers
+        Ct = torch.full((N, M), float("nan"), dtype=torch.float32, device="cuda")
+        nt.addmm(None, a, b, Ct.t(), alpha=-1.0, beta=0.0, tile=tile, act="relu")    # column-major C: element-wise store routine
+        torch.cuda.synchronize()
+        assert np.array_equal(to_f64(C), np.maximum(-prod, 0.0)) and np.array_equal(to_f64(Ct.t()), np.maximum(-prod, 0.0))
+    # K = 0: act(beta * input)
+    inp = torch.from_numpy(np.random.default_rng(62).integers(-8, 8, (M, N)).astype(np.float32)).cuda()
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    nt.addmm(inp, torch.empty((M, 0), dtype=torch.bfloat16, device="cuda"), torch.empty((0, N), dtype=torch.bfloat16, device="cuda"), C,
+             alpha=1.0, beta=-1.0, act="relu")
+    torch.cuda.synchronize()
+    assert np.array_equal(to_f64(C), np.maximum(-to_f64(inp), 0.0))
+    with pytest.raises(ValueError):
+        nt.addmm(inp, a, b, C, act="tanh")
+    with pytest.raises(nt.NtError):
+        nt.addmm(None, a, b, C, beta=1.0, act="relu")                                # beta != 0 needs an input
+
+
 def test_general_strides_and_padded_pitch():
     dt, M, N, K = "bf16", 150, 170, 90
     A, B = si.gemm_inputs(M, N, K, dt, seed=4, dist="uniform")
