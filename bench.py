@@ -37,7 +37,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default 50; 2000 for the kernels that run for tens of microseconds)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 50; 1000 for those short kernels)")
     ap.add_argument("--workload", default="p_f16_8192",
-                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c1_f16_256, f1_f16_addmm, f3_f16_add, f3_f16_silu, f3_f16_softmax, f3_f16_rms_norm, f4_f16_sdpa")
+                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c1_f16_256, f1_f16_addmm, f1_f16_bias_gelu, f3_f16_add, f3_f16_silu, f3_f16_softmax, f3_f16_rms_norm, f4_f16_sdpa")
     ap.add_argument("--tile", default=None, help="bm,bn,bk (default: library choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -64,7 +64,9 @@ def flops_and_bytes(cfg):
         return 2.0 * N * P * Q * K * C * R * S, 2 * (N * C * H * W + K * C * R * S) + osz * N * K * P * Q
     b = cfg.get("batch", 1)
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
-    extra = osz * M * N if cfg["kind"] == "addmm" else 0            # the added input is read once
+    extra = 0
+    if cfg["kind"] == "addmm":                                       # the added input is read once
+        extra = osz * N if cfg.get("bias") == "row" else osz * M * N
     return 2.0 * b * M * N * K, b * (2 * (M * K + K * N) + osz * M * N) + extra
 
 
@@ -252,9 +254,9 @@ def main():
         shape = (cfg["batch"], cfg["M"], cfg["N"]) if cfg["kind"] == "bmm" else (cfg["M"], cfg["N"])
         y = torch.empty(shape, dtype=TORCH_DT[out], device="cuda")
         if cfg["kind"] == "addmm":
-            Ib = si.normal_bits((cfg["M"], cfg["N"]), out, cfg["seed"] + 2, 1.0)
+            Ib = si.normal_bits((cfg["N"],) if cfg.get("bias") == "row" else (cfg["M"], cfg["N"]), out, cfg["seed"] + 2, 1.0)
             inp = to_gpu(Ib, out)
-            step = lambda: nt.addmm(inp, a, b, y, alpha=cfg["alpha"], beta=cfg["beta"], tile=tile)
+            step = lambda: nt.addmm(inp, a, b, y, alpha=cfg["alpha"], beta=cfg["beta"], tile=tile, act=cfg.get("act"))
         else:
             fn = nt.gemm if cfg["kind"] == "gemm" else nt.bmm
             step = lambda: fn(a, b, y, tile=tile)
@@ -312,7 +314,8 @@ def main():
             A2, B2 = (Ab[bsel], Bb[bsel]) if cfg["kind"] == "bmm" else (Ab, Bb)
             ref = onum.gemm_samples(A2, B2, dt, ms, ns)
             if cfg["kind"] == "addmm":
-                ref = cfg["beta"] * onum.decode(Ib, out)[ms, ns] + cfg["alpha"] * ref
+                Iv = onum.decode(Ib, out)
+                ref = onum.activation(cfg["beta"] * (Iv[ns] if cfg.get("bias") == "row" else Iv[ms, ns]) + cfg["alpha"] * ref, cfg.get("act"))
             yy = y[bsel] if cfg["kind"] == "bmm" else y
             got = to_f64(yy[torch.from_numpy(ms).cuda(), torch.from_numpy(ns).cuda()])
         result["parity"] = {"samples": int(ref.size), "max_abs_err": float(np.abs(got - ref).max()),

@@ -3,9 +3,15 @@
 //
 // Arrangement: Q and O are tiled into blocks of 128 query rows, one program per (batch, head,
 // block); K and V are tiled into blocks of 64 keys, all of which every program visits in turn.
-// Application (per program): running row maximum m and row sum l, accumulator O; per key block
-//   S = scale * Q K_j^T;  m' = max(m, rowmax S);  P = exp(S - m');  l = l e^(m - m') + rowsum P;
-//   O = O e^(m - m') + P V_j;       finally O / l.
+// Application (per program): a row reference M (close to the running row maximum), row sum l,
+// accumulator O; per key block
+//   S = Q K_j^T;  P = 2^(c S - M)  (c = scale * log2 e);  l += rowsum P;  O += P V_j;   finally O / l.
+// M only has to stay within a band of the running maximum for this to be exact up to rounding:
+// every term carries the same factor 2^-M, which cancels in O / l.  M is raised (and O, l scaled
+// by 2^(M - M')) when a block holds a score more than 15 above it, which the row sum of that block
+// reveals (2^15 is half the largest fp16 number), and it is set to the block's maximum at the first
+// block.  FlashAttention-2 raises M to the exact maximum at every block; keeping a lagging one
+// removes the maximum search from all but a few blocks.
 //
 // Mapping onto the matrix cores: everything is computed transposed.  A wavefront owns 32 query
 // rows.  S^T = K_j Q^T puts the query on the lane axis of the 32 x 32 MFMA result (lane % 32) and
@@ -15,9 +21,9 @@
 // operand of the second product O^T = V_j^T P^T if the matching A operand lists the keys in the
 // same order: V_j sits in LDS as [key][d] and the transposing LDS read (ds_read_b64_tr_b16)
 // delivers, for a lane's d, four consecutive keys at any position.  O^T again has the query on
-// the lane axis, so rescaling by e^(m - m') is a per-lane scalar.  Q fragments stay in registers.
+// the lane axis, so rescaling by 2^(M - M') is a per-lane scalar.  Q fragments stay in registers.
 // K_j and V_j go global -> registers -> LDS (double buffered), the next block's loads in flight
-// during the current block's arithmetic; 32 KB of LDS and ~128 registers per workgroup let
+// during the current block's arithmetic; 32 KB of LDS and ~160 registers per workgroup let
 // several workgroups share a compute unit, which hides the exponentials of one behind the MFMAs
 // of another.
 #include "gemm_fast.h"
@@ -33,6 +39,7 @@ struct SdpaArgs {
     int64_t v_sb, v_sh, v_ss;
     int64_t o_sb, o_sh, o_ss;
     int32_t H, Sq, Sk;
+    int32_t BH, nqb;                 // batch * heads, query blocks per head (the grid is their product)
     float scale_log2e;               // scale * log2(e): exponentials are taken in base 2
 };
 
@@ -40,15 +47,24 @@ constexpr int kHeadDim = 64, kQBlock = 128, kKeyBlock = 64;
 
 typedef short short4v_a __attribute__((ext_vector_type(4)));
 
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+
+// two fp32 values -> one register of two 16-bit values, round to nearest even (v_cvt_pk_{f16,bf16}_f32)
 template <bool BF16>
 __device__ __forceinline__ uint32_t pack2(float a, float b)
 {
-    if constexpr (BF16) {
-        return (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
-    } else {
-        typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-        return __builtin_bit_cast(uint32_t, half2v{(_Float16)a, (_Float16)b});
-    }
+    if constexpr (BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(float2v{a, b}, bf16x2v));
+    else return __builtin_bit_cast(uint32_t, half2v{(_Float16)a, (_Float16)b});
+}
+
+// acc + the two 16-bit values of w (v_dot2c_f32_{f16,bf16} against a pair of ones)
+template <bool BF16>
+__device__ __forceinline__ float add_pair(uint32_t w, float acc)
+{
+    if constexpr (BF16) return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2v, w), __builtin_bit_cast(bf16x2v, 0x3f803f80u), acc, false);
+    else return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, w), __builtin_bit_cast(half2v, 0x3c003c00u), acc, false);
 }
 
 template <bool BF16>
@@ -58,14 +74,24 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
     __shared__ __attribute__((aligned(16))) char smem[4 * BLK];        // [K0][K1][V0][V1]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
-    const int b = blockIdx.y / g.H, h = blockIdx.y % g.H;
+    // Workgroup -> (batch * head, query block).  Consecutive workgroup indices go to different XCDs (index mod 8),
+    // each with an L2 of its own; the query blocks of one head all read that head's K and V, so every group of
+    // eight heads is dealt out one head per XCD instead of one head across all eight.
+    const int w = blockIdx.x, nqb = g.nqb;
+    int bh = w / nqb, qblk = w % nqb;
+    if (w < (g.BH & ~7) * nqb) {
+        const int j = w >> 3;
+        bh = (j / nqb) * 8 + (w & 7);
+        qblk = j % nqb;
+    }
+    const int b = bh / g.H, h = bh % g.H;
     const uint16_t *Qp = g.Q + b * g.q_sb + h * g.q_sh;
     const uint16_t *Kp = g.K + b * g.k_sb + h * g.k_sh;
     const uint16_t *Vp = g.V + b * g.v_sb + h * g.v_sh;
     uint16_t *Op = g.O + b * g.o_sb + h * g.o_sh;
 
     // ---- Q fragments (B operand of S^T = K Q^T: column = query l32, 8 consecutive d per k step)
-    const int qrow = blockIdx.x * kQBlock + wave * 32 + l32;
+    const int qrow = qblk * kQBlock + wave * 32 + l32;
     const int qrow_c = qrow < g.Sq ? qrow : g.Sq - 1;
     u32x4 qf[4];
 #pragma unroll
@@ -119,7 +145,8 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
     for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int v = 0; v < 16; ++v) ot[db][v] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_ref = 0.f, l_run = 0.f;                                    // row reference M (base-2 units of the scaled scores), row sum
+    bool first = true;
 
     const int nblk = (g.Sk + kKeyBlock - 1) / kKeyBlock;
     fetch(0);
@@ -142,8 +169,7 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
                 st[jb] = mfma32<BF16>(kf, qf[ks], st[jb]);
             }
         }
-        // ---- mask keys past Sk (last block only), running maximum.  The scale (> 0 or < 0) is folded
-        // into the exponent below: m tracks max(scale * S) in base-2 units.
+        // ---- keys past Sk (last block only) get weight 0: their scaled score becomes -inf
         const int key_base = kb * kKeyBlock;
         if (key_base + kKeyBlock > g.Sk) {                                // wavefront-uniform
             const float out = g.scale_log2e >= 0.f ? -INFINITY : INFINITY;
@@ -153,45 +179,48 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
                 for (int v = 0; v < 16; ++v)
                     if (key_base + jb * 32 + 8 * (v / 4) + 4 * hi + (v % 4) >= g.Sk) st[jb][v] = out;
         }
-        float mx = st[0][0];
-        if (g.scale_log2e >= 0.f) {                                      // wavefront-uniform
-#pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, st[jb][v]);
-        } else {
-#pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fminf(mx, st[jb][v]);
-        }
-        mx *= g.scale_log2e;                                             // max of the scaled scores
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 0 at the first block (m_run = -inf)
-        m_run = m_new;
-        // ---- P^T = exp2(scale * S^T - m), its row sum (this lane's keys only; the halves are added at the end), packed to 16 bits
-        float rs = 0.f;
+        // ---- P^T = 2^(c S^T - M), packed to 16 bits, and its row sum (this lane's keys only; the halves are added at the end)
+        float rs;
         u32x4 pk[2][2];
+        auto exponentials = [&](const float m) {
+            rs = 0.f;
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
+            for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                float p[8];
+                for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    p[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[jb][8 * s2 + j], g.scale_log2e, -m_new));
-                    rs += p[j];
-                }
-                pk[jb][s2] = u32x4{pack2<BF16>(p[0], p[1]), pack2<BF16>(p[2], p[3]), pack2<BF16>(p[4], p[5]), pack2<BF16>(p[6], p[7])};
-            }
-        l_run = l_run * alpha + rs;
-        if (__any(alpha != 1.0f)) {                                      // the maximum rarely moves after the first blocks
+                    for (int j = 0; j < 4; ++j) {
+                        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[jb][8 * s2 + 2 * j], g.scale_log2e, -m));
+                        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[jb][8 * s2 + 2 * j + 1], g.scale_log2e, -m));
+                        const uint32_t w = pack2<BF16>(p0, p1);
+                        pk[jb][s2][j] = w;
+                        rs = add_pair<BF16>(w, rs);
+                    }
+        };
+        bool accept = false;
+        if (!first) {
+            exponentials(m_ref);
+            accept = __all(rs < 32768.f);                                // no weight beyond 2^15: the reference is close enough
+        }
+        if (!accept) {                                                   // wavefront-uniform: first block, or a score far above M
+            float mx = st[0][0] * g.scale_log2e;
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, st[jb][v] * g.scale_log2e);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                      // block maximum of the scaled scores
+            const float m_new = first ? mx : fmaxf(m_ref, mx);           // M only rises after the first block
+            const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(m_ref - m_new);
+            exponentials(m_new);
+            l_run *= alpha;
 #pragma unroll
             for (int db = 0; db < 2; ++db)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) ot[db][v] *= alpha;
+            m_ref = m_new;
+            first = false;
         }
+        l_run += rs;
         // ---- O^T += V^T P^T: k step (jb, s2) lists its 16 keys as jb*32 + 16 s2 + 8 part + 4 hi + 0..3
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
@@ -246,11 +275,14 @@ __global__ __launch_bounds__(256, 2) void sdpa_kernel(const SdpaArgs g)
 nt_status launch_sdpa(const SdpaArgs &a, int64_t batch, bool bf16, void *stream)
 {
     if (batch <= 0 || a.H <= 0 || a.Sq <= 0) return NT_OK;
-    const int64_t bh = batch * a.H;
-    if (bh > 65535) return fail(NT_ERR_UNSUPPORTED, "batch * heads exceeds 65535");
-    dim3 grid((unsigned)((a.Sq + kQBlock - 1) / kQBlock), (unsigned)bh), block(256);
-    if (bf16) hipLaunchKernelGGL((sdpa_kernel<true>), grid, block, 0, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL((sdpa_kernel<false>), grid, block, 0, (hipStream_t)stream, a);
+    const int64_t bh = batch * a.H, nqb = (a.Sq + kQBlock - 1) / kQBlock;
+    if (bh * nqb > 0x7fffffffLL) return fail(NT_ERR_UNSUPPORTED, "batch * heads * query blocks exceeds 2^31 - 1");
+    SdpaArgs k = a;
+    k.BH = (int32_t)bh;
+    k.nqb = (int32_t)nqb;
+    dim3 grid((unsigned)(bh * nqb)), block(256);
+    if (bf16) hipLaunchKernelGGL((sdpa_kernel<true>), grid, block, 0, (hipStream_t)stream, k);
+    else hipLaunchKernelGGL((sdpa_kernel<false>), grid, block, 0, (hipStream_t)stream, k);
     return check_launch("sdpa_kernel");
 }
 

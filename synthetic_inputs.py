@@ -85,6 +85,8 @@ CONFIGS = {
     "c4_f16_bmm": dict(kind="bmm", batch=32, M=2048, N=2048, K=512, dtype="f16", out="f16", dist="normal", seed=0),
     "p_f16_8192": dict(kind="gemm", M=8192, N=8192, K=8192, dtype="f16", out="f16", dist="normal", seed=0),
     "f1_f16_addmm": dict(kind="addmm", M=4096, N=4096, K=4096, dtype="f16", out="f16", dist="normal", seed=0, alpha=1.0, beta=1.0),
+    "f1_f16_bias_gelu": dict(kind="addmm", M=4096, N=4096, K=4096, dtype="f16", out="f16", dist="normal", seed=0, alpha=1.0, beta=1.0,
+                             bias="row", act="gelu_tanh"),
     "f3_f16_add": dict(kind="add", n=16777216, dtype="f16", out="f16", seed=0),
     "f3_f16_silu": dict(kind="silu", n=16777216, dtype="f16", out="f16", seed=0),
     "f3_f16_softmax": dict(kind="softmax", rows=4096, cols=4096, dtype="f16", out="f16", seed=0),
