@@ -129,10 +129,8 @@ __device__ __forceinline__ int lds_chunk_pos(int row, int chunk)
 // everything derived from them is wavefront-uniform for the compiler as well.
 __device__ __forceinline__ void locate_program(int64_t mt, int64_t nt, int64_t *b, int64_t *i, int64_t *j)
 {
-    const int64_t per = mt * nt;
-    const int64_t w = blockIdx.x;
-    const int64_t bb = w / per;
-    const int64_t pid = program_of_workgroup(w - bb * per, mt, nt);
+    int64_t bb, pid;
+    program_of_workgroup_batched(blockIdx.x, (int64_t)gridDim.x / (mt * nt), mt, nt, &bb, &pid);
     *b = __builtin_amdgcn_readfirstlane((int)bb);
     *i = __builtin_amdgcn_readfirstlane((int)(pid / nt));
     *j = __builtin_amdgcn_readfirstlane((int)(pid % nt));

@@ -61,19 +61,11 @@ nt_status launch_sdpa_desc(const void *q, const nt_tensor_desc *dq, const void *
                            float scale, int dtype, void *stream);
 
 // workgroup index -> logical program id (shared by host query and device code)
-NT_HD int64_t program_of_workgroup(int64_t w, int64_t mt, int64_t nt)
+// Position seq of the tile sequence -> program id: the grid is walked in bands of up to 8 tile
+// rows, column by column inside a band, so that programs that run at the same time share operand
+// rows / columns.
+NT_HD int64_t program_of_sequence(int64_t seq, int64_t mt, int64_t nt)
 {
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one contiguous share of
-    // the tile sequence so that tiles resident on one L2 share operand rows / columns, and
-    // walk that sequence in bands of up to 8 tile rows.
-    const int64_t G = mt * nt;
-    const int64_t nx = 8;
-    int64_t seq;
-    {
-        const int64_t q = G / nx, r = G % nx;      // first r XCDs get q+1 tiles
-        const int64_t x = w % nx, l = w / nx;
-        seq = x < r ? x * (q + 1) + l : r * (q + 1) + (x - r) * q + l;
-    }
     const int64_t band = 8;
     const int64_t per_band = band * nt;
     const int64_t b = seq / per_band;
@@ -83,6 +75,35 @@ NT_HD int64_t program_of_workgroup(int64_t w, int64_t mt, int64_t nt)
     const int64_t i = first + in % rows;
     const int64_t j = in / rows;
     return i * nt + j;
+}
+
+NT_HD int64_t program_of_workgroup(int64_t w, int64_t mt, int64_t nt)
+{
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one contiguous share of
+    // the tile sequence so that tiles resident on one L2 share operand rows / columns.
+    const int64_t G = mt * nt;
+    const int64_t nx = 8;
+    const int64_t q = G / nx, r = G % nx;          // first r XCDs get q+1 tiles
+    const int64_t x = w % nx, l = w / nx;
+    const int64_t seq = x < r ? x * (q + 1) + l : r * (q + 1) + (x - r) * q + l;
+    return program_of_sequence(seq, mt, nt);
+}
+
+// Batched grids (nb problems of mt x nt programs): every complete group of 8 problems is dealt out
+// one whole problem per XCD (its operands then pass through one L2 only); the problems left over are
+// split across the XCDs like a single problem.
+NT_HD void program_of_workgroup_batched(int64_t w, int64_t nb, int64_t mt, int64_t nt, int64_t *b, int64_t *pid)
+{
+    const int64_t per = mt * nt;
+    if (w < (nb / 8) * 8 * per) {
+        const int64_t l = w / 8;
+        *b = (l / per) * 8 + w % 8;
+        *pid = program_of_sequence(l % per, mt, nt);
+    } else {
+        const int64_t bb = w / per;
+        *b = bb;
+        *pid = program_of_workgroup(w - bb * per, mt, nt);
+    }
 }
 
 }  // namespace nt

@@ -265,8 +265,9 @@ nt_status nt_program_order(int64_t batch, int64_t mt, int64_t nt_, int64_t *pid_
     if (batch < 0 || mt < 0 || nt_ < 0) return fail(NT_ERR_INVALID_ARG, "negative grid size");
     const int64_t per = mt * nt_;
     for (int64_t w = 0; w < batch * per; ++w) {
-        const int64_t b = w / per;
-        pid_out[w] = b * per + nt::program_of_workgroup(w - b * per, mt, nt_);
+        int64_t b, pid;
+        nt::program_of_workgroup_batched(w, batch, mt, nt_, &b, &pid);
+        pid_out[w] = b * per + pid;
     }
     return NT_OK;
 }

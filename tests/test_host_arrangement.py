@@ -147,12 +147,17 @@ def test_conv_arrangement(shape, stride, pad, full):
 
 # ----------------------------------------------------------------- program order swizzle
 @pytest.mark.parametrize("batch,mt,nt_", [(1, 4, 4), (1, 16, 16), (1, 12, 20), (32, 8, 8), (1, 32, 32), (1, 392, 2),
-                                          (1, 1, 1), (1, 7, 3), (2, 9, 1), (1, 47, 79)])
+                                          (1, 1, 1), (1, 7, 3), (2, 9, 1), (1, 47, 79), (19, 5, 3), (8, 1, 1)])
 def test_program_order_is_a_bijection(batch, mt, nt_):
     order = nt.program_order(batch, mt, nt_)
     assert np.array_equal(np.sort(order), np.arange(batch * mt * nt_))
     per = mt * nt_
-    for b in range(batch):                       # each batch entry keeps its own block of programs
+    full = batch // 8 * 8
+    for g in range(full // 8):                   # a complete group of 8 problems: one whole problem per XCD (workgroup index mod 8)
+        blk = order[g * 8 * per:(g + 1) * 8 * per]
+        for x in range(8):
+            assert set(blk[x::8].tolist()) == set(range((g * 8 + x) * per, (g * 8 + x + 1) * per))
+    for b in range(full, batch):                 # the problems left over keep their own block of workgroups
         assert set(order[b * per:(b + 1) * per].tolist()) == set(range(b * per, (b + 1) * per))
 
 
