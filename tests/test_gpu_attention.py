@@ -80,3 +80,23 @@ def test_sdpa_negative_scale():
     dt = "f16"
     q, k, v = (si.normal_bits((1, 2, 90, 64), dt, 40 + i, 1.0) for i in range(3))
     assert_gates(run(q, k, v, dt, scale=-0.3), oat.sdpa(q, k, v, dt, scale=-0.3), dt, "sdpa negative scale")
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+def test_sdpa_scores_rising_along_the_keys(dt):
+    """Keys grow along the sequence, so a row's maximum keeps rising (or falling) from block to block: some
+    blocks stay within the band the kernel tolerates between its row reference and the running maximum, others
+    force the reference up."""
+    rng = np.random.default_rng(70)
+    S, Sk = 96, 640
+    w = rng.standard_normal(64).astype(np.float32)
+    w /= np.linalg.norm(w)
+    for per_block in (3.0, 11.0, 40.0):                       # rise of the top score per 64 keys, in base-2 units
+        q = rng.standard_normal((1, 2, S, 64)).astype(np.float32)
+        proj = np.abs(q @ w).mean()
+        step = per_block / 64.0 / (proj * 0.125 * 1.4427)      # so that scale * q . k_j grows by ~per_block per block
+        kf = (np.arange(Sk, dtype=np.float32)[:, None] * step) * w[None, :] + 0.05 * rng.standard_normal((Sk, 64)).astype(np.float32)
+        kf = np.broadcast_to(kf, (1, 2, Sk, 64))
+        qb, kb = si.round_to_bits(q, dt), si.round_to_bits(np.ascontiguousarray(kf), dt)
+        vb = si.normal_bits((1, 2, Sk, 64), dt, 71, 1.0)
+        assert_gates(run(qb, kb, vb, dt), oat.sdpa(qb, kb, vb, dt), dt, f"sdpa rising scores {per_block} {dt}")
