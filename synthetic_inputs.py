@@ -92,6 +92,8 @@ CONFIGS = {
     "f3_f16_softmax": dict(kind="softmax", rows=4096, cols=4096, dtype="f16", out="f16", seed=0),
     "f3_f16_rms_norm": dict(kind="rms_norm", rows=4096, cols=4096, dtype="f16", out="f16", seed=0, eps=1e-6),
     "f4_f16_sdpa": dict(kind="sdpa", B=4, H=48, S=1024, D=64, dtype="f16", out="f16", seed=0),
+    "f4_bf16_sdpa": dict(kind="sdpa", B=4, H=48, S=1024, D=64, dtype="bf16", out="bf16", seed=0),
+    "f4_f16_sdpa_4k": dict(kind="sdpa", B=1, H=48, S=4096, D=64, dtype="f16", out="f16", seed=0),
     "c5_f16_conv": dict(kind="conv", N=32, C=256, H=56, W=56, K=256, R=3, S=3, stride=1, pad=1,
                         dtype="f16", out="f16", seed=0),
 }
