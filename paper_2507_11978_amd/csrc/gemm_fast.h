@@ -37,6 +37,8 @@ struct FastArgs {
     int64_t sdm, sdn, sd_batch;
     float alpha, beta;
     int32_t act;                   // activation of the combined value (0 = none)
+    // bytes from the first to one past the last element of A / B (one batch entry): the bound of the range-checked loads
+    int64_t a_extent, b_extent;
 };
 
 __device__ __forceinline__ u32x4 gload16(const char *base, uint32_t off)
@@ -138,6 +140,14 @@ struct StageK {
         else r[i] = gload16(base + (i < ip ? i : ip) * step, i < ip ? voff0 : vsel);
         shift = -1;
     }
+    // The same load through a range-checked buffer access (rsrc covers the operand, soff = byte offset of the
+    // block's origin in it): rows past the operand's end lie past the buffer's and read as zero, so a block on
+    // the ragged m / n end needs neither predicate nor clamp.  Only for blocks whose 64 k lie inside the operand.
+    __device__ __forceinline__ void load_piece_buf(__amdgpu_buffer_rsrc_t rsrc, uint32_t soff, int i)
+    {
+        r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff0, soff + (uint32_t)i * (uint32_t)step, 0);
+        shift = -1;
+    }
     template <bool MASKED = EDGE>
     __device__ __forceinline__ void load(const char *base, int64_t rows_left, int64_t k_left)
     {
@@ -234,6 +244,23 @@ struct StageMN {
                 r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
             } else {
                 const u32x2 v = gload8(base + j * step, off);
+                r[j][0] = v[0]; r[j][1] = v[1];
+            }
+        }
+        shift = -1;
+    }
+    // The same through a range-checked buffer access (see StageK::load_piece_buf).  A block on the ragged m / n
+    // end reads on into the next k line (or, past the operand's end, zeros): what it fetches beyond the valid
+    // rows only reaches outputs that are never stored.
+    __device__ __forceinline__ void load_piece_buf(__amdgpu_buffer_rsrc_t rsrc, uint32_t soff, int p)
+    {
+#pragma unroll
+        for (int j = p; j < 8; j += NW) {
+            if constexpr (NW == 8) {
+                const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff0, soff + (uint32_t)j * (uint32_t)step, 0);
+                r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
+            } else {
+                const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff0, soff + (uint32_t)j * (uint32_t)step, 0);
                 r[j][0] = v[0]; r[j][1] = v[1];
             }
         }
@@ -648,6 +675,13 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
     const int64_t a_step = (ALAY == KCONTIG ? (int64_t)kBK : (int64_t)kBK * g.lda) * 2;
     const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kBK : (int64_t)kBK * g.ldb) * 2;
     const int64_t m_left = g.M - row0, n_left = g.N - col0;
+    // Range-checked views of the operands from this program's tile origin on: a buffer access past the operand's end
+    // reads as zero instead of faulting.  (Offsets inside a tile's footprint stay below 2^32: the launcher bounds the
+    // pitches; the record count saturates for operands that go on for more than 2 GB past the origin.)
+    const int64_t a_org = (ALAY == KCONTIG ? row0 * g.lda : row0) * 2, b_org = (BLAY == KCONTIG ? col0 * g.ldb : col0) * 2;
+    const int64_t a_rest = g.a_extent - a_org, b_rest = g.b_extent - b_org;
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(gA), 0, (int)(a_rest < 0x7fffffffLL ? a_rest : 0x7fffffffLL), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(gB), 0, (int)(b_rest < 0x7fffffffLL ? b_rest : 0x7fffffffLL), 0x00020000);
 
     // two sets of staging registers: a tile is requested two trips before it is multiplied
     typename StageSel<BM, ALAY, true>::type sa0, sa1;
@@ -743,9 +777,9 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
     // (ha / hb), moves to the idle LDS copy during k step 2; after the barrier that publishes it,
     // k step 3 already reads its first fragments.
     uint32_t cur = 0;
-    // mode 0: the requested tile lies inside both operands (plain loads); 1: its 64 k do, its rows
-    // may not (clamped loads); 2: anything (predicated loads that zero what lies outside, and a
-    // fix-up of the vectors that straddle a ragged end).
+    // mode 1: the requested tile's 64 k lie inside the operands, its rows may not (range-checked buffer
+    // loads, no predicates); 2: anything (predicated loads that zero what lies outside, and a fix-up of
+    // the vectors that straddle a ragged end).
     auto trip = [&](auto mode_tag, auto &fa_set, auto &fb_set, auto &ha, auto &hb, int64_t k) {
         constexpr int mode = decltype(mode_tag)::value;
         const uint32_t nxt = cur ^ 1u;
@@ -760,13 +794,14 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
         } else {
             // requests without predicates go out one at a time between the MFMAs of k steps 0 and 1
             constexpr int PA = std::remove_reference_t<decltype(fa_set)>::PIECES, PB = std::remove_reference_t<decltype(fb_set)>::PIECES;
+            const uint32_t oa = (uint32_t)(kn * a_step), ob = (uint32_t)(kn * b_step);
             kstep(0, 1, cur, std::false_type{}, ha, hb, nxt, [&](int idx) {
 #pragma unroll
-                for (int i = idx * PA / NM; i < (idx + 1) * PA / NM; ++i) fa_set.template load_piece<mode == 1>(pa, i);
+                for (int i = idx * PA / NM; i < (idx + 1) * PA / NM; ++i) fa_set.load_piece_buf(rsrc_a, oa, i);
             });
             kstep(1, 2, cur, std::false_type{}, ha, hb, nxt, [&](int idx) {
 #pragma unroll
-                for (int i = idx * PB / NM; i < (idx + 1) * PB / NM; ++i) fb_set.template load_piece<mode == 1>(pb, i);
+                for (int i = idx * PB / NM; i < (idx + 1) * PB / NM; ++i) fb_set.load_piece_buf(rsrc_b, ob, i);
             });
         }
         if constexpr (mode == 2) {                   // (trips in modes 0 and 1 only ever hold tiles requested without predicates)
@@ -778,19 +813,16 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
         kstep(1, 0, nxt, std::false_type{}, ha, hb, nxt, nullptr);
         cur = nxt;
     };
-    // Programs whose tile lies inside C request every k tile but the last with plain loads (trip k
-    // requests tile k + 2); the rest, and programs on the ragged edge, mask.  (Clamped requests in
-    // the loop of the edge programs would spare them the predicates, but that loop then needs more
-    // registers than there are.)  Trips come in pairs so that the roles of the two staging sets
-    // are fixed at compile time.
+    // Every k tile but the last ones is requested with range-checked loads (trip k requests tile
+    // k + 2), by programs on the ragged m / n edge as well; the last k tiles mask.  Trips come in
+    // pairs so that the roles of the two staging sets are fixed at compile time.
     int64_t k = 0;
-    typedef std::integral_constant<int, 0> Plain;
+    typedef std::integral_constant<int, 1> Ranged;
     typedef std::integral_constant<int, 2> Masked;
-    if (m_left >= BM && n_left >= BN)
-        for (; k + 1 <= g.kt - 4; k += 2) {
-            trip(Plain{}, sa0, sb0, sa1, sb1, k);
-            trip(Plain{}, sa1, sb1, sa0, sb0, k + 1);
-        }
+    for (; k + 1 <= g.kt - 4; k += 2) {
+        trip(Ranged{}, sa0, sb0, sa1, sb1, k);
+        trip(Ranged{}, sa1, sb1, sa0, sb0, k + 1);
+    }
     for (; k + 1 < g.kt; k += 2) {
         trip(Masked{}, sa0, sb0, sa1, sb1, k);
         trip(Masked{}, sa1, sb1, sa0, sb0, k + 1);

@@ -119,6 +119,9 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         a.alpha = g.alpha;
         a.beta = g.has_d ? g.beta : 0.f;
         a.act = g.act;
+        // bounds of the range-checked loads (the pitches are below 2^22, so every offset inside a tile's footprint fits 32 bits)
+        a.a_extent = (alay == KCONTIG ? (g.M - 1) * a.lda + g.K : (g.K - 1) * a.lda + g.M) * 2;
+        a.b_extent = (blay == KCONTIG ? (g.N - 1) * a.ldb + g.K : (g.K - 1) * a.ldb + g.N) * 2;
         if (g.has_d) {
             a.D = (const char *)g.D + g.md.base * esz;
             a.sdm = g.md.roff[0];
