@@ -289,7 +289,7 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
             const char *pbc = k_left >= kBK ? pb : gB;
             kstep(1, 2, cur, std::false_type{}, ha, hb, nxt, [&](int idx) {
 #pragma unroll
-                for (int i = idx * PB / NM; i < (idx + 1) * PB / NM; ++i) fb_set.template load_piece<false>(pbc, i);
+                for (int i = idx * PB / NM; i < (idx + 1) * PB / NM; ++i) fb_set.load_piece(pbc, i);
             });
         }
         ha.settle();

@@ -97,8 +97,6 @@ struct StageK {
     static constexpr int CH = ROWS * 8 / kThreads;        // 16-byte chunks per thread
     u32x4 r[CH];
     uint32_t voff0;                                       // byte offset of the thread's first chunk from the tile origin
-    uint32_t vsel;                                        // the same with the row clamped to the tile's last valid one (set_edge)
-    int ip;
     int64_t step;                                         // bytes between its chunks (32 rows; wavefront-uniform)
     uint32_t wbase;                                       // swizzled LDS byte offset of chunk 0
     int row0, ch;
@@ -121,23 +119,10 @@ struct StageK {
     // fill in settle(); K must be at least 8 for that address to stay inside the operand.
     // Masked elements read as zero.
     // MASKED = false: the caller knows the whole block is inside the operand.
-    // Preparation of the clamped loads below for a tile with rows_left valid rows.
-    __device__ __forceinline__ void set_edge(int64_t rows_left, int64_t ld)
-    {
-        const int last_row = (int)(rows_left < ROWS ? rows_left : ROWS) - 1;
-        ip = last_row >> 5;                                   // 32-row group that holds the last valid row
-        const int rp = last_row & 31;
-        vsel = row0 > rp ? ((uint32_t)rp * (uint32_t)ld + (uint32_t)(ch * 8)) * 2u : voff0;
-    }
-    // One of the PIECES loads of a block whose 64 k lie inside the operand.  CLAMP = false: so do
-    // all its rows.  CLAMP = true (after set_edge): rows past the ragged end fetch the last valid
-    // row instead -- their products only reach outputs that are never stored -- so the load
-    // needs no predicate and can sit between MFMAs.
-    template <bool CLAMP>
+    // One of the PIECES loads of a block that lies inside the operand (rows and k).
     __device__ __forceinline__ void load_piece(const char *base, int i)
     {
-        if constexpr (!CLAMP) r[i] = gload16(base + i * step, voff0);
-        else r[i] = gload16(base + (i < ip ? i : ip) * step, i < ip ? voff0 : vsel);
+        r[i] = gload16(base + i * step, voff0);
         shift = -1;
     }
     // The same load through a range-checked buffer access (rsrc covers the operand, soff = byte offset of the
@@ -153,7 +138,7 @@ struct StageK {
     {
         if constexpr (!MASKED) {
 #pragma unroll
-            for (int i = 0; i < CH; ++i) load_piece<false>(base, i);
+            for (int i = 0; i < CH; ++i) load_piece(base, i);
         } else {
             const int left = (int)(k_left < kBK ? k_left : kBK) - ch * 8;
             const int sh = (left > 0 && left < 8) ? 8 - left : 0;
@@ -197,7 +182,6 @@ struct StageMN {
     static_assert(NW == 8 || NW == 4, "transposing loader supports 128 or 256 rows");
     uint32_t r[8][NW / 2];                                // [k line][packed pairs of rows]
     uint32_t voff0;                                       // byte offset of the thread's first k line from the tile origin
-    uint32_t vsel;                                        // the same, or that of the tile's first block if this one starts outside (set_edge)
     int64_t step;                                         // bytes between k lines (wavefront-uniform)
     uint32_t wbase;
     int kb, rb;
@@ -221,29 +205,17 @@ struct StageMN {
     // MASKED = false: the caller knows the whole block is inside the operand.
     // plain load of k line j (and j + NW for the narrower block, so that there are PIECES loads)
     // of a block that lies inside the operand
-    // Preparation of the clamped loads below for a tile with rows_left valid rows.
-    __device__ __forceinline__ void set_edge(int64_t rows_left, int64_t ld)
-    {
-        vsel = rb * NW < rows_left ? voff0 : voff0 - (uint32_t)(rb * NW * 2);
-    }
-    // Plain load of k line p (and p + NW for the narrower block, so that there are PIECES loads).
-    // CLAMP = false: the block lies inside the operand.  CLAMP = true (after set_edge): it may lie
-    // on the ragged m / n end of a k tile that is not the operand's last.  A block that starts
-    // inside is fetched where it is (what it reads past the end of its k line is the next k line:
-    // valid memory, and its products only reach outputs that are never stored); a block that
-    // starts outside fetches the tile's first block instead.  No predicate, so the load can sit
-    // between MFMAs.
-    template <bool CLAMP>
+    // Plain load of k line p (and p + NW for the narrower block, so that there are PIECES loads) of a block that
+    // lies inside the operand.
     __device__ __forceinline__ void load_piece(const char *base, int p)
     {
-        const uint32_t off = CLAMP ? vsel : voff0;
 #pragma unroll
         for (int j = p; j < 8; j += NW) {
             if constexpr (NW == 8) {
-                const u32x4 v = gload16(base + j * step, off);
+                const u32x4 v = gload16(base + j * step, voff0);
                 r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
             } else {
-                const u32x2 v = gload8(base + j * step, off);
+                const u32x2 v = gload8(base + j * step, voff0);
                 r[j][0] = v[0]; r[j][1] = v[1];
             }
         }
@@ -271,7 +243,7 @@ struct StageMN {
     {
         if constexpr (!MASKED) {
 #pragma unroll
-            for (int p = 0; p < NW; ++p) load_piece<false>(base, p);
+            for (int p = 0; p < NW; ++p) load_piece(base, p);
             return;
         }
         const int rl = (int)(rows_left < ROWS ? rows_left : ROWS) - rb * NW;     // valid rows of this block
@@ -690,10 +662,6 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
     sb0.init(tid, g.ldb);
     sa1.init(tid, g.lda);
     sb1.init(tid, g.ldb);
-    sa0.set_edge(m_left, g.lda);
-    sb0.set_edge(n_left, g.ldb);
-    sa1.set_edge(m_left, g.lda);
-    sb1.set_edge(n_left, g.ldb);
 
     // per-lane LDS read bases: row (wave origin + l32) of each operand, chunk hi, swizzled
     const int ra = wave_m * (BM / 2) + l32, rb = wave_n * (BN / 2) + l32;
@@ -755,9 +723,9 @@ __global__ __launch_bounds__(kThreads) void gemm_fast_kernel(const FastArgs g)
     sb0.load(gB, n_left, g.K);
     if (last > 1) {                                  // tile 1 is not the last: its 64 k lie inside the operands
 #pragma unroll
-        for (int i = 0; i < decltype(sa1)::PIECES; ++i) sa1.template load_piece<true>(gA + a_step, i);
+        for (int i = 0; i < decltype(sa1)::PIECES; ++i) sa1.load_piece_buf(rsrc_a, (uint32_t)a_step, i);
 #pragma unroll
-        for (int i = 0; i < decltype(sb1)::PIECES; ++i) sb1.template load_piece<true>(gB + b_step, i);
+        for (int i = 0; i < decltype(sb1)::PIECES; ++i) sb1.load_piece_buf(rsrc_b, (uint32_t)b_step, i);
     } else {
         sa1.load(gA + last * a_step, m_left, g.K - last * kBK);
         sb1.load(gB + last * b_step, n_left, g.K - last * kBK);
