@@ -188,6 +188,7 @@ nt_status nt_addmm(const void *input, const nt_tensor_desc *dI, const void *A, c
  *   NT_ACT_SILU       x / (1 + exp(-x))
  *   NT_ACT_GELU_TANH  0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))
  * `input` / dI may be NULL when beta == 0 (then C = act(alpha * A . B)).  Everything else as nt_addmm.
+ * NT_ACT_RELU maps a NaN to 0 (the hardware maximum returns its number operand); the others propagate it.
  */
 typedef enum { NT_ACT_NONE = 0, NT_ACT_RELU = 1, NT_ACT_SILU = 2, NT_ACT_GELU_TANH = 3 } nt_activation;
 nt_status nt_addmm_act(const void *input, const nt_tensor_desc *dI, const void *A, const nt_tensor_desc *dA,
