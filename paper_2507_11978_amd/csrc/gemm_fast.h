@@ -384,83 +384,6 @@ __device__ __forceinline__ void load_row16(const char *p, float (&d)[16])
     }
 }
 
-// C with unit stride along n, 16-bit output: every lane stores its 16 consecutive columns of each
-// block with two 16-byte stores straight from registers.  (Lines of C are completed by several
-// instructions, but the epilogue is one burst of stores at the memory's write rate either way, and
-// this routine issues it sooner than the one through LDS below, which fp32 outputs need.)  row_w / col_w: first row / column of the wavefront's part of the tile.
-// CHECK masks rows >= M and columns >= N (a partly valid run of 16 is stored element-wise).
-// affine: the stored value is alpha * accumulator + beta * D (D: elements of the output type with
-// unit stride along n and row stride sdm, read under the same masks; nullptr = no addend).
-template <int BM, int BN, int OUT, bool CHECK>
-__device__ __forceinline__ void store_tile_regs(char *C, int64_t scm, const float16v (&acc)[BM / 64][BN / 64],
-                                                int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N,
-                                                bool affine, const char *D, int64_t sdm, float alpha, float beta, int act)
-{
-    constexpr int TM = BM / 64, TN = BN / 64;
-    constexpr int ES = OUT == NT_F32 ? 4 : 2;
-    const int l32 = lane & 31, hi = lane >> 5;
-    const ActParams ap = act_params(act);
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        const int64_t row = row_w + tm * 32 + l32;
-        const int64_t col = col_w + 16 * hi;
-        char *prow = C + (row * scm + col) * ES;
-        const char *drow = D + (row * sdm + col) * ES;
-        const bool row_ok = !CHECK || row < M;
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            uint32_t o[16];
-            gather_row16(acc[tm][tn], o);
-            char *p = prow + tn * 32 * ES;
-            const int64_t nv = CHECK ? N - (col + tn * 32) : 16;      // valid columns from the lane's first
-            if (affine) {                                             // wavefront-uniform
-                float d[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) d[i] = 0.f;
-                if (D) {
-                    const char *dp = drow + tn * 32 * ES;
-                    if (row_ok && nv >= 16) {
-                        load_row16<OUT>(dp, d);
-                    } else if (CHECK && row_ok && nv > 0) {
-#pragma unroll
-                        for (int i = 0; i < 16; ++i)
-                            if (i < nv) d[i] = load_as_f32(dp, i, OUT);
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[i] = __builtin_bit_cast(uint32_t, combine(__builtin_bit_cast(float, o[i]), d[i], alpha, beta));
-                if (act) {                                            // wavefront-uniform
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) o[i] = __builtin_bit_cast(uint32_t, activate(__builtin_bit_cast(float, o[i]), ap));
-                }
-            }
-            if (row_ok && nv >= 16) {
-                if constexpr (OUT == NT_F32) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const u32x4 v{o[4 * i], o[4 * i + 1], o[4 * i + 2], o[4 * i + 3]};
-                        __builtin_memcpy(p + 16 * i, &v, 16);
-                    }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        const u32x4 v{pack_pair<OUT>(o[8 * i], o[8 * i + 1]), pack_pair<OUT>(o[8 * i + 2], o[8 * i + 3]),
-                                      pack_pair<OUT>(o[8 * i + 4], o[8 * i + 5]), pack_pair<OUT>(o[8 * i + 6], o[8 * i + 7])};
-                        __builtin_memcpy(p + 16 * i, &v, 16);
-                    }
-                }
-            } else if (CHECK && row_ok && nv > 0) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    if (i < nv) {
-                        if constexpr (OUT == NT_F32) *reinterpret_cast<uint32_t *>(p + 4 * i) = o[i];
-                        else *reinterpret_cast<uint16_t *>(p + 2 * i) = (uint16_t)pack_pair<OUT>(o[i], 0u);
-                    }
-            }
-        }
-    }
-}
-
 // C with unit stride along n.  The wavefront's (BM/2) x (BN/2) part of the tile goes through LDS
 // (free by now; each wavefront uses a region of its own) so that global stores are whole lines:
 //   write phase  every lane gathers 16 consecutive columns of its row per 32 x 32 block, applies
@@ -471,6 +394,8 @@ __device__ __forceinline__ void store_tile_regs(char *C, int64_t scm, const floa
 //   read phase   RB / 16 consecutive lanes read one row, so a store instruction covers 64 / (RB/16)
 //                rows of RB contiguous bytes each.
 // An fp32 tile takes two passes (one per half of the columns) through the same region.
+// (Storing 16-bit outputs straight from registers, two 16-byte stores per lane and block, completes a
+// line of C with several instructions and moved 1.3 times the output's bytes to memory.)
 // row_w / col_w: first row / column of the wavefront's part.  CHECK masks rows >= M and columns
 // >= N (a partly valid 16-byte chunk is stored element-wise).
 template <int BM, int BN, int OUT, bool CHECK>
@@ -609,21 +534,19 @@ __device__ __forceinline__ void store_tile(const FastArgs &g, char *smem, int wa
         }
     }
     const bool affine = D != nullptr || g.alpha != 1.f || g.act != 0;
-#define NT_ROWS(CHECK) store_tile_rows<BM, BN, NT_F32, CHECK>(smem, wave, C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta, g.act)
-#define NT_REGS(OUT, CHECK) store_tile_regs<BM, BN, OUT, CHECK>(C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta, g.act)
+#define NT_ROWS(OUT, CHECK) store_tile_rows<BM, BN, OUT, CHECK>(smem, wave, C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta, g.act)
     if constexpr (EDGE) {
         if (ragged) {
-            if (g.out_dtype == NT_F32) NT_ROWS(true);
-            else if (g.out_dtype == NT_F16) NT_REGS(NT_F16, true);
-            else NT_REGS(NT_BF16, true);
+            if (g.out_dtype == NT_F32) NT_ROWS(NT_F32, true);
+            else if (g.out_dtype == NT_F16) NT_ROWS(NT_F16, true);
+            else NT_ROWS(NT_BF16, true);
             return;
         }
     }
-    if (g.out_dtype == NT_F32) NT_ROWS(false);
-    else if (g.out_dtype == NT_F16) NT_REGS(NT_F16, false);
-    else NT_REGS(NT_BF16, false);
+    if (g.out_dtype == NT_F32) NT_ROWS(NT_F32, false);
+    else if (g.out_dtype == NT_F16) NT_ROWS(NT_F16, false);
+    else NT_ROWS(NT_BF16, false);
 #undef NT_ROWS
-#undef NT_REGS
 }
 
 template <int BM, int BN, bool BF16, int ALAY, int BLAY>
