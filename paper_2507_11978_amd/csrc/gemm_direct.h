@@ -53,6 +53,26 @@ __device__ __forceinline__ void dma16(const char *gbase, uint32_t voff, uint32_t
                  : "memory");   // m0 is not otherwise used by these kernels
 }
 
+// The same through a range-checked buffer access: rsrc describes the memory from the program's tile origin to the
+// operand's end, soff (wavefront-uniform) and voff are byte offsets into it; 4-byte words that do not lie wholly
+// inside it arrive in LDS as zeros instead of being fetched.  Lets tiles on the ragged m / n edge use the same loads.
+__device__ __forceinline__ void dma16_buf(u32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory");
+}
+
+// buffer resource (raw, no swizzle) over `bytes` bytes at p; all words wavefront-uniform
+__device__ __forceinline__ u32x4 make_rsrc(const void *p, int64_t bytes)
+{
+    const uint64_t b = reinterpret_cast<uint64_t>(p);
+    const uint32_t n = bytes < 0x7fffffffLL ? (uint32_t)bytes : 0x7fffffffu;
+    return u32x4{(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b), (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((b >> 32) & 0xffffu)),
+                 (uint32_t)__builtin_amdgcn_readfirstlane((int)n), 0x00020000u};
+}
+
 template <int E, int LAY>
 struct DirectTile;
 
@@ -80,6 +100,10 @@ struct DirectTile<E, KCONTIG> {
     __device__ __forceinline__ void issue_one(int j, const char *g, uint32_t lds_slice, int wave) const
     {
         dma16(g, voff[j], lds_slice + (uint32_t)((wave * PER + j) * 1024));
+    }
+    __device__ __forceinline__ void issue_one_buf(int j, u32x4 rsrc, uint32_t soff, uint32_t lds_slice, int wave) const
+    {
+        dma16_buf(rsrc, voff[j], soff, lds_slice + (uint32_t)((wave * PER + j) * 1024));
     }
     // fragment t (32 rows) of k step ks (0 or 1) of the slice at byte offset slice_off: one 16-byte read
     __device__ __forceinline__ void read(u32x2 (&f)[2], const char *smem, int t, int ks, int part, uint32_t slice_off) const
@@ -126,6 +150,10 @@ struct DirectTile<E, MNCONTIG> {
     {
         dma16(g, voff[j], lds_slice + (uint32_t)((wave * PER + j) * 1024));
     }
+    __device__ __forceinline__ void issue_one_buf(int j, u32x4 rsrc, uint32_t soff, uint32_t lds_slice, int wave) const
+    {
+        dma16_buf(rsrc, voff[j], soff, lds_slice + (uint32_t)((wave * PER + j) * 1024));
+    }
     // half `part` (k 0..3 or 4..7 of the lane's run) of fragment t: one transposing 8-byte read
     __device__ __forceinline__ void read(u32x2 (&f)[2], const char *smem, int t, int ks, int part, uint32_t slice_off) const
     {
@@ -135,7 +163,10 @@ struct DirectTile<E, MNCONTIG> {
     }
 };
 
-template <int BM, int BN, bool BF16, int ALAY, int BLAY>
+// EDGE = false: every tile is full.  EDGE = true: tiles may overhang M or N (K is a whole number of k tiles):
+// the operand loads are range checked (what lies past an operand's end reads as zero, what an overhanging
+// tile reads inside it only reaches outputs that are never stored) and the stores are masked.
+template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE>
 __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_kernel(const FastArgs g)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
@@ -193,9 +224,19 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_ke
     // The global->LDS loads of one slice, numbered 0 .. ND-1 (A's first): load d of the slice
     // at (pa, pb) into ring position `ring`.
     constexpr int NM = TM * TN, ND = TileA::PER + TileB::PER;
+    u32x4 rsrc_a{0, 0, 0, 0}, rsrc_b{0, 0, 0, 0};
+    if constexpr (EDGE) {
+        rsrc_a = make_rsrc(gA, g.a_extent - (gA - reinterpret_cast<const char *>(g.A + bi * g.sa_batch)));
+        rsrc_b = make_rsrc(gB, g.b_extent - (gB - reinterpret_cast<const char *>(g.B + bi * g.sb_batch)));
+    }
     auto dma = [&](int d, const char *pa, const char *pb, uint32_t ring) {
-        if (d < TileA::PER) ta.issue_one(d, pa, lds0 + ring * A_BYTES, wave);
-        else tb.issue_one(d - TileA::PER, pb, lds0 + B_BASE + ring * B_BYTES, wave);
+        if constexpr (!EDGE) {
+            if (d < TileA::PER) ta.issue_one(d, pa, lds0 + ring * A_BYTES, wave);
+            else tb.issue_one(d - TileA::PER, pb, lds0 + B_BASE + ring * B_BYTES, wave);
+        } else {
+            if (d < TileA::PER) ta.issue_one_buf(d, rsrc_a, (uint32_t)(pa - gA), lds0 + ring * A_BYTES, wave);
+            else tb.issue_one_buf(d - TileA::PER, rsrc_b, (uint32_t)(pb - gB), lds0 + B_BASE + ring * B_BYTES, wave);
+        }
     };
     // One k step: the TM x TN MFMAs on fragment slot `slot`.  Between them, one at a time so
     // that neither the LDS queue nor the memory queue ever holds the in-order wavefront back
@@ -259,14 +300,15 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_ke
     NT_WAIT_VMCNT(0);                                      // drain the surplus prefetches ...
     __syncthreads();                                       // ... of every wavefront: the epilogue reuses the LDS
 
-    store_tile<BM, BN, false>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane, false);
+    store_tile<BM, BN, EDGE>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane,
+                             EDGE && (g.M - row0 < BM || g.N - col0 < BN));
 }
 
-template <int BM, int BN, bool BF16, int ALAY, int BLAY>
+template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE = false>
 static nt_status launch_direct_inst(const FastArgs &a, int64_t nwg, hipStream_t s)
 {
     constexpr size_t smem = (size_t)ring_of(BM, BN) * (BM + BN) * kSliceK * sizeof(uint16_t);
-    auto kern = gemm_direct_kernel<BM, BN, BF16, ALAY, BLAY>;
+    auto kern = gemm_direct_kernel<BM, BN, BF16, ALAY, BLAY, EDGE>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -277,19 +319,21 @@ static nt_status launch_direct_inst(const FastArgs &a, int64_t nwg, hipStream_t 
     return check_launch("gemm_direct_kernel");
 }
 
-template <int BM, int BN, bool BF16>
+template <int BM, int BN, bool BF16, bool EDGE = false>
 static nt_status launch_direct_t(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s)
 {
-    if (alay == KCONTIG && blay == MNCONTIG) return launch_direct_inst<BM, BN, BF16, KCONTIG, MNCONTIG>(a, nwg, s);
-    if (alay == KCONTIG && blay == KCONTIG) return launch_direct_inst<BM, BN, BF16, KCONTIG, KCONTIG>(a, nwg, s);
-    if (alay == MNCONTIG && blay == MNCONTIG) return launch_direct_inst<BM, BN, BF16, MNCONTIG, MNCONTIG>(a, nwg, s);
-    return launch_direct_inst<BM, BN, BF16, MNCONTIG, KCONTIG>(a, nwg, s);
+    if (alay == KCONTIG && blay == MNCONTIG) return launch_direct_inst<BM, BN, BF16, KCONTIG, MNCONTIG, EDGE>(a, nwg, s);
+    if (alay == KCONTIG && blay == KCONTIG) return launch_direct_inst<BM, BN, BF16, KCONTIG, KCONTIG, EDGE>(a, nwg, s);
+    if (alay == MNCONTIG && blay == MNCONTIG) return launch_direct_inst<BM, BN, BF16, MNCONTIG, MNCONTIG, EDGE>(a, nwg, s);
+    return launch_direct_inst<BM, BN, BF16, MNCONTIG, KCONTIG, EDGE>(a, nwg, s);
 }
 
 // one translation unit per tile shape and input format defines these (parallel compilation)
 #define NT_DIRECT_DECL(T) \
     nt_status launch_direct_##T##_f16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s); \
-    nt_status launch_direct_##T##_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s);
+    nt_status launch_direct_##T##_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s); \
+    nt_status launch_direct_edge_##T##_f16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s); \
+    nt_status launch_direct_edge_##T##_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s);
 NT_DIRECT_DECL(128x128)
 NT_DIRECT_DECL(256x128)
 NT_DIRECT_DECL(128x256)

@@ -1,0 +1,9 @@
+// Instantiations of the direct-to-LDS kernel for tiles that may overhang M or N, 128 x 128 x 64 tile, bf16 inputs.
+#include "gemm_direct.h"
+
+namespace nt {
+nt_status launch_direct_edge_128x128_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s)
+{
+    return launch_direct_t<128, 128, true, true>(a, alay, blay, nwg, s);
+}
+}  // namespace nt

@@ -131,20 +131,27 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         const bool bf16 = g.in_dtype == NT_BF16;
         const int64_t nwg = g.batch * g.mt * g.nt;
         hipStream_t s = (hipStream_t)g.stream;
-        // full tiles of 16-byte aligned operands, stored to a C (and added to a D) with unit stride
-        // along n, stream straight into LDS; everything else takes the staged kernel
-        const bool ragged = (g.M % t.bm) || (g.N % t.bn) || (g.K % t.bk);
+        // 16-byte aligned operands, stored to a C (and added to a D) with unit stride along n, stream straight into
+        // LDS: full tiles with plain loads; tiles that overhang M or N (K a whole number of k tiles) with range-checked
+        // loads, which needs the extent along an operand's contiguous m / n axis to be a multiple of 8 (no 16-byte
+        // vector may straddle the operand's end) and every offset inside a tile's footprint to fit 32 bits.
+        // Everything else takes the staged kernel.
+        const bool ragged_mn = (g.M % t.bm) || (g.N % t.bn), ragged_k = (g.K % t.bk) != 0;
         auto al16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-        const bool direct = !ragged && a.scn == 1 && (!a.D || a.sdn == 1) && al16(a.A) && al16(a.B) &&
-                            a.lda % 8 == 0 && a.ldb % 8 == 0 && a.sa_batch % 8 == 0 && a.sb_batch % 8 == 0;
+        const bool streamable = !ragged_k && a.scn == 1 && (!a.D || a.sdn == 1) && al16(a.A) && al16(a.B) &&
+                                a.lda % 8 == 0 && a.ldb % 8 == 0 && a.sa_batch % 8 == 0 && a.sb_batch % 8 == 0;
+        const bool edge_ok = (alay == KCONTIG || (g.M % 8 == 0 && g.K * a.lda < (1LL << 30))) &&
+                             (blay == KCONTIG || (g.N % 8 == 0 && g.K * a.ldb < (1LL << 30)));
+        const bool direct = streamable && (!ragged_mn || edge_ok);
         if (path_out) *path_out = direct ? PATH_DIRECT : PATH_FAST;
         typedef nt_status (*Launcher)(const FastArgs &, int, int, int64_t, hipStream_t);
-        struct Entry { int bm, bn; Launcher direct[2], staged[2]; };      // [f16, bf16]
-#define NT_ENTRY(BM, BN, T) {BM, BN, {launch_direct_##T##_f16, launch_direct_##T##_bf16}, {launch_fast_##T##_f16, launch_fast_##T##_bf16}}
+        struct Entry { int bm, bn; Launcher direct[2], edge[2], staged[2]; };      // [f16, bf16]
+#define NT_ENTRY(BM, BN, T) {BM, BN, {launch_direct_##T##_f16, launch_direct_##T##_bf16}, {launch_direct_edge_##T##_f16, launch_direct_edge_##T##_bf16}, \
+                             {launch_fast_##T##_f16, launch_fast_##T##_bf16}}
         static const Entry table[] = {NT_ENTRY(128, 128, 128x128), NT_ENTRY(256, 128, 256x128), NT_ENTRY(128, 256, 128x256), NT_ENTRY(256, 256, 256x256)};
 #undef NT_ENTRY
         for (const Entry &e : table)
-            if (e.bm == t.bm && e.bn == t.bn) return (direct ? e.direct : e.staged)[bf16 ? 1 : 0](a, alay, blay, nwg, s);
+            if (e.bm == t.bm && e.bn == t.bn) return (direct ? (ragged_mn ? e.edge : e.direct) : e.staged)[bf16 ? 1 : 0](a, alay, blay, nwg, s);
         return fail(NT_ERR_UNSUPPORTED, "no fast kernel for this tile");
     }
     return launch_generic(g);

@@ -347,6 +347,43 @@ def test_conv2d_dense_unit_stride(shape, pad, tile, dt, out):
     assert_gates(to_f64(Y), ref, out, f"conv dense {shape} {pad} {tile}")
 
 
+@pytest.mark.parametrize("dt,out", [("f16", "f16"), ("bf16", "f32")])
+@pytest.mark.parametrize("M,N,K,tile", [(500, 512, 256, None), (1000, 520, 192, (128, 128, 64)), (264, 776, 128, (256, 256, 64)),
+                                        (1032, 264, 320, (128, 256, 64)), (520, 1000, 64, (256, 128, 64)), (8, 8, 64, (128, 128, 64))])
+def test_overhanging_tiles_on_the_direct_kernel(M, N, K, tile, dt, out):
+    """Aligned operands, whole k tiles, M / N not multiples of the tile: the direct-to-LDS kernel with
+    range-checked loads and masked stores, in all four operand orientations (bit exact: integer inputs)."""
+    A, B = si.gemm_inputs(M, N, K, dt, seed=81, dist="int")
+    ref = onum.gemm(A, B, dt)
+    a, b = to_gpu(A, dt), to_gpu(B, dt)
+    at, bt = a.t().contiguous().t(), b.t().contiguous().t()          # column-major A, B stored [N, K]
+    for aa, bb, streams in [(a, b, N % 8 == 0), (a, bt, True), (at, b, M % 8 == 0 and N % 8 == 0), (at, bt, M % 8 == 0)]:
+        buf = torch.full((M + 2, N + 8), float("nan"), dtype=TORCH_DT[out], device="cuda")   # what lies around C must stay untouched
+        C = buf[1:M + 1, :N]
+        nt.gemm(aa, bb, C, tile=tile)
+        torch.cuda.synchronize()
+        # an operand that is contiguous along m / n needs that extent to be a multiple of 8 (else: the staged kernel)
+        assert nt.last_kernel_path() == (nt.PATH_DIRECT if streams else nt.PATH_STAGED)
+        assert np.array_equal(to_f64(C), ref)
+        assert torch.isnan(buf[0]).all() and torch.isnan(buf[M + 1]).all() and torch.isnan(buf[:, N:]).all()
+
+
+def test_overhanging_tiles_bmm_and_bias_on_the_direct_kernel():
+    dt, Bn, M, N, K = "f16", 3, 300, 392, 128
+    A, B = si.gemm_inputs(M, N, K, dt, seed=82, dist="normal", batch=Bn)
+    C = torch.full((Bn, M, N), float("nan"), dtype=torch.float16, device="cuda")
+    nt.bmm(to_gpu(A, dt), to_gpu(B, dt), C)
+    torch.cuda.synchronize()
+    assert nt.last_kernel_path() == nt.PATH_DIRECT
+    assert_gates(to_f64(C), onum.bmm(A, B, dt), "f16", "bmm with overhanging tiles")
+    bias = torch.from_numpy(np.random.default_rng(83).standard_normal((N,)).astype(np.float32)).half().cuda()
+    C2 = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+    nt.addmm(bias, to_gpu(A[0], dt), to_gpu(B[0], dt), C2, alpha=1.0, beta=1.0, act="silu")
+    torch.cuda.synchronize()
+    assert nt.last_kernel_path() == nt.PATH_DIRECT
+    assert_gates(to_f64(C2), onum.addmm_act(to_f64(bias), A[0], B[0], dt, "silu"), "f16", "bias + silu with overhanging tiles")
+
+
 def test_kernel_paths_are_the_intended_ones():
     """Aligned full tiles stream directly into LDS, ragged or unaligned problems take the staged
     kernel, other strides and tiny tiles the operand-map kernel, strided convolutions too."""
@@ -364,7 +401,9 @@ def test_kernel_paths_are_the_intended_ones():
         return nt.last_kernel_path()
     assert path_of(512, 512, 256) == nt.PATH_DIRECT
     assert path_of(512, 512, 256, tile=(256, 256, 64)) == nt.PATH_DIRECT
-    assert path_of(500, 512, 256) == nt.PATH_STAGED          # ragged M
+    assert path_of(500, 512, 256) == nt.PATH_DIRECT          # ragged M, whole k tiles: range-checked direct loads
+    assert path_of(504, 520, 256, tile=(128, 128, 64)) == nt.PATH_DIRECT   # ragged M and N
+    assert path_of(500, 512, 200) == nt.PATH_STAGED          # ragged K
     assert path_of(512, 520, 264) == nt.PATH_STAGED          # ragged N and K
     assert path_of(512, 516, 256, tile=(128, 128, 64)) == nt.PATH_STAGED   # pitch of B not a multiple of 8
     assert path_of(512, 512, 256, view="strided_a") == nt.PATH_GENERIC
