@@ -6,9 +6,12 @@
 // them to LDS in the swizzled k-contiguous layout (B, or a column-major A, is transposed
 // in registers on the way) and the wavefronts read 8-element k runs as MFMA operands.
 //
-// This is the path for ragged sizes and operands that are not 16-byte aligned: loads are
-// predicated per 16-byte chunk (edge chunks fall back to element loads, masked elements read
-// as zero) and stores are masked.  Aligned full tiles take the direct kernel instead.
+// This is the path for a ragged K and for operands that are not 16-byte aligned.  Every k tile but the
+// last ones is fetched with range-checked buffer loads (what lies past an operand's end reads as zero,
+// so tiles that overhang M or N need no predicates); the last k tiles are fetched with predicated
+// loads, the one vector per row or k line that straddles a ragged end is fetched early and shifted into
+// place with zero fill (masked elements read as zero); stores are masked.  Aligned operands with whole
+// k tiles take the direct kernel instead.
 #pragma once
 #include <type_traits>
 
