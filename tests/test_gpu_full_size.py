@@ -86,3 +86,75 @@ def test_full_size_conv():
     ti = torch.from_numpy(idx).cuda()
     got = to_f64(Y[ti[:, 0], ti[:, 1], ti[:, 2], ti[:, 3]])
     check_samples(got, ref, "f16")
+
+
+@pytest.mark.parametrize("name", ["f1_f16_addmm", "f1_f16_bias_gelu"])
+def test_full_size_addmm(name):
+    cfg = si.CONFIGS[name]
+    M, N, K, dt, out = cfg["M"], cfg["N"], cfg["K"], cfg["dtype"], cfg["out"]
+    A, B = si.gemm_inputs(M, N, K, dt, cfg["seed"], cfg["dist"])
+    row = cfg.get("bias") == "row"
+    Ib = si.normal_bits((N,) if row else (M, N), out, cfg["seed"] + 2, 1.0)
+    C = torch.full((M, N), float("nan"), dtype=TORCH_DT[out], device="cuda")
+    nt.addmm(to_gpu(Ib, out), to_gpu(A, dt), to_gpu(B, dt), C, alpha=cfg["alpha"], beta=cfg["beta"], act=cfg.get("act"))
+    torch.cuda.synchronize()
+    assert torch.isfinite(C).all()
+    ms, ns = sample_positions(M, N, (256, 256), 300, seed=2)
+    Iv = onum.decode(Ib, out)
+    ref = onum.activation(cfg["beta"] * (Iv[ns] if row else Iv[ms, ns]) + cfg["alpha"] * onum.gemm_samples(A, B, dt, ms, ns), cfg.get("act"))
+    check_samples(to_f64(C[torch.from_numpy(ms).cuda(), torch.from_numpy(ns).cuda()]), ref, out)
+
+
+def test_full_size_attention():
+    from oracle import attention as oat
+    cfg = si.CONFIGS["f4_f16_sdpa"]
+    Bn, H, S, D, dt = cfg["B"], cfg["H"], cfg["S"], cfg["D"], cfg["dtype"]
+    q, k, v = (si.normal_bits((Bn, H, S, D), dt, cfg["seed"] + i, 1.0) for i in range(3))
+    out = torch.full((Bn, H, S, D), float("nan"), dtype=TORCH_DT[dt], device="cuda")
+    nt.sdpa(to_gpu(q, dt), to_gpu(k, dt), to_gpu(v, dt), out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    # every output row is a convex combination of that head's value rows
+    vd = to_f64(to_gpu(v, dt))
+    od = to_f64(out)
+    assert (od <= vd.max(axis=2, keepdims=True) + 1e-3).all() and (od >= vd.min(axis=2, keepdims=True) - 1e-3).all()
+    # whole heads against the definition: first, last, and two in between (spread over batch entries and XCDs)
+    for b, h in [(0, 0), (1, 17), (2, 30), (Bn - 1, H - 1)]:
+        ref = oat.sdpa(q[b, h], k[b, h], v[b, h], dt)
+        check_samples(od[b, h], ref, dt)
+
+
+@pytest.mark.parametrize("name", ["f3_f16_add", "f3_f16_silu", "f3_f16_softmax", "f3_f16_rms_norm"])
+def test_full_size_memory_bound_kernels(name):
+    """The benchmark's inputs and launch; the whole output against the oracle (add: bit for bit; the others:
+    one unit in the last place of the output format)."""
+    from oracle import elementwise as oe
+    cfg = si.CONFIGS[name]
+    dt, kind = cfg["dtype"], cfg["kind"]
+    bits = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    if kind in ("add", "silu"):
+        n = cfg["n"]
+        x = si.normal_bits((n,), dt, cfg["seed"], 2.0)
+        out = torch.full((n,), float("nan"), dtype=TORCH_DT[dt], device="cuda")
+        if kind == "add":
+            y = si.normal_bits((n,), dt, cfg["seed"] + 1, 2.0)
+            nt.add(to_gpu(x, dt), to_gpu(y, dt), out)
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(out), oe.encode(oe.add(x, y, dt), dt))
+            return
+        nt.silu(to_gpu(x, dt), out)
+        ref = oe.silu(x, dt)
+    else:
+        rows, cols = cfg["rows"], cfg["cols"]
+        x = si.normal_bits((rows, cols), dt, cfg["seed"], 2.0)
+        out = torch.full((rows, cols), float("nan"), dtype=TORCH_DT[dt], device="cuda")
+        if kind == "softmax":
+            nt.softmax(to_gpu(x, dt), out)
+            ref = oe.softmax(x, dt)
+        else:
+            nt.rms_norm(to_gpu(x, dt), out, eps=cfg["eps"])
+            ref = oe.rms_norm(x, dt, cfg["eps"])
+    torch.cuda.synchronize()
+    got = oe.decode(bits(out), dt)
+    assert np.isfinite(got).all()
+    assert (np.abs(got - ref) <= 2.0 ** -10 * np.abs(ref) + 2.0 ** -24).all()
