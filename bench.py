@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"p_f16_8192": 1819000000}   # profiles/gemm_direct_8192_f16_counters.md
+MEASURED_TRAFFIC_BYTES = {"p_f16_8192": 1819000000, "f4_f16_sdpa": 100830000}   # profiles/gemm_direct_8192_f16_counters.md, profiles/sdpa_1024_f16_counters.md
 
 
 def parse_args():
