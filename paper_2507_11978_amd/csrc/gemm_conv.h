@@ -5,7 +5,8 @@
 // m = (n, p, q), kk = (c, r, s) and A[m, kk] = x[n, c, p + r - pad_h, q + s - pad_w]
 // (zero outside the image).  A is contiguous along m, so its (256 x 64) block is staged
 // like a column-major operand: every thread owns 8 consecutive m (one run of q inside an
-// image row; Q is a multiple of 8) for 8 consecutive kk, loads each run with one 16-byte
+// image row: the kernel numbers the output positions with the row pitch Q rounded up to a
+// multiple of 8, positions q >= Q are computed and never stored) for 8 consecutive kk, loads each run with one 16-byte
 // load from the unfolded position inside x -- the unfolded matrix itself never exists --
 // clears the one element that can fall into the left / right padding, zeroes runs whose
 // input row lies in the top / bottom padding, and transposes the 8 x 8 patch in registers
@@ -23,7 +24,9 @@ struct ConvArgs {
     void *Y;                       // output: element (m = n*PQ + pq, f) at n*syn + f*syf + pq
     int64_t ldb, syn, syf;
     int64_t x_numel;               // N*C*H*W
-    int32_t M, N, K;               // GEMM sizes: N*P*Q, filters, C*R*S
+    int32_t M, N, K;               // GEMM sizes: N*P*Q8 (positions as the kernel numbers them), filters, C*R*S
+    int32_t Q8, PQ8;               // output row pitch rounded up to a multiple of 8, and P times that
+    int32_t last_e;                // (Q - 1) % 8: place of a row's last output position in its run
     int32_t PQ, Q, H, W, HW, CHW, RS, S, R, ph, pw;
     uint32_t inv_rs, inv_s;        // reciprocals of R*S and S (see udiv_small)
     int64_t mt, nt, kt;
@@ -57,16 +60,15 @@ struct StageConv {
         const int64_t m = row0 + rb * 8;
         const bool m_ok = m < g.M;
         const uint32_t mm = m_ok ? (uint32_t)m : 0u;
-        const uint32_t nn = mm / (uint32_t)g.PQ;
-        const uint32_t pq = mm - nn * (uint32_t)g.PQ;
-        const uint32_t p = pq / (uint32_t)g.Q;
-        q0 = (int32_t)(pq - p * (uint32_t)g.Q);
+        const uint32_t nn = mm / (uint32_t)g.PQ8;
+        const uint32_t pq = mm - nn * (uint32_t)g.PQ8;
+        const uint32_t p = pq / (uint32_t)g.Q8;
+        q0 = (int32_t)(pq - p * (uint32_t)g.Q8);
         base = (int32_t)(nn * (uint32_t)g.CHW) + ((int32_t)p - g.ph) * g.W + q0 - g.pw;
         first_mask = last_mask = 0;
         for (int sx = 0; sx < g.S; ++sx) {
-            const int w0 = q0 + sx - g.pw;
-            if (w0 < 0) first_mask |= 1u << sx;
-            if (w0 + 7 >= g.W) last_mask |= 1u << sx;
+            if (q0 + sx - g.pw < 0) first_mask |= 1u << sx;                          // the run's first position reads column -1
+            if (q0 + 8 >= g.Q && g.Q - 1 + sx - g.pw >= g.W) last_mask |= 1u << sx;  // the row's last position (in this run) reads column W
         }
         l_rr = l_ss = l_off = 0;
         hmask = 0;
@@ -86,7 +88,7 @@ struct StageConv {
     // in the top / bottom padding or past K, clearing the one element in the left / right padding,
     // moving a run that was clamped by one element back into place -- is noted in `todo` (8 bits per
     // line) and done by settle().
-    enum { ZERO = 1, CLEAR_FIRST = 2, CLEAR_LAST = 4, MOVE_UP = 8, MOVE_DOWN = 16 };
+    enum { ZERO = 1, CLEAR_FIRST = 2, CLEAR_LAST = 4, MOVE_UP = 8, DOWN_SHIFT = 4 /* bits 4..6: elements to move down by */ };
     // Lines are fetched in order j = 0 .. 7; (l_rr, l_ss, l_off) walk through the (r, s) taps and
     // channels like an odometer, so only line 0 of a tile costs a division.
     __device__ __forceinline__ void load_line(const ConvArgs &g, int j, int64_t k_left)
@@ -103,9 +105,12 @@ struct StageConv {
         if (!ok) offc = 0;
         uint32_t code = ok ? 0u : (uint32_t)ZERO;
         code |= ((first_mask >> l_ss) & 1u) * CLEAR_FIRST;     // q0 + s - pad = -1: left padding
-        code |= ((last_mask >> l_ss) & 1u) * CLEAR_LAST;       // ... = W: right padding
+        code |= ((last_mask >> l_ss) & 1u) * CLEAR_LAST;       // the row's last position reads column W: right padding
         if (ok && l_off < 0) code |= MOVE_UP;                  // fetched one element late (very first run of the tensor)
-        if (ok && l_off > hi_lim) code |= MOVE_DOWN;           // fetched one element early (very last run)
+        if (ok && l_off > hi_lim) {                            // fetched early (last runs of the tensor): move down, or, if the
+            const int32_t d = l_off - hi_lim;                  // run starts at the tensor's end (its one valid position reads
+            code |= d < 8 ? (uint32_t)d << DOWN_SHIFT : (uint32_t)ZERO;   // the right padding), nothing is left of it
+        }
         if ((j & 3) == 0) todo[j >> 2] = code;
         else todo[j >> 2] |= code << (8 * (j & 3));
         u32x4 v;
@@ -120,8 +125,12 @@ struct StageConv {
         l_rr = chan_done ? 0 : l_rr;
         l_off += chan_done ? g.HW - g.R * g.W : 0;
     }
-    __device__ __forceinline__ void settle()
+    __device__ __forceinline__ void settle(const ConvArgs &g)
     {
+        // CLEAR_LAST: the element at place last_e of the run (wavefront-uniform masks)
+        const uint32_t half = (g.last_e & 1) ? 0x0000ffffu : 0xffff0000u;
+        const uint32_t c0 = (g.last_e >> 1) == 0 ? half : ~0u, c1 = (g.last_e >> 1) == 1 ? half : ~0u;
+        const uint32_t c2 = (g.last_e >> 1) == 2 ? half : ~0u, c3 = (g.last_e >> 1) == 3 ? half : ~0u;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint32_t code = (todo[j >> 2] >> (8 * (j & 3))) & 0xffu;
@@ -130,12 +139,12 @@ struct StageConv {
                 v3 = __builtin_amdgcn_alignbit(v3, v2, 16); v2 = __builtin_amdgcn_alignbit(v2, v1, 16);
                 v1 = __builtin_amdgcn_alignbit(v1, v0, 16); v0 = v0 << 16;
             }
-            if (code & MOVE_DOWN) {                            // element i <- element i + 1 (element 7 is cleared below)
-                v0 = __builtin_amdgcn_alignbit(v1, v0, 16); v1 = __builtin_amdgcn_alignbit(v2, v1, 16);
-                v2 = __builtin_amdgcn_alignbit(v3, v2, 16); v3 = v3 >> 16;
+            if (code >> DOWN_SHIFT) {                          // element i <- element i + d, zeros from the top
+                const u32x4 v = shift_down(u32x4{v0, v1, v2, v3}, (int)(code >> DOWN_SHIFT));
+                v0 = v[0]; v1 = v[1]; v2 = v[2]; v3 = v[3];
             }
             if (code & CLEAR_FIRST) v0 &= 0xffff0000u;
-            if (code & CLEAR_LAST) v3 &= 0x0000ffffu;
+            if (code & CLEAR_LAST) { v0 &= c0; v1 &= c1; v2 &= c2; v3 &= c3; }
             if (code & ZERO) { v0 = 0; v1 = 0; v2 = 0; v3 = 0; }
             r[j][0] = v0; r[j][1] = v1; r[j][2] = v2; r[j][3] = v3;
         }
@@ -255,7 +264,7 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
     for (int j = 0; j < 8; ++j) sa1.load_line(g, j, (int64_t)g.K - kBK);
     sa1.advance(g, 2);
     sb1.template load<true>(gB + kBK * 2, n_left, (int64_t)g.K - kBK);
-    sa0.settle();
+    sa0.settle(g);
     sb0.settle();
     sa0.store(smem, 0);
     sb0.store(smem, B_BASE);
@@ -292,7 +301,7 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
                 for (int i = idx * PB / NM; i < (idx + 1) * PB / NM; ++i) fb_set.load_piece(pbc, i);
             });
         }
-        ha.settle();
+        ha.settle(g);
         kstep(0, 3, cur, std::true_type{}, ha, hb, nxt, nullptr);
         __syncthreads();
         kstep(1, 0, nxt, std::false_type{}, ha, hb, nxt, nullptr);
@@ -307,22 +316,27 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
 
     // epilogue: a lane holds one filter f = lane % 32 of each 32 x 32 block; after the half-wavefronts
     // have traded register groups (gather_row16) it owns 16 consecutive output positions m of it,
-    // stored as two runs of 8 (a run of 8 aligned to 8 lies in one image because P*Q is a multiple of 8)
-    // with 16-byte stores along the contiguous (p, q) axis of the output.
+    // stored as two runs of 8 (a run lies in one output row: the kernel's row pitch is a multiple of 8)
+    // with 16-byte stores along the contiguous (p, q) axis of the output; the run at the end of a row
+    // whose length is no multiple of 8 is stored position by position.
     auto store_runs = [&](auto out_tag) {
         constexpr int OUT = decltype(out_tag)::value;
         constexpr int ES = OUT == NT_F32 ? 4 : 2;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             int64_t o_run[2];
-            bool m_ok[2];
+            int valid[2];                                          // positions of the run that exist (0: none)
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2) {
                 const int64_t m = row0 + wave_m * (BM / 2) + tm * 32 + 16 * hi + 8 * h2;
-                m_ok[h2] = m < g.M;
-                const uint32_t mm = m_ok[h2] ? (uint32_t)m : 0u;
-                const uint32_t n = mm / (uint32_t)g.PQ;
-                o_run[h2] = (int64_t)n * g.syn + (int64_t)(mm - n * (uint32_t)g.PQ);
+                const bool m_ok = m < g.M;
+                const uint32_t mm = m_ok ? (uint32_t)m : 0u;
+                const uint32_t n = mm / (uint32_t)g.PQ8;
+                const uint32_t pq = mm - n * (uint32_t)g.PQ8;
+                const uint32_t p = pq / (uint32_t)g.Q8;
+                const int q0 = (int)(pq - p * (uint32_t)g.Q8);
+                o_run[h2] = (int64_t)n * g.syn + (int64_t)p * g.Q + q0;
+                valid[h2] = m_ok ? (g.Q - q0 < 8 ? g.Q - q0 : 8) : 0;
             }
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
@@ -332,17 +346,26 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
                 if (f < g.N) {
 #pragma unroll
                     for (int h2 = 0; h2 < 2; ++h2) {
-                        if (!m_ok[h2]) continue;
+                        if (valid[h2] <= 0) continue;
                         char *y = reinterpret_cast<char *>(g.Y) + (o_run[h2] + f * g.syf) * ES;
-                        if constexpr (OUT == NT_F32) {
-                            const u32x4 v0{o[8 * h2], o[8 * h2 + 1], o[8 * h2 + 2], o[8 * h2 + 3]};
-                            const u32x4 v1{o[8 * h2 + 4], o[8 * h2 + 5], o[8 * h2 + 6], o[8 * h2 + 7]};
-                            __builtin_memcpy(y, &v0, 16);
-                            __builtin_memcpy(y + 16, &v1, 16);
+                        if (valid[h2] == 8) {
+                            if constexpr (OUT == NT_F32) {
+                                const u32x4 v0{o[8 * h2], o[8 * h2 + 1], o[8 * h2 + 2], o[8 * h2 + 3]};
+                                const u32x4 v1{o[8 * h2 + 4], o[8 * h2 + 5], o[8 * h2 + 6], o[8 * h2 + 7]};
+                                __builtin_memcpy(y, &v0, 16);
+                                __builtin_memcpy(y + 16, &v1, 16);
+                            } else {
+                                const u32x4 v{pack_pair<OUT>(o[8 * h2], o[8 * h2 + 1]), pack_pair<OUT>(o[8 * h2 + 2], o[8 * h2 + 3]),
+                                              pack_pair<OUT>(o[8 * h2 + 4], o[8 * h2 + 5]), pack_pair<OUT>(o[8 * h2 + 6], o[8 * h2 + 7])};
+                                __builtin_memcpy(y, &v, 16);
+                            }
                         } else {
-                            const u32x4 v{pack_pair<OUT>(o[8 * h2], o[8 * h2 + 1]), pack_pair<OUT>(o[8 * h2 + 2], o[8 * h2 + 3]),
-                                          pack_pair<OUT>(o[8 * h2 + 4], o[8 * h2 + 5]), pack_pair<OUT>(o[8 * h2 + 6], o[8 * h2 + 7])};
-                            __builtin_memcpy(y, &v, 16);
+#pragma unroll
+                            for (int i = 0; i < 7; ++i)
+                                if (i < valid[h2]) {
+                                    if constexpr (OUT == NT_F32) *reinterpret_cast<uint32_t *>(y + 4 * i) = o[8 * h2 + i];
+                                    else *reinterpret_cast<uint16_t *>(y + 2 * i) = (uint16_t)pack_pair<OUT>(o[8 * h2 + i], 0u);
+                                }
                         }
                     }
                 }

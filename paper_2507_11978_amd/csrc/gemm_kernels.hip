@@ -48,12 +48,14 @@ static bool match_conv(const GemmLaunch &g, ConvArgs *a)
 {
     const ConvHint &h = g.conv;
     if (!h.valid || g.batch != 1 || g.tile.bm != 256 || g.tile.bk != 64 || (g.tile.bn != 128 && g.tile.bn != 256)) return false;
-    if (h.sh != 1 || h.sw != 1 || h.ph < 0 || h.pw < 0 || h.pw > 1 || h.R > 31 || h.S > 31 || h.Q % 8 != 0 || h.W < 8 || h.P <= 0) return false;
+    if (h.sh != 1 || h.sw != 1 || h.ph < 0 || h.pw < 0 || h.pw > 1 || h.R > 31 || h.S > 31 || h.P <= 0 || h.Q <= 0) return false;
     if (h.xs[3] != 1 || h.xs[2] != h.W || h.xs[1] != h.H * h.W || h.xs[0] != h.C * h.H * h.W) return false;
     if (h.ws[3] != 1 || h.ws[2] != h.S || h.ws[1] != h.R * h.S || h.ws[0] <= 0 || h.ws[0] >= (1 << 22)) return false;
     if (h.ys[3] != 1 || h.ys[2] != h.Q) return false;
-    const int64_t CRS = h.C * h.R * h.S, NPQ = h.N * h.P * h.Q, numel = h.N * h.C * h.H * h.W;
-    if (numel >= (1LL << 31) || NPQ >= (1LL << 31) || CRS >= (1 << 16) - 128 || CRS < 8) return false;   // (the filter loader needs K >= 8)
+    // the kernel numbers the output positions with the row pitch rounded up to a multiple of 8
+    const int64_t Q8 = (h.Q + 7) / 8 * 8;
+    const int64_t CRS = h.C * h.R * h.S, NPQ = h.N * h.P * Q8, numel = h.N * h.C * h.H * h.W;
+    if (numel >= (1LL << 31) || numel < 8 || NPQ >= (1LL << 31) - 256 || CRS >= (1 << 16) - 128 || CRS < 8) return false;   // (the filter loader needs K >= 8)
     a->X = (const uint16_t *)g.A;
     a->Wt = (const uint16_t *)g.B;
     a->Y = g.C;
@@ -63,11 +65,12 @@ static bool match_conv(const GemmLaunch &g, ConvArgs *a)
     a->x_numel = numel;
     a->M = (int32_t)NPQ; a->N = (int32_t)g.N; a->K = (int32_t)CRS;
     a->PQ = (int32_t)(h.P * h.Q); a->Q = (int32_t)h.Q; a->H = (int32_t)h.H; a->W = (int32_t)h.W;
+    a->Q8 = (int32_t)Q8; a->PQ8 = (int32_t)(h.P * Q8); a->last_e = (int32_t)((h.Q - 1) % 8);
     a->HW = (int32_t)(h.H * h.W); a->CHW = (int32_t)(h.C * h.H * h.W);
     a->RS = (int32_t)(h.R * h.S); a->S = (int32_t)h.S; a->R = (int32_t)h.R; a->ph = (int32_t)h.ph; a->pw = (int32_t)h.pw;
     a->inv_rs = h.R * h.S > 1 ? (uint32_t)((1ULL << 32) / (uint64_t)(h.R * h.S)) + 1u : 0u;
     a->inv_s = h.S > 1 ? (uint32_t)((1ULL << 32) / (uint64_t)h.S) + 1u : 0u;
-    a->mt = g.mt; a->nt = g.nt; a->kt = g.kt;
+    a->mt = (NPQ + 255) / 256; a->nt = g.nt; a->kt = g.kt;
     a->out_dtype = g.out_dtype;
     return true;
 }
@@ -101,7 +104,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         if (!g.has_d && g.alpha == 1.f && g.act == 0 && match_conv(g, &c)) {
             if (path_out) *path_out = PATH_CONV;
             const bool edge_b = (g.N % t.bn) || (g.K % t.bk);
-            return launch_conv(c, t.bn, g.in_dtype == NT_BF16, edge_b, g.mt * g.nt, (hipStream_t)g.stream);
+            return launch_conv(c, t.bn, g.in_dtype == NT_BF16, edge_b, c.mt * c.nt, (hipStream_t)g.stream);
         }
     }
     if (fast) {

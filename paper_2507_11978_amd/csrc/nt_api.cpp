@@ -39,9 +39,10 @@ nt_tile_cfg pick_tile(int kind, int64_t batch, int64_t M, int64_t N, int64_t K, 
     if (cfg.bm || cfg.bn || cfg.bk) return cfg;
     if (M <= 64 || N <= 64) return nt_tile_cfg{64, 64, 32};
     if (kind == KIND_CONV) {
-        // the convolution kernel is built for 256 output positions per program
+        // the convolution kernel is built for 256 output positions per program; 128 filters per program when
+        // 256 would leave half the compute units without one
         const int64_t mt = (M + 255) / 256;
-        return mt * ((N + 255) / 256) >= 200 || N > 128 ? nt_tile_cfg{256, 256, 64} : nt_tile_cfg{256, 128, 64};
+        return mt * ((N + 255) / 256) >= 128 ? nt_tile_cfg{256, 256, 64} : nt_tile_cfg{256, 128, 64};
     }
     struct Cand { int bm, bn; double fixed, step; int resident; };
     const Cand cands[] = {{256, 256, 14.0, 1.755, 1}, {128, 256, 8.0, 0.95, 2}, {256, 128, 8.0, 1.08, 2}, {128, 128, 7.0, 0.62, 2}};

@@ -335,7 +335,7 @@ def test_conv2d_small(shape, stride, pad, tile):
     ((5, 64, 24, 16, 256, 3, 3), (1, 1), None),               # library default tile
 ])
 def test_conv2d_dense_unit_stride(shape, pad, tile, dt, out):
-    """Shapes the dedicated implicit-GEMM kernel takes: contiguous NCHW, stride 1, Q % 8 == 0."""
+    """Shapes the dedicated implicit-GEMM kernel takes: contiguous NCHW, stride 1 (here with Q % 8 == 0)."""
     N, Cc, H, W, K, R, S = shape
     X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, dt, seed=21)
     ref = onum.conv2d(X, Wt, dt, (1, 1), pad)
@@ -417,6 +417,36 @@ def test_kernel_paths_are_the_intended_ones():
         if ref.shape[3] % 8 == 0 or want == nt.PATH_GENERIC:
             assert nt.last_kernel_path() == want, (stride, pad)
         assert_gates(to_f64(Y), ref, "f16", f"conv {stride} {pad}")
+
+
+@pytest.mark.parametrize("shape,pad", [
+    ((4, 16, 14, 14, 128, 3, 3), (0, 0)),      # the paper's conv task in small: Q = 12
+    ((4, 16, 14, 14, 128, 3, 3), (1, 1)),      # Q = 14, right padding inside the last run
+    ((3, 8, 7, 7, 130, 3, 3), (1, 1)),         # W < 8: one run per row, seven positions
+    ((2, 8, 9, 11, 128, 3, 3), (1, 1)),        # Q = 11
+    ((2, 8, 12, 9, 128, 1, 1), (0, 0)),        # 1 x 1 filter, Q = 9: the last run holds one position
+    ((1, 8, 6, 17, 128, 3, 2), (0, 1)),        # even filter width, Q = 18
+    ((8, 4, 5, 5, 128, 5, 5), (2, 1)),         # Q = 3 < 8
+    ((1, 24, 28, 28, 256, 3, 3), (1, 1)),      # Q = 28
+])
+def test_conv2d_dense_rows_that_are_no_multiple_of_eight(shape, pad):
+    """Output rows of any length: the kernel numbers positions with the row pitch rounded up to 8 and never stores the
+    surplus.  Small integers: exact, so a wrong halo element, a missed padding column or a position stored in the wrong
+    place changes the result; what lies around the output must stay untouched."""
+    N, Cc, H, W, K, R, S = shape
+    for dt, out in (("f16", "f32"), ("bf16", "bf16")):
+        X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, dt, seed=23, dist="int")
+        ref = onum.conv2d(X, Wt, dt, (1, 1), pad)
+        buf = torch.full((ref.size + 64,), float("nan"), dtype=TORCH_DT[out], device="cuda")
+        Y = buf[32:32 + ref.size].view(ref.shape)
+        nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), pad)
+        torch.cuda.synchronize()
+        assert nt.last_kernel_path() == nt.PATH_CONV
+        if out == "f32":
+            assert np.array_equal(to_f64(Y), ref)
+        else:
+            assert_gates(to_f64(Y), ref, out, f"conv {shape} {pad}")
+        assert torch.isnan(buf[:32]).all() and torch.isnan(buf[32 + ref.size:]).all()
 
 
 def test_conv2d_dense_integer_exact_and_padding_edges():
