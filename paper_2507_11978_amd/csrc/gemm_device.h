@@ -164,39 +164,136 @@ __device__ __forceinline__ void mma_tile(const uint16_t *__restrict__ as, const 
     }
 }
 
-// Store alpha * accumulators (+ beta * D, read through D's operand map, if D is given) through
-// C's operand map (masked: out-of-range elements dropped).
+// The parts of a tile's rows and columns under one operand map, kept in LDS (one entry per row / column).
+template <int BM, int BN>
+struct TileParts {
+    int64_t row_off[BM], col_off[BN];
+    int32_t row_chk[BM][kMaxChecks], col_chk[BN][kMaxChecks];
+
+    __device__ __forceinline__ void fill(const OperandMap &m, int64_t row0, int64_t col0, int tid)
+    {
+        for (int r = tid; r < BM; r += kThreads) {
+            const AxisPart p = row_part(m, row0 + r);
+            row_off[r] = p.off;
+            for (int q = 0; q < kMaxChecks; ++q) row_chk[r][q] = p.chk[q];
+        }
+        for (int n = tid; n < BN; n += kThreads) {
+            const AxisPart p = col_part(m, col0 + n);
+            col_off[n] = p.off;
+            for (int q = 0; q < kMaxChecks; ++q) col_chk[n][q] = p.chk[q];
+        }
+    }
+    __device__ __forceinline__ AxisPart row(int r) const
+    {
+        AxisPart p;
+        p.off = row_off[r];
+        for (int q = 0; q < kMaxChecks; ++q) p.chk[q] = row_chk[r][q];
+        return p;
+    }
+    __device__ __forceinline__ AxisPart col(int n) const
+    {
+        AxisPart p;
+        p.off = col_off[n];
+        for (int q = 0; q < kMaxChecks; ++q) p.chk[q] = col_chk[n][q];
+        return p;
+    }
+};
+
+// Store act(alpha * accumulators + beta * D) (D read through its operand map, if given) through C's operand
+// map (masked: out-of-range elements dropped).  pc / pd: the parts of the tile's rows and columns under
+// C's and D's maps, filled beforehand, so that the unrolled element code does no index decomposition.
 template <int BM, int BN>
 __device__ __forceinline__ void store_tile_generic(void *C, const OperandMap &mc, int64_t c_batch_off,
                                                    float16v (&acc)[BM / 64][BN / 64], int64_t row0, int64_t col0,
                                                    int wave_m, int wave_n, int lane, int out_dtype,
-                                                   const void *D, const OperandMap &md, int64_t d_batch_off, float alpha, float beta, int act)
+                                                   const void *D, const OperandMap &md, int64_t d_batch_off, float alpha, float beta, int act,
+                                                   const TileParts<BM, BN> &pc, const TileParts<BM, BN> &pd)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
     const int l32 = lane & 31, hi = lane >> 5;
     const ActParams ap = act_params(act);
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
-        const int64_t col = col0 + wave_n * (BN / 2) + tn * 32 + l32;
-        const AxisPart cp = col_part(mc, col);
+        const int cl = wave_n * (BN / 2) + tn * 32 + l32;
+        const int64_t col = col0 + cl;
+        const AxisPart cp = pc.col(cl);
+        AxisPart dcp = cp;
+        if (D) dcp = pd.col(cl);
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int64_t row = row0 + wave_m * (BM / 2) + tm * 32 + 8 * (v / 4) + 4 * hi + (v % 4);
-                const AxisPart rp = row_part(mc, row);
+                const int rl = wave_m * (BM / 2) + tm * 32 + 8 * (v / 4) + 4 * hi + (v % 4);
+                const int64_t row = row0 + rl;
                 int64_t off;
-                if (element_at(mc, row, col, rp, cp, &off)) {
+                if (element_at(mc, row, col, pc.row(rl), cp, &off)) {
                     float x = acc[tm][tn][v];
                     if (D) {
                         int64_t doff;
-                        const bool in = element_at(md, row, col, row_part(md, row), col_part(md, col), &doff);
+                        const bool in = element_at(md, row, col, pd.row(rl), dcp, &doff);
                         x = combine(x, in ? load_as_f32(D, d_batch_off + doff, out_dtype) : 0.f, alpha, beta);
                     } else {
                         x *= alpha;
                     }
                     store_out(C, c_batch_off + off, act ? activate(x, ap) : x, out_dtype);
                 }
+            }
+        }
+    }
+}
+
+// One (E x BK) operand block of the operand-map kernel into its k-contiguous LDS image `dst`.
+// e_* : parts of the block's E rows (m for A, n for B), k_* : parts of its BK k indices, both in LDS.
+// `e_is_row`: the operand's logical matrix is indexed (e, k) (A) or (k, e) (B).
+// Lanes run along whichever axis has the smaller memory stride, so that a wavefront's element loads
+// fall into few cache lines: along e (each thread keeps one row, gathers 8 consecutive k and writes
+// them with one 16-byte LDS store) or along k (2-byte LDS stores to consecutive addresses).
+template <int E, int BK>
+__device__ __forceinline__ void stage_mapped(const uint16_t *__restrict__ src, const OperandMap &m, bool e_is_row, bool lanes_along_e,
+                                             int64_t e0, int64_t k0, const int64_t *e_off, const int32_t (*e_chk)[kMaxChecks],
+                                             const int64_t *k_off, const int32_t (*k_chk)[kMaxChecks], uint16_t *dst, int tid)
+{
+    auto element = [&](int e, int k, const AxisPart &ep, const AxisPart &kp) -> uint16_t {
+        int64_t off;
+        const bool ok = e_is_row ? element_at(m, e0 + e, k0 + k, ep, kp, &off) : element_at(m, k0 + k, e0 + e, kp, ep, &off);
+        return ok ? src[off] : (uint16_t)0;
+    };
+    auto part_of = [&](const int64_t *off, const int32_t (*chk)[kMaxChecks], int i) {
+        AxisPart p;
+        p.off = off[i];
+        for (int q = 0; q < kMaxChecks; ++q) p.chk[q] = chk[i][q];
+        return p;
+    };
+    if (lanes_along_e) {
+        constexpr int GROUPS = kThreads / E > 0 ? kThreads / E : 1;      // threads per row
+        const int e = tid % E;
+        const AxisPart ep = part_of(e_off, e_chk, e);
+        for (int c8 = (tid / E) * 8; c8 < BK; c8 += GROUPS * 8) {
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t lo = element(e, c8 + 2 * j, ep, part_of(k_off, k_chk, c8 + 2 * j));
+                const uint32_t hi = element(e, c8 + 2 * j + 1, ep, part_of(k_off, k_chk, c8 + 2 * j + 1));
+                w[j] = lo | (hi << 16);
+            }
+            *reinterpret_cast<u32x4 *>(dst + lds_chunk_pos<BK>(e, c8 >> 3)) = u32x4{w[0], w[1], w[2], w[3]};
+        }
+    } else {
+        constexpr int STEP = kThreads / BK, TRIPS = E / STEP;                // rows per pass, passes
+        constexpr int BATCH = TRIPS % 16 == 0 ? 16 : (TRIPS % 8 == 0 ? 8 : (TRIPS % 4 == 0 ? 4 : 1));   // loads in flight per thread
+        const int c = tid % BK;
+        const AxisPart kp = part_of(k_off, k_chk, c);
+        for (int t = 0; t < TRIPS; t += BATCH) {
+            uint16_t v[BATCH];
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int e = tid / BK + (t + u) * STEP;
+                v[u] = element(e, c, part_of(e_off, e_chk, e), kp);
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int e = tid / BK + (t + u) * STEP;
+                dst[lds_chunk_pos<BK>(e, c >> 3) + (c & 7)] = v[u];
             }
         }
     }
@@ -212,6 +309,11 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(
 {
     __shared__ __attribute__((aligned(16))) uint16_t as[BM * BK];
     __shared__ __attribute__((aligned(16))) uint16_t bs[BN * BK];
+    // The mixed-radix decompositions (64-bit divisions) are done once per index, not once per element: the parts of
+    // the tile's rows of A and columns of B once per program, those of a k tile's 2 BK k indices once per k tile.
+    __shared__ int64_t a_row_off[BM], b_col_off[BN], a_k_off[BK], b_k_off[BK];
+    __shared__ int32_t a_row_chk[BM][kMaxChecks], b_col_chk[BN][kMaxChecks], a_k_chk[BK][kMaxChecks], b_k_chk[BK][kMaxChecks];
+    __shared__ TileParts<BM, BN> parts_c, parts_d;             // for the epilogue
     int64_t bi, ti, tj;
     locate_program(mt, nt, &bi, &ti, &tj);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -228,37 +330,45 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
+    // lanes run along the axis with the smaller memory stride (the innermost digit's)
+    auto mag = [](int64_t v) { return v < 0 ? -v : v; };
+    const bool a_lanes_rows = mag(ma.roff[ma.nrd - 1]) < mag(ma.coff[ma.ncd - 1]);
+    const bool b_lanes_cols = mag(mb.coff[mb.ncd - 1]) <= mag(mb.roff[mb.nrd - 1]);
+    for (int r = tid; r < BM; r += kThreads) {
+        const AxisPart p = row_part(ma, row0 + r);
+        a_row_off[r] = p.off;
+        for (int q = 0; q < kMaxChecks; ++q) a_row_chk[r][q] = p.chk[q];
+    }
+    for (int n = tid; n < BN; n += kThreads) {
+        const AxisPart p = col_part(mb, col0 + n);
+        b_col_off[n] = p.off;
+        for (int q = 0; q < kMaxChecks; ++q) b_col_chk[n][q] = p.chk[q];
+    }
+
     for (int64_t k = 0; k < kt; ++k) {
         const int64_t k0 = k * BK;
-        // A tile: element (r, c) of the tile is A_view[row0 + r, k0 + c]
-        {
-            const int c = tid % BK;
-            const AxisPart cp = col_part(ma, k0 + c);
-            for (int r = tid / BK; r < BM; r += kThreads / BK) {
-                const AxisPart rp = row_part(ma, row0 + r);
-                int64_t off;
-                uint16_t v = 0;
-                if (element_at(ma, row0 + r, k0 + c, rp, cp, &off)) v = Ab[off];
-                as[lds_chunk_pos<BK>(r, c >> 3) + (c & 7)] = v;
-            }
+        if (tid < BK) {
+            const AxisPart p = col_part(ma, k0 + tid);
+            a_k_off[tid] = p.off;
+            for (int q = 0; q < kMaxChecks; ++q) a_k_chk[tid][q] = p.chk[q];
+        } else if (tid < 2 * BK) {
+            const AxisPart p = row_part(mb, k0 + tid - BK);
+            b_k_off[tid - BK] = p.off;
+            for (int q = 0; q < kMaxChecks; ++q) b_k_chk[tid - BK][q] = p.chk[q];
         }
-        // B tile: element (c, n) of the tile is B_view[k0 + c, col0 + n]; stored transposed
-        {
-            const int n = tid % BN;
-            const AxisPart cp = col_part(mb, col0 + n);
-            for (int c = tid / BN; c < BK; c += (kThreads / BN > 0 ? kThreads / BN : 1)) {
-                const AxisPart rp = row_part(mb, k0 + c);
-                int64_t off;
-                uint16_t v = 0;
-                if (element_at(mb, k0 + c, col0 + n, rp, cp, &off)) v = Bb[off];
-                bs[lds_chunk_pos<BK>(n, c >> 3) + (c & 7)] = v;
-            }
-        }
+        __syncthreads();
+        // A tile: element (r, c) is A_view[row0 + r, k0 + c]; B tile: element (c, n) is B_view[k0 + c, col0 + n], stored transposed
+        stage_mapped<BM, BK>(Ab, ma, true, a_lanes_rows, row0, k0, a_row_off, a_row_chk, a_k_off, a_k_chk, as, tid);
+        stage_mapped<BN, BK>(Bb, mb, false, b_lanes_cols, col0, k0, b_col_off, b_col_chk, b_k_off, b_k_chk, bs, tid);
         __syncthreads();
         mma_tile<BM, BN, BK, BF16>(as, bs, acc, wave_m, wave_n, lane);
         __syncthreads();
     }
-    store_tile_generic<BM, BN>(C, mc, bi * sc_batch, acc, row0, col0, wave_m, wave_n, lane, out_dtype, D, md, bi * sd_batch, alpha, beta, act);
+    parts_c.fill(mc, row0, col0, tid);
+    if (D) parts_d.fill(md, row0, col0, tid);
+    __syncthreads();
+    store_tile_generic<BM, BN>(C, mc, bi * sc_batch, acc, row0, col0, wave_m, wave_n, lane, out_dtype, D, md, bi * sd_batch, alpha, beta, act,
+                               parts_c, parts_d);
 }
 
 // ---- host-side helper shared by the translation units that instantiate the kernels

@@ -43,6 +43,8 @@ struct AxisPart {
     int32_t chk[kMaxChecks];
 };
 
+// (Loops run over the fixed capacities with the live counts as predicates: every array index is then a
+// compile-time constant and the map stays in scalar registers on the device.)
 NT_HD AxisPart axis_part(int64_t idx, int nd, const int64_t *rad, const int64_t *off,
                          const int32_t (*chk)[kMaxDigits], int nchk)
 {
@@ -50,14 +52,23 @@ NT_HD AxisPart axis_part(int64_t idx, int nd, const int64_t *rad, const int64_t 
     p.off = 0;
     for (int q = 0; q < kMaxChecks; ++q) p.chk[q] = 0;
     int64_t rem = idx;
-    for (int i = nd - 1; i >= 0; --i) {
-        int64_t d = rem;
-        if (i > 0) {
-            d = rem % rad[i];
-            rem = rem / rad[i];
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+#endif
+    for (int i = kMaxDigits - 1; i >= 0; --i) {
+        if (i < nd) {
+            int64_t d = rem;
+            if (i > 0) {
+                d = rem % rad[i];
+                rem = rem / rad[i];
+            }
+            p.off += d * off[i];
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+#endif
+            for (int q = 0; q < kMaxChecks; ++q)
+                if (q < nchk) p.chk[q] += (int32_t)d * chk[q][i];
         }
-        p.off += d * off[i];
-        for (int q = 0; q < nchk; ++q) p.chk[q] += (int32_t)d * chk[q][i];
     }
     return p;
 }
@@ -77,9 +88,12 @@ NT_HD bool element_at(const OperandMap &m, int64_t row, int64_t col, const AxisP
                       int64_t *offset)
 {
     bool ok = row < m.rows && col < m.cols;
-    for (int q = 0; q < m.nchk; ++q) {
-        int32_t x = m.chk0[q] + r.chk[q] + c.chk[q];
-        ok = ok && x >= 0 && x < m.chk_size[q];
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+#endif
+    for (int q = 0; q < kMaxChecks; ++q) {
+        const int32_t x = m.chk0[q] + r.chk[q] + c.chk[q];
+        ok = ok && (q >= m.nchk || (x >= 0 && x < m.chk_size[q]));
     }
     *offset = m.base + r.off + c.off;
     return ok;
