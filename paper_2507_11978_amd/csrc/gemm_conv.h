@@ -131,6 +131,15 @@ struct StageConv {
         const uint32_t half = (g.last_e & 1) ? 0x0000ffffu : 0xffff0000u;
         const uint32_t c0 = (g.last_e >> 1) == 0 ? half : ~0u, c1 = (g.last_e >> 1) == 1 ? half : ~0u;
         const uint32_t c2 = (g.last_e >> 1) == 2 ? half : ~0u, c3 = (g.last_e >> 1) == 3 ? half : ~0u;
+        // lines that were fetched early (only the last runs of the tensor): one test for all eight
+        if ((todo[0] | todo[1]) & (0x07070707u << DOWN_SHIFT)) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int d = (int)((todo[j >> 2] >> (8 * (j & 3) + DOWN_SHIFT)) & 7u);
+                const u32x4 v = shift_down(u32x4{r[j][0], r[j][1], r[j][2], r[j][3]}, d);   // element i <- element i + d, zeros from the top
+                r[j][0] = v[0]; r[j][1] = v[1]; r[j][2] = v[2]; r[j][3] = v[3];
+            }
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint32_t code = (todo[j >> 2] >> (8 * (j & 3))) & 0xffu;
@@ -138,10 +147,6 @@ struct StageConv {
             if (code & MOVE_UP) {                              // element i <- element i - 1 (element 0 is cleared below)
                 v3 = __builtin_amdgcn_alignbit(v3, v2, 16); v2 = __builtin_amdgcn_alignbit(v2, v1, 16);
                 v1 = __builtin_amdgcn_alignbit(v1, v0, 16); v0 = v0 << 16;
-            }
-            if (code >> DOWN_SHIFT) {                          // element i <- element i + d, zeros from the top
-                const u32x4 v = shift_down(u32x4{v0, v1, v2, v3}, (int)(code >> DOWN_SHIFT));
-                v0 = v[0]; v1 = v[1]; v2 = v[2]; v3 = v[3];
             }
             if (code & CLEAR_FIRST) v0 &= 0xffff0000u;
             if (code & CLEAR_LAST) { v0 &= c0; v1 &= c1; v2 &= c2; v3 &= c3; }
