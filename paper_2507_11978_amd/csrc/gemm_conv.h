@@ -31,6 +31,11 @@ struct ConvArgs {
     uint32_t inv_rs, inv_s;        // reciprocals of R*S and S (see udiv_small)
     int64_t mt, nt, kt;
     int out_dtype;
+    // k split: the grid holds `ksplit` copies of the mt x nt programs; copy i multiplies k tiles [i * kt_per, (i + 1) * kt_per)
+    // and writes its partial tile at Y + i * slice elements (Y then being an fp32 workspace of ksplit dense [n][f][p][q] slices
+    // that conv_ws_sum_kernel adds up in a fixed order).  Without a split: ksplit = 1, kt_per = kt, slice = 0.
+    int32_t ksplit, kt_per;
+    int64_t slice;
 };
 
 // floor(t / d) for 0 <= t < 2^16 with inv = floor(2^32 / d) + 1 (d >= 2), inv = 0 standing for d = 1
@@ -189,21 +194,24 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
     constexpr uint32_t B_BASE = 2 * A_BYTES;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    int64_t bi, ti, tj;
+    int64_t bi, ti, tj;                                  // bi: which part of the k range (k split)
     locate_program(g.mt, g.nt, &bi, &ti, &tj);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave >> 1, wave_n = wave & 1;
     const int l32 = lane & 31, hi = lane >> 5;
     const int64_t row0 = ti * BM, col0 = tj * BN;
+    const int64_t kt0 = bi * g.kt_per;                                                   // first k tile of this program
+    const int64_t kt_n = g.kt - kt0 < g.kt_per ? g.kt - kt0 : g.kt_per;                  // and how many
+    const int64_t k_end = (kt0 + kt_n) * kBK < g.K ? (kt0 + kt_n) * kBK : g.K;           // k past its range reads as zero
 
-    const char *gB = reinterpret_cast<const char *>(g.Wt + col0 * g.ldb);
+    const char *gB = reinterpret_cast<const char *>(g.Wt + col0 * g.ldb + kt0 * kBK);
     const int64_t n_left = g.N - col0;
 
     // two sets of staging registers: a tile is requested two trips before it is multiplied
     StageConv sa0, sa1;
     StageK<BN, true> sb0, sb1;
-    sa0.init(tid, g, row0, 0);
-    sa1.init(tid, g, row0, 1);
+    sa0.init(tid, g, row0, (int)kt0);
+    sa1.init(tid, g, row0, (int)kt0 + 1);
     sb0.init(tid, g.ldb);
     sb1.init(tid, g.ldb);
 
@@ -261,14 +269,15 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
     // ---- prologue: k tile 0 -> LDS copy 0 (through set 0), k tile 1 requested into set 1.
     // A block past the last k tile is fully masked (k_left <= 0): nothing is loaded, the surplus
     // LDS copy holds zeros that are never read.
+    const int64_t k_span = k_end - kt0 * kBK;                      // valid k counted from this program's first k tile
 #pragma unroll
-    for (int j = 0; j < 8; ++j) sa0.load_line(g, j, g.K);
+    for (int j = 0; j < 8; ++j) sa0.load_line(g, j, k_span);
     sa0.advance(g, 2);
-    sb0.template load<true>(gB, n_left, g.K);
+    sb0.template load<true>(gB, n_left, k_span);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) sa1.load_line(g, j, (int64_t)g.K - kBK);
+    for (int j = 0; j < 8; ++j) sa1.load_line(g, j, k_span - kBK);
     sa1.advance(g, 2);
-    sb1.template load<true>(gB + kBK * 2, n_left, (int64_t)g.K - kBK);
+    sb1.template load<true>(gB + kBK * 2, n_left, k_span - kBK);
     sa0.settle(g);
     sb0.settle();
     sa0.store(smem, 0);
@@ -285,7 +294,7 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
     uint32_t cur = 0;
     auto trip = [&](auto &fa_set, auto &fb_set, auto &ha, auto &hb, int64_t k) {
         const uint32_t nxt = cur ^ 1u;
-        const int64_t k_left = (int64_t)g.K - (k + 2) * kBK;
+        const int64_t k_left = k_span - (k + 2) * kBK;
         const char *pb = gB + (k + 2) * (kBK * 2);
         kstep(0, 1, cur, std::false_type{}, ha, hb, nxt, [&](int idx) {
 #pragma unroll
@@ -313,11 +322,11 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
         cur = nxt;
     };
     int64_t k = 0;
-    for (; k + 1 < g.kt; k += 2) {
+    for (; k + 1 < kt_n; k += 2) {
         trip(sa0, sb0, sa1, sb1, k);
         trip(sa1, sb1, sa0, sb0, k + 1);
     }
-    if (k < g.kt) trip(sa0, sb0, sa1, sb1, k);
+    if (k < kt_n) trip(sa0, sb0, sa1, sb1, k);
 
     // epilogue: a lane holds one filter f = lane % 32 of each 32 x 32 block; after the half-wavefronts
     // have traded register groups (gather_row16) it owns 16 consecutive output positions m of it,
@@ -352,7 +361,7 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
 #pragma unroll
                     for (int h2 = 0; h2 < 2; ++h2) {
                         if (valid[h2] <= 0) continue;
-                        char *y = reinterpret_cast<char *>(g.Y) + (o_run[h2] + f * g.syf) * ES;
+                        char *y = reinterpret_cast<char *>(g.Y) + (bi * g.slice + o_run[h2] + f * g.syf) * ES;
                         if (valid[h2] == 8) {
                             if constexpr (OUT == NT_F32) {
                                 const u32x4 v0{o[8 * h2], o[8 * h2 + 1], o[8 * h2 + 2], o[8 * h2 + 3]};
@@ -397,7 +406,9 @@ static nt_status launch_conv_inst(const ConvArgs &a, int64_t nwg, hipStream_t s)
     return check_launch("gemm_conv_kernel");
 }
 
-// bn: 128 or 256
+// bn: 128 or 256; nwg = ksplit * mt * nt
 nt_status launch_conv(const ConvArgs &a, int bn, bool bf16, bool edge_b, int64_t nwg, hipStream_t s);
+// Y[n, f, p, q] (strides syn, syf, Q, 1; out_dtype) = sum over the ksplit slices of ws, added in slice order
+nt_status launch_conv_ws_sum(const float *ws, int ksplit, int64_t slice, void *Y, int64_t fpq, int64_t pq, int64_t syn, int64_t syf, int out_dtype, hipStream_t s);
 
 }  // namespace nt

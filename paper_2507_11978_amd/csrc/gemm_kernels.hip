@@ -1,4 +1,6 @@
 // Dispatch between the kernels, plus the small auxiliary kernels (zero fill, address trace).
+#include <mutex>
+
 #include "gemm_conv.h"
 #include "gemm_direct.h"
 
@@ -72,7 +74,43 @@ static bool match_conv(const GemmLaunch &g, ConvArgs *a)
     a->inv_s = h.S > 1 ? (uint32_t)((1ULL << 32) / (uint64_t)h.S) + 1u : 0u;
     a->mt = (NPQ + 255) / 256; a->nt = g.nt; a->kt = g.kt;
     a->out_dtype = g.out_dtype;
+    a->ksplit = 1; a->kt_per = (int32_t)g.kt; a->slice = 0;
     return true;
+}
+
+// Workspace of the convolution's k split: one allocation per device, grown on demand (never beyond kConvWsMax) and
+// kept until the process ends.  Every call on a device shares it: calls that overlap on one device (two streams) race.
+static constexpr size_t kConvWsMax = 256u << 20;
+static float *conv_workspace(size_t bytes)
+{
+    struct Ws { float *p; size_t bytes; };
+    static Ws table[64] = {};
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64 || bytes > kConvWsMax) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    Ws &w = table[dev];
+    if (w.bytes < bytes) {
+        if (w.p) (void)hipFree(w.p);                           // (waits for the work that still uses it)
+        w.p = nullptr; w.bytes = 0;
+        void *p = nullptr;
+        if (hipMalloc(&p, bytes) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        w.p = (float *)p; w.bytes = bytes;
+    }
+    return w.p;
+}
+
+// A convolution with few output tiles and a long reduction leaves most of the chip idle: its k tiles are dealt to
+// `ksplit` programs per output tile, enough for about one program per compute unit, none with fewer than 4 k tiles.
+static int conv_ksplit(int64_t programs, int64_t kt, int32_t *kt_per)
+{
+    *kt_per = (int32_t)kt;
+    if (programs >= 128 || kt < 8) return 1;
+    const int64_t want = std::min<int64_t>((256 + programs / 2) / programs, kt / 4);
+    if (want < 2) return 1;
+    const int64_t per = (kt + want - 1) / want;
+    *kt_per = (int32_t)per;
+    return (int)((kt + per - 1) / per);
 }
 
 // A map is "plain" when it is a strided matrix without bounds checks beyond rows / cols.
@@ -104,7 +142,20 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         if (!g.has_d && g.alpha == 1.f && g.act == 0 && match_conv(g, &c)) {
             if (path_out) *path_out = PATH_CONV;
             const bool edge_b = (g.N % t.bn) || (g.K % t.bk);
-            return launch_conv(c, t.bn, g.in_dtype == NT_BF16, edge_b, c.mt * c.nt, (hipStream_t)g.stream);
+            hipStream_t s = (hipStream_t)g.stream;
+            int32_t kt_per = 0;
+            const int ksplit = conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
+            const int64_t slice = g.conv.N * (int64_t)c.N * c.PQ;
+            float *ws = ksplit > 1 ? conv_workspace((size_t)ksplit * slice * 4) : nullptr;   // (none: too large, or no memory; then no split)
+            if (ws) {
+                ConvArgs part = c;
+                part.Y = ws; part.syn = (int64_t)c.N * c.PQ; part.syf = c.PQ; part.out_dtype = NT_F32;
+                part.ksplit = ksplit; part.kt_per = kt_per; part.slice = slice;
+                const nt_status st = launch_conv(part, t.bn, g.in_dtype == NT_BF16, edge_b, c.mt * c.nt * ksplit, s);
+                if (st != NT_OK) return st;
+                return launch_conv_ws_sum(ws, ksplit, slice, c.Y, (int64_t)c.N * c.PQ, c.PQ, c.syn, c.syf, c.out_dtype, s);
+            }
+            return launch_conv(c, t.bn, g.in_dtype == NT_BF16, edge_b, c.mt * c.nt, s);
         }
     }
     if (fast) {

@@ -449,6 +449,47 @@ def test_conv2d_dense_rows_that_are_no_multiple_of_eight(shape, pad):
         assert torch.isnan(buf[:32]).all() and torch.isnan(buf[32 + ref.size:]).all()
 
 
+@pytest.mark.parametrize("shape,pad", [
+    ((4, 64, 14, 14, 128, 3, 3), (1, 1)),      # 9 k tiles: two parts (5 + 4)
+    ((2, 100, 10, 10, 96, 3, 3), (1, 1)),      # K = 900: 15 k tiles in three parts, the last one ragged; 96 filters
+    ((3, 256, 8, 8, 130, 3, 3), (0, 0)),       # 36 k tiles, Q = 6
+    ((2, 512, 7, 7, 256, 1, 1), (0, 0)),       # 1 x 1 filter, 8 k tiles
+])
+def test_conv2d_dense_split_along_k(shape, pad):
+    """Few output tiles and a long reduction: the k tiles are dealt to several programs per output tile, whose fp32
+    partial tiles a second kernel adds up.  Small integers: exact whatever the order of the sums, in every output format.  The output is a
+    channel slice of a larger tensor (its batch stride is not its size) and what lies around it must stay untouched;
+    the calls share one workspace, which grows from one shape to the next."""
+    N, Cc, H, W, K, R, S = shape
+    for dt, out in (("f16", "f32"), ("bf16", "bf16"), ("f16", "f16")):
+        X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, dt, seed=29, dist="int")
+        ref = onum.conv2d(X, Wt, dt, (1, 1), pad)
+        big = torch.full((N, K + 3, ref.shape[2], ref.shape[3]), float("nan"), dtype=TORCH_DT[out], device="cuda")
+        Y = big[:, 2:K + 2]
+        nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), pad)
+        torch.cuda.synchronize()
+        assert nt.last_kernel_path() == nt.PATH_CONV
+        # the sums are integers below 2^24: exact in fp32, then rounded once (to nearest even) to the output format
+        want = torch.from_numpy(ref).to(torch.float32).to(TORCH_DT[out])
+        assert torch.equal(Y.cpu(), want), f"conv split {shape} {pad} {dt} {out}"
+        assert torch.isnan(big[:, :2]).all() and torch.isnan(big[:, K + 2:]).all()
+
+
+def test_conv2d_dense_split_along_k_is_reproducible():
+    # the partial tiles are added in a fixed order: two runs give the same bits (random data, fp32 output)
+    N, Cc, H, W, K, R, S = 4, 128, 14, 14, 128, 3, 3
+    X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, "f16", seed=30)
+    ref = onum.conv2d(X, Wt, "f16", (1, 1), (1, 1))
+    x, w = to_gpu(X, "f16"), to_gpu(Wt, "f16")
+    Y1 = torch.full(ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+    Y2 = torch.full(ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+    nt.conv2d_implicit(x, w, Y1, (1, 1), (1, 1))
+    nt.conv2d_implicit(x, w, Y2, (1, 1), (1, 1))
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y2)
+    assert_gates(to_f64(Y1), ref, "f32", "conv split, random data")
+
+
 def test_conv2d_dense_integer_exact_and_padding_edges():
     # small integers: exact; a wrong halo element or a missed padding row changes the result
     N, Cc, H, W, K, R, S = 2, 8, 16, 16, 128, 3, 3
