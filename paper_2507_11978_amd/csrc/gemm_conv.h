@@ -185,6 +185,77 @@ struct StageConv {
     }
 };
 
+// Epilogue of the convolution kernels.  A lane holds one filter f = lane % 32 of each 32 x 32 block; after the
+// half-wavefronts have traded register groups (gather_row16) it owns 16 consecutive output positions m of it,
+// stored as two runs of 8 (a run lies in one output row: the kernel's row pitch is a multiple of 8) with
+// 16-byte stores along the contiguous (p, q) axis of the output; the run at the end of a row whose length is
+// no multiple of 8 is stored position by position.  row0w / col0w: first position / filter of this wavefront;
+// part: which part of the k range the program multiplied (k split; 0 without).
+template <int BM, int BN, int OUT>
+__device__ __forceinline__ void conv_store_runs(const ConvArgs &g, float16v (&acc)[BM / 64][BN / 64], int64_t part, int64_t row0w, int64_t col0w, int lane)
+{
+    constexpr int TM = BM / 64, TN = BN / 64;
+    const int l32 = lane & 31, hi = lane >> 5;
+    constexpr int ES = OUT == NT_F32 ? 4 : 2;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        int64_t o_run[2];
+        int valid[2];                                          // positions of the run that exist (0: none)
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+            const int64_t m = row0w + tm * 32 + 16 * hi + 8 * h2;
+            const bool m_ok = m < g.M;
+            const uint32_t mm = m_ok ? (uint32_t)m : 0u;
+            const uint32_t n = mm / (uint32_t)g.PQ8;
+            const uint32_t pq = mm - n * (uint32_t)g.PQ8;
+            const uint32_t p = pq / (uint32_t)g.Q8;
+            const int q0 = (int)(pq - p * (uint32_t)g.Q8);
+            o_run[h2] = (int64_t)n * g.syn + (int64_t)p * g.Q + q0;
+            valid[h2] = m_ok ? (g.Q - q0 < 8 ? g.Q - q0 : 8) : 0;
+        }
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            uint32_t o[16];
+            gather_row16(acc[tm][tn], o);                      // (all lanes take part)
+            const int64_t f = col0w + tn * 32 + l32;
+            if (f < g.N) {
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    if (valid[h2] <= 0) continue;
+                    char *y = reinterpret_cast<char *>(g.Y) + (part * g.slice + o_run[h2] + f * g.syf) * ES;
+                    if (valid[h2] == 8) {
+                        if constexpr (OUT == NT_F32) {
+                            const u32x4 v0{o[8 * h2], o[8 * h2 + 1], o[8 * h2 + 2], o[8 * h2 + 3]};
+                            const u32x4 v1{o[8 * h2 + 4], o[8 * h2 + 5], o[8 * h2 + 6], o[8 * h2 + 7]};
+                            __builtin_memcpy(y, &v0, 16);
+                            __builtin_memcpy(y + 16, &v1, 16);
+                        } else {
+                            const u32x4 v{pack_pair<OUT>(o[8 * h2], o[8 * h2 + 1]), pack_pair<OUT>(o[8 * h2 + 2], o[8 * h2 + 3]),
+                                          pack_pair<OUT>(o[8 * h2 + 4], o[8 * h2 + 5]), pack_pair<OUT>(o[8 * h2 + 6], o[8 * h2 + 7])};
+                            __builtin_memcpy(y, &v, 16);
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 7; ++i)
+                            if (i < valid[h2]) {
+                                if constexpr (OUT == NT_F32) *reinterpret_cast<uint32_t *>(y + 4 * i) = o[8 * h2 + i];
+                                else *reinterpret_cast<uint16_t *>(y + 2 * i) = (uint16_t)pack_pair<OUT>(o[8 * h2 + i], 0u);
+                            }
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN>
+__device__ __forceinline__ void conv_store(const ConvArgs &g, float16v (&acc)[BM / 64][BN / 64], int64_t part, int64_t row0w, int64_t col0w, int lane)
+{
+    if (g.out_dtype == NT_F32) conv_store_runs<BM, BN, NT_F32>(g, acc, part, row0w, col0w, lane);
+    else if (g.out_dtype == NT_F16) conv_store_runs<BM, BN, NT_F16>(g, acc, part, row0w, col0w, lane);
+    else conv_store_runs<BM, BN, NT_BF16>(g, acc, part, row0w, col0w, lane);
+}
+
 template <int BN, bool BF16, bool EDGE_B>
 __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
 {
@@ -328,67 +399,7 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
     }
     if (k < kt_n) trip(sa0, sb0, sa1, sb1, k);
 
-    // epilogue: a lane holds one filter f = lane % 32 of each 32 x 32 block; after the half-wavefronts
-    // have traded register groups (gather_row16) it owns 16 consecutive output positions m of it,
-    // stored as two runs of 8 (a run lies in one output row: the kernel's row pitch is a multiple of 8)
-    // with 16-byte stores along the contiguous (p, q) axis of the output; the run at the end of a row
-    // whose length is no multiple of 8 is stored position by position.
-    auto store_runs = [&](auto out_tag) {
-        constexpr int OUT = decltype(out_tag)::value;
-        constexpr int ES = OUT == NT_F32 ? 4 : 2;
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
-            int64_t o_run[2];
-            int valid[2];                                          // positions of the run that exist (0: none)
-#pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2) {
-                const int64_t m = row0 + wave_m * (BM / 2) + tm * 32 + 16 * hi + 8 * h2;
-                const bool m_ok = m < g.M;
-                const uint32_t mm = m_ok ? (uint32_t)m : 0u;
-                const uint32_t n = mm / (uint32_t)g.PQ8;
-                const uint32_t pq = mm - n * (uint32_t)g.PQ8;
-                const uint32_t p = pq / (uint32_t)g.Q8;
-                const int q0 = (int)(pq - p * (uint32_t)g.Q8);
-                o_run[h2] = (int64_t)n * g.syn + (int64_t)p * g.Q + q0;
-                valid[h2] = m_ok ? (g.Q - q0 < 8 ? g.Q - q0 : 8) : 0;
-            }
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                uint32_t o[16];
-                gather_row16(acc[tm][tn], o);                      // (all lanes take part)
-                const int64_t f = col0 + wave_n * (BN / 2) + tn * 32 + l32;
-                if (f < g.N) {
-#pragma unroll
-                    for (int h2 = 0; h2 < 2; ++h2) {
-                        if (valid[h2] <= 0) continue;
-                        char *y = reinterpret_cast<char *>(g.Y) + (bi * g.slice + o_run[h2] + f * g.syf) * ES;
-                        if (valid[h2] == 8) {
-                            if constexpr (OUT == NT_F32) {
-                                const u32x4 v0{o[8 * h2], o[8 * h2 + 1], o[8 * h2 + 2], o[8 * h2 + 3]};
-                                const u32x4 v1{o[8 * h2 + 4], o[8 * h2 + 5], o[8 * h2 + 6], o[8 * h2 + 7]};
-                                __builtin_memcpy(y, &v0, 16);
-                                __builtin_memcpy(y + 16, &v1, 16);
-                            } else {
-                                const u32x4 v{pack_pair<OUT>(o[8 * h2], o[8 * h2 + 1]), pack_pair<OUT>(o[8 * h2 + 2], o[8 * h2 + 3]),
-                                              pack_pair<OUT>(o[8 * h2 + 4], o[8 * h2 + 5]), pack_pair<OUT>(o[8 * h2 + 6], o[8 * h2 + 7])};
-                                __builtin_memcpy(y, &v, 16);
-                            }
-                        } else {
-#pragma unroll
-                            for (int i = 0; i < 7; ++i)
-                                if (i < valid[h2]) {
-                                    if constexpr (OUT == NT_F32) *reinterpret_cast<uint32_t *>(y + 4 * i) = o[8 * h2 + i];
-                                    else *reinterpret_cast<uint16_t *>(y + 2 * i) = (uint16_t)pack_pair<OUT>(o[8 * h2 + i], 0u);
-                                }
-                        }
-                    }
-                }
-            }
-        }
-    };
-    if (g.out_dtype == NT_F32) store_runs(std::integral_constant<int, NT_F32>{});
-    else if (g.out_dtype == NT_F16) store_runs(std::integral_constant<int, NT_F16>{});
-    else store_runs(std::integral_constant<int, NT_BF16>{});
+    conv_store<BM, BN>(g, acc, bi, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
 }
 
 template <int BN, bool BF16, bool EDGE_B>

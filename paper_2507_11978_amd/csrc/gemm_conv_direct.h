@@ -1,0 +1,326 @@
+// Implicit-GEMM convolution (Section 4.3) whose operand blocks travel straight into LDS.
+//
+// Same problem class as gemm_conv.h (contiguous NCHW input, unit conv stride, k-contiguous filter, output dense
+// in (p, q)), same numbering of the output positions (row pitch rounded up to a multiple of 8) and same epilogue,
+// with the pipeline of the direct GEMM kernel: 32-k slices in a ring of three or four LDS slots, no staging registers.
+//
+// The unfolded input A[m, kk] = x[n, c, p + r - pad_h, q + s - pad_w] is contiguous along m, so its slice is the
+// mn-major LDS layout [32 kk][256 m] read with transposing LDS reads.  One 16-byte chunk is a run of 8 consecutive
+// q of one (c, r, s) line; the lane that owns the chunk's LDS slot computes where the run starts inside x and fetches
+// it with a range-checked buffer load (2-byte aligned).  What cannot be fetched as it is:
+//   * a run whose input row lies in the top / bottom padding, whose kk is past the program's k range or whose
+//     position is past M: the lane passes an offset outside the buffer and zeros arrive;
+//   * the one element of a run that falls into the left / right padding: fetched (it is the neighbouring row's end /
+//     start, inside x) and overwritten with zero in LDS by the same lane once the run has landed, before the
+//     barrier that publishes the slice;
+//   * the tensor's very first run with a tap left of it, and its last runs with taps right of them, would start
+//     outside x: fetched one element late / up to 7 early and shifted into place in LDS by the same lane.
+// The filter is the direct kernel's k-major B operand (range checked: rows past the last filter read as zero).
+// Requirements checked by the host: K % 32 == 0 (no ragged slice), filter pitch and base 16-byte aligned,
+// R, S <= 8, byte offsets inside x below 2^31.
+#pragma once
+#include "gemm_conv.h"
+#include "gemm_direct.h"
+
+namespace nt {
+
+// mn-major slice of the unfolded input: 32 kk rows x 256 positions
+struct ConvTileA {
+    static constexpr int E = 256;
+    static constexpr uint32_t BYTES = E * kSliceK * 2;
+    static constexpr int PER = BYTES / 1024 / 4;           // load instructions per wavefront and slice (4)
+    static constexpr int RPF = 2;
+    static constexpr int RB = 2 * E;                       // bytes per kk row
+    static constexpr int T = E / 64;
+    static constexpr uint32_t kOutside = 0x80000000u;      // byte offset past every buffer this kernel accepts
+    enum { CLEAR_FIRST = 1, CLEAR_LAST = 2, MOVE_UP = 4, DOWN_SHIFT = 3 /* bits 3..5: elements to move down by */ };
+
+    uint32_t rd[T];
+    // Load j of a slice covers kk row 8 * wave + 2 * j + lane / 32 and, because of the bank swizzle (chunk ^= (kk & 3) * 4),
+    // one of two runs of 8 positions: run j % 2.
+    int32_t base[2];               // element offset of x[n, 0, p - ph, q0 - pw] of the run
+    uint32_t masks[2];             // bits 0..7: input row p + r - ph inside the image (and m < M); bit 8 + 2 s: with tap s the
+                                   // run's first element is padding; bit 9 + 2 s: with tap s its element last_e is padding
+    // the kk row of load j in the slice that is requested next: 4 * (r * S + s), c * HW, and the tap's table entry
+    // (looked up one slice ahead, so that nobody waits for it)
+    uint32_t rs4[PER];
+    int32_t coff[PER];
+    uint32_t tap[PER];
+
+    // Table of the R * S filter taps in LDS (at byte offset `table`): r * W + s | (1 << r) << 16 | (8 + 2 s) << 24
+    static constexpr uint32_t kTableBytes = 64 * 4;
+    static __device__ __forceinline__ void fill_table(char *smem, uint32_t table, const ConvArgs &g, int tid)
+    {
+        if (tid < g.RS) {
+            const uint32_t r = udiv_small((uint32_t)tid, g.inv_s), sx = (uint32_t)tid - r * (uint32_t)g.S;
+            *reinterpret_cast<uint32_t *>(smem + table + 4 * tid) = (r * (uint32_t)g.W + sx) | (0x10000u << r) | ((8 + 2 * sx) << 24);
+        }
+    }
+
+    // k_first: first kk of the program; the table must be complete
+    __device__ __forceinline__ void init(int wave, int lane, const ConvArgs &g, int64_t row0, int32_t k_first, int wave_origin, uint32_t region,
+                                         const char *smem, uint32_t table)
+    {
+        const int hi = lane >> 5;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int chunk = (lane & 31) ^ ((2 * e + hi) << 2);
+            const int64_t m = row0 + chunk * 8;
+            const bool m_ok = m < g.M;
+            const uint32_t mm = m_ok ? (uint32_t)m : 0u;
+            const uint32_t nn = mm / (uint32_t)g.PQ8;
+            const uint32_t pq = mm - nn * (uint32_t)g.PQ8;
+            const uint32_t p = pq / (uint32_t)g.Q8;
+            const int32_t q0 = (int32_t)(pq - p * (uint32_t)g.Q8);
+            base[e] = (int32_t)(nn * (uint32_t)g.CHW) + ((int32_t)p - g.ph) * g.W + q0 - g.pw;
+            uint32_t mk = 0;
+            for (int rr = 0; rr < g.R; ++rr) {
+                const int h = (int)p + rr - g.ph;
+                if (m_ok && h >= 0 && h < g.H) mk |= 1u << rr;
+            }
+            for (int sx = 0; sx < g.S; ++sx) {
+                if (q0 + sx - g.pw < 0) mk |= 0x100u << (2 * sx);
+                if (q0 + 8 >= g.Q && g.Q - 1 + sx - g.pw >= g.W) mk |= 0x200u << (2 * sx);
+            }
+            masks[e] = mk;
+        }
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const uint32_t k = (uint32_t)(k_first + 8 * wave + 2 * j + hi);
+            const uint32_t c = udiv_small(k, g.inv_rs);
+            rs4[j] = 4u * (k - c * (uint32_t)g.RS);
+            coff[j] = (int32_t)c * g.HW;
+            tap[j] = *reinterpret_cast<const uint32_t *>(smem + table + rs4[j]);
+        }
+        // transposing read (see DirectTile<E, MNCONTIG>)
+        const int gq = lane >> 4, i = lane & 15;
+        const int kl = 8 * (gq >> 1) + (i >> 2);
+        const int mn = wave_origin + 16 * (gq & 1) + 4 * (i & 3);
+        const int sw = (i >> 2) << 2;
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+            rd[t] = (uint32_t)(kl * RB + ((((mn >> 3) + 4 * t) ^ sw) << 4) + ((mn >> 2) & 1) * 8) + region;
+    }
+
+    // Requests load j of the next slice into the LDS slot at lds_slice (live = false: the slice lies past the program's
+    // k range, zeros are requested) and moves the state on by one slice (step4 = 4 * (32 % RS), stepc = 32 / RS * HW);
+    // returns what has to be done to the run once it has landed (0: nothing).
+    __device__ __forceinline__ uint32_t issue_one(int j, const ConvArgs &g, u32x4 rsrc, bool live, uint32_t step4, int32_t stepc,
+                                                  const char *smem, uint32_t table, uint32_t lds_slice, int wave)
+    {
+        const int e = j & 1;
+        const uint32_t t = tap[j], mk = masks[e];
+        const int32_t l_off = base[e] + coff[j] + (int32_t)(t & 0xffffu);
+        bool ok = live && (mk & (t >> 16) & 0xffu);
+        uint32_t code = (mk >> (t >> 24)) & 3u;
+        const int32_t hi_lim = (int32_t)g.x_numel - 8;
+        int32_t offc = l_off;
+        if (l_off < 0) { offc = 0; code |= MOVE_UP; }              // (l_off = -1: only pw <= 1 is accepted)
+        if (l_off > hi_lim) {
+            const int32_t d = l_off - hi_lim;
+            offc = hi_lim;
+            if (d < 8) code |= (uint32_t)d << DOWN_SHIFT;
+            else ok = false;                                       // nothing of the run lies inside x
+        }
+        dma16_buf(rsrc, ok ? (uint32_t)offc * 2u : kOutside, 0u, lds_slice + (uint32_t)((wave * PER + j) * 1024));
+        // the same row of the slice after it
+        uint32_t nrs = rs4[j] + step4;
+        int32_t nco = coff[j] + stepc;
+        if (nrs >= 4u * (uint32_t)g.RS) { nrs -= 4u * (uint32_t)g.RS; nco += g.HW; }
+        rs4[j] = nrs;
+        coff[j] = nco;
+        tap[j] = *reinterpret_cast<const uint32_t *>(smem + table + nrs);
+        return ok ? code : 0u;
+    }
+
+    // what issue_one() noted for the four runs of a slice (8 bits each in `codes`), applied in LDS
+    __device__ __forceinline__ void settle(uint32_t codes, char *smem, const ConvArgs &g, uint32_t slot_off, int wave, int lane) const
+    {
+        if (codes == 0) return;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const uint32_t code = (codes >> (8 * j)) & 0xffu;
+            if (code == 0) continue;
+            const uint32_t at = slot_off + (uint32_t)((wave * PER + j) * 1024 + lane * 16);
+            if (code & ~(uint32_t)(CLEAR_FIRST | CLEAR_LAST)) {
+                u32x4 v = lds_read16(smem, at);
+                if (code & MOVE_UP) {                              // element i <- element i - 1 (element 0 is cleared below)
+                    v = u32x4{v[0] << 16, __builtin_amdgcn_alignbit(v[1], v[0], 16), __builtin_amdgcn_alignbit(v[2], v[1], 16),
+                              __builtin_amdgcn_alignbit(v[3], v[2], 16)};
+                } else {
+                    v = shift_down(v, (int)((code >> DOWN_SHIFT) & 7u));   // element i <- element i + d, zeros from the top
+                }
+                lds_write16(smem, at, v);
+            }
+            if (code & CLEAR_FIRST) *reinterpret_cast<uint16_t *>(smem + at) = 0;
+            if (code & CLEAR_LAST) *reinterpret_cast<uint16_t *>(smem + at + 2 * g.last_e) = 0;
+        }
+    }
+
+    __device__ __forceinline__ void read(u32x2 (&f)[2], const char *smem, int t, int ks, int part, uint32_t slice_off) const
+    {
+        typedef short4v __attribute__((address_space(3))) * lds_s4;
+        const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (rd[t] + slice_off + (uint32_t)((ks * 16 + part * 4) * RB))));
+        f[part] = __builtin_bit_cast(u32x2, v);
+    }
+};
+
+template <int BN, bool BF16>
+__global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_direct_kernel(const ConvArgs g)
+{
+    constexpr int BM = 256;
+    constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr int kRing = ring_of(BM, BN);
+    using TileA = ConvTileA;
+    using TileB = DirectTile<BN, KCONTIG>;
+    constexpr uint32_t A_BYTES = TileA::BYTES, B_BYTES = TileB::BYTES, B_BASE = kRing * A_BYTES;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    int64_t bi, ti, tj;                                  // bi: which part of the k range (k split)
+    locate_program(g.mt, g.nt, &bi, &ti, &tj);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = wave >> 1, wave_n = wave & 1;
+    const int64_t row0 = ti * BM, col0 = tj * BN;
+    const int64_t kt0 = bi * g.kt_per;                                                   // first k tile of this program
+    const int64_t kt_n = g.kt - kt0 < g.kt_per ? g.kt - kt0 : g.kt_per;                  // and how many
+    const int32_t k_first = (int32_t)(kt0 * kBK);
+    const int32_t k_end = (int32_t)((kt0 + kt_n) * kBK < g.K ? (kt0 + kt_n) * kBK : g.K);
+    const int64_t n_slices = (k_end - k_first) / kSliceK;                                // (K is a multiple of 32)
+
+    const char *gB0 = reinterpret_cast<const char *>(g.Wt);
+    const char *gB = reinterpret_cast<const char *>(g.Wt + col0 * g.ldb + k_first);
+    constexpr int64_t b_step = (int64_t)kSliceK * 2;
+
+    constexpr uint32_t TABLE = kRing * (A_BYTES + B_BYTES);
+    TileA::fill_table(smem, TABLE, g, tid);
+    __syncthreads();
+    TileA ta;
+    TileB tb;
+    ta.init(wave, lane, g, row0, k_first, wave_m * (BM / 2), 0, smem, TABLE);
+    tb.init(wave, lane, g.ldb, wave_n * (BN / 2), B_BASE);
+    const uint32_t step4 = 4u * (uint32_t)(kSliceK % g.RS);
+    const int32_t stepc = (kSliceK / g.RS) * g.HW;
+    const u32x4 rsrc_a = make_rsrc(g.X, g.x_numel * 2);
+    const u32x4 rsrc_b = make_rsrc(gB, ((int64_t)(g.N - 1) * g.ldb + g.K) * 2 - (gB - gB0));
+
+    float16v acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+
+    u32x2 fa[2][TM][2], fb[2][TN][2];
+    constexpr int NRB = TN * TileB::RPF, NR = TM * TileA::RPF + NRB;
+    auto lds_read = [&](int r, int slot, int ks, uint32_t ring) {
+        if (r < TileA::RPF) {
+            ta.read(fa[slot][0], smem, 0, ks, r, ring * A_BYTES);
+        } else if (r < TileA::RPF + NRB) {
+            const int q = r - TileA::RPF;
+            tb.read(fb[slot][q / TileB::RPF], smem, q / TileB::RPF, ks, q % TileB::RPF, ring * B_BYTES);
+        } else {
+            const int q = r - NRB;
+            ta.read(fa[slot][q / TileA::RPF], smem, q / TileA::RPF, ks, q % TileA::RPF, ring * A_BYTES);
+        }
+    };
+    constexpr int NM = TM * TN, ND = TileA::PER + TileB::PER;
+    const int64_t last = n_slices - 1;
+    // load d of slice s (counted from the program's first) into ring position `ring`; the codes of the input's runs
+    // are collected in `codes`.  A slice past the program's range is requested all the same (the loop has one
+    // shape): its runs arrive as zeros, its filter chunks are those of the last slice, nobody reads either.
+    auto dma = [&](int d, int64_t s, uint32_t ring, uint32_t &codes) {
+        if (d < TileA::PER) {
+            codes |= ta.issue_one(d, g, rsrc_a, s < n_slices, step4, stepc, smem, TABLE, lds0 + ring * A_BYTES, wave) << (8 * d);
+        } else {
+            const int64_t sc = s < last ? s : last;
+            tb.issue_one_buf(d - TileA::PER, rsrc_b, (uint32_t)(sc * b_step), lds0 + B_BASE + ring * B_BYTES, wave);
+        }
+    };
+    auto step = [&](int slot, int ks_next, uint32_t rring, int nd, int64_t s, uint32_t dring, uint32_t &codes) {
+        constexpr int RQ = (NR + NM - 1) / NM;
+#pragma unroll
+        for (int idx = 0; idx < NM; ++idx) {
+            const int tm = idx / TN, tn = idx % TN;
+            const u32x4 xa{fa[slot][tm][0][0], fa[slot][tm][0][1], fa[slot][tm][1][0], fa[slot][tm][1][1]};
+            const u32x4 xb{fb[slot][tn][0][0], fb[slot][tn][0][1], fb[slot][tn][1][0], fb[slot][tn][1][1]};
+            acc[tm][tn] = mfma32<BF16>(xa, xb, acc[tm][tn]);   // a lane holds filter lane % 32 (see conv_store_runs)
+#pragma unroll
+            for (int q = 0; q < RQ; ++q)
+                if (idx * RQ + q < NR) lds_read(idx * RQ + q, slot ^ 1, ks_next, rring);
+            if (nd > 0) {
+                const int per = (nd + NM - 1) / NM;
+                const int gap = nd >= NM ? 1 : NM / nd;
+                if (idx % gap == gap - 1)
+#pragma unroll
+                    for (int q = 0; q < per; ++q)
+                        if ((idx / gap) * per + q < nd) dma((idx / gap) * per + q, s, dring, codes);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // codes of the slices in flight, oldest first: pending[i] belongs to slice (current + 1 + i)
+    uint32_t pending[kRing - 1];
+    {
+        uint32_t c0 = 0;
+#pragma unroll
+        for (int d = 0; d < ND; ++d) dma(d, 0, 0, c0);
+#pragma unroll
+        for (int s = 1; s < kRing; ++s) {
+            pending[s - 1] = 0;
+#pragma unroll
+            for (int d = 0; d < ND; ++d) dma(d, s, s, pending[s - 1]);
+        }
+        NT_WAIT_VMCNT((kRing - 1) * ND);
+        ta.settle(c0, smem, g, 0, wave, lane);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < NR; ++r) lds_read(r, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // one slice per trip, as in the direct GEMM kernel; the runs of slice s + 1 are put right between the wait
+    // for this wavefront's loads and the barrier that publishes the slice
+    uint32_t ring = 0;
+    for (int64_t sl = 0; sl < n_slices; ++sl) {
+        const uint32_t nxt = ring + 1 == kRing ? 0 : ring + 1;
+        uint32_t unused = 0, fresh = 0;
+        step(0, 1, ring, 0, 0, 0, unused);
+        NT_WAIT_VMCNT((kRing - 2) * ND);
+        ta.settle(pending[0], smem, g, nxt * A_BYTES, wave, lane);
+        __syncthreads();
+        step(1, 0, nxt, ND, sl + kRing, ring, fresh);
+#pragma unroll
+        for (int i = 0; i + 1 < kRing - 1; ++i) pending[i] = pending[i + 1];
+        pending[kRing - 2] = fresh;
+        ring = nxt;
+    }
+    NT_WAIT_VMCNT(0);
+    __syncthreads();
+
+    conv_store<BM, BN>(g, acc, bi, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
+}
+
+template <int BN, bool BF16>
+static nt_status launch_conv_direct_inst(const ConvArgs &a, int64_t nwg, hipStream_t s)
+{
+    constexpr size_t smem = (size_t)ring_of(256, BN) * (256 + BN) * kSliceK * sizeof(uint16_t) + ConvTileA::kTableBytes;
+    auto kern = gemm_conv_direct_kernel<BN, BF16>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
+    return check_launch("gemm_conv_direct_kernel");
+}
+
+// bn: 128 or 256; nwg = ksplit * mt * nt
+nt_status launch_conv_direct(const ConvArgs &a, int bn, bool bf16, int64_t nwg, hipStream_t s);
+
+}  // namespace nt

@@ -1,7 +1,7 @@
 // Dispatch between the kernels, plus the small auxiliary kernels (zero fill, address trace).
 #include <mutex>
 
-#include "gemm_conv.h"
+#include "gemm_conv_direct.h"
 #include "gemm_direct.h"
 
 namespace nt {
@@ -147,15 +147,22 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             const int ksplit = conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
             const int64_t slice = g.conv.N * (int64_t)c.N * c.PQ;
             float *ws = ksplit > 1 ? conv_workspace((size_t)ksplit * slice * 4) : nullptr;   // (none: too large, or no memory; then no split)
+            // operands that can stream straight into LDS: whole 32-k slices, 16-byte aligned filter rows, 32-bit byte offsets
+            const bool direct = c.K % 32 == 0 && c.ldb % 8 == 0 && (reinterpret_cast<uintptr_t>(c.Wt) & 15) == 0 && c.R <= 8 && c.S <= 8 &&
+                                c.x_numel < (1LL << 30) && ((int64_t)(c.N - 1) * c.ldb + c.K) < (1LL << 30);
+            const bool bf16 = g.in_dtype == NT_BF16;
+            auto launch = [&](const ConvArgs &ca, int64_t nwg) {
+                return direct ? launch_conv_direct(ca, t.bn, bf16, nwg, s) : launch_conv(ca, t.bn, bf16, edge_b, nwg, s);
+            };
             if (ws) {
                 ConvArgs part = c;
                 part.Y = ws; part.syn = (int64_t)c.N * c.PQ; part.syf = c.PQ; part.out_dtype = NT_F32;
                 part.ksplit = ksplit; part.kt_per = kt_per; part.slice = slice;
-                const nt_status st = launch_conv(part, t.bn, g.in_dtype == NT_BF16, edge_b, c.mt * c.nt * ksplit, s);
+                const nt_status st = launch(part, c.mt * c.nt * ksplit);
                 if (st != NT_OK) return st;
                 return launch_conv_ws_sum(ws, ksplit, slice, c.Y, (int64_t)c.N * c.PQ, c.PQ, c.syn, c.syf, c.out_dtype, s);
             }
-            return launch_conv(c, t.bn, g.in_dtype == NT_BF16, edge_b, c.mt * c.nt, s);
+            return launch(c, c.mt * c.nt);
         }
     }
     if (fast) {
