@@ -33,7 +33,7 @@ struct ConvTileA {
     static constexpr int RB = 2 * E;                       // bytes per kk row
     static constexpr int T = E / 64;
     static constexpr uint32_t kOutside = 0x80000000u;      // byte offset past every buffer this kernel accepts
-    enum { CLEAR_FIRST = 1, CLEAR_LAST = 2, MOVE_UP = 4, DOWN_SHIFT = 3 /* bits 3..5: elements to move down by */ };
+    enum { CLEAR_FIRST = 1, CLEAR_LAST = 2, MOVE_UP = 4, DOWN_SHIFT = 3 /* bits 3..6: elements to move down by (0..8) */ };
 
     uint32_t rd[T];
     // Load j of a slice covers kk row 8 * wave + 2 * j + lane / 32 and, because of the bank swizzle (chunk ^= (kk & 3) * 4),
@@ -102,26 +102,25 @@ struct ConvTileA {
             rd[t] = (uint32_t)(kl * RB + ((((mn >> 3) + 4 * t) ^ sw) << 4) + ((mn >> 2) & 1) * 8) + region;
     }
 
-    // Requests load j of the next slice into the LDS slot at lds_slice (live = false: the slice lies past the program's
-    // k range, zeros are requested) and moves the state on by one slice (step4 = 4 * (32 % RS), stepc = 32 / RS * HW);
-    // returns what has to be done to the run once it has landed (0: nothing).
-    __device__ __forceinline__ uint32_t issue_one(int j, const ConvArgs &g, u32x4 rsrc, bool live, uint32_t step4, int32_t stepc,
+    // Requests load j of the next slice into the LDS slot at lds_slice and moves the state on by one slice
+    // (step4 = 4 * (32 % RS), stepc = 32 / RS * HW); returns what has to be done to the run once it has landed
+    // (0: nothing).  Slices past the program's k range are requested like any other (from wherever the clamped
+    // offsets point inside x): nobody reads them.
+    __device__ __forceinline__ uint32_t issue_one(int j, const ConvArgs &g, u32x4 rsrc, uint32_t step4, int32_t stepc,
                                                   const char *smem, uint32_t table, uint32_t lds_slice, int wave)
     {
         const int e = j & 1;
         const uint32_t t = tap[j], mk = masks[e];
         const int32_t l_off = base[e] + coff[j] + (int32_t)(t & 0xffffu);
-        bool ok = live && (mk & (t >> 16) & 0xffu);
-        uint32_t code = (mk >> (t >> 24)) & 3u;
         const int32_t hi_lim = (int32_t)g.x_numel - 8;
-        int32_t offc = l_off;
-        if (l_off < 0) { offc = 0; code |= MOVE_UP; }              // (l_off = -1: only pw <= 1 is accepted)
-        if (l_off > hi_lim) {
-            const int32_t d = l_off - hi_lim;
-            offc = hi_lim;
-            if (d < 8) code |= (uint32_t)d << DOWN_SHIFT;
-            else ok = false;                                       // nothing of the run lies inside x
-        }
+        // a run that would start before x (by one element: only pw <= 1 is accepted) or end after it is fetched from
+        // the nearest place inside and moved by settle(); 8 or more elements late: nothing of the run lies inside x
+        const int32_t late = std::min(std::max(l_off - hi_lim, 0), 8);
+        const int32_t offc = std::min(std::max(l_off, 0), hi_lim);
+        uint32_t code = (mk >> (t >> 24)) & 3u;
+        code |= ((uint32_t)l_off >> 29) & (uint32_t)MOVE_UP;
+        code |= (uint32_t)late << DOWN_SHIFT;
+        const bool ok = (mk & (t >> 16) & 0xffu) != 0;
         dma16_buf(rsrc, ok ? (uint32_t)offc * 2u : kOutside, 0u, lds_slice + (uint32_t)((wave * PER + j) * 1024));
         // the same row of the slice after it
         uint32_t nrs = rs4[j] + step4;
@@ -148,7 +147,8 @@ struct ConvTileA {
                     v = u32x4{v[0] << 16, __builtin_amdgcn_alignbit(v[1], v[0], 16), __builtin_amdgcn_alignbit(v[2], v[1], 16),
                               __builtin_amdgcn_alignbit(v[3], v[2], 16)};
                 } else {
-                    v = shift_down(v, (int)((code >> DOWN_SHIFT) & 7u));   // element i <- element i + d, zeros from the top
+                    const uint32_t d = code >> DOWN_SHIFT;                 // element i <- element i + d, zeros from the top
+                    v = d < 8 ? shift_down(v, (int)d) : u32x4{0, 0, 0, 0};
                 }
                 lds_write16(smem, at, v);
             }
@@ -231,10 +231,10 @@ __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_dir
     const int64_t last = n_slices - 1;
     // load d of slice s (counted from the program's first) into ring position `ring`; the codes of the input's runs
     // are collected in `codes`.  A slice past the program's range is requested all the same (the loop has one
-    // shape): its runs arrive as zeros, its filter chunks are those of the last slice, nobody reads either.
+    // shape; its filter chunks are those of the last slice): nobody reads it.
     auto dma = [&](int d, int64_t s, uint32_t ring, uint32_t &codes) {
         if (d < TileA::PER) {
-            codes |= ta.issue_one(d, g, rsrc_a, s < n_slices, step4, stepc, smem, TABLE, lds0 + ring * A_BYTES, wave) << (8 * d);
+            codes |= ta.issue_one(d, g, rsrc_a, step4, stepc, smem, TABLE, lds0 + ring * A_BYTES, wave) << (8 * d);
         } else {
             const int64_t sc = s < last ? s : last;
             tb.issue_one_buf(d - TileA::PER, rsrc_b, (uint32_t)(sc * b_step), lds0 + B_BASE + ring * B_BYTES, wave);
