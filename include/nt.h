@@ -145,7 +145,8 @@ nt_status nt_arrange_conv2d(const nt_tensor_desc *dx, const nt_tensor_desc *dw, 
 nt_status nt_program_order(int64_t batch, int64_t mt, int64_t nt, int64_t *pid_out);
 
 /* Which kernel the calling thread's last nt_gemm / nt_addmm / nt_addmm_act / nt_bmm / nt_conv2d_implicit call launched:
- * 0 operand-map (generic) kernel, 1 staged kernel, 2 direct-to-LDS kernel, 3 convolution kernel,
+ * 0 operand-map (generic) kernel, 1 staged kernel, 2 direct-to-LDS kernel, 3 convolution kernel (operands staged
+ * through registers), 4 convolution kernel (operands streamed straight into LDS),
  * -1 none (nothing launched yet, an error, or an empty problem).  For tests and diagnostics. */
 int32_t nt_last_kernel_path(void);
 

@@ -42,10 +42,9 @@ bool tile_is_built(nt_tile_cfg cfg)
     return false;
 }
 
-// The dense convolution that gemm_conv_kernel handles: contiguous NCHW input, conv stride 1, at
-// most one element of left / right padding, output rows that are multiples of 8 long, a filter
-// whose (c, r, s) are contiguous, an output with contiguous (p, q).  Everything else runs on the
-// operand-map kernel.
+// The dense convolution that the convolution kernels handle: contiguous NCHW input, conv stride 1, at
+// most one element of left / right padding, a filter whose (c, r, s) are contiguous, an output with
+// contiguous (p, q).  Everything else runs on the operand-map kernel.
 static bool match_conv(const GemmLaunch &g, ConvArgs *a)
 {
     const ConvHint &h = g.conv;
@@ -150,6 +149,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             // operands that can stream straight into LDS: whole 32-k slices, 16-byte aligned filter rows, 32-bit byte offsets
             const bool direct = c.K % 32 == 0 && c.ldb % 8 == 0 && (reinterpret_cast<uintptr_t>(c.Wt) & 15) == 0 && c.R <= 8 && c.S <= 8 &&
                                 c.x_numel < (1LL << 30) && ((int64_t)(c.N - 1) * c.ldb + c.K) < (1LL << 30);
+            if (direct && path_out) *path_out = PATH_CONV_DIRECT;
             const bool bf16 = g.in_dtype == NT_BF16;
             auto launch = [&](const ConvArgs &ca, int64_t nwg) {
                 return direct ? launch_conv_direct(ca, t.bn, bf16, nwg, s) : launch_conv(ca, t.bn, bf16, edge_b, nwg, s);

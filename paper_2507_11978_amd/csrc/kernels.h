@@ -41,7 +41,7 @@ struct GemmLaunch {
 };
 
 // Which code path a launch would take (reported for tests and the benchmark).
-enum KernelPath { PATH_GENERIC = 0, PATH_FAST = 1, PATH_DIRECT = 2, PATH_CONV = 3 };
+enum KernelPath { PATH_GENERIC = 0, PATH_FAST = 1, PATH_DIRECT = 2, PATH_CONV = 3, PATH_CONV_DIRECT = 4 };
 
 bool tile_is_built(nt_tile_cfg cfg);
 nt_status launch_gemm(const GemmLaunch &g, int *path_out);

@@ -34,10 +34,14 @@ struct ViewPrograms { const nt_meta_op *ops[3]; int32_t n[3]; };
 // launch, prologue and epilogue, which `resident` co-resident workgroups overlap with each
 // other's multiplications.  The constants are fits to measurements on 8192 x 8192 x K and
 // batched 2048 x 2048 x K problems.
-nt_tile_cfg pick_tile(int kind, int64_t batch, int64_t M, int64_t N, int64_t K, nt_tile_cfg cfg)
+// unit_stride: a convolution with stride 1 (the class the dedicated convolution kernels take)
+nt_tile_cfg pick_tile(int kind, int64_t batch, int64_t M, int64_t N, int64_t K, nt_tile_cfg cfg, bool unit_stride = false)
 {
     if (cfg.bm || cfg.bn || cfg.bk) return cfg;
-    if (M <= 64 || N <= 64) return nt_tile_cfg{64, 64, 32};
+    // few output positions and a long reduction (the last layers of a network at batch 1): the convolution kernel, its k
+    // tiles dealt to many programs, beats the small operand-map tile by far although most of its 256 rows stay empty
+    const bool long_conv = kind == KIND_CONV && unit_stride && N >= 128 && K >= 512;
+    if ((M <= 64 && !long_conv) || N <= 64) return nt_tile_cfg{64, 64, 32};
     if (kind == KIND_CONV) {
         // the convolution kernel is built for 256 output positions per program; 128 filters per program when
         // 256 would leave half the compute units without one
@@ -112,7 +116,7 @@ nt_status build_problem(int kind, const nt_tensor_desc *d0, const nt_tensor_desc
     p->N = sb[o + 1];
     if (sb[o] != p->K) return fail(NT_ERR_SHAPE_MISMATCH, "inner dimensions of A and B differ");
     if (sc[o] != p->M || sc[o + 1] != p->N) return fail(NT_ERR_SHAPE_MISMATCH, "output shape differs from [M, N]");
-    p->tile = pick_tile(kind, p->batch, p->M, p->N, p->K, cfg);
+    p->tile = pick_tile(kind, p->batch, p->M, p->N, p->K, cfg, sh == 1 && sw == 1);
     NT_TRY(nt::arrange_matmul(p->va, p->vb, p->vc, p->tile, &p->mm));
     return NT_OK;
 }

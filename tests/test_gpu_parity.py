@@ -343,7 +343,8 @@ def test_conv2d_dense_unit_stride(shape, pad, tile, dt, out):
     Y = torch.full(ref.shape, float("nan"), dtype=TORCH_DT[out], device="cuda")
     nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), pad, tile=tile)
     torch.cuda.synchronize()
-    assert nt.last_kernel_path() == nt.PATH_CONV
+    # whole 32-k slices (C * R * S a multiple of 32) stream straight into LDS, other reductions are staged through registers
+    assert nt.last_kernel_path() == (nt.PATH_CONV_DIRECT if (Cc * R * S) % 32 == 0 else nt.PATH_CONV)
     assert_gates(to_f64(Y), ref, out, f"conv dense {shape} {pad} {tile}")
 
 
@@ -428,6 +429,15 @@ def test_kernel_paths_are_the_intended_ones():
     ((1, 8, 6, 17, 128, 3, 2), (0, 1)),        # even filter width, Q = 18
     ((8, 4, 5, 5, 128, 5, 5), (2, 1)),         # Q = 3 < 8
     ((1, 24, 28, 28, 256, 3, 3), (1, 1)),      # Q = 28
+    # the same with reductions that are whole 32-k slices (the kernel that streams its operands straight into LDS)
+    ((4, 32, 14, 14, 128, 3, 3), (1, 1)),
+    ((4, 32, 14, 14, 128, 3, 3), (0, 0)),
+    ((3, 32, 7, 7, 130, 3, 3), (1, 1)),
+    ((2, 64, 12, 9, 128, 1, 1), (0, 0)),
+    ((1, 16, 6, 17, 128, 3, 2), (0, 1)),
+    ((8, 32, 5, 5, 128, 5, 5), (2, 1)),
+    ((1, 32, 28, 28, 256, 3, 3), (1, 1)),
+    ((2, 32, 9, 11, 136, 3, 3), (1, 0)),
 ])
 def test_conv2d_dense_rows_that_are_no_multiple_of_eight(shape, pad):
     """Output rows of any length: the kernel numbers positions with the row pitch rounded up to 8 and never stores the
@@ -441,11 +451,10 @@ def test_conv2d_dense_rows_that_are_no_multiple_of_eight(shape, pad):
         Y = buf[32:32 + ref.size].view(ref.shape)
         nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), pad)
         torch.cuda.synchronize()
-        assert nt.last_kernel_path() == nt.PATH_CONV
-        if out == "f32":
-            assert np.array_equal(to_f64(Y), ref)
-        else:
-            assert_gates(to_f64(Y), ref, out, f"conv {shape} {pad}")
+        assert nt.last_kernel_path() == (nt.PATH_CONV_DIRECT if (Cc * R * S) % 32 == 0 else nt.PATH_CONV)
+        # the sums are integers below 2^24: exact in fp32, then rounded once (to nearest even) to the output format
+        want = torch.from_numpy(ref).to(torch.float32).to(TORCH_DT[out])
+        assert torch.equal(Y.cpu(), want), f"conv {shape} {pad} {dt} {out}"
         assert torch.isnan(buf[:32]).all() and torch.isnan(buf[32 + ref.size:]).all()
 
 
@@ -454,6 +463,7 @@ def test_conv2d_dense_rows_that_are_no_multiple_of_eight(shape, pad):
     ((2, 100, 10, 10, 96, 3, 3), (1, 1)),      # K = 900: 15 k tiles in three parts, the last one ragged; 96 filters
     ((3, 256, 8, 8, 130, 3, 3), (0, 0)),       # 36 k tiles, Q = 6
     ((2, 512, 7, 7, 256, 1, 1), (0, 0)),       # 1 x 1 filter, 8 k tiles
+    ((1, 128, 7, 7, 256, 3, 3), (1, 1)),       # 49 output positions: one tile of 256 rows, 18 k tiles in four parts
 ])
 def test_conv2d_dense_split_along_k(shape, pad):
     """Few output tiles and a long reduction: the k tiles are dealt to several programs per output tile, whose fp32
@@ -468,7 +478,7 @@ def test_conv2d_dense_split_along_k(shape, pad):
         Y = big[:, 2:K + 2]
         nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), pad)
         torch.cuda.synchronize()
-        assert nt.last_kernel_path() == nt.PATH_CONV
+        assert nt.last_kernel_path() == (nt.PATH_CONV_DIRECT if (Cc * R * S) % 32 == 0 else nt.PATH_CONV)
         # the sums are integers below 2^24: exact in fp32, then rounded once (to nearest even) to the output format
         want = torch.from_numpy(ref).to(torch.float32).to(TORCH_DT[out])
         assert torch.equal(Y.cpu(), want), f"conv split {shape} {pad} {dt} {out}"
