@@ -270,6 +270,13 @@ nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const n
  * out-of-image positions (padding) read as zero.  dy must have P = (H + 2*pad_h - R) /
  * stride_h + 1 (integer division), likewise Q; otherwise NT_ERR_SHAPE_MISMATCH.
  * Descriptors have ndim 4 with arbitrary strides.
+ * Memory: a dense unit-stride call with few output tiles and a long reduction has its reduction dealt to
+ * several programs per tile, whose fp32 partial tiles go through a workspace that the library owns: one device
+ * allocation per GPU, made (or grown, never beyond 256 MB) by the first call that needs it (so such a call can
+ * allocate, and cannot be captured in a HIP graph before the workspace has its size), kept until the process
+ * ends and shared by all calls on that GPU: calls that overlap on one GPU (different streams) race on it.  If
+ * the allocation fails the call runs without the split.  Results do not depend on any of this bit for bit
+ * (the partial tiles are added in a fixed order).
  */
 nt_status nt_conv2d_implicit(const void *x, const nt_tensor_desc *dx, const void *w, const nt_tensor_desc *dw,
                              void *y, const nt_tensor_desc *dy,
