@@ -275,8 +275,8 @@ nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const n
  * allocation per GPU, made (or grown, never beyond 256 MB) by the first call that needs it (so such a call can
  * allocate, and cannot be captured in a HIP graph before the workspace has its size), kept until the process
  * ends and shared by all calls on that GPU: calls that overlap on one GPU (different streams) race on it.  If
- * the allocation fails the call runs without the split.  Results do not depend on any of this bit for bit
- * (the partial tiles are added in a fixed order).
+ * the allocation fails the call runs without the split.  The partial tiles are added in a fixed order: a call
+ * repeated on the same data gives the same bits.
  */
 nt_status nt_conv2d_implicit(const void *x, const nt_tensor_desc *dx, const void *w, const nt_tensor_desc *dw,
                              void *y, const nt_tensor_desc *dy,
