@@ -256,6 +256,59 @@ __device__ __forceinline__ void conv_store(const ConvArgs &g, float16v (&acc)[BM
     else conv_store_runs<BM, BN, NT_BF16>(g, acc, part, row0w, col0w, lane);
 }
 
+// The same for accumulators held the other way round (MFMA operands swapped): a lane holds one output position
+// m = lane % 32 of each 32 x 32 block and, register by register, 16 of its filters (8 * (v / 4) + 4 * (lane / 32) + v % 4).
+// Every store instruction then writes, per half-wavefront, 32 consecutive positions of one filter: whole 64- or 128-byte
+// segments of the output's contiguous (p, q) axis, where conv_store_runs touches 64 different cache lines with 16 bytes each.
+// An element's address is a wavefront-uniform base (the filter) plus a 32-bit lane offset (the position, and the
+// lane half's 4 filters): the host admits only outputs whose byte offsets fit 31 bits.
+template <int BM, int BN, int OUT>
+__device__ __forceinline__ void conv_store_points(const ConvArgs &g, float16v (&acc)[BM / 64][BN / 64], int64_t part, int64_t row0w, int64_t col0w, int lane)
+{
+    constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr int ES = OUT == NT_F32 ? 4 : 2;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int64_t f_pitch = g.syf * ES;
+    char *const y0 = reinterpret_cast<char *>(g.Y) + part * g.slice * ES + col0w * f_pitch;
+    const uint32_t half_off = (uint32_t)(4 * hi) * (uint32_t)f_pitch;
+    auto put = [&](char *at, float x) {
+        if constexpr (OUT == NT_F32) *reinterpret_cast<float *>(at) = x;
+        else *reinterpret_cast<uint16_t *>(at) = (uint16_t)pack_pair<OUT>(__builtin_bit_cast(uint32_t, x), 0u);
+    };
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int64_t m = row0w + tm * 32 + l32;
+        const uint32_t mm = m < g.M ? (uint32_t)m : 0u;
+        const uint32_t n = mm / (uint32_t)g.PQ8;
+        const uint32_t pq = mm - n * (uint32_t)g.PQ8;
+        const uint32_t p = pq / (uint32_t)g.Q8;
+        const int q = (int)(pq - p * (uint32_t)g.Q8);
+        if (m >= g.M || q >= g.Q) continue;                         // past the last position, or one of a row's surplus positions
+        const uint32_t lane_off = (uint32_t)((int64_t)n * g.syn + (int64_t)p * g.Q + q) * (uint32_t)ES + half_off;
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            char *const yb = y0 + (tn * 32) * f_pitch;              // (uniform)
+            if (col0w + tn * 32 + 32 <= g.N) {                      // (the same for the whole wavefront)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) put(yb + (8 * (v / 4) + v % 4) * f_pitch + lane_off, acc[tm][tn][v]);
+            } else {
+                const int64_t room = g.N - (col0w + tn * 32 + 4 * hi);   // filters from this lane's first on
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (8 * (v / 4) + v % 4 < room) put(yb + (8 * (v / 4) + v % 4) * f_pitch + lane_off, acc[tm][tn][v]);
+            }
+        }
+    }
+}
+
+template <int BM, int BN>
+__device__ __forceinline__ void conv_store_transposed(const ConvArgs &g, float16v (&acc)[BM / 64][BN / 64], int64_t part, int64_t row0w, int64_t col0w, int lane)
+{
+    if (g.out_dtype == NT_F32) conv_store_points<BM, BN, NT_F32>(g, acc, part, row0w, col0w, lane);
+    else if (g.out_dtype == NT_F16) conv_store_points<BM, BN, NT_F16>(g, acc, part, row0w, col0w, lane);
+    else conv_store_points<BM, BN, NT_BF16>(g, acc, part, row0w, col0w, lane);
+}
+
 template <int BN, bool BF16, bool EDGE_B>
 __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
 {

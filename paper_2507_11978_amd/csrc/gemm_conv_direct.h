@@ -1,8 +1,8 @@
 // Implicit-GEMM convolution (Section 4.3) whose operand blocks travel straight into LDS.
 //
 // Same problem class as gemm_conv.h (contiguous NCHW input, unit conv stride, k-contiguous filter, output dense
-// in (p, q)), same numbering of the output positions (row pitch rounded up to a multiple of 8) and same epilogue,
-// with the pipeline of the direct GEMM kernel: 32-k slices in a ring of three or four LDS slots, no staging registers.
+// in (p, q)), same numbering of the output positions (row pitch rounded up to a multiple of 8), with the pipeline
+// of the direct GEMM kernel: 32-k slices in a ring of three or four LDS slots, no staging registers.
 //
 // The unfolded input A[m, kk] = x[n, c, p + r - pad_h, q + s - pad_w] is contiguous along m, so its slice is the
 // mn-major LDS layout [32 kk][256 m] read with transposing LDS reads.  One 16-byte chunk is a run of 8 consecutive
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_dir
             const int tm = idx / TN, tn = idx % TN;
             const u32x4 xa{fa[slot][tm][0][0], fa[slot][tm][0][1], fa[slot][tm][1][0], fa[slot][tm][1][1]};
             const u32x4 xb{fb[slot][tn][0][0], fb[slot][tn][0][1], fb[slot][tn][1][0], fb[slot][tn][1][1]};
-            acc[tm][tn] = mfma32<BF16>(xa, xb, acc[tm][tn]);   // a lane holds filter lane % 32 (see conv_store_runs)
+            acc[tm][tn] = mfma32<BF16>(xb, xa, acc[tm][tn]);   // transposed block: a lane holds position lane % 32 (see conv_store_points)
 #pragma unroll
             for (int q = 0; q < RQ; ++q)
                 if (idx * RQ + q < NR) lds_read(idx * RQ + q, slot ^ 1, ks_next, rring);
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_dir
     NT_WAIT_VMCNT(0);
     __syncthreads();
 
-    conv_store<BM, BN>(g, acc, bi, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
+    conv_store_transposed<BM, BN>(g, acc, bi, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
 }
 
 template <int BN, bool BF16>

@@ -147,8 +147,10 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             const int64_t slice = g.conv.N * (int64_t)c.N * c.PQ;
             float *ws = ksplit > 1 ? conv_workspace((size_t)ksplit * slice * 4) : nullptr;   // (none: too large, or no memory; then no split)
             // operands that can stream straight into LDS: whole 32-k slices, 16-byte aligned filter rows, 32-bit byte offsets
+            // (the k split's workspace, at most 256 MB, always has them)
             const bool direct = c.K % 32 == 0 && c.ldb % 8 == 0 && (reinterpret_cast<uintptr_t>(c.Wt) & 15) == 0 && c.R <= 8 && c.S <= 8 &&
-                                c.x_numel < (1LL << 30) && ((int64_t)(c.N - 1) * c.ldb + c.K) < (1LL << 30);
+                                c.x_numel < (1LL << 30) && ((int64_t)(c.N - 1) * c.ldb + c.K) < (1LL << 30) &&
+                                ((g.conv.N - 1) * c.syn + (int64_t)(c.N - 1) * c.syf + c.PQ) < (1LL << 29);   // (output offsets: 31 bits of bytes)
             if (direct && path_out) *path_out = PATH_CONV_DIRECT;
             const bool bf16 = g.in_dtype == NT_BF16;
             auto launch = [&](const ConvArgs &ca, int64_t nwg) {
