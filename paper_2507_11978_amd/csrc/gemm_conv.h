@@ -12,7 +12,7 @@
 // input row lies in the top / bottom padding, and transposes the 8 x 8 patch in registers
 // into the k-contiguous LDS layout.  The filter is a k-contiguous B operand; the MFMA core
 // and the LDS layout are those of the staged GEMM kernel.  The output tile is written
-// along m (contiguous in NKPQ), 4 consecutive m per store.
+// along m (contiguous in NKPQ), 32 consecutive m per half-wavefront and store (conv_store_points).
 #pragma once
 #include "gemm_fast.h"
 
@@ -185,84 +185,18 @@ struct StageConv {
     }
 };
 
-// Epilogue of the convolution kernels.  A lane holds one filter f = lane % 32 of each 32 x 32 block; after the
-// half-wavefronts have traded register groups (gather_row16) it owns 16 consecutive output positions m of it,
-// stored as two runs of 8 (a run lies in one output row: the kernel's row pitch is a multiple of 8) with
-// 16-byte stores along the contiguous (p, q) axis of the output; the run at the end of a row whose length is
-// no multiple of 8 is stored position by position.  row0w / col0w: first position / filter of this wavefront;
-// part: which part of the k range the program multiplied (k split; 0 without).
-template <int BM, int BN, int OUT>
-__device__ __forceinline__ void conv_store_runs(const ConvArgs &g, float16v (&acc)[BM / 64][BN / 64], int64_t part, int64_t row0w, int64_t col0w, int lane)
-{
-    constexpr int TM = BM / 64, TN = BN / 64;
-    const int l32 = lane & 31, hi = lane >> 5;
-    constexpr int ES = OUT == NT_F32 ? 4 : 2;
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        int64_t o_run[2];
-        int valid[2];                                          // positions of the run that exist (0: none)
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-            const int64_t m = row0w + tm * 32 + 16 * hi + 8 * h2;
-            const bool m_ok = m < g.M;
-            const uint32_t mm = m_ok ? (uint32_t)m : 0u;
-            const uint32_t n = mm / (uint32_t)g.PQ8;
-            const uint32_t pq = mm - n * (uint32_t)g.PQ8;
-            const uint32_t p = pq / (uint32_t)g.Q8;
-            const int q0 = (int)(pq - p * (uint32_t)g.Q8);
-            o_run[h2] = (int64_t)n * g.syn + (int64_t)p * g.Q + q0;
-            valid[h2] = m_ok ? (g.Q - q0 < 8 ? g.Q - q0 : 8) : 0;
-        }
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            uint32_t o[16];
-            gather_row16(acc[tm][tn], o);                      // (all lanes take part)
-            const int64_t f = col0w + tn * 32 + l32;
-            if (f < g.N) {
-#pragma unroll
-                for (int h2 = 0; h2 < 2; ++h2) {
-                    if (valid[h2] <= 0) continue;
-                    char *y = reinterpret_cast<char *>(g.Y) + (part * g.slice + o_run[h2] + f * g.syf) * ES;
-                    if (valid[h2] == 8) {
-                        if constexpr (OUT == NT_F32) {
-                            const u32x4 v0{o[8 * h2], o[8 * h2 + 1], o[8 * h2 + 2], o[8 * h2 + 3]};
-                            const u32x4 v1{o[8 * h2 + 4], o[8 * h2 + 5], o[8 * h2 + 6], o[8 * h2 + 7]};
-                            __builtin_memcpy(y, &v0, 16);
-                            __builtin_memcpy(y + 16, &v1, 16);
-                        } else {
-                            const u32x4 v{pack_pair<OUT>(o[8 * h2], o[8 * h2 + 1]), pack_pair<OUT>(o[8 * h2 + 2], o[8 * h2 + 3]),
-                                          pack_pair<OUT>(o[8 * h2 + 4], o[8 * h2 + 5]), pack_pair<OUT>(o[8 * h2 + 6], o[8 * h2 + 7])};
-                            __builtin_memcpy(y, &v, 16);
-                        }
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < 7; ++i)
-                            if (i < valid[h2]) {
-                                if constexpr (OUT == NT_F32) *reinterpret_cast<uint32_t *>(y + 4 * i) = o[8 * h2 + i];
-                                else *reinterpret_cast<uint16_t *>(y + 2 * i) = (uint16_t)pack_pair<OUT>(o[8 * h2 + i], 0u);
-                            }
-                    }
-                }
-            }
-        }
-    }
-}
-
-template <int BM, int BN>
-__device__ __forceinline__ void conv_store(const ConvArgs &g, float16v (&acc)[BM / 64][BN / 64], int64_t part, int64_t row0w, int64_t col0w, int lane)
-{
-    if (g.out_dtype == NT_F32) conv_store_runs<BM, BN, NT_F32>(g, acc, part, row0w, col0w, lane);
-    else if (g.out_dtype == NT_F16) conv_store_runs<BM, BN, NT_F16>(g, acc, part, row0w, col0w, lane);
-    else conv_store_runs<BM, BN, NT_BF16>(g, acc, part, row0w, col0w, lane);
-}
-
-// The same for accumulators held the other way round (MFMA operands swapped): a lane holds one output position
-// m = lane % 32 of each 32 x 32 block and, register by register, 16 of its filters (8 * (v / 4) + 4 * (lane / 32) + v % 4).
-// Every store instruction then writes, per half-wavefront, 32 consecutive positions of one filter: whole 64- or 128-byte
-// segments of the output's contiguous (p, q) axis, where conv_store_runs touches 64 different cache lines with 16 bytes each.
-// An element's address is a wavefront-uniform base (the filter) plus a 32-bit lane offset (the position, and the
-// lane half's 4 filters): the host admits only outputs whose byte offsets fit 31 bits.
-template <int BM, int BN, int OUT>
+// Epilogue of the convolution kernels.  The MFMAs are issued with their operands swapped, so a lane holds one output
+// position m = lane % 32 of each 32 x 32 block and, register by register, 16 of its filters
+// (8 * (v / 4) + 4 * (lane / 32) + v % 4).  Every store instruction then writes, per half-wavefront, 32 consecutive
+// positions of one filter: whole 64- or 128-byte segments of the output's contiguous (p, q) axis.  (With a lane holding
+// one filter and runs of positions, a store touched 64 different cache lines with 16 bytes each and the epilogue of a
+// 256 x 256 program took 16 us instead of 5.6.)  Positions past M and a row's surplus positions (the kernels number
+// positions with the row pitch rounded up to a multiple of 8) are not stored.
+// An element's address is a wavefront-uniform base (the filter) plus a lane offset (the position, and the lane half's
+// 4 filters) of type OFF: uint32_t where the host has checked that the output's byte offsets fit 31 bits, else int64_t.
+// row0w / col0w: first position / filter of this wavefront; part: which part of the k range the program multiplied
+// (k split; 0 without).
+template <int BM, int BN, int OUT, typename OFF>
 __device__ __forceinline__ void conv_store_points(const ConvArgs &g, float16v (&acc)[BM / 64][BN / 64], int64_t part, int64_t row0w, int64_t col0w, int lane)
 {
     constexpr int TM = BM / 64, TN = BN / 64;
@@ -270,7 +204,7 @@ __device__ __forceinline__ void conv_store_points(const ConvArgs &g, float16v (&
     const int l32 = lane & 31, hi = lane >> 5;
     const int64_t f_pitch = g.syf * ES;
     char *const y0 = reinterpret_cast<char *>(g.Y) + part * g.slice * ES + col0w * f_pitch;
-    const uint32_t half_off = (uint32_t)(4 * hi) * (uint32_t)f_pitch;
+    const OFF half_off = (OFF)(4 * hi) * (OFF)f_pitch;
     auto put = [&](char *at, float x) {
         if constexpr (OUT == NT_F32) *reinterpret_cast<float *>(at) = x;
         else *reinterpret_cast<uint16_t *>(at) = (uint16_t)pack_pair<OUT>(__builtin_bit_cast(uint32_t, x), 0u);
@@ -284,7 +218,7 @@ __device__ __forceinline__ void conv_store_points(const ConvArgs &g, float16v (&
         const uint32_t p = pq / (uint32_t)g.Q8;
         const int q = (int)(pq - p * (uint32_t)g.Q8);
         if (m >= g.M || q >= g.Q) continue;                         // past the last position, or one of a row's surplus positions
-        const uint32_t lane_off = (uint32_t)((int64_t)n * g.syn + (int64_t)p * g.Q + q) * (uint32_t)ES + half_off;
+        const OFF lane_off = (OFF)((int64_t)n * g.syn + (int64_t)p * g.Q + q) * (OFF)ES + half_off;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             char *const yb = y0 + (tn * 32) * f_pitch;              // (uniform)
@@ -301,12 +235,12 @@ __device__ __forceinline__ void conv_store_points(const ConvArgs &g, float16v (&
     }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, typename OFF>
 __device__ __forceinline__ void conv_store_transposed(const ConvArgs &g, float16v (&acc)[BM / 64][BN / 64], int64_t part, int64_t row0w, int64_t col0w, int lane)
 {
-    if (g.out_dtype == NT_F32) conv_store_points<BM, BN, NT_F32>(g, acc, part, row0w, col0w, lane);
-    else if (g.out_dtype == NT_F16) conv_store_points<BM, BN, NT_F16>(g, acc, part, row0w, col0w, lane);
-    else conv_store_points<BM, BN, NT_BF16>(g, acc, part, row0w, col0w, lane);
+    if (g.out_dtype == NT_F32) conv_store_points<BM, BN, NT_F32, OFF>(g, acc, part, row0w, col0w, lane);
+    else if (g.out_dtype == NT_F16) conv_store_points<BM, BN, NT_F16, OFF>(g, acc, part, row0w, col0w, lane);
+    else conv_store_points<BM, BN, NT_BF16, OFF>(g, acc, part, row0w, col0w, lane);
 }
 
 template <int BN, bool BF16, bool EDGE_B>
@@ -372,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
         constexpr int GAP = NM / NR > 0 ? NM / NR : 1;
 #pragma unroll
         for (int idx = 0; idx < NM; ++idx) {
-            acc[idx / TN][idx % TN] = mfma32<BF16>(fa[slot][idx / TN], fb[slot][idx % TN], acc[idx / TN][idx % TN]);
+            acc[idx / TN][idx % TN] = mfma32<BF16>(fb[slot][idx % TN], fa[slot][idx / TN], acc[idx / TN][idx % TN]);   // transposed block (see conv_store_points)
             if (idx % GAP == 0)
 #pragma unroll
                 for (int q = 0; q < RQ; ++q)
@@ -452,7 +386,7 @@ __global__ __launch_bounds__(kThreads) void gemm_conv_kernel(const ConvArgs g)
     }
     if (k < kt_n) trip(sa0, sb0, sa1, sb1, k);
 
-    conv_store<BM, BN>(g, acc, bi, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
+    conv_store_transposed<BM, BN, int64_t>(g, acc, bi, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
 }
 
 template <int BN, bool BF16, bool EDGE_B>

@@ -302,7 +302,7 @@ __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_dir
     NT_WAIT_VMCNT(0);
     __syncthreads();
 
-    conv_store_transposed<BM, BN>(g, acc, bi, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
+    conv_store_transposed<BM, BN, uint32_t>(g, acc, bi, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
 }
 
 template <int BN, bool BF16>
