@@ -37,7 +37,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default 50; 2000 for the kernels that run for tens of microseconds)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 50; 1000 for those short kernels)")
     ap.add_argument("--workload", default="p_f16_8192",
-                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c1_f16_256, f1_f16_addmm, f1_f16_bias_gelu, f3_f16_add, f3_f16_silu, f3_f16_softmax, f3_f16_rms_norm, f4_f16_sdpa, f4_bf16_sdpa, f4_f16_sdpa_4k")
+                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c6_f16_conv_paper, c1_f16_256, f1_f16_addmm, f1_f16_bias_gelu, f3_f16_add, f3_f16_silu, f3_f16_softmax, f3_f16_rms_norm, f4_f16_sdpa, f4_bf16_sdpa, f4_f16_sdpa_4k")
     ap.add_argument("--tile", default=None, help="bm,bn,bk (default: library choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -46,7 +46,7 @@ def parse_args():
     args = ap.parse_args()
     # The device needs some tens of milliseconds of continuous work after an idle period before its clocks settle;
     # a 10-launch warm-up of a 15 - 100 us kernel ends long before that and the timed launches then sample the transient.
-    short = args.workload.startswith(("f3_", "f4_"))
+    short = args.workload.startswith(("f3_", "f4_", "c6_"))
     if args.steps is None:
         args.steps = 2000 if short else 50
     if args.warmup is None:
@@ -267,19 +267,25 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        starts[i].record()          # events on the stream the kernel is launched on (torch's current)
-        step()
-        ends[i].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    kern_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, ends)])
-    ms_per_step = wall * 1e3 / args.steps
+    if args.workload.startswith("c6_"):
+        # a step of some tens of microseconds (two dependent launches: the k-split convolution and the sum of its
+        # partial tiles): one event before the first step and one after the last, none in between
+        ms_per_step, kern_avg = time_short_kernel(step, args.steps)
+        kern_ms = np.array([kern_avg])
+    else:
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            starts[i].record()          # events on the stream the kernel is launched on (torch's current)
+            step()
+            ends[i].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        kern_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, ends)])
+        ms_per_step = wall * 1e3 / args.steps
+        kern_avg = float(kern_ms.mean())
     value = flops / (ms_per_step * 1e-3) / 1e12
-    kern_avg = float(kern_ms.mean())
     achieved = flops / (kern_avg * 1e-3) / 1e12
 
     result = {

@@ -88,6 +88,25 @@ def test_full_size_conv():
     check_samples(got, ref, "f16")
 
 
+def test_full_size_conv_of_the_papers_kernel_list():
+    """(4, 512, 14, 14) * (512, 512, 3, 3) in the launch configuration bench.py times (k split over 15 programs per
+    output tile): every output against the oracle, and a second call gives the same bits."""
+    cfg = si.CONFIGS["c6_f16_conv_paper"]
+    N, Cc, H, W, K, R, S = (cfg[k] for k in ("N", "C", "H", "W", "K", "R", "S"))
+    dt = cfg["dtype"]
+    X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, dt, cfg["seed"])
+    ref = onum.conv2d(X, Wt, dt, (1, 1), (0, 0), nthreads=8)
+    x, w = to_gpu(X, dt), to_gpu(Wt, dt)
+    Y = torch.full(ref.shape, float("nan"), dtype=torch.float16, device="cuda")
+    Y2 = torch.full(ref.shape, float("nan"), dtype=torch.float16, device="cuda")
+    nt.conv2d_implicit(x, w, Y, (1, 1), (0, 0))
+    nt.conv2d_implicit(x, w, Y2, (1, 1), (0, 0))
+    torch.cuda.synchronize()
+    assert nt.last_kernel_path() == nt.PATH_CONV_DIRECT
+    assert torch.equal(Y, Y2)
+    check_samples(to_f64(Y).ravel(), ref.ravel(), "f16")
+
+
 @pytest.mark.parametrize("name", ["f1_f16_addmm", "f1_f16_bias_gelu"])
 def test_full_size_addmm(name):
     cfg = si.CONFIGS[name]
