@@ -46,10 +46,7 @@ __device__ __forceinline__ float16v mfma32(u32x4 a, u32x4 b, float16v c)
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // quiet NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return __builtin_bit_cast(uint16_t, (__bf16)f);          // v_cvt_pk_bf16_f32: round to nearest even, NaN stays NaN
 }
 
 __device__ __forceinline__ uint16_t f32_to_f16_rne(float f)

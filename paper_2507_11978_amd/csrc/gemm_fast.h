@@ -348,7 +348,9 @@ __device__ __forceinline__ uint32_t pack_pair(uint32_t lo, uint32_t hi)
         typedef _Float16 half2v __attribute__((ext_vector_type(2)));
         return __builtin_bit_cast(uint32_t, half2v{(_Float16)a, (_Float16)b});          // round to nearest even
     } else {
-        return (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
+        typedef float float2v __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(float2v{a, b}, bf16x2v));   // one v_cvt_pk_bf16_f32
     }
 }
 
