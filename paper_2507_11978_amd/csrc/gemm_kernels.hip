@@ -35,6 +35,22 @@ __global__ void trace_tile_kernel(const OperandMap m, int64_t batch_off, int64_t
 struct TileEntry { int bm, bn, bk; };
 static const TileEntry kTiles[] = {{64, 64, 32}, {128, 128, 64}, {256, 128, 64}, {128, 256, 64}, {256, 256, 64}};
 
+// k split of a GEMM, second step: C[m, n] = act(alpha * sum_i ws[i][m][n] + beta * D[m, n]) with the slices added in slice
+// order (reproducible), converted once.  C and D are plain strided matrices.
+__global__ __launch_bounds__(256) void splitk_sum_kernel(const float *ws, int ksplit, int64_t M, int64_t N, void *C, int64_t scm, int64_t scn, int out_dtype,
+                                                         const void *D, int64_t sdm, int64_t sdn, float alpha, float beta, int act)
+{
+    const ActParams ap = act_params(act);
+    const int64_t total = M * N;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        float sum = ws[i];
+        for (int j = 1; j < ksplit; ++j) sum += ws[j * total + i];
+        const int64_t m = i / N, n = i - m * N;
+        const float x = combine(sum, D ? load_as_f32(D, m * sdm + n * sdn, out_dtype) : 0.f, alpha, beta);
+        store_out(C, m * scm + n * scn, act ? activate(x, ap) : x, out_dtype);
+    }
+}
+
 bool tile_is_built(nt_tile_cfg cfg)
 {
     for (const TileEntry &t : kTiles)
@@ -77,16 +93,16 @@ static bool match_conv(const GemmLaunch &g, ConvArgs *a)
     return true;
 }
 
-// Workspace of the convolution's k split: one allocation per device, grown on demand (never beyond kConvWsMax) and
+// Workspace of the k splits (convolution, skinny GEMM): one allocation per device, grown on demand (never beyond kConvWsMax) and
 // kept until the process ends.  Every call on a device shares it: calls that overlap on one device (two streams) race.
-static constexpr size_t kConvWsMax = 256u << 20;
-static float *conv_workspace(size_t bytes)
+static constexpr size_t kSplitWsMax = 256u << 20;
+static float *split_workspace(size_t bytes)
 {
     struct Ws { float *p; size_t bytes; };
     static Ws table[64] = {};
     static std::mutex mu;
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64 || bytes > kConvWsMax) return nullptr;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64 || bytes > kSplitWsMax) return nullptr;
     std::lock_guard<std::mutex> lock(mu);
     Ws &w = table[dev];
     if (w.bytes < bytes) {
@@ -114,6 +130,17 @@ static int conv_ksplit(int64_t programs, int64_t kt, int32_t *kt_per)
 
 // A map is "plain" when it is a strided matrix without bounds checks beyond rows / cols.
 static bool plain(const OperandMap &m) { return m.nrd == 1 && m.ncd == 1 && m.nchk == 0; }
+
+// The same for a GEMM with few output tiles and a long reduction (a skinny product): the split is run as a batched
+// product over equal parts of K, so only a number of parts that divides the k tiles evenly is taken.
+static int gemm_ksplit(int64_t programs, int64_t kt)
+{
+    if (programs >= 128 || kt < 16) return 1;
+    const int64_t want = std::min<int64_t>((256 + programs / 2) / programs, kt / 4);
+    for (int64_t d = want; d >= 2; --d)
+        if (kt % d == 0) return (int)d;
+    return 1;
+}
 
 nt_status launch_gemm(const GemmLaunch &g, int *path_out)
 {
@@ -145,7 +172,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             int32_t kt_per = 0;
             const int ksplit = conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
             const int64_t slice = g.conv.N * (int64_t)c.N * c.PQ;
-            float *ws = ksplit > 1 ? conv_workspace((size_t)ksplit * slice * 4) : nullptr;   // (none: too large, or no memory; then no split)
+            float *ws = ksplit > 1 ? split_workspace((size_t)ksplit * slice * 4) : nullptr;   // (none: too large, or no memory; then no split)
             // operands that can stream straight into LDS: whole 32-k slices, 16-byte aligned filter rows, 32-bit byte offsets
             // (the k split's workspace, at most 256 MB, always has them)
             const bool direct = c.K % 32 == 0 && c.ldb % 8 == 0 && (reinterpret_cast<uintptr_t>(c.Wt) & 15) == 0 && c.R <= 8 && c.S <= 8 &&
@@ -213,8 +240,30 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
                              {launch_fast_##T##_f16, launch_fast_##T##_bf16}}
         static const Entry table[] = {NT_ENTRY(128, 128, 128x128), NT_ENTRY(256, 128, 256x128), NT_ENTRY(128, 256, 128x256), NT_ENTRY(256, 256, 256x256)};
 #undef NT_ENTRY
-        for (const Entry &e : table)
-            if (e.bm == t.bm && e.bn == t.bn) return (direct ? (ragged_mn ? e.edge : e.direct) : e.staged)[bf16 ? 1 : 0](a, alay, blay, nwg, s);
+        for (const Entry &e : table) {
+            if (e.bm != t.bm || e.bn != t.bn) continue;
+            const Launcher launch = (direct ? (ragged_mn ? e.edge : e.direct) : e.staged)[bf16 ? 1 : 0];
+            // k split: `ksplit` equal parts of K as the entries of a batched product into fp32 slices of the workspace
+            const int ksplit = g.batch == 1 && !ragged_k ? gemm_ksplit(g.mt * g.nt, g.kt) : 1;
+            float *ws = ksplit > 1 ? split_workspace((size_t)ksplit * g.M * g.N * 4) : nullptr;     // (none: too large, or no memory; then no split)
+            if (!ws) return launch(a, alay, blay, nwg, s);
+            FastArgs part = a;
+            const int64_t Kp = g.K / ksplit;
+            part.K = Kp; part.kt = g.kt / ksplit;
+            part.sa_batch = alay == KCONTIG ? Kp : Kp * a.lda;
+            part.sb_batch = blay == KCONTIG ? Kp : Kp * a.ldb;
+            part.a_extent = (alay == KCONTIG ? (g.M - 1) * a.lda + Kp : (Kp - 1) * a.lda + g.M) * 2;
+            part.b_extent = (blay == KCONTIG ? (g.N - 1) * a.ldb + Kp : (Kp - 1) * a.ldb + g.N) * 2;
+            part.C = ws; part.scm = g.N; part.scn = 1; part.sc_batch = g.M * g.N; part.out_dtype = NT_F32;
+            part.D = nullptr; part.alpha = 1.f; part.beta = 0.f; part.act = 0;
+            // (a part is as streamable as the whole: its offsets are multiples of 64 elements, its C is dense fp32)
+            const nt_status st = launch(part, alay, blay, nwg * ksplit, s);
+            if (st != NT_OK) return st;
+            const int64_t blocks = std::min<int64_t>((g.M * g.N + 255) / 256, 4096);
+            hipLaunchKernelGGL(splitk_sum_kernel, dim3((unsigned)blocks), dim3(256), 0, s, ws, ksplit, g.M, g.N, a.C, a.scm, a.scn, a.out_dtype,
+                               (const void *)a.D, a.sdm, a.sdn, a.alpha, a.beta, a.act);
+            return check_launch("splitk_sum_kernel");
+        }
         return fail(NT_ERR_UNSUPPORTED, "no fast kernel for this tile");
     }
     return launch_generic(g);

@@ -385,6 +385,41 @@ def test_overhanging_tiles_bmm_and_bias_on_the_direct_kernel():
     assert_gates(to_f64(C2), onum.addmm_act(to_f64(bias), A[0], B[0], dt, "silu"), "f16", "bias + silu with overhanging tiles")
 
 
+@pytest.mark.parametrize("dt,out", [("f16", "f16"), ("bf16", "f32")])
+@pytest.mark.parametrize("M,N,K", [(16, 1024, 4096), (100, 520, 2048), (8, 264, 1536), (200, 256, 1024)])
+def test_skinny_products_split_along_k(M, N, K, dt, out):
+    """Few output tiles and a long reduction: K is dealt to several programs per tile (a batched product over equal
+    parts of K into fp32 slices of the library's workspace) and a second kernel adds the slices and applies the
+    epilogue.  Small integers: exact whatever the order; every operand orientation; what lies around C stays untouched."""
+    A, B = si.gemm_inputs(M, N, K, dt, seed=91, dist="int")
+    ref = onum.gemm(A, B, dt)
+    want = torch.from_numpy(ref).to(torch.float32).to(TORCH_DT[out])      # integers below 2^24, rounded once
+    a, b = to_gpu(A, dt), to_gpu(B, dt)
+    at, bt = a.t().contiguous().t(), b.t().contiguous().t()
+    for aa, bb in [(a, b), (a, bt), (at, b), (at, bt)]:
+        buf = torch.full((M + 2, N + 8), float("nan"), dtype=TORCH_DT[out], device="cuda")
+        C = buf[1:M + 1, :N]
+        nt.gemm(aa, bb, C)
+        torch.cuda.synchronize()
+        assert nt.last_kernel_path() in (nt.PATH_DIRECT, nt.PATH_STAGED)
+        assert torch.equal(C.cpu(), want)
+        assert torch.isnan(buf[0]).all() and torch.isnan(buf[M + 1]).all() and torch.isnan(buf[:, N:]).all()
+
+
+def test_skinny_addmm_split_along_k_applies_the_epilogue_once():
+    # bias row + activation after the sum of the parts; transposed (column-major) output; random data against the oracle
+    dt, M, N, K = "f16", 48, 640, 4096
+    A, B = si.gemm_inputs(M, N, K, dt, seed=92, dist="normal")
+    bias = torch.from_numpy(np.random.default_rng(93).standard_normal((N,)).astype(np.float32)).half().cuda()
+    C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda").t()
+    nt.addmm(bias, to_gpu(A, dt), to_gpu(B, dt), C, alpha=0.5, beta=2.0, act="gelu_tanh")
+    C2 = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda").t()
+    nt.addmm(bias, to_gpu(A, dt), to_gpu(B, dt), C2, alpha=0.5, beta=2.0, act="gelu_tanh")
+    torch.cuda.synchronize()
+    assert torch.equal(C, C2)                                             # fixed order of the sums: the same bits
+    assert_gates(to_f64(C), onum.addmm_act(to_f64(bias), A, B, dt, "gelu_tanh", alpha=0.5, beta=2.0), "f16", "skinny addmm")
+
+
 def test_kernel_paths_are_the_intended_ones():
     """Aligned full tiles stream directly into LDS, ragged or unaligned problems take the staged
     kernel, other strides and tiny tiles the operand-map kernel, strided convolutions too."""
