@@ -162,6 +162,11 @@ int32_t nt_tile_supported(nt_tile_cfg cfg);
  * Any strides are accepted; unit-stride operands with 16-byte aligned rows take the
  * fastest path.  M or N of 0: nothing is launched.  K of 0: C is zero-filled.
  * C must not alias A or B.
+ * Memory (nt_gemm, nt_addmm, nt_addmm_act): a product with few output tiles and a long reduction (a skinny
+ * product such as 16 x 4096 x 4096) has K dealt to several programs per tile; their fp32 partial tiles go
+ * through the library's workspace, the same one, under the same rules, as described at nt_conv2d_implicit
+ * (one allocation per GPU, at most 256 MB, made by the first call that needs it, shared by all calls on that
+ * GPU; partial tiles added in a fixed order).
  */
 nt_status nt_gemm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
                   void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
