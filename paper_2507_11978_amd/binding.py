@@ -112,12 +112,22 @@ def make_desc(shape: Sequence[int], strides: Sequence[int] | None = None) -> Ten
     return d
 
 
+_desc_cache: dict = {}
+
+
 def _desc_of(t) -> TensorDesc:
-    """Descriptor of a torch tensor (sizes and element strides) or a (shape, strides) pair."""
+    """Descriptor of a torch tensor (sizes and element strides) or a (shape, strides) pair.  Descriptors of tensors
+    are read-only inputs of the library and are kept by (shape, strides): a call on a layout seen before builds none."""
     if isinstance(t, TensorDesc):
         return t
     if hasattr(t, "data_ptr"):
-        return make_desc(tuple(t.shape), tuple(t.stride()))
+        key = (tuple(t.shape), tuple(t.stride()))
+        d = _desc_cache.get(key)
+        if d is None:
+            if len(_desc_cache) > 4096:
+                _desc_cache.clear()
+            d = _desc_cache[key] = make_desc(*key)
+        return d
     return make_desc(*t)
 
 
@@ -240,9 +250,14 @@ def tile_supported(tile) -> bool:
 
 
 # ---------------------------------------------------------------------------- kernels
+_dtype_names: dict = {}
+
+
 def _torch_dtype_name(t) -> str:
-    import torch
-    return {torch.float16: "f16", torch.bfloat16: "bf16", torch.float32: "f32"}[t.dtype]
+    if not _dtype_names:
+        import torch
+        _dtype_names.update({torch.float16: "f16", torch.bfloat16: "bf16", torch.float32: "f32"})
+    return _dtype_names[t.dtype]
 
 
 def _stream_ptr(stream):

@@ -3,7 +3,7 @@
 // Arrangements: add and silu tile every vector into blocks of BLOCK_SIZE (Section 4.1,
 // `tile((BLOCK_SIZE,))`); the application is element-wise, so which program owns which block
 // does not show in the result and the kernels split the vectors their own way: 16-byte vectors
-// (8 elements), four in flight per thread and operand, grid-stride.  softmax and rms_norm tile a
+// (8 elements), four in flight per thread and operand, one contiguous 16 KB chunk per workgroup.  softmax and rms_norm tile a
 // matrix into rows (`tile((1, -1))`): one program per row; a row of up to 8192 elements is read
 // once into the registers of one wavefront, reduced with cross-lane exchanges, and written once.
 // Everything is computed in fp32 and converted once (round to nearest even) to the 16-bit format.
@@ -66,12 +66,15 @@ __global__ __launch_bounds__(256) void map_vec_kernel(const uint16_t *__restrict
                                                       uint16_t *__restrict__ out, int64_t n)
 {
     const int64_t n8 = n / 8;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t v0 = (int64_t)blockIdx.x * 256 + threadIdx.x; v0 < n8; v0 += stride * kVecPerThread) {
+    // a workgroup takes one contiguous chunk of 256 * kVecPerThread vectors at a time (16 KB per operand): measured
+    // 4 - 6 % faster than a thread's four vectors lying a whole grid apart (add 14.7 against 15.6 us, silu 10.5 against
+    // 11.0 us on 16.7 M elements), and than fewer workgroups walking several chunks each
+    for (int64_t c = blockIdx.x; c * (256 * kVecPerThread) < n8; c += gridDim.x) {
+        const int64_t v0 = c * (256 * kVecPerThread) + threadIdx.x;
         u32x4 a[kVecPerThread], b[kVecPerThread];
 #pragma unroll
         for (int u = 0; u < kVecPerThread; ++u) {
-            const int64_t v = v0 + u * stride;
+            const int64_t v = v0 + u * 256;
             if (v < n8) {
                 __builtin_memcpy(&a[u], x + v * 8, 16);
                 if constexpr (OP == 0) __builtin_memcpy(&b[u], y + v * 8, 16);
@@ -79,7 +82,7 @@ __global__ __launch_bounds__(256) void map_vec_kernel(const uint16_t *__restrict
         }
 #pragma unroll
         for (int u = 0; u < kVecPerThread; ++u) {
-            const int64_t v = v0 + u * stride;
+            const int64_t v = v0 + u * 256;
             if (v < n8) {
                 float fa[8], fb[8];
                 unpack8<BF16>(a[u], fa);
@@ -233,7 +236,7 @@ nt_status launch_map(int op, const void *x, int64_t sx, const void *y, int64_t s
     const bool bf16 = dtype == NT_BF16;
     if (sx == 1 && so == 1 && (op == 1 || sy == 1)) {
         const int64_t per_wg = 256 * kVecPerThread;
-        const int64_t wgs = std::max<int64_t>(1, std::min<int64_t>((n / 8 + per_wg - 1) / per_wg, 256 * 16));
+        const int64_t wgs = std::max<int64_t>(1, std::min<int64_t>((n / 8 + per_wg - 1) / per_wg, 1 << 20));   // one chunk per workgroup
         dim3 grid((unsigned)wgs), block(256);
         if (op == 0) {
             if (bf16) hipLaunchKernelGGL((map_vec_kernel<0, true>), grid, block, 0, s, X, Y, O, n);
