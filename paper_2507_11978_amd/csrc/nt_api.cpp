@@ -38,13 +38,12 @@ struct ViewPrograms { const nt_meta_op *ops[3]; int32_t n[3]; };
 nt_tile_cfg pick_tile(int kind, int64_t batch, int64_t M, int64_t N, int64_t K, nt_tile_cfg cfg, bool unit_stride = false)
 {
     if (cfg.bm || cfg.bn || cfg.bk) return cfg;
-    // few output positions and a long reduction (the last layers of a network at batch 1): the convolution kernel, its k
-    // tiles dealt to many programs, beats the small operand-map tile by far although most of its 256 rows stay empty
-    const bool long_conv = kind == KIND_CONV && unit_stride && N >= 128 && K >= 512;
-    // The 64 x 64 tile of the operand-map kernel is for small convolutions and caller-arranged views.  Plain products,
-    // however small or skinny, run better as overhanging 128-wide tiles of the MFMA kernels (measured: 64 x 64 x 64 in
-    // 10.7 us against 18.3, 16 x 4096 x 256 in 11 us against 34, 64 x 64 x 4096 in 13.5 us against 552).
-    const bool tiny = (M <= 64 || N <= 64) && !long_conv && (kind == KIND_CONV || kind == KIND_VIEWS);
+    // The 64 x 64 tile of the operand-map kernel is for small strided convolutions and small caller-arranged views.
+    // Plain products, however small or skinny, run better as overhanging 128-wide tiles of the MFMA kernels (measured:
+    // 64 x 64 x 64 in 10.7 us against 18.3, 16 x 4096 x 256 in 11 us against 34, 64 x 64 x 4096 in 13.5 us against 552),
+    // and unit-stride convolutions on the convolution kernels' 256-position tile although most of it may stay empty
+    // ((32,64,56,56) * (64,64,3,3): 35 us against 242; (1,64,8,8) * (64,64,3,3): 19 us against 104).
+    const bool tiny = (M <= 64 || N <= 64) && ((kind == KIND_CONV && !unit_stride) || kind == KIND_VIEWS);
     if (tiny) return nt_tile_cfg{64, 64, 32};
     if (kind == KIND_CONV) {
         // the convolution kernel is built for 256 output positions per program; 128 filters per program when
