@@ -105,6 +105,21 @@ struct DirectTile<E, KCONTIG> {
     {
         dma16_buf(rsrc, voff[j], soff, lds_slice + (uint32_t)((wave * PER + j) * 1024));
     }
+    // Ragged K: the slice that has just landed at byte offset slot_off holds only `keep` valid k (< 32); what this
+    // lane fetched past them -- the beginning of the operand's next row -- is overwritten with zeros.
+    __device__ __forceinline__ void zero_tail(char *smem, uint32_t slot_off, int wave, int lane, int keep) const
+    {
+        const int left = keep - 8 * ((lane & 3) ^ ((lane >> 4) & 3));      // valid k in this lane's chunks (the same chunk column for all of them)
+        if (left >= 8) return;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const uint32_t at = slot_off + (uint32_t)((wave * PER + j) * 1024 + lane * 16);
+            u32x4 v = lds_read16(smem, at);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) v[w] &= left > 2 * w + 1 ? 0xffffffffu : (left > 2 * w ? 0x0000ffffu : 0u);
+            lds_write16(smem, at, v);
+        }
+    }
     // fragment t (32 rows) of k step ks (0 or 1) of the slice at byte offset slice_off: one 16-byte read
     __device__ __forceinline__ void read(u32x2 (&f)[2], const char *smem, int t, int ks, int part, uint32_t slice_off) const
     {
@@ -154,6 +169,8 @@ struct DirectTile<E, MNCONTIG> {
     {
         dma16_buf(rsrc, voff[j], soff, lds_slice + (uint32_t)((wave * PER + j) * 1024));
     }
+    // (ragged K: the k rows past K lie past the operand's end and arrive as zeros by themselves)
+    __device__ __forceinline__ void zero_tail(char *, uint32_t, int, int, int) const {}
     // half `part` (k 0..3 or 4..7 of the lane's run) of fragment t: one transposing 8-byte read
     __device__ __forceinline__ void read(u32x2 (&f)[2], const char *smem, int t, int ks, int part, uint32_t slice_off) const
     {
@@ -163,9 +180,10 @@ struct DirectTile<E, MNCONTIG> {
     }
 };
 
-// EDGE = false: every tile is full.  EDGE = true: tiles may overhang M or N (K is a whole number of k tiles):
-// the operand loads are range checked (what lies past an operand's end reads as zero, what an overhanging
-// tile reads inside it only reaches outputs that are never stored) and the stores are masked.
+// EDGE = false: every tile is full, every load 16-byte aligned.  EDGE = true: tiles may overhang M or N, K need not be
+// a whole number of slices, rows need only the element's own 2-byte alignment: the operand loads are range checked
+// (what lies past an operand's end reads as zero, what an overhanging tile reads inside it only reaches outputs that
+// are never stored, except the k past K of a k-contiguous operand, which are zeroed in LDS) and the stores are masked.
 template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE>
 __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_kernel(const FastArgs g)
 {
@@ -187,7 +205,8 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_ke
     const char *gB = reinterpret_cast<const char *>(g.B + bi * g.sb_batch + (BLAY == KCONTIG ? col0 * g.ldb : col0));
     const int64_t a_step = (ALAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.lda) * 2;
     const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.ldb) * 2;
-    const int64_t n_slices = g.kt * (kBK / kSliceK);
+    // (EDGE: K need not be a whole number of slices; the tail of the last one is zeroed in LDS, see zero_tail)
+    const int64_t n_slices = EDGE ? (g.K + kSliceK - 1) / kSliceK : g.kt * (kBK / kSliceK);
 
     TileA ta;
     TileB tb;
@@ -276,6 +295,12 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_ke
 #pragma unroll
         for (int d = 0; d < ND; ++d) dma(d, slice_a(s), slice_b(s), s);
     NT_WAIT_VMCNT((kRing - 1) * ND);
+    if constexpr (EDGE) {
+        if (g.K < kSliceK) {
+            ta.zero_tail(smem, 0, wave, lane, (int)g.K);
+            tb.zero_tail(smem, B_BASE, wave, lane, (int)g.K);
+        }
+    }
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < NR; ++r) lds_read(r, 0, 0, 0);
@@ -293,6 +318,13 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_ke
         const uint32_t nxt = ring + 1 == kRing ? 0 : ring + 1;
         step(0, 1, ring, 0, nullptr, nullptr, 0);
         NT_WAIT_VMCNT((kRing - 2) * ND);
+        if constexpr (EDGE) {
+            if (sl + 1 == last && (sl + 2) * kSliceK > g.K) {          // the last slice has landed, and K ends inside it
+                const int keep = (int)(g.K - (sl + 1) * kSliceK);
+                ta.zero_tail(smem, nxt * A_BYTES, wave, lane, keep);
+                tb.zero_tail(smem, B_BASE + nxt * B_BYTES, wave, lane, keep);
+            }
+        }
         __syncthreads();
         step(1, 0, nxt, ND, slice_a(sl + kRing), slice_b(sl + kRing), ring);
         ring = nxt;

@@ -221,18 +221,37 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         const bool bf16 = g.in_dtype == NT_BF16;
         const int64_t nwg = g.batch * g.mt * g.nt;
         hipStream_t s = (hipStream_t)g.stream;
-        // 16-byte aligned operands, stored to a C (and added to a D) with unit stride along n, stream straight into
-        // LDS: full tiles with plain loads; tiles that overhang M or N (K a whole number of k tiles) with range-checked
-        // loads, which needs the extent along an operand's contiguous m / n axis to be a multiple of 8 (no 16-byte
-        // vector may straddle the operand's end) and every offset inside a tile's footprint to fit 32 bits.
-        // Everything else takes the staged kernel.
+        // Operands stored to a C (and added to a D) with unit stride along n stream straight into LDS.  Full tiles of
+        // 16-byte aligned operands: plain loads.  Everything else -- tiles that overhang M or N, a ragged K, rows with
+        // only the element's 2-byte alignment -- takes the same loads as range-checked buffer accesses (EDGE kernels),
+        // which needs every offset inside a tile's footprint to fit 32 bits.  The range check works on the 4-byte words
+        // of a load, counted from the load's own start: with an odd pitch, or an extent that is no multiple of 4 bytes,
+        // the word that holds the operand's last element can reach 2 bytes past it; such an operand gets 2 more bytes of
+        // range (the other half of that word is an element nobody uses; it lies in the same 4 KB page, which is
+        // checked here, so the access cannot fault).  What is left takes the staged kernel.
         const bool ragged_mn = (g.M % t.bm) || (g.N % t.bn), ragged_k = (g.K % t.bk) != 0;
         auto al16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-        const bool streamable = !ragged_k && a.scn == 1 && (!a.D || a.sdn == 1) && al16(a.A) && al16(a.B) &&
-                                a.lda % 8 == 0 && a.ldb % 8 == 0 && a.sa_batch % 8 == 0 && a.sb_batch % 8 == 0;
-        const bool edge_ok = (alay == KCONTIG || (g.M % 8 == 0 && g.K * a.lda < (1LL << 30))) &&
-                             (blay == KCONTIG || (g.N % 8 == 0 && g.K * a.ldb < (1LL << 30)));
-        const bool direct = streamable && (!ragged_mn || edge_ok);
+        const bool out_ok = a.scn == 1 && (!a.D || a.sdn == 1);
+        const bool aligned = al16(a.A) && al16(a.B) && a.lda % 8 == 0 && a.ldb % 8 == 0 && a.sa_batch % 8 == 0 && a.sb_batch % 8 == 0;
+        const bool plain_direct = out_ok && aligned && !ragged_k && !ragged_mn;
+        auto widen = [&](const uint16_t *base, int64_t ld, int64_t s_batch, int64_t *extent) {      // false: the operand ends at a page's end
+            if (*extent % 4 == 0 && ld % 2 == 0 && s_batch % 2 == 0) return true;      // every word of every load lies at a multiple of 4 bytes
+            if (g.batch > 4096) return false;
+            for (int64_t b = 0; b < g.batch; ++b)
+                if ((reinterpret_cast<uintptr_t>(base + b * s_batch) + (uintptr_t)*extent) % 4096 == 0) return false;
+            *extent += 2;
+            return true;
+        };
+        bool direct = plain_direct;
+        int64_t widened_a = 0, widened_b = 0;
+        if (!direct && out_ok && (alay == KCONTIG || g.K * a.lda < (1LL << 30)) && (blay == KCONTIG || g.K * a.ldb < (1LL << 30))) {
+            int64_t ea = a.a_extent, eb = a.b_extent;
+            if (widen(a.A, a.lda, a.sa_batch, &ea) && widen(a.B, a.ldb, a.sb_batch, &eb)) {
+                widened_a = ea - a.a_extent; widened_b = eb - a.b_extent;
+                a.a_extent = ea; a.b_extent = eb;
+                direct = true;
+            }
+        }
         if (path_out) *path_out = direct ? PATH_DIRECT : PATH_FAST;
         typedef nt_status (*Launcher)(const FastArgs &, int, int, int64_t, hipStream_t);
         struct Entry { int bm, bn; Launcher direct[2], edge[2], staged[2]; };      // [f16, bf16]
@@ -242,7 +261,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
 #undef NT_ENTRY
         for (const Entry &e : table) {
             if (e.bm != t.bm || e.bn != t.bn) continue;
-            const Launcher launch = (direct ? (ragged_mn ? e.edge : e.direct) : e.staged)[bf16 ? 1 : 0];
+            const Launcher launch = (direct ? (plain_direct ? e.direct : e.edge) : e.staged)[bf16 ? 1 : 0];
             // k split: `ksplit` equal parts of K as the entries of a batched product into fp32 slices of the workspace
             const int ksplit = g.batch == 1 && !ragged_k ? gemm_ksplit(g.mt * g.nt, g.kt) : 1;
             float *ws = ksplit > 1 ? split_workspace((size_t)ksplit * g.M * g.N * 4) : nullptr;     // (none: too large, or no memory; then no split)
@@ -252,8 +271,10 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             part.K = Kp; part.kt = g.kt / ksplit;
             part.sa_batch = alay == KCONTIG ? Kp : Kp * a.lda;
             part.sb_batch = blay == KCONTIG ? Kp : Kp * a.ldb;
-            part.a_extent = (alay == KCONTIG ? (g.M - 1) * a.lda + Kp : (Kp - 1) * a.lda + g.M) * 2;
-            part.b_extent = (blay == KCONTIG ? (g.N - 1) * a.ldb + Kp : (Kp - 1) * a.ldb + g.N) * 2;
+            // (K and Kp are multiples of 64: a part's extent is as odd or even as the whole's, and the 2 bytes after a
+            // part lie inside the operand, or are the ones checked above)
+            part.a_extent = (alay == KCONTIG ? (g.M - 1) * a.lda + Kp : (Kp - 1) * a.lda + g.M) * 2 + widened_a;
+            part.b_extent = (blay == KCONTIG ? (g.N - 1) * a.ldb + Kp : (Kp - 1) * a.ldb + g.N) * 2 + widened_b;
             part.C = ws; part.scm = g.N; part.scn = 1; part.sc_batch = g.M * g.N; part.out_dtype = NT_F32;
             part.D = nullptr; part.alpha = 1.f; part.beta = 0.f; part.act = 0;
             // (a part is as streamable as the whole: its offsets are multiples of 64 elements, its C is dense fp32)

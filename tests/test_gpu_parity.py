@@ -203,6 +203,7 @@ def test_addmm_strided_input_transposed_output_and_k_zero():
 
 @pytest.mark.parametrize("act", ["relu", "silu", "gelu_tanh"])
 @pytest.mark.parametrize("M,N,K,tile,out,path", [(512, 512, 256, (256, 256, 64), "f16", "direct"), (256, 384, 128, (128, 128, 64), "f32", "direct"),
+                                                 (301, 263, 131, (256, 256, 64), "bf16", "direct"), (300, 264, 200, (128, 256, 64), "f32", "direct"),
                                                  (301, 263, 131, (256, 256, 64), "bf16", "staged"), (300, 264, 200, (128, 256, 64), "f32", "staged"),
                                                  (150, 170, 90, (64, 64, 32), "f16", "generic")])
 def test_addmm_fused_activation(M, N, K, tile, out, path, act):
@@ -212,7 +213,9 @@ def test_addmm_fused_activation(M, N, K, tile, out, path, act):
     A = si.round_to_bits(onum.decode(A, dt).astype(np.float32) * 12.0, dt)         # spread the results over the activations' bends
     bias = torch.from_numpy(np.random.default_rng(52).standard_normal((N,)).astype(np.float32)).to(TORCH_DT[out]).cuda()
     ref = onum.addmm_act(to_f64(bias), A, B, dt, act, alpha=0.5, beta=2.0)
-    C = torch.full((M, N), float("nan"), dtype=TORCH_DT[out], device="cuda")
+    # (ragged, odd-pitched problems stream directly as well; a column-major output takes the staged kernel)
+    C = torch.full((N, M), float("nan"), dtype=TORCH_DT[out], device="cuda").t() if path == "staged" else \
+        torch.full((M, N), float("nan"), dtype=TORCH_DT[out], device="cuda")
     nt.addmm(bias, to_gpu(A, dt), to_gpu(B, dt), C, alpha=0.5, beta=2.0, tile=tile, act=act)
     torch.cuda.synchronize()
     assert nt.last_kernel_path() == {"direct": nt.PATH_DIRECT, "staged": nt.PATH_STAGED, "generic": nt.PATH_GENERIC}[path]
@@ -350,21 +353,26 @@ def test_conv2d_dense_unit_stride(shape, pad, tile, dt, out):
 
 @pytest.mark.parametrize("dt,out", [("f16", "f16"), ("bf16", "f32")])
 @pytest.mark.parametrize("M,N,K,tile", [(500, 512, 256, None), (1000, 520, 192, (128, 128, 64)), (264, 776, 128, (256, 256, 64)),
-                                        (1032, 264, 320, (128, 256, 64)), (520, 1000, 64, (256, 128, 64)), (8, 8, 64, (128, 128, 64))])
+                                        (1032, 264, 320, (128, 256, 64)), (520, 1000, 64, (256, 128, 64)), (8, 8, 64, (128, 128, 64)),
+                                        # ragged K, odd pitches (rows with 2-byte alignment), odd extents (an operand's last
+                                        # element shares its 4-byte word with the byte after the operand)
+                                        (301, 263, 131, (256, 256, 64)), (129, 257, 1999, None), (500, 512, 200, (128, 256, 64)),
+                                        (255, 513, 95, (256, 128, 64)), (77, 33, 17, (128, 128, 64)), (64, 128, 30, None),
+                                        (9, 1001, 4097, None)])
 def test_overhanging_tiles_on_the_direct_kernel(M, N, K, tile, dt, out):
-    """Aligned operands, whole k tiles, M / N not multiples of the tile: the direct-to-LDS kernel with
-    range-checked loads and masked stores, in all four operand orientations (bit exact: integer inputs)."""
+    """M / N not multiples of the tile, K not a multiple of the slice, rows of any alignment: the direct-to-LDS kernel
+    with range-checked loads, the tail of K zeroed in LDS, and masked stores, in all four operand orientations (bit
+    exact: integer inputs)."""
     A, B = si.gemm_inputs(M, N, K, dt, seed=81, dist="int")
     ref = onum.gemm(A, B, dt)
     a, b = to_gpu(A, dt), to_gpu(B, dt)
     at, bt = a.t().contiguous().t(), b.t().contiguous().t()          # column-major A, B stored [N, K]
-    for aa, bb, streams in [(a, b, N % 8 == 0), (a, bt, True), (at, b, M % 8 == 0 and N % 8 == 0), (at, bt, M % 8 == 0)]:
+    for aa, bb in [(a, b), (a, bt), (at, b), (at, bt)]:
         buf = torch.full((M + 2, N + 8), float("nan"), dtype=TORCH_DT[out], device="cuda")   # what lies around C must stay untouched
         C = buf[1:M + 1, :N]
         nt.gemm(aa, bb, C, tile=tile)
         torch.cuda.synchronize()
-        # an operand that is contiguous along m / n needs that extent to be a multiple of 8 (else: the staged kernel)
-        assert nt.last_kernel_path() == (nt.PATH_DIRECT if streams else nt.PATH_STAGED)
+        assert nt.last_kernel_path() == nt.PATH_DIRECT
         assert np.array_equal(to_f64(C), ref)
         assert torch.isnan(buf[0]).all() and torch.isnan(buf[M + 1]).all() and torch.isnan(buf[:, N:]).all()
 
@@ -421,8 +429,9 @@ def test_skinny_addmm_split_along_k_applies_the_epilogue_once():
 
 
 def test_kernel_paths_are_the_intended_ones():
-    """Aligned full tiles stream directly into LDS, ragged or unaligned problems take the staged
-    kernel, other strides and tiny tiles the operand-map kernel, strided convolutions too."""
+    """Operands with unit stride along an axis stream directly into LDS (aligned full tiles with plain loads, ragged or
+    unaligned problems with range-checked ones), an output without unit stride along n takes the staged kernel, other
+    strides and tiny tiles the operand-map kernel, strided convolutions too."""
     def path_of(M, N, K, tile=None, view=None):
         A, B = si.gemm_inputs(M, N, K, "f16", seed=1, dist="int")
         a, b = to_gpu(A, "f16"), to_gpu(B, "f16")
@@ -430,7 +439,7 @@ def test_kernel_paths_are_the_intended_ones():
             buf = torch.zeros((M, 2 * K), dtype=torch.float16, device="cuda")
             buf[:, ::2] = a
             a = buf[:, ::2]
-        Cc = torch.empty((M, N), dtype=torch.float16, device="cuda")
+        Cc = torch.empty((N, M), dtype=torch.float16, device="cuda").t() if view == "strided_c" else torch.empty((M, N), dtype=torch.float16, device="cuda")
         nt.gemm(a, b, Cc, tile=tile)
         torch.cuda.synchronize()
         assert np.array_equal(to_f64(Cc), onum.gemm(A, B, "f16"))
@@ -439,9 +448,11 @@ def test_kernel_paths_are_the_intended_ones():
     assert path_of(512, 512, 256, tile=(256, 256, 64)) == nt.PATH_DIRECT
     assert path_of(500, 512, 256) == nt.PATH_DIRECT          # ragged M, whole k tiles: range-checked direct loads
     assert path_of(504, 520, 256, tile=(128, 128, 64)) == nt.PATH_DIRECT   # ragged M and N
-    assert path_of(500, 512, 200) == nt.PATH_STAGED          # ragged K
-    assert path_of(512, 520, 264) == nt.PATH_STAGED          # ragged N and K
-    assert path_of(512, 516, 256, tile=(128, 128, 64)) == nt.PATH_STAGED   # pitch of B not a multiple of 8
+    assert path_of(500, 512, 200) == nt.PATH_DIRECT          # ragged K: the tail of the last slice is zeroed in LDS
+    assert path_of(512, 520, 264) == nt.PATH_DIRECT          # ragged N and K
+    assert path_of(512, 516, 256, tile=(128, 128, 64)) == nt.PATH_DIRECT   # pitch of B not a multiple of 8: 2-byte aligned rows
+    assert path_of(501, 515, 201) == nt.PATH_DIRECT          # everything odd
+    assert path_of(512, 512, 256, view="strided_c") == nt.PATH_STAGED      # C without unit stride along n
     assert path_of(512, 512, 256, view="strided_a") == nt.PATH_GENERIC
     assert path_of(256, 256, 64, tile=(64, 64, 32)) == nt.PATH_GENERIC
     X, Wt = si.conv_inputs(2, 8, 16, 16, 128, 3, 3, "f16", seed=3)

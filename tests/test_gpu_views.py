@@ -49,12 +49,12 @@ def test_plain_transposed_gathered_and_batched_views():
     Cc = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
     nt.matmul_views(a, [], b, [], Cc, [])                                     # empty programs: the tensors themselves
     torch.cuda.synchronize()
-    assert np.array_equal(to_f64(Cc), ref) and nt.last_kernel_path() == nt.PATH_STAGED
+    assert np.array_equal(to_f64(Cc), ref) and nt.last_kernel_path() == nt.PATH_DIRECT
     bt = to_gpu(np.ascontiguousarray(B.T), dt)                                # [N, K] storage viewed as [K, N]
     Cc.fill_(float("nan"))
     nt.matmul_views(a, [], bt, [("permute", (1, 0))], Cc, [])
     torch.cuda.synchronize()
-    assert np.array_equal(to_f64(Cc), ref) and nt.last_kernel_path() == nt.PATH_STAGED
+    assert np.array_equal(to_f64(Cc), ref) and nt.last_kernel_path() == nt.PATH_DIRECT
     # every third row of A, written as an arrangement: tiles of height 1 every 3 rows, flattened back to a matrix
     gather = [("tile", (1, -1), (3, -1)), ("squeeze", 1), ("descend",), ("squeeze", 0), ("ascend",), ("ravel",)]
     # (a strided tiling has ceil((M - 1) / 3) + 1 = 101 tiles; the last starts at row 300, outside A, and reads as zeros)
