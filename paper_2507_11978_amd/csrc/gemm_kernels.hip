@@ -132,13 +132,22 @@ static int conv_ksplit(int64_t programs, int64_t kt, int32_t *kt_per)
 static bool plain(const OperandMap &m) { return m.nrd == 1 && m.ncd == 1 && m.nchk == 0; }
 
 // The same for a GEMM with few output tiles and a long reduction (a skinny product): the split is run as a batched
-// product over equal parts of K, so only a number of parts that divides the k tiles evenly is taken.
-static int gemm_ksplit(int64_t programs, int64_t kt)
+// product over equal parts of K, so only a number of parts that divides the k tiles evenly is taken (at least 8 k tiles
+// each).  Two dependent launches and the trip of the partial tiles through memory have their price: the split is taken
+// when an estimate of it (12 us for the launches, 0.37 us per k tile of a program that has its compute unit to
+// itself, the slices written and read at 3 TB/s) beats the estimate of the single launch (7 us + 0.37 us per k tile).
+// Measured: 1024 x 1024 x 1024 11 us unsplit against 19 split, 1024 x 1024 x 4096 31 against 24, 256 x 256 x 8192 55
+// against 15, 512 x 512 x 2048 17 against 13.
+static int gemm_ksplit(int64_t programs, int64_t kt, int64_t M, int64_t N)
 {
-    if (programs >= 128 || kt < 16) return 1;
-    const int64_t want = std::min<int64_t>((256 + programs / 2) / programs, kt / 4);
-    for (int64_t d = want; d >= 2; --d)
-        if (kt % d == 0) return (int)d;
+    if (programs >= 128 || kt < 32) return 1;
+    const int64_t want = std::min<int64_t>((256 + programs / 2) / programs, kt / 8);
+    for (int64_t d = want; d >= 2; --d) {
+        if (kt % d) continue;
+        const double single = 7.0 + 0.37 * (double)kt;
+        const double split = 12.0 + 0.37 * (double)kt / (double)d + (double)d * (double)M * (double)N * 8.0 / 3.0e6;
+        return split < single ? (int)d : 1;
+    }
     return 1;
 }
 
@@ -263,7 +272,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             if (e.bm != t.bm || e.bn != t.bn) continue;
             const Launcher launch = (direct ? (plain_direct ? e.direct : e.edge) : e.staged)[bf16 ? 1 : 0];
             // k split: `ksplit` equal parts of K as the entries of a batched product into fp32 slices of the workspace
-            const int ksplit = g.batch == 1 && !ragged_k ? gemm_ksplit(g.mt * g.nt, g.kt) : 1;
+            const int ksplit = g.batch == 1 && !ragged_k ? gemm_ksplit(g.mt * g.nt, g.kt, g.M, g.N) : 1;
             float *ws = ksplit > 1 ? split_workspace((size_t)ksplit * g.M * g.N * 4) : nullptr;     // (none: too large, or no memory; then no split)
             if (!ws) return launch(a, alay, blay, nwg, s);
             FastArgs part = a;

@@ -394,7 +394,7 @@ def test_overhanging_tiles_bmm_and_bias_on_the_direct_kernel():
 
 
 @pytest.mark.parametrize("dt,out", [("f16", "f16"), ("bf16", "f32")])
-@pytest.mark.parametrize("M,N,K", [(16, 1024, 4096), (100, 520, 2048), (8, 264, 1536), (200, 256, 1024)])
+@pytest.mark.parametrize("M,N,K", [(16, 1024, 4096), (100, 520, 2048), (8, 264, 3072), (200, 256, 2048)])
 def test_skinny_products_split_along_k(M, N, K, dt, out):
     """Few output tiles and a long reduction: K is dealt to several programs per tile (a batched product over equal
     parts of K into fp32 slices of the library's workspace) and a second kernel adds the slices and applies the
