@@ -146,7 +146,8 @@ nt_status nt_program_order(int64_t batch, int64_t mt, int64_t nt, int64_t *pid_o
 
 /* Which kernel the calling thread's last nt_gemm / nt_addmm / nt_addmm_act / nt_bmm / nt_conv2d_implicit call launched:
  * 0 operand-map (generic) kernel, 1 staged kernel, 2 direct-to-LDS kernel, 3 convolution kernel (operands staged
- * through registers), 4 convolution kernel (operands streamed straight into LDS),
+ * through registers), 4 convolution kernel (operands streamed straight into LDS), 5 unfolded input written to the
+ * workspace + the matrix kernels,
  * -1 none (nothing launched yet, an error, or an empty problem).  For tests and diagnostics. */
 int32_t nt_last_kernel_path(void);
 
@@ -275,6 +276,10 @@ nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const n
  * out-of-image positions (padding) read as zero.  dy must have P = (H + 2*pad_h - R) /
  * stride_h + 1 (integer division), likewise Q; otherwise NT_ERR_SHAPE_MISMATCH.
  * Descriptors have ndim 4 with arbitrary strides.
+ * Dense unit-stride calls (contiguous NCHW input, at most one column of padding) never materialise anything; the
+ * other convolutions (strided, widely padded, channels-last views) on the library's own tile write the unfolded
+ * input once into the library's workspace when it fits (else, or with a tile named by the caller, every tile is
+ * gathered through the index map) and run the product on the matrix kernels.
  * Memory: a dense unit-stride call with few output tiles and a long reduction has its reduction dealt to
  * several programs per tile, whose fp32 partial tiles go through a workspace that the library owns: one device
  * allocation per GPU, made (or grown, never beyond 256 MB) by the first call that needs it (so such a call can

@@ -281,7 +281,7 @@ def gemm(A, B, Cout, tile=None, stream=None):
     return Cout
 
 
-PATH_GENERIC, PATH_STAGED, PATH_DIRECT, PATH_CONV, PATH_CONV_DIRECT = 0, 1, 2, 3, 4
+PATH_GENERIC, PATH_STAGED, PATH_DIRECT, PATH_CONV, PATH_CONV_DIRECT, PATH_CONV_UNFOLD = 0, 1, 2, 3, 4, 5
 
 
 def last_kernel_path() -> int:

@@ -35,6 +35,68 @@ __global__ void trace_tile_kernel(const OperandMap m, int64_t batch_off, int64_t
 struct TileEntry { int bm, bn, bk; };
 static const TileEntry kTiles[] = {{64, 64, 32}, {128, 128, 64}, {256, 128, 64}, {128, 256, 64}, {256, 256, 64}};
 
+// A compute unit works through p = ceil(programs / 256) programs; a program costs kt steps of `step` microseconds
+// (time of one 64-wide k tile with the whole unit's matrix rate) plus a fixed `fixed` microseconds of launch, prologue and
+// epilogue, which `resident` co-resident workgroups overlap with each other's multiplications.  The constants are fits to
+// measurements on 8192 x 8192 x K and batched 2048 x 2048 x K problems.
+nt_tile_cfg pick_gemm_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
+{
+    struct Cand { int bm, bn; double fixed, step; int resident; };
+    const Cand cands[] = {{256, 256, 14.0, 1.755, 1}, {128, 256, 8.0, 0.95, 2}, {256, 128, 8.0, 1.08, 2}, {128, 128, 7.0, 0.62, 2}};
+    const double kt = (double)((K + 63) / 64);
+    nt_tile_cfg best{128, 128, 64};
+    double best_cost = 0;
+    for (const Cand &c : cands) {
+        const int64_t programs = batch * ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+        const int64_t p = (programs + 255) / 256;
+        // (problems that are not whole aligned tiles run with one workgroup per unit for every tile but the smallest)
+        const bool full = M % c.bm == 0 && N % c.bn == 0 && K % 64 == 0;
+        const int resident = full || (c.bm == 128 && c.bn == 128) ? c.resident : 1;
+        const double cost = (double)((p + resident - 1) / resident) * c.fixed + (double)p * kt * c.step;
+        if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = nt_tile_cfg{c.bm, c.bn, 64}; }
+    }
+    return best;
+}
+
+// Unfolded input of a convolution (Section 4.3: A[m, kk] = x[n, c, p sh + r - ph, q sw + s - pw], zero outside the
+// image), written out for the convolutions the implicit kernels do not take (strided, widely padded, channels-last):
+// U[kk][m] with m = (n, p, q) contiguous and the row pitch Mp (a multiple of 8; the surplus columns are zeros).  One
+// thread: 8 consecutive m of one kk, one 16-byte store; x has any strides.
+struct UnfoldArgs {
+    const uint16_t *x;
+    uint16_t *U;
+    int64_t xs[4];
+    int64_t M, Mp, K;
+    int32_t C, H, W, R, S, P, Q, sh, sw, ph, pw;
+};
+
+__global__ __launch_bounds__(256) void conv_unfold_kernel(const UnfoldArgs g)
+{
+    const int64_t groups = g.Mp / 8;
+    const int64_t total = g.K * groups;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+        const int64_t kk = t / groups, m0 = (t - kk * groups) * 8;
+        const int32_t c = (int32_t)(kk / (g.R * g.S)), rs = (int32_t)(kk - (int64_t)c * (g.R * g.S));
+        const int32_t r = rs / g.S, sx = rs - r * g.S;
+        const int64_t pq = (int64_t)g.P * g.Q;
+        int64_t n = m0 / pq;
+        int32_t rem = (int32_t)(m0 - n * pq);
+        int32_t p = rem / g.Q, q = rem - p * g.Q;
+        uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            uint32_t v = 0;
+            const int32_t h = p * g.sh + r - g.ph, col = q * g.sw + sx - g.pw;
+            if (m0 + e < g.M && h >= 0 && h < g.H && col >= 0 && col < g.W)
+                v = g.x[n * g.xs[0] + (int64_t)c * g.xs[1] + (int64_t)h * g.xs[2] + (int64_t)col * g.xs[3]];
+            w[e >> 1] |= v << (16 * (e & 1));
+            if (++q == g.Q) { q = 0; if (++p == g.P) { p = 0; ++n; } }
+        }
+        const u32x4 o{w[0], w[1], w[2], w[3]};
+        __builtin_memcpy(g.U + kk * g.Mp + m0, &o, 16);
+    }
+}
+
 // k split of a GEMM, second step: C[m, n] = act(alpha * sum_i ws[i][m][n] + beta * D[m, n]) with the slices added in slice
 // order (reproducible), converted once.  C and D are plain strided matrices.
 __global__ __launch_bounds__(256) void splitk_sum_kernel(const float *ws, int ksplit, int64_t M, int64_t N, void *C, int64_t scm, int64_t scn, int out_dtype,
@@ -204,6 +266,49 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             }
             return launch(c, c.mt * c.nt);
         }
+        // Any other convolution on the library's own tile: the unfolded input is written out once (if it fits the
+        // workspace) and the product runs per image on the MFMA kernels, Y[n] (filters x positions) = W (filters x CRS) .
+        // U[:, n] (CRS x positions) -- far faster than gathering every element of every tile through the operand map.
+        const ConvHint &h = g.conv;
+        if (h.valid && !g.user_tile && !g.no_workspace && g.batch == 1 && !g.has_d && g.alpha == 1.f && g.act == 0 &&
+            h.ys[3] == 1 && h.ys[2] == h.Q && h.ws[3] == 1 && h.ws[2] == h.S && h.ws[1] == h.R * h.S && h.ws[0] >= h.C * h.R * h.S && h.ws[0] < (1 << 22) &&
+            h.N * h.C * h.H * h.W > 0 && h.P * h.Q >= 8 && h.C * h.R * h.S >= 8) {
+            const int64_t K = h.C * h.R * h.S, PQ = h.P * h.Q, M = h.N * PQ, Mp = (M + 7) / 8 * 8;
+            uint16_t *U = Mp < (1 << 22) ? (uint16_t *)split_workspace((size_t)K * Mp * 2) : nullptr;
+            if (U) {
+                hipStream_t s = (hipStream_t)g.stream;
+                UnfoldArgs ua{};
+                ua.x = (const uint16_t *)g.A; ua.U = U;
+                for (int d = 0; d < 4; ++d) ua.xs[d] = h.xs[d];
+                ua.M = M; ua.Mp = Mp; ua.K = K;
+                ua.C = (int32_t)h.C; ua.H = (int32_t)h.H; ua.W = (int32_t)h.W; ua.R = (int32_t)h.R; ua.S = (int32_t)h.S;
+                ua.P = (int32_t)h.P; ua.Q = (int32_t)h.Q; ua.sh = (int32_t)h.sh; ua.sw = (int32_t)h.sw; ua.ph = (int32_t)h.ph; ua.pw = (int32_t)h.pw;
+                const int64_t blocks = std::min<int64_t>((K * (Mp / 8) + 255) / 256, 1 << 20);
+                hipLaunchKernelGGL(conv_unfold_kernel, dim3((unsigned)blocks), dim3(256), 0, s, ua);
+                { const nt_status lst = check_launch("conv_unfold_kernel"); if (lst != NT_OK) return lst; }
+                auto matrix = [](int64_t rows, int64_t cols, int64_t row_pitch) {
+                    OperandMap m{};
+                    m.rows = rows; m.cols = cols; m.base = 0; m.nrd = 1; m.ncd = 1; m.nchk = 0;
+                    m.rrad[0] = rows; m.crad[0] = cols; m.roff[0] = row_pitch; m.coff[0] = 1;
+                    return m;
+                };
+                GemmLaunch u{};
+                u.A = g.B; u.B = U; u.C = g.C;
+                u.ma = matrix(h.K, K, h.ws[0]);                      // filters x CRS
+                u.mb = matrix(K, PQ, Mp);                            // CRS x the image's positions
+                u.mc = matrix(h.K, PQ, h.ys[1]);                     // filters x positions
+                u.batch = h.N; u.sa_batch = 0; u.sb_batch = PQ; u.sc_batch = h.ys[0];
+                u.M = h.K; u.N = PQ; u.K = K;
+                u.tile = pick_gemm_tile(u.batch, u.M, u.N, u.K);
+                u.mt = (u.M + u.tile.bm - 1) / u.tile.bm; u.nt = (u.N + u.tile.bn - 1) / u.tile.bn; u.kt = (u.K + u.tile.bk - 1) / u.tile.bk;
+                u.in_dtype = g.in_dtype; u.out_dtype = g.out_dtype; u.stream = g.stream;
+                u.alpha = 1.f; u.beta = 0.f; u.act = 0; u.has_d = false;
+                u.no_workspace = true;                               // (the workspace holds U)
+                const nt_status st = launch_gemm(u, nullptr);
+                if (path_out) *path_out = PATH_CONV_UNFOLD;
+                return st;
+            }
+        }
     }
     if (fast) {
         a.A = (const uint16_t *)g.A + g.ma.base;
@@ -274,7 +379,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             if (e.bm != t.bm || e.bn != t.bn) continue;
             const Launcher launch = (direct ? (plain_direct ? e.direct : e.edge) : e.staged)[bf16 ? 1 : 0];
             // k split: `ksplit` equal parts of K as the entries of a batched product into fp32 slices of the workspace
-            const int ksplit = g.batch == 1 && !ragged_k ? gemm_ksplit(g.mt * g.nt, g.kt, g.M, g.N) : 1;
+            const int ksplit = g.batch == 1 && !ragged_k && !g.no_workspace ? gemm_ksplit(g.mt * g.nt, g.kt, g.M, g.N) : 1;
             float *ws = ksplit > 1 ? split_workspace((size_t)ksplit * g.M * g.N * 4) : nullptr;     // (none: too large, or no memory; then no split)
             if (!ws) return launch(a, alay, blay, nwg, s);
             FastArgs part = a;

@@ -38,12 +38,16 @@ struct GemmLaunch {
     int act;                                // activation of the combined value (nt_activation)
     bool has_d;
     ConvHint conv;
+    bool user_tile;                         // the caller named the tile (then the kernels the library would prefer are not substituted)
+    bool no_workspace;                      // the library's workspace is in use by the caller of this launch: no k split
 };
 
 // Which code path a launch would take (reported for tests and the benchmark).
-enum KernelPath { PATH_GENERIC = 0, PATH_FAST = 1, PATH_DIRECT = 2, PATH_CONV = 3, PATH_CONV_DIRECT = 4 };
+enum KernelPath { PATH_GENERIC = 0, PATH_FAST = 1, PATH_DIRECT = 2, PATH_CONV = 3, PATH_CONV_DIRECT = 4, PATH_CONV_UNFOLD = 5 };
 
 bool tile_is_built(nt_tile_cfg cfg);
+// the tile the MFMA kernels run a plain (batched) product of this size fastest with, by a cost model fitted to measurements
+nt_tile_cfg pick_gemm_tile(int64_t batch, int64_t M, int64_t N, int64_t K);
 nt_status launch_gemm(const GemmLaunch &g, int *path_out);
 nt_status launch_fill_zero(void *C, const OperandMap &mc, int64_t batch, int64_t sc_batch, int out_dtype, void *stream);
 nt_status launch_trace(const OperandMap &m, int64_t batch_off, int64_t row0, int64_t col0, int32_t rows, int32_t cols,

@@ -51,22 +51,7 @@ nt_tile_cfg pick_tile(int kind, int64_t batch, int64_t M, int64_t N, int64_t K, 
         const int64_t mt = (M + 255) / 256;
         return mt * ((N + 255) / 256) >= 128 ? nt_tile_cfg{256, 256, 64} : nt_tile_cfg{256, 128, 64};
     }
-    struct Cand { int bm, bn; double fixed, step; int resident; };
-    const Cand cands[] = {{256, 256, 14.0, 1.755, 1}, {128, 256, 8.0, 0.95, 2}, {256, 128, 8.0, 1.08, 2}, {128, 128, 7.0, 0.62, 2}};
-    const double kt = (double)((K + 63) / 64);
-    nt_tile_cfg best{128, 128, 64};
-    double best_cost = 0;
-    for (const Cand &c : cands) {
-        const int64_t programs = batch * ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
-        const int64_t p = (programs + 255) / 256;
-        // ragged problems run on the staged kernels, whose larger LDS footprint leaves one
-        // workgroup per unit for every tile but the smallest
-        const bool full = M % c.bm == 0 && N % c.bn == 0 && K % 64 == 0;
-        const int resident = full || (c.bm == 128 && c.bn == 128) ? c.resident : 1;
-        const double cost = (double)((p + resident - 1) / resident) * c.fixed + (double)p * kt * c.step;
-        if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = nt_tile_cfg{c.bm, c.bn, 64}; }
-    }
-    return best;
+    return nt::pick_gemm_tile(batch, M, N, K);
 }
 
 
@@ -200,6 +185,7 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
     g.M = p.M; g.N = p.N; g.K = p.K;
     g.mt = p.mm.mt; g.nt = p.mm.nt; g.kt = p.mm.kt;
     g.tile = p.tile;
+    g.user_tile = cfg.bm || cfg.bn || cfg.bk;
     g.in_dtype = in_dtype;
     g.out_dtype = out_dtype;
     g.stream = stream;

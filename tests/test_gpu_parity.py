@@ -431,7 +431,8 @@ def test_skinny_addmm_split_along_k_applies_the_epilogue_once():
 def test_kernel_paths_are_the_intended_ones():
     """Operands with unit stride along an axis stream directly into LDS (aligned full tiles with plain loads, ragged or
     unaligned problems with range-checked ones), an output without unit stride along n takes the staged kernel, other
-    strides and tiny tiles the operand-map kernel, strided convolutions too."""
+    strides and tiny tiles the operand-map kernel; strided and widely padded convolutions unfold their input into the
+    workspace unless the caller names a tile."""
     def path_of(M, N, K, tile=None, view=None):
         A, B = si.gemm_inputs(M, N, K, "f16", seed=1, dist="int")
         a, b = to_gpu(A, "f16"), to_gpu(B, "f16")
@@ -456,13 +457,16 @@ def test_kernel_paths_are_the_intended_ones():
     assert path_of(512, 512, 256, view="strided_a") == nt.PATH_GENERIC
     assert path_of(256, 256, 64, tile=(64, 64, 32)) == nt.PATH_GENERIC
     X, Wt = si.conv_inputs(2, 8, 16, 16, 128, 3, 3, "f16", seed=3)
-    for stride, pad, want in [((1, 1), (1, 1), nt.PATH_CONV), ((2, 2), (1, 1), nt.PATH_GENERIC), ((1, 1), (2, 2), nt.PATH_GENERIC)]:
+    for stride, pad, want in [((1, 1), (1, 1), nt.PATH_CONV), ((2, 2), (1, 1), nt.PATH_CONV_UNFOLD), ((1, 1), (2, 2), nt.PATH_CONV_UNFOLD)]:
         ref = onum.conv2d(X, Wt, "f16", stride, pad)
         Y = torch.empty(ref.shape, dtype=torch.float16, device="cuda")
         nt.conv2d_implicit(to_gpu(X, "f16"), to_gpu(Wt, "f16"), Y, stride, pad)
         torch.cuda.synchronize()
-        if ref.shape[3] % 8 == 0 or want == nt.PATH_GENERIC:
-            assert nt.last_kernel_path() == want, (stride, pad)
+        assert nt.last_kernel_path() == want, (stride, pad)
+        nt.conv2d_implicit(to_gpu(X, "f16"), to_gpu(Wt, "f16"), Y, stride, pad, tile=(64, 64, 32))      # a tile named by the caller: the index map
+        torch.cuda.synchronize()
+        assert nt.last_kernel_path() == nt.PATH_GENERIC, (stride, pad)
+        assert_gates(to_f64(Y), ref, "f16", f"conv {stride} {pad} through the index map")
         assert_gates(to_f64(Y), ref, "f16", f"conv {stride} {pad}")
 
 
@@ -544,6 +548,34 @@ def test_conv2d_dense_split_along_k_is_reproducible():
     torch.cuda.synchronize()
     assert torch.equal(Y1, Y2)
     assert_gates(to_f64(Y1), ref, "f32", "conv split, random data")
+
+
+@pytest.mark.parametrize("shape,stride,pad", [
+    ((4, 32, 28, 28, 64, 3, 3), (2, 2), (1, 1)),       # the strided 3 x 3 of a residual stage
+    ((2, 64, 14, 14, 128, 1, 1), (2, 2), (0, 0)),      # strided 1 x 1 (downsample)
+    ((2, 3, 32, 32, 64, 7, 7), (2, 2), (3, 3)),        # a stem: wide padding, few channels (C R S = 147)
+    ((3, 16, 12, 12, 40, 5, 5), (1, 1), (2, 2)),       # 5 x 5, padding 2
+    ((2, 8, 9, 7, 24, 3, 2), (2, 1), (2, 1)),          # mixed strides, 49 > P Q = 35 positions per image, ragged everything
+    ((1, 8, 5, 5, 16, 3, 3), (2, 2), (1, 1)),          # 9 positions per image
+])
+def test_conv2d_unfolded_into_the_workspace(shape, stride, pad):
+    """Convolutions the implicit kernels do not take: the unfolded input is written once into the workspace and the product
+    runs per image on the matrix kernels.  Small integers: exact; NCHW and channels-last views; what lies around the
+    output (a channel slice of a larger tensor) stays untouched."""
+    N, Cc, H, W, K, R, S = shape
+    for dt, out in (("f16", "f32"), ("bf16", "bf16")):
+        X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, dt, seed=31, dist="int")
+        ref = onum.conv2d(X, Wt, dt, stride, pad)
+        want = torch.from_numpy(ref).to(torch.float32).to(TORCH_DT[out])
+        for channels_last in (False, True):
+            x = to_gpu(X.transpose(0, 2, 3, 1).copy(), dt).permute(0, 3, 1, 2) if channels_last else to_gpu(X, dt)
+            big = torch.full((N, K + 3, ref.shape[2], ref.shape[3]), float("nan"), dtype=TORCH_DT[out], device="cuda")
+            Y = big[:, 2:K + 2]
+            nt.conv2d_implicit(x, to_gpu(Wt, dt), Y, stride, pad)
+            torch.cuda.synchronize()
+            assert nt.last_kernel_path() == nt.PATH_CONV_UNFOLD
+            assert torch.equal(Y.cpu(), want), f"conv {shape} {stride} {pad} {dt} {out} channels_last={channels_last}"
+            assert torch.isnan(big[:, :2]).all() and torch.isnan(big[:, K + 2:]).all()
 
 
 def test_conv2d_dense_integer_exact_and_padding_edges():
