@@ -151,6 +151,10 @@ nt_status nt_program_order(int64_t batch, int64_t mt, int64_t nt, int64_t *pid_o
  * -1 none (nothing launched yet, an error, or an empty problem).  For tests and diagnostics. */
 int32_t nt_last_kernel_path(void);
 
+/* Into how many parts the reduction of that call was split (see "Memory" at nt_gemm and nt_conv2d_implicit); 1: not split.
+ * For tests and diagnostics. */
+int32_t nt_last_k_split(void);
+
 /* 1 if kernels for this (bm, bn, bk) are built, else 0.  (0,0,0) is always supported. */
 int32_t nt_tile_supported(nt_tile_cfg cfg);
 

@@ -81,6 +81,7 @@ def load():
                  "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm", "nt_matmul_views", "nt_sdpa"):
         getattr(L, name).restype = i32
     L.nt_last_kernel_path.restype = i32
+    L.nt_last_k_split.restype = i32
     L.nt_last_error.restype = C.c_char_p
     L.nt_version.restype = C.c_char_p
     _lib = L
@@ -287,6 +288,11 @@ PATH_GENERIC, PATH_STAGED, PATH_DIRECT, PATH_CONV, PATH_CONV_DIRECT, PATH_CONV_U
 def last_kernel_path() -> int:
     """Kernel launched by this thread's last gemm / addmm / bmm / conv2d_implicit call (-1: none)."""
     return int(load().nt_last_kernel_path())
+
+
+def last_k_split() -> int:
+    """Into how many parts the reduction of this thread's last product / convolution call was split (1: not split)."""
+    return int(load().nt_last_k_split())
 
 
 ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu_tanh": 3}

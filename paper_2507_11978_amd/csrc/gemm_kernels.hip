@@ -215,8 +215,13 @@ static int gemm_ksplit(int64_t programs, int64_t kt, int64_t M, int64_t N)
     return 1;
 }
 
+static thread_local int t_k_split = 1;
+int last_k_split() { return t_k_split; }
+
 nt_status launch_gemm(const GemmLaunch &g, int *path_out)
 {
+    if (!g.no_workspace) t_k_split = 1;
+
     if (g.batch * g.mt * g.nt > 0x7fffffffLL) return fail(NT_ERR_UNSUPPORTED, "grid too large");
     const nt_tile_cfg t = g.tile;
     // fast path: plain operands, each with unit stride along one of its axes
@@ -257,6 +262,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
                 return direct ? launch_conv_direct(ca, t.bn, bf16, nwg, s) : launch_conv(ca, t.bn, bf16, edge_b, nwg, s);
             };
             if (ws) {
+                t_k_split = ksplit;
                 ConvArgs part = c;
                 part.Y = ws; part.syn = (int64_t)c.N * c.PQ; part.syf = c.PQ; part.out_dtype = NT_F32;
                 part.ksplit = ksplit; part.kt_per = kt_per; part.slice = slice;
@@ -382,6 +388,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             const int ksplit = g.batch == 1 && !ragged_k && !g.no_workspace ? gemm_ksplit(g.mt * g.nt, g.kt, g.M, g.N) : 1;
             float *ws = ksplit > 1 ? split_workspace((size_t)ksplit * g.M * g.N * 4) : nullptr;     // (none: too large, or no memory; then no split)
             if (!ws) return launch(a, alay, blay, nwg, s);
+            t_k_split = ksplit;
             FastArgs part = a;
             const int64_t Kp = g.K / ksplit;
             part.K = Kp; part.kt = g.kt / ksplit;

@@ -46,6 +46,8 @@ struct GemmLaunch {
 enum KernelPath { PATH_GENERIC = 0, PATH_FAST = 1, PATH_DIRECT = 2, PATH_CONV = 3, PATH_CONV_DIRECT = 4, PATH_CONV_UNFOLD = 5 };
 
 bool tile_is_built(nt_tile_cfg cfg);
+// into how many parts the calling thread's last launch_gemm split its reduction (1: no split)
+int last_k_split();
 // the tile the MFMA kernels run a plain (batched) product of this size fastest with, by a cost model fitted to measurements
 nt_tile_cfg pick_gemm_tile(int64_t batch, int64_t M, int64_t N, int64_t K);
 nt_status launch_gemm(const GemmLaunch &g, int *path_out);

@@ -273,6 +273,7 @@ int32_t nt_tile_supported(nt_tile_cfg cfg)
 }
 
 int32_t nt_last_kernel_path(void) { return t_last_path; }
+int32_t nt_last_k_split(void) { return t_last_path < 0 ? 1 : nt::last_k_split(); }
 
 nt_status nt_matmul_views(const void *A, const nt_tensor_desc *dA, const nt_meta_op *opsA, int32_t nA,
                           const void *B, const nt_tensor_desc *dB, const nt_meta_op *opsB, int32_t nB,

@@ -89,7 +89,7 @@ def test_full_size_conv():
 
 
 def test_full_size_conv_of_the_papers_kernel_list():
-    """(4, 512, 14, 14) * (512, 512, 3, 3) in the launch configuration bench.py times (k split over 15 programs per
+    """(4, 512, 14, 14) * (512, 512, 3, 3) in the launch configuration bench.py times (k split over 18 programs per
     output tile): every output against the oracle, and a second call gives the same bits."""
     cfg = si.CONFIGS["c6_f16_conv_paper"]
     N, Cc, H, W, K, R, S = (cfg[k] for k in ("N", "C", "H", "W", "K", "R", "S"))
@@ -102,7 +102,7 @@ def test_full_size_conv_of_the_papers_kernel_list():
     nt.conv2d_implicit(x, w, Y, (1, 1), (0, 0))
     nt.conv2d_implicit(x, w, Y2, (1, 1), (0, 0))
     torch.cuda.synchronize()
-    assert nt.last_kernel_path() == nt.PATH_CONV_DIRECT
+    assert nt.last_kernel_path() == nt.PATH_CONV_DIRECT and nt.last_k_split() == 18
     assert torch.equal(Y, Y2)
     check_samples(to_f64(Y).ravel(), ref.ravel(), "f16")
 

@@ -409,9 +409,19 @@ def test_skinny_products_split_along_k(M, N, K, dt, out):
         C = buf[1:M + 1, :N]
         nt.gemm(aa, bb, C)
         torch.cuda.synchronize()
-        assert nt.last_kernel_path() in (nt.PATH_DIRECT, nt.PATH_STAGED)
+        assert nt.last_kernel_path() in (nt.PATH_DIRECT, nt.PATH_STAGED) and nt.last_k_split() > 1
         assert torch.equal(C.cpu(), want)
         assert torch.isnan(buf[0]).all() and torch.isnan(buf[M + 1]).all() and torch.isnan(buf[:, N:]).all()
+
+
+def test_k_split_is_left_alone_where_it_does_not_pay():
+    for M, N, K in [(1024, 1024, 1024), (4096, 4096, 4096), (512, 2048, 1024)]:
+        A, B = si.gemm_inputs(M, N, K, "f16", seed=94, dist="int")
+        C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        nt.gemm(to_gpu(A, "f16"), to_gpu(B, "f16"), C)
+        torch.cuda.synchronize()
+        assert nt.last_k_split() == 1, (M, N, K)
+    assert np.array_equal(to_f64(C), onum.gemm(A, B, "f16"))
 
 
 def test_skinny_addmm_split_along_k_applies_the_epilogue_once():
@@ -424,6 +434,7 @@ def test_skinny_addmm_split_along_k_applies_the_epilogue_once():
     C2 = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda").t()
     nt.addmm(bias, to_gpu(A, dt), to_gpu(B, dt), C2, alpha=0.5, beta=2.0, act="gelu_tanh")
     torch.cuda.synchronize()
+    assert nt.last_k_split() == 8                                         # 5 programs of 128 x 128, 64 k tiles
     assert torch.equal(C, C2)                                             # fixed order of the sums: the same bits
     assert_gates(to_f64(C), onum.addmm_act(to_f64(bias), A, B, dt, "gelu_tanh", alpha=0.5, beta=2.0), "f16", "skinny addmm")
 
@@ -529,6 +540,7 @@ def test_conv2d_dense_split_along_k(shape, pad):
         nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), pad)
         torch.cuda.synchronize()
         assert nt.last_kernel_path() == (nt.PATH_CONV_DIRECT if (Cc * R * S) % 32 == 0 else nt.PATH_CONV)
+        assert nt.last_k_split() > 1
         # the sums are integers below 2^24: exact in fp32, then rounded once (to nearest even) to the output format
         want = torch.from_numpy(ref).to(torch.float32).to(TORCH_DT[out])
         assert torch.equal(Y.cpu(), want), f"conv split {shape} {pad} {dt} {out}"
