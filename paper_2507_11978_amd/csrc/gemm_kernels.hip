@@ -60,8 +60,8 @@ nt_tile_cfg pick_gemm_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
 
 // Unfolded input of a convolution (Section 4.3: A[m, kk] = x[n, c, p sh + r - ph, q sw + s - pw], zero outside the
 // image), written out for the convolutions the implicit kernels do not take (strided, widely padded, channels-last):
-// U[kk][m] with m = (n, p, q) contiguous and the row pitch Mp (a multiple of 8; the surplus columns are zeros).  One
-// thread: 8 consecutive m of one kk, one 16-byte store; x has any strides.
+// U[kk][m] with m = (n, p, q) contiguous and the row pitch Mp (a multiple of 8; the surplus columns are zeros);
+// x has any strides.
 struct UnfoldArgs {
     const uint16_t *x;
     uint16_t *U;
@@ -72,28 +72,45 @@ struct UnfoldArgs {
 
 __global__ __launch_bounds__(256) void conv_unfold_kernel(const UnfoldArgs g)
 {
-    const int64_t groups = g.Mp / 8;
-    const int64_t total = g.K * groups;
-    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
-        const int64_t kk = t / groups, m0 = (t - kk * groups) * 8;
-        const int32_t c = (int32_t)(kk / (g.R * g.S)), rs = (int32_t)(kk - (int64_t)c * (g.R * g.S));
-        const int32_t r = rs / g.S, sx = rs - r * g.S;
-        const int64_t pq = (int64_t)g.P * g.Q;
-        int64_t n = m0 / pq;
-        int32_t rem = (int32_t)(m0 - n * pq);
-        int32_t p = rem / g.Q, q = rem - p * g.Q;
-        uint32_t w[4] = {0, 0, 0, 0};
+    // blockIdx.y: the line kk = (c, r, s), taken apart once per workgroup in scalar registers; x: groups of 8 positions.
+    // Element offsets are 32-bit (the host admits inputs whose offsets stay below 2^31).
+    const uint32_t kk = blockIdx.y;
+    const uint32_t c = kk / (uint32_t)(g.R * g.S), rs = kk - c * (uint32_t)(g.R * g.S);
+    const uint32_t r = rs / (uint32_t)g.S, sx = rs - r * (uint32_t)g.S;
+    const uint16_t *xc = g.x + (int64_t)c * g.xs[1];
+    const int32_t xs0 = (int32_t)g.xs[0], xs2 = (int32_t)g.xs[2], xs3 = (int32_t)g.xs[3];
+    const uint32_t groups = (uint32_t)(g.Mp / 8), pq = (uint32_t)(g.P * g.Q);
+    for (uint32_t grp = blockIdx.x * 256 + threadIdx.x; grp < groups; grp += gridDim.x * 256) {
+        const uint32_t m0 = grp * 8;
+        uint32_t n = m0 / pq;
+        const uint32_t rem = m0 - n * pq;
+        int32_t p = (int32_t)(rem / (uint32_t)g.Q), q = (int32_t)(rem - (uint32_t)p * (uint32_t)g.Q);
+        // all eight offsets first (an element outside the image or past M points at element 0 and is dropped), then the
+        // eight loads back to back, with no branch between them: the kernel is bound by the latency of its loads
+        int32_t off[8];
+        uint32_t keep = 0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            uint32_t v = 0;
-            const int32_t h = p * g.sh + r - g.ph, col = q * g.sw + sx - g.pw;
-            if (m0 + e < g.M && h >= 0 && h < g.H && col >= 0 && col < g.W)
-                v = g.x[n * g.xs[0] + (int64_t)c * g.xs[1] + (int64_t)h * g.xs[2] + (int64_t)col * g.xs[3]];
-            w[e >> 1] |= v << (16 * (e & 1));
-            if (++q == g.Q) { q = 0; if (++p == g.P) { p = 0; ++n; } }
+            const int32_t h = p * g.sh + (int32_t)r - g.ph, col = q * g.sw + (int32_t)sx - g.pw;
+            const bool in = m0 + e < (uint32_t)g.M && (uint32_t)h < (uint32_t)g.H && (uint32_t)col < (uint32_t)g.W;
+            off[e] = in ? (int32_t)n * xs0 + h * xs2 + col * xs3 : 0;
+            keep |= (in ? 1u : 0u) << e;
+            const bool row_end = ++q == g.Q;
+            q = row_end ? 0 : q;
+            p += row_end ? 1 : 0;
+            const bool image_end = p == g.P;
+            p = image_end ? 0 : p;
+            n += image_end ? 1 : 0;
         }
+        uint32_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = xc[off[e]];
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 8; e += 2)
+            w[e >> 1] = ((keep >> e) & 1u ? v[e] : 0u) | (((keep >> (e + 1)) & 1u ? v[e + 1] : 0u) << 16);
         const u32x4 o{w[0], w[1], w[2], w[3]};
-        __builtin_memcpy(g.U + kk * g.Mp + m0, &o, 16);
+        __builtin_memcpy(g.U + (int64_t)kk * g.Mp + m0, &o, 16);
     }
 }
 
@@ -278,7 +295,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
         const ConvHint &h = g.conv;
         if (h.valid && !g.user_tile && !g.no_workspace && g.batch == 1 && !g.has_d && g.alpha == 1.f && g.act == 0 &&
             h.ys[3] == 1 && h.ys[2] == h.Q && h.ws[3] == 1 && h.ws[2] == h.S && h.ws[1] == h.R * h.S && h.ws[0] >= h.C * h.R * h.S && h.ws[0] < (1 << 22) &&
-            h.N * h.C * h.H * h.W > 0 && h.P * h.Q >= 8 && h.C * h.R * h.S >= 8) {
+            h.N * h.C * h.H * h.W > 0 && (h.N - 1) * h.xs[0] + (h.H - 1) * h.xs[2] + (h.W - 1) * h.xs[3] < (1LL << 31) && h.xs[0] >= 0 && h.xs[2] >= 0 && h.xs[3] >= 0 && h.P * h.Q >= 8 && h.C * h.R * h.S >= 8 && h.C * h.R * h.S <= 65535) {
             const int64_t K = h.C * h.R * h.S, PQ = h.P * h.Q, M = h.N * PQ, Mp = (M + 7) / 8 * 8;
             uint16_t *U = Mp < (1 << 22) ? (uint16_t *)split_workspace((size_t)K * Mp * 2) : nullptr;
             if (U) {
@@ -289,8 +306,8 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
                 ua.M = M; ua.Mp = Mp; ua.K = K;
                 ua.C = (int32_t)h.C; ua.H = (int32_t)h.H; ua.W = (int32_t)h.W; ua.R = (int32_t)h.R; ua.S = (int32_t)h.S;
                 ua.P = (int32_t)h.P; ua.Q = (int32_t)h.Q; ua.sh = (int32_t)h.sh; ua.sw = (int32_t)h.sw; ua.ph = (int32_t)h.ph; ua.pw = (int32_t)h.pw;
-                const int64_t blocks = std::min<int64_t>((K * (Mp / 8) + 255) / 256, 1 << 20);
-                hipLaunchKernelGGL(conv_unfold_kernel, dim3((unsigned)blocks), dim3(256), 0, s, ua);
+                const int64_t blocks = std::min<int64_t>((Mp / 8 + 255) / 256, 1 << 16);
+                hipLaunchKernelGGL(conv_unfold_kernel, dim3((unsigned)blocks, (unsigned)K), dim3(256), 0, s, ua);
                 { const nt_status lst = check_launch("conv_unfold_kernel"); if (lst != NT_OK) return lst; }
                 auto matrix = [](int64_t rows, int64_t cols, int64_t row_pitch) {
                     OperandMap m{};
