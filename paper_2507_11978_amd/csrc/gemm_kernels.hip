@@ -58,6 +58,58 @@ nt_tile_cfg pick_gemm_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
     return best;
 }
 
+// Dense zero-padded copy of a convolution's input: P[n][c][h'][w'] = x[n, c, h' - ph, w' - pw] (zero outside the image),
+// rows Wp = W + 2 pw long (the caller rounds nothing: the copy is as dense as a tensor).  For unit-stride convolutions
+// that the implicit kernels do not take as they are (more than one column of padding, channels-last or otherwise strided
+// input): on the copy they are convolutions without padding.  One thread: 8 consecutive elements of the copy, offsets
+// first, the eight loads back to back (see conv_unfold_kernel).  The workspace holds total rounded up to 8 elements.
+struct PadArgs {
+    const uint16_t *x;
+    uint16_t *P;
+    int64_t xs[4];
+    int64_t total;                 // N * C * Hp * Wp
+    int32_t C, H, W, Hp, Wp, ph, pw;
+};
+
+__global__ __launch_bounds__(256) void conv_pad_kernel(const PadArgs g)
+{
+    const int64_t groups = (g.total + 7) / 8;
+    const int32_t xs2 = (int32_t)g.xs[2], xs3 = (int32_t)g.xs[3];
+    for (int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x; grp < groups; grp += (int64_t)gridDim.x * 256) {
+        const int64_t e0 = grp * 8;
+        const int64_t plane = e0 / ((int64_t)g.Hp * g.Wp);                  // (n, c)
+        const int32_t rem = (int32_t)(e0 - plane * ((int64_t)g.Hp * g.Wp));
+        const int64_t n = plane / g.C, c = plane - n * g.C;
+        const int64_t n2 = c + 1 == g.C ? n + 1 : n, c2 = c + 1 == g.C ? 0 : c + 1;     // the plane after it (a group may run into it)
+        const int64_t base = n * g.xs[0] + c * g.xs[1], base2 = n2 * g.xs[0] + c2 * g.xs[1];
+        int32_t h = rem / g.Wp, w = rem - h * g.Wp;
+        int64_t off[8];
+        uint32_t keep = 0;
+        bool next = false;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool in = e0 + e < g.total && (uint32_t)(h - g.ph) < (uint32_t)g.H && (uint32_t)(w - g.pw) < (uint32_t)g.W;
+            off[e] = in ? (next ? base2 : base) + (h - g.ph) * xs2 + (w - g.pw) * xs3 : 0;
+            keep |= (in ? 1u : 0u) << e;
+            const bool row_end = ++w == g.Wp;
+            w = row_end ? 0 : w;
+            h += row_end ? 1 : 0;
+            const bool plane_end = h == g.Hp;
+            h = plane_end ? 0 : h;
+            next = next || plane_end;
+        }
+        uint32_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = g.x[off[e]];
+        uint32_t o[4];
+#pragma unroll
+        for (int e = 0; e < 8; e += 2)
+            o[e >> 1] = ((keep >> e) & 1u ? v[e] : 0u) | (((keep >> (e + 1)) & 1u ? v[e + 1] : 0u) << 16);
+        const u32x4 ov{o[0], o[1], o[2], o[3]};
+        __builtin_memcpy(g.P + e0, &ov, 16);
+    }
+}
+
 // Unfolded input of a convolution (Section 4.3: A[m, kk] = x[n, c, p sh + r - ph, q sw + s - pw], zero outside the
 // image), written out for the convolutions the implicit kernels do not take (strided, widely padded, channels-last):
 // U[kk][m] with m = (n, p, q) contiguous and the row pitch Mp (a multiple of 8; the surplus columns are zeros);
@@ -267,7 +319,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             int32_t kt_per = 0;
             const int ksplit = conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
             const int64_t slice = g.conv.N * (int64_t)c.N * c.PQ;
-            float *ws = ksplit > 1 ? split_workspace((size_t)ksplit * slice * 4) : nullptr;   // (none: too large, or no memory; then no split)
+            float *ws = ksplit > 1 && !g.no_workspace ? split_workspace((size_t)ksplit * slice * 4) : nullptr;   // (none: too large, no memory, or the workspace is in use; then no split)
             // operands that can stream straight into LDS: whole 32-k slices, 16-byte aligned filter rows, 32-bit byte offsets
             // (the k split's workspace, at most 256 MB, always has them)
             const bool direct = c.K % 32 == 0 && c.ldb % 8 == 0 && (reinterpret_cast<uintptr_t>(c.Wt) & 15) == 0 && c.R <= 8 && c.S <= 8 &&
@@ -288,6 +340,37 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
                 return launch_conv_ws_sum(ws, ksplit, slice, c.Y, (int64_t)c.N * c.PQ, c.PQ, c.syn, c.syf, c.out_dtype, s);
             }
             return launch(c, c.mt * c.nt);
+        }
+        // A unit-stride convolution that the implicit kernels do not take as it is (more than one column of padding, a
+        // channels-last or otherwise strided input): on a dense zero-padded copy of its input, made once in the workspace
+        // (the input's size, not C R S times it), it is a dense convolution without padding.
+        {
+            const ConvHint &h = g.conv;
+            if (h.valid && h.sh == 1 && h.sw == 1 && !g.user_tile && !g.no_workspace && g.batch == 1 && !g.has_d && g.alpha == 1.f && g.act == 0 &&
+                h.ph >= 0 && h.pw >= 0 && h.xs[0] >= 0 && h.xs[1] >= 0 && h.xs[2] >= 0 && h.xs[3] >= 0 &&
+                (h.H - 1) * h.xs[2] + (h.W - 1) * h.xs[3] < (1LL << 31)) {
+                const int64_t Hp = h.H + 2 * h.ph, Wp = h.W + 2 * h.pw, total = h.N * h.C * Hp * Wp;
+                GemmLaunch g2 = g;
+                g2.conv.H = Hp; g2.conv.W = Wp; g2.conv.ph = 0; g2.conv.pw = 0;
+                g2.conv.xs[3] = 1; g2.conv.xs[2] = Wp; g2.conv.xs[1] = Hp * Wp; g2.conv.xs[0] = h.C * Hp * Wp;
+                g2.no_workspace = true;                              // (the workspace holds the copy: no k split)
+                ConvArgs probe{};
+                const size_t bytes = (size_t)((total + 7) / 8 * 8) * 2;
+                uint16_t *P = Hp * Wp >= 8 && total < (1LL << 31) && match_conv(g2, &probe) ? (uint16_t *)split_workspace(bytes) : nullptr;
+                if (P) {
+                    PadArgs pa{};
+                    pa.x = (const uint16_t *)g.A; pa.P = P;
+                    for (int d = 0; d < 4; ++d) pa.xs[d] = h.xs[d];
+                    pa.total = total;
+                    pa.C = (int32_t)h.C; pa.H = (int32_t)h.H; pa.W = (int32_t)h.W; pa.Hp = (int32_t)Hp; pa.Wp = (int32_t)Wp;
+                    pa.ph = (int32_t)h.ph; pa.pw = (int32_t)h.pw;
+                    const int64_t blocks = std::min<int64_t>(((total + 7) / 8 + 255) / 256, 1 << 20);
+                    hipLaunchKernelGGL(conv_pad_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)g.stream, pa);
+                    { const nt_status lst = check_launch("conv_pad_kernel"); if (lst != NT_OK) return lst; }
+                    g2.A = P;
+                    return launch_gemm(g2, path_out);
+                }
+            }
         }
         // Any other convolution on the library's own tile: the unfolded input is written out once (if it fits the
         // workspace) and the product runs per image on the MFMA kernels, Y[n] (filters x positions) = W (filters x CRS) .

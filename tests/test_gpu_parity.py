@@ -468,7 +468,8 @@ def test_kernel_paths_are_the_intended_ones():
     assert path_of(512, 512, 256, view="strided_a") == nt.PATH_GENERIC
     assert path_of(256, 256, 64, tile=(64, 64, 32)) == nt.PATH_GENERIC
     X, Wt = si.conv_inputs(2, 8, 16, 16, 128, 3, 3, "f16", seed=3)
-    for stride, pad, want in [((1, 1), (1, 1), nt.PATH_CONV), ((2, 2), (1, 1), nt.PATH_CONV_UNFOLD), ((1, 1), (2, 2), nt.PATH_CONV_UNFOLD)]:
+    # (unit stride with two columns of padding: the convolution kernel on a zero-padded copy of the input)
+    for stride, pad, want in [((1, 1), (1, 1), nt.PATH_CONV), ((2, 2), (1, 1), nt.PATH_CONV_UNFOLD), ((1, 1), (2, 2), nt.PATH_CONV)]:
         ref = onum.conv2d(X, Wt, "f16", stride, pad)
         Y = torch.empty(ref.shape, dtype=torch.float16, device="cuda")
         nt.conv2d_implicit(to_gpu(X, "f16"), to_gpu(Wt, "f16"), Y, stride, pad)
@@ -567,13 +568,18 @@ def test_conv2d_dense_split_along_k_is_reproducible():
     ((2, 64, 14, 14, 128, 1, 1), (2, 2), (0, 0)),      # strided 1 x 1 (downsample)
     ((2, 3, 32, 32, 64, 7, 7), (2, 2), (3, 3)),        # a stem: wide padding, few channels (C R S = 147)
     ((3, 16, 12, 12, 40, 5, 5), (1, 1), (2, 2)),       # 5 x 5, padding 2
+    ((2, 32, 9, 11, 72, 7, 7), (1, 1), (3, 3)),        # 7 x 7, padding 3; C R S = 1568 (whole 32-k slices)
+    ((2, 8, 6, 5, 16, 3, 3), (1, 1), (0, 2)),          # padding along w only; planes of 6 x 9 = 54 elements (groups of 8 cross planes)
+    ((1, 8, 3, 3, 8, 1, 1), (1, 1), (0, 0)),           # 9 positions, nothing padded (only the channels-last view takes the copy)
     ((2, 8, 9, 7, 24, 3, 2), (2, 1), (2, 1)),          # mixed strides, 49 > P Q = 35 positions per image, ragged everything
     ((1, 8, 5, 5, 16, 3, 3), (2, 2), (1, 1)),          # 9 positions per image
 ])
-def test_conv2d_unfolded_into_the_workspace(shape, stride, pad):
-    """Convolutions the implicit kernels do not take: the unfolded input is written once into the workspace and the product
-    runs per image on the matrix kernels.  Small integers: exact; NCHW and channels-last views; what lies around the
-    output (a channel slice of a larger tensor) stays untouched."""
+def test_conv2d_through_the_workspace(shape, stride, pad):
+    """Convolutions the implicit kernels do not take as they are.  Strided ones: the unfolded input is written once into
+    the workspace and the product runs per image on the matrix kernels.  Unit-stride ones (wide padding, channels-last
+    input): a dense zero-padded copy of the input is made and the implicit kernels run on it without padding.  Small
+    integers: exact; NCHW and channels-last views; what lies around the output (a channel slice of a larger tensor)
+    stays untouched."""
     N, Cc, H, W, K, R, S = shape
     for dt, out in (("f16", "f32"), ("bf16", "bf16")):
         X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, dt, seed=31, dist="int")
@@ -585,7 +591,10 @@ def test_conv2d_unfolded_into_the_workspace(shape, stride, pad):
             Y = big[:, 2:K + 2]
             nt.conv2d_implicit(x, to_gpu(Wt, dt), Y, stride, pad)
             torch.cuda.synchronize()
-            assert nt.last_kernel_path() == nt.PATH_CONV_UNFOLD
+            if stride == (1, 1):
+                assert nt.last_kernel_path() == (nt.PATH_CONV_DIRECT if (Cc * R * S) % 32 == 0 else nt.PATH_CONV)
+            else:
+                assert nt.last_kernel_path() == nt.PATH_CONV_UNFOLD
             assert torch.equal(Y.cpu(), want), f"conv {shape} {stride} {pad} {dt} {out} channels_last={channels_last}"
             assert torch.isnan(big[:, :2]).all() and torch.isnan(big[:, K + 2:]).all()
 
