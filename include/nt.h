@@ -280,10 +280,11 @@ nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const n
  * out-of-image positions (padding) read as zero.  dy must have P = (H + 2*pad_h - R) /
  * stride_h + 1 (integer division), likewise Q; otherwise NT_ERR_SHAPE_MISMATCH.
  * Descriptors have ndim 4 with arbitrary strides.
- * Dense unit-stride calls (contiguous NCHW input, at most one column of padding) never materialise anything; the
- * other convolutions (strided, widely padded, channels-last views) on the library's own tile write the unfolded
- * input once into the library's workspace when it fits (else, or with a tile named by the caller, every tile is
- * gathered through the index map) and run the product on the matrix kernels.
+ * Dense unit-stride calls (contiguous NCHW input, at most one column of padding) never materialise anything.  The
+ * other convolutions on the library's own tile go through the library's workspace when what they need fits it:
+ * unit-stride ones (wide padding, channels-last views) make a dense zero-padded copy of the input and run on that;
+ * strided ones write the unfolded input once and run the product on the matrix kernels.  Else, or with a tile
+ * named by the caller, every tile is gathered through the index map.
  * Memory: a dense unit-stride call with few output tiles and a long reduction has its reduction dealt to
  * several programs per tile, whose fp32 partial tiles go through a workspace that the library owns: one device
  * allocation per GPU, made (or grown, never beyond 256 MB) by the first call that needs it (so such a call can

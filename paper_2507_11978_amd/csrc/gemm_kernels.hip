@@ -319,7 +319,11 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             int32_t kt_per = 0;
             const int ksplit = conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
             const int64_t slice = g.conv.N * (int64_t)c.N * c.PQ;
-            float *ws = ksplit > 1 && !g.no_workspace ? split_workspace((size_t)ksplit * slice * 4) : nullptr;   // (none: too large, no memory, or the workspace is in use; then no split)
+            float *ws = nullptr;                                     // (none: too large, or no memory; then no split)
+            if (ksplit > 1) {
+                if (!g.no_workspace) ws = split_workspace((size_t)ksplit * slice * 4);
+                else if ((size_t)ksplit * slice * 4 <= g.ws_given_bytes) ws = g.ws_given;
+            }
             // operands that can stream straight into LDS: whole 32-k slices, 16-byte aligned filter rows, 32-bit byte offsets
             // (the k split's workspace, at most 256 MB, always has them)
             const bool direct = c.K % 32 == 0 && c.ldb % 8 == 0 && (reinterpret_cast<uintptr_t>(c.Wt) & 15) == 0 && c.R <= 8 && c.S <= 8 &&
@@ -353,10 +357,20 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
                 GemmLaunch g2 = g;
                 g2.conv.H = Hp; g2.conv.W = Wp; g2.conv.ph = 0; g2.conv.pw = 0;
                 g2.conv.xs[3] = 1; g2.conv.xs[2] = Wp; g2.conv.xs[1] = Hp * Wp; g2.conv.xs[0] = h.C * Hp * Wp;
-                g2.no_workspace = true;                              // (the workspace holds the copy: no k split)
+                g2.no_workspace = true;                              // (the workspace holds the copy)
                 ConvArgs probe{};
-                const size_t bytes = (size_t)((total + 7) / 8 * 8) * 2;
-                uint16_t *P = Hp * Wp >= 8 && total < (1LL << 31) && match_conv(g2, &probe) ? (uint16_t *)split_workspace(bytes) : nullptr;
+                const size_t bytes = ((size_t)((total + 7) / 8 * 8) * 2 + 255) / 256 * 256;
+                uint16_t *P = nullptr;
+                if (Hp * Wp >= 8 && total < (1LL << 31) && match_conv(g2, &probe)) {
+                    // the copy and, behind it, the slices of the k split that the convolution will ask for, in one request
+                    // (a second request could move the workspace)
+                    int32_t kt_per = 0;
+                    const int ks = conv_ksplit(probe.mt * probe.nt, probe.kt, &kt_per);
+                    const size_t split_bytes = ks > 1 ? (size_t)ks * h.N * probe.N * probe.PQ * 4 : 0;
+                    P = (uint16_t *)split_workspace(bytes + split_bytes);
+                    if (P && split_bytes) { g2.ws_given = (float *)((char *)P + bytes); g2.ws_given_bytes = split_bytes; }
+                    if (!P && split_bytes) P = (uint16_t *)split_workspace(bytes);
+                }
                 if (P) {
                     PadArgs pa{};
                     pa.x = (const uint16_t *)g.A; pa.P = P;
