@@ -320,7 +320,7 @@ static nt_status launch_conv_direct_inst(const ConvArgs &a, int64_t nwg, hipStre
     return check_launch("gemm_conv_direct_kernel");
 }
 
-// bn: 128 or 256; nwg = ksplit * mt * nt
+// bn: 64, 128 or 256 filters per program; nwg = ksplit * mt * nt
 nt_status launch_conv_direct(const ConvArgs &a, int bn, bool bf16, int64_t nwg, hipStream_t s);
 
 }  // namespace nt

@@ -33,7 +33,7 @@ constexpr int kSliceK = 32;      // k extent of one LDS slice
 // per unit (at most 72 KB and 256 registers each), whose epilogues, launches and prologues
 // then overlap the other's multiplications; their ring is three slices (256 x 128: 72 KB) or
 // four (128 x 128: 64 KB).
-constexpr int ring_of(int bm, int bn) { return bm + bn == 384 ? 3 : 4; }
+constexpr int ring_of(int bm, int bn) { return bm + bn == 384 || bm + bn == 320 ? 3 : 4; }   // (320: the convolution kernel's 256 x 64, 60 KB)
 constexpr int residency_of(int bm, int bn) { return bm + bn == 512 ? 1 : 2; }
 
 // s_waitcnt that waits until at most n vector-memory operations are outstanding and leaves

@@ -332,7 +332,10 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
             if (direct && path_out) *path_out = PATH_CONV_DIRECT;
             const bool bf16 = g.in_dtype == NT_BF16;
             auto launch = [&](const ConvArgs &ca, int64_t nwg) {
-                return direct ? launch_conv_direct(ca, t.bn, bf16, nwg, s) : launch_conv(ca, t.bn, bf16, edge_b, nwg, s);
+                // (one column of tiles with few filters: the same grid is run by the kernel built for 64 or 128 filters per
+                // program, which spends a quarter or half of the MFMAs)
+                const int bn = ca.N <= 64 && direct ? 64 : (ca.N <= 128 ? 128 : t.bn);
+                return direct ? launch_conv_direct(ca, bn, bf16, nwg, s) : launch_conv(ca, bn, bf16, edge_b || (ca.N % bn) != 0, nwg, s);
             };
             if (ws) {
                 t_k_split = ksplit;
