@@ -500,6 +500,10 @@ def test_kernel_paths_are_the_intended_ones():
     ((8, 32, 5, 5, 128, 5, 5), (2, 1)),
     ((1, 32, 28, 28, 256, 3, 3), (1, 1)),
     ((2, 32, 9, 11, 136, 3, 3), (1, 0)),
+    # 64 filters or fewer: the kernel built for 64 filters per program (40: its second half-wavefront column is ragged)
+    ((4, 32, 14, 14, 40, 3, 3), (1, 1)),
+    ((2, 64, 9, 11, 64, 1, 1), (0, 0)),
+    ((8, 32, 16, 16, 24, 3, 3), (1, 1)),
 ])
 def test_conv2d_dense_rows_that_are_no_multiple_of_eight(shape, pad):
     """Output rows of any length: the kernel numbers positions with the row pitch rounded up to 8 and never stores the
