@@ -289,7 +289,9 @@ def main():
     achieved = flops / (kern_avg * 1e-3) / 1e12
 
     result = {
-        "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        # (the headline metric's name only for the headline workload; the other workloads say what they are)
+        "metric": METRIC if args.workload == "p_f16_8192" else f"TFLOP/s and % of MI355X MFMA peak, 1 GPU, workload {args.workload}",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "pct_of_mfma_peak": round(100.0 * value / MFMA_PEAK_TFLOPS, 2),
