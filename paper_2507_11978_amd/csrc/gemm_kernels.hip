@@ -171,8 +171,27 @@ __global__ __launch_bounds__(256) void conv_unfold_kernel(const UnfoldArgs g)
         uint32_t n = m0 / pq;
         const uint32_t rem = m0 - n * pq;
         int32_t p = (int32_t)(rem / (uint32_t)g.Q), q = (int32_t)(rem - (uint32_t)p * (uint32_t)g.Q);
-        // all eight offsets first (an element outside the image or past M points at element 0 and is dropped), then the
-        // eight loads back to back, with no branch between them: the kernel is bound by the latency of its loads
+        // A group that lies in one output row and reads 8 (conv stride 1) or 16 (stride 2) consecutive elements of one
+        // input row, all inside the image: one or two 16-byte loads (2-byte aligned), every second element picked for
+        // stride 2.  (Input contiguous along w only.)
+        if (xs3 == 1 && g.sw <= 2 && q + 8 <= g.Q && m0 + 8 <= (uint32_t)g.M) {
+            const int32_t h = p * g.sh + (int32_t)r - g.ph, col = q * g.sw + (int32_t)sx - g.pw;
+            if ((uint32_t)h < (uint32_t)g.H && col >= 0 && col + 8 * g.sw <= g.W) {
+                const uint16_t *src = xc + ((int32_t)n * xs0 + h * xs2 + col);
+                u32x4 a;
+                __builtin_memcpy(&a, src, 16);
+                if (g.sw == 2) {
+                    u32x4 b;
+                    __builtin_memcpy(&b, src + 8, 16);
+                    a = u32x4{__builtin_amdgcn_perm(a[1], a[0], 0x05040100u), __builtin_amdgcn_perm(a[3], a[2], 0x05040100u),
+                              __builtin_amdgcn_perm(b[1], b[0], 0x05040100u), __builtin_amdgcn_perm(b[3], b[2], 0x05040100u)};
+                }
+                __builtin_memcpy(g.U + (int64_t)kk * g.Mp + m0, &a, 16);
+                continue;
+            }
+        }
+        // Otherwise all eight offsets first (an element outside the image or past M points at element 0 and is dropped),
+        // then the eight loads back to back, with no branch between them: this part is bound by the latency of its loads
         int32_t off[8];
         uint32_t keep = 0;
 #pragma unroll
