@@ -44,9 +44,49 @@ def lib_path() -> str:
     return _LIB_PATH
 
 
+class _Recorder:
+    """Stands in for the library while prepare() runs a binding function: notes the one C call it makes."""
+
+    def __init__(self, lib):
+        self._lib, self.call = lib, None
+
+    def __getattr__(self, name):
+        fn = getattr(self._lib, name)
+
+        def note(*args):
+            self.call = (fn, args)
+            return 0
+        return note
+
+
+_recorder = None
+
+
+def prepare(op, *args, **kwargs):
+    """The C call that `op(*args, **kwargs)` (any launching function of this module) would make, marshalled once:
+    returns a function of no arguments that makes it.  For loops that repeat one call on the same tensors (the tensors
+    must stay alive and in place, the stream is the one current now): it skips the per-call marshalling, nothing else."""
+    global _recorder
+    lib = load()
+    _recorder = _Recorder(lib)
+    try:
+        op(*args, **kwargs)
+        fn, cargs = _recorder.call
+    finally:
+        _recorder = None
+    keep = (args, kwargs)                                   # the tensors: their memory must outlive the prepared call
+
+    def call():
+        _check(fn(*cargs))
+    call.keep = keep
+    return call
+
+
 def load():
     """Load libnt.so (built beforehand by paper_2507_11978_amd/build.py); never falls back."""
     global _lib
+    if _recorder is not None:
+        return _recorder
     if _lib is not None:
         return _lib
     if not os.path.exists(_LIB_PATH):

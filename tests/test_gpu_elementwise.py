@@ -132,3 +132,21 @@ def test_row_kernels_padded_pitch_transposed_views_and_extremes():
         nt.softmax(z, torch.empty((3, 65), dtype=torch.float16, device="cuda"))
     with pytest.raises(nt.NtError):
         nt.rms_norm(z, o, eps=-1.0)
+
+
+def test_prepared_call_is_the_same_call():
+    """nt.prepare marshals a call once; the function it returns repeats exactly that call."""
+    x = torch.randn(4099, device="cuda").half()
+    y = torch.randn(4099, device="cuda").half()
+    a, b = torch.empty_like(x), torch.full_like(x, float("nan"))
+    nt.add(x, y, a)
+    again = nt.prepare(nt.add, x, y, b)
+    assert torch.isnan(b).all()                              # preparing launches nothing
+    again()
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    x.mul_(2)                                                # same memory, new contents
+    again()
+    nt.add(x, y, a)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
