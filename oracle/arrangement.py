@@ -390,6 +390,14 @@ def view_index_set(a: Arranged):
     return np.where(valid, off, np.int64(-1)).reshape(shape), valid.reshape(shape)
 
 
+def _dot_by_definition(A, B):
+    """sum_k A[..., m, k] * B[..., k, n] in fp64, the terms added one k after another (no library product)."""
+    out = np.zeros(A.shape[:-1] + (B.shape[-1],), dtype=np.float64)
+    for k in range(A.shape[-1]):
+        out += A[..., :, k, None] * B[..., k, None, :]
+    return out
+
+
 def matmul_views(a_view: Arranged, b_view: Arranged, c_view: Arranged, a_flat, b_flat, c_flat):
     """C_view = A_view . B_view (Sections 4.2 / 4.3: the matrix product over operands that are
     themselves arranged tensors) on flat fp64 source arrays: elements of A_view / B_view outside
@@ -403,7 +411,7 @@ def matmul_views(a_view: Arranged, b_view: Arranged, c_view: Arranged, a_flat, b
     if A.ndim != B.ndim or A.ndim != oc.ndim or A.shape[-1] != B.shape[-2] or oc.shape[-2:] != (A.shape[-2], B.shape[-1]) \
             or A.shape[:-2] != B.shape[:-2] or A.shape[:-2] != oc.shape[:-2]:
         raise ShapeMismatch("view shapes do not form a matrix product")
-    prod = np.matmul(A, B)
+    prod = _dot_by_definition(A, B)
     out = np.array(c_flat, dtype=np.float64, copy=True)
     out[oc[mc]] = prod[mc]
     return out
@@ -426,7 +434,7 @@ def apply_mm(a_arr, b_arr, c_arr, a_flat, b_flat, c_flat):
             b_off, b_mask, b_shape = tile_index_set(b_arr, pid, (k,))
             a_tile = np.where(a_mask != 0, a_flat[np.maximum(a_off, 0)], 0.0).reshape(a_shape)
             b_tile = np.where(b_mask != 0, b_flat[np.maximum(b_off, 0)], 0.0).reshape(b_shape)
-            acc += a_tile @ b_tile
+            acc += _dot_by_definition(a_tile, b_tile)
         keep = c_mask != 0
         c_flat[c_off[keep]] = acc.reshape(-1)[keep]
     return c_flat
