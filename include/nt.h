@@ -11,7 +11,12 @@
  *   - Plain C types only.  "device" pointers are HIP device addresses (for example
  *     torch.Tensor.data_ptr()); "host" pointers are ordinary process memory.
  *   - Strides are in ELEMENTS, not bytes, and may describe any non-overlapping view.
- *   - The caller owns every buffer.  Nothing user-visible is allocated or kept between calls.
+ *   - The caller owns every buffer it passes.  The library keeps one thing between calls: a workspace of 256 MB
+ *     per GPU, allocated by the first call on that GPU that needs one (see "Memory" at nt_gemm and
+ *     nt_conv2d_implicit) and kept, never moved, until the process ends.  Calls that need it while another call's
+ *     work on it is still queued -- from other host threads or on other streams of the same GPU -- wait their turn:
+ *     the later call's stream waits (on the device, through an event) for the earlier call's last kernel that
+ *     touches the workspace.  Results never depend on what other calls do.
  *   - Kernel-launching calls enqueue on `hip_stream` (a hipStream_t, NULL = default
  *     stream) and return without waiting.  nt_arrange_* calls are synchronous host code.
  *   - Errors are returned as nt_status; nothing throws or aborts across the ABI.
@@ -170,8 +175,8 @@ int32_t nt_tile_supported(nt_tile_cfg cfg);
  * Memory (nt_gemm, nt_addmm, nt_addmm_act): a product with few output tiles and a long reduction (a skinny
  * product such as 16 x 4096 x 4096) has K dealt to several programs per tile; their fp32 partial tiles go
  * through the library's workspace, the same one, under the same rules, as described at nt_conv2d_implicit
- * (one allocation per GPU, at most 256 MB, made by the first call that needs it, shared by all calls on that
- * GPU; partial tiles added in a fixed order).
+ * (one allocation of 256 MB per GPU, made by the first call that needs it, handed from call to call in stream
+ * order; partial tiles added in a fixed order).
  */
 nt_status nt_gemm(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
                   void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
@@ -287,11 +292,12 @@ nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const n
  * named by the caller, every tile is gathered through the index map.
  * Memory: a dense unit-stride call with few output tiles and a long reduction has its reduction dealt to
  * several programs per tile, whose fp32 partial tiles go through a workspace that the library owns: one device
- * allocation per GPU, made (or grown, never beyond 256 MB) by the first call that needs it (so such a call can
- * allocate, and cannot be captured in a HIP graph before the workspace has its size), kept until the process
- * ends and shared by all calls on that GPU: calls that overlap on one GPU (different streams) race on it.  If
- * the allocation fails the call runs without the split.  The partial tiles are added in a fixed order: a call
- * repeated on the same data gives the same bits.
+ * allocation of 256 MB per GPU, made by the first call on that GPU that needs it (that one call allocates, and
+ * cannot be captured in a HIP graph), never moved or freed until the process ends.  All calls on a GPU share it,
+ * one after the other: a call that finds it last used on another stream makes its own stream wait for that use
+ * to finish (an event), so overlapping calls queue up for the workspace instead of racing.  What does not fit
+ * the workspace, or a failed allocation, runs without it (no split, or through the index map).  The partial tiles
+ * are added in a fixed order: a call repeated on the same data gives the same bits.
  */
 nt_status nt_conv2d_implicit(const void *x, const nt_tensor_desc *dx, const void *w, const nt_tensor_desc *dw,
                              void *y, const nt_tensor_desc *dy,
@@ -300,7 +306,8 @@ nt_status nt_conv2d_implicit(const void *x, const nt_tensor_desc *dx, const void
 
 /*
  * nt_trace_tile: device twin of the *_arrange_tile calls.  Launches a small kernel that
- * runs the SAME device address generator the compute kernels use, for one operand tile of
+ * runs the operand-map address generator (the one the operand-map kernel gathers through; the
+ * matrix and convolution kernels derive their own per-lane addresses), for one operand tile of
  * program `program_id` at k tile `k`, and writes offsets (int64, -1 where masked) and masks
  * (uint8) to the DEVICE arrays offsets_out / mask_out of `capacity` entries (row-major over
  * the tile).  kind: 0 = gemm, 1 = bmm, 2 = conv2d (conv arguments ignored otherwise).

@@ -394,11 +394,11 @@ static nt_status launch_conv_inst(const ConvArgs &a, int64_t nwg, hipStream_t s)
 {
     constexpr size_t smem = (size_t)2 * (256 + BN) * kBK * sizeof(uint16_t);
     auto kern = gemm_conv_kernel<BN, BF16, EDGE_B>;
-    static bool configured = false;
-    if (!configured) {
+    static DeviceOnce configured;
+    if (!configured.done()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
-        configured = true;
+        configured.set();
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
     return check_launch("gemm_conv_kernel");

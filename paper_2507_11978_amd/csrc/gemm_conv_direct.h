@@ -310,11 +310,11 @@ static nt_status launch_conv_direct_inst(const ConvArgs &a, int64_t nwg, hipStre
 {
     constexpr size_t smem = (size_t)ring_of(256, BN) * (256 + BN) * kSliceK * sizeof(uint16_t) + ConvTileA::kTableBytes;
     auto kern = gemm_conv_direct_kernel<BN, BF16>;
-    static bool configured = false;
-    if (!configured) {
+    static DeviceOnce configured;
+    if (!configured.done()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
-        configured = true;
+        configured.set();
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
     return check_launch("gemm_conv_direct_kernel");

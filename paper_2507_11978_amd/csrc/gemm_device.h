@@ -17,6 +17,7 @@
 //   gemm_fast_kernel     unit-stride operands (either orientation), 16-byte global loads,
 //                        register-staged prefetch of the next k tile, double-buffered LDS.
 #pragma once
+#include <atomic>
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -375,6 +376,16 @@ inline nt_status check_launch(const char *what)
     if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string(what) + ": " + hipGetErrorString(e));
     return NT_OK;
 }
+
+// "Done once on this device" flag for per-kernel set-up (hipFuncSetAttribute is a per-device setting); the work it
+// guards is idempotent, so two threads that both find it unset merely do it twice.
+struct DeviceOnce {
+    std::atomic<bool> flag[64];
+    DeviceOnce() { for (auto &f : flag) f.store(false); }
+    static int device() { int d = 0; return hipGetDevice(&d) == hipSuccess && d >= 0 && d < 64 ? d : 0; }
+    bool done() const { return flag[device()].load(std::memory_order_acquire); }
+    void set() { flag[device()].store(true, std::memory_order_release); }
+};
 
 nt_status launch_generic(const GemmLaunch &g);
 

@@ -105,6 +105,12 @@ struct DirectTile<E, KCONTIG> {
     {
         dma16_buf(rsrc, voff[j], soff, lds_slice + (uint32_t)((wave * PER + j) * 1024));
     }
+    // where element (row r, k kk) of a slice lies in it (byte offset), and which wavefront's load brings it in
+    static __device__ __forceinline__ uint32_t place(int r, int kk)
+    {
+        return (uint32_t)((r >> 4) * 1024 + (((r & 15) << 2) + ((kk >> 3) ^ ((r >> 2) & 3))) * 16 + (kk & 7) * 2);
+    }
+    static __device__ __forceinline__ int owner(int r, int) { return (r >> 4) / PER; }
     // Ragged K: the slice that has just landed at byte offset slot_off holds only `keep` valid k (< 32); what this
     // lane fetched past them -- the beginning of the operand's next row -- is overwritten with zeros.
     __device__ __forceinline__ void zero_tail(char *smem, uint32_t slot_off, int wave, int lane, int keep) const
@@ -169,6 +175,12 @@ struct DirectTile<E, MNCONTIG> {
     {
         dma16_buf(rsrc, voff[j], soff, lds_slice + (uint32_t)((wave * PER + j) * 1024));
     }
+    // where element (column r along m / n, k row kk) of a slice lies in it, and which wavefront's load brings it in
+    static __device__ __forceinline__ uint32_t place(int r, int kk)
+    {
+        return (uint32_t)((kk / RPI) * 1024 + ((kk % RPI) * CPR + ((r >> 3) ^ ((kk & 3) << 2))) * 16 + (r & 7) * 2);
+    }
+    static __device__ __forceinline__ int owner(int, int kk) { return (kk / RPI) / PER; }
     // (ragged K: the k rows past K lie past the operand's end and arrive as zeros by themselves)
     __device__ __forceinline__ void zero_tail(char *, uint32_t, int, int, int) const {}
     // half `part` (k 0..3 or 4..7 of the lane's run) of fragment t: one transposing 8-byte read
@@ -286,6 +298,25 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_ke
     };
 
     const int64_t last = n_slices - 1;
+    // The range check of a buffer load works on the load's 4-byte words: with an odd pitch or extent the word that holds an
+    // operand's very last element can end 2 bytes past the operand, and then arrives as zero.  The wavefront whose load
+    // brings that word in fetches the element by itself (a 2-byte load inside the operand) and puts it in its place once
+    // the last slice has landed (g.patch: bit 0 = A, bit 1 = B; set by the host for such operands only).
+    int patch_a = -1, patch_b = -1;
+    if constexpr (EDGE) {
+        const int kk = (int)(g.K - 1 - last * kSliceK);
+        const int64_t ra = g.M - 1 - row0, rb = g.N - 1 - col0;
+        if ((g.patch & 1) && ra < BM && TileA::owner((int)ra, kk) == wave) patch_a = (int)TileA::place((int)ra, kk);
+        if ((g.patch & 2) && rb < BN && TileB::owner((int)rb, kk) == wave) patch_b = (int)TileB::place((int)rb, kk);
+    }
+    auto patch_last = [&](uint32_t slot_a, uint32_t slot_b) {
+        if (lane == 0) {
+            if (patch_a >= 0)
+                *reinterpret_cast<uint16_t *>(smem + slot_a + patch_a) = *reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(g.A + bi * g.sa_batch) + g.a_extent - 2);
+            if (patch_b >= 0)
+                *reinterpret_cast<uint16_t *>(smem + slot_b + patch_b) = *reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(g.B + bi * g.sb_batch) + g.b_extent - 2);
+        }
+    };
     auto slice_a = [&](int64_t s) { return gA + (s < last ? s : last) * a_step; };   // clamped: surplus slices are never read
     auto slice_b = [&](int64_t s) { return gB + (s < last ? s : last) * b_step; };
 
@@ -300,6 +331,7 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_ke
             ta.zero_tail(smem, 0, wave, lane, (int)g.K);
             tb.zero_tail(smem, B_BASE, wave, lane, (int)g.K);
         }
+        if (last == 0 && g.patch) patch_last(0, B_BASE);
     }
     __syncthreads();
 #pragma unroll
@@ -324,6 +356,7 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct_ke
                 ta.zero_tail(smem, nxt * A_BYTES, wave, lane, keep);
                 tb.zero_tail(smem, B_BASE + nxt * B_BYTES, wave, lane, keep);
             }
+            if (sl + 1 == last && g.patch) patch_last(nxt * A_BYTES, B_BASE + nxt * B_BYTES);
         }
         __syncthreads();
         step(1, 0, nxt, ND, slice_a(sl + kRing), slice_b(sl + kRing), ring);
@@ -341,11 +374,11 @@ static nt_status launch_direct_inst(const FastArgs &a, int64_t nwg, hipStream_t 
 {
     constexpr size_t smem = (size_t)ring_of(BM, BN) * (BM + BN) * kSliceK * sizeof(uint16_t);
     auto kern = gemm_direct_kernel<BM, BN, BF16, ALAY, BLAY, EDGE>;
-    static bool configured = false;
-    if (!configured) {
+    static DeviceOnce configured;
+    if (!configured.done()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
-        configured = true;
+        configured.set();
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
     return check_launch("gemm_direct_kernel");

@@ -42,6 +42,9 @@ struct FastArgs {
     int32_t act;                   // activation of the combined value (0 = none)
     // bytes from the first to one past the last element of A / B (one batch entry): the bound of the range-checked loads
     int64_t a_extent, b_extent;
+    // direct kernel, range-checked flavour: bit 0 / 1 = the word of a load that holds A's / B's very last element can end
+    // past the operand (odd pitch or extent) and is dropped by the range check; the kernel then puts that element in place itself
+    int32_t patch;
 };
 
 __device__ __forceinline__ u32x4 gload16(const char *base, uint32_t off)
@@ -736,11 +739,11 @@ static nt_status launch_fast_inst(const FastArgs &a, int64_t nwg, hipStream_t s)
 {
     constexpr size_t smem = (size_t)2 * (BM + BN) * kBK * sizeof(uint16_t);
     auto kern = gemm_fast_kernel<BM, BN, BF16, ALAY, BLAY>;
-    static bool configured = false;              // raise the dynamic LDS limit once per instantiation
-    if (!configured) {
+    static DeviceOnce configured;              // raise the dynamic LDS limit once per instantiation
+    if (!configured.done()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
-        configured = true;
+        configured.set();
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
     return check_launch("gemm_fast_kernel");

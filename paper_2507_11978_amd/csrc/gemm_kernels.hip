@@ -7,16 +7,16 @@
 namespace nt {
 
 // ------------------------------------------------------------- auxiliary kernels
-__global__ void fill_zero_kernel(void *C, const OperandMap mc, int64_t sc_batch, int out_dtype)
+__global__ void fill_zero_kernel(void *C, const OperandMap mc, int64_t batch, int64_t sc_batch, int out_dtype)
 {
     const int64_t total = mc.rows * mc.cols;
-    const int64_t b = blockIdx.y;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = e / mc.cols, col = e % mc.cols;
-        int64_t off;
-        if (element_at(mc, row, col, row_part(mc, row), col_part(mc, col), &off))
-            store_out(C, b * sc_batch + off, 0.f, out_dtype);
-    }
+    for (int64_t b = blockIdx.y; b < batch; b += gridDim.y)
+        for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+            const int64_t row = e / mc.cols, col = e % mc.cols;
+            int64_t off;
+            if (element_at(mc, row, col, row_part(mc, row), col_part(mc, col), &off))
+                store_out(C, b * sc_batch + off, 0.f, out_dtype);
+        }
 }
 
 __global__ void trace_tile_kernel(const OperandMap m, int64_t batch_off, int64_t row0, int64_t col0,
@@ -277,27 +277,59 @@ static bool match_conv(const GemmLaunch &g, ConvArgs *a)
     return true;
 }
 
-// Workspace of the k splits (convolution, skinny GEMM): one allocation per device, grown on demand (never beyond kConvWsMax) and
-// kept until the process ends.  Every call on a device shares it: calls that overlap on one device (two streams) race.
+// Workspace of the k splits (convolution, skinny GEMM), of the zero-padded copy and of the unfolded input of a convolution:
+// one allocation of kSplitWsMax bytes per device, made by the first call on that device that needs it and kept until the
+// process ends (never freed or moved, so work in flight never loses it).  Every call on a device shares it.  A call holds it
+// through a WorkspaceLease from before its first launch that touches it until after its last: the lease serialises host
+// threads (a mutex) and streams (an event recorded behind the last consumer, which a call on any other stream makes its
+// stream wait for before its own first launch), so calls that overlap on one device queue up instead of racing.
 static constexpr size_t kSplitWsMax = 256u << 20;
-static float *split_workspace(size_t bytes)
-{
-    struct Ws { float *p; size_t bytes; };
-    static Ws table[64] = {};
-    static std::mutex mu;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64 || bytes > kSplitWsMax) return nullptr;
-    std::lock_guard<std::mutex> lock(mu);
-    Ws &w = table[dev];
-    if (w.bytes < bytes) {
-        if (w.p) (void)hipFree(w.p);                           // (waits for the work that still uses it)
-        w.p = nullptr; w.bytes = 0;
-        void *p = nullptr;
-        if (hipMalloc(&p, bytes) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
-        w.p = (float *)p; w.bytes = bytes;
+
+class WorkspaceLease {
+public:
+    WorkspaceLease() = default;
+    WorkspaceLease(const WorkspaceLease &) = delete;
+    WorkspaceLease &operator=(const WorkspaceLease &) = delete;
+    // nullptr: more than the workspace holds, no memory, or no device -- the caller then runs without it
+    void *acquire(size_t bytes, hipStream_t stream)
+    {
+        int dev = 0;
+        if (slot_ || bytes > kSplitWsMax || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+        Slot &w = table()[dev];
+        w.mu.lock();
+        bool ok = true;
+        if (!w.p) {
+            void *p = nullptr;
+            hipEvent_t ev = nullptr;
+            if (hipMalloc(&p, kSplitWsMax) != hipSuccess) { (void)hipGetLastError(); ok = false; }
+            else if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(p); ok = false; }
+            else { w.p = p; w.done = ev; }
+        }
+        if (ok && w.used && w.last != stream && hipStreamWaitEvent(stream, w.done, 0) != hipSuccess) { (void)hipGetLastError(); ok = false; }
+        if (!ok) { w.mu.unlock(); return nullptr; }
+        slot_ = &w;
+        stream_ = stream;
+        return w.p;
     }
-    return w.p;
-}
+    ~WorkspaceLease()
+    {
+        if (!slot_) return;
+        if (hipEventRecord(slot_->done, stream_) == hipSuccess) { slot_->last = stream_; slot_->used = true; }
+        else {
+            // without the marker a later call on another stream could not wait for this one's work: wait for it here
+            (void)hipGetLastError();
+            (void)hipStreamSynchronize(stream_);
+            slot_->used = false;
+        }
+        slot_->mu.unlock();
+    }
+
+private:
+    struct Slot { void *p = nullptr; hipEvent_t done = nullptr; hipStream_t last = nullptr; bool used = false; std::mutex mu; };
+    static Slot *table() { static Slot t[64]; return t; }
+    Slot *slot_ = nullptr;
+    hipStream_t stream_ = nullptr;
+};
 
 // A convolution with few output tiles and a long reduction leaves most of the chip idle: its k tiles are dealt to
 // `ksplit` programs per output tile, enough for about one program per compute unit, none with fewer than 4 k tiles.
@@ -340,253 +372,293 @@ static int gemm_ksplit(int64_t programs, int64_t kt, int64_t M, int64_t N)
 static thread_local int t_k_split = 1;
 int last_k_split() { return t_k_split; }
 
+// Where a k split's fp32 partial tiles go: the region the caller of this launch has set aside (a route that already holds
+// the workspace, or an entry point that brings its own scratch memory), else the library's workspace through `lease`.
+// nullptr: none (then the launch runs unsplit); *status is set when the caller's region is too small and must be.
+static float *split_region(const GemmLaunch &g, size_t bytes, WorkspaceLease &lease, nt_status *status)
+{
+    *status = NT_OK;
+    if (g.ws_given) {
+        if (bytes <= g.ws_given_bytes) return g.ws_given;
+        if (g.ws_strict)
+            *status = fail(NT_ERR_UNSUPPORTED, "this product's k split needs " + std::to_string(bytes) + " bytes of scratch memory, more than the " +
+                                                   std::to_string(g.ws_given_bytes) + " this entry point has");
+        return nullptr;
+    }
+    if (g.no_workspace) return nullptr;
+    return (float *)lease.acquire(bytes, (hipStream_t)g.stream);
+}
+
+// ---- route 1: the dense unit-stride convolution on the implicit-GEMM kernels (with the k split for small grids)
+static nt_status route_conv_implicit(const GemmLaunch &g, const ConvArgs &c, int *path_out)
+{
+    const nt_tile_cfg t = g.tile;
+    if (path_out) *path_out = PATH_CONV;
+    const bool edge_b = (g.N % t.bn) || (g.K % t.bk);
+    hipStream_t s = (hipStream_t)g.stream;
+    int32_t kt_per = 0;
+    const int ksplit = conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
+    const int64_t slice = g.conv.N * (int64_t)c.N * c.PQ;
+    WorkspaceLease lease;
+    float *ws = nullptr;                                     // (none: too large, or no memory; then no split)
+    if (ksplit > 1) {
+        nt_status st;
+        ws = split_region(g, (size_t)ksplit * slice * 4, lease, &st);
+        if (st != NT_OK) return st;
+    }
+    // operands that can stream straight into LDS: whole 32-k slices, 16-byte aligned filter rows, 32-bit byte offsets
+    // (the k split's workspace, at most 256 MB, always has them)
+    const bool direct = c.K % 32 == 0 && c.ldb % 8 == 0 && (reinterpret_cast<uintptr_t>(c.Wt) & 15) == 0 && c.R <= 8 && c.S <= 8 &&
+                        c.x_numel < (1LL << 30) && ((int64_t)(c.N - 1) * c.ldb + c.K) < (1LL << 30) &&
+                        ((g.conv.N - 1) * c.syn + (int64_t)(c.N - 1) * c.syf + c.PQ) < (1LL << 29);   // (output offsets: 31 bits of bytes)
+    if (direct && path_out) *path_out = PATH_CONV_DIRECT;
+    const bool bf16 = g.in_dtype == NT_BF16;
+    auto launch = [&](const ConvArgs &ca, int64_t nwg) {
+        // (one column of tiles with few filters: the same grid is run by the kernel built for 64 or 128 filters per
+        // program, which spends a quarter or half of the MFMAs)
+        const int bn = ca.N <= 64 && direct ? 64 : (ca.N <= 128 ? 128 : t.bn);
+        return direct ? launch_conv_direct(ca, bn, bf16, nwg, s) : launch_conv(ca, bn, bf16, edge_b || (ca.N % bn) != 0, nwg, s);
+    };
+    if (!ws) return launch(c, c.mt * c.nt);
+    t_k_split = ksplit;
+    ConvArgs part = c;
+    part.Y = ws; part.syn = (int64_t)c.N * c.PQ; part.syf = c.PQ; part.out_dtype = NT_F32;
+    part.ksplit = ksplit; part.kt_per = kt_per; part.slice = slice;
+    const nt_status st = launch(part, c.mt * c.nt * ksplit);
+    if (st != NT_OK) return st;
+    return launch_conv_ws_sum(ws, ksplit, slice, c.Y, (int64_t)c.N * c.PQ, c.PQ, c.syn, c.syf, c.out_dtype, s);
+}
+
+static bool conv_is_bare(const GemmLaunch &g)        // a convolution and nothing else: library tile, no epilogue terms, free to use the workspace
+{
+    return g.conv.valid && !g.user_tile && !g.no_workspace && !g.ws_given && g.batch == 1 && !g.has_d && g.alpha == 1.f && g.act == 0;
+}
+
+// ---- route 2: a unit-stride convolution that the implicit kernels do not take as it is (more than one column of padding, a
+// channels-last or otherwise strided input): on a dense zero-padded copy of its input, made once in the workspace (the
+// input's size, not C R S times it), it is a dense convolution without padding.  *taken = false: not this route.
+static nt_status route_conv_padded_copy(const GemmLaunch &g, int *path_out, bool *taken)
+{
+    *taken = false;
+    const ConvHint &h = g.conv;
+    if (!(conv_is_bare(g) && h.sh == 1 && h.sw == 1 && h.ph >= 0 && h.pw >= 0 && h.xs[0] >= 0 && h.xs[1] >= 0 && h.xs[2] >= 0 && h.xs[3] >= 0 &&
+          (h.H - 1) * h.xs[2] + (h.W - 1) * h.xs[3] < (1LL << 31)))
+        return NT_OK;
+    const int64_t Hp = h.H + 2 * h.ph, Wp = h.W + 2 * h.pw, total = h.N * h.C * Hp * Wp;
+    GemmLaunch g2 = g;
+    g2.conv.H = Hp; g2.conv.W = Wp; g2.conv.ph = 0; g2.conv.pw = 0;
+    g2.conv.xs[3] = 1; g2.conv.xs[2] = Wp; g2.conv.xs[1] = Hp * Wp; g2.conv.xs[0] = h.C * Hp * Wp;
+    g2.no_workspace = true;                              // (this route holds the workspace)
+    ConvArgs probe{};
+    const size_t bytes = ((size_t)((total + 7) / 8 * 8) * 2 + 255) / 256 * 256;
+    if (!(Hp * Wp >= 8 && total < (1LL << 31) && match_conv(g2, &probe))) return NT_OK;
+    // the copy and, behind it, the slices of the k split that the convolution will ask for
+    int32_t kt_per = 0;
+    const int ks = conv_ksplit(probe.mt * probe.nt, probe.kt, &kt_per);
+    size_t split_bytes = ks > 1 ? (size_t)ks * h.N * probe.N * probe.PQ * 4 : 0;
+    if (bytes + split_bytes > kSplitWsMax) split_bytes = 0;
+    WorkspaceLease lease;
+    uint16_t *P = (uint16_t *)lease.acquire(bytes + split_bytes, (hipStream_t)g.stream);
+    if (!P) return NT_OK;
+    *taken = true;
+    if (split_bytes) { g2.ws_given = (float *)((char *)P + bytes); g2.ws_given_bytes = split_bytes; }
+    PadArgs pa{};
+    pa.x = (const uint16_t *)g.A; pa.P = P;
+    for (int d = 0; d < 4; ++d) pa.xs[d] = h.xs[d];
+    pa.total = total;
+    pa.C = (int32_t)h.C; pa.H = (int32_t)h.H; pa.W = (int32_t)h.W; pa.Hp = (int32_t)Hp; pa.Wp = (int32_t)Wp;
+    pa.ph = (int32_t)h.ph; pa.pw = (int32_t)h.pw;
+    const bool nhwc = h.xs[1] == 1 && h.xs[3] == h.C && h.xs[2] == h.W * h.C && h.xs[0] == h.H * h.W * h.C &&
+                      Hp <= 65535 && h.N * ((h.C + 63) / 64) <= 65535;
+    if (nhwc) {
+        hipLaunchKernelGGL(conv_pad_nhwc_kernel, dim3((unsigned)((Wp + 31) / 32), (unsigned)Hp, (unsigned)(h.N * ((h.C + 63) / 64))), dim3(256), 0,
+                           (hipStream_t)g.stream, pa);
+    } else {
+        const int64_t blocks = std::min<int64_t>(((total + 7) / 8 + 255) / 256, 1 << 20);
+        hipLaunchKernelGGL(conv_pad_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)g.stream, pa);
+    }
+    { const nt_status lst = check_launch("conv_pad_kernel"); if (lst != NT_OK) return lst; }
+    g2.A = P;
+    return launch_gemm(g2, path_out);
+}
+
+// ---- route 3: any other convolution on the library's own tile: the unfolded input is written out once (if it fits the
+// workspace) and the product runs per image on the MFMA kernels, Y[n] (filters x positions) = W (filters x CRS) .
+// U[:, n] (CRS x positions) -- far faster than gathering every element of every tile through the operand map.
+static nt_status route_conv_unfold(const GemmLaunch &g, int *path_out, bool *taken)
+{
+    *taken = false;
+    const ConvHint &h = g.conv;
+    if (!(conv_is_bare(g) && h.ys[3] == 1 && h.ys[2] == h.Q && h.ws[3] == 1 && h.ws[2] == h.S && h.ws[1] == h.R * h.S && h.ws[0] >= h.C * h.R * h.S &&
+          h.ws[0] < (1 << 22) && h.N * h.C * h.H * h.W > 0 && (h.N - 1) * h.xs[0] + (h.H - 1) * h.xs[2] + (h.W - 1) * h.xs[3] < (1LL << 31) &&
+          h.xs[0] >= 0 && h.xs[2] >= 0 && h.xs[3] >= 0 && h.P * h.Q >= 8 && h.C * h.R * h.S >= 8 && h.C * h.R * h.S <= 65535))
+        return NT_OK;
+    const int64_t K = h.C * h.R * h.S, PQ = h.P * h.Q, M = h.N * PQ, Mp = (M + 7) / 8 * 8;
+    if (Mp >= (1 << 22)) return NT_OK;
+    WorkspaceLease lease;
+    uint16_t *U = (uint16_t *)lease.acquire((size_t)K * Mp * 2, (hipStream_t)g.stream);
+    if (!U) return NT_OK;
+    *taken = true;
+    hipStream_t s = (hipStream_t)g.stream;
+    UnfoldArgs ua{};
+    ua.x = (const uint16_t *)g.A; ua.U = U;
+    for (int d = 0; d < 4; ++d) ua.xs[d] = h.xs[d];
+    ua.M = M; ua.Mp = Mp; ua.K = K;
+    ua.C = (int32_t)h.C; ua.H = (int32_t)h.H; ua.W = (int32_t)h.W; ua.R = (int32_t)h.R; ua.S = (int32_t)h.S;
+    ua.P = (int32_t)h.P; ua.Q = (int32_t)h.Q; ua.sh = (int32_t)h.sh; ua.sw = (int32_t)h.sw; ua.ph = (int32_t)h.ph; ua.pw = (int32_t)h.pw;
+    const int64_t blocks = std::min<int64_t>((Mp / 8 + 255) / 256, 1 << 16);
+    hipLaunchKernelGGL(conv_unfold_kernel, dim3((unsigned)blocks, (unsigned)K), dim3(256), 0, s, ua);
+    { const nt_status lst = check_launch("conv_unfold_kernel"); if (lst != NT_OK) return lst; }
+    auto matrix = [](int64_t rows, int64_t cols, int64_t row_pitch) {
+        OperandMap m{};
+        m.rows = rows; m.cols = cols; m.base = 0; m.nrd = 1; m.ncd = 1; m.nchk = 0;
+        m.rrad[0] = rows; m.crad[0] = cols; m.roff[0] = row_pitch; m.coff[0] = 1;
+        return m;
+    };
+    GemmLaunch u{};
+    u.A = g.B; u.B = U; u.C = g.C;
+    u.ma = matrix(h.K, K, h.ws[0]);                      // filters x CRS
+    u.mb = matrix(K, PQ, Mp);                            // CRS x the image's positions
+    u.mc = matrix(h.K, PQ, h.ys[1]);                     // filters x positions
+    u.batch = h.N; u.sa_batch = 0; u.sb_batch = PQ; u.sc_batch = h.ys[0];
+    u.M = h.K; u.N = PQ; u.K = K;
+    u.tile = pick_gemm_tile(u.batch, u.M, u.N, u.K);
+    u.mt = (u.M + u.tile.bm - 1) / u.tile.bm; u.nt = (u.N + u.tile.bn - 1) / u.tile.bn; u.kt = (u.K + u.tile.bk - 1) / u.tile.bk;
+    u.in_dtype = g.in_dtype; u.out_dtype = g.out_dtype; u.stream = g.stream;
+    u.alpha = 1.f; u.beta = 0.f; u.act = 0; u.has_d = false;
+    u.no_workspace = true;                               // (this route holds the workspace)
+    const nt_status st = launch_gemm(u, nullptr);
+    if (path_out) *path_out = PATH_CONV_UNFOLD;
+    return st;
+}
+
+// Plain operands, each with unit stride along one of its axes, on a tile the MFMA kernels are built for: the arguments
+// of those kernels.  false: the operand-map kernel takes the launch.
+static bool lower_plain(const GemmLaunch &g, FastArgs *out, int *alay_out, int *blay_out)
+{
+    const nt_tile_cfg t = g.tile;
+    if (!(plain(g.ma) && plain(g.mb) && plain(g.mc) && (!g.has_d || plain(g.md)) && t.bk == 64 && t.bm >= 128 && t.bn >= 128 && g.kt > 0)) return false;
+    FastArgs a{};
+    int alay, blay;
+    if (g.ma.coff[0] == 1) { alay = KCONTIG; a.lda = g.ma.roff[0]; }
+    else if (g.ma.roff[0] == 1) { alay = MNCONTIG; a.lda = g.ma.coff[0]; }
+    else return false;
+    if (g.mb.coff[0] == 1) { blay = MNCONTIG; a.ldb = g.mb.roff[0]; }
+    else if (g.mb.roff[0] == 1) { blay = KCONTIG; a.ldb = g.mb.coff[0]; }
+    else return false;
+    if (a.lda < 0 || a.ldb < 0 || a.lda >= (1 << 22) || a.ldb >= (1 << 22)) return false;   // 32-bit lane offsets
+    // the staged loader fetches a block that straddles the ragged end of the contiguous
+    // axis up to 7 elements early: that axis must be at least one block (8 elements) long
+    if ((alay == MNCONTIG ? g.M : g.K) < 8 || (blay == MNCONTIG ? g.N : g.K) < 8) return false;
+    const int64_t esz = g.out_dtype == NT_F32 ? 4 : 2;
+    a.A = (const uint16_t *)g.A + g.ma.base;
+    a.B = (const uint16_t *)g.B + g.mb.base;
+    a.C = (char *)g.C + g.mc.base * esz;
+    a.scm = g.mc.roff[0];
+    a.scn = g.mc.coff[0];
+    a.sa_batch = g.sa_batch; a.sb_batch = g.sb_batch; a.sc_batch = g.sc_batch;
+    a.M = g.M; a.N = g.N; a.K = g.K;
+    a.mt = g.mt; a.nt = g.nt; a.kt = g.kt;
+    a.out_dtype = g.out_dtype;
+    a.alpha = g.alpha;
+    a.beta = g.has_d ? g.beta : 0.f;
+    a.act = g.act;
+    // bounds of the range-checked loads (the pitches are below 2^22, so every offset inside a tile's footprint fits 32 bits)
+    a.a_extent = (alay == KCONTIG ? (g.M - 1) * a.lda + g.K : (g.K - 1) * a.lda + g.M) * 2;
+    a.b_extent = (blay == KCONTIG ? (g.N - 1) * a.ldb + g.K : (g.K - 1) * a.ldb + g.N) * 2;
+    if (g.has_d) {
+        a.D = (const char *)g.D + g.md.base * esz;
+        a.sdm = g.md.roff[0];
+        a.sdn = g.md.coff[0];
+        a.sd_batch = g.sd_batch;
+    }
+    *out = a;
+    *alay_out = alay;
+    *blay_out = blay;
+    return true;
+}
+
+// ---- route 4: plain matrices on the MFMA kernels (with the k split for skinny products)
+static nt_status route_matrix(const GemmLaunch &g, FastArgs a, int alay, int blay, int *path_out)
+{
+    const nt_tile_cfg t = g.tile;
+    const bool bf16 = g.in_dtype == NT_BF16;
+    const int64_t nwg = g.batch * g.mt * g.nt;
+    hipStream_t s = (hipStream_t)g.stream;
+    // Operands stored to a C (and added to a D) with unit stride along n stream straight into LDS.  Full tiles of
+    // 16-byte aligned operands: plain loads.  Everything else -- tiles that overhang M or N, a ragged K, rows with
+    // only the element's 2-byte alignment -- takes the same loads as range-checked buffer accesses (EDGE kernels),
+    // which needs every offset inside a tile's footprint to fit 32 bits.  The range check works on the 4-byte words
+    // of a load, counted from the load's own start: with an odd pitch, or an extent that is no multiple of 4 bytes,
+    // the word that holds the operand's last element can end 2 bytes past it and is then dropped; the kernel is told
+    // (patch) and fetches that one element by itself.  The range never extends past the operand.
+    const bool ragged_mn = (g.M % t.bm) || (g.N % t.bn), ragged_k = (g.K % t.bk) != 0;
+    auto al16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+    const bool out_ok = a.scn == 1 && (!a.D || a.sdn == 1);
+    const bool aligned = al16(a.A) && al16(a.B) && a.lda % 8 == 0 && a.ldb % 8 == 0 && a.sa_batch % 8 == 0 && a.sb_batch % 8 == 0;
+    const bool plain_direct = out_ok && aligned && !ragged_k && !ragged_mn;
+    auto words_aligned = [&](int64_t ld, int64_t s_batch, int64_t extent) {      // every word of every load lies at a multiple of 4 bytes from the operand's start
+        return extent % 4 == 0 && ld % 2 == 0 && s_batch % 2 == 0;
+    };
+    const bool direct = plain_direct || (out_ok && (alay == KCONTIG || g.K * a.lda < (1LL << 30)) && (blay == KCONTIG || g.K * a.ldb < (1LL << 30)));
+    if (direct && !plain_direct)
+        a.patch = (words_aligned(a.lda, a.sa_batch, a.a_extent) ? 0 : 1) | (words_aligned(a.ldb, a.sb_batch, a.b_extent) ? 0 : 2);
+    if (path_out) *path_out = direct ? PATH_DIRECT : PATH_FAST;
+    typedef nt_status (*Launcher)(const FastArgs &, int, int, int64_t, hipStream_t);
+    struct Entry { int bm, bn; Launcher direct[2], edge[2], staged[2]; };      // [f16, bf16]
+#define NT_ENTRY(BM, BN, T) {BM, BN, {launch_direct_##T##_f16, launch_direct_##T##_bf16}, {launch_direct_edge_##T##_f16, launch_direct_edge_##T##_bf16}, \
+                             {launch_fast_##T##_f16, launch_fast_##T##_bf16}}
+    static const Entry table[] = {NT_ENTRY(128, 128, 128x128), NT_ENTRY(256, 128, 256x128), NT_ENTRY(128, 256, 128x256), NT_ENTRY(256, 256, 256x256)};
+#undef NT_ENTRY
+    for (const Entry &e : table) {
+        if (e.bm != t.bm || e.bn != t.bn) continue;
+        const Launcher launch = (direct ? (plain_direct ? e.direct : e.edge) : e.staged)[bf16 ? 1 : 0];
+        // k split: `ksplit` equal parts of K as the entries of a batched product into fp32 slices of the workspace
+        const int ksplit = g.batch == 1 && !ragged_k ? gemm_ksplit(g.mt * g.nt, g.kt, g.M, g.N) : 1;
+        WorkspaceLease lease;
+        float *ws = nullptr;                                 // (none: too large, or no memory; then no split)
+        if (ksplit > 1) {
+            nt_status st;
+            ws = split_region(g, (size_t)ksplit * g.M * g.N * 4, lease, &st);
+            if (st != NT_OK) return st;
+        }
+        if (!ws) return launch(a, alay, blay, nwg, s);
+        t_k_split = ksplit;
+        FastArgs part = a;
+        const int64_t Kp = g.K / ksplit;
+        part.K = Kp; part.kt = g.kt / ksplit;
+        part.sa_batch = alay == KCONTIG ? Kp : Kp * a.lda;
+        part.sb_batch = blay == KCONTIG ? Kp : Kp * a.ldb;
+        // (K and Kp are multiples of 64: a part's words are as aligned as the whole's, and a part is as streamable)
+        part.a_extent = (alay == KCONTIG ? (g.M - 1) * a.lda + Kp : (Kp - 1) * a.lda + g.M) * 2;
+        part.b_extent = (blay == KCONTIG ? (g.N - 1) * a.ldb + Kp : (Kp - 1) * a.ldb + g.N) * 2;
+        part.C = ws; part.scm = g.N; part.scn = 1; part.sc_batch = g.M * g.N; part.out_dtype = NT_F32;
+        part.D = nullptr; part.alpha = 1.f; part.beta = 0.f; part.act = 0;
+        const nt_status st = launch(part, alay, blay, nwg * ksplit, s);
+        if (st != NT_OK) return st;
+        const int64_t blocks = std::min<int64_t>((g.M * g.N + 255) / 256, 4096);
+        hipLaunchKernelGGL(splitk_sum_kernel, dim3((unsigned)blocks), dim3(256), 0, s, ws, ksplit, g.M, g.N, a.C, a.scm, a.scn, a.out_dtype,
+                           (const void *)a.D, a.sdm, a.sdn, a.alpha, a.beta, a.act);
+        return check_launch("splitk_sum_kernel");
+    }
+    return fail(NT_ERR_UNSUPPORTED, "no fast kernel for this tile");
+}
+
 nt_status launch_gemm(const GemmLaunch &g, int *path_out)
 {
     if (!g.no_workspace) t_k_split = 1;
-
     if (g.batch * g.mt * g.nt > 0x7fffffffLL) return fail(NT_ERR_UNSUPPORTED, "grid too large");
-    const nt_tile_cfg t = g.tile;
-    // fast path: plain operands, each with unit stride along one of its axes
-    bool fast = plain(g.ma) && plain(g.mb) && plain(g.mc) && (!g.has_d || plain(g.md)) && t.bk == 64 && t.bm >= 128 && t.bn >= 128 && g.kt > 0;
-    int alay = KCONTIG, blay = MNCONTIG;
     FastArgs a{};
-    if (fast) {
-        if (g.ma.coff[0] == 1) { alay = KCONTIG; a.lda = g.ma.roff[0]; }
-        else if (g.ma.roff[0] == 1) { alay = MNCONTIG; a.lda = g.ma.coff[0]; }
-        else fast = false;
-        if (g.mb.coff[0] == 1) { blay = MNCONTIG; a.ldb = g.mb.roff[0]; }
-        else if (g.mb.roff[0] == 1) { blay = KCONTIG; a.ldb = g.mb.coff[0]; }
-        else fast = false;
-        if (a.lda < 0 || a.ldb < 0 || a.lda >= (1 << 22) || a.ldb >= (1 << 22)) fast = false;   // 32-bit lane offsets
-        // the staged loader fetches a block that straddles the ragged end of the contiguous
-        // axis up to 7 elements early: that axis must be at least one block (8 elements) long
-        if ((alay == MNCONTIG ? g.M : g.K) < 8 || (blay == MNCONTIG ? g.N : g.K) < 8) fast = false;
-    }
-    if (path_out) *path_out = fast ? PATH_FAST : PATH_GENERIC;
-    if (!fast) {
-        ConvArgs c{};
-        if (!g.has_d && g.alpha == 1.f && g.act == 0 && match_conv(g, &c)) {
-            if (path_out) *path_out = PATH_CONV;
-            const bool edge_b = (g.N % t.bn) || (g.K % t.bk);
-            hipStream_t s = (hipStream_t)g.stream;
-            int32_t kt_per = 0;
-            const int ksplit = conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
-            const int64_t slice = g.conv.N * (int64_t)c.N * c.PQ;
-            float *ws = nullptr;                                     // (none: too large, or no memory; then no split)
-            if (ksplit > 1) {
-                if (!g.no_workspace) ws = split_workspace((size_t)ksplit * slice * 4);
-                else if ((size_t)ksplit * slice * 4 <= g.ws_given_bytes) ws = g.ws_given;
-            }
-            // operands that can stream straight into LDS: whole 32-k slices, 16-byte aligned filter rows, 32-bit byte offsets
-            // (the k split's workspace, at most 256 MB, always has them)
-            const bool direct = c.K % 32 == 0 && c.ldb % 8 == 0 && (reinterpret_cast<uintptr_t>(c.Wt) & 15) == 0 && c.R <= 8 && c.S <= 8 &&
-                                c.x_numel < (1LL << 30) && ((int64_t)(c.N - 1) * c.ldb + c.K) < (1LL << 30) &&
-                                ((g.conv.N - 1) * c.syn + (int64_t)(c.N - 1) * c.syf + c.PQ) < (1LL << 29);   // (output offsets: 31 bits of bytes)
-            if (direct && path_out) *path_out = PATH_CONV_DIRECT;
-            const bool bf16 = g.in_dtype == NT_BF16;
-            auto launch = [&](const ConvArgs &ca, int64_t nwg) {
-                // (one column of tiles with few filters: the same grid is run by the kernel built for 64 or 128 filters per
-                // program, which spends a quarter or half of the MFMAs)
-                const int bn = ca.N <= 64 && direct ? 64 : (ca.N <= 128 ? 128 : t.bn);
-                return direct ? launch_conv_direct(ca, bn, bf16, nwg, s) : launch_conv(ca, bn, bf16, edge_b || (ca.N % bn) != 0, nwg, s);
-            };
-            if (ws) {
-                t_k_split = ksplit;
-                ConvArgs part = c;
-                part.Y = ws; part.syn = (int64_t)c.N * c.PQ; part.syf = c.PQ; part.out_dtype = NT_F32;
-                part.ksplit = ksplit; part.kt_per = kt_per; part.slice = slice;
-                const nt_status st = launch(part, c.mt * c.nt * ksplit);
-                if (st != NT_OK) return st;
-                return launch_conv_ws_sum(ws, ksplit, slice, c.Y, (int64_t)c.N * c.PQ, c.PQ, c.syn, c.syf, c.out_dtype, s);
-            }
-            return launch(c, c.mt * c.nt);
-        }
-        // A unit-stride convolution that the implicit kernels do not take as it is (more than one column of padding, a
-        // channels-last or otherwise strided input): on a dense zero-padded copy of its input, made once in the workspace
-        // (the input's size, not C R S times it), it is a dense convolution without padding.
-        {
-            const ConvHint &h = g.conv;
-            if (h.valid && h.sh == 1 && h.sw == 1 && !g.user_tile && !g.no_workspace && g.batch == 1 && !g.has_d && g.alpha == 1.f && g.act == 0 &&
-                h.ph >= 0 && h.pw >= 0 && h.xs[0] >= 0 && h.xs[1] >= 0 && h.xs[2] >= 0 && h.xs[3] >= 0 &&
-                (h.H - 1) * h.xs[2] + (h.W - 1) * h.xs[3] < (1LL << 31)) {
-                const int64_t Hp = h.H + 2 * h.ph, Wp = h.W + 2 * h.pw, total = h.N * h.C * Hp * Wp;
-                GemmLaunch g2 = g;
-                g2.conv.H = Hp; g2.conv.W = Wp; g2.conv.ph = 0; g2.conv.pw = 0;
-                g2.conv.xs[3] = 1; g2.conv.xs[2] = Wp; g2.conv.xs[1] = Hp * Wp; g2.conv.xs[0] = h.C * Hp * Wp;
-                g2.no_workspace = true;                              // (the workspace holds the copy)
-                ConvArgs probe{};
-                const size_t bytes = ((size_t)((total + 7) / 8 * 8) * 2 + 255) / 256 * 256;
-                uint16_t *P = nullptr;
-                if (Hp * Wp >= 8 && total < (1LL << 31) && match_conv(g2, &probe)) {
-                    // the copy and, behind it, the slices of the k split that the convolution will ask for, in one request
-                    // (a second request could move the workspace)
-                    int32_t kt_per = 0;
-                    const int ks = conv_ksplit(probe.mt * probe.nt, probe.kt, &kt_per);
-                    const size_t split_bytes = ks > 1 ? (size_t)ks * h.N * probe.N * probe.PQ * 4 : 0;
-                    P = (uint16_t *)split_workspace(bytes + split_bytes);
-                    if (P && split_bytes) { g2.ws_given = (float *)((char *)P + bytes); g2.ws_given_bytes = split_bytes; }
-                    if (!P && split_bytes) P = (uint16_t *)split_workspace(bytes);
-                }
-                if (P) {
-                    PadArgs pa{};
-                    pa.x = (const uint16_t *)g.A; pa.P = P;
-                    for (int d = 0; d < 4; ++d) pa.xs[d] = h.xs[d];
-                    pa.total = total;
-                    pa.C = (int32_t)h.C; pa.H = (int32_t)h.H; pa.W = (int32_t)h.W; pa.Hp = (int32_t)Hp; pa.Wp = (int32_t)Wp;
-                    pa.ph = (int32_t)h.ph; pa.pw = (int32_t)h.pw;
-                    const bool nhwc = h.xs[1] == 1 && h.xs[3] == h.C && h.xs[2] == h.W * h.C && h.xs[0] == h.H * h.W * h.C &&
-                                      Hp <= 65535 && h.N * ((h.C + 63) / 64) <= 65535;
-                    if (nhwc) {
-                        hipLaunchKernelGGL(conv_pad_nhwc_kernel, dim3((unsigned)((Wp + 31) / 32), (unsigned)Hp, (unsigned)(h.N * ((h.C + 63) / 64))), dim3(256), 0,
-                                           (hipStream_t)g.stream, pa);
-                    } else {
-                        const int64_t blocks = std::min<int64_t>(((total + 7) / 8 + 255) / 256, 1 << 20);
-                        hipLaunchKernelGGL(conv_pad_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)g.stream, pa);
-                    }
-                    { const nt_status lst = check_launch("conv_pad_kernel"); if (lst != NT_OK) return lst; }
-                    g2.A = P;
-                    return launch_gemm(g2, path_out);
-                }
-            }
-        }
-        // Any other convolution on the library's own tile: the unfolded input is written out once (if it fits the
-        // workspace) and the product runs per image on the MFMA kernels, Y[n] (filters x positions) = W (filters x CRS) .
-        // U[:, n] (CRS x positions) -- far faster than gathering every element of every tile through the operand map.
-        const ConvHint &h = g.conv;
-        if (h.valid && !g.user_tile && !g.no_workspace && g.batch == 1 && !g.has_d && g.alpha == 1.f && g.act == 0 &&
-            h.ys[3] == 1 && h.ys[2] == h.Q && h.ws[3] == 1 && h.ws[2] == h.S && h.ws[1] == h.R * h.S && h.ws[0] >= h.C * h.R * h.S && h.ws[0] < (1 << 22) &&
-            h.N * h.C * h.H * h.W > 0 && (h.N - 1) * h.xs[0] + (h.H - 1) * h.xs[2] + (h.W - 1) * h.xs[3] < (1LL << 31) && h.xs[0] >= 0 && h.xs[2] >= 0 && h.xs[3] >= 0 && h.P * h.Q >= 8 && h.C * h.R * h.S >= 8 && h.C * h.R * h.S <= 65535) {
-            const int64_t K = h.C * h.R * h.S, PQ = h.P * h.Q, M = h.N * PQ, Mp = (M + 7) / 8 * 8;
-            uint16_t *U = Mp < (1 << 22) ? (uint16_t *)split_workspace((size_t)K * Mp * 2) : nullptr;
-            if (U) {
-                hipStream_t s = (hipStream_t)g.stream;
-                UnfoldArgs ua{};
-                ua.x = (const uint16_t *)g.A; ua.U = U;
-                for (int d = 0; d < 4; ++d) ua.xs[d] = h.xs[d];
-                ua.M = M; ua.Mp = Mp; ua.K = K;
-                ua.C = (int32_t)h.C; ua.H = (int32_t)h.H; ua.W = (int32_t)h.W; ua.R = (int32_t)h.R; ua.S = (int32_t)h.S;
-                ua.P = (int32_t)h.P; ua.Q = (int32_t)h.Q; ua.sh = (int32_t)h.sh; ua.sw = (int32_t)h.sw; ua.ph = (int32_t)h.ph; ua.pw = (int32_t)h.pw;
-                const int64_t blocks = std::min<int64_t>((Mp / 8 + 255) / 256, 1 << 16);
-                hipLaunchKernelGGL(conv_unfold_kernel, dim3((unsigned)blocks, (unsigned)K), dim3(256), 0, s, ua);
-                { const nt_status lst = check_launch("conv_unfold_kernel"); if (lst != NT_OK) return lst; }
-                auto matrix = [](int64_t rows, int64_t cols, int64_t row_pitch) {
-                    OperandMap m{};
-                    m.rows = rows; m.cols = cols; m.base = 0; m.nrd = 1; m.ncd = 1; m.nchk = 0;
-                    m.rrad[0] = rows; m.crad[0] = cols; m.roff[0] = row_pitch; m.coff[0] = 1;
-                    return m;
-                };
-                GemmLaunch u{};
-                u.A = g.B; u.B = U; u.C = g.C;
-                u.ma = matrix(h.K, K, h.ws[0]);                      // filters x CRS
-                u.mb = matrix(K, PQ, Mp);                            // CRS x the image's positions
-                u.mc = matrix(h.K, PQ, h.ys[1]);                     // filters x positions
-                u.batch = h.N; u.sa_batch = 0; u.sb_batch = PQ; u.sc_batch = h.ys[0];
-                u.M = h.K; u.N = PQ; u.K = K;
-                u.tile = pick_gemm_tile(u.batch, u.M, u.N, u.K);
-                u.mt = (u.M + u.tile.bm - 1) / u.tile.bm; u.nt = (u.N + u.tile.bn - 1) / u.tile.bn; u.kt = (u.K + u.tile.bk - 1) / u.tile.bk;
-                u.in_dtype = g.in_dtype; u.out_dtype = g.out_dtype; u.stream = g.stream;
-                u.alpha = 1.f; u.beta = 0.f; u.act = 0; u.has_d = false;
-                u.no_workspace = true;                               // (the workspace holds U)
-                const nt_status st = launch_gemm(u, nullptr);
-                if (path_out) *path_out = PATH_CONV_UNFOLD;
-                return st;
-            }
-        }
-    }
-    if (fast) {
-        a.A = (const uint16_t *)g.A + g.ma.base;
-        a.B = (const uint16_t *)g.B + g.mb.base;
-        a.C = g.C;
-        a.scm = g.mc.roff[0];
-        a.scn = g.mc.coff[0];
-        const int64_t esz = g.out_dtype == NT_F32 ? 4 : 2;
-        a.C = (char *)g.C + g.mc.base * esz;
-        a.sa_batch = g.sa_batch; a.sb_batch = g.sb_batch; a.sc_batch = g.sc_batch;
-        a.M = g.M; a.N = g.N; a.K = g.K;
-        a.mt = g.mt; a.nt = g.nt; a.kt = g.kt;
-        a.out_dtype = g.out_dtype;
-        a.alpha = g.alpha;
-        a.beta = g.has_d ? g.beta : 0.f;
-        a.act = g.act;
-        // bounds of the range-checked loads (the pitches are below 2^22, so every offset inside a tile's footprint fits 32 bits)
-        a.a_extent = (alay == KCONTIG ? (g.M - 1) * a.lda + g.K : (g.K - 1) * a.lda + g.M) * 2;
-        a.b_extent = (blay == KCONTIG ? (g.N - 1) * a.ldb + g.K : (g.K - 1) * a.ldb + g.N) * 2;
-        if (g.has_d) {
-            a.D = (const char *)g.D + g.md.base * esz;
-            a.sdm = g.md.roff[0];
-            a.sdn = g.md.coff[0];
-            a.sd_batch = g.sd_batch;
-        }
-        const bool bf16 = g.in_dtype == NT_BF16;
-        const int64_t nwg = g.batch * g.mt * g.nt;
-        hipStream_t s = (hipStream_t)g.stream;
-        // Operands stored to a C (and added to a D) with unit stride along n stream straight into LDS.  Full tiles of
-        // 16-byte aligned operands: plain loads.  Everything else -- tiles that overhang M or N, a ragged K, rows with
-        // only the element's 2-byte alignment -- takes the same loads as range-checked buffer accesses (EDGE kernels),
-        // which needs every offset inside a tile's footprint to fit 32 bits.  The range check works on the 4-byte words
-        // of a load, counted from the load's own start: with an odd pitch, or an extent that is no multiple of 4 bytes,
-        // the word that holds the operand's last element can reach 2 bytes past it; such an operand gets 2 more bytes of
-        // range (the other half of that word is an element nobody uses; it lies in the same 4 KB page, which is
-        // checked here, so the access cannot fault).  What is left takes the staged kernel.
-        const bool ragged_mn = (g.M % t.bm) || (g.N % t.bn), ragged_k = (g.K % t.bk) != 0;
-        auto al16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-        const bool out_ok = a.scn == 1 && (!a.D || a.sdn == 1);
-        const bool aligned = al16(a.A) && al16(a.B) && a.lda % 8 == 0 && a.ldb % 8 == 0 && a.sa_batch % 8 == 0 && a.sb_batch % 8 == 0;
-        const bool plain_direct = out_ok && aligned && !ragged_k && !ragged_mn;
-        auto widen = [&](const uint16_t *base, int64_t ld, int64_t s_batch, int64_t *extent) {      // false: the operand ends at a page's end
-            if (*extent % 4 == 0 && ld % 2 == 0 && s_batch % 2 == 0) return true;      // every word of every load lies at a multiple of 4 bytes
-            if (g.batch > 4096) return false;
-            for (int64_t b = 0; b < g.batch; ++b)
-                if ((reinterpret_cast<uintptr_t>(base + b * s_batch) + (uintptr_t)*extent) % 4096 == 0) return false;
-            *extent += 2;
-            return true;
-        };
-        bool direct = plain_direct;
-        int64_t widened_a = 0, widened_b = 0;
-        if (!direct && out_ok && (alay == KCONTIG || g.K * a.lda < (1LL << 30)) && (blay == KCONTIG || g.K * a.ldb < (1LL << 30))) {
-            int64_t ea = a.a_extent, eb = a.b_extent;
-            if (widen(a.A, a.lda, a.sa_batch, &ea) && widen(a.B, a.ldb, a.sb_batch, &eb)) {
-                widened_a = ea - a.a_extent; widened_b = eb - a.b_extent;
-                a.a_extent = ea; a.b_extent = eb;
-                direct = true;
-            }
-        }
-        if (path_out) *path_out = direct ? PATH_DIRECT : PATH_FAST;
-        typedef nt_status (*Launcher)(const FastArgs &, int, int, int64_t, hipStream_t);
-        struct Entry { int bm, bn; Launcher direct[2], edge[2], staged[2]; };      // [f16, bf16]
-#define NT_ENTRY(BM, BN, T) {BM, BN, {launch_direct_##T##_f16, launch_direct_##T##_bf16}, {launch_direct_edge_##T##_f16, launch_direct_edge_##T##_bf16}, \
-                             {launch_fast_##T##_f16, launch_fast_##T##_bf16}}
-        static const Entry table[] = {NT_ENTRY(128, 128, 128x128), NT_ENTRY(256, 128, 256x128), NT_ENTRY(128, 256, 128x256), NT_ENTRY(256, 256, 256x256)};
-#undef NT_ENTRY
-        for (const Entry &e : table) {
-            if (e.bm != t.bm || e.bn != t.bn) continue;
-            const Launcher launch = (direct ? (plain_direct ? e.direct : e.edge) : e.staged)[bf16 ? 1 : 0];
-            // k split: `ksplit` equal parts of K as the entries of a batched product into fp32 slices of the workspace
-            const int ksplit = g.batch == 1 && !ragged_k && !g.no_workspace ? gemm_ksplit(g.mt * g.nt, g.kt, g.M, g.N) : 1;
-            float *ws = ksplit > 1 ? split_workspace((size_t)ksplit * g.M * g.N * 4) : nullptr;     // (none: too large, or no memory; then no split)
-            if (!ws) return launch(a, alay, blay, nwg, s);
-            t_k_split = ksplit;
-            FastArgs part = a;
-            const int64_t Kp = g.K / ksplit;
-            part.K = Kp; part.kt = g.kt / ksplit;
-            part.sa_batch = alay == KCONTIG ? Kp : Kp * a.lda;
-            part.sb_batch = blay == KCONTIG ? Kp : Kp * a.ldb;
-            // (K and Kp are multiples of 64: a part's extent is as odd or even as the whole's, and the 2 bytes after a
-            // part lie inside the operand, or are the ones checked above)
-            part.a_extent = (alay == KCONTIG ? (g.M - 1) * a.lda + Kp : (Kp - 1) * a.lda + g.M) * 2 + widened_a;
-            part.b_extent = (blay == KCONTIG ? (g.N - 1) * a.ldb + Kp : (Kp - 1) * a.ldb + g.N) * 2 + widened_b;
-            part.C = ws; part.scm = g.N; part.scn = 1; part.sc_batch = g.M * g.N; part.out_dtype = NT_F32;
-            part.D = nullptr; part.alpha = 1.f; part.beta = 0.f; part.act = 0;
-            // (a part is as streamable as the whole: its offsets are multiples of 64 elements, its C is dense fp32)
-            const nt_status st = launch(part, alay, blay, nwg * ksplit, s);
-            if (st != NT_OK) return st;
-            const int64_t blocks = std::min<int64_t>((g.M * g.N + 255) / 256, 4096);
-            hipLaunchKernelGGL(splitk_sum_kernel, dim3((unsigned)blocks), dim3(256), 0, s, ws, ksplit, g.M, g.N, a.C, a.scm, a.scn, a.out_dtype,
-                               (const void *)a.D, a.sdm, a.sdn, a.alpha, a.beta, a.act);
-            return check_launch("splitk_sum_kernel");
-        }
-        return fail(NT_ERR_UNSUPPORTED, "no fast kernel for this tile");
-    }
+    int alay = KCONTIG, blay = MNCONTIG;
+    if (lower_plain(g, &a, &alay, &blay)) return route_matrix(g, a, alay, blay, path_out);
+    if (path_out) *path_out = PATH_GENERIC;
+    ConvArgs c{};
+    if (!g.has_d && g.alpha == 1.f && g.act == 0 && match_conv(g, &c)) return route_conv_implicit(g, c, path_out);
+    bool taken = false;
+    nt_status st = route_conv_padded_copy(g, path_out, &taken);
+    if (taken || st != NT_OK) return st;
+    st = route_conv_unfold(g, path_out, &taken);
+    if (taken || st != NT_OK) return st;
     return launch_generic(g);
 }
 
@@ -595,8 +667,8 @@ nt_status launch_fill_zero(void *C, const OperandMap &mc, int64_t batch, int64_t
     const int64_t total = mc.rows * mc.cols;
     if (total <= 0 || batch <= 0) return NT_OK;
     const int64_t blocks = std::min<int64_t>((total + 255) / 256, 4096);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks, (unsigned)batch), dim3(256), 0, (hipStream_t)stream,
-                       C, mc, sc_batch, out_dtype);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks, (unsigned)std::min<int64_t>(batch, 1024)), dim3(256), 0, (hipStream_t)stream,
+                       C, mc, batch, sc_batch, out_dtype);
     return check_launch("fill_zero_kernel");
 }
 

@@ -39,9 +39,10 @@ struct GemmLaunch {
     bool has_d;
     ConvHint conv;
     bool user_tile;                         // the caller named the tile (then the kernels the library would prefer are not substituted)
-    bool no_workspace;                      // the library's workspace is in use by the caller of this launch: a k split only
+    bool no_workspace;                      // the library's workspace is in use by the caller of this launch, or must not be touched: a k split only
     float *ws_given;                        // inside the region the caller has set aside for it (ws_given_bytes; may be none)
     size_t ws_given_bytes;
+    bool ws_strict;                         // a k split that would need more than ws_given_bytes is an error (else: run unsplit)
 };
 
 // Which code path a launch would take (reported for tests and the benchmark).
