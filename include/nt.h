@@ -182,6 +182,20 @@ nt_status nt_gemm(const void *A, const nt_tensor_desc *dA, const void *B, const 
                   void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
                   nt_tile_cfg cfg, void *hip_stream);
 
+/* nt_gemm_noalloc: nt_gemm for callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results bit for bit; it calls
+ * no hipMalloc / hipFree and never touches the library's workspace.  The k split of a skinny product puts its fp32
+ * partial tiles into a fixed array of NT_NOALLOC_SCRATCH_BYTES inside the library's device image instead (every GPU
+ * the library is loaded on holds its own copy from load time until the process ends).  A product whose split needs
+ * more (parts x M x N x 4 bytes) is refused with NT_ERR_UNSUPPORTED and a message that names both sizes; nothing is
+ * launched then.  Every call on a GPU shares that GPU's array and nothing orders them: calls that overlap on one
+ * GPU (different streams or host threads, both splitting) race on it -- keep them on one stream.  The array needs no
+ * clearing between calls: every part writes its whole slice before the sum reads it. */
+#define NT_NOALLOC_SCRATCH_BYTES (32u << 20)
+nt_status nt_gemm_noalloc(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
+                          void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
+                          nt_tile_cfg cfg, void *hip_stream);
+
 /* nt_addmm: C[M,N] = beta * input[M,N] + alpha * (A[M,K] . B[K,N])  -- the addmm kernel of the paper's
  * task list (Section 5.1): the matmul arrangement and application of Section 4.2 with `input` arranged
  * like the output (tile(BM, BN)) and combined with the accumulator in fp32 before the one conversion to

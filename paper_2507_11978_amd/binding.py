@@ -105,6 +105,7 @@ def load():
     L.nt_tile_supported.argtypes = [TileCfg]
     L.nt_tile_supported.restype = i32
     L.nt_gemm.argtypes = [P, D, P, D, P, D, i32, i32, TileCfg, P]
+    L.nt_gemm_noalloc.argtypes = [P, D, P, D, P, D, i32, i32, TileCfg, P]
     L.nt_bmm.argtypes = [P, D, P, D, P, D, i32, i32, TileCfg, P]
     L.nt_addmm.argtypes = [P, D, P, D, P, D, P, D, C.c_float, C.c_float, i32, i32, TileCfg, P]
     L.nt_addmm_act.argtypes = [P, D, P, D, P, D, P, D, C.c_float, C.c_float, i32, i32, i32, TileCfg, P]
@@ -117,7 +118,7 @@ def load():
     L.nt_rms_norm.argtypes = [P, D, P, D, C.c_float, i32, P]
     L.nt_trace_tile.argtypes = [i32, D, D, D, i32, i32, i32, i32, TileCfg, i32, i64, i64, P, P, C.c_size_t, P]
     for name in ("nt_arrange_levels", "nt_arrange_tile", "nt_arrange_gemm", "nt_arrange_bmm", "nt_arrange_conv2d",
-                 "nt_program_order", "nt_gemm", "nt_addmm", "nt_addmm_act", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile",
+                 "nt_program_order", "nt_gemm", "nt_gemm_noalloc", "nt_addmm", "nt_addmm_act", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile",
                  "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm", "nt_matmul_views", "nt_sdpa"):
         getattr(L, name).restype = i32
     L.nt_last_kernel_path.restype = i32
@@ -319,6 +320,15 @@ def gemm(A, B, Cout, tile=None, stream=None):
     _check(load().nt_gemm(A.data_ptr(), C.byref(_desc_of(A)), B.data_ptr(), C.byref(_desc_of(B)),
                           Cout.data_ptr(), C.byref(_desc_of(Cout)), _DTYPES[_torch_dtype_name(A)],
                           _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
+    return Cout
+
+
+def gemm_noalloc(A, B, Cout, tile=None, stream=None):
+    """gemm() through the entry point that allocates no device memory (a k split uses the library's fixed scratch array)."""
+    _require_cuda(A, B, Cout)
+    _check(load().nt_gemm_noalloc(A.data_ptr(), C.byref(_desc_of(A)), B.data_ptr(), C.byref(_desc_of(B)),
+                                  Cout.data_ptr(), C.byref(_desc_of(Cout)), _DTYPES[_torch_dtype_name(A)],
+                                  _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
     return Cout
 
 

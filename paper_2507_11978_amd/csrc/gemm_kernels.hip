@@ -331,6 +331,31 @@ private:
     hipStream_t stream_ = nullptr;
 };
 
+// Scratch memory for callers that cannot allocate (nt_gemm_noalloc): a fixed array in the library's device image, one copy
+// per GPU, held from the moment the library is loaded on that GPU until the process ends.  Host code never uses the array's
+// name as an address: the device address is looked up once per device, with that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[NT_NOALLOC_SCRATCH_BYTES];
+
+nt_status static_scratch(void **ptr_out, size_t *bytes_out)
+{
+    static void *table[64] = {};
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    if (dev < 0 || dev >= 64) return fail(NT_ERR_UNSUPPORTED, "device index beyond 63");
+    std::lock_guard<std::mutex> lock(mu);
+    if (!table[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { (void)hipGetLastError(); return fail(NT_ERR_DEVICE, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e)); }
+        table[dev] = p;
+    }
+    *ptr_out = table[dev];
+    *bytes_out = sizeof(scratch);
+    return NT_OK;
+}
+
 // A convolution with few output tiles and a long reduction leaves most of the chip idle: its k tiles are dealt to
 // `ksplit` programs per output tile, enough for about one program per compute unit, none with fewer than 4 k tiles.
 // (Measured on 13 shapes from 1 to 112 programs and 8 to 72 k tiles: the split run is faster in every one, e.g.
@@ -646,7 +671,7 @@ static nt_status route_matrix(const GemmLaunch &g, FastArgs a, int alay, int bla
 
 nt_status launch_gemm(const GemmLaunch &g, int *path_out)
 {
-    if (!g.no_workspace) t_k_split = 1;
+    if (!g.no_workspace || g.ws_strict) t_k_split = 1;
     if (g.batch * g.mt * g.nt > 0x7fffffffLL) return fail(NT_ERR_UNSUPPORTED, "grid too large");
     FastArgs a{};
     int alay = KCONTIG, blay = MNCONTIG;

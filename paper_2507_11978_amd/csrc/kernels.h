@@ -54,6 +54,8 @@ int last_k_split();
 // the tile the MFMA kernels run a plain (batched) product of this size fastest with, by a cost model fitted to measurements
 nt_tile_cfg pick_gemm_tile(int64_t batch, int64_t M, int64_t N, int64_t K);
 nt_status launch_gemm(const GemmLaunch &g, int *path_out);
+// device address and size of the fixed scratch array of the entry point that allocates nothing (this device's copy)
+nt_status static_scratch(void **ptr_out, size_t *bytes_out);
 nt_status launch_fill_zero(void *C, const OperandMap &mc, int64_t batch, int64_t sc_batch, int out_dtype, void *stream);
 nt_status launch_trace(const OperandMap &m, int64_t batch_off, int64_t row0, int64_t col0, int32_t rows, int32_t cols,
                        int64_t *offsets_out, uint8_t *mask_out, void *stream);

@@ -137,7 +137,7 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
               void *C, const nt_tensor_desc *dC, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
               nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *stream,
               const void *D = nullptr, const nt_tensor_desc *dD = nullptr, float alpha = 1.f, float beta = 0.f,
-              const ViewPrograms *views = nullptr, int act = 0)
+              const ViewPrograms *views = nullptr, int act = 0, bool static_ws = false)
 {
     t_last_path = -1;
     if (!dtype_in_ok(in_dtype)) return fail(NT_ERR_UNSUPPORTED, "input dtype must be NT_F16 or NT_BF16");
@@ -169,7 +169,7 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
     if (p.K == 0) {
         if (!g.has_d) return nt::launch_fill_zero(C, g.mc, p.batch, g.sc_batch, out_dtype, stream);
         // C = beta * input: the operand-map kernel with no k tiles (its grid is that of the 64 x 64 tile)
-        if (p.tile.bm != 64) return run(kind, A, dA, B, dB, C, dC, sh, sw, ph, pw, in_dtype, out_dtype, nt_tile_cfg{64, 64, 32}, stream, D, dD, alpha, beta, views, act);
+        if (p.tile.bm != 64) return run(kind, A, dA, B, dB, C, dC, sh, sw, ph, pw, in_dtype, out_dtype, nt_tile_cfg{64, 64, 32}, stream, D, dD, alpha, beta, views, act, static_ws);
     }
     if (kind == KIND_CONV) {
         nt::ConvHint &h = g.conv;
@@ -189,6 +189,16 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
     g.in_dtype = in_dtype;
     g.out_dtype = out_dtype;
     g.stream = stream;
+    if (static_ws) {
+        // the library's workspace is out of bounds (it is allocated on first use); a k split goes through the fixed array
+        void *p = nullptr;
+        size_t bytes = 0;
+        NT_TRY(nt::static_scratch(&p, &bytes));
+        g.no_workspace = true;
+        g.ws_given = (float *)p;
+        g.ws_given_bytes = bytes;
+        g.ws_strict = true;
+    }
     return nt::launch_gemm(g, &t_last_path);
 }
 
@@ -289,6 +299,13 @@ nt_status nt_gemm(const void *A, const nt_tensor_desc *dA, const void *B, const 
                   nt_tile_cfg cfg, void *hip_stream)
 {
     return run(KIND_GEMM, A, dA, B, dB, C, dC, 1, 1, 0, 0, in_dtype, out_dtype, cfg, hip_stream);
+}
+
+nt_status nt_gemm_noalloc(const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
+                          void *C, const nt_tensor_desc *dC, nt_dtype in_dtype, nt_dtype out_dtype,
+                          nt_tile_cfg cfg, void *hip_stream)
+{
+    return run(KIND_GEMM, A, dA, B, dB, C, dC, 1, 1, 0, 0, in_dtype, out_dtype, cfg, hip_stream, nullptr, nullptr, 1.f, 0.f, nullptr, 0, true);
 }
 
 nt_status nt_addmm(const void *input, const nt_tensor_desc *dI, const void *A, const nt_tensor_desc *dA,
