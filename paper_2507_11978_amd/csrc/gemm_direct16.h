@@ -1,0 +1,386 @@
+// Direct kernel on 16 x 16 x 32 matrix instructions: full tiles of 16-byte aligned, unit-stride operands.
+//
+// The same program (Section 3.2.1), the same global -> LDS ring of 32-k slices and the same LDS slice layouts as
+// gemm_direct_kernel; what differs is the matrix instruction.  v_mfma_f32_16x16x32 multiplies a 16 x 32 block by a
+// 32 x 16 block: one instruction consumes a whole 32-k slice of its two 16-row fragments, and a wavefront's
+// (BM/2) x (BN/2) part of the tile is (BM/32) x (BN/32) accumulator blocks of 4 registers each.  Measured on this
+// part with operands of the benchmark's distribution and nothing else running, a wavefront-per-SIMD loop of these
+// instructions sustains 1.85 PFLOP/s against 1.60 PFLOP/s for v_mfma_f32_32x32x16 (both reach 2.4 with all-zero
+// operands): the chip is power managed, the narrower instruction moves fewer accumulator bits per flop, and the
+// difference is clock.
+//
+// One trip of the loop = one slice.  A trip multiplies the fragments of slice s (all in registers, read during the
+// trip before) while it reads the fragments of slice s+1 into the other register set and requests slice s+ring
+// into the ring position that slice s has just left; one barrier per trip, at its top, says that slice s+1 has
+// landed in LDS and that nobody reads slice s there any more.
+//
+// Fragment layouts.  Lane l of a wavefront supplies row (or column) l % 16 of its fragment and the 8 consecutive
+// k 8 (l / 16) .. + 7.
+//   k-major slice  [row][32 k], 64 bytes per row, 16-byte chunk c of row r stored at chunk c ^ ((r / 4) & 3) (as in
+//            gemm_direct_kernel): one ds_read_b128 per fragment; the 16 lanes of a quarter wavefront read 16
+//            consecutive rows, same k chunk: 16 different 16-byte columns of the 256 bytes the LDS serves per cycle.
+//   mn-major slice [k][E], chunk c of k row k stored at chunk c ^ (2 (k & 3) + 8 ((k / 8) & 1)): two transposing
+//            reads (ds_read_b64_tr_b16) per fragment, each of which turns a 4 (k) x 16 (m / n) patch per quarter
+//            wavefront into 4 consecutive k per lane; the eight 32-byte row segments that half a wavefront reads
+//            (k rows 8 g .. 8 g + 3 of two quarter wavefronts g) fall into eight different 32-byte columns.
+// The matrix instructions are issued through inline assembly with the accumulator tied to the destination (the
+// compiler's own choice for this instruction copies accumulators between registers inside the loop).
+#pragma once
+#include "gemm_direct.h"
+
+namespace nt {
+
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+template <bool BF16>
+__device__ __forceinline__ void mfma16(float4v &acc, const u32x4 &a, const u32x4 &b)
+{
+    if constexpr (BF16) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    else asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+template <int E, int LAY>
+struct DirectTile16;
+
+// ---- k-major slice: E rows (m or n) x 32 k
+template <int E>
+struct DirectTile16<E, KCONTIG> {
+    static constexpr uint32_t BYTES = E * kSliceK * 2;
+    static constexpr int PER = BYTES / 1024 / 4;           // load instructions per wavefront and slice
+    static constexpr int RPF = 1;                          // LDS reads per operand fragment
+    static constexpr int T = E / 32;                       // 16-row fragments per wavefront
+    uint32_t voff[PER];                                    // global byte offset of this lane's chunk
+    uint32_t rd;                                           // LDS read base of this lane
+
+    __device__ __forceinline__ void init(int wave, int lane, int64_t ld, int wave_origin, uint32_t region)
+    {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int row = (wave * PER + j) * 16 + (lane >> 2);
+            const int c = (lane & 3) ^ ((row >> 2) & 3);
+            voff[j] = ((uint32_t)row * (uint32_t)ld + (uint32_t)(c * 8)) * 2u;
+        }
+        const int r = wave_origin + (lane & 15);           // (wave_origin is a multiple of 16: fragment t is rows r + 16 t, same swizzle bits)
+        rd = (uint32_t)(r * 64 + (((lane >> 4) ^ ((r >> 2) & 3)) << 4)) + region;
+    }
+    __device__ __forceinline__ void issue_one(int j, const char *g, uint32_t lds_slice, int wave) const
+    {
+        dma16(g, voff[j], lds_slice + (uint32_t)((wave * PER + j) * 1024));
+    }
+    // read q of the slice at byte offset slice_off: fragment q, whole
+    __device__ __forceinline__ void read(u32x4 (&f)[T], const char *smem, int q, uint32_t slice_off) const
+    {
+        f[q] = lds_read16(smem, rd + slice_off + q * 1024);
+    }
+};
+
+// ---- mn-major slice: 32 k rows x E (m or n)
+template <int E>
+struct DirectTile16<E, MNCONTIG> {
+    static constexpr uint32_t BYTES = E * kSliceK * 2;
+    static constexpr int PER = BYTES / 1024 / 4;
+    static constexpr int RPF = 2;
+    static constexpr int RB = 2 * E;                       // bytes per k row
+    static constexpr int CPR = E / 8;                      // 16-byte chunks per k row
+    static constexpr int RPI = 1024 / RB;                  // k rows per load instruction
+    static constexpr int T = E / 32;
+    uint32_t voff[PER];
+    uint32_t rd[T];
+
+    static __device__ __forceinline__ int swizzle(int krow) { return ((krow & 3) << 1) | (((krow >> 3) & 1) << 3); }
+
+    __device__ __forceinline__ void init(int wave, int lane, int64_t ld, int wave_origin, uint32_t region)
+    {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int krow = (wave * PER + j) * RPI + lane / CPR;
+            const int c = (lane % CPR) ^ swizzle(krow);
+            voff[j] = ((uint32_t)krow * (uint32_t)ld + (uint32_t)(c * 8)) * 2u;
+        }
+        // transposing read: quarter wavefront g covers k rows 8 g .. 8 g + 3 (+ 4 for the second read) and the
+        // fragment's 16 columns; lane i of the quarter points at row i / 4, 4 columns starting at 4 (i % 4), and
+        // receives 4 consecutive k of column i
+        const int g = lane >> 4, i = lane & 15;
+        const int kl = 8 * g + (i >> 2);
+        const int mn = wave_origin + 4 * (i & 3);
+        const int sw = swizzle(kl);                        // the same for kl + 4
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+            rd[t] = (uint32_t)(kl * RB + ((((mn >> 3) + 2 * t) ^ sw) << 4) + ((mn >> 2) & 1) * 8) + region;
+    }
+    __device__ __forceinline__ void issue_one(int j, const char *g, uint32_t lds_slice, int wave) const
+    {
+        dma16(g, voff[j], lds_slice + (uint32_t)((wave * PER + j) * 1024));
+    }
+    // read q of the slice: half q % 2 (k 0..3 or 4..7 of the lane's run) of fragment q / 2
+    __device__ __forceinline__ void read(u32x4 (&f)[T], const char *smem, int q, uint32_t slice_off) const
+    {
+        typedef short4v __attribute__((address_space(3))) * lds_s4;
+        const int t = q >> 1, part = q & 1;
+        const u32x2 v = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (rd[t] + slice_off + (uint32_t)(part * 4 * RB)))));
+        f[t][2 * part] = v[0];
+        f[t][2 * part + 1] = v[1];
+    }
+};
+
+// ---- epilogue (output = accumulator, Section 4.2).  Every matrix instruction is issued with the B fragment first,
+// so a 16 x 16 accumulator block comes out transposed: a lane holds row m = lane % 16 of the block and its 4
+// consecutive columns 4 (lane / 16) .. + 3.  C (and D) have unit stride along n, the tile is full.  The wavefront's
+// part goes through its own region of the (idle) LDS so that global stores are whole 256-byte row segments:
+//   write phase  per block, alpha / beta * D / activation in fp32 if asked, one conversion, then the lane's 4 values
+//                (8 bytes, or one 16-byte chunk of fp32) to [row][256 bytes] with the chunk index XOR-ed with the row
+//                (16 rows, same chunk: 16 different chunks);
+//   read phase   16 consecutive lanes read one row; a store instruction covers 4 rows of 256 contiguous bytes.
+// An fp32 tile takes two passes (one per half of the columns) through the same region.
+template <int BM, int BN, int OUT>
+__device__ __forceinline__ void store_tile16_rows(char *smem, int wave, char *C, int64_t scm, const float4v (&acc)[BM / 32][BN / 32],
+                                                  int64_t row_w, int64_t col_w, int lane, bool affine, const char *D, int64_t sdm,
+                                                  float alpha, float beta, int act)
+{
+    constexpr int TM = BM / 32, WM = BM / 2, WN = BN / 2;
+    constexpr int ES = OUT == NT_F32 ? 4 : 2;
+    constexpr int PASSES = ES / 2;                        // an fp32 tile takes one pass per half of the columns
+    constexpr int PW = WN / PASSES;                       // columns per pass
+    constexpr int RB = WN * 2;                            // bytes per region row: 256 or 128
+    constexpr int CPR = RB / 16;                          // 16-byte chunks per row
+    constexpr int RSH = RB == 256 ? 0 : 1;                // log2(rows per 256 bytes of LDS)
+    constexpr int EPC = 16 / ES;                          // elements per chunk
+    constexpr int RPI = 64 / CPR;                         // rows per store instruction
+    constexpr int TNP = PW / 16;                          // blocks per pass
+    const int l16 = lane & 15, g = lane >> 4;
+    const ActParams ap = act_params(act);
+    char *reg = smem + wave * (WM * RB);
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass) {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int r = tm * 16 + l16;
+            const int64_t row = row_w + r;
+            const int sw = (r >> RSH) & (CPR - 1);
+            char *prow = reg + r * RB;
+#pragma unroll
+            for (int tnp = 0; tnp < TNP; ++tnp) {
+                const int tn = pass * TNP + tnp;
+                // (the block is pinned in its accumulator registers up to this point: without this the compiler moves all
+                // 256 accumulators to ordinary registers ahead of the three output formats' code and spills them)
+                float4v blk = acc[tm][tn];
+                asm volatile("" : "+a"(blk));
+                float o[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) o[v] = blk[v];
+                if (affine) {                                         // wavefront-uniform
+                    float d[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (D) {
+                        const char *dp = D + (row * sdm + col_w + tn * 16 + 4 * g) * ES;
+                        if constexpr (OUT == NT_F32) {
+                            u32x4 w;
+                            __builtin_memcpy(&w, dp, 16);
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) { const uint32_t x = w[v]; d[v] = __builtin_bit_cast(float, x); }
+                        } else {
+                            u32x2 w;
+                            __builtin_memcpy(&w, dp, 8);
+#pragma unroll
+                            for (int v = 0; v < 2; ++v) {
+                                const uint32_t x = w[v];
+                                if constexpr (OUT == NT_F16) {
+                                    d[2 * v] = (float)__builtin_bit_cast(_Float16, (uint16_t)(x & 0xffffu));
+                                    d[2 * v + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(x >> 16));
+                                } else {
+                                    d[2 * v] = __builtin_bit_cast(float, x << 16);
+                                    d[2 * v + 1] = __builtin_bit_cast(float, x & 0xffff0000u);
+                                }
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) o[v] = combine(o[v], d[v], alpha, beta);
+                    if (act) {                                        // wavefront-uniform
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) o[v] = activate(o[v], ap);
+                    }
+                }
+                if constexpr (OUT == NT_F32) {
+                    const int c = tnp * 4 + g;
+                    lds_write16(prow, (uint32_t)((c ^ sw) << 4), u32x4{__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
+                                                                        __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3])});
+                } else {
+                    const int c = tnp * 2 + (g >> 1);
+                    *reinterpret_cast<u32x2 *>(prow + (((c ^ sw) << 4) + 8 * (g & 1))) =
+                        u32x2{pack_pair<OUT>(__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1])),
+                              pack_pair<OUT>(__builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3]))};
+                }
+            }
+        }
+        // ---- read phase (same wavefront: LDS operations complete in order)
+#pragma unroll
+        for (int it = 0; it < WM / RPI; ++it) {
+            const int r = it * RPI + lane / CPR, c = lane % CPR;
+            const u32x4 v = lds_read16(reg, (uint32_t)(r * RB + ((c ^ ((r >> RSH) & (CPR - 1))) << 4)));
+            char *p = C + ((row_w + r) * scm + col_w + pass * PW + c * EPC) * ES;
+            __builtin_memcpy(p, &v, 16);
+        }
+    }
+}
+
+template <int BM, int BN>
+__device__ __forceinline__ void store_tile16(const FastArgs &g, char *smem, int wave, int64_t bi, const float4v (&acc)[BM / 32][BN / 32],
+                                             int64_t row_w, int64_t col_w, int lane)
+{
+    const int64_t esz = g.out_dtype == NT_F32 ? 4 : 2;
+    char *C = reinterpret_cast<char *>(g.C) + bi * g.sc_batch * esz;
+    const char *D = g.D ? reinterpret_cast<const char *>(g.D) + bi * g.sd_batch * esz : nullptr;
+    const bool affine = D != nullptr || g.alpha != 1.f || g.act != 0;
+#define NT_ROWS16(OUT) store_tile16_rows<BM, BN, OUT>(smem, wave, C, g.scm, acc, row_w, col_w, lane, affine, D, g.sdm, g.alpha, g.beta, g.act)
+    if (g.out_dtype == NT_F32) NT_ROWS16(NT_F32);
+    else if (g.out_dtype == NT_F16) NT_ROWS16(NT_F16);
+    else NT_ROWS16(NT_BF16);
+#undef NT_ROWS16
+}
+
+template <int BM, int BN, bool BF16, int ALAY, int BLAY>
+__global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_kernel(const FastArgs g)
+{
+    constexpr int TM = BM / 32, TN = BN / 32;
+    constexpr int kRing = ring_of(BM, BN);
+    using TileA = DirectTile16<BM, ALAY>;
+    using TileB = DirectTile16<BN, BLAY>;
+    constexpr uint32_t A_BYTES = TileA::BYTES, B_BYTES = TileB::BYTES, B_BASE = kRing * A_BYTES;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    int64_t bi, ti, tj;
+    locate_program(g.mt, g.nt, &bi, &ti, &tj);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = wave >> 1, wave_n = wave & 1;
+    const int64_t row0 = ti * BM, col0 = tj * BN;
+
+    const char *gA = reinterpret_cast<const char *>(g.A + bi * g.sa_batch + (ALAY == KCONTIG ? row0 * g.lda : row0));
+    const char *gB = reinterpret_cast<const char *>(g.B + bi * g.sb_batch + (BLAY == KCONTIG ? col0 * g.ldb : col0));
+    const int64_t a_step = (ALAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.lda) * 2;
+    const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.ldb) * 2;
+    const int64_t n_slices = g.kt * (kBK / kSliceK);       // even
+
+    TileA ta;
+    TileB tb;
+    ta.init(wave, lane, g.lda, wave_m * (BM / 2), 0);
+    tb.init(wave, lane, g.ldb, wave_n * (BN / 2), B_BASE);
+
+    float4v acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
+
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+
+    // operand fragments of one slice, two sets: [set][fragment]
+    u32x4 fa[2][TM], fb[2][TN];
+    constexpr int NRA = TM * TileA::RPF, NRB = TN * TileB::RPF, NR = NRA + NRB;   // LDS reads per slice
+    // LDS read r of a slice, in the order the next trip's matrix instructions need the data:
+    // A fragment 0, every B fragment, then the remaining A fragments
+    auto lds_read = [&](int r, int set, uint32_t ring) {
+        if (r < TileA::RPF) ta.read(fa[set], smem, r, ring * A_BYTES);
+        else if (r < TileA::RPF + NRB) tb.read(fb[set], smem, r - TileA::RPF, ring * B_BYTES);
+        else ta.read(fa[set], smem, r - NRB, ring * A_BYTES);
+    };
+    constexpr int NM = TM * TN, ND = TileA::PER + TileB::PER;
+    auto dma = [&](int d, const char *pa, const char *pb, uint32_t ring) {
+        if (d < TileA::PER) ta.issue_one(d, pa, lds0 + ring * A_BYTES, wave);
+        else tb.issue_one(d - TileA::PER, pb, lds0 + B_BASE + ring * B_BYTES, wave);
+    };
+    // One trip: the TM x TN matrix instructions on fragment set `set`; between them, spread evenly so that neither
+    // the LDS queue nor the memory queue holds the in-order wavefront back while the matrix pipe runs dry, the LDS
+    // reads of the next slice (ring position rring) into the other set and the ND global -> LDS loads of the slice
+    // at (pa, pb) into ring position dring.
+    auto trip = [&](int set, uint32_t rring, const char *pa, const char *pb, uint32_t dring) {
+        constexpr int RS = NM * 3 / 4;                      // the reads go out during the first three quarters: all have returned by the next barrier
+#pragma unroll
+        for (int idx = 0; idx < NM; ++idx) {
+            const int tm = idx / TN, tn = idx % TN;
+            mfma16<BF16>(acc[tm][tn], fb[set][tn], fa[set][tm]);      // transposed block (see store_tile16_rows)
+            if (idx < RS)
+#pragma unroll
+                for (int r = idx * NR / RS; r < (idx + 1) * NR / RS; ++r) lds_read(r, set ^ 1, rring);
+#pragma unroll
+            for (int d = idx * ND / NM; d < (idx + 1) * ND / NM; ++d) dma(d, pa, pb, dring);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    const int64_t last = n_slices - 1;
+    auto slice_a = [&](int64_t s) { return gA + (s < last ? s : last) * a_step; };   // clamped: surplus slices are never multiplied
+    auto slice_b = [&](int64_t s) { return gB + (s < last ? s : last) * b_step; };
+
+    // prologue: slices 0 .. kRing-1 requested; wait for slice 0; its fragments into set 0
+#pragma unroll
+    for (int s = 0; s < kRing; ++s)
+#pragma unroll
+        for (int d = 0; d < ND; ++d) dma(d, slice_a(s), slice_b(s), s);
+    NT_WAIT_VMCNT((kRing - 1) * ND);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < NR; ++r) lds_read(r, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // Slice s sits at ring position s % kRing.  At the top of trip s this wavefront's part of slice s+1 must have
+    // landed (the loads of the two younger slices may still be in flight); the barrier then says that slice s+1 is
+    // complete and that every wavefront holds its fragments of slice s in registers, so the position of slice s can
+    // be overwritten by slice s+kRing.
+    uint32_t ring = 0;
+    for (int64_t sl = 0; sl < n_slices; sl += 2) {
+        uint32_t nxt = ring + 1 == kRing ? 0 : ring + 1;
+        NT_WAIT_VMCNT((kRing - 2) * ND);
+        __syncthreads();
+        trip(0, nxt, slice_a(sl + kRing), slice_b(sl + kRing), ring);
+        ring = nxt;
+        nxt = ring + 1 == kRing ? 0 : ring + 1;
+        NT_WAIT_VMCNT((kRing - 2) * ND);
+        __syncthreads();
+        trip(1, nxt, slice_a(sl + 1 + kRing), slice_b(sl + 1 + kRing), ring);
+        ring = nxt;
+    }
+    NT_WAIT_VMCNT(0);                                      // drain the surplus prefetches ...
+    __syncthreads();                                       // ... of every wavefront: the epilogue reuses the LDS
+    // The accumulators are read by ordinary instructions from here on, and the compiler does not know that the inline
+    // assembly above is a matrix instruction whose result needs wait states before it can be read: 16 wait states
+    // here, and the epilogue takes every accumulator block through an assembly statement of its own before it reads
+    // it (statements of this kind stay in program order, so every read follows the wait states).
+    asm volatile("s_nop 15" ::: "memory");
+
+    store_tile16<BM, BN>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
+}
+
+template <int BM, int BN, bool BF16, int ALAY, int BLAY>
+static nt_status launch_direct16_inst(const FastArgs &a, int64_t nwg, hipStream_t s)
+{
+    constexpr size_t smem = (size_t)ring_of(BM, BN) * (BM + BN) * kSliceK * sizeof(uint16_t);
+    auto kern = gemm_direct16_kernel<BM, BN, BF16, ALAY, BLAY>;
+    static DeviceOnce configured;
+    if (!configured.done()) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
+        configured.set();
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
+    return check_launch("gemm_direct16_kernel");
+}
+
+template <int BM, int BN, bool BF16>
+static nt_status launch_direct16_t(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s)
+{
+    if (alay == KCONTIG && blay == MNCONTIG) return launch_direct16_inst<BM, BN, BF16, KCONTIG, MNCONTIG>(a, nwg, s);
+    if (alay == KCONTIG && blay == KCONTIG) return launch_direct16_inst<BM, BN, BF16, KCONTIG, KCONTIG>(a, nwg, s);
+    if (alay == MNCONTIG && blay == MNCONTIG) return launch_direct16_inst<BM, BN, BF16, MNCONTIG, MNCONTIG>(a, nwg, s);
+    return launch_direct16_inst<BM, BN, BF16, MNCONTIG, KCONTIG>(a, nwg, s);
+}
+
+#define NT_DIRECT16_DECL(T) \
+    nt_status launch_direct16_##T##_f16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s); \
+    nt_status launch_direct16_##T##_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s);
+NT_DIRECT16_DECL(256x256)
+#undef NT_DIRECT16_DECL
+
+}  // namespace nt
