@@ -19,10 +19,12 @@
 //   k-major slice  [row][32 k], 64 bytes per row, 16-byte chunk c of row r stored at chunk c ^ ((r / 4) & 3) (as in
 //            gemm_direct_kernel): one ds_read_b128 per fragment; the 16 lanes of a quarter wavefront read 16
 //            consecutive rows, same k chunk: 16 different 16-byte columns of the 256 bytes the LDS serves per cycle.
-//   mn-major slice [k][E], chunk c of k row k stored at chunk c ^ (2 (k & 3) + 8 ((k / 8) & 1)): two transposing
+//   mn-major slice [k][E], chunk c of k row k stored at chunk c ^ (4 (k & 3) + 2 ((k / 8) & 1)): two transposing
 //            reads (ds_read_b64_tr_b16) per fragment, each of which turns a 4 (k) x 16 (m / n) patch per quarter
-//            wavefront into 4 consecutive k per lane; the eight 32-byte row segments that half a wavefront reads
-//            (k rows 8 g .. 8 g + 3 of two quarter wavefronts g) fall into eight different 32-byte columns.
+//            wavefront into 4 consecutive k per lane; the four 32-byte row segments of a quarter wavefront g (k rows
+//            8 g .. 8 g + 3) fall into the four 64-byte quarters of the 256 bytes, those of quarter wavefront g + 1
+//            into the other halves of the same quarters.  (With the four segments of a quarter wavefront in two
+//            64-byte quarters the counters show one conflict cycle in three.)
 // The matrix instructions are issued through inline assembly with the accumulator tied to the destination (the
 // compiler's own choice for this instruction copies accumulators between registers inside the loop).
 #pragma once
@@ -87,7 +89,7 @@ struct DirectTile16<E, MNCONTIG> {
     uint32_t voff[PER];
     uint32_t rd[T];
 
-    static __device__ __forceinline__ int swizzle(int krow) { return ((krow & 3) << 1) | (((krow >> 3) & 1) << 3); }
+    static __device__ __forceinline__ int swizzle(int krow) { return ((krow & 3) << 2) | (((krow >> 3) & 1) << 1); }
 
     __device__ __forceinline__ void init(int wave, int lane, int64_t ld, int wave_origin, uint32_t region)
     {
@@ -353,18 +355,168 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_
     store_tile16<BM, BN>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
 }
 
+// ---- the same kernel with the ring unrolled: for reductions of a whole number of 128-k steps (4 slices) and a ring of four.
+// A wavefront is alone on its SIMD, so every instruction it issues costs the SIMD one issue turn (4 cycles) and only
+// three fit behind a 16-cycle matrix instruction.  With the ring position a compile-time constant, every LDS read is a
+// per-lane base plus an immediate offset and every LDS target of a global -> LDS load a precomputed scalar (no address
+// arithmetic in the loop); the global pointers advance by one scalar addition per slice and operand, issued between matrix
+// instructions; no clamping per load: the last pass of the loop, which has nothing left to request, fetches the last
+// slice again.  At most two other instructions follow any matrix instruction.
+template <int BM, int BN, bool BF16, int ALAY, int BLAY>
+__global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16u_kernel(const FastArgs g)
+{
+    constexpr int TM = BM / 32, TN = BN / 32;
+    constexpr int kRing = 4;
+    static_assert(ring_of(BM, BN) == kRing, "ring of four");
+    using TileA = DirectTile16<BM, ALAY>;
+    using TileB = DirectTile16<BN, BLAY>;
+    constexpr uint32_t A_BYTES = TileA::BYTES, B_BYTES = TileB::BYTES, B_BASE = kRing * A_BYTES;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    int64_t bi, ti, tj;
+    locate_program(g.mt, g.nt, &bi, &ti, &tj);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = wave >> 1, wave_n = wave & 1;
+    const int64_t row0 = ti * BM, col0 = tj * BN;
+
+    const char *pa = reinterpret_cast<const char *>(g.A + bi * g.sa_batch + (ALAY == KCONTIG ? row0 * g.lda : row0));
+    const char *pb = reinterpret_cast<const char *>(g.B + bi * g.sb_batch + (BLAY == KCONTIG ? col0 * g.ldb : col0));
+    const int64_t a_step = (ALAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.lda) * 2;
+    const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.ldb) * 2;
+    const int64_t n_slices = g.kt * (kBK / kSliceK);       // a multiple of 4, at least 4 (checked by the host)
+
+    TileA ta;
+    TileB tb;
+    ta.init(wave, lane, g.lda, wave_m * (BM / 2), 0);
+    tb.init(wave, lane, g.ldb, wave_n * (BN / 2), B_BASE);
+
+    float4v acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
+
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    constexpr int NRA = TM * TileA::RPF, NRB = TN * TileB::RPF, NR = NRA + NRB;   // LDS reads per slice
+    constexpr int NM = TM * TN, ND = TileA::PER + TileB::PER;
+    static_assert(2 * NR <= NM * 3 / 2 && 8 * ND <= NM, "the trip's schedule: a read every other matrix instruction, a load every eighth");
+
+    // LDS targets of this wavefront's loads, per ring position: scalars
+    uint32_t tgt[kRing][ND];
+#pragma unroll
+    for (int r = 0; r < kRing; ++r)
+#pragma unroll
+        for (int d = 0; d < ND; ++d)
+            tgt[r][d] = d < TileA::PER ? lds0 + r * A_BYTES + (uint32_t)((wave * TileA::PER + d) * 1024)
+                                       : lds0 + B_BASE + r * B_BYTES + (uint32_t)((wave * TileB::PER + d - TileA::PER) * 1024);
+
+    u32x4 fa[2][TM], fb[2][TN];
+    auto lds_read = [&](int r, int set, uint32_t ring) {
+        if (r < TileA::RPF) ta.read(fa[set], smem, r, ring * A_BYTES);
+        else if (r < TileA::RPF + NRB) tb.read(fb[set], smem, r - TileA::RPF, ring * B_BYTES);
+        else ta.read(fa[set], smem, r - NRB, ring * A_BYTES);
+    };
+    // load d of the slice at (pa, pb) into ring position `ring`, in two halves that go behind different matrix
+    // instructions (the matrix instruction between them is the wait state the hardware wants after a write to m0)
+    auto dma_aim = [&](int d, int ring) { asm volatile("s_mov_b32 m0, %0" : : "s"(tgt[ring][d]) : "memory"); };
+    auto dma_go = [&](int d) {
+        if (d < TileA::PER) asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(ta.voff[d]), "s"(pa) : "memory");
+        else asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(tb.voff[d - TileA::PER]), "s"(pb) : "memory");
+    };
+
+    // One trip = one slice: the matrix instructions on fragment set SET (slice s); behind them the LDS reads of slice
+    // s+1 (ring position RING+1) into the other set and, if DMA, the loads of slice s+4 into ring position RING.
+    auto trip = [&](auto ring_c, auto set_c, int64_t a_adv, int64_t b_adv) {
+        constexpr int RING = decltype(ring_c)::value, SET = decltype(set_c)::value;
+        constexpr int NXT = (RING + 1) % kRing;
+#pragma unroll
+        for (int idx = 0; idx < NM; ++idx) {
+            const int tm = idx / TN, tn = idx % TN;
+            mfma16<BF16>(acc[tm][tn], fb[SET][tn], fa[SET][tm]);      // transposed block (see store_tile16_rows)
+            if (idx % 2 == 0 && idx / 2 < NR) lds_read(idx / 2, SET ^ 1, NXT);
+            if (idx % 8 == 1 && idx / 8 < ND) dma_aim(idx / 8, RING);
+            if (idx % 8 == 3 && idx / 8 < ND) {
+                dma_go(idx / 8);
+                // the operand's last load of this trip is out: its pointer moves on to the next slice
+                if (idx / 8 == TileA::PER - 1) { pa += a_adv; asm volatile("" : "+s"(pa)); }
+                if (idx / 8 == ND - 1) { pb += b_adv; asm volatile("" : "+s"(pb)); }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    using std::integral_constant;
+
+    // prologue: slices 0 .. 3 requested; wait for slice 0; its fragments into set 0
+#pragma unroll
+    for (int s = 0; s < kRing; ++s) {
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+            dma_aim(d, s);
+            asm volatile("s_nop 0");
+            dma_go(d);
+        }
+        pa += a_step;
+        pb += b_step;
+    }
+    asm volatile("" : "+s"(pa), "+s"(pb));
+    NT_WAIT_VMCNT((kRing - 1) * ND);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < NR; ++r) lds_read(r, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // Slice s sits at ring position s % 4.  At the top of trip s this wavefront's part of slice s+1 must have landed
+    // (the loads of the two younger slices may still be in flight); the barrier then says that slice s+1 is complete
+    // and that every wavefront holds its fragments of slice s in registers, so that slice s+4 can overwrite it.
+    // One pass of the loop = four trips.  The last pass has nothing left to request: its loads fetch the last slice
+    // again (the pointers are set back to it and stand still) into ring positions that nobody reads any more, so that
+    // the loop has one shape, one wait count, and no second copy of its body.
+    const char *pa_last = pa - a_step, *pb_last = pb - b_step;         // (after the prologue's four steps: slice 3)
+    pa_last += (n_slices - kRing) * a_step;
+    pb_last += (n_slices - kRing) * b_step;
+    int64_t a_adv = a_step, b_adv = b_step;
+    for (int64_t sl = 0; sl < n_slices; sl += kRing) {
+        if (sl + kRing >= n_slices) { pa = pa_last; pb = pb_last; a_adv = 0; b_adv = 0; }     // wavefront-uniform
+        asm volatile("" : "+s"(pa), "+s"(pb), "+s"(a_adv), "+s"(b_adv));
+        NT_WAIT_VMCNT(2 * ND); __syncthreads(); trip(integral_constant<int, 0>{}, integral_constant<int, 0>{}, a_adv, b_adv);
+        NT_WAIT_VMCNT(2 * ND); __syncthreads(); trip(integral_constant<int, 1>{}, integral_constant<int, 1>{}, a_adv, b_adv);
+        NT_WAIT_VMCNT(2 * ND); __syncthreads(); trip(integral_constant<int, 2>{}, integral_constant<int, 0>{}, a_adv, b_adv);
+        NT_WAIT_VMCNT(2 * ND); __syncthreads(); trip(integral_constant<int, 3>{}, integral_constant<int, 1>{}, a_adv, b_adv);
+        // (wait states between the last matrix instruction and anything the compiler may do to an accumulator at the
+        // loop's end: it does not know that the inline assembly is a matrix instruction)
+        asm volatile("s_nop 7" ::: "memory");
+    }
+    NT_WAIT_VMCNT(0);                                      // drain the surplus loads ...
+    __syncthreads();                                       // ... of every wavefront: the epilogue reuses the LDS
+    // The accumulators are read by ordinary instructions from here on: 16 more wait states here, and the epilogue takes
+    // every accumulator block through an assembly statement of its own before it reads it (statements of this kind stay
+    // in program order, so every read follows the wait states).
+    asm volatile("s_nop 15" ::: "memory");
+
+    store_tile16<BM, BN>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
+}
+
 template <int BM, int BN, bool BF16, int ALAY, int BLAY>
 static nt_status launch_direct16_inst(const FastArgs &a, int64_t nwg, hipStream_t s)
 {
     constexpr size_t smem = (size_t)ring_of(BM, BN) * (BM + BN) * kSliceK * sizeof(uint16_t);
+    // (a ring of four and a reduction of whole 128-k steps: the kernel with the unrolled ring)
+    const bool unrolled = ring_of(BM, BN) == 4 && a.kt % 2 == 0 && a.kt >= 2;
     auto kern = gemm_direct16_kernel<BM, BN, BF16, ALAY, BLAY>;
+    auto kern_u = gemm_direct16u_kernel<BM, BN, BF16, ALAY, BLAY>;
     static DeviceOnce configured;
     if (!configured.done()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern_u), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
         configured.set();
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
+    static const bool no_unroll = getenv("NT_DIRECT16_V1") != nullptr;      // TEMPORARY switch for A/B timing
+    if (unrolled && !no_unroll) hipLaunchKernelGGL(kern_u, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
+    else hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
     return check_launch("gemm_direct16_kernel");
 }
 
