@@ -16,9 +16,8 @@
 //
 // Fragment layouts.  Lane l of a wavefront supplies row (or column) l % 16 of its fragment and the 8 consecutive
 // k 8 (l / 16) .. + 7.
-//   k-major slice  [row][32 k], 64 bytes per row, 16-byte chunk c of row r stored at chunk c ^ ((r / 4) & 3) (as in
-//            gemm_direct_kernel): one ds_read_b128 per fragment; the 16 lanes of a quarter wavefront read 16
-//            consecutive rows, same k chunk: 16 different 16-byte columns of the 256 bytes the LDS serves per cycle.
+//   k-major slice  [row][32 k], 64 bytes per row, 16-byte chunk c of row r stored at chunk c ^ ((-(r / 4)) & 3): one
+//            ds_read_b128 per fragment, conflict free (see DirectTile16<E, KCONTIG>::swizzle).
 //   mn-major slice [k][E], chunk c of k row k stored at chunk c ^ (4 (k & 3) + 2 ((k / 8) & 1)): two transposing
 //            reads (ds_read_b64_tr_b16) per fragment, each of which turns a 4 (k) x 16 (m / n) patch per quarter
 //            wavefront into 4 consecutive k per lane; the four 32-byte row segments of a quarter wavefront g (k rows
@@ -54,16 +53,24 @@ struct DirectTile16<E, KCONTIG> {
     uint32_t voff[PER];                                    // global byte offset of this lane's chunk
     uint32_t rd;                                           // LDS read base of this lane
 
+    // Chunk c of row r is stored at chunk c ^ swizzle(r).  A ds_read_b128 is served in four cycles, 16 lanes each, and the
+    // 16 lanes are not consecutive ones: within either half of the wavefront the eight groups of four lanes are split by
+    // the parity of their group number's bits (groups 0, 3, 5, 6 and groups 1, 2, 4, 7; found with a one-wavefront probe
+    // and the bank-conflict counter).  In a fragment read, lane group q holds rows 4 (q % 4) .. + 3 and k chunk q / 4: a
+    // cycle sees row groups {0, 3} with one chunk and {1, 2} with the next, so the four must land in four different
+    // 16-byte columns: swizzle = (-(r / 4)) % 4.
+    static __device__ __forceinline__ int swizzle(int row) { return (4 - ((row >> 2) & 3)) & 3; }
+
     __device__ __forceinline__ void init(int wave, int lane, int64_t ld, int wave_origin, uint32_t region)
     {
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
             const int row = (wave * PER + j) * 16 + (lane >> 2);
-            const int c = (lane & 3) ^ ((row >> 2) & 3);
+            const int c = (lane & 3) ^ swizzle(row);
             voff[j] = ((uint32_t)row * (uint32_t)ld + (uint32_t)(c * 8)) * 2u;
         }
         const int r = wave_origin + (lane & 15);           // (wave_origin is a multiple of 16: fragment t is rows r + 16 t, same swizzle bits)
-        rd = (uint32_t)(r * 64 + (((lane >> 4) ^ ((r >> 2) & 3)) << 4)) + region;
+        rd = (uint32_t)(r * 64 + (((lane >> 4) ^ swizzle(r)) << 4)) + region;
     }
     __device__ __forceinline__ void issue_one(int j, const char *g, uint32_t lds_slice, int wave) const
     {
@@ -514,8 +521,7 @@ static nt_status launch_direct16_inst(const FastArgs &a, int64_t nwg, hipStream_
         if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
         configured.set();
     }
-    static const bool no_unroll = getenv("NT_DIRECT16_V1") != nullptr;      // TEMPORARY switch for A/B timing
-    if (unrolled && !no_unroll) hipLaunchKernelGGL(kern_u, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
+    if (unrolled) hipLaunchKernelGGL(kern_u, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
     else hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
     return check_launch("gemm_direct16_kernel");
 }

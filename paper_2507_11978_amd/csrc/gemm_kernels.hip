@@ -640,8 +640,7 @@ static nt_status route_matrix(const GemmLaunch &g, FastArgs a, int alay, int bla
         if (e.bm != t.bm || e.bn != t.bn) continue;
         Launcher launch = (direct ? (plain_direct ? e.direct : e.edge) : e.staged)[bf16 ? 1 : 0];
         // full aligned 256 x 256 tiles: the kernel on 16 x 16 x 32 matrix instructions (fewer accumulator bits moved per flop)
-        static const bool mfma32_only = getenv("NT_DIRECT_MFMA32") != nullptr;      // TEMPORARY switch for A/B timing
-        if (plain_direct && t.bm == 256 && t.bn == 256 && !mfma32_only) launch = bf16 ? launch_direct16_256x256_bf16 : launch_direct16_256x256_f16;
+        if (plain_direct && t.bm == 256 && t.bn == 256) launch = bf16 ? launch_direct16_256x256_bf16 : launch_direct16_256x256_f16;
         // k split: `ksplit` equal parts of K as the entries of a batched product into fp32 slices of the workspace
         const int ksplit = g.batch == 1 && !ragged_k ? gemm_ksplit(g.mt * g.nt, g.kt, g.M, g.N) : 1;
         WorkspaceLease lease;
