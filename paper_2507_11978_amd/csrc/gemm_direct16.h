@@ -76,6 +76,31 @@ struct DirectTile16<E, KCONTIG> {
     {
         dma16(g, voff[j], lds_slice + (uint32_t)((wave * PER + j) * 1024));
     }
+    __device__ __forceinline__ void issue_one_buf(int j, u32x4 rsrc, uint32_t soff, uint32_t lds_slice, int wave) const
+    {
+        dma16_buf(rsrc, voff[j], soff, lds_slice + (uint32_t)((wave * PER + j) * 1024));
+    }
+    // where element (row r, k kk) of a slice lies in it (byte offset), and which wavefront's load brings it in
+    static __device__ __forceinline__ uint32_t place(int r, int kk)
+    {
+        return (uint32_t)((r >> 4) * 1024 + (((r & 15) << 2) + ((kk >> 3) ^ swizzle(r))) * 16 + (kk & 7) * 2);
+    }
+    static __device__ __forceinline__ int owner(int r, int) { return (r >> 4) / PER; }
+    // Ragged K: the slice that has just landed at byte offset slot_off holds only `keep` valid k (< 32); what this
+    // lane fetched past them -- the beginning of the operand's next row -- is overwritten with zeros.
+    __device__ __forceinline__ void zero_tail(char *smem, uint32_t slot_off, int wave, int lane, int keep) const
+    {
+        const int left = keep - 8 * ((lane & 3) ^ swizzle(lane >> 2));     // valid k in this lane's chunks (the same chunk column for all of them)
+        if (left >= 8) return;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const uint32_t at = slot_off + (uint32_t)((wave * PER + j) * 1024 + lane * 16);
+            u32x4 v = lds_read16(smem, at);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) v[w] &= left > 2 * w + 1 ? 0xffffffffu : (left > 2 * w ? 0x0000ffffu : 0u);
+            lds_write16(smem, at, v);
+        }
+    }
     // read q of the slice at byte offset slice_off: fragment q, whole
     __device__ __forceinline__ void read(u32x4 (&f)[T], const char *smem, int q, uint32_t slice_off) const
     {
@@ -121,6 +146,18 @@ struct DirectTile16<E, MNCONTIG> {
     {
         dma16(g, voff[j], lds_slice + (uint32_t)((wave * PER + j) * 1024));
     }
+    __device__ __forceinline__ void issue_one_buf(int j, u32x4 rsrc, uint32_t soff, uint32_t lds_slice, int wave) const
+    {
+        dma16_buf(rsrc, voff[j], soff, lds_slice + (uint32_t)((wave * PER + j) * 1024));
+    }
+    // where element (column r along m / n, k row kk) of a slice lies in it, and which wavefront's load brings it in
+    static __device__ __forceinline__ uint32_t place(int r, int kk)
+    {
+        return (uint32_t)((kk / RPI) * 1024 + ((kk % RPI) * CPR + ((r >> 3) ^ swizzle(kk))) * 16 + (r & 7) * 2);
+    }
+    static __device__ __forceinline__ int owner(int, int kk) { return (kk / RPI) / PER; }
+    // (ragged K: the k rows past K lie past the operand's end and arrive as zeros by themselves)
+    __device__ __forceinline__ void zero_tail(char *, uint32_t, int, int, int) const {}
     // read q of the slice: half q % 2 (k 0..3 or 4..7 of the lane's run) of fragment q / 2
     __device__ __forceinline__ void read(u32x4 (&f)[T], const char *smem, int q, uint32_t slice_off) const
     {
@@ -141,10 +178,11 @@ struct DirectTile16<E, MNCONTIG> {
 //                (16 rows, same chunk: 16 different chunks);
 //   read phase   16 consecutive lanes read one row; a store instruction covers 4 rows of 256 contiguous bytes.
 // An fp32 tile takes two passes (one per half of the columns) through the same region.
-template <int BM, int BN, int OUT>
+// CHECK masks rows >= M and columns >= N (a partly valid 16-byte chunk is stored element-wise; D is read element-wise there).
+template <int BM, int BN, int OUT, bool CHECK>
 __device__ __forceinline__ void store_tile16_rows(char *smem, int wave, char *C, int64_t scm, const float4v (&acc)[BM / 32][BN / 32],
-                                                  int64_t row_w, int64_t col_w, int lane, bool affine, const char *D, int64_t sdm,
-                                                  float alpha, float beta, int act)
+                                                  int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N, bool affine, const char *D,
+                                                  int64_t sdm, float alpha, float beta, int act)
 {
     constexpr int TM = BM / 32, WM = BM / 2, WN = BN / 2;
     constexpr int ES = OUT == NT_F32 ? 4 : 2;
@@ -179,7 +217,13 @@ __device__ __forceinline__ void store_tile16_rows(char *smem, int wave, char *C,
                 for (int v = 0; v < 4; ++v) o[v] = blk[v];
                 if (affine) {                                         // wavefront-uniform
                     float d[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (D) {
+                    const int64_t nv = CHECK ? N - (col_w + tn * 16 + 4 * g) : 4;      // valid columns from the lane's first
+                    if (D && CHECK && (row >= M || nv < 4)) {
+                        if (row < M)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                if (v < nv) d[v] = load_as_f32(D, row * sdm + col_w + tn * 16 + 4 * g + v, OUT);
+                    } else if (D) {
                         const char *dp = D + (row * sdm + col_w + tn * 16 + 4 * g) * ES;
                         if constexpr (OUT == NT_F32) {
                             u32x4 w;
@@ -226,28 +270,53 @@ __device__ __forceinline__ void store_tile16_rows(char *smem, int wave, char *C,
         for (int it = 0; it < WM / RPI; ++it) {
             const int r = it * RPI + lane / CPR, c = lane % CPR;
             const u32x4 v = lds_read16(reg, (uint32_t)(r * RB + ((c ^ ((r >> RSH) & (CPR - 1))) << 4)));
-            char *p = C + ((row_w + r) * scm + col_w + pass * PW + c * EPC) * ES;
-            __builtin_memcpy(p, &v, 16);
+            const int64_t row = row_w + r, col = col_w + pass * PW + c * EPC;
+            char *p = C + (row * scm + col) * ES;
+            if (!CHECK || (row < M && col + EPC <= N)) {
+                __builtin_memcpy(p, &v, 16);
+            } else if (row < M && col < N) {
+                const int nv = (int)(N - col);
+#pragma unroll
+                for (int e = 0; e < EPC; ++e)
+                    if (e < nv) {
+                        const uint32_t w = v[ES == 4 ? e : e / 2];
+                        if constexpr (OUT == NT_F32) *reinterpret_cast<uint32_t *>(p + 4 * e) = w;
+                        else *reinterpret_cast<uint16_t *>(p + 2 * e) = (uint16_t)((e & 1) ? w >> 16 : w & 0xffffu);
+                    }
+            }
         }
     }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool EDGE = false>
 __device__ __forceinline__ void store_tile16(const FastArgs &g, char *smem, int wave, int64_t bi, const float4v (&acc)[BM / 32][BN / 32],
-                                             int64_t row_w, int64_t col_w, int lane)
+                                             int64_t row_w, int64_t col_w, int lane, bool ragged = false)
 {
     const int64_t esz = g.out_dtype == NT_F32 ? 4 : 2;
     char *C = reinterpret_cast<char *>(g.C) + bi * g.sc_batch * esz;
     const char *D = g.D ? reinterpret_cast<const char *>(g.D) + bi * g.sd_batch * esz : nullptr;
     const bool affine = D != nullptr || g.alpha != 1.f || g.act != 0;
-#define NT_ROWS16(OUT) store_tile16_rows<BM, BN, OUT>(smem, wave, C, g.scm, acc, row_w, col_w, lane, affine, D, g.sdm, g.alpha, g.beta, g.act)
-    if (g.out_dtype == NT_F32) NT_ROWS16(NT_F32);
-    else if (g.out_dtype == NT_F16) NT_ROWS16(NT_F16);
-    else NT_ROWS16(NT_BF16);
+#define NT_ROWS16(OUT, CHECK) store_tile16_rows<BM, BN, OUT, CHECK>(smem, wave, C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta, g.act)
+    if constexpr (EDGE) {
+        if (ragged) {
+            if (g.out_dtype == NT_F32) NT_ROWS16(NT_F32, true);
+            else if (g.out_dtype == NT_F16) NT_ROWS16(NT_F16, true);
+            else NT_ROWS16(NT_BF16, true);
+            return;
+        }
+    }
+    if (g.out_dtype == NT_F32) NT_ROWS16(NT_F32, false);
+    else if (g.out_dtype == NT_F16) NT_ROWS16(NT_F16, false);
+    else NT_ROWS16(NT_BF16, false);
 #undef NT_ROWS16
 }
 
-template <int BM, int BN, bool BF16, int ALAY, int BLAY>
+// EDGE = false: every tile is full, every load 16-byte aligned, K a whole number of 64-k tiles.  EDGE = true: tiles may
+// overhang M or N, K need not be a whole number of slices, rows need only the element's own 2-byte alignment: the operand
+// loads are range checked (what lies past an operand's end reads as zero, what an overhanging tile reads inside it only
+// reaches outputs that are never stored, except the k past K of a k-contiguous operand, which are zeroed in LDS) and the
+// stores are masked (see gemm_direct_kernel, whose rules these are).
+template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE>
 __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_kernel(const FastArgs g)
 {
     constexpr int TM = BM / 32, TN = BN / 32;
@@ -268,7 +337,8 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_
     const char *gB = reinterpret_cast<const char *>(g.B + bi * g.sb_batch + (BLAY == KCONTIG ? col0 * g.ldb : col0));
     const int64_t a_step = (ALAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.lda) * 2;
     const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.ldb) * 2;
-    const int64_t n_slices = g.kt * (kBK / kSliceK);       // even
+    // (EDGE: K need not be a whole number of slices; the tail of the last one is zeroed in LDS, see zero_tail)
+    const int64_t n_slices = EDGE ? (g.K + kSliceK - 1) / kSliceK : g.kt * (kBK / kSliceK);
 
     TileA ta;
     TileB tb;
@@ -296,9 +366,19 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_
         else ta.read(fa[set], smem, r - NRB, ring * A_BYTES);
     };
     constexpr int NM = TM * TN, ND = TileA::PER + TileB::PER;
+    u32x4 rsrc_a{0, 0, 0, 0}, rsrc_b{0, 0, 0, 0};
+    if constexpr (EDGE) {
+        rsrc_a = make_rsrc(gA, g.a_extent - (gA - reinterpret_cast<const char *>(g.A + bi * g.sa_batch)));
+        rsrc_b = make_rsrc(gB, g.b_extent - (gB - reinterpret_cast<const char *>(g.B + bi * g.sb_batch)));
+    }
     auto dma = [&](int d, const char *pa, const char *pb, uint32_t ring) {
-        if (d < TileA::PER) ta.issue_one(d, pa, lds0 + ring * A_BYTES, wave);
-        else tb.issue_one(d - TileA::PER, pb, lds0 + B_BASE + ring * B_BYTES, wave);
+        if constexpr (!EDGE) {
+            if (d < TileA::PER) ta.issue_one(d, pa, lds0 + ring * A_BYTES, wave);
+            else tb.issue_one(d - TileA::PER, pb, lds0 + B_BASE + ring * B_BYTES, wave);
+        } else {
+            if (d < TileA::PER) ta.issue_one_buf(d, rsrc_a, (uint32_t)(pa - gA), lds0 + ring * A_BYTES, wave);
+            else tb.issue_one_buf(d - TileA::PER, rsrc_b, (uint32_t)(pb - gB), lds0 + B_BASE + ring * B_BYTES, wave);
+        }
     };
     // One trip: the TM x TN matrix instructions on fragment set `set`; between them, spread evenly so that neither
     // the LDS queue nor the memory queue holds the in-order wavefront back while the matrix pipe runs dry, the LDS
@@ -320,8 +400,42 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_
     };
 
     const int64_t last = n_slices - 1;
-    auto slice_a = [&](int64_t s) { return gA + (s < last ? s : last) * a_step; };   // clamped: surplus slices are never multiplied
-    auto slice_b = [&](int64_t s) { return gB + (s < last ? s : last) * b_step; };
+    // The range check of a buffer load works on the load's 4-byte words: with an odd pitch or extent the word that holds an
+    // operand's very last element can end 2 bytes past the operand, and then arrives as zero.  The wavefront whose load
+    // brings that word in fetches the element by itself (a 2-byte load inside the operand) and puts it in its place once
+    // the last slice has landed (g.patch: bit 0 = A, bit 1 = B; set by the host for such operands only).
+    int patch_a = -1, patch_b = -1;
+    if constexpr (EDGE) {
+        const int kk = (int)(g.K - 1 - last * kSliceK);
+        const int64_t ra = g.M - 1 - row0, rb = g.N - 1 - col0;
+        if ((g.patch & 1) && ra < BM && TileA::owner((int)ra, kk) == wave) patch_a = (int)TileA::place((int)ra, kk);
+        if ((g.patch & 2) && rb < BN && TileB::owner((int)rb, kk) == wave) patch_b = (int)TileB::place((int)rb, kk);
+    }
+    // what has to happen to slice `s`, which has just landed at ring position `pos` (this wavefront's part), before the
+    // barrier that publishes it: only the last slice of a ragged or odd-sized problem needs anything
+    auto settle = [&](int64_t s, uint32_t pos) {
+        if constexpr (EDGE) {
+            if (s != last) return;
+            if ((s + 1) * kSliceK > g.K) {
+                const int keep = (int)(g.K - s * kSliceK);
+                ta.zero_tail(smem, pos * A_BYTES, wave, lane, keep);
+                tb.zero_tail(smem, B_BASE + pos * B_BYTES, wave, lane, keep);
+            }
+            if (g.patch && lane == 0) {
+                if (patch_a >= 0)
+                    *reinterpret_cast<uint16_t *>(smem + pos * A_BYTES + patch_a) =
+                        *reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(g.A + bi * g.sa_batch) + g.a_extent - 2);
+                if (patch_b >= 0)
+                    *reinterpret_cast<uint16_t *>(smem + B_BASE + pos * B_BYTES + patch_b) =
+                        *reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(g.B + bi * g.sb_batch) + g.b_extent - 2);
+            }
+        }
+    };
+    // Slices past the last one are requested all the same (the loop has one shape).  Full tiles: the last slice again, never
+    // multiplied.  EDGE: an offset beyond any buffer (2^31; the lanes' own offsets stay below 2^31), so that zeros arrive:
+    // an odd number of slices is rounded up to whole passes of the loop below by one trip that multiplies zeros.
+    auto slice_a = [&](int64_t s) { return gA + (s <= last ? s * a_step : (EDGE ? (int64_t)0x80000000LL : last * a_step)); };
+    auto slice_b = [&](int64_t s) { return gB + (s <= last ? s * b_step : (EDGE ? (int64_t)0x80000000LL : last * b_step)); };
 
     // prologue: slices 0 .. kRing-1 requested; wait for slice 0; its fragments into set 0
 #pragma unroll
@@ -329,24 +443,27 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_
 #pragma unroll
         for (int d = 0; d < ND; ++d) dma(d, slice_a(s), slice_b(s), s);
     NT_WAIT_VMCNT((kRing - 1) * ND);
+    settle(0, 0);
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < NR; ++r) lds_read(r, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
 
     // Slice s sits at ring position s % kRing.  At the top of trip s this wavefront's part of slice s+1 must have
-    // landed (the loads of the two younger slices may still be in flight); the barrier then says that slice s+1 is
+    // landed (the loads of the younger slices may still be in flight); the barrier then says that slice s+1 is
     // complete and that every wavefront holds its fragments of slice s in registers, so the position of slice s can
-    // be overwritten by slice s+kRing.
+    // be overwritten by slice s+kRing.  Two trips per pass (the fragment sets alternate).
     uint32_t ring = 0;
     for (int64_t sl = 0; sl < n_slices; sl += 2) {
         uint32_t nxt = ring + 1 == kRing ? 0 : ring + 1;
         NT_WAIT_VMCNT((kRing - 2) * ND);
+        settle(sl + 1, nxt);
         __syncthreads();
         trip(0, nxt, slice_a(sl + kRing), slice_b(sl + kRing), ring);
         ring = nxt;
         nxt = ring + 1 == kRing ? 0 : ring + 1;
         NT_WAIT_VMCNT((kRing - 2) * ND);
+        settle(sl + 2, nxt);
         __syncthreads();
         trip(1, nxt, slice_a(sl + 1 + kRing), slice_b(sl + 1 + kRing), ring);
         ring = nxt;
@@ -359,7 +476,8 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_
     // it (statements of this kind stay in program order, so every read follows the wait states).
     asm volatile("s_nop 15" ::: "memory");
 
-    store_tile16<BM, BN>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
+    store_tile16<BM, BN, EDGE>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane,
+                               EDGE && (g.M - row0 < BM || g.N - col0 < BN));
 }
 
 // ---- the same kernel with the ring unrolled: for reductions of a whole number of 128-k steps (4 slices) and a ring of four.
@@ -506,38 +624,48 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16u
     store_tile16<BM, BN>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
 }
 
-template <int BM, int BN, bool BF16, int ALAY, int BLAY>
+template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE = false>
 static nt_status launch_direct16_inst(const FastArgs &a, int64_t nwg, hipStream_t s)
 {
     constexpr size_t smem = (size_t)ring_of(BM, BN) * (BM + BN) * kSliceK * sizeof(uint16_t);
-    // (a ring of four and a reduction of whole 128-k steps: the kernel with the unrolled ring)
-    const bool unrolled = ring_of(BM, BN) == 4 && a.kt % 2 == 0 && a.kt >= 2;
-    auto kern = gemm_direct16_kernel<BM, BN, BF16, ALAY, BLAY>;
-    auto kern_u = gemm_direct16u_kernel<BM, BN, BF16, ALAY, BLAY>;
+    auto kern = gemm_direct16_kernel<BM, BN, BF16, ALAY, BLAY, EDGE>;
     static DeviceOnce configured;
     if (!configured.done()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern_u), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if constexpr (BM == 256 && BN == 256 && !EDGE)
+            if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_direct16u_kernel<BM, BN, BF16, ALAY, BLAY>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
         configured.set();
     }
-    if (unrolled) hipLaunchKernelGGL(kern_u, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
-    else hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
+    // (the 256 x 256 tile -- one workgroup per compute unit, every issue turn counts -- with a reduction of whole 128-k steps:
+    // the kernel with the unrolled ring)
+    if constexpr (BM == 256 && BN == 256 && !EDGE) {
+        if (a.kt % 2 == 0 && a.kt >= 2) {
+            hipLaunchKernelGGL((gemm_direct16u_kernel<BM, BN, BF16, ALAY, BLAY>), dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
+            return check_launch("gemm_direct16u_kernel");
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
     return check_launch("gemm_direct16_kernel");
 }
 
-template <int BM, int BN, bool BF16>
+template <int BM, int BN, bool BF16, bool EDGE = false>
 static nt_status launch_direct16_t(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s)
 {
-    if (alay == KCONTIG && blay == MNCONTIG) return launch_direct16_inst<BM, BN, BF16, KCONTIG, MNCONTIG>(a, nwg, s);
-    if (alay == KCONTIG && blay == KCONTIG) return launch_direct16_inst<BM, BN, BF16, KCONTIG, KCONTIG>(a, nwg, s);
-    if (alay == MNCONTIG && blay == MNCONTIG) return launch_direct16_inst<BM, BN, BF16, MNCONTIG, MNCONTIG>(a, nwg, s);
-    return launch_direct16_inst<BM, BN, BF16, MNCONTIG, KCONTIG>(a, nwg, s);
+    if (alay == KCONTIG && blay == MNCONTIG) return launch_direct16_inst<BM, BN, BF16, KCONTIG, MNCONTIG, EDGE>(a, nwg, s);
+    if (alay == KCONTIG && blay == KCONTIG) return launch_direct16_inst<BM, BN, BF16, KCONTIG, KCONTIG, EDGE>(a, nwg, s);
+    if (alay == MNCONTIG && blay == MNCONTIG) return launch_direct16_inst<BM, BN, BF16, MNCONTIG, MNCONTIG, EDGE>(a, nwg, s);
+    return launch_direct16_inst<BM, BN, BF16, MNCONTIG, KCONTIG, EDGE>(a, nwg, s);
 }
 
 #define NT_DIRECT16_DECL(T) \
     nt_status launch_direct16_##T##_f16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s); \
-    nt_status launch_direct16_##T##_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s);
+    nt_status launch_direct16_##T##_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s); \
+    nt_status launch_direct16_edge_##T##_f16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s); \
+    nt_status launch_direct16_edge_##T##_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s);
+NT_DIRECT16_DECL(128x128)
+NT_DIRECT16_DECL(256x128)
+NT_DIRECT16_DECL(128x256)
 NT_DIRECT16_DECL(256x256)
 #undef NT_DIRECT16_DECL
 

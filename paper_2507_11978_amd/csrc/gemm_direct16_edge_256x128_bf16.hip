@@ -1,0 +1,9 @@
+// Instantiations of the range-checked flavour of the direct-to-LDS kernel on 16 x 16 x 32 matrix instructions, 256 x 128 x 64 tile, bf16 inputs.
+#include "gemm_direct16.h"
+
+namespace nt {
+nt_status launch_direct16_edge_256x128_bf16(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s)
+{
+    return launch_direct16_t<256, 128, true, true>(a, alay, blay, nwg, s);
+}
+}  // namespace nt

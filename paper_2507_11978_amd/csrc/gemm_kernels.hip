@@ -631,16 +631,16 @@ static nt_status route_matrix(const GemmLaunch &g, FastArgs a, int alay, int bla
         a.patch = (words_aligned(a.lda, a.sa_batch, a.a_extent) ? 0 : 1) | (words_aligned(a.ldb, a.sb_batch, a.b_extent) ? 0 : 2);
     if (path_out) *path_out = direct ? PATH_DIRECT : PATH_FAST;
     typedef nt_status (*Launcher)(const FastArgs &, int, int, int64_t, hipStream_t);
-    struct Entry { int bm, bn; Launcher direct[2], edge[2], staged[2]; };      // [f16, bf16]
-#define NT_ENTRY(BM, BN, T) {BM, BN, {launch_direct_##T##_f16, launch_direct_##T##_bf16}, {launch_direct_edge_##T##_f16, launch_direct_edge_##T##_bf16}, \
+    // [f16, bf16]; direct: full aligned tiles (the kernel on 16 x 16 x 32 matrix instructions: fewer accumulator bits moved per
+    // flop, which on this power-managed part is clock), edge: the range-checked flavour, staged: through registers
+    struct Entry { int bm, bn; Launcher direct[2], edge[2], staged[2]; };
+#define NT_ENTRY(BM, BN, T) {BM, BN, {launch_direct16_##T##_f16, launch_direct16_##T##_bf16}, {launch_direct16_edge_##T##_f16, launch_direct16_edge_##T##_bf16}, \
                              {launch_fast_##T##_f16, launch_fast_##T##_bf16}}
     static const Entry table[] = {NT_ENTRY(128, 128, 128x128), NT_ENTRY(256, 128, 256x128), NT_ENTRY(128, 256, 128x256), NT_ENTRY(256, 256, 256x256)};
 #undef NT_ENTRY
     for (const Entry &e : table) {
         if (e.bm != t.bm || e.bn != t.bn) continue;
-        Launcher launch = (direct ? (plain_direct ? e.direct : e.edge) : e.staged)[bf16 ? 1 : 0];
-        // full aligned 256 x 256 tiles: the kernel on 16 x 16 x 32 matrix instructions (fewer accumulator bits moved per flop)
-        if (plain_direct && t.bm == 256 && t.bn == 256) launch = bf16 ? launch_direct16_256x256_bf16 : launch_direct16_256x256_f16;
+        const Launcher launch = (direct ? (plain_direct ? e.direct : e.edge) : e.staged)[bf16 ? 1 : 0];
         // k split: `ksplit` equal parts of K as the entries of a batched product into fp32 slices of the workspace
         const int ksplit = g.batch == 1 && !ragged_k ? gemm_ksplit(g.mt * g.nt, g.kt, g.M, g.N) : 1;
         WorkspaceLease lease;
