@@ -2,7 +2,8 @@
 //
 // Same problem class as gemm_conv.h (contiguous NCHW input, unit conv stride, k-contiguous filter, output dense
 // in (p, q)), same numbering of the output positions (row pitch rounded up to a multiple of 8), with the pipeline
-// of the direct GEMM kernel: 32-k slices in a ring of three or four LDS slots, no staging registers.
+// of the direct GEMM kernel on 16 x 16 x 32 matrix instructions (gemm_direct16.h): 32-k slices in a ring of three or four
+// LDS slots, no staging registers, one trip of the loop per slice.
 //
 // The unfolded input A[m, kk] = x[n, c, p + r - pad_h, q + s - pad_w] is contiguous along m, so its slice is the
 // mn-major LDS layout [32 kk][256 m] read with transposing LDS reads.  One 16-byte chunk is a run of 8 consecutive
@@ -20,7 +21,7 @@
 // R, S <= 8, byte offsets inside x below 2^31.
 #pragma once
 #include "gemm_conv.h"
-#include "gemm_direct.h"
+#include "gemm_direct16.h"
 
 namespace nt {
 
@@ -31,12 +32,13 @@ struct ConvTileA {
     static constexpr int PER = BYTES / 1024 / 4;           // load instructions per wavefront and slice (4)
     static constexpr int RPF = 2;
     static constexpr int RB = 2 * E;                       // bytes per kk row
-    static constexpr int T = E / 64;
+    static constexpr int T = E / 32;                       // 16-position fragments per wavefront
     static constexpr uint32_t kOutside = 0x80000000u;      // byte offset past every buffer this kernel accepts
     enum { CLEAR_FIRST = 1, CLEAR_LAST = 2, MOVE_UP = 4, DOWN_SHIFT = 3 /* bits 3..6: elements to move down by (0..8) */ };
 
     uint32_t rd[T];
-    // Load j of a slice covers kk row 8 * wave + 2 * j + lane / 32 and, because of the bank swizzle (chunk ^= (kk & 3) * 4),
+    // Load j of a slice covers kk row 8 * wave + 2 * j + lane / 32 and, because of the bank swizzle (that of
+    // DirectTile16<E, MNCONTIG>: chunk ^= 4 (kk & 3) + 2 ((kk / 8) & 1), the second term being the wavefront's parity),
     // one of two runs of 8 positions: run j % 2.
     int32_t base[2];               // element offset of x[n, 0, p - ph, q0 - pw] of the run
     uint32_t masks[2];             // bits 0..7: input row p + r - ph inside the image (and m < M); bit 8 + 2 s: with tap s the
@@ -48,7 +50,7 @@ struct ConvTileA {
     uint32_t tap[PER];
 
     // Table of the R * S filter taps in LDS (at byte offset `table`): r * W + s | (1 << r) << 16 | (8 + 2 s) << 24
-    static constexpr uint32_t kTableBytes = 64 * 4;
+    static constexpr uint32_t kTableBytes = 64 * 4 + 64 * 4;      // the table, and a spare word per lane (see settle)
     static __device__ __forceinline__ void fill_table(char *smem, uint32_t table, const ConvArgs &g, int tid)
     {
         if (tid < g.RS) {
@@ -64,7 +66,7 @@ struct ConvTileA {
         const int hi = lane >> 5;
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            const int chunk = (lane & 31) ^ ((2 * e + hi) << 2);
+            const int chunk = (lane & 31) ^ (((2 * e + hi) << 2) | ((wave & 1) << 1));
             const int64_t m = row0 + chunk * 8;
             const bool m_ok = m < g.M;
             const uint32_t mm = m_ok ? (uint32_t)m : 0u;
@@ -92,22 +94,22 @@ struct ConvTileA {
             coff[j] = (int32_t)c * g.HW;
             tap[j] = *reinterpret_cast<const uint32_t *>(smem + table + rs4[j]);
         }
-        // transposing read (see DirectTile<E, MNCONTIG>)
+        // transposing read (see DirectTile16<E, MNCONTIG>)
         const int gq = lane >> 4, i = lane & 15;
-        const int kl = 8 * (gq >> 1) + (i >> 2);
-        const int mn = wave_origin + 16 * (gq & 1) + 4 * (i & 3);
-        const int sw = (i >> 2) << 2;
+        const int kl = 8 * gq + (i >> 2);
+        const int mn = wave_origin + 4 * (i & 3);
+        const int sw = DirectTile16<E, MNCONTIG>::swizzle(kl);
 #pragma unroll
         for (int t = 0; t < T; ++t)
-            rd[t] = (uint32_t)(kl * RB + ((((mn >> 3) + 4 * t) ^ sw) << 4) + ((mn >> 2) & 1) * 8) + region;
+            rd[t] = (uint32_t)(kl * RB + ((((mn >> 3) + 2 * t) ^ sw) << 4) + ((mn >> 2) & 1) * 8) + region;
     }
 
     // Requests load j of the next slice into the LDS slot at lds_slice and moves the state on by one slice
     // (step4 = 4 * (32 % RS), stepc = 32 / RS * HW); returns what has to be done to the run once it has landed
-    // (0: nothing).  Slices past the program's k range are requested like any other (from wherever the clamped
-    // offsets point inside x): nobody reads them.
+    // (0: nothing).  beyond: the slice lies past the program's k range; it is requested like any other (the loop has
+    // one shape) but from outside the buffer, so that zeros arrive (a surplus trip multiplies it).
     __device__ __forceinline__ uint32_t issue_one(int j, const ConvArgs &g, u32x4 rsrc, uint32_t step4, int32_t stepc,
-                                                  const char *smem, uint32_t table, uint32_t lds_slice, int wave)
+                                                  const char *smem, uint32_t table, uint32_t lds_slice, int wave, bool beyond)
     {
         const int e = j & 1;
         const uint32_t t = tap[j], mk = masks[e];
@@ -120,7 +122,7 @@ struct ConvTileA {
         uint32_t code = (mk >> (t >> 24)) & 3u;
         code |= ((uint32_t)l_off >> 29) & (uint32_t)MOVE_UP;
         code |= (uint32_t)late << DOWN_SHIFT;
-        const bool ok = (mk & (t >> 16) & 0xffu) != 0;
+        const bool ok = (mk & (t >> 16) & 0xffu) != 0 && !beyond;
         dma16_buf(rsrc, ok ? (uint32_t)offc * 2u : kOutside, 0u, lds_slice + (uint32_t)((wave * PER + j) * 1024));
         // the same row of the slice after it
         uint32_t nrs = rs4[j] + step4;
@@ -132,16 +134,22 @@ struct ConvTileA {
         return ok ? code : 0u;
     }
 
-    // what issue_one() noted for the four runs of a slice (8 bits each in `codes`), applied in LDS
-    __device__ __forceinline__ void settle(uint32_t codes, char *smem, const ConvArgs &g, uint32_t slot_off, int wave, int lane) const
+    // What issue_one() noted for the four runs of a slice (8 bits each in `codes`), applied in LDS.  The common work -- the one
+    // element of a run that lies in the left / right padding is overwritten with zero -- has no branch: a run without such an
+    // element writes its zero to a spare place of its own (at byte offset `spare`).  (With a branch per run and case, this
+    // function was 300 instructions between the wait for the slice and the barrier that publishes it, every trip, with the
+    // matrix pipe idle.)  The rare work -- a run that had to be fetched from another place, the tensor's first and last
+    // runs -- sits behind one wavefront-uniform test.
+    __device__ __forceinline__ void settle(uint32_t codes, char *smem, const ConvArgs &g, uint32_t slot_off, int wave, int lane, uint32_t spare) const
     {
-        if (codes == 0) return;
+        constexpr uint32_t kClears = 0x01010101u * (uint32_t)(CLEAR_FIRST | CLEAR_LAST);
+        if (__builtin_amdgcn_ballot_w64(codes != 0) == 0) return;                       // (uniform)
+        if (__builtin_amdgcn_ballot_w64((codes & ~kClears) != 0) != 0) {                // (uniform, rare)
 #pragma unroll
-        for (int j = 0; j < PER; ++j) {
-            const uint32_t code = (codes >> (8 * j)) & 0xffu;
-            if (code == 0) continue;
-            const uint32_t at = slot_off + (uint32_t)((wave * PER + j) * 1024 + lane * 16);
-            if (code & ~(uint32_t)(CLEAR_FIRST | CLEAR_LAST)) {
+            for (int j = 0; j < PER; ++j) {
+                const uint32_t code = (codes >> (8 * j)) & 0xffu;
+                if ((code & ~(uint32_t)(CLEAR_FIRST | CLEAR_LAST)) == 0) continue;
+                const uint32_t at = slot_off + (uint32_t)((wave * PER + j) * 1024 + lane * 16);
                 u32x4 v = lds_read16(smem, at);
                 if (code & MOVE_UP) {                              // element i <- element i - 1 (element 0 is cleared below)
                     v = u32x4{v[0] << 16, __builtin_amdgcn_alignbit(v[1], v[0], 16), __builtin_amdgcn_alignbit(v[2], v[1], 16),
@@ -152,27 +160,81 @@ struct ConvTileA {
                 }
                 lds_write16(smem, at, v);
             }
-            if (code & CLEAR_FIRST) *reinterpret_cast<uint16_t *>(smem + at) = 0;
-            if (code & CLEAR_LAST) *reinterpret_cast<uint16_t *>(smem + at + 2 * g.last_e) = 0;
+        }
+        const uint32_t own = spare + (uint32_t)lane * 4u;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const uint32_t at = slot_off + (uint32_t)((wave * PER + j) * 1024 + lane * 16);
+            const uint32_t a_first = (codes >> (8 * j)) & (uint32_t)CLEAR_FIRST ? at : own;
+            const uint32_t a_last = (codes >> (8 * j)) & (uint32_t)CLEAR_LAST ? at + 2u * (uint32_t)g.last_e : own;
+            *reinterpret_cast<uint16_t *>(smem + a_first) = 0;
+            *reinterpret_cast<uint16_t *>(smem + a_last) = 0;
         }
     }
 
-    __device__ __forceinline__ void read(u32x2 (&f)[2], const char *smem, int t, int ks, int part, uint32_t slice_off) const
+    // read q of the slice: half q % 2 (k 0..3 or 4..7 of the lane's run) of fragment q / 2
+    __device__ __forceinline__ void read(u32x4 (&f)[T], const char *smem, int q, uint32_t slice_off) const
     {
         typedef short4v __attribute__((address_space(3))) * lds_s4;
-        const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (rd[t] + slice_off + (uint32_t)((ks * 16 + part * 4) * RB))));
-        f[part] = __builtin_bit_cast(u32x2, v);
+        const int t = q >> 1, part = q & 1;
+        const u32x2 v = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (rd[t] + slice_off + (uint32_t)(part * 4 * RB)))));
+        f[t][2 * part] = v[0];
+        f[t][2 * part + 1] = v[1];
     }
 };
+
+// Epilogue.  Every matrix instruction is issued with the filter fragment first, so a lane holds one output position
+// m = lane % 16 of each 16 x 16 block and, register by register, 4 of its filters (4 (lane / 16) + v).  A store instruction
+// writes, per quarter wavefront, 16 consecutive positions of one filter: 32- or 64-byte segments of the output's contiguous
+// (p, q) axis.  Positions past M and a row's surplus positions (the kernel numbers positions with the row pitch rounded up
+// to a multiple of 8) are not stored.  An element's address is a wavefront-uniform base (the filter) plus a lane offset (the
+// position, and the lane quarter's 4 filters); the host has checked that the output's byte offsets fit 31 bits.
+// row0w / col0w: first position / filter of this wavefront; part: which part of the k range the program multiplied.
+template <int BM, int BN, int OUT>
+__device__ __forceinline__ void conv_store_points16(const ConvArgs &g, const float4v (&acc)[BM / 32][BN / 32], int64_t part, int64_t row0w, int64_t col0w, int lane)
+{
+    constexpr int TM = BM / 32, TN = BN / 32;
+    constexpr int ES = OUT == NT_F32 ? 4 : 2;
+    const int l16 = lane & 15, gq = lane >> 4;
+    const int64_t f_pitch = g.syf * ES;
+    char *const y0 = reinterpret_cast<char *>(g.Y) + part * g.slice * ES + col0w * f_pitch;
+    const uint32_t quarter_off = (uint32_t)(4 * gq) * (uint32_t)f_pitch;
+    auto put = [&](char *at, float x) {
+        if constexpr (OUT == NT_F32) *reinterpret_cast<float *>(at) = x;
+        else *reinterpret_cast<uint16_t *>(at) = (uint16_t)pack_pair<OUT>(__builtin_bit_cast(uint32_t, x), 0u);
+    };
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int64_t m = row0w + tm * 16 + l16;
+        const uint32_t mm = m < g.M ? (uint32_t)m : 0u;
+        const uint32_t n = mm / (uint32_t)g.PQ8;
+        const uint32_t pq = mm - n * (uint32_t)g.PQ8;
+        const uint32_t p = pq / (uint32_t)g.Q8;
+        const int q = (int)(pq - p * (uint32_t)g.Q8);
+        const bool keep = m < g.M && q < g.Q;                        // not past the last position, not one of a row's surplus positions
+        const uint32_t lane_off = (uint32_t)((int64_t)n * g.syn + (int64_t)p * g.Q + q) * (uint32_t)ES + quarter_off;
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            // (the block is pinned in its accumulator registers up to this point, see store_tile16_rows)
+            float4v blk = acc[tm][tn];
+            asm volatile("" : "+a"(blk));
+            char *const yb = y0 + (tn * 16) * f_pitch;               // (uniform)
+            const int64_t room = g.N - (col0w + tn * 16 + 4 * gq);   // filters from this lane's first on
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (keep && v < room) put(yb + v * f_pitch + lane_off, blk[v]);
+        }
+    }
+}
 
 template <int BN, bool BF16>
 __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_direct_kernel(const ConvArgs g)
 {
     constexpr int BM = 256;
-    constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr int TM = BM / 32, TN = BN / 32;
     constexpr int kRing = ring_of(BM, BN);
     using TileA = ConvTileA;
-    using TileB = DirectTile<BN, KCONTIG>;
+    using TileB = DirectTile16<BN, KCONTIG>;
     constexpr uint32_t A_BYTES = TileA::BYTES, B_BYTES = TileB::BYTES, B_BASE = kRing * A_BYTES;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
@@ -204,61 +266,49 @@ __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_dir
     const u32x4 rsrc_a = make_rsrc(g.X, g.x_numel * 2);
     const u32x4 rsrc_b = make_rsrc(gB, ((int64_t)(g.N - 1) * g.ldb + g.K) * 2 - (gB - gB0));
 
-    float16v acc[TM][TN];
+    float4v acc[TM][TN];
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
         for (int b = 0; b < TN; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+            for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
 
-    u32x2 fa[2][TM][2], fb[2][TN][2];
-    constexpr int NRB = TN * TileB::RPF, NR = TM * TileA::RPF + NRB;
-    auto lds_read = [&](int r, int slot, int ks, uint32_t ring) {
-        if (r < TileA::RPF) {
-            ta.read(fa[slot][0], smem, 0, ks, r, ring * A_BYTES);
-        } else if (r < TileA::RPF + NRB) {
-            const int q = r - TileA::RPF;
-            tb.read(fb[slot][q / TileB::RPF], smem, q / TileB::RPF, ks, q % TileB::RPF, ring * B_BYTES);
-        } else {
-            const int q = r - NRB;
-            ta.read(fa[slot][q / TileA::RPF], smem, q / TileA::RPF, ks, q % TileA::RPF, ring * A_BYTES);
-        }
+    // operand fragments of one slice, two sets: [set][fragment]
+    u32x4 fa[2][TM], fb[2][TN];
+    constexpr int NRA = TM * TileA::RPF, NRB = TN * TileB::RPF, NR = NRA + NRB;
+    auto lds_read = [&](int r, int set, uint32_t ring) {
+        if (r < TileA::RPF) ta.read(fa[set], smem, r, ring * A_BYTES);
+        else if (r < TileA::RPF + NRB) tb.read(fb[set], smem, r - TileA::RPF, ring * B_BYTES);
+        else ta.read(fa[set], smem, r - NRB, ring * A_BYTES);
     };
     constexpr int NM = TM * TN, ND = TileA::PER + TileB::PER;
     const int64_t last = n_slices - 1;
     // load d of slice s (counted from the program's first) into ring position `ring`; the codes of the input's runs
-    // are collected in `codes`.  A slice past the program's range is requested all the same (the loop has one
-    // shape; its filter chunks are those of the last slice): nobody reads it.
+    // are collected in `codes`.  A slice past the program's range is requested all the same (the loop has one shape),
+    // from outside both buffers: zeros arrive, and the surplus trip of an odd number of slices multiplies zeros.
     auto dma = [&](int d, int64_t s, uint32_t ring, uint32_t &codes) {
         if (d < TileA::PER) {
-            codes |= ta.issue_one(d, g, rsrc_a, step4, stepc, smem, TABLE, lds0 + ring * A_BYTES, wave) << (8 * d);
+            codes |= ta.issue_one(d, g, rsrc_a, step4, stepc, smem, TABLE, lds0 + ring * A_BYTES, wave, s > last) << (8 * d);
         } else {
-            const int64_t sc = s < last ? s : last;
-            tb.issue_one_buf(d - TileA::PER, rsrc_b, (uint32_t)(sc * b_step), lds0 + B_BASE + ring * B_BYTES, wave);
+            tb.issue_one_buf(d - TileA::PER, rsrc_b, s <= last ? (uint32_t)(s * b_step) : 0x80000000u, lds0 + B_BASE + ring * B_BYTES, wave);
         }
     };
-    auto step = [&](int slot, int ks_next, uint32_t rring, int nd, int64_t s, uint32_t dring, uint32_t &codes) {
-        constexpr int RQ = (NR + NM - 1) / NM;
+    // One trip: the matrix instructions on fragment set `set`; behind them the LDS reads of the next slice (ring position
+    // rring) into the other set and the loads of slice s into ring position dring (see gemm_direct16_kernel).
+    auto trip = [&](int set, uint32_t rring, int64_t s, uint32_t dring, uint32_t &codes) {
+        constexpr int RS = NM * 3 / 4;
 #pragma unroll
         for (int idx = 0; idx < NM; ++idx) {
             const int tm = idx / TN, tn = idx % TN;
-            const u32x4 xa{fa[slot][tm][0][0], fa[slot][tm][0][1], fa[slot][tm][1][0], fa[slot][tm][1][1]};
-            const u32x4 xb{fb[slot][tn][0][0], fb[slot][tn][0][1], fb[slot][tn][1][0], fb[slot][tn][1][1]};
-            acc[tm][tn] = mfma32<BF16>(xb, xa, acc[tm][tn]);   // transposed block: a lane holds position lane % 32 (see conv_store_points)
+            mfma16<BF16>(acc[tm][tn], fb[set][tn], fa[set][tm]);      // transposed block: a lane holds position lane % 16 (see conv_store_points16)
+            if (idx < RS)
 #pragma unroll
-            for (int q = 0; q < RQ; ++q)
-                if (idx * RQ + q < NR) lds_read(idx * RQ + q, slot ^ 1, ks_next, rring);
-            if (nd > 0) {
-                const int per = (nd + NM - 1) / NM;
-                const int gap = nd >= NM ? 1 : NM / nd;
-                if (idx % gap == gap - 1)
+                for (int r = idx * NR / RS; r < (idx + 1) * NR / RS; ++r) lds_read(r, set ^ 1, rring);
 #pragma unroll
-                    for (int q = 0; q < per; ++q)
-                        if ((idx / gap) * per + q < nd) dma((idx / gap) * per + q, s, dring, codes);
-            }
+            for (int d = idx * ND / NM; d < (idx + 1) * ND / NM; ++d) dma(d, s, dring, codes);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -276,33 +326,40 @@ __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_dir
             for (int d = 0; d < ND; ++d) dma(d, s, s, pending[s - 1]);
         }
         NT_WAIT_VMCNT((kRing - 1) * ND);
-        ta.settle(c0, smem, g, 0, wave, lane);
+        ta.settle(c0, smem, g, 0, wave, lane, TABLE + 256);
     }
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < NR; ++r) lds_read(r, 0, 0, 0);
+    for (int r = 0; r < NR; ++r) lds_read(r, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
 
-    // one slice per trip, as in the direct GEMM kernel; the runs of slice s + 1 are put right between the wait
-    // for this wavefront's loads and the barrier that publishes the slice
+    // one slice per trip, two trips per pass (the fragment sets alternate), as in gemm_direct16_kernel; the runs of slice
+    // s + 1 are put right between the wait for this wavefront's loads and the barrier that publishes the slice
     uint32_t ring = 0;
-    for (int64_t sl = 0; sl < n_slices; ++sl) {
-        const uint32_t nxt = ring + 1 == kRing ? 0 : ring + 1;
-        uint32_t unused = 0, fresh = 0;
-        step(0, 1, ring, 0, 0, 0, unused);
-        NT_WAIT_VMCNT((kRing - 2) * ND);
-        ta.settle(pending[0], smem, g, nxt * A_BYTES, wave, lane);
-        __syncthreads();
-        step(1, 0, nxt, ND, sl + kRing, ring, fresh);
+    for (int64_t sl = 0; sl < n_slices; sl += 2) {
 #pragma unroll
-        for (int i = 0; i + 1 < kRing - 1; ++i) pending[i] = pending[i + 1];
-        pending[kRing - 2] = fresh;
-        ring = nxt;
+        for (int half = 0; half < 2; ++half) {
+            const uint32_t nxt = ring + 1 == kRing ? 0 : ring + 1;
+            uint32_t fresh = 0;
+            NT_WAIT_VMCNT((kRing - 2) * ND);
+            ta.settle(pending[0], smem, g, nxt * A_BYTES, wave, lane, TABLE + 256);
+            __syncthreads();
+            trip(half, nxt, sl + half + kRing, ring, fresh);
+#pragma unroll
+            for (int i = 0; i + 1 < kRing - 1; ++i) pending[i] = pending[i + 1];
+            pending[kRing - 2] = fresh;
+            ring = nxt;
+        }
     }
     NT_WAIT_VMCNT(0);
     __syncthreads();
+    // (wait states before ordinary instructions read the accumulators, see gemm_direct16_kernel)
+    asm volatile("s_nop 15" ::: "memory");
 
-    conv_store_transposed<BM, BN, uint32_t>(g, acc, bi, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
+    const int64_t row_w = row0 + wave_m * (BM / 2), col_w = col0 + wave_n * (BN / 2);
+    if (g.out_dtype == NT_F32) conv_store_points16<BM, BN, NT_F32>(g, acc, bi, row_w, col_w, lane);
+    else if (g.out_dtype == NT_F16) conv_store_points16<BM, BN, NT_F16>(g, acc, bi, row_w, col_w, lane);
+    else conv_store_points16<BM, BN, NT_BF16>(g, acc, bi, row_w, col_w, lane);
 }
 
 template <int BN, bool BF16>
