@@ -1,13 +1,17 @@
 // Direct kernel on 16 x 16 x 32 matrix instructions: full tiles of 16-byte aligned, unit-stride operands.
 //
-// The same program (Section 3.2.1), the same global -> LDS ring of 32-k slices and the same LDS slice layouts as
-// gemm_direct_kernel; what differs is the matrix instruction.  v_mfma_f32_16x16x32 multiplies a 16 x 32 block by a
-// 32 x 16 block: one instruction consumes a whole 32-k slice of its two 16-row fragments, and a wavefront's
-// (BM/2) x (BN/2) part of the tile is (BM/32) x (BN/32) accumulator blocks of 4 registers each.  Measured on this
-// part with operands of the benchmark's distribution and nothing else running, a wavefront-per-SIMD loop of these
-// instructions sustains 1.85 PFLOP/s against 1.60 PFLOP/s for v_mfma_f32_32x32x16 (both reach 2.4 with all-zero
-// operands): the chip is power managed, the narrower instruction moves fewer accumulator bits per flop, and the
-// difference is clock.
+// One workgroup (4 wavefronts, 2 x 2) computes one BM x BN output tile (one program of the tile-to-program mapping,
+// Section 3.2.1).  The blocks of A and B that the program multiplies (source-to-target mapping, Section 3.2.2) travel
+// from global memory straight into LDS (16 bytes per lane, no staging registers) in slices of 32 k (each 64-wide k tile
+// of the arrangement is two such slices).  LDS holds a ring of three or four slices per operand (see ring_of), so a
+// slice is requested two or three slice-times before it is multiplied: long enough to cover an L2 miss.
+//
+// The matrix instruction is v_mfma_f32_16x16x32: it multiplies a 16 x 32 block by a 32 x 16 block, so one instruction
+// consumes a whole 32-k slice of its two 16-row fragments, and a wavefront's (BM/2) x (BN/2) part of the tile is
+// (BM/32) x (BN/32) accumulator blocks of 4 registers each.  Measured on this part with operands of the benchmark's
+// distribution and nothing else running, a wavefront-per-SIMD loop of these instructions sustains 1.85 PFLOP/s against
+// 1.60 PFLOP/s for v_mfma_f32_32x32x16 (both reach 2.4 with all-zero operands): the chip is power managed, the narrower
+// instruction moves fewer accumulator bits per flop, and the difference is clock.
 //
 // One trip of the loop = one slice.  A trip multiplies the fragments of slice s (all in registers, read during the
 // trip before) while it reads the fragments of slice s+1 into the other register set and requests slice s+ring
@@ -315,7 +319,7 @@ __device__ __forceinline__ void store_tile16(const FastArgs &g, char *smem, int 
 // overhang M or N, K need not be a whole number of slices, rows need only the element's own 2-byte alignment: the operand
 // loads are range checked (what lies past an operand's end reads as zero, what an overhanging tile reads inside it only
 // reaches outputs that are never stored, except the k past K of a k-contiguous operand, which are zeroed in LDS) and the
-// stores are masked (see gemm_direct_kernel, whose rules these are).
+// stores are masked.
 template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE>
 __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_kernel(const FastArgs g)
 {
