@@ -25,8 +25,18 @@ METRIC = "GEMM TFLOP/s and % of MI355X fp16 MFMA peak, 1 GPU, 8192^3 fp16"
 MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense fp16/bf16 matrix peak (published)
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None = not measured.
+# HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy
+# kernel of known size): profiles/traffic.json holds, per workload, the bytes and the library version they were measured on; a
+# figure measured on another version of the kernels is not reported.
+def measured_traffic(workload, version):
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            entry = json.load(f).get(workload)
+    except (OSError, ValueError):
+        return None
+    if not entry or entry.get("library_version") != version:
+        return None
+    return int(entry["hbm_bytes_per_launch"])
 
 
 def _torch_dt():
@@ -46,7 +56,78 @@ def to_f64(t):
     return t.detach().to(torch.float64).cpu().numpy()
 
 
-MEASURED_TRAFFIC_BYTES = {"p_f16_8192": 1819000000, "f4_f16_sdpa": 100830000}   # profiles/gemm_direct_8192_f16_counters.md, profiles/sdpa_1024_f16_counters.md
+class ClockSampler:
+    """Shader clock while the timed region runs, from the driver's sysfs file (the line marked '*' is the current clock)."""
+
+    def __init__(self):
+        import glob
+        import threading
+        self.files = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.samples = []
+        self._stop = threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True) if self.files else None
+
+    def _run(self):
+        while not self._stop.is_set():
+            try:
+                for line in open(self.files[0]):
+                    if "*" in line:
+                        self.samples.append(int(line.split(":")[1].strip().split("Mhz")[0].split("MHz")[0]))
+            except (OSError, ValueError, IndexError):
+                return
+            time.sleep(0.002)
+
+    def __enter__(self):
+        if self._thread:
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        if self._thread:
+            self._thread.join(timeout=1.0)
+
+    def summary(self):
+        if not self.samples:
+            return None
+        return {"mean": round(sum(self.samples) / len(self.samples), 1), "min": min(self.samples), "max": max(self.samples), "samples": len(self.samples)}
+
+
+def settle_clock(step, ms=40.0):
+    """The first tens of milliseconds of work after an idle period run at clocks that are still moving: untimed steps until
+    `ms` of stream time have passed, whatever the warm-up count asked for.  Returns the steps taken."""
+    import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n, total = 0, 0.0
+    while total < ms and n < 100000:
+        e0.record()
+        for _ in range(8):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        total += e0.elapsed_time(e1)
+        n += 8
+    return n
+
+
+def mfma_only_rate(nt, data, seconds=0.25):
+    """Sustained rate of the product kernels' matrix instruction alone on this workload's operand values (nt_mfma_probe)."""
+    import torch
+    out = torch.empty(1024 * 256, dtype=torch.float32, device="cuda")
+    flat = data.reshape(-1)
+    flat = flat[: min(flat.numel(), 1 << 22)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    flops, total, warm = 0.0, 0.0, 0.0
+    while warm < seconds * 500:                                        # half the time again to settle, then the timed part
+        e0.record(); nt.mfma_probe(flat, out); e1.record(); torch.cuda.synchronize()
+        warm += e0.elapsed_time(e1)
+    while total < seconds * 1000:
+        e0.record()
+        f = sum(nt.mfma_probe(flat, out) for _ in range(4))
+        e1.record(); torch.cuda.synchronize()
+        total += e0.elapsed_time(e1)
+        flops += f
+    return flops / (total * 1e-3) / 1e12
 
 
 def parse_args():
@@ -157,7 +238,7 @@ def bench_memory_bound(args, cfg):
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "config": {"workload": args.workload, "shape": shape, "in_dtype": dt, "out_dtype": dt, "arithmetic": "f32"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "kernel_ms_avg": round(kern_avg, 5), "algorithmic_bytes": int(alg_bytes)},
+                     "traffic": measured_traffic(args.workload, nt.version()), "kernel_ms_avg": round(kern_avg, 5), "algorithmic_bytes": int(alg_bytes)},
     }
     if not args.no_check:
         got = oe.decode(out[sample_sl].contiguous().view(torch.int16).cpu().numpy().view(np.uint16), dt)
@@ -203,7 +284,7 @@ def bench_sdpa(args, cfg):
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "config": {"workload": args.workload, "shape": {"B": B, "H": H, "S": S, "D": D}, "in_dtype": dt, "out_dtype": dt, "accumulate": "f32"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "kernel_ms_avg": round(kern_avg, 5), "algorithmic_bytes": int(alg_bytes)},
+                     "traffic": measured_traffic(args.workload, nt.version()), "kernel_ms_avg": round(kern_avg, 5), "algorithmic_bytes": int(alg_bytes)},
     }
     if not args.no_check:
         ref = oat.sdpa(qb[B - 1, H - 1, :256], kb[B - 1, H - 1], vb[B - 1, H - 1], dt)
@@ -281,10 +362,13 @@ def main():
         grid, kt = (nt.arrange_bmm if cfg["kind"] == "bmm" else nt.arrange_gemm)(a, b, y, tile=tile)
     flops, alg_bytes = flops_and_bytes(cfg)
 
-    # ---- warm-up, then exactly K timed steps bracketed by synchronisation
+    # ---- clocks settled, warm-up, then exactly K timed steps bracketed by synchronisation
+    settle_steps = settle_clock(step)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    sampler = ClockSampler()
+    sampler.__enter__()
     if args.workload.startswith("c6_"):
         # a step of some tens of microseconds (two dependent launches: the k-split convolution and the sum of its
         # partial tiles): one event before the first step and one after the last, none in between
@@ -303,8 +387,11 @@ def main():
         kern_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, ends)])
         ms_per_step = wall * 1e3 / args.steps
         kern_avg = float(kern_ms.mean())
+    sampler.__exit__()
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (kern_avg * 1e-3) / 1e12
+    # the matrix instruction alone on the same operand values, right behind the timed run (same clock regime)
+    mfma_only = mfma_only_rate(nt, x if cfg["kind"] == "conv" else a)
 
     result = {
         # (the headline metric's name only for the headline workload; the other workloads say what they are)
@@ -317,11 +404,13 @@ def main():
                    "in_dtype": dt, "out_dtype": out, "accumulate": "f32",
                    "grid": list(grid), "k_tiles": int(kt), "tile": list(tile) if tile else "library default"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": measured_traffic(args.workload, nt.version()),
                      "kernel_ms_avg": round(kern_avg, 4), "kernel_ms_min": round(float(kern_ms.min()), 4),
                      "kernel_ms_median": round(float(np.median(kern_ms)), 4),
                      "algorithmic_bytes": int(alg_bytes),
-                     "hbm_gbs_algorithmic": round(alg_bytes / (kern_avg * 1e-3) / 1e9, 1), "hbm_peak_gbs": HBM_PEAK_GBS},
+                     "hbm_gbs_algorithmic": round(alg_bytes / (kern_avg * 1e-3) / 1e9, 1), "hbm_peak_gbs": HBM_PEAK_GBS,
+                     "mfma_only_tflops_same_data": round(mfma_only, 1), "frac_of_mfma_only": round(achieved / mfma_only, 4),
+                     "sclk_mhz": sampler.summary(), "settle_steps": settle_steps},
     }
 
     # ---- the CPU oracle on a bounded part of the same workload: timed (reported baseline only) and then used as the

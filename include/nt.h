@@ -331,6 +331,17 @@ nt_status nt_trace_tile(int32_t kind, const nt_tensor_desc *d0, const nt_tensor_
                         nt_tile_cfg cfg, int32_t operand, int64_t program_id, int64_t k,
                         int64_t *offsets_out, uint8_t *mask_out, size_t capacity, void *hip_stream);
 
+/*
+ * nt_mfma_probe: a measurement aid for the roofline of the matrix kernels (the application of Section 4.2 is one `dot` per k
+ * tile; this runs that instruction and nothing else).  `blocks` workgroups of 4 wavefronts each read a few operand fragments
+ * from `data` (device pointer, 16-byte aligned, n_elems >= 8 elements of `dtype`, NT_F16 or NT_BF16) and issue
+ * iters x 64 v_mfma_f32_16x16x32 instructions per wavefront on them, back to back: 2 * 16 * 16 * 32 * 64 * iters * 4 * blocks
+ * flop per call, no memory traffic inside the loop.  The part is power managed and the rate depends on the operand values, so
+ * the rate this call sustains on a workload's own data is the ceiling for a kernel on that instruction and data.
+ * out: device array of blocks * 256 floats (checksums; written so that the loop cannot be optimised away).
+ */
+nt_status nt_mfma_probe(const void *data, int64_t n_elems, nt_dtype dtype, int32_t iters, int32_t blocks, float *out, void *hip_stream);
+
 /* Thread-local, statically stored description of the last error on this thread ("" if none). */
 const char *nt_last_error(void);
 

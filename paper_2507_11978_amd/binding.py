@@ -116,10 +116,11 @@ def load():
     L.nt_silu.argtypes = [P, D, P, D, i32, i64, P]
     L.nt_softmax.argtypes = [P, D, P, D, i32, P]
     L.nt_rms_norm.argtypes = [P, D, P, D, C.c_float, i32, P]
+    L.nt_mfma_probe.argtypes = [P, i64, i32, i32, i32, P, P]
     L.nt_trace_tile.argtypes = [i32, D, D, D, i32, i32, i32, i32, TileCfg, i32, i64, i64, P, P, C.c_size_t, P]
     for name in ("nt_arrange_levels", "nt_arrange_tile", "nt_arrange_gemm", "nt_arrange_bmm", "nt_arrange_conv2d",
                  "nt_program_order", "nt_gemm", "nt_gemm_noalloc", "nt_addmm", "nt_addmm_act", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile",
-                 "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm", "nt_matmul_views", "nt_sdpa"):
+                 "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm", "nt_matmul_views", "nt_sdpa", "nt_mfma_probe"):
         getattr(L, name).restype = i32
     L.nt_last_kernel_path.restype = i32
     L.nt_last_k_split.restype = i32
@@ -330,6 +331,15 @@ def gemm_noalloc(A, B, Cout, tile=None, stream=None):
                                   Cout.data_ptr(), C.byref(_desc_of(Cout)), _DTYPES[_torch_dtype_name(A)],
                                   _DTYPES[_torch_dtype_name(Cout)], _cfg(tile), _stream_ptr(stream)))
     return Cout
+
+
+def mfma_probe(data, out, iters=2000, blocks=1024, stream=None):
+    """Matrix-instruction-only loop on the 16-bit elements of `data` (see nt_mfma_probe); returns the flop count of the call."""
+    _require_cuda(data, out)
+    if out.numel() < blocks * 256:
+        raise ValueError("out must hold blocks * 256 floats")
+    _check(load().nt_mfma_probe(data.data_ptr(), data.numel(), _DTYPES[_torch_dtype_name(data)], int(iters), int(blocks), out.data_ptr(), _stream_ptr(stream)))
+    return 2.0 * 16 * 16 * 32 * 64 * iters * 4 * blocks
 
 
 PATH_GENERIC, PATH_STAGED, PATH_DIRECT, PATH_CONV, PATH_CONV_DIRECT, PATH_CONV_UNFOLD = 0, 1, 2, 3, 4, 5

@@ -60,6 +60,9 @@ nt_status launch_fill_zero(void *C, const OperandMap &mc, int64_t batch, int64_t
 nt_status launch_trace(const OperandMap &m, int64_t batch_off, int64_t row0, int64_t col0, int32_t rows, int32_t cols,
                        int64_t *offsets_out, uint8_t *mask_out, void *stream);
 
+// matrix-instruction-only loop on the caller's operand data (a measurement aid, see nt_mfma_probe)
+nt_status launch_mfma_probe(const void *data, int64_t n_elems, int dtype, int32_t iters, int32_t blocks, float *out, void *stream);
+
 // memory-bound kernels: op 0 = add (x + y), 1 = silu (y unused); strides in elements
 nt_status launch_map(int op, const void *x, int64_t sx, const void *y, int64_t sy, void *out, int64_t so, int64_t n, int dtype, void *stream);
 // row-wise kernels: op 0 = softmax, 1 = rms_norm (eps used)

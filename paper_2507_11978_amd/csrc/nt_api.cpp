@@ -439,8 +439,17 @@ nt_status nt_trace_tile(int32_t kind, const nt_tensor_desc *d0, const nt_tensor_
     return nt::launch_trace(m, b * bstride, row0, col0, rows, cols, offsets_out, mask_out, hip_stream);
 }
 
+nt_status nt_mfma_probe(const void *data, int64_t n_elems, nt_dtype dtype, int32_t iters, int32_t blocks, float *out, void *hip_stream)
+{
+    if (!dtype_in_ok(dtype)) return fail(NT_ERR_UNSUPPORTED, "dtype must be NT_F16 or NT_BF16");
+    if (!data || !out) return fail(NT_ERR_INVALID_ARG, "null device pointer");
+    if (n_elems < 8 || iters < 0 || blocks <= 0) return fail(NT_ERR_INVALID_ARG, "n_elems >= 8, iters >= 0 and blocks > 0 wanted");
+    if ((reinterpret_cast<uintptr_t>(data) & 15) != 0) return fail(NT_ERR_INVALID_ARG, "data must be 16-byte aligned");
+    return nt::launch_mfma_probe(data, n_elems, dtype, iters, blocks, out, hip_stream);
+}
+
 const char *nt_last_error(void) { return nt::last_error().c_str(); }
 
-const char *nt_version(void) { return "nt-mi355x 0.1 (gfx950)"; }
+const char *nt_version(void) { return "nt-mi355x 0.2 (gfx950)"; }
 
 }  // extern "C"
