@@ -332,6 +332,29 @@ nt_status nt_trace_tile(int32_t kind, const nt_tensor_desc *d0, const nt_tensor_
                         int64_t *offsets_out, uint8_t *mask_out, size_t capacity, void *hip_stream);
 
 /*
+ * nt_trace_loader_slice: the source-to-target mapping (Section 3.2.2) as the matrix-instruction kernels execute it.  Those
+ * kernels do not go through the operand map that nt_trace_tile runs: each lane derives its own addresses (swizzled LDS slots,
+ * range-checked loads, for the convolution the unfolded input generated on the fly with its padding fix-ups).  This call
+ * launches ONE workgroup of the very kernel that nt_gemm / nt_bmm / nt_conv2d_implicit would launch for the same arguments
+ * (kind: 0 / 1 / 2 as in nt_trace_tile; no k split), as program `program_id` (b * mt * nt + i * nt + j).  The workgroup
+ * requests that program's 32-k slice `slice` (slice s covers k 32 s .. 32 s + 31; a k tile of 64 is two slices) with the
+ * kernel's own loads, waits, applies what the kernel applies to a slice once it has landed (zeroing the k past K, the
+ * padding elements of the convolution's runs), and copies the slice out of LDS:
+ *   values_out[r * 32 + kk] = the 16-bit pattern the matrix instructions would read for row r of the operand's tile
+ *   (A: output row, or output position of a convolution; B: output column / filter) and k index kk of the slice.
+ * A caller who fills the operand with its elements' own indices (16 bits at a time) reads back, element by element, which
+ * source element the loader put there, and zero where it fed a zero: compare with nt_arrange_* / the arrangement.
+ * A, B: device pointers, read.  dC: the output's descriptor (shape only; nothing is stored).  values_out: DEVICE array of
+ * `capacity` entries, at least 32 * (tile rows of the operand).  Only launches that stream their operands straight into LDS
+ * (nt_last_kernel_path() 2 or 4 for the same arguments) can be traced: otherwise NT_ERR_UNSUPPORTED.  The ring-unrolled
+ * variant of the 256 x 256 kernel has the same per-lane offsets and slice stepping as the kernel traced here.
+ */
+nt_status nt_trace_loader_slice(int32_t kind, const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
+                                const nt_tensor_desc *dC, int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                                nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, int32_t operand, int64_t program_id, int64_t slice,
+                                uint16_t *values_out, size_t capacity, void *hip_stream);
+
+/*
  * nt_mfma_probe: a measurement aid for the roofline of the matrix kernels (the application of Section 4.2 is one `dot` per k
  * tile; this runs that instruction and nothing else).  `blocks` workgroups of 4 wavefronts each read a few operand fragments
  * from `data` (device pointer, 16-byte aligned, n_elems >= 8 elements of `dtype`, NT_F16 or NT_BF16) and issue

@@ -118,8 +118,9 @@ def load():
     L.nt_rms_norm.argtypes = [P, D, P, D, C.c_float, i32, P]
     L.nt_mfma_probe.argtypes = [P, i64, i32, i32, i32, P, P]
     L.nt_trace_tile.argtypes = [i32, D, D, D, i32, i32, i32, i32, TileCfg, i32, i64, i64, P, P, C.c_size_t, P]
+    L.nt_trace_loader_slice.argtypes = [i32, P, D, P, D, D, i32, i32, i32, i32, i32, i32, TileCfg, i32, i64, i64, P, C.c_size_t, P]
     for name in ("nt_arrange_levels", "nt_arrange_tile", "nt_arrange_gemm", "nt_arrange_bmm", "nt_arrange_conv2d",
-                 "nt_program_order", "nt_gemm", "nt_gemm_noalloc", "nt_addmm", "nt_addmm_act", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile",
+                 "nt_program_order", "nt_gemm", "nt_gemm_noalloc", "nt_addmm", "nt_addmm_act", "nt_bmm", "nt_conv2d_implicit", "nt_trace_tile", "nt_trace_loader_slice",
                  "nt_add", "nt_silu", "nt_softmax", "nt_rms_norm", "nt_matmul_views", "nt_sdpa", "nt_mfma_probe"):
         getattr(L, name).restype = i32
     L.nt_last_kernel_path.restype = i32
@@ -461,6 +462,23 @@ def conv2d_implicit(x, w, y, stride=(1, 1), pad=(0, 0), tile=None, stream=None):
                                      int(pad[0]), int(pad[1]), _DTYPES[_torch_dtype_name(x)],
                                      _DTYPES[_torch_dtype_name(y)], _cfg(tile), _stream_ptr(stream)))
     return y
+
+
+def trace_loader_slice(kind, a, b, c, operand, program_id, slice_index, tile=None, stride=(1, 1), pad=(0, 0), stream=None):
+    """What the matrix-instruction kernel's own loader leaves in LDS for one operand (0 = A, 1 = B) of program `program_id` and
+    32-k slice `slice_index`: a numpy uint16 array [256, 32] of 16-bit patterns, row r = row of the operand's tile, 0xFFFF in
+    the rows past the tile's.  a, b: device tensors (read); c: a tensor of the output's shape and dtype (not written)."""
+    import numpy as np
+    import torch
+    kinds = {"gemm": 0, "bmm": 1, "conv2d": 2}
+    _require_cuda(a, b, c)
+    out = torch.full((256 * 32,), -1, dtype=torch.int16, device="cuda")
+    _check(load().nt_trace_loader_slice(kinds[kind], a.data_ptr(), C.byref(_desc_of(a)), b.data_ptr(), C.byref(_desc_of(b)),
+                                        C.byref(_desc_of(c)), int(stride[0]), int(stride[1]), int(pad[0]), int(pad[1]),
+                                        _DTYPES[_torch_dtype_name(a)], _DTYPES[_torch_dtype_name(c)], _cfg(tile), int(operand),
+                                        int(program_id), int(slice_index), out.data_ptr(), out.numel(), _stream_ptr(stream)))
+    torch.cuda.synchronize()
+    return out.cpu().numpy().view(np.uint16).reshape(256, 32)
 
 
 def trace_tile(kind, d0, d1, d2, tile, operand, program_id, k, stride=(1, 1), pad=(0, 0), stream=None):

@@ -36,6 +36,10 @@ struct ConvArgs {
     // that conv_ws_sum_kernel adds up in a fixed order).  Without a split: ksplit = 1, kt_per = kt, slice = 0.
     int32_t ksplit, kt_per;
     int64_t slice;
+    // loader trace of the direct kernel (nullptr otherwise), see FastArgs
+    uint16_t *trace_out;
+    int64_t trace_program;
+    int32_t trace_slice, trace_operand;
 };
 
 // floor(t / d) for 0 <= t < 2^16 with inv = floor(2^32 / d) + 1 (d >= 2), inv = 0 standing for d = 1

@@ -227,7 +227,10 @@ __device__ __forceinline__ void conv_store_points16(const ConvArgs &g, const flo
     }
 }
 
-template <int BN, bool BF16>
+// TRACE: one workgroup as program g.trace_program; the loader is stepped slice by slice up to g.trace_slice (its state moves
+// on with every request), that slice is fixed up as in the loop, and one operand's slice is copied out of LDS in
+// (position or filter, k) order (see gemm_direct16_kernel).
+template <int BN, bool BF16, bool TRACE = false>
 __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_direct_kernel(const ConvArgs g)
 {
     constexpr int BM = 256;
@@ -239,7 +242,8 @@ __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_dir
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     int64_t bi, ti, tj;                                  // bi: which part of the k range (k split)
-    locate_program(g.mt, g.nt, &bi, &ti, &tj);
+    if constexpr (TRACE) { bi = 0; ti = g.trace_program / g.nt; tj = g.trace_program % g.nt; }
+    else locate_program(g.mt, g.nt, &bi, &ti, &tj);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = wave >> 1, wave_n = wave & 1;
@@ -313,6 +317,23 @@ __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_dir
         }
     };
 
+    if constexpr (TRACE) {
+        uint32_t codes = 0;
+        for (int64_t s = 0; s <= g.trace_slice; ++s) {
+            codes = 0;
+#pragma unroll
+            for (int d = 0; d < ND; ++d) dma(d, s, 0, codes);
+            NT_WAIT_VMCNT(0);
+        }
+        ta.settle(codes, smem, g, 0, wave, lane, TABLE + 256);
+        __syncthreads();
+        const bool first = g.trace_operand == 0;
+        for (int e = tid; e < (first ? BM : BN) * kSliceK; e += kThreads) {
+            const uint32_t at = first ? DirectTile16<BM, MNCONTIG>::place(e / kSliceK, e % kSliceK) : B_BASE + TileB::place(e / kSliceK, e % kSliceK);
+            g.trace_out[e] = *reinterpret_cast<const uint16_t *>(smem + at);
+        }
+        return;
+    }
     // codes of the slices in flight, oldest first: pending[i] belongs to slice (current + 1 + i)
     uint32_t pending[kRing - 1];
     {
@@ -362,11 +383,11 @@ __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_dir
     else conv_store_points16<BM, BN, NT_BF16>(g, acc, bi, row_w, col_w, lane);
 }
 
-template <int BN, bool BF16>
+template <int BN, bool BF16, bool TRACE = false>
 static nt_status launch_conv_direct_inst(const ConvArgs &a, int64_t nwg, hipStream_t s)
 {
     constexpr size_t smem = (size_t)ring_of(256, BN) * (256 + BN) * kSliceK * sizeof(uint16_t) + ConvTileA::kTableBytes;
-    auto kern = gemm_conv_direct_kernel<BN, BF16>;
+    auto kern = gemm_conv_direct_kernel<BN, BF16, TRACE>;
     static DeviceOnce configured;
     if (!configured.done()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -379,5 +400,7 @@ static nt_status launch_conv_direct_inst(const ConvArgs &a, int64_t nwg, hipStre
 
 // bn: 64, 128 or 256 filters per program; nwg = ksplit * mt * nt
 nt_status launch_conv_direct(const ConvArgs &a, int bn, bool bf16, int64_t nwg, hipStream_t s);
+// the loader trace of the same kernel: one workgroup
+nt_status launch_conv_direct_trace(const ConvArgs &a, int bn, hipStream_t s);
 
 }  // namespace nt

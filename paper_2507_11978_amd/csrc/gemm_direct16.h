@@ -320,7 +320,11 @@ __device__ __forceinline__ void store_tile16(const FastArgs &g, char *smem, int 
 // loads are range checked (what lies past an operand's end reads as zero, what an overhanging tile reads inside it only
 // reaches outputs that are never stored, except the k past K of a k-contiguous operand, which are zeroed in LDS) and the
 // stores are masked.
-template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE>
+// TRACE: not a product at all.  One workgroup sets itself up as program g.trace_program, requests that program's 32-k slice
+// g.trace_slice with the very loads of the kernel (swizzle, range check), applies what the kernel applies to a slice once
+// it has landed, and copies one operand's slice out of LDS in (row, k) order: the source-to-target mapping (Section 3.2.2)
+// as this kernel's loader executes it, for a caller who has filled the operand with the elements' own indices.
+template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE, bool TRACE = false>
 __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_kernel(const FastArgs g)
 {
     constexpr int TM = BM / 32, TN = BN / 32;
@@ -331,7 +335,13 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     int64_t bi, ti, tj;
-    locate_program(g.mt, g.nt, &bi, &ti, &tj);
+    if constexpr (TRACE) {
+        bi = g.trace_program / (g.mt * g.nt);
+        ti = (g.trace_program - bi * g.mt * g.nt) / g.nt;
+        tj = g.trace_program % g.nt;
+    } else {
+        locate_program(g.mt, g.nt, &bi, &ti, &tj);
+    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = wave >> 1, wave_n = wave & 1;
@@ -441,6 +451,20 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_
     auto slice_a = [&](int64_t s) { return gA + (s <= last ? s * a_step : (EDGE ? (int64_t)0x80000000LL : last * a_step)); };
     auto slice_b = [&](int64_t s) { return gB + (s <= last ? s * b_step : (EDGE ? (int64_t)0x80000000LL : last * b_step)); };
 
+    if constexpr (TRACE) {
+        const int64_t s = g.trace_slice;
+#pragma unroll
+        for (int d = 0; d < ND; ++d) dma(d, slice_a(s), slice_b(s), 0);
+        NT_WAIT_VMCNT(0);
+        settle(s, 0);
+        __syncthreads();
+        const bool first = g.trace_operand == 0;
+        for (int e = tid; e < (first ? BM : BN) * kSliceK; e += kThreads) {
+            const uint32_t at = first ? TileA::place(e / kSliceK, e % kSliceK) : B_BASE + TileB::place(e / kSliceK, e % kSliceK);
+            g.trace_out[e] = *reinterpret_cast<const uint16_t *>(smem + at);
+        }
+        return;
+    }
     // prologue: slices 0 .. kRing-1 requested; wait for slice 0; its fragments into set 0
 #pragma unroll
     for (int s = 0; s < kRing; ++s)
@@ -653,6 +677,22 @@ static nt_status launch_direct16_inst(const FastArgs &a, int64_t nwg, hipStream_
     return check_launch("gemm_direct16_kernel");
 }
 
+// the loader trace of the same kernel (see TRACE): one workgroup
+template <int BM, int BN, int ALAY, int BLAY, bool EDGE>
+static nt_status launch_direct16_trace_inst(const FastArgs &a, hipStream_t s)
+{
+    constexpr size_t smem = (size_t)ring_of(BM, BN) * (BM + BN) * kSliceK * sizeof(uint16_t);
+    auto kern = gemm_direct16_kernel<BM, BN, false, ALAY, BLAY, EDGE, true>;
+    static DeviceOnce configured;
+    if (!configured.done()) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
+        configured.set();
+    }
+    hipLaunchKernelGGL(kern, dim3(1), dim3(kThreads), smem, s, a);
+    return check_launch("gemm_direct16_kernel (trace)");
+}
+
 template <int BM, int BN, bool BF16, bool EDGE = false>
 static nt_status launch_direct16_t(const FastArgs &a, int alay, int blay, int64_t nwg, hipStream_t s)
 {
@@ -672,5 +712,7 @@ NT_DIRECT16_DECL(256x128)
 NT_DIRECT16_DECL(128x256)
 NT_DIRECT16_DECL(256x256)
 #undef NT_DIRECT16_DECL
+// loader trace: bm x bn in {128, 256}^2, either flavour
+nt_status launch_direct16_trace(const FastArgs &a, int bm, int bn, int alay, int blay, bool edge, hipStream_t s);
 
 }  // namespace nt

@@ -423,7 +423,7 @@ static nt_status route_conv_implicit(const GemmLaunch &g, const ConvArgs &c, int
     const bool edge_b = (g.N % t.bn) || (g.K % t.bk);
     hipStream_t s = (hipStream_t)g.stream;
     int32_t kt_per = 0;
-    const int ksplit = conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
+    const int ksplit = g.trace.out ? 1 : conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
     const int64_t slice = g.conv.N * (int64_t)c.N * c.PQ;
     WorkspaceLease lease;
     float *ws = nullptr;                                     // (none: too large, or no memory; then no split)
@@ -439,6 +439,17 @@ static nt_status route_conv_implicit(const GemmLaunch &g, const ConvArgs &c, int
                         ((g.conv.N - 1) * c.syn + (int64_t)(c.N - 1) * c.syf + c.PQ) < (1LL << 29);   // (output offsets: 31 bits of bytes)
     if (direct && path_out) *path_out = PATH_CONV_DIRECT;
     const bool bf16 = g.in_dtype == NT_BF16;
+    if (g.trace.out) {
+        if (!direct) return fail(NT_ERR_UNSUPPORTED, "this convolution does not run on the kernel that streams its operands into LDS");
+        const int bn = c.N <= 64 ? 64 : (c.N <= 128 ? 128 : t.bn);
+        const int64_t rows = g.trace.operand == 0 ? 256 : bn;
+        if ((size_t)rows * 32 > g.trace.capacity) return fail(NT_ERR_BUFFER_TOO_SMALL, "trace buffer smaller than the slice");
+        if (g.trace.program < 0 || g.trace.program >= c.mt * c.nt) return fail(NT_ERR_INVALID_ARG, "program_id outside the grid");
+        if (g.trace.slice < 0 || g.trace.slice >= c.K / 32) return fail(NT_ERR_INVALID_ARG, "slice outside the reduction");
+        ConvArgs ca = c;
+        ca.trace_out = g.trace.out; ca.trace_program = g.trace.program; ca.trace_slice = g.trace.slice; ca.trace_operand = g.trace.operand;
+        return launch_conv_direct_trace(ca, bn, s);
+    }
     auto launch = [&](const ConvArgs &ca, int64_t nwg) {
         // (one column of tiles with few filters: the same grid is run by the kernel built for 64 or 128 filters per
         // program, which spends a quarter or half of the MFMAs)
@@ -630,6 +641,15 @@ static nt_status route_matrix(const GemmLaunch &g, FastArgs a, int alay, int bla
     if (direct && !plain_direct)
         a.patch = (words_aligned(a.lda, a.sa_batch, a.a_extent) ? 0 : 1) | (words_aligned(a.ldb, a.sb_batch, a.b_extent) ? 0 : 2);
     if (path_out) *path_out = direct ? PATH_DIRECT : PATH_FAST;
+    if (g.trace.out) {
+        if (!direct) return fail(NT_ERR_UNSUPPORTED, "this product does not run on the kernels that stream their operands into LDS");
+        const int64_t rows = g.trace.operand == 0 ? t.bm : t.bn;
+        if ((size_t)rows * 32 > g.trace.capacity) return fail(NT_ERR_BUFFER_TOO_SMALL, "trace buffer smaller than the slice");
+        if (g.trace.program < 0 || g.trace.program >= nwg) return fail(NT_ERR_INVALID_ARG, "program_id outside the grid");
+        if (g.trace.slice < 0 || g.trace.slice >= (g.K + 31) / 32) return fail(NT_ERR_INVALID_ARG, "slice outside the reduction");
+        a.trace_out = g.trace.out; a.trace_program = g.trace.program; a.trace_slice = g.trace.slice; a.trace_operand = g.trace.operand;
+        return launch_direct16_trace(a, t.bm, t.bn, alay, blay, !plain_direct, s);
+    }
     typedef nt_status (*Launcher)(const FastArgs &, int, int, int64_t, hipStream_t);
     // [f16, bf16]; direct: full aligned tiles (the kernel on 16 x 16 x 32 matrix instructions: fewer accumulator bits moved per
     // flop, which on this power-managed part is clock), edge: the range-checked flavour, staged: through registers
@@ -682,6 +702,7 @@ nt_status launch_gemm(const GemmLaunch &g, int *path_out)
     if (path_out) *path_out = PATH_GENERIC;
     ConvArgs c{};
     if (!g.has_d && g.alpha == 1.f && g.act == 0 && match_conv(g, &c)) return route_conv_implicit(g, c, path_out);
+    if (g.trace.out) return fail(NT_ERR_UNSUPPORTED, "this launch does not run on the kernels that stream their operands into LDS");
     bool taken = false;
     nt_status st = route_conv_padded_copy(g, path_out, &taken);
     if (taken || st != NT_OK) return st;

@@ -18,6 +18,14 @@ struct ConvHint {
     int64_t xs[4], ws[4], ys[4];
 };
 
+// Request for a loader trace instead of a product (nt_trace_loader_slice); out == nullptr: none.
+struct LoaderTrace {
+    uint16_t *out;
+    size_t capacity;
+    int64_t program;
+    int32_t slice, operand;
+};
+
 struct GemmLaunch {
     const void *A;
     const void *B;
@@ -43,6 +51,7 @@ struct GemmLaunch {
     float *ws_given;                        // inside the region the caller has set aside for it (ws_given_bytes; may be none)
     size_t ws_given_bytes;
     bool ws_strict;                         // a k split that would need more than ws_given_bytes is an error (else: run unsplit)
+    LoaderTrace trace;
 };
 
 // Which code path a launch would take (reported for tests and the benchmark).

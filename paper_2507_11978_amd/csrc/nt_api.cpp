@@ -137,7 +137,7 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
               void *C, const nt_tensor_desc *dC, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
               nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, void *stream,
               const void *D = nullptr, const nt_tensor_desc *dD = nullptr, float alpha = 1.f, float beta = 0.f,
-              const ViewPrograms *views = nullptr, int act = 0, bool static_ws = false)
+              const ViewPrograms *views = nullptr, int act = 0, bool static_ws = false, const nt::LoaderTrace *trace = nullptr)
 {
     t_last_path = -1;
     if (!dtype_in_ok(in_dtype)) return fail(NT_ERR_UNSUPPORTED, "input dtype must be NT_F16 or NT_BF16");
@@ -189,6 +189,7 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
     g.in_dtype = in_dtype;
     g.out_dtype = out_dtype;
     g.stream = stream;
+    if (trace) g.trace = *trace;
     if (static_ws) {
         // the library's workspace is out of bounds (it is allocated on first use); a k split goes through the fixed array
         void *p = nullptr;
@@ -437,6 +438,21 @@ nt_status nt_trace_tile(int32_t kind, const nt_tensor_desc *d0, const nt_tensor_
     else { row0 = i * p.tile.bm; col0 = j * p.tile.bn; rows = p.tile.bm; cols = p.tile.bn; }
     if ((size_t)rows * (size_t)cols > capacity) return fail(NT_ERR_BUFFER_TOO_SMALL, "trace buffers smaller than the tile");
     return nt::launch_trace(m, b * bstride, row0, col0, rows, cols, offsets_out, mask_out, hip_stream);
+}
+
+nt_status nt_trace_loader_slice(int32_t kind, const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
+                                const nt_tensor_desc *dC, int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                                nt_dtype in_dtype, nt_dtype out_dtype, nt_tile_cfg cfg, int32_t operand, int64_t program_id, int64_t slice,
+                                uint16_t *values_out, size_t capacity, void *hip_stream)
+{
+    if (kind < KIND_GEMM || kind > KIND_CONV) return fail(NT_ERR_INVALID_ARG, "kind must be 0 (gemm), 1 (bmm) or 2 (conv2d)");
+    if (operand != NT_OPERAND_A && operand != NT_OPERAND_B) return fail(NT_ERR_INVALID_ARG, "operand must be 0 (A) or 1 (B)");
+    if (!values_out) return fail(NT_ERR_INVALID_ARG, "null output pointer");
+    const nt::LoaderTrace tr{values_out, capacity, program_id, (int32_t)slice, operand};
+    if (slice < 0 || slice > 0x7fffffff) return fail(NT_ERR_INVALID_ARG, "slice outside the reduction");
+    // (the output pointer only has to be non-null: a trace stores nothing through it)
+    return run(kind, A, dA, B, dB, values_out, dC, stride_h, stride_w, pad_h, pad_w, in_dtype, out_dtype, cfg, hip_stream,
+               nullptr, nullptr, 1.f, 0.f, nullptr, 0, false, &tr);
 }
 
 nt_status nt_mfma_probe(const void *data, int64_t n_elems, nt_dtype dtype, int32_t iters, int32_t blocks, float *out, void *hip_stream)
