@@ -152,7 +152,9 @@ nt_status nt_program_order(int64_t batch, int64_t mt, int64_t nt, int64_t *pid_o
 /* Which kernel the calling thread's last nt_gemm / nt_addmm / nt_addmm_act / nt_bmm / nt_conv2d_implicit call launched:
  * 0 operand-map (generic) kernel, 1 staged kernel, 2 direct-to-LDS kernel, 3 convolution kernel (operands staged
  * through registers), 4 convolution kernel (operands streamed straight into LDS), 5 unfolded input written to the
- * workspace + the matrix kernels,
+ * workspace + the matrix kernels, 6 convolution kernel that streams into LDS and walks the reduction filter tap by filter
+ * tap (256 filters per program, channels in whole blocks of 32; reads a tap-major copy of the filter that it puts in the
+ * workspace),
  * -1 none (nothing launched yet, an error, or an empty problem).  For tests and diagnostics. */
 int32_t nt_last_kernel_path(void);
 
@@ -299,7 +301,8 @@ nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const n
  * out-of-image positions (padding) read as zero.  dy must have P = (H + 2*pad_h - R) /
  * stride_h + 1 (integer division), likewise Q; otherwise NT_ERR_SHAPE_MISMATCH.
  * Descriptors have ndim 4 with arbitrary strides.
- * Dense unit-stride calls (contiguous NCHW input, at most one column of padding) never materialise anything.  The
+ * Dense unit-stride calls (contiguous NCHW input, at most one column of padding) never materialise the unfolded input; with
+ * more than 128 filters and channels in whole blocks of 32 they copy the filter (only) into the workspace in tap-major order.  The
  * other convolutions on the library's own tile go through the library's workspace when what they need fits it:
  * unit-stride ones (wide padding, channels-last views) make a dense zero-padded copy of the input and run on that;
  * strided ones write the unfolded input once and run the product on the matrix kernels.  Else, or with a tile
@@ -346,8 +349,10 @@ nt_status nt_trace_tile(int32_t kind, const nt_tensor_desc *d0, const nt_tensor_
  * source element the loader put there, and zero where it fed a zero: compare with nt_arrange_* / the arrangement.
  * A, B: device pointers, read.  dC: the output's descriptor (shape only; nothing is stored).  values_out: DEVICE array of
  * `capacity` entries, at least 32 * (tile rows of the operand).  Only launches that stream their operands straight into LDS
- * (nt_last_kernel_path() 2 or 4 for the same arguments) can be traced: otherwise NT_ERR_UNSUPPORTED.  The ring-unrolled
+ * (nt_last_kernel_path() 2, 4 or 6 for the same arguments) can be traced: otherwise NT_ERR_UNSUPPORTED.  The ring-unrolled
  * variant of the 256 x 256 kernel has the same per-lane offsets and slice stepping as the kernel traced here.
+ * Path 6 sums over the reduction index in another order than the arrangement lists it: its slice s, index kk is channel
+ * c = 32 (s % (C / 32)) + kk of filter tap t = s / (C / 32), i.e. the arrangement's k = c * R * S + t.
  */
 nt_status nt_trace_loader_slice(int32_t kind, const void *A, const nt_tensor_desc *dA, const void *B, const nt_tensor_desc *dB,
                                 const nt_tensor_desc *dC, int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,

@@ -343,7 +343,7 @@ def mfma_probe(data, out, iters=2000, blocks=1024, stream=None):
     return 2.0 * 16 * 16 * 32 * 64 * iters * 4 * blocks
 
 
-PATH_GENERIC, PATH_STAGED, PATH_DIRECT, PATH_CONV, PATH_CONV_DIRECT, PATH_CONV_UNFOLD = 0, 1, 2, 3, 4, 5
+PATH_GENERIC, PATH_STAGED, PATH_DIRECT, PATH_CONV, PATH_CONV_DIRECT, PATH_CONV_UNFOLD, PATH_CONV_TAP = 0, 1, 2, 3, 4, 5, 6
 
 
 def last_kernel_path() -> int:

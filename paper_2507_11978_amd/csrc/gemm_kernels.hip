@@ -2,6 +2,7 @@
 #include <mutex>
 
 #include "gemm_conv_direct.h"
+#include "gemm_conv_tap.h"
 #include "gemm_direct.h"
 #include "gemm_direct16.h"
 
@@ -415,6 +416,32 @@ static float *split_region(const GemmLaunch &g, size_t bytes, WorkspaceLease &le
     return (float *)lease.acquire(bytes, (hipStream_t)g.stream);
 }
 
+// operands that can stream straight into LDS: whole 32-k slices, 16-byte aligned filter rows, 32-bit byte offsets
+static bool conv_direct_ok(const GemmLaunch &g, const ConvArgs &c)
+{
+    return c.K % 32 == 0 && c.ldb % 8 == 0 && (reinterpret_cast<uintptr_t>(c.Wt) & 15) == 0 && c.R <= 8 && c.S <= 8 &&
+           c.x_numel < (1LL << 30) && ((int64_t)(c.N - 1) * c.ldb + c.K) < (1LL << 30) &&
+           ((g.conv.N - 1) * c.syn + (int64_t)(c.N - 1) * c.syf + c.PQ) < (1LL << 29);   // (output offsets: 31 bits of bytes)
+}
+
+// ... and that the kernel which walks the reduction tap by tap takes (gemm_conv_tap.h): 256 filters per program, channels in
+// whole blocks of 32, padding smaller than the image; it reads the filter from a tap-major copy of `*repack_bytes` bytes
+static bool conv_tap_ok(const GemmLaunch &g, const ConvArgs &c, size_t *repack_bytes)
+{
+    *repack_bytes = ((size_t)c.N * c.K * 2 + 255) / 256 * 256;
+    return conv_direct_ok(g, c) && g.tile.bn == 256 && c.N > 128 && g.conv.C % 32 == 0 && c.ph < c.H && c.pw < c.W;
+}
+
+// workspace that route 1 asks for: the filter's tap-major copy, then the fp32 slices of the k split
+static size_t conv_scratch_need(const GemmLaunch &g, const ConvArgs &c)
+{
+    size_t repack = 0;
+    const bool tap = conv_tap_ok(g, c, &repack);
+    int32_t kt_per = 0;
+    const int ks = conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
+    return (tap ? repack : 0) + (ks > 1 ? (size_t)ks * g.conv.N * c.N * c.PQ * 4 : 0);
+}
+
 // ---- route 1: the dense unit-stride convolution on the implicit-GEMM kernels (with the k split for small grids)
 static nt_status route_conv_implicit(const GemmLaunch &g, const ConvArgs &c, int *path_out)
 {
@@ -425,40 +452,55 @@ static nt_status route_conv_implicit(const GemmLaunch &g, const ConvArgs &c, int
     int32_t kt_per = 0;
     const int ksplit = g.trace.out ? 1 : conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
     const int64_t slice = g.conv.N * (int64_t)c.N * c.PQ;
+    const bool direct = conv_direct_ok(g, c);
+    size_t repack_bytes = 0;
+    bool tap = conv_tap_ok(g, c, &repack_bytes);
+    const size_t split_bytes = ksplit > 1 ? (size_t)ksplit * slice * 4 : 0;
+    // one piece of workspace: the filter's copy, then the split's slices.  None to be had (too large, no memory, a caller
+    // who holds the workspace and has set aside less): the copy is given up first (the kernel in the arrangement's k
+    // order needs none), then the split.
     WorkspaceLease lease;
-    float *ws = nullptr;                                     // (none: too large, or no memory; then no split)
-    if (ksplit > 1) {
+    char *region = nullptr;
+    if (tap || ksplit > 1) {
         nt_status st;
-        ws = split_region(g, (size_t)ksplit * slice * 4, lease, &st);
+        region = (char *)split_region(g, (tap ? repack_bytes : 0) + split_bytes, lease, &st);
+        if (!region && tap) {
+            tap = false;
+            if (ksplit > 1) region = (char *)split_region(g, split_bytes, lease, &st);
+        }
         if (st != NT_OK) return st;
     }
-    // operands that can stream straight into LDS: whole 32-k slices, 16-byte aligned filter rows, 32-bit byte offsets
-    // (the k split's workspace, at most 256 MB, always has them)
-    const bool direct = c.K % 32 == 0 && c.ldb % 8 == 0 && (reinterpret_cast<uintptr_t>(c.Wt) & 15) == 0 && c.R <= 8 && c.S <= 8 &&
-                        c.x_numel < (1LL << 30) && ((int64_t)(c.N - 1) * c.ldb + c.K) < (1LL << 30) &&
-                        ((g.conv.N - 1) * c.syn + (int64_t)(c.N - 1) * c.syf + c.PQ) < (1LL << 29);   // (output offsets: 31 bits of bytes)
-    if (direct && path_out) *path_out = PATH_CONV_DIRECT;
+    uint16_t *wt_tap = tap ? (uint16_t *)region : nullptr;
+    float *ws = region && ksplit > 1 ? (float *)(region + (tap ? repack_bytes : 0)) : nullptr;
+    if (direct && path_out) *path_out = tap ? PATH_CONV_TAP : PATH_CONV_DIRECT;
     const bool bf16 = g.in_dtype == NT_BF16;
+    ConvArgs base = c;
+    if (tap) {
+        const nt_status st = launch_conv_repack_filter(c.Wt, c.ldb, wt_tap, c.N, (int32_t)g.conv.C, c.RS, s);
+        if (st != NT_OK) return st;
+        base.Wt = wt_tap;
+        base.ldb = c.K;
+    }
     if (g.trace.out) {
-        if (!direct) return fail(NT_ERR_UNSUPPORTED, "this convolution does not run on the kernel that streams its operands into LDS");
+        if (!direct) return fail(NT_ERR_UNSUPPORTED, "this convolution does not run on the kernels that stream their operands into LDS");
         const int bn = c.N <= 64 ? 64 : (c.N <= 128 ? 128 : t.bn);
         const int64_t rows = g.trace.operand == 0 ? 256 : bn;
         if ((size_t)rows * 32 > g.trace.capacity) return fail(NT_ERR_BUFFER_TOO_SMALL, "trace buffer smaller than the slice");
         if (g.trace.program < 0 || g.trace.program >= c.mt * c.nt) return fail(NT_ERR_INVALID_ARG, "program_id outside the grid");
         if (g.trace.slice < 0 || g.trace.slice >= c.K / 32) return fail(NT_ERR_INVALID_ARG, "slice outside the reduction");
-        ConvArgs ca = c;
-        ca.trace_out = g.trace.out; ca.trace_program = g.trace.program; ca.trace_slice = g.trace.slice; ca.trace_operand = g.trace.operand;
-        return launch_conv_direct_trace(ca, bn, s);
+        base.trace_out = g.trace.out; base.trace_program = g.trace.program; base.trace_slice = g.trace.slice; base.trace_operand = g.trace.operand;
+        return tap ? launch_conv_tap_trace(base, s) : launch_conv_direct_trace(base, bn, s);
     }
     auto launch = [&](const ConvArgs &ca, int64_t nwg) {
+        if (tap) return launch_conv_tap(ca, bf16, nwg, s);
         // (one column of tiles with few filters: the same grid is run by the kernel built for 64 or 128 filters per
         // program, which spends a quarter or half of the MFMAs)
         const int bn = ca.N <= 64 && direct ? 64 : (ca.N <= 128 ? 128 : t.bn);
         return direct ? launch_conv_direct(ca, bn, bf16, nwg, s) : launch_conv(ca, bn, bf16, edge_b || (ca.N % bn) != 0, nwg, s);
     };
-    if (!ws) return launch(c, c.mt * c.nt);
+    if (!ws) return launch(base, c.mt * c.nt);
     t_k_split = ksplit;
-    ConvArgs part = c;
+    ConvArgs part = base;
     part.Y = ws; part.syn = (int64_t)c.N * c.PQ; part.syf = c.PQ; part.out_dtype = NT_F32;
     part.ksplit = ksplit; part.kt_per = kt_per; part.slice = slice;
     const nt_status st = launch(part, c.mt * c.nt * ksplit);
@@ -489,10 +531,8 @@ static nt_status route_conv_padded_copy(const GemmLaunch &g, int *path_out, bool
     ConvArgs probe{};
     const size_t bytes = ((size_t)((total + 7) / 8 * 8) * 2 + 255) / 256 * 256;
     if (!(Hp * Wp >= 8 && total < (1LL << 31) && match_conv(g2, &probe))) return NT_OK;
-    // the copy and, behind it, the slices of the k split that the convolution will ask for
-    int32_t kt_per = 0;
-    const int ks = conv_ksplit(probe.mt * probe.nt, probe.kt, &kt_per);
-    size_t split_bytes = ks > 1 ? (size_t)ks * h.N * probe.N * probe.PQ * 4 : 0;
+    // the copy and, behind it, what the convolution on it will ask for (the filter's tap-major copy, the k split's slices)
+    size_t split_bytes = conv_scratch_need(g2, probe);
     if (bytes + split_bytes > kSplitWsMax) split_bytes = 0;
     WorkspaceLease lease;
     uint16_t *P = (uint16_t *)lease.acquire(bytes + split_bytes, (hipStream_t)g.stream);

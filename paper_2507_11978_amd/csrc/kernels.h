@@ -55,7 +55,7 @@ struct GemmLaunch {
 };
 
 // Which code path a launch would take (reported for tests and the benchmark).
-enum KernelPath { PATH_GENERIC = 0, PATH_FAST = 1, PATH_DIRECT = 2, PATH_CONV = 3, PATH_CONV_DIRECT = 4, PATH_CONV_UNFOLD = 5 };
+enum KernelPath { PATH_GENERIC = 0, PATH_FAST = 1, PATH_DIRECT = 2, PATH_CONV = 3, PATH_CONV_DIRECT = 4, PATH_CONV_UNFOLD = 5, PATH_CONV_TAP = 6 };
 
 bool tile_is_built(nt_tile_cfg cfg);
 // into how many parts the calling thread's last launch_gemm split its reduction (1: no split)

@@ -133,6 +133,10 @@ def whole_matrix(view, n_row_tiles, n_col_tiles, kt, pid_of, rows_first):
     (2, 32, 12, 13, 130, 3, 3, (1, 0)),       # padding above and below only, rows of 11
     (1, 32, 9, 12, 64, 3, 5, (0, 1)),         # 3 x 5 filter, one column of padding
     (2, 96, 8, 8, 64, 1, 1, (0, 0)),          # 1 x 1 filter
+    (2, 64, 14, 14, 256, 3, 3, (1, 1)),       # 256 filters, channels in blocks of 32: the tap-major kernel; rows of 14, padding
+    (3, 32, 16, 16, 300, 3, 3, (1, 1)),       # the same with one channel block per tap, rows of 16, a ragged last filter tile
+    (1, 64, 9, 9, 192, 2, 2, (0, 1)),         # 2 x 2 filter, rows of 9 (a run that starts in the right padding)
+    (2, 32, 6, 20, 256, 5, 3, (1, 1)),        # 5 x 3 filter
 ])
 def test_convolution(Nn, C, H, W, F, R, S, pad):
     dt = "f16"
@@ -158,7 +162,12 @@ def test_convolution(Nn, C, H, W, F, R, S, pad):
         i, j = pid // nto, pid % nto
         for sl in sorted({0, 1, n_slices // 2, n_slices - 1}):
             ks = slice(32 * sl, 32 * sl + 32)
-            got = loader_offsets("conv2d", shx, sx, shw, sw, shy, dt, 0, pid, sl, tile=tile, pad=pad, want_path=nt.PATH_CONV_DIRECT)
+            got = loader_offsets("conv2d", shx, sx, shw, sw, shy, dt, 0, pid, sl, tile=tile, pad=pad)
+            path = nt.last_kernel_path()
+            assert path == (nt.PATH_CONV_TAP if F > 128 and C % 32 == 0 else nt.PATH_CONV_DIRECT)
+            if path == nt.PATH_CONV_TAP:        # the reduction is walked tap by tap: slice sl = 32 channels of one tap
+                cb = C // 32
+                ks = (32 * (sl % cb) + np.arange(32)) * (R * S) + sl // cb
             for r in range(256):
                 m = i * 256 + r
                 n, p, q = m // (P * Q8), (m % (P * Q8)) // Q8, m % Q8

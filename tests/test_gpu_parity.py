@@ -347,7 +347,7 @@ def test_conv2d_dense_unit_stride(shape, pad, tile, dt, out):
     nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), pad, tile=tile)
     torch.cuda.synchronize()
     # whole 32-k slices (C * R * S a multiple of 32) stream straight into LDS, other reductions are staged through registers
-    assert nt.last_kernel_path() == (nt.PATH_CONV_DIRECT if (Cc * R * S) % 32 == 0 else nt.PATH_CONV)
+    assert nt.last_kernel_path() in ((nt.PATH_CONV_DIRECT, nt.PATH_CONV_TAP) if (Cc * R * S) % 32 == 0 else (nt.PATH_CONV,))
     assert_gates(to_f64(Y), ref, out, f"conv dense {shape} {pad} {tile}")
 
 
@@ -517,7 +517,7 @@ def test_conv2d_dense_rows_that_are_no_multiple_of_eight(shape, pad):
         Y = buf[32:32 + ref.size].view(ref.shape)
         nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), pad)
         torch.cuda.synchronize()
-        assert nt.last_kernel_path() == (nt.PATH_CONV_DIRECT if (Cc * R * S) % 32 == 0 else nt.PATH_CONV)
+        assert nt.last_kernel_path() in ((nt.PATH_CONV_DIRECT, nt.PATH_CONV_TAP) if (Cc * R * S) % 32 == 0 else (nt.PATH_CONV,))
         # the sums are integers below 2^24: exact in fp32, then rounded once (to nearest even) to the output format
         want = torch.from_numpy(ref).to(torch.float32).to(TORCH_DT[out])
         assert torch.equal(Y.cpu(), want), f"conv {shape} {pad} {dt} {out}"
@@ -544,7 +544,7 @@ def test_conv2d_dense_split_along_k(shape, pad):
         Y = big[:, 2:K + 2]
         nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), pad)
         torch.cuda.synchronize()
-        assert nt.last_kernel_path() == (nt.PATH_CONV_DIRECT if (Cc * R * S) % 32 == 0 else nt.PATH_CONV)
+        assert nt.last_kernel_path() in ((nt.PATH_CONV_DIRECT, nt.PATH_CONV_TAP) if (Cc * R * S) % 32 == 0 else (nt.PATH_CONV,))
         assert nt.last_k_split() > 1
         # the sums are integers below 2^24: exact in fp32, then rounded once (to nearest even) to the output format
         want = torch.from_numpy(ref).to(torch.float32).to(TORCH_DT[out])
@@ -596,7 +596,7 @@ def test_conv2d_through_the_workspace(shape, stride, pad):
             nt.conv2d_implicit(x, to_gpu(Wt, dt), Y, stride, pad)
             torch.cuda.synchronize()
             if stride == (1, 1):
-                assert nt.last_kernel_path() == (nt.PATH_CONV_DIRECT if (Cc * R * S) % 32 == 0 else nt.PATH_CONV)
+                assert nt.last_kernel_path() in ((nt.PATH_CONV_DIRECT, nt.PATH_CONV_TAP) if (Cc * R * S) % 32 == 0 else (nt.PATH_CONV,))
             else:
                 assert nt.last_kernel_path() == nt.PATH_CONV_UNFOLD
             assert torch.equal(Y.cpu(), want), f"conv {shape} {stride} {pad} {dt} {out} channels_last={channels_last}"
