@@ -7,9 +7,12 @@
 // order.  This kernel takes it tap-major: kk' = (r * S + s) * C + c, for C a multiple of 32.  A slice is then 32 consecutive
 // channels of ONE tap, and everything that depends on the tap -- whether a run's input row lies in the top / bottom
 // padding, whether its first or last element lies in the left / right padding -- is the same for the C / 32 slices of
-// that tap and is recomputed only when the tap changes.  Per slice a load costs one addition: the lane's run offset
+// that tap: one bit per tap and lane, tested per slice.  Per slice a load costs one addition: the lane's run offset
 // (fixed) plus the slice's scalar offset c0 * H W + r * W + s.  The ring of four slices is unrolled as in
-// gemm_direct16u_kernel (LDS addresses are immediates, load targets precomputed scalars).
+// gemm_direct16u_kernel (LDS addresses are immediates, load targets precomputed scalars), and all of a slice's
+// bookkeeping -- the two walks over the slices, the tests -- is branch-free and sits between the matrix instructions
+// (whatever precedes a trip's first matrix instruction is time in which the matrix pipe idles: with that bookkeeping in
+// front of every trip, under branches, a trip took 1.6 times the time of its matrix instructions).
 // The filter is read from a copy in tap-major order, [filter][r * S + s][c], made by launch_conv_repack_filter.
 //
 // Runs that cannot be fetched as they are (see gemm_conv_direct.h for the layout and the numbering of positions):
@@ -25,16 +28,20 @@
 
 namespace nt {
 
-template <bool BF16, bool TRACE = false>
+// TM: the program's tile is 32 TM positions high (224 or 256; the LDS slots are laid out for 256 either way).  The host picks
+// the height that fills the chip's rounds best: 392 tiles of 256 positions are 1.53 rounds of 256 programs and cost two,
+// 448 tiles of 224 cost two rounds of 7/8 the length.
+template <bool BF16, int TM, bool TRACE = false>
 __global__ __launch_bounds__(kThreads, 1) void gemm_conv_tap_kernel(const ConvArgs g)
 {
-    constexpr int BM = 256, BN = 256;
-    constexpr int TM = BM / 32, TN = BN / 32;
+    constexpr int BM = 32 * TM, BN = 256;
+    constexpr int TN = BN / 32;
+    constexpr int SLOT_M = 256;                             // positions per LDS slot
     constexpr int kRing = 4;
     using TileB = DirectTile16<BN, KCONTIG>;
     constexpr int PER = 4;                                  // loads of the input per wavefront and slice
-    constexpr int RB = 2 * BM;                              // bytes per kk row of the input's slice
-    constexpr uint32_t A_BYTES = BM * kSliceK * 2, B_BYTES = TileB::BYTES, B_BASE = kRing * A_BYTES;
+    constexpr int RB = 2 * SLOT_M;                          // bytes per kk row of the input's slice
+    constexpr uint32_t A_BYTES = SLOT_M * kSliceK * 2, B_BYTES = TileB::BYTES, B_BASE = kRing * A_BYTES;
     constexpr uint32_t kOutside = 0x80000000u;
     static_assert(TileB::PER == 4 && TileB::RPF == 1, "schedule of the trip");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -61,34 +68,37 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_conv_tap_kernel(const ConvAr
     tb.init(wave, lane, g.ldb, wave_n * (BN / 2), B_BASE);
     const u32x4 rsrc_a = make_rsrc(g.X, g.x_numel * 2);
     const u32x4 rsrc_b = make_rsrc(gB, ((int64_t)(g.N - 1) * g.ldb + g.K) * 2 - (gB - gB0));
-    const u32x4 rsrc_z = u32x4{rsrc_a[0], rsrc_a[1], 0u, rsrc_a[3]};      // nothing is inside: every load reads zeros
 
-    // ---- the input: per-lane state
-    int32_t base[2];               // element offset of x[n, 0, p - ph, q0 - pw] of the lane's two runs (see ConvTileA)
-    uint32_t masks[2];             // bits 0..7: input row p + r - ph inside the image (and m < M); bit 8 + 2 s / 9 + 2 s: with tap
-                                   // column s the run's first element / its element last_e is padding
+    // ---- the input: per-lane state.  A lane owns two runs of 8 positions (see ConvTileA); per run, one bit per filter tap
+    // t = r * S + s (the host admits R * S <= 32):
+    //   rows_in: the tap's input row p + r - ph lies inside the image (and the run's positions exist);
+    //   pad_first / pad_last: rows_in, and with the tap's column s the run's first element / its element last_e is padding.
+    int32_t base[2];               // element offset of x[n, 0, p - ph, q0 - pw]
+    uint32_t rows_in[2], pad_first[2], pad_last[2];
     bool risk_lo = false, risk_hi = false;
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
         const int chunk = (lane & 31) ^ (((2 * e + hi) << 2) | ((wave & 1) << 1));
         const int64_t m = row0 + chunk * 8;
-        const bool m_ok = m < g.M;
+        const bool m_ok = m < g.M && chunk * 8 < BM;
         const uint32_t mm = m_ok ? (uint32_t)m : 0u;
         const uint32_t nn = mm / (uint32_t)g.PQ8;
         const uint32_t pq = mm - nn * (uint32_t)g.PQ8;
         const uint32_t p = pq / (uint32_t)g.Q8;
         const int32_t q0 = (int32_t)(pq - p * (uint32_t)g.Q8);
         base[e] = (int32_t)(nn * (uint32_t)g.CHW) + ((int32_t)p - g.ph) * g.W + q0 - g.pw;
-        uint32_t mk = 0;
+        uint32_t in = 0, pf = 0, pl = 0;
         for (int rr = 0; rr < g.R; ++rr) {
             const int h = (int)p + rr - g.ph;
-            if (m_ok && h >= 0 && h < g.H) mk |= 1u << rr;
+            if (!(m_ok && h >= 0 && h < g.H)) continue;
+            for (int sx = 0; sx < g.S; ++sx) {
+                const uint32_t bit = 1u << (rr * g.S + sx);
+                in |= bit;
+                if (q0 + sx - g.pw < 0) pf |= bit;
+                if (q0 + 8 >= g.Q && g.Q - 1 + sx - g.pw >= g.W) pl |= bit;
+            }
         }
-        for (int sx = 0; sx < g.S; ++sx) {
-            if (q0 + sx - g.pw < 0) mk |= 0x100u << (2 * sx);
-            if (q0 + 8 >= g.Q && g.Q - 1 + sx - g.pw >= g.W) mk |= 0x200u << (2 * sx);
-        }
-        masks[e] = mk;
+        rows_in[e] = in; pad_first[e] = pf; pad_last[e] = pl;
         // (conservative: a run of this lane may start before x in channel 0, or end after x in the last channel)
         risk_lo |= m_ok && base[e] < 0;
         risk_hi |= m_ok && (int64_t)base[e] + (int64_t)(g.CHW - g.HW) + (g.R - 1) * g.W + (g.S - 1) + 8 > g.x_numel;
@@ -99,56 +109,77 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_conv_tap_kernel(const ConvAr
 #pragma unroll
     for (int j = 0; j < PER; ++j) rowoff[j] = 2u * (uint32_t)(base[j & 1] + (8 * wave + 2 * j + hi) * g.HW);   // (wraps for the few negative ones)
     const uint32_t clr = (uint32_t)(wave * PER * 1024 + lane * 16);      // this lane's chunk inside a slice, load 0
+    const uint32_t clr_last = clr + 2u * (uint32_t)g.last_e;
     // transposing reads of the input's fragments (see DirectTile16<E, MNCONTIG>)
     uint32_t rd[TM];
     {
         const int gq = lane >> 4, i = lane & 15;
         const int kl = 8 * gq + (i >> 2);
         const int mn = wave_m * (BM / 2) + 4 * (i & 3);
-        const int sw = DirectTile16<BM, MNCONTIG>::swizzle(kl);
+        const int sw = DirectTile16<SLOT_M, MNCONTIG>::swizzle(kl);
 #pragma unroll
         for (int t = 0; t < TM; ++t) rd[t] = (uint32_t)(kl * RB + ((((mn >> 3) + 2 * t) ^ sw) << 4) + ((mn >> 2) & 1) * 8);
     }
 
-    // ---- the two walks over the program's slices (all scalar): the slice requested next, and the slice fixed up next
+    // ---- two walks over the program's slices, all scalar and branch-free: the slice requested next, the slice fixed up next
+    // (each walk's step is cut into pieces of a few instructions, which the trip places behind different matrix instructions)
+    struct Walk { int32_t idx, cblk, r, s, tap; bool wrap; };
     const int32_t sl0 = k_first / kSliceK;
-    int32_t rq_cblk = sl0 % cb, rq_r = (sl0 / cb) / g.S, rq_s = (sl0 / cb) % g.S, rq_left = n_slices;
-    uint32_t rq_aoff = 2u * (uint32_t)(rq_cblk * kSliceK * g.HW + rq_r * g.W + rq_s), rq_boff = 0;
-    int32_t st_cblk = rq_cblk, st_r = rq_r, st_s = rq_s, st_left = n_slices;
-    auto retap_request = [&]() {                             // (after a change of rq_r: which runs are padding rows)
-#pragma unroll
-        for (int j = 0; j < PER; ++j) voff[j] = (masks[j & 1] >> rq_r) & 1u ? rowoff[j] : kOutside;
+    const Walk first{0, sl0 % cb, (sl0 / cb) / g.S, (sl0 / cb) % g.S, sl0 / cb, false};
+    auto step_a = [&](Walk &w) {
+        w.wrap = w.cblk + 1 == cb;
+        ++w.idx;
+        w.cblk = w.wrap ? 0 : w.cblk + 1;
+        w.tap += w.wrap ? 1 : 0;
     };
-    bool cf[2], cl[2], any_clear;
-    auto retap_settle = [&]() {
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            cf[e] = (masks[e] >> (8 + 2 * st_s)) & 1u & (masks[e] >> st_r);
-            cl[e] = (masks[e] >> (9 + 2 * st_s)) & 1u & (masks[e] >> st_r);
+    auto step_b = [&](Walk &w) {
+        const int32_t s1 = w.s + (w.wrap ? 1 : 0);
+        const bool wrap_s = s1 == g.S;
+        w.s = wrap_s ? 0 : s1;
+        w.r += wrap_s ? 1 : 0;
+    };
+    Walk rq = first, st = first;
+    // request side: the slice's offsets, which loads fetch a padding row, and the resources (past the program's last slice:
+    // records of length zero, so that zeros arrive)
+    uint32_t rq_aoff, rq_boff;
+    u32x4 ra = rsrc_a, rb = rsrc_b;
+    auto aim_request_a = [&]() {
+        rq_aoff = 2u * (uint32_t)(rq.cblk * kSliceK * g.HW + rq.r * g.W + rq.s);
+        rq_boff = (uint32_t)rq.idx * (kSliceK * 2);
+    };
+    auto aim_request_b = [&](int e) {
+        const bool in = (rows_in[e] & (1u << (rq.tap & 31))) != 0;
+        voff[e] = in ? rowoff[e] : kOutside;
+        voff[e + 2] = in ? rowoff[e + 2] : kOutside;
+    };
+    auto aim_request_c = [&]() {
+        const bool live = rq.idx < n_slices;                                       // (uniform)
+        ra[2] = live ? rsrc_a[2] : 0u;
+        rb[2] = live ? rsrc_b[2] : 0u;
+    };
+    auto step_request = [&]() { step_a(rq); step_b(rq); };
+    auto aim_request = [&]() { aim_request_a(); aim_request_b(0); aim_request_b(1); aim_request_c(); };
+    // fix-up side: which of this lane's runs have a padding element to clear (as wavefront masks), and whether this wavefront
+    // has to look for runs that cross an end of x
+    uint64_t mf0, mf1, ml0, ml1;
+    uint32_t st_bit;
+    bool hazard;
+    auto aim_settle_a = [&]() {
+        const bool live = st.idx < n_slices;                                       // (a slice past the last is zeros and stays so)
+        st_bit = live ? 1u << (st.tap & 31) : 0u;
+        hazard = live & ((any_lo & (st.cblk == 0)) | (any_hi & (st.cblk == cb - 1)));
+    };
+    auto aim_settle_b = [&](int e) {
+        if (e == 0) {
+            mf0 = __builtin_amdgcn_ballot_w64((pad_first[0] & st_bit) != 0);
+            ml0 = __builtin_amdgcn_ballot_w64((pad_last[0] & st_bit) != 0);
+        } else {
+            mf1 = __builtin_amdgcn_ballot_w64((pad_first[1] & st_bit) != 0);
+            ml1 = __builtin_amdgcn_ballot_w64((pad_last[1] & st_bit) != 0);
         }
-        any_clear = __builtin_amdgcn_ballot_w64(cf[0] || cf[1] || cl[0] || cl[1]) != 0;
     };
-    retap_request();
-    retap_settle();
-    auto advance_request = [&]() {
-        --rq_left;
-        rq_boff += kSliceK * 2;
-        rq_aoff += 2u * (uint32_t)(kSliceK * g.HW);
-        if (++rq_cblk == cb) {                               // (uniform)
-            rq_cblk = 0;
-            if (++rq_s == g.S) { rq_s = 0; ++rq_r; }
-            rq_aoff = 2u * (uint32_t)(rq_r * g.W + rq_s);
-            retap_request();
-        }
-    };
-    auto advance_settle = [&]() {
-        --st_left;
-        if (++st_cblk == cb) {                               // (uniform)
-            st_cblk = 0;
-            if (++st_s == g.S) { st_s = 0; ++st_r; }
-            retap_settle();
-        }
-    };
+    auto step_settle = [&]() { step_a(st); step_b(st); };
+    auto aim_settle = [&]() { aim_settle_a(); aim_settle_b(0); aim_settle_b(1); };
 
     float4v acc[TM][TN];
 #pragma unroll
@@ -161,7 +192,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_conv_tap_kernel(const ConvAr
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
     constexpr int NRA = 2 * TM, NRB = TN, NR = NRA + NRB;      // LDS reads per slice
     constexpr int NM = TM * TN, ND = PER + TileB::PER;
-    static_assert(2 * NR <= NM * 3 / 2 && 8 * ND <= NM, "the trip's schedule: a read every other matrix instruction, a load every eighth");
+    // The trip's schedule: PRE matrix instructions before the barrier; after it an LDS read behind every other one; the
+    // pieces of the request walk's step behind the odd ones of the first HOLD; the halves of load d behind the 2nd and 4th
+    // of the d-th group of STEP from then on; the pieces of the settle walk's step behind the 1st of the first groups.
+    constexpr int PRE = 8, HOLD = 11, STEP = (NM - PRE - HOLD) / ND;
+    static_assert(2 * NR <= NM - PRE && STEP >= 4, "the trip's schedule");
     uint32_t tgt[kRing][ND];                                   // LDS targets of this wavefront's loads, per ring position: scalars
 #pragma unroll
     for (int r = 0; r < kRing; ++r)
@@ -184,118 +219,153 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_conv_tap_kernel(const ConvAr
         else read_a(r - NRB, set, ring);
     };
     // load d of the slice the request walk stands at, into ring position `ring`; in two halves that go behind different
-    // matrix instructions (see gemm_direct16u_kernel).  ra / rb: the operands' resources, or rsrc_z past the program's last slice.
-    auto dma_aim = [&](int d, int ring) { asm volatile("s_mov_b32 m0, %0" : : "s"(tgt[ring][d]) : "memory"); };
+    // matrix instructions (see gemm_direct16u_kernel).  ra / rb: the operands' resources (of length zero past the program's last slice).
+    // (loads of the input, two thirds of which start at an odd element and keep the texture addresser busy four times as long,
+    // alternate with loads of the filter: i-th load = input load i / 2 or filter load i / 2)
+    auto nth = [](int i) { return i % 2 == 0 ? i / 2 : PER + i / 2; };
+    uint32_t a_at = 0;                                         // (the input load's address: computed a matrix instruction ahead of the load)
+    auto dma_aim = [&](int d, int ring) {
+        asm volatile("s_mov_b32 m0, %0" : : "s"(tgt[ring][d]) : "memory");
+        if (d < PER) { a_at = voff[d] + rq_aoff; asm volatile("" : "+v"(a_at)); }
+    };
     auto dma_go = [&](int d, const u32x4 &ra, const u32x4 &rb) {
         if (d < PER) {
-            const uint32_t at = voff[d] + rq_aoff;
-            asm volatile("buffer_load_dwordx4 %0, %1, 0 offen lds" : : "v"(at), "s"(ra) : "memory");
+            asm volatile("buffer_load_dwordx4 %0, %1, 0 offen lds" : : "v"(a_at), "s"(ra) : "memory");
         } else {
             asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds" : : "v"(tb.voff[d - PER]), "s"(rb), "s"(rq_boff) : "memory");
         }
     };
 
-    // What a slice needs once it has landed at ring position `ring` (the settle walk stands at it).
-    auto zero16 = [&](uint32_t at) { *reinterpret_cast<uint16_t *>(smem + at) = 0; };
-    auto settle = [&](uint32_t ring) {
-        if (st_left <= 0) return;                                                        // (uniform: a slice past the last is zeros and stays so)
-        if ((any_lo && st_cblk == 0) || (any_hi && st_cblk == cb - 1)) {                 // (uniform, first / last programs only)
+    // What the slice the settle walk stands at needs once this wavefront's part of it has landed at ring position RING.
+    // Common: the padding elements of runs are overwritten with zero, under the four wavefront masks (every lane is active
+    // here; the execution mask is put back before the statement ends).  Rare: runs that cross an end of x.
+    auto settle = [&](auto ring_c) {
+        constexpr uint32_t o = decltype(ring_c)::value * A_BYTES;
+        if (hazard) {                                                                    // (uniform, first / last programs only)
             const int32_t lim = (int32_t)g.x_numel;
 #pragma unroll
             for (int j = 0; j < PER; ++j) {
-                const int32_t l_off = base[j & 1] + ((st_cblk * kSliceK + 8 * wave + 2 * j + hi) * g.HW + st_r * g.W + st_s);
-                const bool row_in = (masks[j & 1] >> st_r) & 1u;
+                const int32_t l_off = base[j & 1] + ((st.cblk * kSliceK + 8 * wave + 2 * j + hi) * g.HW + st.r * g.W + st.s);
+                const bool row_in = (rows_in[j & 1] >> (st.tap & 31)) & 1u;
                 if (row_in && (l_off < 0 || l_off + 8 > lim)) {
-                    const uint32_t at = ring * A_BYTES + clr + (uint32_t)(j * 1024);
+                    const uint32_t at = o + clr + (uint32_t)(j * 1024);
                     for (int i = 0; i < 8; ++i) {
                         const int32_t idx = l_off + i;
                         *reinterpret_cast<uint16_t *>(smem + at + 2 * i) = idx >= 0 && idx < lim ? g.X[idx] : (uint16_t)0;
                     }
                 }
             }
+            __builtin_amdgcn_s_waitcnt(0xc07f);                                           // (those LDS writes before the ones below: lgkmcnt(0))
         }
-        if (any_clear) {                                                                 // (uniform)
-            const uint32_t at = ring * A_BYTES + clr, last = at + 2u * (uint32_t)g.last_e;
-            if (cf[0]) { zero16(at); zero16(at + 2048); }
-            if (cf[1]) { zero16(at + 1024); zero16(at + 3072); }
-            if (cl[0]) { zero16(last); zero16(last + 2048); }
-            if (cl[1]) { zero16(last + 1024); zero16(last + 3072); }
-        }
-        advance_settle();
+        const uint64_t f0 = mf0, f1 = mf1, l0 = ml0, l1 = ml1;
+        const uint32_t ca = clr, cl = clr_last;
+        asm volatile("s_mov_b64 exec, %[f0]\n\t"
+                     "ds_write_b16 %[a], %[z] offset:%[o0]\n\tds_write_b16 %[a], %[z] offset:%[o2]\n\t"
+                     "s_mov_b64 exec, %[f1]\n\t"
+                     "ds_write_b16 %[a], %[z] offset:%[o1]\n\tds_write_b16 %[a], %[z] offset:%[o3]\n\t"
+                     "s_mov_b64 exec, %[l0]\n\t"
+                     "ds_write_b16 %[b], %[z] offset:%[o0]\n\tds_write_b16 %[b], %[z] offset:%[o2]\n\t"
+                     "s_mov_b64 exec, %[l1]\n\t"
+                     "ds_write_b16 %[b], %[z] offset:%[o1]\n\tds_write_b16 %[b], %[z] offset:%[o3]\n\t"
+                     "s_mov_b64 exec, -1"
+                     :
+                     : [f0] "s"(f0), [f1] "s"(f1), [l0] "s"(l0), [l1] "s"(l1), [a] "v"(ca), [b] "v"(cl), [z] "v"(0u),
+                       [o0] "n"(o), [o1] "n"(o + 1024), [o2] "n"(o + 2048), [o3] "n"(o + 3072)
+                     : "memory");
     };
+    using std::integral_constant;
 
     if constexpr (TRACE) {
         for (int32_t s = 0; s <= g.trace_slice; ++s) {
+            if (s > 0) { step_request(); step_settle(); }
+            aim_request();
 #pragma unroll
             for (int d = 0; d < ND; ++d) {
                 dma_aim(d, 0);
                 asm volatile("s_nop 0");
-                dma_go(d, rsrc_a, rsrc_b);
+                dma_go(d, ra, rb);
             }
-            advance_request();
             NT_WAIT_VMCNT(0);
-            if (s < g.trace_slice) advance_settle();
         }
-        settle(0);
+        aim_settle();
+        settle(integral_constant<int, 0>{});
         __syncthreads();
         const bool first = g.trace_operand == 0;
         for (int e = tid; e < (first ? BM : BN) * kSliceK; e += kThreads) {
-            const uint32_t at = first ? DirectTile16<BM, MNCONTIG>::place(e / kSliceK, e % kSliceK) : B_BASE + TileB::place(e / kSliceK, e % kSliceK);
+            const uint32_t at = first ? DirectTile16<SLOT_M, MNCONTIG>::place(e / kSliceK, e % kSliceK) : B_BASE + TileB::place(e / kSliceK, e % kSliceK);
             g.trace_out[e] = *reinterpret_cast<const uint16_t *>(smem + at);
         }
         return;
     }
 
-    // One trip = one slice: the matrix instructions on fragment set SET; behind them the LDS reads of the next slice (ring
-    // position RING + 1) into the other set and the loads of the slice three further on into ring position RING.
+    // One trip = one slice: the matrix instructions on fragment set SET (slice s, in registers since the trip before).  This
+    // wavefront's part of slice s + 1 has landed (the caller has waited for it): it is fixed up, and while those LDS writes
+    // are on their way the first PRE matrix instructions go out; then the barrier, which says that slice s + 1 is complete
+    // and that every wavefront holds its fragments of slice s, so that slice s + 4 may overwrite it.  Behind the remaining
+    // matrix instructions: the LDS reads of slice s + 1 (ring position RING + 1) into the other set, the request walk's step
+    // to slice s + 4 and that slice's loads into ring position RING, and the settle walk's step to slice s + 2.
     auto trip = [&](auto ring_c, auto set_c) {
         constexpr int RING = decltype(ring_c)::value, SET = decltype(set_c)::value;
         constexpr int NXT = (RING + 1) % kRing;
-        const bool live = rq_left > 0;                             // (uniform)
-        const u32x4 ra = live ? rsrc_a : rsrc_z, rb = live ? rsrc_b : rsrc_z;
+        settle(integral_constant<int, NXT>{});
 #pragma unroll
         for (int idx = 0; idx < NM; ++idx) {
             const int tm = idx / TN, tn = idx % TN;
+            if (idx == PRE) __syncthreads();
             mfma16<BF16>(acc[tm][tn], fb[SET][tn], fa[SET][tm]);      // transposed block: a lane holds position lane % 16 (see conv_store_points16)
-            if (idx % 2 == 0 && idx / 2 < NR) lds_read(idx / 2, SET ^ 1, NXT);
-            if (idx % 8 == 1 && idx / 8 < ND) dma_aim(idx / 8, RING);
-            if (idx % 8 == 3 && idx / 8 < ND) dma_go(idx / 8, ra, rb);
+            if (idx >= PRE) {
+                const int i = idx - PRE;
+                if (i % 2 == 0 && i / 2 < NR) lds_read(i / 2, SET ^ 1, NXT);
+                if (i == 1) step_a(rq);
+                if (i == 3) step_b(rq);
+                if (i == 5) aim_request_a();
+                if (i == 7) aim_request_b(0);
+                if (i == 9) { aim_request_b(1); aim_request_c(); }
+                if (i >= HOLD) {
+                    const int k = i - HOLD;
+                    if (k % STEP == 1 && k / STEP < ND) dma_aim(nth(k / STEP), RING);
+                    if (k % STEP == 3 && k / STEP < ND) dma_go(nth(k / STEP), ra, rb);
+                    if (k == 0) step_a(st);
+                    if (k == STEP) step_b(st);
+                    if (k == 2 * STEP) aim_settle_a();
+                    if (k == 3 * STEP) aim_settle_b(0);
+                    if (k == 4 * STEP) aim_settle_b(1);
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
-        advance_request();
     };
-    using std::integral_constant;
 
     // prologue: slices 0 .. 3 requested; slice 0 fixed up and published; its fragments into set 0
 #pragma unroll
     for (int s = 0; s < kRing; ++s) {
-        const bool live = rq_left > 0;
-        const u32x4 ra = live ? rsrc_a : rsrc_z, rb = live ? rsrc_b : rsrc_z;
+        if (s > 0) step_request();
+        aim_request();
 #pragma unroll
         for (int d = 0; d < ND; ++d) {
             dma_aim(d, s);
             asm volatile("s_nop 0");
             dma_go(d, ra, rb);
         }
-        advance_request();
     }
     NT_WAIT_VMCNT((kRing - 1) * ND);
-    settle(0);
+    aim_settle();
+    settle(integral_constant<int, 0>{});
+    step_settle();
+    aim_settle();
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < NR; ++r) lds_read(r, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
 
-    // Slice s sits at ring position s % 4.  At the top of trip s this wavefront's part of slice s + 1 must have landed; it
-    // is fixed up, and the barrier then says that slice s + 1 is complete and that every wavefront holds its fragments of
-    // slice s in registers, so that slice s + 4 can overwrite it.  One pass = four trips.  A number of slices that is no
-    // multiple of four is rounded up: the slices past the last are requested from rsrc_z, arrive as zeros, and their trips
-    // add nothing.
+    // Slice s sits at ring position s % 4.  At the top of trip s this wavefront's part of slice s + 1 must have landed.
+    // One pass = four trips.  A number of slices that is no multiple of four is rounded up: the slices past the last are
+    // requested from records of length zero, arrive as zeros, and their trips add nothing.
     for (int32_t sl = 0; sl < n_slices; sl += kRing) {
-        NT_WAIT_VMCNT(2 * ND); settle(1); __syncthreads(); trip(integral_constant<int, 0>{}, integral_constant<int, 0>{});
-        NT_WAIT_VMCNT(2 * ND); settle(2); __syncthreads(); trip(integral_constant<int, 1>{}, integral_constant<int, 1>{});
-        NT_WAIT_VMCNT(2 * ND); settle(3); __syncthreads(); trip(integral_constant<int, 2>{}, integral_constant<int, 0>{});
-        NT_WAIT_VMCNT(2 * ND); settle(0); __syncthreads(); trip(integral_constant<int, 3>{}, integral_constant<int, 1>{});
+        NT_WAIT_VMCNT(2 * ND); trip(integral_constant<int, 0>{}, integral_constant<int, 0>{});
+        NT_WAIT_VMCNT(2 * ND); trip(integral_constant<int, 1>{}, integral_constant<int, 1>{});
+        NT_WAIT_VMCNT(2 * ND); trip(integral_constant<int, 2>{}, integral_constant<int, 0>{});
+        NT_WAIT_VMCNT(2 * ND); trip(integral_constant<int, 3>{}, integral_constant<int, 1>{});
         // (wait states between the last matrix instruction and anything the compiler may do to an accumulator at the
         // loop's end: it does not know that the inline assembly is a matrix instruction)
         asm volatile("s_nop 7" ::: "memory");
@@ -310,11 +380,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_conv_tap_kernel(const ConvAr
     else conv_store_points16<BM, BN, NT_BF16>(g, acc, bi, row_w, col_w, lane);
 }
 
-template <bool BF16, bool TRACE = false>
+template <bool BF16, int TM, bool TRACE = false>
 static nt_status launch_conv_tap_inst(const ConvArgs &a, int64_t nwg, hipStream_t s)
 {
     constexpr size_t smem = (size_t)4 * (256 + 256) * kSliceK * sizeof(uint16_t);
-    auto kern = gemm_conv_tap_kernel<BF16, TRACE>;
+    auto kern = gemm_conv_tap_kernel<BF16, TM, TRACE>;
     static DeviceOnce configured;
     if (!configured.done()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -325,9 +395,10 @@ static nt_status launch_conv_tap_inst(const ConvArgs &a, int64_t nwg, hipStream_
     return check_launch("gemm_conv_tap_kernel");
 }
 
-// a.Wt: the filter in tap-major order (see launch_conv_repack_filter), a.ldb its row pitch; nwg = ksplit * mt * nt
-nt_status launch_conv_tap(const ConvArgs &a, bool bf16, int64_t nwg, hipStream_t s);
-nt_status launch_conv_tap_trace(const ConvArgs &a, hipStream_t s);
+// a.Wt: the filter in tap-major order (see launch_conv_repack_filter), a.ldb its row pitch; rows: positions per program
+// (224 or 256), a.mt the number of tiles of that height; nwg = ksplit * mt * nt
+nt_status launch_conv_tap(const ConvArgs &a, int rows, bool bf16, int64_t nwg, hipStream_t s);
+nt_status launch_conv_tap_trace(const ConvArgs &a, int rows, hipStream_t s);
 // filter [F][C][R * S] (row pitch ldb) -> out [F][R * S][C] (row pitch C R S)
 nt_status launch_conv_repack_filter(const uint16_t *w, int64_t ldb, uint16_t *out, int32_t F, int32_t C, int32_t RS, hipStream_t s);
 

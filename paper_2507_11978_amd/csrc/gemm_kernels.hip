@@ -475,35 +475,43 @@ static nt_status route_conv_implicit(const GemmLaunch &g, const ConvArgs &c, int
     if (direct && path_out) *path_out = tap ? PATH_CONV_TAP : PATH_CONV_DIRECT;
     const bool bf16 = g.in_dtype == NT_BF16;
     ConvArgs base = c;
+    int tap_rows = 256;
     if (tap) {
         const nt_status st = launch_conv_repack_filter(c.Wt, c.ldb, wt_tap, c.N, (int32_t)g.conv.C, c.RS, s);
         if (st != NT_OK) return st;
         base.Wt = wt_tap;
         base.ldb = c.K;
+        // tile height: whole rounds of 256 programs (one per compute unit) cost their length, 32 h positions plus a fixed part
+        auto cost = [&](int rows) {
+            const int64_t programs = (c.M + rows - 1) / rows * c.nt * ksplit;
+            return (double)((programs + 255) / 256) * (rows / 32 + 1.5);
+        };
+        if (cost(224) < cost(256)) tap_rows = 224;
+        base.mt = (c.M + tap_rows - 1) / tap_rows;
     }
     if (g.trace.out) {
         if (!direct) return fail(NT_ERR_UNSUPPORTED, "this convolution does not run on the kernels that stream their operands into LDS");
         const int bn = c.N <= 64 ? 64 : (c.N <= 128 ? 128 : t.bn);
-        const int64_t rows = g.trace.operand == 0 ? 256 : bn;
+        const int64_t rows = g.trace.operand == 0 ? (tap ? tap_rows : 256) : bn;
         if ((size_t)rows * 32 > g.trace.capacity) return fail(NT_ERR_BUFFER_TOO_SMALL, "trace buffer smaller than the slice");
-        if (g.trace.program < 0 || g.trace.program >= c.mt * c.nt) return fail(NT_ERR_INVALID_ARG, "program_id outside the grid");
+        if (g.trace.program < 0 || g.trace.program >= base.mt * c.nt) return fail(NT_ERR_INVALID_ARG, "program_id outside the grid");
         if (g.trace.slice < 0 || g.trace.slice >= c.K / 32) return fail(NT_ERR_INVALID_ARG, "slice outside the reduction");
         base.trace_out = g.trace.out; base.trace_program = g.trace.program; base.trace_slice = g.trace.slice; base.trace_operand = g.trace.operand;
-        return tap ? launch_conv_tap_trace(base, s) : launch_conv_direct_trace(base, bn, s);
+        return tap ? launch_conv_tap_trace(base, tap_rows, s) : launch_conv_direct_trace(base, bn, s);
     }
     auto launch = [&](const ConvArgs &ca, int64_t nwg) {
-        if (tap) return launch_conv_tap(ca, bf16, nwg, s);
+        if (tap) return launch_conv_tap(ca, tap_rows, bf16, nwg, s);
         // (one column of tiles with few filters: the same grid is run by the kernel built for 64 or 128 filters per
         // program, which spends a quarter or half of the MFMAs)
         const int bn = ca.N <= 64 && direct ? 64 : (ca.N <= 128 ? 128 : t.bn);
         return direct ? launch_conv_direct(ca, bn, bf16, nwg, s) : launch_conv(ca, bn, bf16, edge_b || (ca.N % bn) != 0, nwg, s);
     };
-    if (!ws) return launch(base, c.mt * c.nt);
+    if (!ws) return launch(base, base.mt * c.nt);
     t_k_split = ksplit;
     ConvArgs part = base;
     part.Y = ws; part.syn = (int64_t)c.N * c.PQ; part.syf = c.PQ; part.out_dtype = NT_F32;
     part.ksplit = ksplit; part.kt_per = kt_per; part.slice = slice;
-    const nt_status st = launch(part, c.mt * c.nt * ksplit);
+    const nt_status st = launch(part, base.mt * c.nt * ksplit);
     if (st != NT_OK) return st;
     return launch_conv_ws_sum(ws, ksplit, slice, c.Y, (int64_t)c.N * c.PQ, c.PQ, c.syn, c.syf, c.out_dtype, s);
 }
