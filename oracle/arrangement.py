@@ -84,30 +84,38 @@ class Arranged:
         self.levels, self.fn = inner.levels, inner.fn
 
     # ---------------------------------------------------------- meta-operations
-    def tile(self, tile_shape, strides=None, pad=None):
+    def tile(self, tile_shape, strides=None, pad=None, dilation=None):
+        """Element j of tile o along a dimension is source coordinate o * stride + j * dilation - pad_low (the paper's tile
+        has dilation 1 and no padding; both are extensions, with the usual meaning for convolutions).  A tile then
+        spans (t - 1) * dilation + 1 source coordinates, and as many tiles exist as start inside the padded extent
+        with their whole span (the last one may overhang: ceiling)."""
         L, S = self.cursor, self.shape
         if len(tile_shape) != len(S):
             raise ShapeMismatch("tile_shape rank differs from the level's rank")
-        T, st, lo, outer = [], [], [], []
+        T, st, lo, dil, outer = [], [], [], [], []
         for i, size in enumerate(S):
             t = size if tile_shape[i] == -1 else int(tile_shape[i])
             s = t if strides is None or strides[i] == -1 else int(strides[i])
+            d = 1 if dilation is None or dilation[i] in (-1, 0) else int(dilation[i])
             p_lo, p_hi = (0, 0) if pad is None else (int(pad[i][0]), int(pad[i][1]))
             if t <= 0 and not (t == 0 and size == 0):
                 raise ShapeMismatch("tile sizes must be positive")
+            if d < 1:
+                raise ShapeMismatch("dilation must be positive")
             if s <= 0:
                 s = 1
+            span = (t - 1) * d + 1 if t > 0 else 0
             if size + p_lo + p_hi > 0:
-                o = max(_ceil_div(size + p_lo + p_hi - t, s) + 1, 0)
+                o = max(_ceil_div(size + p_lo + p_hi - span, s) + 1, 0)
             else:                       # empty dimension: "-1" still yields its one (empty) tile
                 o = 1 if tile_shape[i] == -1 else 0
-            T.append(t), st.append(s), lo.append(p_lo), outer.append(o)
+            T.append(t), st.append(s), lo.append(p_lo), dil.append(d), outer.append(o)
         old_fn = self.fn
 
-        def fn(idx, L=L, S=S, st=tuple(st), lo=tuple(lo)):
+        def fn(idx, L=L, S=S, st=tuple(st), lo=tuple(lo), dil=tuple(dil)):
             parent, ok = [], True
             for i in range(len(S)):
-                x = idx[L][i] * st[i] + idx[L + 1][i] - lo[i]
+                x = idx[L][i] * st[i] + idx[L + 1][i] * dil[i] - lo[i]
                 ok = ok & (x >= 0) & (x < S[i])
                 parent.append(x)
             coords, valid = old_fn(idx[:L] + [parent] + idx[L + 2:])
@@ -223,7 +231,7 @@ def Tensor(shape, strides=None) -> Arranged:
 # ----------------------------------------------------------------- arrangement programs
 def run_program(t: Arranged, ops) -> Arranged:
     """Apply a list of meta-operations given as tuples:
-    ("tile", tile_shape[, strides[, pad]]), ("expand", shape), ("squeeze", dim),
+    ("tile", tile_shape[, strides[, pad[, dilation]]]), ("expand", shape), ("squeeze", dim),
     ("permute", order), ("flatten", start, end), ("ravel",), ("descend",), ("ascend",).
     descend / ascend stand for taking `.dtype` and assigning the result back."""
     stack = []
@@ -289,18 +297,20 @@ def bmm_arrangement(A: Arranged, B: Arranged, Cm: Arranged, BM, BN, BK):
     return run_program(A, pa), run_program(B, pb), c_arr
 
 
-def conv2d_operand_programs(R, S, C, stride=(1, 1), pad=(0, 0), P=None, Q=None, H=None, W=None):
+def conv2d_operand_programs(R, S, C, stride=(1, 1), pad=(0, 0), P=None, Q=None, H=None, W=None, dilation=(1, 1)):
     """Programs turning input (N,C,H,W), filter (K,C,R,S), output (N,K,P,Q) into the
     implicit-GEMM matrices (N*P*Q, C*R*S), (C*R*S, K), (N*P*Q, K) (Section 4.3).
     The paper's listing has stride 1 and no padding; stride and padding are carried by
     the tile's strides and pad arguments.  pad_hi is chosen so that exactly P (Q) filter
     positions exist, P being the usual floor formula."""
     pads = None
-    if pad != (0, 0) or stride != (1, 1):
-        hi_h = (P - 1) * stride[0] + R - H - pad[0]
-        hi_w = (Q - 1) * stride[1] + S - W - pad[1]
+    if pad != (0, 0) or stride != (1, 1) or dilation != (1, 1):
+        hi_h = (P - 1) * stride[0] + (R - 1) * dilation[0] + 1 - H - pad[0]
+        hi_w = (Q - 1) * stride[1] + (S - 1) * dilation[1] + 1 - W - pad[1]
         pads = ((0, 0), (0, 0), (pad[0], hi_h), (pad[1], hi_w))
     tile = ("tile", (1, C, R, S), (-1, -1, stride[0], stride[1])) + ((pads,) if pads else ())
+    if dilation != (1, 1):
+        tile = tile + ((-1, -1, dilation[0], dilation[1]),)
     x = [tile, ("squeeze", 1), ("descend",), ("squeeze", 0), ("ascend",), ("ravel",),
          ("flatten", 0, 3), ("flatten", 1, 4)]
     w = [("flatten", 1, 4), ("permute", (1, 0))]
@@ -308,11 +318,30 @@ def conv2d_operand_programs(R, S, C, stride=(1, 1), pad=(0, 0), P=None, Q=None, 
     return x, w, y
 
 
-def conv2d_arrangement(X: Arranged, Wt: Arranged, Y: Arranged, BM, BN, BK, stride=(1, 1), pad=(0, 0)):
+def grouped_conv2d_view_programs(G, Cg, Kg, R, S, stride=(1, 1), pad=(0, 0), P=None, Q=None, H=None, W=None, dilation=(1, 1)):
+    """A grouped convolution (input (N, G*Cg, H, W), filter (G*Kg, Cg, R, S), output (N, G*Kg, P, Q); group g's filters see
+    only group g's channels) written as ONE batched matrix product over the groups, with the meta-operations of Table 1
+    only: programs that turn the three tensors into the single-level views (G, N*P*Q, Cg*R*S), (G, Cg*R*S, Kg) and
+    (G, N*P*Q, Kg).  The input is tiled as in Section 4.3, the channel axis in tiles of Cg, so that the outer level gains
+    the group index; G = 1 gives the implicit-GEMM views of Section 4.3 with a leading batch axis of one.  Depthwise:
+    Cg = Kg = 1."""
+    hi_h = (P - 1) * stride[0] + (R - 1) * dilation[0] + 1 - H - pad[0]
+    hi_w = (Q - 1) * stride[1] + (S - 1) * dilation[1] + 1 - W - pad[1]
+    pads = ((0, 0), (0, 0), (pad[0], hi_h), (pad[1], hi_w))
+    x = [("tile", (1, Cg, R, S), (-1, -1, stride[0], stride[1]), pads, (-1, -1, dilation[0], dilation[1])),   # (N, G, P, Q) of (1, Cg, R, S)
+         ("permute", (1, 0, 2, 3)), ("descend",), ("squeeze", 0), ("ascend",), ("ravel",),                    # (G, N, P, Q, Cg, R, S)
+         ("flatten", 1, 4), ("flatten", 2, 5)]
+    w = [("flatten", 1, 4), ("tile", (Kg, -1)), ("ravel",), ("squeeze", 1), ("permute", (0, 2, 1))]           # (G, Cg R S, Kg)
+    y = [("tile", (-1, Kg, -1, -1)), ("ravel",), ("squeeze", 0), ("squeeze", 1), ("squeeze", 1),              # (G, N, Kg, P, Q)
+         ("permute", (0, 1, 3, 4, 2)), ("flatten", 1, 4)]
+    return x, w, y
+
+
+def conv2d_arrangement(X: Arranged, Wt: Arranged, Y: Arranged, BM, BN, BK, stride=(1, 1), pad=(0, 0), dilation=(1, 1)):
     _, C, H, W = X.shape
     _, _, R, S = Wt.shape
     _, _, P, Q = Y.shape
-    px, pw, py = conv2d_operand_programs(R, S, C, stride, pad, P, Q, H, W)
+    px, pw, py = conv2d_operand_programs(R, S, C, stride, pad, P, Q, H, W, dilation)
     return mm_arrangement(run_program(X, px), run_program(Wt, pw), run_program(Y, py), BM, BN, BK)
 
 
