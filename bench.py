@@ -136,7 +136,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default 50; 2000 for the kernels that run for tens of microseconds)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 50; 1000 for those short kernels)")
     ap.add_argument("--workload", default="p_f16_8192",
-                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c6_f16_conv_paper, c1_f16_256, f1_f16_addmm, f1_f16_bias_gelu, f3_f16_add, f3_f16_silu, f3_f16_softmax, f3_f16_rms_norm, f4_f16_sdpa, f4_bf16_sdpa, f4_f16_sdpa_4k")
+                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, f2_f16_conv_views, c6_f16_conv_paper, c1_f16_256, f1_f16_addmm, f1_f16_bias_gelu, f3_f16_add, f3_f16_silu, f3_f16_softmax, f3_f16_rms_norm, f4_f16_sdpa, f4_bf16_sdpa, f4_f16_sdpa_4k")
     ap.add_argument("--tile", default=None, help="bm,bn,bk (default: library choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -346,6 +346,16 @@ def main():
         y = torch.empty((cfg["N"], cfg["K"], P, Q), dtype=TORCH_DT[out], device="cuda")
         st, pd = (cfg["stride"],) * 2, (cfg["pad"],) * 2
         step = lambda: nt.conv2d_implicit(x, w, y, st, pd, tile=tile)
+        if cfg.get("via") == "views":
+            # the arrangement of Section 4.3 as a caller writes it: the input tiled by (1, C, R, S) with the convolution's
+            # strides and padding and flattened to (N P Q, C R S), the filter to (C R S, K), the output to (N P Q, K)
+            hi_h = (P - 1) * st[0] + cfg["R"] - cfg["H"] - pd[0]
+            hi_w = (Q - 1) * st[1] + cfg["S"] - cfg["W"] - pd[1]
+            px = [("tile", (1, cfg["C"], cfg["R"], cfg["S"]), (-1, -1, st[0], st[1]), ((0, 0), (0, 0), (pd[0], hi_h), (pd[1], hi_w))),
+                  ("squeeze", 1), ("descend",), ("squeeze", 0), ("ascend",), ("ravel",), ("flatten", 0, 3), ("flatten", 1, 4)]
+            pw = [("flatten", 1, 4), ("permute", (1, 0))]
+            py = [("permute", (0, 2, 3, 1)), ("flatten", 0, 3)]
+            step = lambda: nt.matmul_views(x, px, w, pw, y, py, tile=tile)
         grid, kt = nt.arrange_conv2d(x, w, y, st, pd, tile=tile)
     else:
         Ab, Bb = si.gemm_inputs(cfg["M"], cfg["N"], cfg["K"], dt, cfg["seed"], cfg["dist"], batch=cfg.get("batch"))

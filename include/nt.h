@@ -32,7 +32,7 @@
 extern "C" {
 #endif
 
-#define NT_MAX_DIMS 6
+#define NT_MAX_DIMS 8
 #define NT_MAX_LEVELS 8
 
 typedef enum {
@@ -57,8 +57,10 @@ typedef struct {
 /* One meta-operation (Table 1).  An arrangement is an array of these, applied in order
  * to the level the cursor points at (initially the outermost).
  *   TILE     a = tile shape (-1 = whole dimension), b = strides between tiles (-1 or 0 =
- *            default = tile shape; Section 3.1.3), c = low padding, d = high padding
- *            (c, d: 0 in the paper; needed for padded convolution).  n = rank.
+ *            default = tile shape; Section 3.1.3), c = low padding, d = high padding,
+ *            e = dilation (-1, 0 or 1 = none): element j of tile o is source coordinate
+ *            o * b + j * e - c.  (c, d, e: 0 / none in the paper; needed for padded and
+ *            dilated convolutions.)  n = rank.
  *   EXPAND   a = new shape (-1 keeps a dimension); only singleton dimensions grow.
  *   SQUEEZE  a[0] = dimension to drop; it must have size 1.
  *   PERMUTE  a = order (new dimension i is old dimension a[i]).
@@ -80,6 +82,7 @@ typedef struct {
     int64_t b[NT_MAX_DIMS];
     int64_t c[NT_MAX_DIMS];
     int64_t d[NT_MAX_DIMS];
+    int64_t e[NT_MAX_DIMS];
 } nt_meta_op;
 
 /* Meta-parameters of the matmul arrangement (BLOCK_SIZE_M/N/K of Section 4.2).

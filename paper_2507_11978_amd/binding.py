@@ -9,7 +9,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libnt.so")
-MAX_DIMS, MAX_LEVELS = 6, 8
+MAX_DIMS, MAX_LEVELS = 8, 8
 
 OP_TILE, OP_EXPAND, OP_SQUEEZE, OP_PERMUTE, OP_FLATTEN, OP_RAVEL, OP_DESCEND, OP_ASCEND = range(8)
 _DTYPES = {"f16": 0, "bf16": 1, "f32": 2}
@@ -30,7 +30,7 @@ class TensorDesc(C.Structure):
 
 class MetaOp(C.Structure):
     _fields_ = [("kind", C.c_int32), ("n", C.c_int32), ("a", C.c_int64 * MAX_DIMS), ("b", C.c_int64 * MAX_DIMS),
-                ("c", C.c_int64 * MAX_DIMS), ("d", C.c_int64 * MAX_DIMS)]
+                ("c", C.c_int64 * MAX_DIMS), ("d", C.c_int64 * MAX_DIMS), ("e", C.c_int64 * MAX_DIMS)]
 
 
 class TileCfg(C.Structure):
@@ -176,19 +176,21 @@ def _desc_of(t) -> TensorDesc:
 
 
 def make_ops(ops) -> tuple:
-    """ops: tuples ("tile", shape[, strides[, pad]]), ("expand", shape), ("squeeze", dim),
+    """ops: tuples ("tile", shape[, strides[, pad[, dilation]]]), ("expand", shape), ("squeeze", dim),
     ("permute", order), ("flatten", start, end), ("ravel",), ("descend",), ("ascend",);
     pad is a sequence of (low, high) pairs."""
     arr = (MetaOp * max(len(ops), 1))()
     for o, op in zip(arr, ops):
         kind = op[0]
-        vals = {"a": [], "b": [], "c": [], "d": []}
+        vals = {"a": [], "b": [], "c": [], "d": [], "e": []}
         if kind == "tile":
             o.kind, vals["a"] = OP_TILE, list(op[1])
             if len(op) > 2 and op[2] is not None:
                 vals["b"] = list(op[2])
             if len(op) > 3 and op[3] is not None:
                 vals["c"], vals["d"] = [p[0] for p in op[3]], [p[1] for p in op[3]]
+            if len(op) > 4 and op[4] is not None:
+                vals["e"] = list(op[4])
         elif kind == "expand":
             o.kind, vals["a"] = OP_EXPAND, list(op[1])
         elif kind == "squeeze":

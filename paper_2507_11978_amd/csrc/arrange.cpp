@@ -54,14 +54,14 @@ int64_t Arrangement::num_programs() const
 }
 
 nt_status Arrangement::tile(std::vector<int64_t> shape, std::vector<int64_t> strides,
-                            std::vector<int64_t> pad_lo, std::vector<int64_t> pad_hi)
+                            std::vector<int64_t> pad_lo, std::vector<int64_t> pad_hi, std::vector<int64_t> dilation)
 {
     std::vector<int> &lv = levels_[cursor_];
     const size_t r = lv.size();
     if (shape.size() != r) return fail(NT_ERR_SHAPE_MISMATCH, "tile: rank of tile_shape differs from the level's rank");
     if ((!strides.empty() && strides.size() != r) || (!pad_lo.empty() && pad_lo.size() != r) ||
-        (!pad_hi.empty() && pad_hi.size() != r))
-        return fail(NT_ERR_INVALID_ARG, "tile: strides/padding rank differs from the level's rank");
+        (!pad_hi.empty() && pad_hi.size() != r) || (!dilation.empty() && dilation.size() != r))
+        return fail(NT_ERR_INVALID_ARG, "tile: strides/padding/dilation rank differs from the level's rank");
     if ((int)levels_.size() + 1 > NT_MAX_LEVELS) return fail(NT_ERR_UNSUPPORTED, "tile: too many levels");
     std::vector<int> outer(r), inner(r);
     std::vector<Node> fresh;
@@ -76,10 +76,13 @@ nt_status Arrangement::tile(std::vector<int64_t> shape, std::vector<int64_t> str
         if (st <= 0) st = 1;
         const int64_t lo = pad_lo.empty() ? 0 : pad_lo[i];
         const int64_t hi = pad_hi.empty() ? 0 : pad_hi[i];
+        const int64_t dil = (dilation.empty() || dilation[i] == -1 || dilation[i] == 0) ? 1 : dilation[i];
+        if (dil < 1) return fail(NT_ERR_INVALID_ARG, "tile: dilation must be positive");
         const int64_t ext = S + lo + hi;
+        const int64_t span = T > 0 ? (T - 1) * dil + 1 : 0;     // source coordinates from a tile's first to its last element
         int64_t O;
         if (ext > 0)
-            O = std::max<int64_t>(ceil_div(ext - T, st) + 1, 0);
+            O = std::max<int64_t>(ceil_div(ext - span, st) + 1, 0);
         else
             O = whole ? 1 : 0;
         Node nd;
@@ -92,6 +95,7 @@ nt_status Arrangement::tile(std::vector<int64_t> shape, std::vector<int64_t> str
         nd.nout = 1;
         nd.st = st;
         nd.lo = lo;
+        nd.dil = dil;
         nd.bound = S;
         outer[i] = nd.in0;
         inner[i] = nd.in1;
@@ -182,7 +186,7 @@ nt_status Arrangement::ravel()
 {
     std::vector<int> flat;
     for (size_t l = cursor_; l < levels_.size(); ++l) flat.insert(flat.end(), levels_[l].begin(), levels_[l].end());
-    if (flat.size() > NT_MAX_DIMS) return fail(NT_ERR_UNSUPPORTED, "ravel: more than 6 dimensions in one level");
+    if (flat.size() > NT_MAX_DIMS) return fail(NT_ERR_UNSUPPORTED, "ravel: more than NT_MAX_DIMS dimensions in one level");
     levels_.resize(cursor_ + 1);
     levels_[cursor_] = flat;
     return NT_OK;
@@ -207,7 +211,7 @@ nt_status Arrangement::apply(const nt_meta_op &op)
     if (op.n < 0 || op.n > NT_MAX_DIMS) return fail(NT_ERR_INVALID_ARG, "meta-op: n out of range");
     auto vec = [&](const int64_t *p) { return std::vector<int64_t>(p, p + op.n); };
     switch (op.kind) {
-    case NT_OP_TILE: return tile(vec(op.a), vec(op.b), vec(op.c), vec(op.d));
+    case NT_OP_TILE: return tile(vec(op.a), vec(op.b), vec(op.c), vec(op.d), vec(op.e));
     case NT_OP_EXPAND: return expand(vec(op.a));
     case NT_OP_SQUEEZE: return squeeze(op.a[0]);
     case NT_OP_PERMUTE: return permute(vec(op.a));
@@ -237,7 +241,7 @@ bool Arrangement::eval(std::vector<int64_t> &vals, int64_t *offset) const
     for (size_t n = nodes_.size(); n-- > 0;) {
         const Node &nd = nodes_[n];
         if (nd.kind == Node::TILE) {
-            const int64_t v = vals[nd.in0] * nd.st + vals[nd.in1] - nd.lo;
+            const int64_t v = vals[nd.in0] * nd.st + vals[nd.in1] * nd.dil - nd.lo;
             valid = valid && v >= 0 && v < nd.bound;
             vals[nd.out[0]] = v;
         } else if (nd.kind == Node::ZERO) {
@@ -368,9 +372,9 @@ nt_status Arrangement::lower_matrix_view(OperandMap *map, int64_t *batch_out, in
             if (!lin.count(nd.in0) || !lin.count(nd.in1))
                 return fail(NT_ERR_UNSUPPORTED, "lowering: tile fed by a dimension outside the view");
             Lin r;
-            r.c = lin[nd.in0].c * nd.st + lin[nd.in1].c - nd.lo;
+            r.c = lin[nd.in0].c * nd.st + lin[nd.in1].c * nd.dil - nd.lo;
             for (auto &kv : lin[nd.in0].coef) r.coef[kv.first] += kv.second * nd.st;
-            for (auto &kv : lin[nd.in1].coef) r.coef[kv.first] += kv.second;
+            for (auto &kv : lin[nd.in1].coef) r.coef[kv.first] += kv.second * nd.dil;
             int64_t mn, mx;
             range(r, &mn, &mx);
             if (mn < 0 || mx >= nd.bound) {
@@ -564,18 +568,19 @@ nt_status arrange_matmul(const Arrangement &va, const Arrangement &vb, const Arr
 // permuted and flattened to (N*P*Q, K).
 nt_status conv2d_views(const nt_tensor_desc *dx, const nt_tensor_desc *dw, const nt_tensor_desc *dy,
                        int32_t sh, int32_t sw, int32_t ph, int32_t pw,
-                       Arrangement *vx, Arrangement *vw, Arrangement *vy)
+                       Arrangement *vx, Arrangement *vw, Arrangement *vy, int32_t dh, int32_t dw_)
 {
     if (!dx || !dw || !dy) return fail(NT_ERR_INVALID_ARG, "null tensor descriptor");
     if (dx->ndim != 4 || dw->ndim != 4 || dy->ndim != 4)
         return fail(NT_ERR_SHAPE_MISMATCH, "conv2d tensors must be 4-D (NCHW, KCRS, NKPQ)");
-    if (sh < 1 || sw < 1 || ph < 0 || pw < 0) return fail(NT_ERR_INVALID_ARG, "conv2d stride must be >= 1, padding >= 0");
+    if (sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw_ < 1) return fail(NT_ERR_INVALID_ARG, "conv2d stride and dilation must be >= 1, padding >= 0");
     const int64_t N = dx->size[0], C = dx->size[1], H = dx->size[2], W = dx->size[3];
     const int64_t K = dw->size[0], R = dw->size[2], S = dw->size[3];
     if (dw->size[1] != C) return fail(NT_ERR_SHAPE_MISMATCH, "conv2d: channel counts of input and filter differ");
     if (R < 1 || S < 1 || C < 1) return fail(NT_ERR_INVALID_ARG, "conv2d: empty filter");
-    const int64_t P = H + 2 * ph >= R ? (H + 2 * ph - R) / sh + 1 : 0;
-    const int64_t Q = W + 2 * pw >= S ? (W + 2 * pw - S) / sw + 1 : 0;
+    const int64_t span_h = (R - 1) * dh + 1, span_w = (S - 1) * dw_ + 1;      // input rows / columns under one filter
+    const int64_t P = H + 2 * ph >= span_h ? (H + 2 * ph - span_h) / sh + 1 : 0;
+    const int64_t Q = W + 2 * pw >= span_w ? (W + 2 * pw - span_w) / sw + 1 : 0;
     if (dy->size[0] != N || dy->size[1] != K || dy->size[2] != P || dy->size[3] != Q) {
         std::ostringstream os;
         os << "conv2d: output must be [" << N << "," << K << "," << P << "," << Q << "]";
@@ -586,8 +591,8 @@ nt_status conv2d_views(const nt_tensor_desc *dx, const nt_tensor_desc *dw, const
     NT_TRY(vx->init(dx));
     NT_TRY(vw->init(dw));
     NT_TRY(vy->init(dy));
-    const int64_t hi_h = (P - 1) * sh + R - H - ph, hi_w = (Q - 1) * sw + S - W - pw;
-    NT_TRY(vx->tile({1, C, R, S}, {-1, -1, sh, sw}, {0, 0, ph, pw}, {0, 0, hi_h, hi_w}));
+    const int64_t hi_h = (P - 1) * sh + span_h - H - ph, hi_w = (Q - 1) * sw + span_w - W - pw;
+    NT_TRY(vx->tile({1, C, R, S}, {-1, -1, sh, sw}, {0, 0, ph, pw}, {0, 0, hi_h, hi_w}, {1, 1, dh, dw_}));
     NT_TRY(vx->squeeze(1));
     NT_TRY(vx->descend());
     NT_TRY(vx->squeeze(0));

@@ -28,7 +28,7 @@ struct Node {
     int in0 = -1, in1 = -1;          // TILE: outer, inner.  SPLIT: merged.  ZERO: unused
     int out[NT_MAX_DIMS];            // TILE/ZERO: one parent.  SPLIT: nout parents
     int nout = 0;
-    int64_t st = 1, lo = 0, bound = 0;
+    int64_t st = 1, lo = 0, bound = 0, dil = 1;     // TILE: parent = outer * st + inner * dil - lo, valid in [0, bound)
     int64_t radix[NT_MAX_DIMS];
 };
 
@@ -40,7 +40,7 @@ public:
 
     // convenience builders used by the library's own arrangements
     nt_status tile(std::vector<int64_t> shape, std::vector<int64_t> strides = {},
-                   std::vector<int64_t> pad_lo = {}, std::vector<int64_t> pad_hi = {});
+                   std::vector<int64_t> pad_lo = {}, std::vector<int64_t> pad_hi = {}, std::vector<int64_t> dilation = {});
     nt_status expand(std::vector<int64_t> shape);
     nt_status squeeze(int64_t dim);
     nt_status permute(std::vector<int64_t> order);
@@ -84,6 +84,6 @@ nt_status arrange_matmul(const Arrangement &va, const Arrangement &vb, const Arr
                          nt_tile_cfg cfg, MatmulArrangement *out);
 nt_status conv2d_views(const nt_tensor_desc *dx, const nt_tensor_desc *dw, const nt_tensor_desc *dy,
                        int32_t sh, int32_t sw, int32_t ph, int32_t pw,
-                       Arrangement *vx, Arrangement *vw, Arrangement *vy);
+                       Arrangement *vx, Arrangement *vw, Arrangement *vy, int32_t dh = 1, int32_t dw_ = 1);
 
 }  // namespace nt

@@ -155,7 +155,7 @@ struct UnfoldArgs {
     uint16_t *U;
     int64_t xs[4];
     int64_t M, Mp, K;
-    int32_t C, H, W, R, S, P, Q, sh, sw, ph, pw;
+    int32_t C, H, W, R, S, P, Q, sh, sw, ph, pw, dh, dw;
 };
 
 __global__ __launch_bounds__(256) void conv_unfold_kernel(const UnfoldArgs g)
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(256) void conv_unfold_kernel(const UnfoldArgs g)
         // input row, all inside the image: one or two 16-byte loads (2-byte aligned), every second element picked for
         // stride 2.  (Input contiguous along w only.)
         if (xs3 == 1 && g.sw <= 2 && q + 8 <= g.Q && m0 + 8 <= (uint32_t)g.M) {
-            const int32_t h = p * g.sh + (int32_t)r - g.ph, col = q * g.sw + (int32_t)sx - g.pw;
+            const int32_t h = p * g.sh + (int32_t)r * g.dh - g.ph, col = q * g.sw + (int32_t)sx * g.dw - g.pw;
             if ((uint32_t)h < (uint32_t)g.H && col >= 0 && col + 8 * g.sw <= g.W) {
                 const uint16_t *src = xc + ((int32_t)n * xs0 + h * xs2 + col);
                 u32x4 a;
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(256) void conv_unfold_kernel(const UnfoldArgs g)
         uint32_t keep = 0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const int32_t h = p * g.sh + (int32_t)r - g.ph, col = q * g.sw + (int32_t)sx - g.pw;
+            const int32_t h = p * g.sh + (int32_t)r * g.dh - g.ph, col = q * g.sw + (int32_t)sx * g.dw - g.pw;
             const bool in = m0 + e < (uint32_t)g.M && (uint32_t)h < (uint32_t)g.H && (uint32_t)col < (uint32_t)g.W;
             off[e] = in ? (int32_t)n * xs0 + h * xs2 + col * xs3 : 0;
             keep |= (in ? 1u : 0u) << e;
@@ -251,7 +251,7 @@ static bool match_conv(const GemmLaunch &g, ConvArgs *a)
 {
     const ConvHint &h = g.conv;
     if (!h.valid || g.batch != 1 || g.tile.bm != 256 || g.tile.bk != 64 || (g.tile.bn != 128 && g.tile.bn != 256)) return false;
-    if (h.sh != 1 || h.sw != 1 || h.ph < 0 || h.pw < 0 || h.pw > 1 || h.R > 31 || h.S > 31 || h.P <= 0 || h.Q <= 0) return false;
+    if (h.sh != 1 || h.sw != 1 || h.dh != 1 || h.dw != 1 || h.ph < 0 || h.pw < 0 || h.pw > 1 || h.R > 31 || h.S > 31 || h.P <= 0 || h.Q <= 0) return false;
     if (h.xs[3] != 1 || h.xs[2] != h.W || h.xs[1] != h.H * h.W || h.xs[0] != h.C * h.H * h.W) return false;
     if (h.ws[3] != 1 || h.ws[2] != h.S || h.ws[1] != h.R * h.S || h.ws[0] <= 0 || h.ws[0] >= (1 << 22)) return false;
     if (h.ys[3] != 1 || h.ys[2] != h.Q) return false;
@@ -528,7 +528,7 @@ static nt_status route_conv_padded_copy(const GemmLaunch &g, int *path_out, bool
 {
     *taken = false;
     const ConvHint &h = g.conv;
-    if (!(conv_is_bare(g) && h.sh == 1 && h.sw == 1 && h.ph >= 0 && h.pw >= 0 && h.xs[0] >= 0 && h.xs[1] >= 0 && h.xs[2] >= 0 && h.xs[3] >= 0 &&
+    if (!(conv_is_bare(g) && h.sh == 1 && h.sw == 1 && h.dh == 1 && h.dw == 1 && h.ph >= 0 && h.pw >= 0 && h.xs[0] >= 0 && h.xs[1] >= 0 && h.xs[2] >= 0 && h.xs[3] >= 0 &&
           (h.H - 1) * h.xs[2] + (h.W - 1) * h.xs[3] < (1LL << 31)))
         return NT_OK;
     const int64_t Hp = h.H + 2 * h.ph, Wp = h.W + 2 * h.pw, total = h.N * h.C * Hp * Wp;
@@ -591,6 +591,7 @@ static nt_status route_conv_unfold(const GemmLaunch &g, int *path_out, bool *tak
     ua.M = M; ua.Mp = Mp; ua.K = K;
     ua.C = (int32_t)h.C; ua.H = (int32_t)h.H; ua.W = (int32_t)h.W; ua.R = (int32_t)h.R; ua.S = (int32_t)h.S;
     ua.P = (int32_t)h.P; ua.Q = (int32_t)h.Q; ua.sh = (int32_t)h.sh; ua.sw = (int32_t)h.sw; ua.ph = (int32_t)h.ph; ua.pw = (int32_t)h.pw;
+    ua.dh = (int32_t)h.dh; ua.dw = (int32_t)h.dw;
     const int64_t blocks = std::min<int64_t>((Mp / 8 + 255) / 256, 1 << 16);
     hipLaunchKernelGGL(conv_unfold_kernel, dim3((unsigned)blocks, (unsigned)K), dim3(256), 0, s, ua);
     { const nt_status lst = check_launch("conv_unfold_kernel"); if (lst != NT_OK) return lst; }

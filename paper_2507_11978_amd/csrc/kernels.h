@@ -15,6 +15,7 @@ nt_status fail(nt_status st, const std::string &msg);   // records the thread-lo
 struct ConvHint {
     bool valid;
     int64_t N, C, H, W, K, R, S, P, Q, sh, sw, ph, pw;
+    int64_t dh, dw;                 // dilation (1 unless the views say otherwise)
     int64_t xs[4], ws[4], ys[4];
 };
 

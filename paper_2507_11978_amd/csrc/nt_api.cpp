@@ -55,12 +55,108 @@ nt_tile_cfg pick_tile(int kind, int64_t batch, int64_t M, int64_t N, int64_t K, 
 }
 
 
+// Views of a caller (nt_matmul_views) recognised as the implicit-GEMM views of a convolution (Section 4.3), possibly one per
+// group of a grouped convolution along the batch axis: the convolution of one group, and the element steps between groups.
+struct ViewConv {
+    bool found = false;
+    int64_t groups = 1;
+    nt::ConvHint hint{};
+    int64_t step_a = 0, step_b = 0, step_c = 0;
+};
+
 struct Problem {
     Arrangement va, vb, vc;          // single-level matrix views of the three operands
     MatmulArrangement mm;            // the matmul arrangement applied to them
     nt_tile_cfg tile;
     int64_t batch = 1, M = 0, N = 0, K = 0;
+    ViewConv vconv;
 };
+
+bool same_map(const OperandMap &a, const OperandMap &b)
+{
+    if (a.rows != b.rows || a.cols != b.cols || a.base != b.base || a.nrd != b.nrd || a.ncd != b.ncd || a.nchk != b.nchk) return false;
+    for (int i = 0; i < a.nrd; ++i)
+        if ((i > 0 && a.rrad[i] != b.rrad[i]) || a.roff[i] != b.roff[i]) return false;
+    for (int i = 0; i < a.ncd; ++i)
+        if ((i > 0 && a.crad[i] != b.crad[i]) || a.coff[i] != b.coff[i]) return false;
+    for (int q = 0; q < a.nchk; ++q) {
+        if (a.chk0[q] != b.chk0[q] || a.chk_size[q] != b.chk_size[q]) return false;
+        for (int i = 0; i < a.nrd; ++i)
+            if (a.rchk[q][i] != b.rchk[q][i]) return false;
+        for (int i = 0; i < a.ncd; ++i)
+            if (a.cchk[q][i] != b.cchk[q][i]) return false;
+    }
+    return true;
+}
+
+// Do the caller's three views address their tensors exactly like the library's own Section 4.3 arrangement of some
+// convolution (input (N, G Cg, H, W), filter (G Kg, Cg, R, S), output (N, G Kg, P, Q), G = the views' batch size)?  The
+// candidate's stride, dilation and padding are read off the input view's offsets; the answer is yes only if the
+// library's arrangement of that candidate lowers to the same three operand maps, field by field.  Then the views can run
+// on the convolution routes (the dedicated kernels, the padded copy, the unfolded input) instead of the operand-map kernel.
+void recognise_conv(const nt_tensor_desc *dx, const nt_tensor_desc *dw, const nt_tensor_desc *dy, const Arrangement &va,
+                    const Arrangement &vb, const Arrangement &vc, ViewConv *out)
+{
+    out->found = false;
+    if (dx->ndim != 4 || dw->ndim != 4 || dy->ndim != 4) return;
+    OperandMap ma, mb, mc;
+    int64_t ga = 1, gb = 1, gc = 1, sa = 0, sb = 0, sc = 0;
+    if (va.lower_matrix_view(&ma, &ga, &sa) != NT_OK || vb.lower_matrix_view(&mb, &gb, &sb) != NT_OK ||
+        vc.lower_matrix_view(&mc, &gc, &sc) != NT_OK)
+        return;
+    const int64_t G = va.level_shape(0).size() == 3 ? ga : 1;
+    const int64_t N = dx->size[0], H = dx->size[2], W = dx->size[3];
+    const int64_t F = dw->size[0], Cg = dw->size[1], R = dw->size[2], S = dw->size[3];
+    const int64_t P = dy->size[2], Q = dy->size[3];
+    if (G < 1 || N < 1 || Cg < 1 || R < 1 || S < 1 || P < 1 || Q < 1 || H < 1 || W < 1 || F < 1 || F % G) return;
+    const int64_t Kg = F / G;
+    if (dx->size[1] != G * Cg || dy->size[0] != N || dy->size[1] != F) return;
+    if (ma.rows != N * P * Q || ma.cols != Cg * R * S || mb.rows != ma.cols || mb.cols != Kg || mc.rows != ma.rows || mc.cols != Kg) return;
+    const int64_t xs2 = dx->stride[2], xs3 = dx->stride[3];
+    if (xs2 <= 0 || xs3 <= 0 || ma.rows >= (1LL << 40)) return;
+    auto at = [&](int64_t n, int64_t pp, int64_t q, int64_t c, int64_t r, int64_t s_) {
+        const int64_t row = (n * P + pp) * Q + q, col = (c * R + r) * S + s_;
+        int64_t off = 0;
+        (void)nt::element_at(ma, row, col, nt::row_part(ma, row), nt::col_part(ma, col), &off);
+        return off;
+    };
+    const int64_t f0 = at(0, 0, 0, 0, 0, 0);
+    auto step = [&](int64_t d, int64_t unit, int64_t *v) {      // a step of d elements along an axis of pitch `unit`: how many coordinates
+        if (d <= 0 || d % unit) return false;
+        *v = d / unit;
+        return *v < (1 << 20);
+    };
+    int64_t sh = 1, sw = 1, dh = 1, dw_ = 1;
+    if (P > 1 && !step(at(0, 1, 0, 0, 0, 0) - f0, xs2, &sh)) return;
+    if (Q > 1 && !step(at(0, 0, 1, 0, 0, 0) - f0, xs3, &sw)) return;
+    if (R > 1 && !step(at(0, 0, 0, 0, 1, 0) - f0, xs2, &dh)) return;
+    if (S > 1 && !step(at(0, 0, 0, 0, 0, 1) - f0, xs3, &dw_)) return;
+    // one group's tensors
+    nt_tensor_desc gx = *dx, gw = *dw, gy = *dy;
+    gx.size[1] = Cg; gw.size[0] = Kg; gy.size[1] = Kg;
+    for (int64_t ph = 0; ph <= (R - 1) * dh; ++ph)
+        for (int64_t pw = 0; pw <= (S - 1) * dw_; ++pw) {
+            if (-ph * xs2 - pw * xs3 != f0) continue;
+            Arrangement ex, ew, ey;
+            if (nt::conv2d_views(&gx, &gw, &gy, (int32_t)sh, (int32_t)sw, (int32_t)ph, (int32_t)pw, &ex, &ew, &ey, (int32_t)dh, (int32_t)dw_) != NT_OK) continue;
+            OperandMap ea, eb, ec;
+            int64_t b1, s1;
+            if (ex.lower_matrix_view(&ea, &b1, &s1) != NT_OK || ew.lower_matrix_view(&eb, &b1, &s1) != NT_OK ||
+                ey.lower_matrix_view(&ec, &b1, &s1) != NT_OK)
+                continue;
+            if (!same_map(ea, ma) || !same_map(eb, mb) || !same_map(ec, mc)) continue;
+            if (G > 1 && (sa != Cg * dx->stride[1] || sb != Kg * dw->stride[0] || sc != Kg * dy->stride[1])) continue;
+            nt::ConvHint &h = out->hint;
+            h.valid = true;
+            h.N = N; h.C = Cg; h.H = H; h.W = W; h.K = Kg; h.R = R; h.S = S; h.P = P; h.Q = Q;
+            h.sh = sh; h.sw = sw; h.ph = ph; h.pw = pw; h.dh = 1; h.dw = 1; h.dh = dh; h.dw = dw_;
+            for (int d = 0; d < 4; ++d) { h.xs[d] = dx->stride[d]; h.ws[d] = dw->stride[d]; h.ys[d] = dy->stride[d]; }
+            out->groups = G;
+            out->step_a = sa; out->step_b = sb; out->step_c = sc;
+            out->found = true;
+            return;
+        }
+}
 
 nt_status build_problem(int kind, const nt_tensor_desc *d0, const nt_tensor_desc *d1, const nt_tensor_desc *d2,
                         int32_t sh, int32_t sw, int32_t ph, int32_t pw, nt_tile_cfg cfg, Problem *p,
@@ -85,6 +181,8 @@ nt_status build_problem(int kind, const nt_tensor_desc *d0, const nt_tensor_desc
         const size_t ra = p->va.level_shape(0).size(), rb = p->vb.level_shape(0).size(), rc = p->vc.level_shape(0).size();
         if (ra != rb || ra != rc || (ra != 2 && ra != 3))
             return fail(NT_ERR_SHAPE_MISMATCH, "the three views must all be [rows, cols] or all [batch, rows, cols]");
+        recognise_conv(d0, d1, d2, p->va, p->vb, p->vc, &p->vconv);
+        (void)fail(NT_OK, "");                       // (attempts that did not fit leave no error text behind)
     } else {
         const int want = kind == KIND_BMM ? 3 : 2;
         if (d0->ndim != want || d1->ndim != want || d2->ndim != want)
@@ -104,7 +202,12 @@ nt_status build_problem(int kind, const nt_tensor_desc *d0, const nt_tensor_desc
     p->N = sb[o + 1];
     if (sb[o] != p->K) return fail(NT_ERR_SHAPE_MISMATCH, "inner dimensions of A and B differ");
     if (sc[o] != p->M || sc[o + 1] != p->N) return fail(NT_ERR_SHAPE_MISMATCH, "output shape differs from [M, N]");
-    p->tile = pick_tile(kind, p->batch, p->M, p->N, p->K, cfg, sh == 1 && sw == 1);
+    if (p->vconv.found) {
+        const nt::ConvHint &h = p->vconv.hint;
+        p->tile = pick_tile(KIND_CONV, 1, p->M, p->N, p->K, cfg, h.sh == 1 && h.sw == 1 && h.dh == 1 && h.dw == 1);
+    } else {
+        p->tile = pick_tile(kind, p->batch, p->M, p->N, p->K, cfg, sh == 1 && sw == 1);
+    }
     NT_TRY(nt::arrange_matmul(p->va, p->vb, p->vc, p->tile, &p->mm));
     return NT_OK;
 }
@@ -177,7 +280,7 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
         h.N = dA->size[0]; h.C = dA->size[1]; h.H = dA->size[2]; h.W = dA->size[3];
         h.K = dB->size[0]; h.R = dB->size[2]; h.S = dB->size[3];
         h.P = dC->size[2]; h.Q = dC->size[3];
-        h.sh = sh; h.sw = sw; h.ph = ph; h.pw = pw;
+        h.sh = sh; h.sw = sw; h.ph = ph; h.pw = pw; h.dh = 1; h.dw = 1;
         for (int d = 0; d < 4; ++d) { h.xs[d] = dA->stride[d]; h.ws[d] = dB->stride[d]; h.ys[d] = dC->stride[d]; }
     }
     g.A = A; g.B = B; g.C = C;
@@ -190,6 +293,20 @@ nt_status run(int kind, const void *A, const nt_tensor_desc *dA, const void *B, 
     g.out_dtype = out_dtype;
     g.stream = stream;
     if (trace) g.trace = *trace;
+    if (kind == KIND_VIEWS && p.vconv.found && !g.has_d) {
+        // the views are a convolution's: one launch per group on the convolution routes
+        const ViewConv &v = p.vconv;
+        const int64_t esz = out_dtype == NT_F32 ? 4 : 2;
+        g.conv = v.hint;
+        g.batch = 1;
+        for (int64_t gi = 0; gi < v.groups; ++gi) {
+            g.A = (const char *)A + gi * v.step_a * 2;
+            g.B = (const char *)B + gi * v.step_b * 2;
+            g.C = (char *)C + gi * v.step_c * esz;
+            NT_TRY(nt::launch_gemm(g, &t_last_path));
+        }
+        return NT_OK;
+    }
     if (static_ws) {
         // the library's workspace is out of bounds (it is allocated on first use); a k split goes through the fixed array
         void *p = nullptr;

@@ -96,6 +96,9 @@ CONFIGS = {
     "f4_f16_sdpa_4k": dict(kind="sdpa", B=1, H=48, S=4096, D=64, dtype="f16", out="f16", seed=0),
     "c5_f16_conv": dict(kind="conv", N=32, C=256, H=56, W=56, K=256, R=3, S=3, stride=1, pad=1,
                         dtype="f16", out="f16", seed=0),
+    # the same convolution written by the caller as an arrangement (Section 4.3) and run through the view interface
+    "f2_f16_conv_views": dict(kind="conv", via="views", N=32, C=256, H=56, W=56, K=256, R=3, S=3, stride=1, pad=1,
+                              dtype="f16", out="f16", seed=0),
     # the conv2d task of the paper's kernel list (Section 5.1): few output tiles, a long reduction
     "c6_f16_conv_paper": dict(kind="conv", N=4, C=512, H=14, W=14, K=512, R=3, S=3, stride=1, pad=0,
                               dtype="f16", out="f16", seed=0),

@@ -41,6 +41,82 @@ def test_convolution_written_as_an_arrangement_by_the_caller(shape, stride, pad,
     assert np.array_equal(to_f64(Y), ref)
 
 
+@pytest.mark.parametrize("shape,stride,pad,want", [
+    ((2, 32, 20, 24, 64, 3, 3), (1, 1), (1, 1), "direct"),        # dense, unit stride: the convolution kernel that streams into LDS
+    ((48, 64, 28, 28, 256, 3, 3), (1, 1), (1, 1), "tap"),          # ... and the one that walks the reduction tap by tap
+    ((2, 16, 21, 21, 64, 3, 3), (2, 2), (1, 1), "unfold"),        # strided: the unfolded input + the matrix kernels
+    ((2, 8, 20, 20, 32, 5, 5), (1, 1), (2, 2), "padded"),         # two columns of padding: the zero-padded copy
+])
+def test_a_callers_convolution_views_reach_the_convolution_kernels(shape, stride, pad, want):
+    """Views that address their tensors exactly like the Section 4.3 arrangement are recognised from their lowered index maps
+    and run where nt_conv2d_implicit runs: same kernels, bit-identical output."""
+    dt = "f16"
+    N, Cc, H, W, K, R, S = shape
+    X, Wt = si.small_int_bits((N, Cc, H, W), dt, 6), si.small_int_bits((K, Cc, R, S), dt, 7)
+    P = (H + 2 * pad[0] - R) // stride[0] + 1
+    Q = (W + 2 * pad[1] - S) // stride[1] + 1
+    px, pw, py = arr.conv2d_operand_programs(R, S, Cc, stride, pad, P, Q, H, W)
+    ref = onum.conv2d(X, Wt, dt, stride, pad, nthreads=16)
+    x, w = to_gpu(X, dt), to_gpu(Wt, dt)
+    Y = torch.full((N, K, P, Q), float("nan"), dtype=torch.float32, device="cuda")
+    nt.matmul_views(x, px, w, pw, Y, py)
+    torch.cuda.synchronize()
+    path = nt.last_kernel_path()
+    assert path == {"direct": nt.PATH_CONV_DIRECT, "tap": nt.PATH_CONV_TAP, "unfold": nt.PATH_CONV_UNFOLD, "padded": nt.PATH_CONV}[want]
+    assert np.array_equal(to_f64(Y), ref)
+    Y2 = torch.full((N, K, P, Q), float("nan"), dtype=torch.float32, device="cuda")
+    nt.conv2d_implicit(x, w, Y2, stride, pad)
+    torch.cuda.synchronize()
+    assert nt.last_kernel_path() == path and torch.equal(Y, Y2)
+
+
+@pytest.mark.parametrize("shape,stride,pad,dilation", [((2, 16, 20, 22, 64, 3, 3), (1, 1), (2, 2), (2, 2)), ((1, 8, 17, 19, 40, 3, 2), (2, 1), (1, 3), (1, 3)),
+                                                       ((2, 32, 16, 16, 96, 3, 3), (1, 1), (0, 0), (3, 2))])
+def test_dilated_convolution_views(shape, stride, pad, dilation):
+    """The tile operation's dilation, through the public interface: against the oracle's view product and, for its element
+    offsets, the oracle's enumerator (the unfolded input + the matrix kernels run it)."""
+    dt = "bf16"
+    N, Cc, H, W, K, R, S = shape
+    X, Wt = si.small_int_bits((N, Cc, H, W), dt, 16), si.small_int_bits((K, Cc, R, S), dt, 17)
+    P = (H + 2 * pad[0] - (R - 1) * dilation[0] - 1) // stride[0] + 1
+    Q = (W + 2 * pad[1] - (S - 1) * dilation[1] - 1) // stride[1] + 1
+    px, pw, py = arr.conv2d_operand_programs(R, S, Cc, stride, pad, P, Q, H, W, dilation)
+    ref = oracle_views(X, px, Wt, pw, (N, K, P, Q), py, dt)
+    for tile, want in ((None, nt.PATH_CONV_UNFOLD), ((64, 64, 32), nt.PATH_GENERIC)):
+        Y = torch.full((N, K, P, Q), float("nan"), dtype=torch.float32, device="cuda")
+        nt.matmul_views(to_gpu(X, dt), px, to_gpu(Wt, dt), pw, Y, py, tile=tile)
+        torch.cuda.synchronize()
+        assert nt.last_kernel_path() == want
+        assert np.array_equal(to_f64(Y), ref)
+
+
+@pytest.mark.parametrize("G,Cg,Kg,hw,stride,pad,dilation,want", [
+    (2, 32, 64, 24, (1, 1), (1, 1), (1, 1), "direct"),      # two groups, each on the convolution kernel
+    (4, 8, 8, 15, (2, 2), (1, 1), (1, 1), "unfold"),        # strided groups
+    (16, 1, 1, 12, (1, 1), (1, 1), (1, 1), None),            # depthwise: reduction of 9
+    (3, 4, 6, 11, (1, 2), (2, 0), (2, 1), None),            # dilated groups
+])
+def test_grouped_convolution_as_a_batched_view(G, Cg, Kg, hw, stride, pad, dilation, want):
+    dt = "f16"
+    N, H, W, R, S = 2, hw, hw + 1, 3, 3
+    X, Wt = si.small_int_bits((N, G * Cg, H, W), dt, 26), si.small_int_bits((G * Kg, Cg, R, S), dt, 27)
+    P = (H + 2 * pad[0] - (R - 1) * dilation[0] - 1) // stride[0] + 1
+    Q = (W + 2 * pad[1] - (S - 1) * dilation[1] - 1) // stride[1] + 1
+    px, pw, py = arr.grouped_conv2d_view_programs(G, Cg, Kg, R, S, stride, pad, P, Q, H, W, dilation)
+    ref = oracle_views(X, px, Wt, pw, (N, G * Kg, P, Q), py, dt)
+    Y = torch.full((N, G * Kg, P, Q), float("nan"), dtype=torch.float32, device="cuda")
+    nt.matmul_views(to_gpu(X, dt), px, to_gpu(Wt, dt), pw, Y, py)
+    torch.cuda.synchronize()
+    if want:
+        assert nt.last_kernel_path() == {"direct": nt.PATH_CONV_DIRECT, "unfold": nt.PATH_CONV_UNFOLD}[want]
+    assert np.array_equal(to_f64(Y), ref)
+    # the same views on the operand-map kernel (a tile named by the caller): one batched launch
+    Y.fill_(float("nan"))
+    nt.matmul_views(to_gpu(X, dt), px, to_gpu(Wt, dt), pw, Y, py, tile=(64, 64, 32))
+    torch.cuda.synchronize()
+    assert nt.last_kernel_path() == nt.PATH_GENERIC and np.array_equal(to_f64(Y), ref)
+
+
 def test_plain_transposed_gathered_and_batched_views():
     dt, M, N, K = "bf16", 300, 260, 200
     A, B = si.gemm_inputs(M, N, K, dt, seed=8, dist="int")

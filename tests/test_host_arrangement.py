@@ -203,3 +203,22 @@ def test_k_zero_and_empty_shapes():
     assert grid == (1, 2, 2) and kt == 0
     grid, kt = nt.arrange_gemm(((0, 5), None), ((5, 4), None), ((0, 4), None), tile=(2, 2, 2))
     assert grid == (1, 0, 2)
+
+
+@pytest.mark.parametrize("G,Cg,Kg,stride,pad,dilation", [(2, 3, 2, (1, 1), (1, 1), (1, 1)), (4, 1, 1, (2, 1), (0, 2), (1, 2)), (3, 2, 1, (1, 1), (2, 2), (2, 2))])
+def test_grouped_convolution_views_match_oracle(G, Cg, Kg, stride, pad, dilation):
+    """The programs that write a grouped convolution as one batched view: level shapes and every element's offset / mask."""
+    N, H, W, R, S = 2, 7, 6, 3, 3
+    P = (H + 2 * pad[0] - (R - 1) * dilation[0] - 1) // stride[0] + 1
+    Q = (W + 2 * pad[1] - (S - 1) * dilation[1] - 1) // stride[1] + 1
+    progs = arr.grouped_conv2d_view_programs(G, Cg, Kg, R, S, stride, pad, P, Q, H, W, dilation)
+    shapes = ((N, G * Cg, H, W), (G * Kg, Cg, R, S), (N, G * Kg, P, Q))
+    for shape, ops in zip(shapes, progs):
+        a = arr.run_program(arr.Tensor(shape), ops)
+        assert nt.arrange_levels(shape, None, ops) == a.levels
+        off, mask = arr.view_index_set(a)
+        # a single-level view is a grid of one-element tiles: program p is element p of the view
+        flat_off, flat_mask = off.ravel(), mask.ravel()
+        for pid in np.linspace(0, flat_off.size - 1, 97).astype(int):
+            o, m, _, _ = nt.arrange_tile(shape, None, ops, int(pid))
+            assert int(o[0]) == int(flat_off[pid]) and int(m[0]) == int(flat_mask[pid]), (shape, pid)
