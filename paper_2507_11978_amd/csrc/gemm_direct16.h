@@ -508,14 +508,19 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16_
                                EDGE && (g.M - row0 < BM || g.N - col0 < BN));
 }
 
-// ---- the same kernel with the ring unrolled: for reductions of a whole number of 128-k steps (4 slices) and a ring of four.
+// ---- the same kernel with the ring unrolled, for the 256 x 256 tile (ring of four).
 // A wavefront is alone on its SIMD, so every instruction it issues costs the SIMD one issue turn (4 cycles) and only
 // three fit behind a 16-cycle matrix instruction.  With the ring position a compile-time constant, every LDS read is a
 // per-lane base plus an immediate offset and every LDS target of a global -> LDS load a precomputed scalar (no address
-// arithmetic in the loop); the global pointers advance by one scalar addition per slice and operand, issued between matrix
-// instructions; no clamping per load: the last pass of the loop, which has nothing left to request, fetches the last
-// slice again.  At most two other instructions follow any matrix instruction.
-template <int BM, int BN, bool BF16, int ALAY, int BLAY>
+// arithmetic in the loop).  At most two other instructions follow any matrix instruction.
+// EDGE = false (full tiles of aligned operands, a whole number of 128-k steps): plain loads; the global pointers advance by
+// one scalar addition per slice and operand; no clamping per load: the last pass of the loop, which has nothing left to
+// request, fetches the last slice again.
+// EDGE = true (see gemm_direct16_kernel): range-checked loads at a scalar offset per slice and operand; slices past the last
+// are requested at an offset beyond any buffer, arrive as zeros, and their trips add nothing (any number of slices is
+// rounded up to whole passes); the last slice's ragged tail and the operand's last odd element are put right once it has
+// landed, behind one uniform test per trip.
+template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE = false>
 __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16u_kernel(const FastArgs g)
 {
     constexpr int TM = BM / 32, TN = BN / 32;
@@ -537,7 +542,9 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16u
     const char *pb = reinterpret_cast<const char *>(g.B + bi * g.sb_batch + (BLAY == KCONTIG ? col0 * g.ldb : col0));
     const int64_t a_step = (ALAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.lda) * 2;
     const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.ldb) * 2;
-    const int64_t n_slices = g.kt * (kBK / kSliceK);       // a multiple of 4, at least 4 (checked by the host)
+    // (full tiles: a multiple of 4, at least 4, checked by the host)
+    const int64_t n_slices = EDGE ? (g.K + kSliceK - 1) / kSliceK : g.kt * (kBK / kSliceK);
+    const int32_t last = (int32_t)n_slices - 1;
 
     TileA ta;
     TileB tb;
@@ -566,22 +573,64 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16u
             tgt[r][d] = d < TileA::PER ? lds0 + r * A_BYTES + (uint32_t)((wave * TileA::PER + d) * 1024)
                                        : lds0 + B_BASE + r * B_BYTES + (uint32_t)((wave * TileB::PER + d - TileA::PER) * 1024);
 
+    // EDGE: range-checked views of the operands from this program's tile origin on, the scalar offsets of the slice that is
+    // requested next (slice `rq`), and the one element that the range check may have dropped (see gemm_direct16_kernel)
+    u32x4 rsrc_a{0, 0, 0, 0}, rsrc_b{0, 0, 0, 0};
+    uint32_t rq_aoff = 0, rq_boff = 0;
+    int32_t rq = 0;
+    int patch_a = -1, patch_b = -1;
+    if constexpr (EDGE) {
+        rsrc_a = make_rsrc(pa, g.a_extent - (pa - reinterpret_cast<const char *>(g.A + bi * g.sa_batch)));
+        rsrc_b = make_rsrc(pb, g.b_extent - (pb - reinterpret_cast<const char *>(g.B + bi * g.sb_batch)));
+        const int kk = (int)(g.K - 1 - (int64_t)last * kSliceK);
+        const int64_t ra = g.M - 1 - row0, rb = g.N - 1 - col0;
+        if ((g.patch & 1) && ra < BM && TileA::owner((int)ra, kk) == wave) patch_a = (int)TileA::place((int)ra, kk);
+        if ((g.patch & 2) && rb < BN && TileB::owner((int)rb, kk) == wave) patch_b = (int)TileB::place((int)rb, kk);
+    }
+    auto aim_request = [&]() {                               // (after a change of rq)
+        const bool live = rq <= last;                          // (uniform)
+        rq_aoff = live ? (uint32_t)rq * (uint32_t)a_step : 0x80000000u;
+        rq_boff = live ? (uint32_t)rq * (uint32_t)b_step : 0x80000000u;
+    };
+    // what the last slice needs once this wavefront's part of it has landed at ring position `pos`
+    auto settle_last = [&](uint32_t pos) {
+        if ((int64_t)(last + 1) * kSliceK > g.K) {
+            const int keep = (int)(g.K - (int64_t)last * kSliceK);
+            ta.zero_tail(smem, pos * A_BYTES, wave, lane, keep);
+            tb.zero_tail(smem, B_BASE + pos * B_BYTES, wave, lane, keep);
+        }
+        if (g.patch && lane == 0) {
+            if (patch_a >= 0)
+                *reinterpret_cast<uint16_t *>(smem + pos * A_BYTES + patch_a) =
+                    *reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(g.A + bi * g.sa_batch) + g.a_extent - 2);
+            if (patch_b >= 0)
+                *reinterpret_cast<uint16_t *>(smem + B_BASE + pos * B_BYTES + patch_b) =
+                    *reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(g.B + bi * g.sb_batch) + g.b_extent - 2);
+        }
+    };
+
     u32x4 fa[2][TM], fb[2][TN];
     auto lds_read = [&](int r, int set, uint32_t ring) {
         if (r < TileA::RPF) ta.read(fa[set], smem, r, ring * A_BYTES);
         else if (r < TileA::RPF + NRB) tb.read(fb[set], smem, r - TileA::RPF, ring * B_BYTES);
         else ta.read(fa[set], smem, r - NRB, ring * A_BYTES);
     };
-    // load d of the slice at (pa, pb) into ring position `ring`, in two halves that go behind different matrix
-    // instructions (the matrix instruction between them is the wait state the hardware wants after a write to m0)
+    // load d of the slice at (pa, pb) / at the request offsets into ring position `ring`, in two halves that go behind
+    // different matrix instructions (the matrix instruction between them is the wait state the hardware wants after a
+    // write to m0)
     auto dma_aim = [&](int d, int ring) { asm volatile("s_mov_b32 m0, %0" : : "s"(tgt[ring][d]) : "memory"); };
     auto dma_go = [&](int d) {
-        if (d < TileA::PER) asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(ta.voff[d]), "s"(pa) : "memory");
-        else asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(tb.voff[d - TileA::PER]), "s"(pb) : "memory");
+        if constexpr (EDGE) {
+            if (d < TileA::PER) asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds" : : "v"(ta.voff[d]), "s"(rsrc_a), "s"(rq_aoff) : "memory");
+            else asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds" : : "v"(tb.voff[d - TileA::PER]), "s"(rsrc_b), "s"(rq_boff) : "memory");
+        } else {
+            if (d < TileA::PER) asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(ta.voff[d]), "s"(pa) : "memory");
+            else asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(tb.voff[d - TileA::PER]), "s"(pb) : "memory");
+        }
     };
 
     // One trip = one slice: the matrix instructions on fragment set SET (slice s); behind them the LDS reads of slice
-    // s+1 (ring position RING+1) into the other set and, if DMA, the loads of slice s+4 into ring position RING.
+    // s+1 (ring position RING+1) into the other set and the loads of slice s+4 into ring position RING.
     auto trip = [&](auto ring_c, auto set_c, int64_t a_adv, int64_t b_adv) {
         constexpr int RING = decltype(ring_c)::value, SET = decltype(set_c)::value;
         constexpr int NXT = (RING + 1) % kRing;
@@ -590,12 +639,15 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16u
             const int tm = idx / TN, tn = idx % TN;
             mfma16<BF16>(acc[tm][tn], fb[SET][tn], fa[SET][tm]);      // transposed block (see store_tile16_rows)
             if (idx % 2 == 0 && idx / 2 < NR) lds_read(idx / 2, SET ^ 1, NXT);
+            if (EDGE && idx == 0) { ++rq; aim_request(); }
             if (idx % 8 == 1 && idx / 8 < ND) dma_aim(idx / 8, RING);
             if (idx % 8 == 3 && idx / 8 < ND) {
                 dma_go(idx / 8);
-                // the operand's last load of this trip is out: its pointer moves on to the next slice
-                if (idx / 8 == TileA::PER - 1) { pa += a_adv; asm volatile("" : "+s"(pa)); }
-                if (idx / 8 == ND - 1) { pb += b_adv; asm volatile("" : "+s"(pb)); }
+                if constexpr (!EDGE) {
+                    // the operand's last load of this trip is out: its pointer moves on to the next slice
+                    if (idx / 8 == TileA::PER - 1) { pa += a_adv; asm volatile("" : "+s"(pa)); }
+                    if (idx / 8 == ND - 1) { pb += b_adv; asm volatile("" : "+s"(pb)); }
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -605,6 +657,7 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16u
     // prologue: slices 0 .. 3 requested; wait for slice 0; its fragments into set 0
 #pragma unroll
     for (int s = 0; s < kRing; ++s) {
+        if constexpr (EDGE) { rq = s; aim_request(); }
 #pragma unroll
         for (int d = 0; d < ND; ++d) {
             dma_aim(d, s);
@@ -616,6 +669,9 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16u
     }
     asm volatile("" : "+s"(pa), "+s"(pb));
     NT_WAIT_VMCNT((kRing - 1) * ND);
+    if constexpr (EDGE) {
+        if (last == 0) settle_last(0);
+    }
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < NR; ++r) lds_read(r, 0, 0);
@@ -624,20 +680,30 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16u
     // Slice s sits at ring position s % 4.  At the top of trip s this wavefront's part of slice s+1 must have landed
     // (the loads of the two younger slices may still be in flight); the barrier then says that slice s+1 is complete
     // and that every wavefront holds its fragments of slice s in registers, so that slice s+4 can overwrite it.
-    // One pass of the loop = four trips.  The last pass has nothing left to request: its loads fetch the last slice
-    // again (the pointers are set back to it and stand still) into ring positions that nobody reads any more, so that
+    // One pass of the loop = four trips.  Full tiles: the last pass has nothing left to request; its loads fetch the last
+    // slice again (the pointers are set back to it and stand still) into ring positions that nobody reads any more, so that
     // the loop has one shape, one wait count, and no second copy of its body.
     const char *pa_last = pa - a_step, *pb_last = pb - b_step;         // (after the prologue's four steps: slice 3)
     pa_last += (n_slices - kRing) * a_step;
     pb_last += (n_slices - kRing) * b_step;
     int64_t a_adv = a_step, b_adv = b_step;
+    // (EDGE) the trip of slice s fixes up slice s + 1 when that is the last one
+    auto top = [&](int64_t s, uint32_t nxt) {
+        NT_WAIT_VMCNT(2 * ND);
+        if constexpr (EDGE) {
+            if (s + 1 == last) settle_last(nxt);                       // (uniform)
+        }
+        __syncthreads();
+    };
     for (int64_t sl = 0; sl < n_slices; sl += kRing) {
-        if (sl + kRing >= n_slices) { pa = pa_last; pb = pb_last; a_adv = 0; b_adv = 0; }     // wavefront-uniform
-        asm volatile("" : "+s"(pa), "+s"(pb), "+s"(a_adv), "+s"(b_adv));
-        NT_WAIT_VMCNT(2 * ND); __syncthreads(); trip(integral_constant<int, 0>{}, integral_constant<int, 0>{}, a_adv, b_adv);
-        NT_WAIT_VMCNT(2 * ND); __syncthreads(); trip(integral_constant<int, 1>{}, integral_constant<int, 1>{}, a_adv, b_adv);
-        NT_WAIT_VMCNT(2 * ND); __syncthreads(); trip(integral_constant<int, 2>{}, integral_constant<int, 0>{}, a_adv, b_adv);
-        NT_WAIT_VMCNT(2 * ND); __syncthreads(); trip(integral_constant<int, 3>{}, integral_constant<int, 1>{}, a_adv, b_adv);
+        if constexpr (!EDGE) {
+            if (sl + kRing >= n_slices) { pa = pa_last; pb = pb_last; a_adv = 0; b_adv = 0; }     // wavefront-uniform
+            asm volatile("" : "+s"(pa), "+s"(pb), "+s"(a_adv), "+s"(b_adv));
+        }
+        top(sl + 0, 1); trip(integral_constant<int, 0>{}, integral_constant<int, 0>{}, a_adv, b_adv);
+        top(sl + 1, 2); trip(integral_constant<int, 1>{}, integral_constant<int, 1>{}, a_adv, b_adv);
+        top(sl + 2, 3); trip(integral_constant<int, 2>{}, integral_constant<int, 0>{}, a_adv, b_adv);
+        top(sl + 3, 0); trip(integral_constant<int, 3>{}, integral_constant<int, 1>{}, a_adv, b_adv);
         // (wait states between the last matrix instruction and anything the compiler may do to an accumulator at the
         // loop's end: it does not know that the inline assembly is a matrix instruction)
         asm volatile("s_nop 7" ::: "memory");
@@ -649,7 +715,8 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16u
     // in program order, so every read follows the wait states).
     asm volatile("s_nop 15" ::: "memory");
 
-    store_tile16<BM, BN>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane);
+    store_tile16<BM, BN, EDGE>(g, smem, wave, bi, acc, row0 + wave_m * (BM / 2), col0 + wave_n * (BN / 2), lane,
+                               EDGE && (g.M - row0 < BM || g.N - col0 < BN));
 }
 
 template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE = false>
@@ -660,16 +727,17 @@ static nt_status launch_direct16_inst(const FastArgs &a, int64_t nwg, hipStream_
     static DeviceOnce configured;
     if (!configured.done()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if constexpr (BM == 256 && BN == 256 && !EDGE)
-            if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_direct16u_kernel<BM, BN, BF16, ALAY, BLAY>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if constexpr (BM == 256 && BN == 256)
+            if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_direct16u_kernel<BM, BN, BF16, ALAY, BLAY, EDGE>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
         configured.set();
     }
     // (the 256 x 256 tile -- one workgroup per compute unit, every issue turn counts -- with a reduction of whole 128-k steps:
     // the kernel with the unrolled ring)
-    if constexpr (BM == 256 && BN == 256 && !EDGE) {
-        if (a.kt % 2 == 0 && a.kt >= 2) {
-            hipLaunchKernelGGL((gemm_direct16u_kernel<BM, BN, BF16, ALAY, BLAY>), dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
+    if constexpr (BM == 256 && BN == 256) {
+        // (range-checked flavour: any number of slices is rounded up to whole passes of four; worth it from three passes on)
+        if (EDGE ? a.K > 8 * kSliceK : (a.kt % 2 == 0 && a.kt >= 2)) {
+            hipLaunchKernelGGL((gemm_direct16u_kernel<BM, BN, BF16, ALAY, BLAY, EDGE>), dim3((unsigned)nwg), dim3(kThreads), smem, s, a);
             return check_launch("gemm_direct16u_kernel");
         }
     }
