@@ -136,7 +136,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default 50; 2000 for the kernels that run for tens of microseconds)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 50; 1000 for those short kernels)")
     ap.add_argument("--workload", default="p_f16_8192",
-                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, f2_f16_conv_views, c6_f16_conv_paper, c1_f16_256, f1_f16_addmm, f1_f16_bias_gelu, f3_f16_add, f3_f16_silu, f3_f16_softmax, f3_f16_rms_norm, f4_f16_sdpa, f4_bf16_sdpa, f4_f16_sdpa_4k")
+                    help="p_f16_8192 (default, headline), c2_f16_4096, c3_bf16_ragged, c4_f16_bmm, c5_f16_conv, c5_f16_conv_krsc, f2_f16_conv_views, c6_f16_conv_paper, c1_f16_256, f1_f16_addmm, f1_f16_bias_gelu, f3_f16_add, f3_f16_silu, f3_f16_softmax, f3_f16_rms_norm, f4_f16_sdpa, f4_bf16_sdpa, f4_f16_sdpa_4k")
     ap.add_argument("--tile", default=None, help="bm,bn,bk (default: library choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -341,6 +341,8 @@ def main():
     if cfg["kind"] == "conv":
         Xb, Wb = si.conv_inputs(cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"], cfg["R"], cfg["S"], dt, cfg["seed"])
         x, w = to_gpu(Xb, dt), to_gpu(Wb, dt)
+        if cfg.get("filter") == "krsc":
+            w = w.permute(0, 2, 3, 1).contiguous().permute(0, 3, 1, 2)       # the same tensor, stored (f, r, s, c)
         P = (cfg["H"] + 2 * cfg["pad"] - cfg["R"]) // cfg["stride"] + 1
         Q = (cfg["W"] + 2 * cfg["pad"] - cfg["S"]) // cfg["stride"] + 1
         y = torch.empty((cfg["N"], cfg["K"], P, Q), dtype=TORCH_DT[out], device="cuda")

@@ -305,7 +305,8 @@ nt_status nt_bmm(const void *A, const nt_tensor_desc *dA, const void *B, const n
  * stride_h + 1 (integer division), likewise Q; otherwise NT_ERR_SHAPE_MISMATCH.
  * Descriptors have ndim 4 with arbitrary strides.
  * Dense unit-stride calls (contiguous NCHW input, at most one column of padding) never materialise the unfolded input; with
- * more than 128 filters and channels in whole blocks of 32 they copy the filter (only) into the workspace in tap-major order.  The
+ * more than 128 filters and channels in whole blocks of 32 they copy the filter (only) into the workspace in tap-major order,
+ * unless it is stored that way already (a channels-last filter: strides (R S C, 1, S C, C)), which is then read as it is.  The
  * other convolutions on the library's own tile go through the library's workspace when what they need fits it:
  * unit-stride ones (wide padding, channels-last views) make a dense zero-padded copy of the input and run on that;
  * strided ones write the unfolded input once and run the product on the matrix kernels.  Else, or with a tile

@@ -36,6 +36,9 @@ struct ConvArgs {
     // that conv_ws_sum_kernel adds up in a fixed order).  Without a split: ksplit = 1, kt_per = kt, slice = 0.
     int32_t ksplit, kt_per;
     int64_t slice;
+    // the filter is stored tap-major already, [filter][r][s][c] (a channels-last filter): Wt[f * ldb + (r * S + s) * C + c];
+    // only the kernel that walks the reduction tap by tap takes it
+    int32_t filter_tap_major;
     // loader trace of the direct kernel (nullptr otherwise), see FastArgs
     uint16_t *trace_out;
     int64_t trace_program;

@@ -3,14 +3,19 @@
 
 namespace nt {
 
-// filter [F][C][R * S] (row pitch ldb) -> [F][R * S][C] (row pitch K = C R S)
-__global__ __launch_bounds__(256) void conv_repack_filter_kernel(const uint16_t *w, int64_t ldb, uint16_t *out, int32_t F, int32_t C, int32_t RS)
+// filter [F][C][R * S] (row pitch ldb) -> [F][R * S][C] (row pitch K = C R S): one workgroup per filter, the row read and
+// written with consecutive lanes on consecutive elements, permuted on its way through LDS
+__global__ __launch_bounds__(256) void conv_repack_filter_kernel(const uint16_t *w, int64_t ldb, uint16_t *out, int32_t C, int32_t RS)
 {
-    const int64_t K = (int64_t)C * RS, total = (int64_t)F * K;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-        const int64_t f = i / K;
-        const int32_t kk = (int32_t)(i - f * K), tap = kk / C, c = kk - tap * C;
-        out[i] = w[f * ldb + (int64_t)c * RS + tap];
+    extern __shared__ uint16_t row[];
+    const int32_t K = C * RS;
+    const uint16_t *src = w + (int64_t)blockIdx.x * ldb;
+    uint16_t *dst = out + (int64_t)blockIdx.x * K;
+    for (int32_t i = threadIdx.x; i < K; i += 256) row[i] = src[i];
+    __syncthreads();
+    for (int32_t j = threadIdx.x; j < K; j += 256) {
+        const int32_t tap = j / C, c = j - tap * C;
+        dst[j] = row[c * RS + tap];
     }
 }
 
@@ -30,9 +35,8 @@ nt_status launch_conv_tap_trace(const ConvArgs &a, int rows, hipStream_t s)
 
 nt_status launch_conv_repack_filter(const uint16_t *w, int64_t ldb, uint16_t *out, int32_t F, int32_t C, int32_t RS, hipStream_t s)
 {
-    const int64_t total = (int64_t)F * C * RS;
-    const int64_t blocks = std::min<int64_t>((total + 255) / 256, 2048);
-    hipLaunchKernelGGL(conv_repack_filter_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, ldb, out, F, C, RS);
+    // (the reduction is below 2^16 elements: a row fits LDS)
+    hipLaunchKernelGGL(conv_repack_filter_kernel, dim3((unsigned)F), dim3(256), (size_t)C * RS * sizeof(uint16_t), s, w, ldb, out, C, RS);
     return check_launch("conv_repack_filter_kernel");
 }
 

@@ -247,13 +247,18 @@ bool tile_is_built(nt_tile_cfg cfg)
 // The dense convolution that the convolution kernels handle: contiguous NCHW input, conv stride 1, at
 // most one element of left / right padding, a filter whose (c, r, s) are contiguous, an output with
 // contiguous (p, q).  Everything else runs on the operand-map kernel.
+static bool conv_tap_ok(const GemmLaunch &g, const ConvArgs &c, size_t *repack_bytes);
+
 static bool match_conv(const GemmLaunch &g, ConvArgs *a)
 {
     const ConvHint &h = g.conv;
     if (!h.valid || g.batch != 1 || g.tile.bm != 256 || g.tile.bk != 64 || (g.tile.bn != 128 && g.tile.bn != 256)) return false;
     if (h.sh != 1 || h.sw != 1 || h.dh != 1 || h.dw != 1 || h.ph < 0 || h.pw < 0 || h.pw > 1 || h.R > 31 || h.S > 31 || h.P <= 0 || h.Q <= 0) return false;
     if (h.xs[3] != 1 || h.xs[2] != h.W || h.xs[1] != h.H * h.W || h.xs[0] != h.C * h.H * h.W) return false;
-    if (h.ws[3] != 1 || h.ws[2] != h.S || h.ws[1] != h.R * h.S || h.ws[0] <= 0 || h.ws[0] >= (1 << 22)) return false;
+    // filter rows contiguous in (c, r, s), or in (r, s, c) (a channels-last filter, which is the tap-major kernel's own order)
+    const bool krsc = h.ws[1] == 1 && h.ws[3] == h.C && h.ws[2] == h.S * h.C && (h.C > 1 || h.R * h.S == 1);
+    if (!krsc && (h.ws[3] != 1 || h.ws[2] != h.S || h.ws[1] != h.R * h.S)) return false;
+    if (h.ws[0] <= 0 || h.ws[0] >= (1 << 22)) return false;
     if (h.ys[3] != 1 || h.ys[2] != h.Q) return false;
     // the kernel numbers the output positions with the row pitch rounded up to a multiple of 8
     const int64_t Q8 = (h.Q + 7) / 8 * 8;
@@ -276,6 +281,11 @@ static bool match_conv(const GemmLaunch &g, ConvArgs *a)
     a->mt = (NPQ + 255) / 256; a->nt = g.nt; a->kt = g.kt;
     a->out_dtype = g.out_dtype;
     a->ksplit = 1; a->kt_per = (int32_t)g.kt; a->slice = 0;
+    a->filter_tap_major = krsc && !(h.ws[3] == 1 && h.ws[2] == h.S && h.ws[1] == h.R * h.S) ? 1 : 0;
+    if (a->filter_tap_major) {                               // (no other kernel reads that layout)
+        size_t unused = 0;
+        if (!conv_tap_ok(g, *a, &unused)) return false;
+    }
     return true;
 }
 
@@ -428,8 +438,9 @@ static bool conv_direct_ok(const GemmLaunch &g, const ConvArgs &c)
 // whole blocks of 32, padding smaller than the image; it reads the filter from a tap-major copy of `*repack_bytes` bytes
 static bool conv_tap_ok(const GemmLaunch &g, const ConvArgs &c, size_t *repack_bytes)
 {
-    *repack_bytes = ((size_t)c.N * c.K * 2 + 255) / 256 * 256;
-    return conv_direct_ok(g, c) && g.tile.bn == 256 && c.N > 128 && g.conv.C % 32 == 0 && c.ph < c.H && c.pw < c.W;
+    *repack_bytes = c.filter_tap_major ? 0 : ((size_t)c.N * c.K * 2 + 255) / 256 * 256;
+    // (a filter row fits the LDS of the kernel that copies it: K <= 32768; one bit per tap: R S <= 32)
+    return conv_direct_ok(g, c) && g.tile.bn == 256 && c.N > 128 && g.conv.C % 32 == 0 && c.ph < c.H && c.pw < c.W && c.K <= 32768 && c.RS <= 32;
 }
 
 // workspace that route 1 asks for: the filter's tap-major copy, then the fp32 slices of the k split
@@ -461,26 +472,28 @@ static nt_status route_conv_implicit(const GemmLaunch &g, const ConvArgs &c, int
     // order needs none), then the split.
     WorkspaceLease lease;
     char *region = nullptr;
-    if (tap || ksplit > 1) {
+    if ((tap && repack_bytes) || ksplit > 1) {
         nt_status st;
         region = (char *)split_region(g, (tap ? repack_bytes : 0) + split_bytes, lease, &st);
-        if (!region && tap) {
+        if (!region && tap && !c.filter_tap_major) {
             tap = false;
             if (ksplit > 1) region = (char *)split_region(g, split_bytes, lease, &st);
         }
         if (st != NT_OK) return st;
     }
-    uint16_t *wt_tap = tap ? (uint16_t *)region : nullptr;
+    uint16_t *wt_tap = tap && repack_bytes ? (uint16_t *)region : nullptr;
     float *ws = region && ksplit > 1 ? (float *)(region + (tap ? repack_bytes : 0)) : nullptr;
     if (direct && path_out) *path_out = tap ? PATH_CONV_TAP : PATH_CONV_DIRECT;
     const bool bf16 = g.in_dtype == NT_BF16;
     ConvArgs base = c;
     int tap_rows = 256;
     if (tap) {
-        const nt_status st = launch_conv_repack_filter(c.Wt, c.ldb, wt_tap, c.N, (int32_t)g.conv.C, c.RS, s);
-        if (st != NT_OK) return st;
-        base.Wt = wt_tap;
-        base.ldb = c.K;
+        if (wt_tap) {
+            const nt_status st = launch_conv_repack_filter(c.Wt, c.ldb, wt_tap, c.N, (int32_t)g.conv.C, c.RS, s);
+            if (st != NT_OK) return st;
+            base.Wt = wt_tap;
+            base.ldb = c.K;
+        }
         // tile height: whole rounds of 256 programs (one per compute unit) cost their length, 32 h positions plus a fixed part
         auto cost = [&](int rows) {
             const int64_t programs = (c.M + rows - 1) / rows * c.nt * ksplit;

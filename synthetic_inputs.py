@@ -96,6 +96,10 @@ CONFIGS = {
     "f4_f16_sdpa_4k": dict(kind="sdpa", B=1, H=48, S=4096, D=64, dtype="f16", out="f16", seed=0),
     "c5_f16_conv": dict(kind="conv", N=32, C=256, H=56, W=56, K=256, R=3, S=3, stride=1, pad=1,
                         dtype="f16", out="f16", seed=0),
+    # the same convolution with its filter stored channels-last, (f, r, s, c): the order in which the kernel for 256 filters walks
+    # the reduction, so that it reads the filter as it is instead of copying it first
+    "c5_f16_conv_krsc": dict(kind="conv", filter="krsc", N=32, C=256, H=56, W=56, K=256, R=3, S=3, stride=1, pad=1,
+                             dtype="f16", out="f16", seed=0),
     # the same convolution written by the caller as an arrangement (Section 4.3) and run through the view interface
     "f2_f16_conv_views": dict(kind="conv", via="views", N=32, C=256, H=56, W=56, K=256, R=3, S=3, stride=1, pad=1,
                               dtype="f16", out="f16", seed=0),

@@ -126,7 +126,7 @@ def whole_matrix(view, n_row_tiles, n_col_tiles, kt, pid_of, rows_first):
     return np.concatenate(blocks, axis=0 if rows_first else 1)
 
 
-@pytest.mark.parametrize("Nn,C,H,W,F,R,S,pad", [
+@pytest.mark.parametrize("Nn,C,H,W,F,R,S,pad,layout", [(*c, "kcrs") if len(c) == 8 else c for c in [
     (2, 32, 16, 16, 64, 3, 3, (1, 1)),        # output rows of 16 positions; left / right / top / bottom padding
     (3, 32, 14, 14, 96, 3, 3, (1, 1)),        # rows of 14 positions: the kernel numbers them with a pitch of 16
     (2, 64, 10, 10, 256, 3, 3, (0, 0)),       # no padding, rows of 8
@@ -137,8 +137,9 @@ def whole_matrix(view, n_row_tiles, n_col_tiles, kt, pid_of, rows_first):
     (3, 32, 16, 16, 300, 3, 3, (1, 1)),       # the same with one channel block per tap, rows of 16, a ragged last filter tile
     (1, 64, 9, 9, 192, 2, 2, (0, 1)),         # 2 x 2 filter, rows of 9 (a run that starts in the right padding)
     (2, 32, 6, 20, 256, 5, 3, (1, 1)),        # 5 x 3 filter
-])
-def test_convolution(Nn, C, H, W, F, R, S, pad):
+    (2, 64, 14, 14, 256, 3, 3, (1, 1), "krsc"),   # the filter stored channels-last, (f, r, s, c): read as it is, no copy
+]])
+def test_convolution(Nn, C, H, W, F, R, S, pad, layout):
     dt = "f16"
     P, Q = H + 2 * pad[0] - R + 1, W + 2 * pad[1] - S + 1
     Q8 = -(-Q // 8) * 8
@@ -149,8 +150,10 @@ def test_convolution(Nn, C, H, W, F, R, S, pad):
     BNk = 64 if F <= 64 else BN                 # few filters: the same grid is run by the kernel built for 64 per program
     shx, shw, shy = (Nn, C, H, W), (F, C, R, S), (Nn, F, P, Q)
     sx, sw = contiguous(shx), contiguous(shw)
+    if layout == "krsc":
+        sw = (R * S * C, 1, S * C, C)
     BMo, BKo = 64, 64
-    a_arr, b_arr, _ = arr.conv2d_arrangement(arr.Tensor(shx), arr.Tensor(shw), arr.Tensor(shy), BMo, BN, BKo, (1, 1), pad)
+    a_arr, b_arr, _ = arr.conv2d_arrangement(arr.Tensor(shx), arr.Tensor(shw, sw), arr.Tensor(shy), BMo, BN, BKo, (1, 1), pad)
     Mo = Nn * P * Q
     mto, nto, kto = -(-Mo // BMo), -(-F // BN), -(-K // BKo)
     A_ref = whole_matrix(a_arr, mto, nto, kto, lambda t: t * nto, True)[:Mo, :K]          # [positions, C R S]

@@ -685,3 +685,21 @@ def test_device_address_generator_matches_oracle():
         off, mask = nt.trace_tile("bmm", *d, tile, 0, pid, 1)
         o_off, o_mask, _ = arr.tile_index_set(a, pid, (1,))
         assert np.array_equal(off, o_off) and np.array_equal(mask, o_mask)
+
+
+def test_convolution_with_a_channels_last_filter():
+    """A filter stored (f, r, s, c) and described by its strides: the kernel that walks the reduction tap by tap reads it as it
+    is (that is its own order); same result, bit for bit, as with the (f, c, r, s) filter."""
+    dt = "f16"
+    N, Cc, H, W, K, R, S, pad = 40, 64, 28, 28, 256, 3, 3, (1, 1)
+    X, Wt = si.small_int_bits((N, Cc, H, W), dt, 31), si.small_int_bits((K, Cc, R, S), dt, 32)
+    ref = onum.conv2d(X, Wt, dt, (1, 1), pad, nthreads=16)
+    x, w = to_gpu(X, dt), to_gpu(Wt, dt)
+    w_last = w.permute(0, 2, 3, 1).contiguous().permute(0, 3, 1, 2)              # same tensor, channels-last storage
+    assert w_last.stride() == (R * S * Cc, 1, S * Cc, Cc) and torch.equal(w_last, w)
+    for filt in (w, w_last):
+        Y = torch.full(ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+        nt.conv2d_implicit(x, filt, Y, (1, 1), pad, tile=(256, 256, 64))
+        torch.cuda.synchronize()
+        assert nt.last_kernel_path() == nt.PATH_CONV_TAP
+        assert np.array_equal(to_f64(Y), ref)
