@@ -387,6 +387,19 @@ struct DeviceOnce {
     void set() { flag[device()].store(true, std::memory_order_release); }
 };
 
+// Compute units of the current device (0 if the query fails), asked once per device.
+inline int64_t compute_units()
+{
+    static std::atomic<int> count[64];
+    const int d = DeviceOnce::device();
+    int n = count[d].load(std::memory_order_acquire);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, d) != hipSuccess || n < 0) n = 0;
+        count[d].store(n, std::memory_order_release);
+    }
+    return n;
+}
+
 nt_status launch_generic(const GemmLaunch &g);
 
 }  // namespace nt

@@ -183,9 +183,17 @@ struct DirectTile16<E, MNCONTIG> {
 //   read phase   16 consecutive lanes read one row; a store instruction covers 4 rows of 256 contiguous bytes.
 // An fp32 tile takes two passes (one per half of the columns) through the same region.
 // CHECK masks rows >= M and columns >= N (a partly valid 16-byte chunk is stored element-wise; D is read element-wise there).
-template <int BM, int BN, int OUT, bool CHECK>
+// RP: the wavefront's 128 rows go through the region in RP passes of 128 / RP rows (a region of 32 / RP KB per wavefront:
+// the persistent kernel stages through the 32 KB of LDS that its ring leaves free).
+// AFFINE: alpha, beta * D or an activation is asked for.  A variant of its own, because the plain product's epilogue must be
+// straight-line code: a wavefront-uniform test per accumulator block costs an instruction fetch each, which nothing hides
+// with one wavefront per SIMD (measured on the 256 x 256 tile: 5.6 us per program with the tests, 6 % of a 4096-cubed product).
+// STREAM: full 16-byte stores carry the non-temporal hint (the output is not read again by the launch and should not push
+// the operands out of L2: 18 % on a batch of 32 2048 x 2048 x 512 products); not for the range-checked kernels, whose rows
+// need not be 16-byte aligned (there the hint costs more than it saves: partial lines).
+template <int BM, int BN, int OUT, bool CHECK, int RP, bool AFFINE, bool STREAM>
 __device__ __forceinline__ void store_tile16_rows(char *smem, int wave, char *C, int64_t scm, const float4v (&acc)[BM / 32][BN / 32],
-                                                  int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N, bool affine, const char *D,
+                                                  int64_t row_w, int64_t col_w, int lane, int64_t M, int64_t N, const char *D,
                                                   int64_t sdm, float alpha, float beta, int act)
 {
     constexpr int TM = BM / 32, WM = BM / 2, WN = BN / 2;
@@ -200,13 +208,18 @@ __device__ __forceinline__ void store_tile16_rows(char *smem, int wave, char *C,
     constexpr int TNP = PW / 16;                          // blocks per pass
     const int l16 = lane & 15, g = lane >> 4;
     const ActParams ap = act_params(act);
-    char *reg = smem + wave * (WM * RB);
+    constexpr int TMP = TM / RP, WMP = WM / RP;           // blocks and rows per row pass
+    static_assert(TM % RP == 0 && WMP % RPI == 0, "row passes");
+    char *reg = smem + wave * (WMP * RB);
+#pragma unroll
+    for (int rp = 0; rp < RP; ++rp)
 #pragma unroll
     for (int pass = 0; pass < PASSES; ++pass) {
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
-            const int r = tm * 16 + l16;
-            const int64_t row = row_w + r;
+        for (int tmp = 0; tmp < TMP; ++tmp) {
+            const int tm = rp * TMP + tmp;
+            const int r = tmp * 16 + l16;
+            const int64_t row = row_w + rp * WMP + r;
             const int sw = (r >> RSH) & (CPR - 1);
             char *prow = reg + r * RB;
 #pragma unroll
@@ -219,7 +232,7 @@ __device__ __forceinline__ void store_tile16_rows(char *smem, int wave, char *C,
                 float o[4];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) o[v] = blk[v];
-                if (affine) {                                         // wavefront-uniform
+                if constexpr (AFFINE) {
                     float d[4] = {0.f, 0.f, 0.f, 0.f};
                     const int64_t nv = CHECK ? N - (col_w + tn * 16 + 4 * g) : 4;      // valid columns from the lane's first
                     if (D && CHECK && (row >= M || nv < 4)) {
@@ -271,13 +284,16 @@ __device__ __forceinline__ void store_tile16_rows(char *smem, int wave, char *C,
         }
         // ---- read phase (same wavefront: LDS operations complete in order)
 #pragma unroll
-        for (int it = 0; it < WM / RPI; ++it) {
+        for (int it = 0; it < WMP / RPI; ++it) {
             const int r = it * RPI + lane / CPR, c = lane % CPR;
             const u32x4 v = lds_read16(reg, (uint32_t)(r * RB + ((c ^ ((r >> RSH) & (CPR - 1))) << 4)));
-            const int64_t row = row_w + r, col = col_w + pass * PW + c * EPC;
+            const int64_t row = row_w + rp * WMP + r, col = col_w + pass * PW + c * EPC;
             char *p = C + (row * scm + col) * ES;
             if (!CHECK || (row < M && col + EPC <= N)) {
-                __builtin_memcpy(p, &v, 16);
+                // (streamed where rows are 16-byte aligned: the output is not read again by this launch and should not
+                // push the operands out of L2)
+                if constexpr (STREAM) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+                else __builtin_memcpy(p, &v, 16);
             } else if (row < M && col < N) {
                 const int nv = (int)(N - col);
 #pragma unroll
@@ -292,7 +308,7 @@ __device__ __forceinline__ void store_tile16_rows(char *smem, int wave, char *C,
     }
 }
 
-template <int BM, int BN, bool EDGE = false>
+template <int BM, int BN, bool EDGE = false, int RP = 1>
 __device__ __forceinline__ void store_tile16(const FastArgs &g, char *smem, int wave, int64_t bi, const float4v (&acc)[BM / 32][BN / 32],
                                              int64_t row_w, int64_t col_w, int lane, bool ragged = false)
 {
@@ -300,7 +316,12 @@ __device__ __forceinline__ void store_tile16(const FastArgs &g, char *smem, int 
     char *C = reinterpret_cast<char *>(g.C) + bi * g.sc_batch * esz;
     const char *D = g.D ? reinterpret_cast<const char *>(g.D) + bi * g.sd_batch * esz : nullptr;
     const bool affine = D != nullptr || g.alpha != 1.f || g.act != 0;
-#define NT_ROWS16(OUT, CHECK) store_tile16_rows<BM, BN, OUT, CHECK>(smem, wave, C, g.scm, acc, row_w, col_w, lane, g.M, g.N, affine, D, g.sdm, g.alpha, g.beta, g.act)
+    // (the plain product's path is straight-line code: with one wavefront per SIMD nothing hides an instruction fetch that
+    // a branch per accumulator block would cost)
+#define NT_ROWS16(OUT, CHECK) do { \
+        if (affine) store_tile16_rows<BM, BN, OUT, CHECK, RP, true, !EDGE>(smem, wave, C, g.scm, acc, row_w, col_w, lane, g.M, g.N, D, g.sdm, g.alpha, g.beta, g.act); \
+        else store_tile16_rows<BM, BN, OUT, CHECK, RP, false, !EDGE>(smem, wave, C, g.scm, acc, row_w, col_w, lane, g.M, g.N, D, g.sdm, g.alpha, g.beta, g.act); \
+    } while (0)
     if constexpr (EDGE) {
         if (ragged) {
             if (g.out_dtype == NT_F32) NT_ROWS16(NT_F32, true);
@@ -719,6 +740,166 @@ __global__ __launch_bounds__(kThreads, residency_of(BM, BN)) void gemm_direct16u
                                EDGE && (g.M - row0 < BM || g.N - col0 < BN));
 }
 
+// ---- the unrolled kernel as a persistent one: one workgroup per compute unit walks programs w, w + grid, w + 2 grid, ...
+// (full tiles of aligned operands, a whole number of 128-k steps).  The slices of consecutive programs form one stream: the
+// last pass of a program, which has nothing of its own left to request, requests the first four slices of the next program,
+// so that program's prologue (and the latency of its first loads) is hidden behind this one's last trips and epilogue.  The
+// epilogue therefore must leave the ring alone: it stages through the 32 KB of LDS behind the ring, a quarter of the
+// wavefront's rows at a time.  Loads and stores share one counter of outstanding operations, and a count cannot tell which
+// are which: everything requested is awaited before the epilogue's stores go out, and the first three trips of the next
+// program (whose slices are then resident) wait for nothing, so the stores drain while the matrix pipe works.
+template <int BM, int BN, bool BF16, int ALAY, int BLAY>
+__global__ __launch_bounds__(kThreads, 1) void gemm_direct16p_kernel(const FastArgs g)
+{
+    constexpr int TM = BM / 32, TN = BN / 32;
+    constexpr int kRing = 4;
+    static_assert(ring_of(BM, BN) == kRing, "ring of four");
+    using TileA = DirectTile16<BM, ALAY>;
+    using TileB = DirectTile16<BN, BLAY>;
+    constexpr uint32_t A_BYTES = TileA::BYTES, B_BYTES = TileB::BYTES, B_BASE = kRing * A_BYTES;
+    constexpr uint32_t STAGE = kRing * (A_BYTES + B_BYTES);         // the epilogue's staging region, behind the ring
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = wave >> 1, wave_n = wave & 1;
+    const int64_t per = g.mt * g.nt, nb = g.nprog / per;
+    const int64_t a_step = (ALAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.lda) * 2;
+    const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.ldb) * 2;
+    const int64_t n_slices = g.kt * (kBK / kSliceK);       // a multiple of 4, at least 4 (checked by the host)
+
+    // program v of the launch: batch entry, tile row and column, the operands' tile origins
+    struct Where { int64_t bi, row0, col0; const char *pa, *pb; };
+    auto locate = [&](int64_t v) {
+        int64_t bb, pid;
+        program_of_workgroup_batched(v, nb, g.mt, g.nt, &bb, &pid);
+        Where w;
+        w.bi = __builtin_amdgcn_readfirstlane((int)bb);
+        w.row0 = (int64_t)__builtin_amdgcn_readfirstlane((int)(pid / g.nt)) * BM;
+        w.col0 = (int64_t)__builtin_amdgcn_readfirstlane((int)(pid % g.nt)) * BN;
+        w.pa = reinterpret_cast<const char *>(g.A + w.bi * g.sa_batch + (ALAY == KCONTIG ? w.row0 * g.lda : w.row0));
+        w.pb = reinterpret_cast<const char *>(g.B + w.bi * g.sb_batch + (BLAY == KCONTIG ? w.col0 * g.ldb : w.col0));
+        return w;
+    };
+
+    TileA ta;
+    TileB tb;
+    ta.init(wave, lane, g.lda, wave_m * (BM / 2), 0);
+    tb.init(wave, lane, g.ldb, wave_n * (BN / 2), B_BASE);
+
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    constexpr int NRA = TM * TileA::RPF, NRB = TN * TileB::RPF, NR = NRA + NRB;   // LDS reads per slice
+    constexpr int NM = TM * TN, ND = TileA::PER + TileB::PER;
+    static_assert(2 * NR <= NM * 3 / 2 && 8 * ND <= NM, "the trip's schedule: a read every other matrix instruction, a load every eighth");
+    uint32_t tgt[kRing][ND];
+#pragma unroll
+    for (int r = 0; r < kRing; ++r)
+#pragma unroll
+        for (int d = 0; d < ND; ++d)
+            tgt[r][d] = d < TileA::PER ? lds0 + r * A_BYTES + (uint32_t)((wave * TileA::PER + d) * 1024)
+                                       : lds0 + B_BASE + r * B_BYTES + (uint32_t)((wave * TileB::PER + d - TileA::PER) * 1024);
+
+    float4v acc[TM][TN];
+    u32x4 fa[2][TM], fb[2][TN];
+    auto lds_read = [&](int r, int set, uint32_t ring) {
+        if (r < TileA::RPF) ta.read(fa[set], smem, r, ring * A_BYTES);
+        else if (r < TileA::RPF + NRB) tb.read(fb[set], smem, r - TileA::RPF, ring * B_BYTES);
+        else ta.read(fa[set], smem, r - NRB, ring * A_BYTES);
+    };
+    const char *pa, *pb;                                     // the slice that is requested next
+    auto dma_aim = [&](int d, int ring) { asm volatile("s_mov_b32 m0, %0" : : "s"(tgt[ring][d]) : "memory"); };
+    auto dma_go = [&](int d) {
+        if (d < TileA::PER) asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(ta.voff[d]), "s"(pa) : "memory");
+        else asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(tb.voff[d - TileA::PER]), "s"(pb) : "memory");
+    };
+    auto trip = [&](auto ring_c, auto set_c, int64_t a_adv, int64_t b_adv) {
+        constexpr int RING = decltype(ring_c)::value, SET = decltype(set_c)::value;
+        constexpr int NXT = (RING + 1) % kRing;
+#pragma unroll
+        for (int idx = 0; idx < NM; ++idx) {
+            const int tm = idx / TN, tn = idx % TN;
+            mfma16<BF16>(acc[tm][tn], fb[SET][tn], fa[SET][tm]);      // transposed block (see store_tile16_rows)
+            if (idx % 2 == 0 && idx / 2 < NR) lds_read(idx / 2, SET ^ 1, NXT);
+            if (idx % 8 == 1 && idx / 8 < ND) dma_aim(idx / 8, RING);
+            if (idx % 8 == 3 && idx / 8 < ND) {
+                dma_go(idx / 8);
+                if (idx / 8 == TileA::PER - 1) { pa += a_adv; asm volatile("" : "+s"(pa)); }
+                if (idx / 8 == ND - 1) { pb += b_adv; asm volatile("" : "+s"(pb)); }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    using std::integral_constant;
+
+    int64_t v = blockIdx.x;
+    Where cur = locate(v);
+    // the first program's slices 0 .. 3
+    pa = cur.pa;
+    pb = cur.pb;
+#pragma unroll
+    for (int s = 0; s < kRing; ++s) {
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+            dma_aim(d, s);
+            asm volatile("s_nop 0");
+            dma_go(d);
+        }
+        pa += a_step;
+        pb += b_step;
+    }
+    asm volatile("" : "+s"(pa), "+s"(pb));
+    bool resident = false;                                   // all four slices at the head of the ring have landed (every program but the first)
+
+    for (;;) {
+        const int64_t vn = v + gridDim.x;
+        const bool more = vn < g.nprog;                      // (uniform)
+        Where nxt = cur;
+        if (more) nxt = locate(vn);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+#pragma unroll
+                for (int x = 0; x < 4; ++x) acc[a][b][x] = 0.f;
+        if (!resident) NT_WAIT_VMCNT((kRing - 1) * ND);
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < NR; ++r) lds_read(r, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // this program's slices 4 .. continue at pa / pb; its last pass requests the next program's slices 0 .. 3 (or, if
+        // there is none, this program's last slice again, into ring positions that nobody reads any more)
+        const char *pa_end = cur.pa + (n_slices - 1) * a_step, *pb_end = cur.pb + (n_slices - 1) * b_step;
+        int64_t a_adv = a_step, b_adv = b_step;
+        for (int64_t sl = 0; sl < n_slices; sl += kRing) {
+            if (sl + kRing >= n_slices) {                    // (uniform)
+                if (more) { pa = nxt.pa; pb = nxt.pb; }
+                else { pa = pa_end; pb = pb_end; a_adv = 0; b_adv = 0; }
+            }
+            asm volatile("" : "+s"(pa), "+s"(pb), "+s"(a_adv), "+s"(b_adv));
+            const bool wait = !(resident && sl == 0);        // (uniform) slices 1 .. 3 of a program whose head is resident need no wait
+            if (wait) NT_WAIT_VMCNT(2 * ND);
+            __syncthreads(); trip(integral_constant<int, 0>{}, integral_constant<int, 0>{}, a_adv, b_adv);
+            if (wait) NT_WAIT_VMCNT(2 * ND);
+            __syncthreads(); trip(integral_constant<int, 1>{}, integral_constant<int, 1>{}, a_adv, b_adv);
+            if (wait) NT_WAIT_VMCNT(2 * ND);
+            __syncthreads(); trip(integral_constant<int, 2>{}, integral_constant<int, 0>{}, a_adv, b_adv);
+            NT_WAIT_VMCNT(2 * ND);
+            __syncthreads(); trip(integral_constant<int, 3>{}, integral_constant<int, 1>{}, a_adv, b_adv);
+            asm volatile("s_nop 7" ::: "memory");
+        }
+        // everything requested has to have landed before stores join the count of outstanding operations
+        NT_WAIT_VMCNT(0);
+        asm volatile("s_nop 15" ::: "memory");
+        store_tile16<BM, BN, false, 4>(g, smem + STAGE, wave, cur.bi, acc, cur.row0 + wave_m * (BM / 2), cur.col0 + wave_n * (BN / 2), lane);
+        if (!more) break;
+        v = vn;
+        cur = nxt;
+        resident = true;
+        // (the next program's slices 0 .. 3 were requested by the last pass: the request pointers stand at its slice 4)
+    }
+}
+
 template <int BM, int BN, bool BF16, int ALAY, int BLAY, bool EDGE = false>
 static nt_status launch_direct16_inst(const FastArgs &a, int64_t nwg, hipStream_t s)
 {
@@ -734,6 +915,25 @@ static nt_status launch_direct16_inst(const FastArgs &a, int64_t nwg, hipStream_
     }
     // (the 256 x 256 tile -- one workgroup per compute unit, every issue turn counts -- with a reduction of whole 128-k steps:
     // the kernel with the unrolled ring)
+    if constexpr (BM == 256 && BN == 256 && !EDGE) {
+        // several programs per compute unit: the persistent kernel (one workgroup per unit, 160 KB of LDS)
+        // (a grid that is a multiple of 8 keeps every program of a workgroup on the workgroup's own XCD)
+        const int64_t units = compute_units() / 8 * 8;
+        if (a.kt % 2 == 0 && a.kt >= 2 && units > 0 && nwg > units) {
+            constexpr size_t smem_p = smem + 32768;
+            auto kp = gemm_direct16p_kernel<BM, BN, BF16, ALAY, BLAY>;
+            static DeviceOnce configured_p;
+            if (!configured_p.done()) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kp), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_p);
+                if (e != hipSuccess) return fail(NT_ERR_DEVICE, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
+                configured_p.set();
+            }
+            FastArgs ap = a;
+            ap.nprog = nwg;
+            hipLaunchKernelGGL(kp, dim3((unsigned)units), dim3(kThreads), smem_p, s, ap);
+            return check_launch("gemm_direct16p_kernel");
+        }
+    }
     if constexpr (BM == 256 && BN == 256) {
         // (range-checked flavour: any number of slices is rounded up to whole passes of four; worth it from three passes on)
         if (EDGE ? a.K > 8 * kSliceK : (a.kt % 2 == 0 && a.kt >= 2)) {

@@ -45,6 +45,8 @@ struct FastArgs {
     // direct kernel, range-checked flavour: bit 0 / 1 = the word of a load that holds A's / B's very last element can end
     // past the operand (odd pitch or extent) and is dropped by the range check; the kernel then puts that element in place itself
     int32_t patch;
+    // persistent kernel: the launch's number of programs (each workgroup walks programs w, w + grid, w + 2 grid, ...)
+    int64_t nprog;
     // loader trace (nt_trace_loader_tile; nullptr otherwise): one workgroup runs program trace_program's loads of 32-k slice
     // trace_slice for real and writes what they left in LDS for operand trace_operand (0 = A, 1 = B), element by element
     uint16_t *trace_out;

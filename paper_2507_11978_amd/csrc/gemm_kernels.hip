@@ -44,7 +44,9 @@ static const TileEntry kTiles[] = {{64, 64, 32}, {128, 128, 64}, {256, 128, 64},
 nt_tile_cfg pick_gemm_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
 {
     struct Cand { int bm, bn; double fixed, step; int resident; };
-    const Cand cands[] = {{256, 256, 14.0, 1.755, 1}, {128, 256, 8.0, 0.95, 2}, {256, 128, 8.0, 1.08, 2}, {128, 128, 7.0, 0.62, 2}};
+    // (fits to 8192 x 8192 x K, 4096 x 4096 x K and 32 x 2048 x 2048 x K for K = 256 .. 8192 on a chip with every unit busy;
+    // the 256 x 256 figures are those of the persistent kernel)
+    const Cand cands[] = {{256, 256, 8.5, 1.42, 1}, {128, 256, 7.0, 0.82, 2}, {256, 128, 6.5, 0.915, 2}, {128, 128, 4.5, 0.51, 2}};
     const double kt = (double)((K + 63) / 64);
     nt_tile_cfg best{128, 128, 64};
     double best_cost = 0;
