@@ -127,11 +127,13 @@ __device__ __forceinline__ int lds_chunk_pos(int row, int chunk)
 // everything derived from them is wavefront-uniform for the compiler as well.
 __device__ __forceinline__ void locate_program(int64_t mt, int64_t nt, int64_t *b, int64_t *i, int64_t *j)
 {
-    int64_t bb, pid;
-    program_of_workgroup_batched(blockIdx.x, (int64_t)gridDim.x / (mt * nt), mt, nt, &bb, &pid);
+    const uint32_t m32 = (uint32_t)mt, n32 = (uint32_t)nt;
+    uint32_t bb, pid;
+    program_of_workgroup_batched_t<uint32_t>(blockIdx.x, gridDim.x / (m32 * n32), m32, n32, &bb, &pid);
+    const uint32_t ii = pid / n32;
     *b = __builtin_amdgcn_readfirstlane((int)bb);
-    *i = __builtin_amdgcn_readfirstlane((int)(pid / nt));
-    *j = __builtin_amdgcn_readfirstlane((int)(pid % nt));
+    *i = __builtin_amdgcn_readfirstlane((int)ii);
+    *j = __builtin_amdgcn_readfirstlane((int)(pid - ii * n32));
 }
 
 // The LDS -> MFMA core for one staged k tile: acc[tm][tn] += A_tile . B_tile.

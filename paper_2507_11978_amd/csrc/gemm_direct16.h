@@ -763,7 +763,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_direct16p_kernel(const FastA
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = wave >> 1, wave_n = wave & 1;
-    const int64_t per = g.mt * g.nt, nb = g.nprog / per;
+    const uint32_t mt32 = (uint32_t)g.mt, nt32 = (uint32_t)g.nt, nb32 = (uint32_t)g.nprog / (mt32 * nt32);
     const int64_t a_step = (ALAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.lda) * 2;
     const int64_t b_step = (BLAY == KCONTIG ? (int64_t)kSliceK : (int64_t)kSliceK * g.ldb) * 2;
     const int64_t n_slices = g.kt * (kBK / kSliceK);       // a multiple of 4, at least 4 (checked by the host)
@@ -771,12 +771,13 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_direct16p_kernel(const FastA
     // program v of the launch: batch entry, tile row and column, the operands' tile origins
     struct Where { int64_t bi, row0, col0; const char *pa, *pb; };
     auto locate = [&](int64_t v) {
-        int64_t bb, pid;
-        program_of_workgroup_batched(v, nb, g.mt, g.nt, &bb, &pid);
+        uint32_t bb, pid;
+        program_of_workgroup_batched_t<uint32_t>((uint32_t)v, nb32, mt32, nt32, &bb, &pid);
+        const uint32_t ti = pid / nt32;
         Where w;
         w.bi = __builtin_amdgcn_readfirstlane((int)bb);
-        w.row0 = (int64_t)__builtin_amdgcn_readfirstlane((int)(pid / g.nt)) * BM;
-        w.col0 = (int64_t)__builtin_amdgcn_readfirstlane((int)(pid % g.nt)) * BN;
+        w.row0 = (int64_t)__builtin_amdgcn_readfirstlane((int)ti) * BM;
+        w.col0 = (int64_t)__builtin_amdgcn_readfirstlane((int)(pid - ti * nt32)) * BN;
         w.pa = reinterpret_cast<const char *>(g.A + w.bi * g.sa_batch + (ALAY == KCONTIG ? w.row0 * g.lda : w.row0));
         w.pb = reinterpret_cast<const char *>(g.B + w.bi * g.sb_batch + (BLAY == KCONTIG ? w.col0 * g.ldb : w.col0));
         return w;

@@ -88,46 +88,58 @@ nt_status launch_sdpa_desc(const void *q, const nt_tensor_desc *dq, const void *
 // Position seq of the tile sequence -> program id: the grid is walked in bands of up to 8 tile
 // rows, column by column inside a band, so that programs that run at the same time share operand
 // rows / columns.
-NT_HD int64_t program_of_sequence(int64_t seq, int64_t mt, int64_t nt)
+// (I: int64_t on the host; uint32_t in the kernels, whose launchers have checked that every count is below 2^31 -- a
+// 64-bit division costs a wavefront some hundred instructions, and a program's start has eight of them)
+template <typename I>
+NT_HD I program_of_sequence_t(I seq, I mt, I nt)
 {
-    const int64_t band = 8;
-    const int64_t per_band = band * nt;
-    const int64_t b = seq / per_band;
-    const int64_t first = b * band;
-    const int64_t rows = mt - first < band ? mt - first : band;
-    const int64_t in = seq - b * per_band;
-    const int64_t i = first + in % rows;
-    const int64_t j = in / rows;
+    const I band = 8;
+    const I per_band = band * nt;
+    const I b = seq / per_band;
+    const I first = b * band;
+    const I rows = mt - first < band ? mt - first : band;
+    const I in = seq - b * per_band;
+    const I j = in / rows;
+    const I i = first + (in - j * rows);
     return i * nt + j;
 }
+NT_HD int64_t program_of_sequence(int64_t seq, int64_t mt, int64_t nt) { return program_of_sequence_t<int64_t>(seq, mt, nt); }
 
-NT_HD int64_t program_of_workgroup(int64_t w, int64_t mt, int64_t nt)
+template <typename I>
+NT_HD I program_of_workgroup_t(I w, I mt, I nt)
 {
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one contiguous share of
     // the tile sequence so that tiles resident on one L2 share operand rows / columns.
-    const int64_t G = mt * nt;
-    const int64_t nx = 8;
-    const int64_t q = G / nx, r = G % nx;          // first r XCDs get q+1 tiles
-    const int64_t x = w % nx, l = w / nx;
-    const int64_t seq = x < r ? x * (q + 1) + l : r * (q + 1) + (x - r) * q + l;
-    return program_of_sequence(seq, mt, nt);
+    const I G = mt * nt;
+    const I nx = 8;
+    const I q = G / nx, r = G % nx;          // first r XCDs get q+1 tiles
+    const I x = w % nx, l = w / nx;
+    const I seq = x < r ? x * (q + 1) + l : r * (q + 1) + (x - r) * q + l;
+    return program_of_sequence_t<I>(seq, mt, nt);
 }
+NT_HD int64_t program_of_workgroup(int64_t w, int64_t mt, int64_t nt) { return program_of_workgroup_t<int64_t>(w, mt, nt); }
 
 // Batched grids (nb problems of mt x nt programs): every complete group of 8 problems is dealt out
 // one whole problem per XCD (its operands then pass through one L2 only); the problems left over are
 // split across the XCDs like a single problem.
+template <typename I>
+NT_HD void program_of_workgroup_batched_t(I w, I nb, I mt, I nt, I *b, I *pid)
+{
+    const I per = mt * nt;
+    if (w < (nb / 8) * 8 * per) {
+        const I l = w / 8;
+        const I grp = l / per;
+        *b = grp * 8 + w % 8;
+        *pid = program_of_sequence_t<I>(l - grp * per, mt, nt);
+    } else {
+        const I bb = w / per;
+        *b = bb;
+        *pid = program_of_workgroup_t<I>(w - bb * per, mt, nt);
+    }
+}
 NT_HD void program_of_workgroup_batched(int64_t w, int64_t nb, int64_t mt, int64_t nt, int64_t *b, int64_t *pid)
 {
-    const int64_t per = mt * nt;
-    if (w < (nb / 8) * 8 * per) {
-        const int64_t l = w / 8;
-        *b = (l / per) * 8 + w % 8;
-        *pid = program_of_sequence(l % per, mt, nt);
-    } else {
-        const int64_t bb = w / per;
-        *b = bb;
-        *pid = program_of_workgroup(w - bb * per, mt, nt);
-    }
+    program_of_workgroup_batched_t<int64_t>(w, nb, mt, nt, b, pid);
 }
 
 }  // namespace nt
