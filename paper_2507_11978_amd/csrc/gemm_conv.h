@@ -30,6 +30,9 @@ struct ConvArgs {
     int32_t PQ, Q, H, W, HW, CHW, RS, S, R, ph, pw;
     uint32_t inv_rs, inv_s;        // reciprocals of R*S and S (see udiv_small)
     int64_t mt, nt, kt;
+    // the kernel that walks the reduction tap by tap: the first mt_a of the mt tiles of positions are of its first height, the
+    // others of its second (32 positions lower)
+    int32_t mt_a;
     int out_dtype;
     // k split: the grid holds `ksplit` copies of the mt x nt programs; copy i multiplies k tiles [i * kt_per, (i + 1) * kt_per)
     // and writes its partial tile at Y + i * slice elements (Y then being an fp32 workspace of ksplit dense [n][f][p][q] slices

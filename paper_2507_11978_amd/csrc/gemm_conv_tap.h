@@ -129,11 +129,10 @@ __device__ __forceinline__ void conv_store_rows16(const ConvArgs &g, char *smem,
     }
 }
 
-// TM: the program's tile is 32 TM positions high (224 or 256; the LDS slots are laid out for 256 either way).  The host picks
-// the height that fills the chip's rounds best: 392 tiles of 256 positions are 1.53 rounds of 256 programs and cost two,
-// 448 tiles of 224 cost two rounds of 7/8 the length.
-template <bool BF16, int TM, bool TRACE = false>
-__global__ __launch_bounds__(kThreads, 1) void gemm_conv_tap_kernel(const ConvArgs g)
+// One program: TM: its tile is 32 TM positions high (192, 224 or 256; the LDS slots are laid out for 256 either way), starts
+// at position row_base + ti * 32 TM and at filter 256 tj; bi: which part of the k range (k split).
+template <bool BF16, int TM, bool TRACE>
+__device__ __forceinline__ void conv_tap_program(const ConvArgs &g, char *smem, int64_t bi, int64_t ti, int64_t tj, int64_t row_base)
 {
     constexpr int BM = 32 * TM, BN = 256;
     constexpr int TN = BN / 32;
@@ -145,16 +144,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_conv_tap_kernel(const ConvAr
     constexpr uint32_t A_BYTES = SLOT_M * kSliceK * 2, B_BYTES = TileB::BYTES, B_BASE = kRing * A_BYTES;
     constexpr uint32_t kOutside = 0x80000000u;
     static_assert(TileB::PER == 4 && TileB::RPF == 1, "schedule of the trip");
-    extern __shared__ __attribute__((aligned(1024))) char smem[];
-
-    int64_t bi, ti, tj;                                  // bi: which part of the k range (k split)
-    if constexpr (TRACE) { bi = 0; ti = g.trace_program / g.nt; tj = g.trace_program % g.nt; }
-    else locate_program(g.mt, g.nt, &bi, &ti, &tj);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = wave >> 1, wave_n = wave & 1;
     const int hi = lane >> 5;
-    const int64_t row0 = ti * BM, col0 = tj * BN;
+    const int64_t row0 = row_base + ti * BM, col0 = tj * BN;
     const int64_t kt0 = bi * g.kt_per;
     const int64_t kt_n = g.kt - kt0 < g.kt_per ? g.kt - kt0 : g.kt_per;
     const int32_t k_first = (int32_t)(kt0 * kBK);
@@ -299,8 +293,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_conv_tap_kernel(const ConvAr
     // The trip's schedule: PRE matrix instructions before the barrier; after it an LDS read behind every other one; the
     // pieces of the request walk's step behind the odd ones of the first HOLD; the halves of load d behind the 2nd and 4th
     // of the d-th group of STEP from then on; the pieces of the settle walk's step behind the 1st of the first groups.
-    constexpr int PRE = 8, HOLD = 11, STEP = (NM - PRE - HOLD) / ND;
-    static_assert(2 * NR <= NM - PRE && STEP >= 4, "the trip's schedule");
+    // (the lowest tile has 48 matrix instructions per trip: two fewer before the barrier and one fewer ahead of the loads leave
+    // the 8 loads their 4 each)
+    constexpr int PRE = TM >= 7 ? 8 : 6, HOLD = TM >= 7 ? 11 : 10, STEP = (NM - PRE - HOLD) / ND;
+    static_assert(2 * NR <= NM - PRE && STEP >= 4 && HOLD >= 10, "the trip's schedule");
     uint32_t tgt[kRing][ND];                                   // LDS targets of this wavefront's loads, per ring position: scalars
 #pragma unroll
     for (int r = 0; r < kRing; ++r)
@@ -484,11 +480,43 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_conv_tap_kernel(const ConvAr
     else conv_store_rows16<BM, NT_BF16>(g, smem, wave, acc, bi, row_w, col_w, lane);
 }
 
-template <bool BF16, int TM, bool TRACE = false>
+// The grid: g.mt_a tiles of 32 TMA positions, then g.mt - g.mt_a tiles of 32 TMB positions, each kind times g.nt filter tiles
+// times g.ksplit parts of the k range.  Two heights because whole rounds of programs (one per compute unit) cost their
+// length: 100352 positions are 12.25 blocks of 32 per unit, which 448 tiles of 224 positions serve in two rounds of 7 blocks,
+// and 256 tiles of 224 followed by 224 tiles of 192 in a round of 7 and a round of 6.  The host picks the heights and
+// the counts (either count may be zero).
+template <bool BF16, int TMA, int TMB, bool TRACE = false>
+__global__ __launch_bounds__(kThreads, 1) void gemm_conv_tap_kernel(const ConvArgs g)
+{
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const uint32_t nt32 = (uint32_t)g.nt, mta = (uint32_t)g.mt_a, mtb = (uint32_t)g.mt - mta;
+    const uint32_t ks = (uint32_t)(g.ksplit > 1 ? g.ksplit : 1);
+    const uint32_t n_a = ks * mta * nt32;
+    const int64_t base_b = (int64_t)mta * (32 * TMA);
+    uint32_t w = TRACE ? (uint32_t)g.trace_program : blockIdx.x;
+    // (the trace numbers programs tile row by tile row over both kinds, one k part)
+    const bool first = TRACE ? w < mta * nt32 : w < n_a;                       // (uniform)
+    uint32_t bb = 0, pid;
+    if (first) {
+        if constexpr (TRACE) pid = w;
+        else program_of_workgroup_batched_t<uint32_t>(w, ks, mta, nt32, &bb, &pid);
+    } else {
+        if constexpr (TRACE) pid = w - mta * nt32;
+        else program_of_workgroup_batched_t<uint32_t>(w - n_a, ks, mtb, nt32, &bb, &pid);
+    }
+    const uint32_t ti32 = pid / nt32;
+    const int64_t bi = __builtin_amdgcn_readfirstlane((int)bb);
+    const int64_t ti = __builtin_amdgcn_readfirstlane((int)ti32);
+    const int64_t tj = __builtin_amdgcn_readfirstlane((int)(pid - ti32 * nt32));
+    if (first) conv_tap_program<BF16, TMA, TRACE>(g, smem, bi, ti, tj, 0);
+    else conv_tap_program<BF16, TMB, TRACE>(g, smem, bi, ti, tj, base_b);
+}
+
+template <bool BF16, int TMA, int TMB, bool TRACE = false>
 static nt_status launch_conv_tap_inst(const ConvArgs &a, int64_t nwg, hipStream_t s)
 {
     constexpr size_t smem = (size_t)4 * (256 + 256) * kSliceK * sizeof(uint16_t);
-    auto kern = gemm_conv_tap_kernel<BF16, TM, TRACE>;
+    auto kern = gemm_conv_tap_kernel<BF16, TMA, TMB, TRACE>;
     static DeviceOnce configured;
     if (!configured.done()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -499,8 +527,8 @@ static nt_status launch_conv_tap_inst(const ConvArgs &a, int64_t nwg, hipStream_
     return check_launch("gemm_conv_tap_kernel");
 }
 
-// a.Wt: the filter in tap-major order (see launch_conv_repack_filter), a.ldb its row pitch; rows: positions per program
-// (224 or 256), a.mt the number of tiles of that height; nwg = ksplit * mt * nt
+// a.Wt: the filter in tap-major order (see launch_conv_repack_filter), a.ldb its row pitch; rows: positions per program of
+// the first a.mt_a tiles (256 or 224), the other a.mt - a.mt_a tiles being 32 positions lower; nwg = ksplit * mt * nt
 nt_status launch_conv_tap(const ConvArgs &a, int rows, bool bf16, int64_t nwg, hipStream_t s);
 nt_status launch_conv_tap_trace(const ConvArgs &a, int rows, hipStream_t s);
 // filter [F][C][R * S] (row pitch ldb) -> out [F][R * S][C] (row pitch C R S)

@@ -21,15 +21,15 @@ __global__ __launch_bounds__(256) void conv_repack_filter_kernel(const uint16_t 
 
 nt_status launch_conv_tap(const ConvArgs &a, int rows, bool bf16, int64_t nwg, hipStream_t s)
 {
-    if (rows == 256) return bf16 ? launch_conv_tap_inst<true, 8>(a, nwg, s) : launch_conv_tap_inst<false, 8>(a, nwg, s);
-    if (rows == 224) return bf16 ? launch_conv_tap_inst<true, 7>(a, nwg, s) : launch_conv_tap_inst<false, 7>(a, nwg, s);
+    if (rows == 256) return bf16 ? launch_conv_tap_inst<true, 8, 7>(a, nwg, s) : launch_conv_tap_inst<false, 8, 7>(a, nwg, s);
+    if (rows == 224) return bf16 ? launch_conv_tap_inst<true, 7, 6>(a, nwg, s) : launch_conv_tap_inst<false, 7, 6>(a, nwg, s);
     return fail(NT_ERR_UNSUPPORTED, "no convolution kernel for this tile height");
 }
 
 nt_status launch_conv_tap_trace(const ConvArgs &a, int rows, hipStream_t s)
 {
-    if (rows == 256) return launch_conv_tap_inst<false, 8, true>(a, 1, s);
-    if (rows == 224) return launch_conv_tap_inst<false, 7, true>(a, 1, s);
+    if (rows == 256) return launch_conv_tap_inst<false, 8, 7, true>(a, 1, s);
+    if (rows == 224) return launch_conv_tap_inst<false, 7, 6, true>(a, 1, s);
     return fail(NT_ERR_UNSUPPORTED, "no convolution kernel for this tile height");
 }
 

@@ -496,18 +496,37 @@ static nt_status route_conv_implicit(const GemmLaunch &g, const ConvArgs &c, int
             base.Wt = wt_tap;
             base.ldb = c.K;
         }
-        // tile height: whole rounds of 256 programs (one per compute unit) cost their length, 32 h positions plus a fixed part
-        auto cost = [&](int rows) {
-            const int64_t programs = (c.M + rows - 1) / rows * c.nt * ksplit;
-            return (double)((programs + 255) / 256) * (rows / 32 + 1.5);
+        // Tile heights: the kernel is built for a first height of h = 8 or 7 blocks of 32 positions and a second of h - 1.
+        // Whole rounds of programs (one per compute unit) cost their length, h blocks plus a fixed part; ra rounds of the
+        // first height, then as many of the second as the remaining positions need: the cheapest (h, ra).  With a k split
+        // (small grids) one height only.
+        const int64_t units = 256, blocks = ((int64_t)c.M + 31) / 32;
+        const int64_t per_round = units / (c.nt * ksplit) > 0 ? units / (c.nt * ksplit) : 1;      // tiles of positions per round
+        const double fixed = 1.5;
+        double best = 0;
+        int64_t best_a = 0, best_mt = 0;
+        auto consider = [&](int h, int64_t mt_a) {
+            const int64_t left = blocks - mt_a * h > 0 ? blocks - mt_a * h : 0;
+            const int64_t mt_b = (left + h - 2) / (h - 1);
+            const int64_t ra = (mt_a * c.nt * ksplit + units - 1) / units, rb = (mt_b * c.nt * ksplit + units - 1) / units;
+            const double cost = (double)ra * (h + fixed) + (double)rb * (h - 1 + fixed);
+            if (best == 0 || cost < best) { best = cost; tap_rows = 32 * h; best_a = mt_a; best_mt = mt_a + mt_b; }
         };
-        if (cost(224) < cost(256)) tap_rows = 224;
-        base.mt = (c.M + tap_rows - 1) / tap_rows;
+        for (int h = 8; h >= 7; --h) {
+            const int64_t all_a = (blocks + h - 1) / h;                        // tiles if every tile had the first height
+            consider(h, 0);
+            if (ksplit == 1)
+                for (int64_t mt_a = per_round; mt_a < all_a; mt_a += per_round) consider(h, mt_a);
+            consider(h, all_a);
+        }
+        base.mt_a = (int32_t)best_a;
+        base.mt = best_mt;
     }
     if (g.trace.out) {
         if (!direct) return fail(NT_ERR_UNSUPPORTED, "this convolution does not run on the kernels that stream their operands into LDS");
         const int bn = c.N <= 64 ? 64 : (c.N <= 128 ? 128 : t.bn);
-        const int64_t rows = g.trace.operand == 0 ? (tap ? tap_rows : 256) : bn;
+        // (positions per program: the traced program's own height)
+        const int64_t rows = g.trace.operand == 0 ? (tap ? (g.trace.program < base.mt_a * c.nt ? tap_rows : tap_rows - 32) : 256) : bn;
         if ((size_t)rows * 32 > g.trace.capacity) return fail(NT_ERR_BUFFER_TOO_SMALL, "trace buffer smaller than the slice");
         if (g.trace.program < 0 || g.trace.program >= base.mt * c.nt) return fail(NT_ERR_INVALID_ARG, "program_id outside the grid");
         if (g.trace.slice < 0 || g.trace.slice >= c.K / 32) return fail(NT_ERR_INVALID_ARG, "slice outside the reduction");

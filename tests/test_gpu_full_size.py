@@ -98,6 +98,32 @@ def test_full_size_conv():
     check_whole(to_f64(Y), ref, "f16")
 
 
+@pytest.mark.parametrize("dt,out", [("f16", "f16"), ("bf16", "f32")])
+@pytest.mark.parametrize("shape,pad", [
+    ((16, 32, 56, 56, 256, 3, 3), 1),      # 1568 blocks of 32 positions on 256 units: a round of 224-position tiles, then lower ones
+    ((9, 32, 60, 64, 512, 3, 3), 1),       # two tiles of filters per tile of positions
+    ((33, 32, 30, 40, 256, 1, 1), 0),      # 1 x 1 filter, the last tile of the second kind ragged
+    ((13, 64, 47, 53, 300, 3, 3), 1),      # rows of 53 positions (pitch 56), ragged filters
+])
+def test_conv_grids_of_more_programs_than_units(shape, pad, dt, out):
+    """Grids of more programs than compute units: the kernel for 256 filters runs tiles of two heights (the first rounds
+    32 positions higher than the last).  Every output against the oracle (reference as in test_full_size_conv)."""
+    N, Cc, H, W, K, R, S = shape
+    X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, dt, seed=27)
+    P, Q = H + 2 * pad - R + 1, W + 2 * pad - S + 1
+    Y = torch.full((N, K, P, Q), float("nan"), dtype=TORCH_DT[out], device="cuda")
+    nt.conv2d_implicit(to_gpu(X, dt), to_gpu(Wt, dt), Y, (1, 1), (pad, pad))
+    torch.cuda.synchronize()
+    assert nt.last_kernel_path() == nt.PATH_CONV_TAP
+    Wm = Wt.reshape(K, Cc * R * S).T
+    ref = np.empty((N, K, P, Q), dtype=np.float64)
+    for n in range(N):
+        ref[n] = onum.gemm(unfolded_input(X[n], R, S, pad), Wm, dt, nthreads=THREADS).T.reshape(K, P, Q)
+    direct = onum.conv2d(X[N - 1:N], Wt, dt, (1, 1), (pad, pad), nthreads=THREADS)[0]
+    assert np.array_equal(direct, ref[N - 1])
+    check_whole(to_f64(Y), ref, out)
+
+
 def test_full_size_conv_of_the_papers_kernel_list():
     """(4, 512, 14, 14) * (512, 512, 3, 3) in the launch configuration bench.py times (k split over 18 programs per
     output tile): every output against the oracle, and a second call gives the same bits."""
