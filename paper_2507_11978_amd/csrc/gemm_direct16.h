@@ -210,75 +210,115 @@ __device__ __forceinline__ void store_tile16_rows(char *smem, int wave, char *C,
     const ActParams ap = act_params(act);
     constexpr int TMP = TM / RP, WMP = WM / RP;           // blocks and rows per row pass
     static_assert(TM % RP == 0 && WMP % RPI == 0, "row passes");
+    constexpr int NBR = !AFFINE ? 1 : (TMP * TNP <= 8 ? TMP : (TNP >= 8 ? 1 : 8 / TNP));      // rows of blocks per batch of the write phase (8 blocks)
+    static_assert(NBR >= 1 && TMP % NBR == 0, "batches of the write phase");
     char *reg = smem + wave * (WMP * RB);
 #pragma unroll
     for (int rp = 0; rp < RP; ++rp)
 #pragma unroll
     for (int pass = 0; pass < PASSES; ++pass) {
+        // ---- write phase, NBR rows of blocks (8 blocks) at a time: their accumulators; with AFFINE the loads of D for all of
+        // them before the first is waited for, the combination, the activation; the conversions and LDS writes
 #pragma unroll
-        for (int tmp = 0; tmp < TMP; ++tmp) {
-            const int tm = rp * TMP + tmp;
-            const int r = tmp * 16 + l16;
-            const int64_t row = row_w + rp * WMP + r;
-            const int sw = (r >> RSH) & (CPR - 1);
-            char *prow = reg + r * RB;
+        for (int tb = 0; tb < TMP; tb += NBR) {
+            float o[NBR][TNP][4];
 #pragma unroll
-            for (int tnp = 0; tnp < TNP; ++tnp) {
-                const int tn = pass * TNP + tnp;
-                // (the block is pinned in its accumulator registers up to this point: without this the compiler moves all
-                // 256 accumulators to ordinary registers ahead of the three output formats' code and spills them)
-                float4v blk = acc[tm][tn];
-                asm volatile("" : "+a"(blk));
-                float o[4];
+            for (int i = 0; i < NBR; ++i)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) o[v] = blk[v];
-                if constexpr (AFFINE) {
-                    float d[4] = {0.f, 0.f, 0.f, 0.f};
-                    const int64_t nv = CHECK ? N - (col_w + tn * 16 + 4 * g) : 4;      // valid columns from the lane's first
-                    if (D && CHECK && (row >= M || nv < 4)) {
-                        if (row < M)
+                for (int tnp = 0; tnp < TNP; ++tnp) {
+                    // (the block is pinned in its accumulator registers up to this point: without this the compiler moves all
+                    // 256 accumulators to ordinary registers ahead of the three output formats' code and spills them)
+                    float4v blk = acc[rp * TMP + tb + i][pass * TNP + tnp];
+                    asm volatile("" : "+a"(blk));
 #pragma unroll
-                            for (int v = 0; v < 4; ++v)
-                                if (v < nv) d[v] = load_as_f32(D, row * sdm + col_w + tn * 16 + 4 * g + v, OUT);
-                    } else if (D) {
-                        const char *dp = D + (row * sdm + col_w + tn * 16 + 4 * g) * ES;
-                        if constexpr (OUT == NT_F32) {
-                            u32x4 w;
-                            __builtin_memcpy(&w, dp, 16);
+                    for (int v = 0; v < 4; ++v) o[i][tnp][v] = blk[v];
+                }
+            if constexpr (AFFINE) {
+                if (D) {                                                  // wavefront-uniform
+                    typedef uint32_t raw_t __attribute__((ext_vector_type(ES)));      // the lane's 4 elements of D as stored
+                    raw_t w[NBR][TNP];
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) { const uint32_t x = w[v]; d[v] = __builtin_bit_cast(float, x); }
-                        } else {
-                            u32x2 w;
-                            __builtin_memcpy(&w, dp, 8);
+                    for (int i = 0; i < NBR; ++i) {
+                        const int64_t row = row_w + rp * WMP + (tb + i) * 16 + l16;
 #pragma unroll
-                            for (int v = 0; v < 2; ++v) {
-                                const uint32_t x = w[v];
-                                if constexpr (OUT == NT_F16) {
-                                    d[2 * v] = (float)__builtin_bit_cast(_Float16, (uint16_t)(x & 0xffffu));
-                                    d[2 * v + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(x >> 16));
-                                } else {
-                                    d[2 * v] = __builtin_bit_cast(float, x << 16);
-                                    d[2 * v + 1] = __builtin_bit_cast(float, x & 0xffff0000u);
-                                }
+                        for (int tnp = 0; tnp < TNP; ++tnp) {
+                            const int64_t col = col_w + (pass * TNP + tnp) * 16 + 4 * g;
+                            const int64_t nv = CHECK ? N - col : 4;                   // valid columns from the lane's first
+                            if (CHECK && (row >= M || nv < 4)) {
+                                uint32_t e[4] = {0u, 0u, 0u, 0u};                      // element by element, as 32- or 16-bit patterns
+                                if (row < M)
+#pragma unroll
+                                    for (int v = 0; v < 4; ++v)
+                                        if (v < nv) {
+                                            if constexpr (ES == 4) e[v] = *reinterpret_cast<const uint32_t *>(D + (row * sdm + col + v) * 4);
+                                            else e[v] = *reinterpret_cast<const uint16_t *>(D + (row * sdm + col + v) * 2);
+                                        }
+                                if constexpr (ES == 4) w[i][tnp] = raw_t{e[0], e[1], e[2], e[3]};
+                                else w[i][tnp] = raw_t{e[0] | (e[1] << 16), e[2] | (e[3] << 16)};
+                            } else {
+                                __builtin_memcpy(&w[i][tnp], D + (row * sdm + col) * ES, 4 * ES);
                             }
                         }
                     }
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) o[v] = combine(o[v], d[v], alpha, beta);
-                    if (act) {                                        // wavefront-uniform
+                    for (int i = 0; i < NBR; ++i)
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) o[v] = activate(o[v], ap);
-                    }
-                }
-                if constexpr (OUT == NT_F32) {
-                    const int c = tnp * 4 + g;
-                    lds_write16(prow, (uint32_t)((c ^ sw) << 4), u32x4{__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
-                                                                        __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3])});
+                        for (int tnp = 0; tnp < TNP; ++tnp) {
+                            float d[4];
+                            if constexpr (OUT == NT_F32) {
+#pragma unroll
+                                for (int v = 0; v < 4; ++v) { const uint32_t x = w[i][tnp][v]; d[v] = __builtin_bit_cast(float, x); }
+                            } else {
+#pragma unroll
+                                for (int v = 0; v < 2; ++v) {
+                                    const uint32_t x = w[i][tnp][v];
+                                    if constexpr (OUT == NT_F16) {
+                                        d[2 * v] = (float)__builtin_bit_cast(_Float16, (uint16_t)(x & 0xffffu));
+                                        d[2 * v + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(x >> 16));
+                                    } else {
+                                        d[2 * v] = __builtin_bit_cast(float, x << 16);
+                                        d[2 * v + 1] = __builtin_bit_cast(float, x & 0xffff0000u);
+                                    }
+                                }
+                            }
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) o[i][tnp][v] = combine(o[i][tnp][v], d[v], alpha, beta);
+                        }
                 } else {
-                    const int c = tnp * 2 + (g >> 1);
-                    *reinterpret_cast<u32x2 *>(prow + (((c ^ sw) << 4) + 8 * (g & 1))) =
-                        u32x2{pack_pair<OUT>(__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1])),
-                              pack_pair<OUT>(__builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3]))};
+#pragma unroll
+                    for (int i = 0; i < NBR; ++i)
+#pragma unroll
+                        for (int tnp = 0; tnp < TNP; ++tnp)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) o[i][tnp][v] = combine(o[i][tnp][v], 0.f, alpha, beta);
+                }
+                if (act) {                                                // wavefront-uniform
+#pragma unroll
+                    for (int i = 0; i < NBR; ++i)
+#pragma unroll
+                        for (int tnp = 0; tnp < TNP; ++tnp)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) o[i][tnp][v] = activate(o[i][tnp][v], ap);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < NBR; ++i) {
+                const int r = (tb + i) * 16 + l16;
+                const int sw = (r >> RSH) & (CPR - 1);
+                char *prow = reg + r * RB;
+#pragma unroll
+                for (int tnp = 0; tnp < TNP; ++tnp) {
+                    const float *ov = o[i][tnp];
+                    if constexpr (OUT == NT_F32) {
+                        const int c = tnp * 4 + g;
+                        lds_write16(prow, (uint32_t)((c ^ sw) << 4), u32x4{__builtin_bit_cast(uint32_t, ov[0]), __builtin_bit_cast(uint32_t, ov[1]),
+                                                                            __builtin_bit_cast(uint32_t, ov[2]), __builtin_bit_cast(uint32_t, ov[3])});
+                    } else {
+                        const int c = tnp * 2 + (g >> 1);
+                        *reinterpret_cast<u32x2 *>(prow + (((c ^ sw) << 4) + 8 * (g & 1))) =
+                            u32x2{pack_pair<OUT>(__builtin_bit_cast(uint32_t, ov[0]), __builtin_bit_cast(uint32_t, ov[1])),
+                                  pack_pair<OUT>(__builtin_bit_cast(uint32_t, ov[2]), __builtin_bit_cast(uint32_t, ov[3]))};
+                    }
                 }
             }
         }
