@@ -583,6 +583,6 @@ nt_status nt_mfma_probe(const void *data, int64_t n_elems, nt_dtype dtype, int32
 
 const char *nt_last_error(void) { return nt::last_error().c_str(); }
 
-const char *nt_version(void) { return "nt-mi355x 0.3 (gfx950)"; }
+const char *nt_version(void) { return "nt-mi355x 0.4 (gfx950)"; }
 
 }  // extern "C"
