@@ -47,6 +47,8 @@ struct FastArgs {
     int32_t patch;
     // persistent kernel: the launch's number of programs (each workgroup walks programs w, w + grid, w + 2 grid, ...)
     int64_t nprog;
+    // ... and the start-up stagger: workgroup w starts ((w / 8) % 4) * stagger hundredths of a microsecond late (0: none)
+    int32_t stagger;
     // loader trace (nt_trace_loader_tile; nullptr otherwise): one workgroup runs program trace_program's loads of 32-k slice
     // trace_slice for real and writes what they left in LDS for operand trace_operand (0 = A, 1 = B), element by element
     uint16_t *trace_out;
