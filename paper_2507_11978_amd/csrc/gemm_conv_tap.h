@@ -339,7 +339,7 @@ __device__ __forceinline__ void conv_tap_program(const ConvArgs &g, char *smem, 
     // What the slice the settle walk stands at needs once this wavefront's part of it has landed at ring position RING.
     // Common: the padding elements of runs are overwritten with zero, under the four wavefront masks (every lane is active
     // here; the execution mask is put back before the statement ends).  Rare: runs that cross an end of x.
-    auto settle = [&](auto ring_c) {
+    auto settle_hazard = [&](auto ring_c) {
         constexpr uint32_t o = decltype(ring_c)::value * A_BYTES;
         if (hazard) {                                                                    // (uniform, first / last programs only)
             const int32_t lim = (int32_t)g.x_numel;
@@ -357,21 +357,23 @@ __device__ __forceinline__ void conv_tap_program(const ConvArgs &g, char *smem, 
             }
             __builtin_amdgcn_s_waitcnt(0xc07f);                                           // (those LDS writes before the ones below: lgkmcnt(0))
         }
-        const uint64_t f0 = mf0, f1 = mf1, l0 = ml0, l1 = ml1;
-        const uint32_t ca = clr, cl = clr_last;
-        asm volatile("s_mov_b64 exec, %[f0]\n\t"
-                     "ds_write_b16 %[a], %[z] offset:%[o0]\n\tds_write_b16 %[a], %[z] offset:%[o2]\n\t"
-                     "s_mov_b64 exec, %[f1]\n\t"
-                     "ds_write_b16 %[a], %[z] offset:%[o1]\n\tds_write_b16 %[a], %[z] offset:%[o3]\n\t"
-                     "s_mov_b64 exec, %[l0]\n\t"
-                     "ds_write_b16 %[b], %[z] offset:%[o0]\n\tds_write_b16 %[b], %[z] offset:%[o2]\n\t"
-                     "s_mov_b64 exec, %[l1]\n\t"
-                     "ds_write_b16 %[b], %[z] offset:%[o1]\n\tds_write_b16 %[b], %[z] offset:%[o3]\n\t"
-                     "s_mov_b64 exec, -1"
-                     :
-                     : [f0] "s"(f0), [f1] "s"(f1), [l0] "s"(l0), [l1] "s"(l1), [a] "v"(ca), [b] "v"(cl), [z] "v"(0u),
-                       [o0] "n"(o), [o1] "n"(o + 1024), [o2] "n"(o + 2048), [o3] "n"(o + 3072)
-                     : "memory");
+    };
+    // piece q = 0 .. 3 of the clears: the first elements of run 0, of run 1, the last elements of run 0, of run 1
+    auto settle_piece = [&](auto ring_c, int q) {
+        constexpr uint32_t o = decltype(ring_c)::value * A_BYTES;
+        const uint64_t m = q == 0 ? mf0 : q == 1 ? mf1 : q == 2 ? ml0 : ml1;
+        const uint32_t at = q < 2 ? clr : clr_last;
+        if (q % 2 == 0)
+            asm volatile("s_mov_b64 exec, %[m]\n\tds_write_b16 %[a], %[z] offset:%[o0]\n\tds_write_b16 %[a], %[z] offset:%[o2]\n\ts_mov_b64 exec, -1"
+                         : : [m] "s"(m), [a] "v"(at), [z] "v"(0u), [o0] "n"(o), [o2] "n"(o + 2048) : "memory");
+        else
+            asm volatile("s_mov_b64 exec, %[m]\n\tds_write_b16 %[a], %[z] offset:%[o1]\n\tds_write_b16 %[a], %[z] offset:%[o3]\n\ts_mov_b64 exec, -1"
+                         : : [m] "s"(m), [a] "v"(at), [z] "v"(0u), [o1] "n"(o + 1024), [o3] "n"(o + 3072) : "memory");
+    };
+    auto settle = [&](auto ring_c) {
+        settle_hazard(ring_c);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) settle_piece(ring_c, q);
     };
     using std::integral_constant;
 
@@ -399,20 +401,25 @@ __device__ __forceinline__ void conv_tap_program(const ConvArgs &g, char *smem, 
     }
 
     // One trip = one slice: the matrix instructions on fragment set SET (slice s, in registers since the trip before).  This
-    // wavefront's part of slice s + 1 has landed (the caller has waited for it): it is fixed up, and while those LDS writes
-    // are on their way the first PRE matrix instructions go out; then the barrier, which says that slice s + 1 is complete
+    // wavefront's part of slice s + 1 has landed (the caller has waited for it): it is fixed up behind the first four matrix
+    // instructions (a piece of the clears each), and while those LDS writes are on their way the rest of the first PRE go out;
+    // then the barrier, which says that slice s + 1 is complete
     // and that every wavefront holds its fragments of slice s, so that slice s + 4 may overwrite it.  Behind the remaining
     // matrix instructions: the LDS reads of slice s + 1 (ring position RING + 1) into the other set, the request walk's step
     // to slice s + 4 and that slice's loads into ring position RING, and the settle walk's step to slice s + 2.
     auto trip = [&](auto ring_c, auto set_c) {
         constexpr int RING = decltype(ring_c)::value, SET = decltype(set_c)::value;
         constexpr int NXT = (RING + 1) % kRing;
-        settle(integral_constant<int, NXT>{});
+        settle_hazard(integral_constant<int, NXT>{});
 #pragma unroll
         for (int idx = 0; idx < NM; ++idx) {
             const int tm = idx / TN, tn = idx % TN;
-            if (idx == PRE) __syncthreads();
+            if (idx == PRE) {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");        // (the clears below have reached LDS)
+                __syncthreads();
+            }
             mfma16<BF16>(acc[tm][tn], fa[SET][tm], fb[SET][tn]);      // a lane holds filter lane % 16 and 4 positions (see conv_store_rows16)
+            if (idx < 4) settle_piece(integral_constant<int, NXT>{}, idx);     // the clears of slice s + 1, one piece behind each of the first four
             if (idx >= PRE) {
                 const int i = idx - PRE;
                 if (i % 2 == 0 && i / 2 < NR) lds_read(i / 2, SET ^ 1, NXT);
