@@ -183,46 +183,153 @@ struct ConvTileA {
     }
 };
 
-// Epilogue.  Every matrix instruction is issued with the filter fragment first, so a lane holds one output position
-// m = lane % 16 of each 16 x 16 block and, register by register, 4 of its filters (4 (lane / 16) + v).  A store instruction
-// writes, per quarter wavefront, 16 consecutive positions of one filter: 32- or 64-byte segments of the output's contiguous
-// (p, q) axis.  Positions past M and a row's surplus positions (the kernel numbers positions with the row pitch rounded up
-// to a multiple of 8) are not stored.  An element's address is a wavefront-uniform base (the filter) plus a lane offset (the
-// position, and the lane quarter's 4 filters); the host has checked that the output's byte offsets fit 31 bits.
-// row0w / col0w: first position / filter of this wavefront; part: which part of the k range the program multiplied.
+// Epilogue of the kernels that stream their operands into LDS.  Their matrix instructions are issued with the input's fragment first, so a lane holds one FILTER
+// f = lane % 16 of each 16 x 16 block and four consecutive POSITIONS 4 (lane / 16) .. + 3 of it: eight (four) contiguous
+// bytes of the output, whose unit-stride axis is the position.  As in store_tile16_rows the wavefront's part (BN / 2 filters x
+// 16 TM positions) goes through its own region (BN / 2 x 256 bytes) of the idle ring so that the global stores are 16-byte chunks and a
+// store instruction covers 4 filters x 256 contiguous bytes (an epilogue that stored from the registers, one position and four
+// filters per lane, wrote 2 bytes per lane: eight times the store instructions, in 32-byte pieces):
+//   write phase  per block one conversion, the lane's 4 values to [filter][256 bytes] with the 16-byte chunk index XOR-ed
+//                with the filter (16 filters, same chunk: 16 different chunks);
+//   read phase   16 consecutive lanes read one filter's 256 bytes; a lane's chunk is 16 / ES consecutive positions of one
+//                output row (the kernel numbers positions with the row pitch rounded up to a multiple of 8, so a chunk never
+//                crosses a row), decomposed into (image, row, column) once per lane and pass.
+// An fp32 tile takes two passes (64 positions each).  A chunk that lies wholly inside its row and starts at a 4-byte
+// boundary is stored whole, any other element by element (the last chunk of rows whose length is no multiple of the chunk,
+// 16-bit rows of odd length).  Positions past M
+// and a row's surplus positions are not stored.  part: which part of the k range the program multiplied.
 template <int BM, int BN, int OUT>
-__device__ __forceinline__ void conv_store_points16(const ConvArgs &g, const float4v (&acc)[BM / 32][BN / 32], int64_t part, int64_t row0w, int64_t col0w, int lane)
+__device__ __forceinline__ void conv_store_rows16(const ConvArgs &g, char *smem, int wave, const float4v (&acc)[BM / 32][BN / 32], int64_t part,
+                                                  int64_t row0w, int64_t col0w, int lane)
 {
-    constexpr int TM = BM / 32, TN = BN / 32;
+    constexpr int TM = BM / 32;                            // blocks of 16 positions per wavefront
+    constexpr int TNW = BN / 32, FW = BN / 2;              // blocks of 16 filters, and filters, per wavefront
     constexpr int ES = OUT == NT_F32 ? 4 : 2;
+    constexpr int PASSES = ES / 2;
+    constexpr int BPP = 8 / PASSES;                        // position blocks per pass
+    constexpr int EPC = 16 / ES;                           // positions per chunk
+    constexpr int RB = 256;                                // bytes per region row (one filter)
     const int l16 = lane & 15, gq = lane >> 4;
+    char *reg = smem + wave * (FW * RB);
     const int64_t f_pitch = g.syf * ES;
     char *const y0 = reinterpret_cast<char *>(g.Y) + part * g.slice * ES + col0w * f_pitch;
-    const uint32_t quarter_off = (uint32_t)(4 * gq) * (uint32_t)f_pitch;
-    auto put = [&](char *at, float x) {
-        if constexpr (OUT == NT_F32) *reinterpret_cast<float *>(at) = x;
-        else *reinterpret_cast<uint16_t *>(at) = (uint16_t)pack_pair<OUT>(__builtin_bit_cast(uint32_t, x), 0u);
-    };
+    const int64_t filters = g.N - col0w;                   // filters from this wavefront's first on
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass) {
+        // ---- write phase
+#pragma unroll
+        for (int tmp = 0; tmp < BPP; ++tmp) {
+            const int tm = pass * BPP + tmp;
+            if (tm >= TM) break;
+#pragma unroll
+            for (int tn = 0; tn < TNW; ++tn) {
+                // (the block is pinned in its accumulator registers up to this point, see store_tile16_rows)
+                float4v blk = acc[tm][tn];
+                asm volatile("" : "+a"(blk));
+                float o[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) o[v] = blk[v];
+                const int r = tn * 16 + l16;
+                char *prow = reg + r * RB;
+                if constexpr (OUT == NT_F32) {
+                    const int c = tmp * 4 + gq;
+                    lds_write16(prow, (uint32_t)((c ^ l16) << 4), u32x4{__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
+                                                                         __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3])});
+                } else {
+                    const int c = tmp * 2 + (gq >> 1);
+                    *reinterpret_cast<u32x2 *>(prow + (((c ^ l16) << 4) + 8 * (gq & 1))) =
+                        u32x2{pack_pair<OUT>(__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1])),
+                              pack_pair<OUT>(__builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3]))};
+                }
+            }
+        }
+        // ---- read phase (same wavefront: LDS operations complete in order).  The lane's chunk: positions m .. m + EPC - 1
+        const int c = lane & 15;
+        const int pos = pass * (128 / PASSES) + c * EPC;                         // first position, within the wavefront's part
+        const int64_t m = row0w + pos;
+        const bool live = pos < 16 * TM && m < g.M;
+        const uint32_t mm = live ? (uint32_t)m : 0u;
+        const uint32_t n = mm / (uint32_t)g.PQ8;
+        const uint32_t pq = mm - n * (uint32_t)g.PQ8;
+        const uint32_t p = pq / (uint32_t)g.Q8;
+        const int q = (int)(pq - p * (uint32_t)g.Q8);
+        const int nv = !live ? 0 : (g.Q - q >= EPC ? EPC : (g.Q - q > 0 ? g.Q - q : 0));   // positions of the chunk that exist
+        const int64_t lane_off = ((int64_t)n * g.syn + (int64_t)p * g.Q + q) * ES;
+        // a whole chunk is stored with one instruction if it starts at a 4-byte boundary; streamed if all of the wavefront's
+        // chunks are whole and start at 16-byte boundaries (see store_tile16_rows)
+        const uintptr_t at0 = reinterpret_cast<uintptr_t>(y0) + (uintptr_t)lane_off;
+        const bool whole = nv == EPC && (at0 & 3) == 0 && (f_pitch & 3) == 0;
+        const bool stream = __builtin_amdgcn_ballot_w64((whole && (at0 & 15) == 0 && (f_pitch & 15) == 0) || nv == 0) == ~0ull;      // (uniform)
+        if (stream) {
+#pragma unroll
+            for (int it = 0; it < FW / 4; ++it) {
+                const int r = it * 4 + gq;
+                const u32x4 v = lds_read16(reg, (uint32_t)(r * RB + ((c ^ (r & 15)) << 4)));
+                if (nv != 0 && r < filters) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(y0 + r * f_pitch + lane_off));
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < FW / 4; ++it) {
+                const int r = it * 4 + gq;
+                const u32x4 v = lds_read16(reg, (uint32_t)(r * RB + ((c ^ (r & 15)) << 4)));
+                char *at = y0 + r * f_pitch + lane_off;
+                if (r < filters) {
+                    if (whole) {
+                        __builtin_memcpy(at, &v, 16);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < EPC; ++e)
+                            if (e < nv) {
+                                const uint32_t w = v[ES == 4 ? e : e / 2];
+                                if constexpr (OUT == NT_F32) *reinterpret_cast<uint32_t *>(at + 4 * e) = w;
+                                else *reinterpret_cast<uint16_t *>(at + 2 * e) = (uint16_t)((e & 1) ? w >> 16 : w & 0xffffu);
+                            }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Epilogue of a k split's programs (few, short programs whose fp32 partial tiles go to the workspace): straight from the
+// registers, a lane's 4 consecutive positions of one filter as one 16-byte store where they lie in one output row at a
+// 4-byte boundary (they do: the workspace slices are dense and fp32), else element by element.  No LDS round trip: with
+// at most one such program per compute unit its latency would not be hidden by anything.
+template <int BM, int BN>
+__device__ __forceinline__ void conv_store_partial16(const ConvArgs &g, const float4v (&acc)[BM / 32][BN / 32], int64_t part, int64_t row0w, int64_t col0w, int lane)
+{
+    constexpr int TM = BM / 32, TN = BN / 32;
+    const int l16 = lane & 15, gq = lane >> 4;
+    const int64_t f_pitch = g.syf * 4;
+    char *const y0 = reinterpret_cast<char *>(g.Y) + part * g.slice * 4 + (col0w + l16) * f_pitch;
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
-        const int64_t m = row0w + tm * 16 + l16;
+        const int64_t m = row0w + tm * 16 + 4 * gq;                  // the lane's first position (a multiple of 4: one output row)
         const uint32_t mm = m < g.M ? (uint32_t)m : 0u;
         const uint32_t n = mm / (uint32_t)g.PQ8;
         const uint32_t pq = mm - n * (uint32_t)g.PQ8;
         const uint32_t p = pq / (uint32_t)g.Q8;
         const int q = (int)(pq - p * (uint32_t)g.Q8);
-        const bool keep = m < g.M && q < g.Q;                        // not past the last position, not one of a row's surplus positions
-        const uint32_t lane_off = (uint32_t)((int64_t)n * g.syn + (int64_t)p * g.Q + q) * (uint32_t)ES + quarter_off;
+        const int nv = m < g.M ? (g.Q - q >= 4 ? 4 : (g.Q - q > 0 ? g.Q - q : 0)) : 0;
+        char *const at0 = y0 + ((int64_t)n * g.syn + (int64_t)p * g.Q + q) * 4;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             // (the block is pinned in its accumulator registers up to this point, see store_tile16_rows)
             float4v blk = acc[tm][tn];
             asm volatile("" : "+a"(blk));
-            char *const yb = y0 + (tn * 16) * f_pitch;               // (uniform)
-            const int64_t room = g.N - (col0w + tn * 16 + 4 * gq);   // filters from this lane's first on
+            float o[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (keep && v < room) put(yb + v * f_pitch + lane_off, blk[v]);
+            for (int v = 0; v < 4; ++v) o[v] = blk[v];
+            if (col0w + tn * 16 + l16 >= g.N) continue;               // a filter past the last
+            char *at = at0 + (tn * 16) * f_pitch;
+            if (nv == 4) {
+                const u32x4 w{__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]), __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3])};
+                __builtin_memcpy(at, &w, 16);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (v < nv) *reinterpret_cast<float *>(at + 4 * v) = o[v];
+            }
         }
     }
 }
@@ -307,7 +414,7 @@ __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_dir
 #pragma unroll
         for (int idx = 0; idx < NM; ++idx) {
             const int tm = idx / TN, tn = idx % TN;
-            mfma16<BF16>(acc[tm][tn], fb[set][tn], fa[set][tm]);      // transposed block: a lane holds position lane % 16 (see conv_store_points16)
+            mfma16<BF16>(acc[tm][tn], fa[set][tm], fb[set][tn]);      // a lane holds filter lane % 16 and 4 positions (see conv_store_rows16)
             if (idx < RS)
 #pragma unroll
                 for (int r = idx * NR / RS; r < (idx + 1) * NR / RS; ++r) lds_read(r, set ^ 1, rring);
@@ -378,9 +485,10 @@ __global__ __launch_bounds__(kThreads, residency_of(256, BN)) void gemm_conv_dir
     asm volatile("s_nop 15" ::: "memory");
 
     const int64_t row_w = row0 + wave_m * (BM / 2), col_w = col0 + wave_n * (BN / 2);
-    if (g.out_dtype == NT_F32) conv_store_points16<BM, BN, NT_F32>(g, acc, bi, row_w, col_w, lane);
-    else if (g.out_dtype == NT_F16) conv_store_points16<BM, BN, NT_F16>(g, acc, bi, row_w, col_w, lane);
-    else conv_store_points16<BM, BN, NT_BF16>(g, acc, bi, row_w, col_w, lane);
+    if (g.ksplit > 1) conv_store_partial16<BM, BN>(g, acc, bi, row_w, col_w, lane);       // (fp32 partial tiles)
+    else if (g.out_dtype == NT_F32) conv_store_rows16<BM, BN, NT_F32>(g, smem, wave, acc, bi, row_w, col_w, lane);
+    else if (g.out_dtype == NT_F16) conv_store_rows16<BM, BN, NT_F16>(g, smem, wave, acc, bi, row_w, col_w, lane);
+    else conv_store_rows16<BM, BN, NT_BF16>(g, smem, wave, acc, bi, row_w, col_w, lane);
 }
 
 template <int BN, bool BF16, bool TRACE = false>

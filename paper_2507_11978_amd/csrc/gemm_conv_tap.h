@@ -28,107 +28,6 @@
 
 namespace nt {
 
-// Epilogue of this kernel.  Its matrix instructions are issued with the input's fragment first, so a lane holds one FILTER
-// f = lane % 16 of each 16 x 16 block and four consecutive POSITIONS 4 (lane / 16) .. + 3 of it: eight (four) contiguous
-// bytes of the output, whose unit-stride axis is the position.  As in store_tile16_rows the wavefront's part (128 filters x
-// 16 TM positions) goes through its own 32 KB region of the idle ring so that the global stores are 16-byte chunks and a
-// store instruction covers 4 filters x 256 contiguous bytes (the other epilogue, conv_store_points16, writes 2 bytes per
-// lane: four times the store instructions, in 32-byte pieces):
-//   write phase  per block one conversion, the lane's 4 values to [filter][256 bytes] with the 16-byte chunk index XOR-ed
-//                with the filter (16 filters, same chunk: 16 different chunks);
-//   read phase   16 consecutive lanes read one filter's 256 bytes; a lane's chunk is 16 / ES consecutive positions of one
-//                output row (the kernel numbers positions with the row pitch rounded up to a multiple of 8, so a chunk never
-//                crosses a row), decomposed into (image, row, column) once per lane and pass.
-// An fp32 tile takes two passes (64 positions each).  A chunk that lies wholly inside its row and starts at a 16-byte
-// boundary is stored whole, any other element by element (rows whose length is no multiple of 8 elements).  Positions past M
-// and a row's surplus positions are not stored.  part: which part of the k range the program multiplied.
-template <int BM, int OUT>
-__device__ __forceinline__ void conv_store_rows16(const ConvArgs &g, char *smem, int wave, const float4v (&acc)[BM / 32][8], int64_t part,
-                                                  int64_t row0w, int64_t col0w, int lane)
-{
-    constexpr int TM = BM / 32;                            // blocks of 16 positions per wavefront
-    constexpr int ES = OUT == NT_F32 ? 4 : 2;
-    constexpr int PASSES = ES / 2;
-    constexpr int BPP = 8 / PASSES;                        // position blocks per pass
-    constexpr int EPC = 16 / ES;                           // positions per chunk
-    constexpr int RB = 256;                                // bytes per region row (one filter)
-    const int l16 = lane & 15, gq = lane >> 4;
-    char *reg = smem + wave * (128 * RB);
-    const int64_t f_pitch = g.syf * ES;
-    char *const y0 = reinterpret_cast<char *>(g.Y) + part * g.slice * ES + col0w * f_pitch;
-    const int64_t filters = g.N - col0w;                   // filters from this wavefront's first on
-#pragma unroll
-    for (int pass = 0; pass < PASSES; ++pass) {
-        // ---- write phase
-#pragma unroll
-        for (int tmp = 0; tmp < BPP; ++tmp) {
-            const int tm = pass * BPP + tmp;
-            if (tm >= TM) break;
-#pragma unroll
-            for (int tn = 0; tn < 8; ++tn) {
-                // (the block is pinned in its accumulator registers up to this point, see store_tile16_rows)
-                float4v blk = acc[tm][tn];
-                asm volatile("" : "+a"(blk));
-                float o[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) o[v] = blk[v];
-                const int r = tn * 16 + l16;
-                char *prow = reg + r * RB;
-                if constexpr (OUT == NT_F32) {
-                    const int c = tmp * 4 + gq;
-                    lds_write16(prow, (uint32_t)((c ^ l16) << 4), u32x4{__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
-                                                                         __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3])});
-                } else {
-                    const int c = tmp * 2 + (gq >> 1);
-                    *reinterpret_cast<u32x2 *>(prow + (((c ^ l16) << 4) + 8 * (gq & 1))) =
-                        u32x2{pack_pair<OUT>(__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1])),
-                              pack_pair<OUT>(__builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3]))};
-                }
-            }
-        }
-        // ---- read phase (same wavefront: LDS operations complete in order).  The lane's chunk: positions m .. m + EPC - 1
-        const int c = lane & 15;
-        const int pos = pass * (128 / PASSES) + c * EPC;                         // first position, within the wavefront's part
-        const int64_t m = row0w + pos;
-        const bool live = pos < 16 * TM && m < g.M;
-        const uint32_t mm = live ? (uint32_t)m : 0u;
-        const uint32_t n = mm / (uint32_t)g.PQ8;
-        const uint32_t pq = mm - n * (uint32_t)g.PQ8;
-        const uint32_t p = pq / (uint32_t)g.Q8;
-        const int q = (int)(pq - p * (uint32_t)g.Q8);
-        const int nv = !live ? 0 : (g.Q - q >= EPC ? EPC : (g.Q - q > 0 ? g.Q - q : 0));   // positions of the chunk that exist
-        const int64_t lane_off = ((int64_t)n * g.syn + (int64_t)p * g.Q + q) * ES;
-        const bool whole = nv == EPC && ((reinterpret_cast<uintptr_t>(y0) + (uintptr_t)lane_off) & 15) == 0 && (f_pitch & 15) == 0;
-        const bool all_whole = __builtin_amdgcn_ballot_w64(whole || nv == 0) == ~0ull;      // (uniform)
-        if (all_whole) {
-#pragma unroll
-            for (int it = 0; it < 32; ++it) {
-                const int r = it * 4 + gq;
-                const u32x4 v = lds_read16(reg, (uint32_t)(r * RB + ((c ^ (r & 15)) << 4)));
-                if (nv != 0 && r < filters) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(y0 + r * f_pitch + lane_off));
-            }
-        } else {
-            for (int it = 0; it < 32; ++it) {
-                const int r = it * 4 + gq;
-                const u32x4 v = lds_read16(reg, (uint32_t)(r * RB + ((c ^ (r & 15)) << 4)));
-                if (r >= filters) continue;
-                char *at = y0 + r * f_pitch + lane_off;
-                if (whole) {
-                    __builtin_memcpy(at, &v, 16);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < EPC; ++e)
-                        if (e < nv) {
-                            const uint32_t w = v[ES == 4 ? e : e / 2];
-                            if constexpr (OUT == NT_F32) *reinterpret_cast<uint32_t *>(at + 4 * e) = w;
-                            else *reinterpret_cast<uint16_t *>(at + 2 * e) = (uint16_t)((e & 1) ? w >> 16 : w & 0xffffu);
-                        }
-                }
-            }
-        }
-    }
-}
-
 // One program: TM: its tile is 32 TM positions high (192, 224 or 256; the LDS slots are laid out for 256 either way), starts
 // at position row_base + ti * 32 TM and at filter 256 tj; bi: which part of the k range (k split).
 template <bool BF16, int TM, bool TRACE>
@@ -482,9 +381,9 @@ __device__ __forceinline__ void conv_tap_program(const ConvArgs &g, char *smem, 
     asm volatile("s_nop 15" ::: "memory");
 
     const int64_t row_w = row0 + wave_m * (BM / 2), col_w = col0 + wave_n * (BN / 2);
-    if (g.out_dtype == NT_F32) conv_store_rows16<BM, NT_F32>(g, smem, wave, acc, bi, row_w, col_w, lane);
-    else if (g.out_dtype == NT_F16) conv_store_rows16<BM, NT_F16>(g, smem, wave, acc, bi, row_w, col_w, lane);
-    else conv_store_rows16<BM, NT_BF16>(g, smem, wave, acc, bi, row_w, col_w, lane);
+    if (g.out_dtype == NT_F32) conv_store_rows16<BM, BN, NT_F32>(g, smem, wave, acc, bi, row_w, col_w, lane);
+    else if (g.out_dtype == NT_F16) conv_store_rows16<BM, BN, NT_F16>(g, smem, wave, acc, bi, row_w, col_w, lane);
+    else conv_store_rows16<BM, BN, NT_BF16>(g, smem, wave, acc, bi, row_w, col_w, lane);
 }
 
 // The grid: g.mt_a tiles of 32 TMA positions, then g.mt - g.mt_a tiles of 32 TMB positions, each kind times g.nt filter tiles
