@@ -276,6 +276,13 @@ __device__ __forceinline__ void conv_store_rows16(const ConvArgs &g, char *smem,
                 if (r < filters) {
                     if (whole) {
                         __builtin_memcpy(at, &v, 16);
+                    } else if (ES == 2 && (at0 & 3) == 0 && (f_pitch & 3) == 0) {
+                        // (the part of a 16-bit chunk that exists, pairs of positions at a time)
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            if (2 * d + 1 < nv) *reinterpret_cast<uint32_t *>(at + 4 * d) = v[d];
+                            else if (2 * d < nv) *reinterpret_cast<uint16_t *>(at + 4 * d) = (uint16_t)(v[d] & 0xffffu);
+                        }
                     } else {
 #pragma unroll
                         for (int e = 0; e < EPC; ++e)

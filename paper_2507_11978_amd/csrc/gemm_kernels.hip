@@ -373,19 +373,69 @@ nt_status static_scratch(void **ptr_out, size_t *bytes_out)
     return NT_OK;
 }
 
-// A convolution with few output tiles and a long reduction leaves most of the chip idle: its k tiles are dealt to
-// `ksplit` programs per output tile, enough for about one program per compute unit, none with fewer than 4 k tiles.
-// (Measured on 13 shapes from 1 to 112 programs and 8 to 72 k tiles: the split run is faster in every one, e.g.
-// (8,64,14,14) * (64,64,3,3) 26 -> 21 us, (4,256,14,14) * (256,256,3,3) 78 -> 23 us.)
-static int conv_ksplit(int64_t programs, int64_t kt, int32_t *kt_per)
+// Estimated time (us) of a dense unit-stride convolution -- an implicit GEMM of M positions x N filters x kt k tiles -- on
+// tiles of 256 positions x bn filters with `per` k tiles per program (ks = ceil(kt / per) programs per output tile).  A
+// program costs a fixed part plus its 32-k slices (0.8 us each on the 256-filter tile, 1.15 on the narrower ones, which do
+// half the work or less per slice: their loader, not the matrix pipe, sets the pace; the 256-filter tile's fixed part
+// includes the copy of the filter); programs run in rounds of one per compute unit (two for the narrower tiles, which are
+// co-resident); a split adds a second launch and the partial tiles' trip through memory.  Fits (us, measured):
+// (256,512,7,7)*(512,512,3,3) 172 on 128-filter tiles, 111-119 on 256-filter tiles split in two; (32,512,14,14)*(512,512,3,3)
+// 99 / 73; (8,256,56,56)*(256,256,3,3) 73 / 60; (16,256,28,28)*(256,256,3,3) 58.5 / 57.8; (32,256,14,14)*(1024,256,1,1) 18 / 31.
+static double conv_cost(int64_t M, int64_t N, int64_t kt, int bn, int64_t per)
+{
+    const int64_t ks = (kt + per - 1) / per;
+    const int64_t programs = ((M + 255) / 256) * ((N + bn - 1) / bn) * ks;
+    const int64_t slots = bn == 256 ? 256 : 512;
+    const double fixed = bn == 256 ? 14.0 : 7.0, slice = bn == 256 ? 0.8 : 1.15;
+    double c = (double)((programs + slots - 1) / slots) * (fixed + 2.0 * (double)per * slice);
+    if (ks > 1) c += 6.0 + (double)ks * (double)M * (double)N * 8.0 / 5.0e6;
+    return c;
+}
+
+// The split of the reduction for that tile: `*kt_per` k tiles per program (none with fewer than 4), the number of parts
+// returned.  Small grids (fewer than 48 tiles of 256 x 256): enough parts for about one program per compute unit
+// (measured on 13 shapes from 1 to 112 programs and 8 to 72 k tiles: the split run is faster in every one, e.g.
+// (8,64,14,14) * (64,64,3,3) 26 -> 21 us, (4,256,14,14) * (256,256,3,3) 78 -> 23 us).  Larger ones: the cheapest by the
+// estimate above, which knows about whole rounds (5 parts of 56 tiles are 280 programs and cost two rounds, 4 parts one).
+static bool conv_small(int64_t M, int64_t N) { return ((M + 255) / 256) * ((N + 255) / 256) < 48; }
+static int conv_ksplit(int64_t M, int64_t N, int64_t kt, int bn, int32_t *kt_per, double *cost_out = nullptr)
 {
     *kt_per = (int32_t)kt;
-    if (programs >= 128 || kt < 8) return 1;
-    const int64_t want = std::min<int64_t>((256 + programs / 2) / programs, kt / 4);
-    if (want < 2) return 1;
-    const int64_t per = (kt + want - 1) / want;
-    *kt_per = (int32_t)per;
-    return (int)((kt + per - 1) / per);
+    if (conv_small(M, N)) {
+        const int64_t programs = ((M + 255) / 256) * ((N + bn - 1) / bn);
+        if (programs >= 128 || kt < 8) return 1;
+        const int64_t want = std::min<int64_t>((256 + programs / 2) / programs, kt / 4);
+        if (want < 2) return 1;
+        const int64_t per = (kt + want - 1) / want;
+        *kt_per = (int32_t)per;
+        return (int)((kt + per - 1) / per);
+    }
+    int64_t best_per = kt;
+    double best = conv_cost(M, N, kt, bn, kt);
+    for (int64_t ks = 2; ks <= 64; ++ks) {
+        const int64_t per = (kt + ks - 1) / ks;
+        if (per < 4 || (double)ks * (double)M * (double)N * 4.0 > (double)kSplitWsMax) break;
+        if ((kt + per - 1) / per != ks) continue;                              // (that many parts come out one fewer)
+        const double c = conv_cost(M, N, kt, bn, per);
+        if (c < best) { best = c; best_per = per; }
+    }
+    *kt_per = (int32_t)best_per;
+    if (cost_out) *cost_out = best;
+    return (int)((kt + best_per - 1) / best_per);
+}
+
+// The tile of filters for such a convolution.  Small grids: 256 filters per program when 256 would not leave half the
+// compute units without a program, else 128; larger ones: by the estimate, each tile with its best split.
+nt_tile_cfg pick_conv_tile(int64_t M, int64_t N, int64_t K)
+{
+    if (N <= 128) return nt_tile_cfg{256, 128, 64};
+    if (conv_small(M, N)) return nt_tile_cfg{256, 128, 64};
+    const int64_t kt = (K + 63) / 64;
+    int32_t per = 0;
+    double c256 = 0, c128 = 0;
+    conv_ksplit(M, N, kt, 256, &per, &c256);
+    conv_ksplit(M, N, kt, 128, &per, &c128);
+    return c256 <= c128 ? nt_tile_cfg{256, 256, 64} : nt_tile_cfg{256, 128, 64};
 }
 
 // A map is "plain" when it is a strided matrix without bounds checks beyond rows / cols.
@@ -454,7 +504,7 @@ static size_t conv_scratch_need(const GemmLaunch &g, const ConvArgs &c)
     size_t repack = 0;
     const bool tap = conv_tap_ok(g, c, &repack);
     int32_t kt_per = 0;
-    const int ks = conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
+    const int ks = conv_ksplit(c.M, c.N, c.kt, g.tile.bn, &kt_per);
     return (tap ? repack : 0) + (ks > 1 ? (size_t)ks * g.conv.N * c.N * c.PQ * 4 : 0);
 }
 
@@ -466,7 +516,7 @@ static nt_status route_conv_implicit(const GemmLaunch &g, const ConvArgs &c, int
     const bool edge_b = (g.N % t.bn) || (g.K % t.bk);
     hipStream_t s = (hipStream_t)g.stream;
     int32_t kt_per = 0;
-    const int ksplit = g.trace.out ? 1 : conv_ksplit(c.mt * c.nt, c.kt, &kt_per);
+    const int ksplit = g.trace.out ? 1 : conv_ksplit(c.M, c.N, c.kt, t.bn, &kt_per);
     const int64_t slice = g.conv.N * (int64_t)c.N * c.PQ;
     const bool direct = conv_direct_ok(g, c);
     size_t repack_bytes = 0;

@@ -63,6 +63,8 @@ bool tile_is_built(nt_tile_cfg cfg);
 int last_k_split();
 // the tile the MFMA kernels run a plain (batched) product of this size fastest with, by a cost model fitted to measurements
 nt_tile_cfg pick_gemm_tile(int64_t batch, int64_t M, int64_t N, int64_t K);
+// the tile of a dense unit-stride convolution (M positions, N filters, reduction K), by an estimate that includes the k split
+nt_tile_cfg pick_conv_tile(int64_t M, int64_t N, int64_t K);
 nt_status launch_gemm(const GemmLaunch &g, int *path_out);
 // device address and size of the fixed scratch array of the entry point that allocates nothing (this device's copy)
 nt_status static_scratch(void **ptr_out, size_t *bytes_out);

@@ -45,12 +45,7 @@ nt_tile_cfg pick_tile(int kind, int64_t batch, int64_t M, int64_t N, int64_t K, 
     // ((32,64,56,56) * (64,64,3,3): 35 us against 242; (1,64,8,8) * (64,64,3,3): 19 us against 104).
     const bool tiny = (M <= 64 || N <= 64) && ((kind == KIND_CONV && !unit_stride) || kind == KIND_VIEWS);
     if (tiny) return nt_tile_cfg{64, 64, 32};
-    if (kind == KIND_CONV) {
-        // the convolution kernel is built for 256 output positions per program; 128 filters per program when
-        // 256 would leave half the compute units without one
-        const int64_t mt = (M + 255) / 256;
-        return mt * ((N + 255) / 256) >= 128 ? nt_tile_cfg{256, 256, 64} : nt_tile_cfg{256, 128, 64};
-    }
+    if (kind == KIND_CONV) return nt::pick_conv_tile(M, N, K);     // 256 output positions per program, 256 or 128 filters
     return nt::pick_gemm_tile(batch, M, N, K);
 }
 

@@ -43,7 +43,7 @@ def test_convolution_written_as_an_arrangement_by_the_caller(shape, stride, pad,
 
 @pytest.mark.parametrize("shape,stride,pad,want", [
     ((2, 32, 20, 24, 64, 3, 3), (1, 1), (1, 1), "direct"),        # dense, unit stride: the convolution kernel that streams into LDS
-    ((48, 64, 28, 28, 256, 3, 3), (1, 1), (1, 1), "tap"),          # ... and the one that walks the reduction tap by tap
+    ((32, 128, 20, 24, 256, 3, 3), (1, 1), (1, 1), "tap"),         # ... and the one that walks the reduction tap by tap
     ((2, 16, 21, 21, 64, 3, 3), (2, 2), (1, 1), "unfold"),        # strided: the unfolded input + the matrix kernels
     ((2, 8, 20, 20, 32, 5, 5), (1, 1), (2, 2), "padded"),         # two columns of padding: the zero-padded copy
 ])
