@@ -354,7 +354,10 @@ nt_status nt_trace_tile(int32_t kind, const nt_tensor_desc *d0, const nt_tensor_
  * A, B: device pointers, read.  dC: the output's descriptor (shape only; nothing is stored).  values_out: DEVICE array of
  * `capacity` entries, at least 32 * (tile rows of the operand).  Only launches that stream their operands straight into LDS
  * (nt_last_kernel_path() 2, 4 or 6 for the same arguments) can be traced: otherwise NT_ERR_UNSUPPORTED.  The ring-unrolled
- * variant of the 256 x 256 kernel has the same per-lane offsets and slice stepping as the kernel traced here.
+ * variant of the 256 x 256 kernel and its persistent form (one workgroup walking several programs) have the same per-lane
+ * offsets and slice stepping as the kernel traced here.
+ * Path 6 may run tile rows of two heights (the first ones 256 or 224 positions, the rest 32 fewer; tile row i starts where
+ * the tile rows before it end): the rows of values_out past the traced program's height are left untouched.
  * Path 6 sums over the reduction index in another order than the arrangement lists it: its slice s, index kk is channel
  * c = 32 (s % (C / 32)) + kk of filter tap t = s / (C / 32), i.e. the arrangement's k = c * R * S + t.
  */
