@@ -981,7 +981,8 @@ static nt_status launch_direct16_inst(const FastArgs &a, int64_t nwg, hipStream_
             FastArgs ap = a;
             ap.nprog = nwg;
             // (measured on 2 .. 16 programs per unit: 6 - 14 % for K <= 512, 2 - 4 % at K = 1024, nothing or a small loss beyond)
-            ap.stagger = a.kt <= 16 ? 200 : 0;
+            // (every unit has at least two programs: with fewer the late starters would only lengthen the launch)
+            ap.stagger = a.kt <= 16 && nwg >= 2 * units ? 200 : 0;
             hipLaunchKernelGGL(kp, dim3((unsigned)units), dim3(kThreads), smem_p, s, ap);
             return check_launch("gemm_direct16p_kernel");
         }

@@ -57,7 +57,7 @@ nt_tile_cfg pick_gemm_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
         const bool full = M % c.bm == 0 && N % c.bn == 0 && K % 64 == 0;
         const int resident = full || (c.bm == 128 && c.bn == 128) ? c.resident : 1;
         // (the persistent kernel staggers short programs: a program's fixed part then overlaps other units' multiplications)
-        const bool staggered = c.bm == 256 && c.bn == 256 && full && programs > 256 && kt <= 16;
+        const bool staggered = c.bm == 256 && c.bn == 256 && full && programs >= 512 && kt <= 16;
         const double cost = staggered ? 4.0 + (double)p * (6.0 + kt * c.step)
                                       : (double)((p + resident - 1) / resident) * c.fixed + (double)p * kt * c.step;
         if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = nt_tile_cfg{c.bm, c.bn, 64}; }
