@@ -238,7 +238,10 @@ def bench_memory_bound(args, cfg):
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "config": {"workload": args.workload, "shape": shape, "in_dtype": dt, "out_dtype": dt, "arithmetic": "f32"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(args.workload, nt.version()), "kernel_ms_avg": round(kern_avg, 5), "algorithmic_bytes": int(alg_bytes)},
+                     "traffic": measured_traffic(args.workload, nt.version()), "kernel_ms_avg": round(kern_avg, 5), "algorithmic_bytes": int(alg_bytes),
+                     # the paper's task sizes (67 - 101 MB per launch, the same buffers every launch) fit the 256 MB Infinity Cache:
+                     # part of the traffic never reaches HBM, so `frac` can exceed what HBM alone would allow
+                     "working_set_fits_infinity_cache": bool(alg_bytes < 256 * 2 ** 20)},
     }
     if not args.no_check:
         got = oe.decode(out[sample_sl].contiguous().view(torch.int16).cpu().numpy().view(np.uint16), dt)
@@ -284,7 +287,10 @@ def bench_sdpa(args, cfg):
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "config": {"workload": args.workload, "shape": {"B": B, "H": H, "S": S, "D": D}, "in_dtype": dt, "out_dtype": dt, "accumulate": "f32"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 4),
-                     "traffic": measured_traffic(args.workload, nt.version()), "kernel_ms_avg": round(kern_avg, 5), "algorithmic_bytes": int(alg_bytes)},
+                     "traffic": measured_traffic(args.workload, nt.version()), "kernel_ms_avg": round(kern_avg, 5), "algorithmic_bytes": int(alg_bytes),
+                     # the paper's task sizes (67 - 101 MB per launch, the same buffers every launch) fit the 256 MB Infinity Cache:
+                     # part of the traffic never reaches HBM, so `frac` can exceed what HBM alone would allow
+                     "working_set_fits_infinity_cache": bool(alg_bytes < 256 * 2 ** 20)},
     }
     if not args.no_check:
         ref = oat.sdpa(qb[B - 1, H - 1, :256], kb[B - 1, H - 1], vb[B - 1, H - 1], dt)

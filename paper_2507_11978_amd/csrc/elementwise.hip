@@ -90,7 +90,10 @@ __global__ __launch_bounds__(256) void map_vec_kernel(const uint16_t *__restrict
 #pragma unroll
                 for (int e = 0; e < 8; ++e) fa[e] = OP == 0 ? fa[e] + fb[e] : silu_f32(fa[e]);
                 const u32x4 r = pack8<BF16>(fa);
-                __builtin_memcpy(out + v * 8, &r, 16);
+                // (the result is streamed past L2 where that pays -- one operand: 12.3 -> 7.9 us on 16.7 M elements; with two
+                // operands it costs 2 %, and streaming the loads costs 15 - 20 % in either case)
+                if constexpr (OP == 0) __builtin_memcpy(out + v * 8, &r, 16);
+                else __builtin_nontemporal_store(r, reinterpret_cast<u32x4 *>(out + v * 8));
             }
         }
     }
@@ -183,7 +186,7 @@ __global__ __launch_bounds__(256) void row_wave_kernel(const uint16_t *__restric
 #pragma unroll
             for (int e = 0; e < 8; ++e) f[v][e] *= scale;
             const u32x4 r = pack8<BF16>(f[v]);
-            __builtin_memcpy(orow + idx * 8, &r, 16);
+            __builtin_nontemporal_store(r, reinterpret_cast<u32x4 *>(orow + idx * 8));       // (streamed: softmax 12.4 -> 10.3 us, rms_norm 11.3 -> 8.4 us at 4096 x 4096)
         }
     }
 }
