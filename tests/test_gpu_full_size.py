@@ -125,6 +125,36 @@ def test_conv_grids_of_more_programs_than_units(shape, pad, dt, out):
     check_whole(to_f64(Y), ref, out)
 
 
+@pytest.mark.parametrize("shape,want_split", [
+    ((32, 512, 14, 14, 512, 3, 3), True),      # 56 tiles of 256 x 256, 72 k tiles: the 256-filter tile with its reduction in 4 parts (one round)
+    ((8, 256, 56, 56, 256, 3, 3), None),       # 98 tiles: whatever the estimate picks
+    ((64, 256, 14, 14, 512, 3, 3), None),      # 112 tiles
+])
+def test_conv_tile_and_split_chosen_together(shape, want_split):
+    """Mid-sized grids, where the library weighs the 256-filter tile against the 128-filter one together with the split of
+    the reduction: every output against the oracle (reference as in test_full_size_conv), and the same bits twice."""
+    N, Cc, H, W, K, R, S = shape
+    dt, pad = "f16", 1
+    X, Wt = si.conv_inputs(N, Cc, H, W, K, R, S, dt, seed=29)
+    Y = torch.full((N, K, H, W), float("nan"), dtype=torch.float16, device="cuda")
+    Y2 = torch.full((N, K, H, W), float("nan"), dtype=torch.float16, device="cuda")
+    x, w = to_gpu(X, dt), to_gpu(Wt, dt)
+    nt.conv2d_implicit(x, w, Y, (1, 1), (pad, pad))
+    nt.conv2d_implicit(x, w, Y2, (1, 1), (pad, pad))
+    torch.cuda.synchronize()
+    assert nt.last_kernel_path() in (nt.PATH_CONV_DIRECT, nt.PATH_CONV_TAP)
+    if want_split:
+        assert nt.last_kernel_path() == nt.PATH_CONV_TAP and nt.last_k_split() > 1
+    assert torch.equal(Y, Y2)
+    Wm = Wt.reshape(K, Cc * R * S).T
+    ref = np.empty((N, K, H, W), dtype=np.float64)
+    for n in range(N):
+        ref[n] = onum.gemm(unfolded_input(X[n], R, S, pad), Wm, dt, nthreads=THREADS).T.reshape(K, H, W)
+    direct = onum.conv2d(X[N - 1:N], Wt[:32], dt, (1, 1), (pad, pad), nthreads=THREADS)[0]
+    assert np.array_equal(direct, ref[N - 1, :32])
+    check_whole(to_f64(Y), ref, "f16")
+
+
 def test_full_size_conv_of_the_papers_kernel_list():
     """(4, 512, 14, 14) * (512, 512, 3, 3) in the launch configuration bench.py times (k split over 18 programs per
     output tile): every output against the oracle, and a second call gives the same bits."""
